@@ -1,0 +1,16 @@
+"""CPU oracle of the output-equivalence check.  TEST INFRASTRUCTURE ONLY.
+
+Imported by tests/, by the smoke check and by the benchmark's CPU-baseline leg.
+The product package never imports it.
+"""
+from .oracle import (  # noqa: F401
+    RECORD_DTYPE,
+    DTYPE_CODES,
+    ELEM_SIZE,
+    build,
+    check_segment,
+    check_dense,
+    check_ragged,
+    decode_f16,
+    decode_bf16,
+)

@@ -1,0 +1,142 @@
+"""ctypes front end of the plain-C oracle (geak_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+The rule it applies is the reading of GEAK section 3.1 (tolerance-based comparison of
+output tensors) and section 3.3 (every unit test must pass; the reference is ground
+truth) written out in geak_oracle.c.  Nothing here is shared with the HIP path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "geak_oracle.c")
+_LIB = os.path.join(_HERE, "libgeak_oracle.so")
+
+DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2, "i32": 3}
+ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4}
+
+# One record per (segment, candidate); field meaning as in geak_oracle.c (R7-R9).
+RECORD_DTYPE = np.dtype(
+    [
+        ("pass", "<i4"),
+        ("reserved", "<i4"),
+        ("mismatch_count", "<u8"),
+        ("first_mismatch", "<i8"),
+        ("max_abs_err", "<f8"),
+        ("max_rel_err", "<f8"),
+    ]
+)
+
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile geak_oracle.c with gcc (no FMA contraction, no fast-math)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = [
+            "gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+            "-o", _LIB, _SRC, "-lm",
+        ]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            lib = ctypes.CDLL(build())
+            lib.oracle_check_segment.restype = ctypes.c_int
+            lib.oracle_check_segment.argtypes = [
+                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
+                ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_void_p,
+            ]
+            lib.oracle_decode_f16.restype = ctypes.c_float
+            lib.oracle_decode_f16.argtypes = [ctypes.c_uint16]
+            lib.oracle_decode_bf16.restype = ctypes.c_float
+            lib.oracle_decode_bf16.argtypes = [ctypes.c_uint16]
+            _lib = lib
+    return _lib
+
+
+def decode_f16(bits: int) -> float:
+    return float(_load().oracle_decode_f16(int(bits) & 0xFFFF))
+
+
+def decode_bf16(bits: int) -> float:
+    return float(_load().oracle_decode_bf16(int(bits) & 0xFFFF))
+
+
+def _as_bytes(x) -> np.ndarray:
+    """Raw little-endian bytes of a contiguous numpy array, no copy when possible."""
+    a = np.ascontiguousarray(x)
+    return a.reshape(-1).view(np.uint8)
+
+
+def check_segment(ref, cand, numel: int, dtype: str, atol: float, rtol: float,
+                  equal_nan: bool, ref_byte_offset: int = 0, cand_byte_offset: int | None = None):
+    """One (segment, candidate) pair.  ref/cand: numpy arrays holding the raw storage
+    (f16/bf16 as uint16 bit patterns or any array whose bytes are the tensor's bytes)."""
+    lib = _load()
+    if cand_byte_offset is None:
+        cand_byte_offset = ref_byte_offset
+    rb, cb = _as_bytes(ref), _as_bytes(cand)
+    need = numel * ELEM_SIZE[dtype]
+    if ref_byte_offset + need > rb.size or cand_byte_offset + need > cb.size:
+        raise ValueError("segment exceeds buffer")
+    out = np.zeros(1, dtype=RECORD_DTYPE)
+    rc = lib.oracle_check_segment(
+        rb.ctypes.data + ref_byte_offset, cb.ctypes.data + cand_byte_offset,
+        numel, DTYPE_CODES[dtype], float(atol), float(rtol), int(bool(equal_nan)),
+        out.ctypes.data,
+    )
+    if rc != 0:
+        raise RuntimeError("oracle_check_segment failed")
+    return out[0]
+
+
+def _run_pairs(jobs, threads: int):
+    """jobs: list of zero-argument callables; ctypes releases the GIL during the C loop."""
+    if threads <= 1 or len(jobs) <= 1:
+        return [j() for j in jobs]
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        return list(ex.map(lambda j: j(), jobs))
+
+
+def check_dense(ref, cands, dtype: str, atol: float, rtol: float, equal_nan: bool,
+                threads: int = 1) -> np.ndarray:
+    """Dense case: one segment.  Returns RECORD_DTYPE array of shape (K,)."""
+    rb = _as_bytes(ref)
+    numel = rb.size // ELEM_SIZE[dtype]
+    jobs = [
+        (lambda c=c: check_segment(rb, c, numel, dtype, atol, rtol, equal_nan))
+        for c in cands
+    ]
+    return np.array(_run_pairs(jobs, threads), dtype=RECORD_DTYPE)
+
+
+def check_ragged(ref_buf, cand_bufs, segments, atol: float, rtol: float, equal_nan: bool,
+                 threads: int = 1) -> np.ndarray:
+    """Ragged case.  segments: iterable of (byte_offset, numel, dtype_name); every candidate
+    buffer is packed with the same table as the reference.  Returns records of shape (S, K),
+    index [s, k]."""
+    rb = _as_bytes(ref_buf)
+    cbs = [_as_bytes(c) for c in cand_bufs]
+    segments = list(segments)
+    jobs = []
+    for (off, numel, dt) in segments:
+        for cb in cbs:
+            jobs.append(
+                lambda off=off, numel=numel, dt=dt, cb=cb: check_segment(
+                    rb, cb, numel, dt, atol, rtol, equal_nan, ref_byte_offset=off)
+            )
+    flat = _run_pairs(jobs, threads)
+    return np.array(flat, dtype=RECORD_DTYPE).reshape(len(segments), len(cbs))

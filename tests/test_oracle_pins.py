@@ -1,0 +1,350 @@
+"""Pins for the CPU oracle: each test checks it against something fixed by the rule's
+definition or by mathematics, not against another run of the same formula.
+
+  * hand-derived records (tests/golden/pins.txt)
+  * its fp16 / bf16 decoders against numpy's and torch's conversions, all 65536 patterns
+  * an exact rational-arithmetic model of the binary32 rounding steps (fractions.Fraction with
+    an explicit round-to-nearest-even), including a case that a fused multiply-add gets wrong
+  * structural invariants (copy, independence of K, concatenation, permutation, empty)
+  * numpy.isclose on finite data away from the tolerance boundary
+  * mismatch counts and first indices known from how the synthetic workloads were planted
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import load_pins, record_tuple, expect_tuple, NP_STORAGE
+from paper_2507_23194_amd import synth
+
+PINS = load_pins()
+
+
+# ------------------------------------------------------------------------------------------
+# hand-derived golden records
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", PINS, ids=[c["name"] for c in PINS])
+def test_golden_pin(oracle_mod, case):
+    rec = oracle_mod.check_segment(case["ref"], case["cand"], case["ref"].size, case["dtype"],
+                                   case["atol"], case["rtol"], case["equal_nan"])
+    assert record_tuple(rec) == expect_tuple(case["expect"]), (case["name"], rec)
+
+
+def test_pins_cover_every_policy_branch():
+    names = " ".join(c["name"] for c in PINS)
+    for key in ("boundary_f32", "boundary_f16", "boundary_bf16", "nan_equal", "nan_not_equal",
+                "inf_same", "inf_opposite", "fin_vs_inf", "inf_vs_fin", "tol_overflow",
+                "signed_zero", "subnormal", "int_off_by_one", "int_extremes", "empty"):
+        assert key in names
+
+
+# ------------------------------------------------------------------------------------------
+# decoders against library conversions
+# ------------------------------------------------------------------------------------------
+def _same_float(x: float, y: float) -> bool:
+    if math.isnan(x) or math.isnan(y):
+        return math.isnan(x) and math.isnan(y)
+    return x == y and math.copysign(1.0, x) == math.copysign(1.0, y)
+
+
+def test_decode_f16_all_patterns(oracle_mod):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    lib = bits.view(np.float16).astype(np.float32)
+    for h in range(65536):
+        assert _same_float(oracle_mod.decode_f16(h), float(lib[h])), hex(h)
+
+
+def test_decode_bf16_all_patterns(oracle_mod):
+    bits = torch.arange(65536, dtype=torch.int32)
+    bits = torch.where(bits >= 0x8000, bits - 0x10000, bits).to(torch.int16)
+    lib = bits.view(torch.bfloat16).to(torch.float32).numpy()
+    for h in range(65536):
+        assert _same_float(oracle_mod.decode_bf16(h), float(lib[h])), hex(h)
+
+
+# ------------------------------------------------------------------------------------------
+# exact rational model of the arithmetic
+# ------------------------------------------------------------------------------------------
+INF = "inf"
+
+
+def rn32(x):
+    """Round a non-negative exact rational to binary32, nearest-even, subnormals kept,
+    overflow to INF.  Pure integer arithmetic."""
+    if x == INF:
+        return INF
+    assert x >= 0
+    if x == 0:
+        return Fraction(0)
+    num, den = x.numerator, x.denominator
+    e = num.bit_length() - den.bit_length()          # 2^(e-1) < x < 2^(e+1)
+    if Fraction(2) ** e > x:
+        e -= 1                                        # now 2^e <= x < 2^(e+1)
+    q_exp = max(e, -126) - 23                         # exponent of one unit in the last place
+    scaled = x / (Fraction(2) ** q_exp)
+    n = scaled.numerator // scaled.denominator
+    rem = scaled - n
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and n % 2 == 1):
+        n += 1
+    y = n * Fraction(2) ** q_exp
+    return INF if y >= Fraction(2) ** 128 else y
+
+
+def model_element(a: float, b: float, atol_f: float, rtol_f: float):
+    """Finite a, b (binary32 values held in Python floats).  Returns (close, d, r) with d, r
+    exact rationals or INF, each step rounded once, product and sum rounded separately."""
+    fa, fb = Fraction(a), Fraction(b)
+    d = rn32(abs(fa - fb))
+    prod = rn32(Fraction(rtol_f) * abs(fb))
+    tol = INF if prod == INF else rn32(Fraction(atol_f) + prod)
+    if tol == INF:
+        close = True
+    elif d == INF:
+        close = False
+    else:
+        close = d <= tol
+    if d == 0:
+        r = Fraction(0)
+    elif d == INF or fb == 0:
+        r = INF
+    else:
+        r = rn32(d / abs(fb))
+    return close, d, r
+
+
+def _to_float(x):
+    return math.inf if x == INF else float(x)
+
+
+def _boundary_cases(rng, n):
+    """Random finite binary32 (b, a, atol, rtol) with a placed within a few ulps of b +- tol."""
+    out = []
+    for _ in range(n):
+        kind = rng.integers(0, 4)
+        if kind == 0:      # ordinary magnitudes
+            b = np.float32(rng.normal() * 10.0 ** rng.integers(-3, 4))
+        elif kind == 1:    # subnormal / tiny reference
+            b = np.array([rng.integers(0, 1 << 24)], dtype=np.uint32).view(np.float32)[0]
+            if rng.random() < 0.5:
+                b = -b
+        elif kind == 2:    # huge reference
+            b = np.float32(rng.normal() * 1e37)
+        else:              # any finite bit pattern
+            u = np.uint32(rng.integers(0, 1 << 32))
+            if (u & 0x7F800000) == 0x7F800000:
+                u = np.uint32(u & 0x807FFFFF)
+            b = np.array([u], dtype=np.uint32).view(np.float32)[0]
+        atol = float(np.float32(10.0 ** rng.uniform(-45, 1))) if rng.random() < 0.8 else 0.0
+        rtol = float(np.float32(10.0 ** rng.uniform(-8, 0.5))) if rng.random() < 0.8 else 0.0
+        tol64 = atol + rtol * abs(float(b))
+        target = float(b) + (tol64 if rng.random() < 0.5 else -tol64)
+        if not math.isfinite(target) or abs(target) > 3.0e38:
+            target = float(b)
+        a0 = np.float32(target)
+        ai = a0.view(np.int32) + np.int32(rng.integers(-3, 4))
+        a = np.array([ai], dtype=np.int32).view(np.float32)[0]
+        if not np.isfinite(a):
+            a = a0
+        out.append((float(b), float(a), atol, rtol))
+    return out
+
+
+def test_rational_model_matches_oracle(oracle_mod):
+    rng = np.random.default_rng(20250723)
+    boundary_hits = 0
+    for (b, a, atol, rtol) in _boundary_cases(rng, 4000):
+        atol_f, rtol_f = float(np.float32(atol)), float(np.float32(rtol))
+        close, d, r = model_element(a, b, atol_f, rtol_f)
+        rec = oracle_mod.check_segment(np.array([b], np.float32), np.array([a], np.float32), 1, "f32",
+                                       atol, rtol, False)
+        exp = (int(close), int(not close), -1 if close else 0, _to_float(d), _to_float(r))
+        got = (int(rec["pass"]), int(rec["mismatch_count"]), int(rec["first_mismatch"]),
+               float(rec["max_abs_err"]), float(rec["max_rel_err"]))
+        assert got == exp, (b, a, atol, rtol, got, exp)
+        prod = rn32(Fraction(rtol_f) * abs(Fraction(b)))
+        if prod != INF and d != INF and d == rn32(Fraction(atol_f) + prod):
+            boundary_hits += 1
+    assert boundary_hits > 50            # the generator really lands on the inclusive boundary
+
+
+def test_fma_contraction_would_be_caught(oracle_mod):
+    """Find (b, rtol, atol) where rounding the product before the sum changes the tolerance,
+    put d exactly on the two-rounding tolerance, and require the two-rounding verdict."""
+    rng = np.random.default_rng(7)
+    found = 0
+    for _ in range(20000):
+        b = float(np.float32(rng.uniform(1.0, 2.0)))
+        rtol = float(np.float32(rng.uniform(1e-3, 1e-2)))
+        atol = float(np.float32(rng.uniform(1e-3, 1e-2)))
+        two = rn32(Fraction(atol) + rn32(Fraction(rtol) * Fraction(b)))
+        one = rn32(Fraction(atol) + Fraction(rtol) * Fraction(b))
+        if two == one:
+            continue
+        # a = b + max(two, one): representable?  d must equal the larger tolerance exactly
+        big, small = max(two, one), min(two, one)
+        a = float(np.float32(float(Fraction(b) + big)))
+        if rn32(abs(Fraction(a) - Fraction(b))) != big:
+            continue
+        rec = oracle_mod.check_segment(np.array([b], np.float32), np.array([a], np.float32), 1, "f32",
+                                       atol, rtol, False)
+        assert int(rec["pass"]) == int(big == two), (b, a, atol, rtol)
+        found += 1
+        if found >= 25:
+            break
+    assert found >= 25
+
+
+# ------------------------------------------------------------------------------------------
+# structural invariants
+# ------------------------------------------------------------------------------------------
+def _rand_case(rng, dtype, n):
+    if dtype == "i32":
+        b = rng.integers(-1000, 1001, n).astype(np.int32)
+        a = b.copy()
+        idx = rng.random(n) < 0.05
+        a[idx] += rng.integers(-3, 4, int(idx.sum())).astype(np.int32)
+        return b, a
+    b32 = rng.normal(size=n).astype(np.float32)
+    a32 = (b32 + 1e-3 * rng.normal(size=n) * (rng.random(n) < 0.3)).astype(np.float32)
+    sp = rng.random(n) < 0.02
+    a32[sp] = rng.choice(np.array([np.nan, np.inf, -np.inf, 0.0, -0.0], np.float32), int(sp.sum()))
+    sp = rng.random(n) < 0.02
+    b32[sp] = rng.choice(np.array([np.nan, np.inf, -np.inf, 0.0, -0.0], np.float32), int(sp.sum()))
+    if dtype == "f32":
+        return b32, a32
+    if dtype == "f16":
+        return b32.astype(np.float16).view(np.uint16), a32.astype(np.float16).view(np.uint16)
+    tb = torch.from_numpy(b32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    ta = torch.from_numpy(a32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    return tb, ta
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32"])
+def test_invariants(oracle_mod, dtype):
+    rng = np.random.default_rng(11)
+    n = 3001
+    b, a = _rand_case(rng, dtype, n)
+    kw = dict(atol=1e-4, rtol=1e-3, equal_nan=True)
+    full = oracle_mod.check_segment(b, a, n, dtype, **kw)
+
+    # a bit-identical copy of a NaN-free tensor is the neutral record
+    if dtype == "i32":
+        clean = b
+    else:
+        _, clean = _rand_case(np.random.default_rng(12), dtype, n)
+        store = clean.view(np.uint32) if dtype == "f32" else clean
+        expo = (store & 0x7F800000) == 0x7F800000 if dtype == "f32" else (
+            (store & 0x7C00) == 0x7C00 if dtype == "f16" else (store & 0x7F80) == 0x7F80)
+        clean = clean.copy()
+        clean[expo] = 0
+    cp = oracle_mod.check_segment(clean, clean.copy(), n, dtype, **kw)
+    assert record_tuple(cp) == (1, 0, -1, 0, 0)
+
+    # independent of how many other candidates ride along
+    many = oracle_mod.check_dense(b, [b, a, a[::-1].copy(), a], dtype, 1e-4, 1e-3, True)
+    assert record_tuple(many[1]) == record_tuple(full) == record_tuple(many[3])
+
+    # concatenation: result(X || Y) = combine(result X, result Y)
+    cut = 1234
+    w = b.itemsize
+    x = oracle_mod.check_segment(b[:cut], a[:cut], cut, dtype, **kw)
+    y = oracle_mod.check_segment(b[cut:], a[cut:], n - cut, dtype, **kw)
+    cnt = int(x["mismatch_count"]) + int(y["mismatch_count"])
+    first = int(x["first_mismatch"]) if x["first_mismatch"] >= 0 else (
+        int(y["first_mismatch"]) + cut if y["first_mismatch"] >= 0 else -1)
+    assert int(full["mismatch_count"]) == cnt and int(full["first_mismatch"]) == first
+    assert float(full["max_abs_err"]) == max(float(x["max_abs_err"]), float(y["max_abs_err"]))
+    assert float(full["max_rel_err"]) == max(float(x["max_rel_err"]), float(y["max_rel_err"]))
+    assert int(full["pass"]) == int(cnt == 0)
+    del w
+
+    # permuting elements keeps the count and both maxima
+    perm = rng.permutation(n)
+    p = oracle_mod.check_segment(b[perm].copy(), a[perm].copy(), n, dtype, **kw)
+    assert record_tuple(p)[1] == record_tuple(full)[1]
+    assert record_tuple(p)[3:] == record_tuple(full)[3:]
+
+    # first_mismatch really is the least failing index: the prefix before it passes
+    f = int(full["first_mismatch"])
+    assert f >= 0
+    pre = oracle_mod.check_segment(b[:f], a[:f], f, dtype, **kw)
+    assert int(pre["pass"]) == 1
+    one = oracle_mod.check_segment(b[f:f + 1], a[f:f + 1], 1, dtype, **kw)
+    assert int(one["pass"]) == 0
+
+
+def test_ragged_offsets_and_index_space(oracle_mod):
+    """Ragged records are indexed [segment, candidate] and first_mismatch is segment-relative."""
+    rng = np.random.default_rng(5)
+    buf = np.zeros(256, np.uint8)
+    segs = [(16, 10, "f32"), (64, 7, "i32"), (100, 20, "f16"), (144, 0, "bf16")]
+    ref = buf.copy()
+    ref[16:56] = rng.normal(size=10).astype(np.float32).view(np.uint8)
+    ref[64:92] = np.arange(7, dtype=np.int32).view(np.uint8)
+    ref[100:140] = rng.normal(size=20).astype(np.float16).view(np.uint8)
+    c0 = ref.copy()
+    c1 = ref.copy()
+    c1[16 + 4 * 3:16 + 4 * 4] = np.array([1e6], np.float32).view(np.uint8)      # element 3 of segment 0
+    c1[64 + 4 * 5:64 + 4 * 6] = np.array([6], np.int32).view(np.uint8)          # element 5 of segment 1: 5 -> 6
+    rec = oracle_mod.check_ragged(ref, [c0, c1], segs, 1e-3, 1e-3, False)
+    assert rec.shape == (4, 2)
+    for s in range(4):
+        assert record_tuple(rec[s, 0]) == (1, 0, -1, 0, 0)
+    assert (int(rec[0, 1]["mismatch_count"]), int(rec[0, 1]["first_mismatch"])) == (1, 3)
+    assert (int(rec[1, 1]["mismatch_count"]), int(rec[1, 1]["first_mismatch"])) == (1, 5)
+    assert float(rec[1, 1]["max_abs_err"]) == 1.0 and float(rec[1, 1]["max_rel_err"]) == 1.0 / 5.0
+    assert record_tuple(rec[2, 1]) == (1, 0, -1, 0, 0)
+    assert record_tuple(rec[3, 1]) == (1, 0, -1, 0, 0)          # empty segment passes
+
+
+# ------------------------------------------------------------------------------------------
+# library special case: numpy.isclose on finite data, away from the boundary
+# ------------------------------------------------------------------------------------------
+def test_agrees_with_numpy_isclose_off_boundary(oracle_mod):
+    rng = np.random.default_rng(3)
+    n = 20000
+    b = rng.normal(size=n).astype(np.float32)
+    a = (b + rng.normal(size=n) * 10.0 ** rng.uniform(-8, -1, n)).astype(np.float32)
+    atol, rtol = 1e-5, 1e-4
+    d64 = np.abs(a.astype(np.float64) - b.astype(np.float64))
+    t64 = atol + rtol * np.abs(b.astype(np.float64))
+    near = np.abs(d64 - t64) <= 1e-5 * t64            # our binary32 steps may differ only here
+    lib_close = np.isclose(a, b, rtol=rtol, atol=atol)
+    keep = ~near
+    rec = oracle_mod.check_segment(b[keep].copy(), a[keep].copy(), int(keep.sum()), "f32", atol, rtol, False)
+    assert int(rec["mismatch_count"]) == int((~lib_close[keep]).sum())
+    bad = np.nonzero(~lib_close[keep])[0]
+    assert int(rec["first_mismatch"]) == (int(bad[0]) if bad.size else -1)
+    assert 0.2 < (~lib_close).mean() < 0.8            # both verdicts occur in bulk
+    # maxima against float64 evaluation: binary32 subtraction/division are within 1 ulp of these
+    assert abs(float(rec["max_abs_err"]) - d64[keep].max()) <= 2.0 ** -23 * d64[keep].max()
+    nz = keep & (b != 0)
+    rel64 = (d64[nz] / np.abs(b[nz].astype(np.float64))).max()
+    assert abs(float(rec["max_rel_err"]) - rel64) <= 2.0 ** -22 * rel64
+
+
+# ------------------------------------------------------------------------------------------
+# closed-form facts of the synthetic workloads
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_planted_counts(oracle_mod, cid):
+    w = synth.small(cid, device="cpu")
+    ref = synth.to_numpy_raw(w.ref)
+    cands = [synth.to_numpy_raw(c) for c in w.cands]
+    if w.segments is None:
+        rec = oracle_mod.check_dense(ref, cands, w.dtype, w.atol, w.rtol, w.equal_nan, threads=4).reshape(1, -1)
+    else:
+        rec = oracle_mod.check_ragged(ref, cands, w.segments, w.atol, w.rtol, w.equal_nan, threads=4)
+    assert len(w.expect) == rec.size
+    n_fail = 0
+    for (s, k), e in w.expect.items():
+        r = rec[s, k]
+        assert int(r["mismatch_count"]) == e["count"], (cid, s, k)
+        assert int(r["first_mismatch"]) == e["first"], (cid, s, k)
+        assert int(r["pass"]) == int(e["count"] == 0)
+        n_fail += e["count"] > 0
+    assert n_fail > 0
+    if cid in (1, 3, 4):
+        assert n_fail < rec.size            # these recipes contain passing candidates too
