@@ -1,0 +1,180 @@
+/*
+ * geak_check -- output-equivalence check of K candidate tensors against one reference tensor,
+ * on one MI355X (gfx950).  C ABI; plain pointers and sizes only.
+ *
+ * What it computes.  The evaluator of the GEAK kernel-generation agent (arXiv 2507.23194) judges
+ * a candidate kernel by a "tolerance based tensor comparison of output tensors produced by test
+ * functions" against reference outputs (section 3.1, second enhancement bullet); a kernel is
+ * correct only if it satisfies all unit tests and the reference kernels are the ground truth
+ * (section 3.3); the check runs once per candidate x unit test x refinement iteration x parallel
+ * run (sections 4.1, 4.2, 5.2).  The paper gives no formula, so this library fixes one:
+ *
+ *   floating dtypes, a = candidate element, b = reference element, all steps in IEEE binary32,
+ *   round-to-nearest-even, one rounding per step, no fused multiply-add, subnormals honoured:
+ *       d = |a - b|,  tol = atol_f + (rtol_f * |b|),  close <=> d <= tol
+ *       a or b NaN   : close <=> equal_nan and both NaN
+ *       a or b +-Inf : close <=> a == b
+ *   int32:             close <=> a == b   (atol, rtol, equal_nan ignored; d exact)
+ *
+ *   and reduces, for every (segment, candidate) pair, the record `geak_result`:
+ *       mismatch_count  number of elements that are not close
+ *       first_mismatch  least flat 0-based index (within the segment) that is not close, else -1
+ *       pass            1 iff mismatch_count == 0 (an empty segment passes)
+ *       max_abs_err     max of d over ALL elements, NaN d skipped, +Inf kept, starting at +0
+ *       max_rel_err     max over all elements of (d == 0 ? 0 : d / |b|) (binary32 division for
+ *                       floating dtypes, binary64 for int32; x/0 = +Inf; NaN skipped), from +0
+ *   Every field is an order-independent reduction, so results are bit-reproducible.
+ *
+ * Memory model.  The caller owns every device buffer (reference, candidates, workspace, results)
+ * and the HIP stream.  The library owns only the opaque plan: a host structure plus a small device
+ * work table allocated in geak_check_plan and freed in geak_check_destroy.  geak_check_run is
+ * asynchronous on the given stream, never synchronises and never allocates.
+ */
+#ifndef GEAK_CHECK_H
+#define GEAK_CHECK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GEAK_OK = 0,
+    GEAK_EINVAL = 1,     /* null pointer, nsegs == 0, K out of range, bad atol/rtol/equal_nan, host-only plan run */
+    GEAK_EDTYPE = 2,     /* unknown dtype code */
+    GEAK_EALIGN = 3,     /* byte_offset not a multiple of the element size; base pointer not 16-byte aligned */
+    GEAK_EBOUNDS = 4,    /* byte_offset + numel * size overflows, segments overlap, or too many elements */
+    GEAK_ENOMEM = 5,     /* host or device allocation failed while planning */
+    GEAK_EWORKSPACE = 6, /* workspace pointer missing although geak_check_workspace_bytes() > 0 */
+    GEAK_EHIP = 7        /* a HIP runtime call failed (no device, launch error) */
+} geak_status;
+
+typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3 } geak_dtype;
+
+#define GEAK_MAX_CANDIDATES 256
+#define GEAK_MAX_SEGMENT_NUMEL (1ull << 40)
+
+/* One tensor of a packed (ragged) batch.  Every buffer -- the reference and each candidate -- is
+ * packed with the same table.  byte_offset must be a multiple of the element size; 16-byte aligned
+ * starts take the vector path from the first element, other starts peel a short head.  numel == 0 is
+ * legal.  Segments must not overlap. */
+typedef struct {
+    uint64_t byte_offset;
+    uint64_t numel;
+    int32_t  dtype;      /* geak_dtype */
+    int32_t  reserved;   /* must be 0 */
+} geak_segment;
+
+/* One record per (segment, candidate); see the file comment for field meaning.  40 bytes. */
+typedef struct {
+    int32_t  pass;
+    int32_t  reserved;
+    uint64_t mismatch_count;
+    int64_t  first_mismatch;
+    double   max_abs_err;
+    double   max_rel_err;
+} geak_result;
+
+typedef struct geak_plan geak_plan; /* opaque */
+
+/*
+ * Plan a check of `num_candidates` packed candidate buffers against one packed reference buffer
+ * (section 3.3: a kernel has many unit-test outputs and must satisfy all of them -- one segment per
+ * output).  Validates the arguments, cuts the segments into fixed-size work items, assigns them to
+ * the persistent grid and sizes the workspace.
+ *   out            receives the plan; untouched on failure
+ *   segs, nsegs    host array, copied; nsegs >= 1
+ *   num_candidates 1 .. GEAK_MAX_CANDIDATES
+ *   atol, rtol     finite, >= 0; converted once to binary32
+ *   equal_nan      0 or 1
+ *   device         HIP device ordinal that geak_check_run will use; -1 builds a host-only plan
+ *                  (for inspection; geak_check_run then returns GEAK_EINVAL) laid out for 256 compute units
+ * Returns GEAK_OK or an error code; never throws, aborts or prints.
+ */
+geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t nsegs,
+                            int32_t num_candidates, double atol, double rtol, int32_t equal_nan,
+                            int32_t device);
+
+/* Dense convenience (section 3.1: one output tensor against its reference): a single segment at
+ * offset 0 with prod(shape) elements; shape is a host array of ndim >= 0 non-negative extents
+ * (ndim == 0 is a scalar).  Only the element count matters: indices are flat, row-major. */
+geak_status geak_check_plan_dense(geak_plan **out, int32_t dtype, const int64_t *shape, int32_t ndim,
+                                  int32_t num_candidates, double atol, double rtol, int32_t equal_nan,
+                                  int32_t device);
+
+/* Bytes of device workspace geak_check_run needs (may be 0); the buffer must be 16-byte aligned. */
+uint64_t geak_check_workspace_bytes(const geak_plan *plan);
+
+/* Number of result records = nsegs * num_candidates; record index = segment * num_candidates + candidate. */
+uint64_t geak_check_result_count(const geak_plan *plan);
+
+/*
+ * Run the planned check (the comparison of section 3.1 for all candidates in one pass: the
+ * reference is read once and every candidate once).
+ *   ref_dev      device pointer, packed reference buffer, 16-byte aligned (may be NULL, like the
+ *                candidate pointers, when every segment is empty: nothing is read then)
+ *   cand_dev     HOST array of num_candidates DEVICE pointers, each 16-byte aligned and packed like ref_dev
+ *   workspace    device pointer to geak_check_workspace_bytes() bytes (ignored when that is 0)
+ *   results_dev  device pointer to geak_check_result_count() records; fully overwritten
+ *   hip_stream   hipStream_t (NULL = default stream); three kernels are enqueued on it
+ * Results are valid once the caller has synchronised the stream.  Concurrent runs of one plan are
+ * allowed when they use distinct workspace and results buffers.
+ */
+geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                           void *workspace_dev, geak_result *results_dev, void *hip_stream);
+
+void geak_check_destroy(geak_plan *plan);
+
+const char *geak_status_string(geak_status status);
+
+/* ---- inspection (host only; used by tests and the benchmark's reporting) ---------------------- */
+
+typedef struct {
+    uint64_t num_segments;
+    uint64_t num_items;          /* work items (one wavefront processes one item against all candidates) */
+    uint64_t num_slots;          /* partial-result slots in the workspace */
+    uint64_t algorithmic_bytes;  /* (K + 1) * sum(numel * element size): every element of every tensor once */
+    uint32_t num_candidates;
+    uint32_t grid_blocks;        /* persistent grid of the compare kernel */
+    uint32_t block_threads;
+    uint32_t lds_bytes;          /* dynamic LDS per block */
+    uint32_t item_bytes;         /* bytes of one full work item per tensor */
+    int32_t  device;
+} geak_plan_info;
+
+/* One work item, as the compare kernel sees it. */
+typedef struct {
+    uint64_t byte_offset;  /* of the item's first element, within every packed buffer */
+    uint64_t elem_start;   /* flat index of that element within its segment */
+    uint32_t segment;
+    uint32_t slot;         /* workspace slot its run accumulates into */
+    uint32_t numel;        /* 1 .. item_bytes / element size */
+    uint8_t  dtype;
+    uint8_t  flags;        /* GEAK_ITEM_* */
+    uint16_t reserved;
+} geak_item;
+
+#define GEAK_ITEM_FULL  1u /* 16-byte aligned start and exactly item_bytes long: vector loads */
+#define GEAK_ITEM_FIRST 2u /* first item of its (worker, segment) run: running state is reset */
+#define GEAK_ITEM_LAST  4u /* last item of its run: running state is written to the slot */
+
+geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
+
+/* Copies up to `capacity` items into `out` (host); returns the total number of items. */
+uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t capacity);
+
+/* ---- optional device timing of the compare kernel (section 4.1: the evaluator also measures
+ * latency; here the check times itself) ---------------------------------------------------------
+ * After geak_check_profile_enable(plan, n) every geak_check_run records a HIP event pair around the
+ * compare kernel on the run's stream, into a ring of n pairs (no synchronisation is added).
+ * geak_check_profile_read must be called after the caller has synchronised the stream(s); it
+ * returns the number of milliseconds values written (oldest first, at most capacity) and resets the
+ * ring.  While profiling is enabled, runs of this plan must not overlap.  n == 0 disables it. */
+geak_status geak_check_profile_enable(geak_plan *plan, uint32_t num_pairs);
+uint64_t    geak_check_profile_read(geak_plan *plan, float *ms_out, uint64_t capacity);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEAK_CHECK_H */

@@ -1,0 +1,244 @@
+"""ctypes binding of libgeakcheck.so -- argument marshalling only.
+
+Every function named ``geak_check_*`` below is the C entry point of the same name declared in
+``include/geak_check.h``; all computation happens in the HIP kernels behind it.  PyTorch is used
+for device memory and streams and nowhere else.  There is no CPU fallback: if the library has not
+been built, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgeakcheck.so")
+BUILD_SCRIPT = os.path.join(_HERE, "csrc", "build.sh")
+
+GEAK_OK = 0
+GEAK_EINVAL, GEAK_EDTYPE, GEAK_EALIGN, GEAK_EBOUNDS, GEAK_ENOMEM, GEAK_EWORKSPACE, GEAK_EHIP = 1, 2, 3, 4, 5, 6, 7
+GEAK_F32, GEAK_F16, GEAK_BF16, GEAK_I32 = 0, 1, 2, 3
+GEAK_MAX_CANDIDATES = 256
+GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST = 1, 2, 4
+
+DTYPE_CODE = {"f32": GEAK_F32, "f16": GEAK_F16, "bf16": GEAK_BF16, "i32": GEAK_I32}
+ELEM_SIZE = {GEAK_F32: 4, GEAK_F16: 2, GEAK_BF16: 2, GEAK_I32: 4}
+
+SEGMENT_DTYPE = np.dtype([("byte_offset", "<u8"), ("numel", "<u8"), ("dtype", "<i4"), ("reserved", "<i4")])
+RESULT_DTYPE = np.dtype([("pass", "<i4"), ("reserved", "<i4"), ("mismatch_count", "<u8"),
+                         ("first_mismatch", "<i8"), ("max_abs_err", "<f8"), ("max_rel_err", "<f8")])
+ITEM_DTYPE = np.dtype([("byte_offset", "<u8"), ("elem_start", "<u8"), ("segment", "<u4"), ("slot", "<u4"),
+                       ("numel", "<u4"), ("dtype", "u1"), ("flags", "u1"), ("reserved", "<u2")])
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [("num_segments", ctypes.c_uint64), ("num_items", ctypes.c_uint64), ("num_slots", ctypes.c_uint64),
+                ("algorithmic_bytes", ctypes.c_uint64), ("num_candidates", ctypes.c_uint32),
+                ("grid_blocks", ctypes.c_uint32), ("block_threads", ctypes.c_uint32), ("lds_bytes", ctypes.c_uint32),
+                ("item_bytes", ctypes.c_uint32), ("device", ctypes.c_int32)]
+
+
+class GeakError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {geak_status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/ for gfx950 with hipcc into libgeakcheck.so next to this file."""
+    proc = subprocess.run(["bash", BUILD_SCRIPT], capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("building libgeakcheck.so failed:\n" + proc.stdout + proc.stderr)
+    if verbose:
+        print(proc.stdout.strip())
+    return LIB_PATH
+
+
+def library() -> ctypes.CDLL:
+    """The loaded C library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run paper_2507_23194_amd/csrc/build.sh "
+                               "(or __graft_entry__.build()) first; there is no CPU fallback")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, u64, i32, dbl = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_double
+        lib.geak_check_plan.restype = ctypes.c_int
+        lib.geak_check_plan.argtypes = [ctypes.POINTER(vp), vp, u64, i32, dbl, dbl, i32, i32]
+        lib.geak_check_plan_dense.restype = ctypes.c_int
+        lib.geak_check_plan_dense.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(ctypes.c_int64), i32, i32, dbl, dbl, i32, i32]
+        lib.geak_check_workspace_bytes.restype = u64
+        lib.geak_check_workspace_bytes.argtypes = [vp]
+        lib.geak_check_result_count.restype = u64
+        lib.geak_check_result_count.argtypes = [vp]
+        lib.geak_check_run.restype = ctypes.c_int
+        lib.geak_check_run.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, vp]
+        lib.geak_check_destroy.restype = None
+        lib.geak_check_destroy.argtypes = [vp]
+        lib.geak_status_string.restype = ctypes.c_char_p
+        lib.geak_status_string.argtypes = [ctypes.c_int]
+        lib.geak_check_plan_info.restype = ctypes.c_int
+        lib.geak_check_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+        lib.geak_check_plan_items.restype = u64
+        lib.geak_check_plan_items.argtypes = [vp, vp, u64]
+        lib.geak_check_profile_enable.restype = ctypes.c_int
+        lib.geak_check_profile_enable.argtypes = [vp, ctypes.c_uint32]
+        lib.geak_check_profile_read.restype = u64
+        lib.geak_check_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), u64]
+        _lib = lib
+    return _lib
+
+
+EXPORTED = ["geak_check_plan", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
+            "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
+            "geak_check_plan_items", "geak_check_profile_enable", "geak_check_profile_read"]
+
+
+# ---- one Python function per C entry point -------------------------------------------------------
+def geak_status_string(status: int) -> str:
+    return library().geak_status_string(int(status)).decode()
+
+
+def geak_check_plan(segments, num_candidates: int, atol: float, rtol: float, equal_nan, device: int):
+    """segments: iterable of (byte_offset, numel, dtype code or name).  Returns (status, plan handle or None)."""
+    segs = list(segments)
+    arr = np.zeros(len(segs), dtype=SEGMENT_DTYPE)
+    for i, (off, n, dt) in enumerate(segs):
+        arr[i] = (off, n, DTYPE_CODE.get(dt, dt), 0)
+    return geak_check_plan_raw(arr, len(segs), num_candidates, atol, rtol, int(equal_nan), device)
+
+
+def geak_check_plan_raw(seg_array, nsegs: int, num_candidates: int, atol: float, rtol: float, equal_nan: int, device: int):
+    """As the C call: seg_array is a numpy SEGMENT_DTYPE array or None (null pointer)."""
+    out = ctypes.c_void_p(None)
+    ptr = None if seg_array is None else seg_array.ctypes.data
+    st = library().geak_check_plan(ctypes.byref(out), ptr, nsegs, num_candidates, float(atol), float(rtol),
+                                   int(equal_nan), int(device))
+    return st, (out.value if st == GEAK_OK else None)
+
+
+def geak_check_plan_dense(dtype, shape: Sequence[int], num_candidates: int, atol: float, rtol: float, equal_nan, device: int):
+    out = ctypes.c_void_p(None)
+    shp = (ctypes.c_int64 * max(1, len(shape)))(*shape)
+    st = library().geak_check_plan_dense(ctypes.byref(out), DTYPE_CODE.get(dtype, dtype), shp, len(shape), num_candidates,
+                                         float(atol), float(rtol), int(equal_nan), int(device))
+    return st, (out.value if st == GEAK_OK else None)
+
+
+def geak_check_workspace_bytes(plan) -> int:
+    return int(library().geak_check_workspace_bytes(plan))
+
+
+def geak_check_result_count(plan) -> int:
+    return int(library().geak_check_result_count(plan))
+
+
+def geak_check_run(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: int, results_ptr: int, stream: int) -> int:
+    """All pointers are device addresses as integers; stream is a hipStream_t as integer (0 = default)."""
+    arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
+    return int(library().geak_check_run(plan, ref_ptr, arr, workspace_ptr, results_ptr, stream))
+
+
+def geak_check_destroy(plan) -> None:
+    library().geak_check_destroy(plan)
+
+
+def geak_check_plan_info(plan) -> PlanInfo:
+    info = PlanInfo()
+    st = library().geak_check_plan_info(plan, ctypes.byref(info))
+    if st != GEAK_OK:
+        raise GeakError(st, "geak_check_plan_info")
+    return info
+
+
+def geak_check_plan_items(plan) -> np.ndarray:
+    n = int(library().geak_check_plan_items(plan, None, 0))
+    out = np.zeros(n, dtype=ITEM_DTYPE)
+    if n:
+        library().geak_check_plan_items(plan, out.ctypes.data, n)
+    return out
+
+
+def geak_check_profile_enable(plan, num_pairs: int) -> int:
+    return int(library().geak_check_profile_enable(plan, num_pairs))
+
+
+def geak_check_profile_read(plan, capacity: int) -> np.ndarray:
+    buf = (ctypes.c_float * max(1, capacity))()
+    n = int(library().geak_check_profile_read(plan, buf, capacity))
+    return np.array(buf[:n], dtype=np.float32)
+
+
+# ---- torch plumbing: device buffers and the current stream ----------------------------------------
+class Checker:
+    """A plan plus its workspace and results buffers (torch tensors on the plan's device)."""
+
+    def __init__(self, segments=None, *, dense=None, num_candidates: int, atol: float, rtol: float,
+                 equal_nan: bool, device: int = 0):
+        import torch
+        if dense is not None:
+            dtype, shape = dense
+            st, plan = geak_check_plan_dense(dtype, list(shape), num_candidates, atol, rtol, equal_nan, device)
+        else:
+            st, plan = geak_check_plan(segments, num_candidates, atol, rtol, equal_nan, device)
+        if st != GEAK_OK:
+            raise GeakError(st, "geak_check_plan")
+        self.plan = plan
+        self.device = device
+        self.num_candidates = num_candidates
+        dev = torch.device("cuda", device)
+        self.workspace = torch.empty(max(16, geak_check_workspace_bytes(plan)), dtype=torch.uint8, device=dev)
+        self.n_results = geak_check_result_count(plan)
+        self.results = torch.empty(self.n_results * RESULT_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+
+    def info(self) -> PlanInfo:
+        return geak_check_plan_info(self.plan)
+
+    def run(self, ref, cands) -> None:
+        """Enqueue on torch's current stream of the plan's device; asynchronous."""
+        import torch
+        assert len(cands) == self.num_candidates
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        st = geak_check_run(self.plan, ref.data_ptr(), [c.data_ptr() for c in cands],
+                            self.workspace.data_ptr(), self.results.data_ptr(), stream)
+        if st != GEAK_OK:
+            raise GeakError(st, "geak_check_run")
+
+    def read(self) -> np.ndarray:
+        """Synchronise and return the records as a RESULT_DTYPE array of shape (segments, candidates)."""
+        import torch
+        torch.cuda.current_stream(self.device).synchronize()
+        host = self.results.cpu().numpy().view(RESULT_DTYPE)
+        return host.reshape(-1, self.num_candidates)
+
+    def close(self) -> None:
+        if self.plan is not None:
+            geak_check_destroy(self.plan)
+            self.plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def check_workload(w, device: int = 0) -> np.ndarray:
+    """Run a synth.Workload (tensors already on the device) and return its records (segments, candidates)."""
+    if w.segments is None:
+        ck = Checker(dense=(w.dtype, (w.ref.numel(),)), num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol,
+                     equal_nan=w.equal_nan, device=device)
+    else:
+        ck = Checker(w.segments, num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol, equal_nan=w.equal_nan,
+                     device=device)
+    try:
+        ck.run(w.ref, w.cands)
+        return ck.read().copy()
+    finally:
+        ck.close()

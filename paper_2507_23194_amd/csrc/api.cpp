@@ -1,0 +1,303 @@
+// C-ABI entry points: plan lifetime, argument checks, kernel enqueue.  See include/geak_check.h.
+#include <hip/hip_runtime.h>
+#include <cstring>
+#include <new>
+#include "geak_internal.hpp"
+
+using namespace geak;
+
+struct geak_plan {
+    HostPlan host;
+    int device = -1;
+    uint32_t lds_bytes = 0;
+    // device copies of the work table
+    geak_item *items_dev = nullptr;
+    uint32_t *slot_begin_dev = nullptr;
+    // optional timing ring
+    std::vector<hipEvent_t> ev_start, ev_stop;
+    uint32_t ev_next = 0, ev_used = 0;
+};
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
+    }
+    ~DeviceGuard() {
+        int cur = -1;
+        if (ok && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+void free_device_side(geak_plan *p)
+{
+    if (p->device < 0) return;
+    DeviceGuard g(p->device);
+    if (p->items_dev) (void)hipFree(p->items_dev);
+    if (p->slot_begin_dev) (void)hipFree(p->slot_begin_dev);
+    for (auto e : p->ev_start) (void)hipEventDestroy(e);
+    for (auto e : p->ev_stop) (void)hipEventDestroy(e);
+    p->items_dev = nullptr;
+    p->slot_begin_dev = nullptr;
+    p->ev_start.clear();
+    p->ev_stop.clear();
+}
+
+}  // namespace
+
+extern "C" {
+
+geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t nsegs, int32_t num_candidates,
+                            double atol, double rtol, int32_t equal_nan, int32_t device)
+{
+    if (!out) return GEAK_EINVAL;
+    if (device < -1) return GEAK_EINVAL;
+    if (num_candidates < 1 || num_candidates > GEAK_MAX_CANDIDATES) return GEAK_EINVAL;
+    if (nsegs > 0x7FFFFFFFull / GEAK_MAX_CANDIDATES) return GEAK_EINVAL;   // one reduce block per record
+
+    geak_plan *p = new (std::nothrow) geak_plan;
+    if (!p) return GEAK_ENOMEM;
+    p->device = device;
+    p->lds_bytes = lds_bytes_for(num_candidates);
+
+    uint32_t max_blocks = (uint32_t)(kDefaultComputeUnits * kDefaultBlocksPerCU);
+    if (device >= 0) {
+        int n_dev = 0;
+        if (hipGetDeviceCount(&n_dev) != hipSuccess || device >= n_dev) { delete p; return GEAK_EHIP; }
+        DeviceGuard g(device);
+        hipDeviceProp_t prop;
+        if (!g.ok || hipGetDeviceProperties(&prop, device) != hipSuccess) { delete p; return GEAK_EHIP; }
+        const int per_cu = compare_blocks_per_cu(p->lds_bytes);
+        if (per_cu <= 0 || prop.multiProcessorCount <= 0) { delete p; return GEAK_EHIP; }
+        max_blocks = (uint32_t)prop.multiProcessorCount * (uint32_t)per_cu;
+    }
+
+    geak_status st = build_host_plan(p->host, segs, nsegs, num_candidates, atol, rtol, equal_nan, max_blocks);
+    if (st != GEAK_OK) { delete p; return st; }
+
+    if (device >= 0) {
+        DeviceGuard g(device);
+        const size_t item_bytes = p->host.items.size() * sizeof(geak_item);
+        const size_t slot_bytes = p->host.slot_begin.size() * sizeof(uint32_t);
+        bool ok = g.ok;
+        if (ok && item_bytes) ok = hipMalloc((void **)&p->items_dev, item_bytes) == hipSuccess;
+        if (ok) ok = hipMalloc((void **)&p->slot_begin_dev, slot_bytes) == hipSuccess;
+        if (!ok) { free_device_side(p); delete p; return GEAK_ENOMEM; }
+        if (item_bytes) ok = hipMemcpy(p->items_dev, p->host.items.data(), item_bytes, hipMemcpyHostToDevice) == hipSuccess;
+        if (ok) ok = hipMemcpy(p->slot_begin_dev, p->host.slot_begin.data(), slot_bytes, hipMemcpyHostToDevice) == hipSuccess;
+        if (!ok) { free_device_side(p); delete p; return GEAK_EHIP; }
+    }
+    *out = p;
+    return GEAK_OK;
+}
+
+geak_status geak_check_plan_dense(geak_plan **out, int32_t dtype, const int64_t *shape, int32_t ndim,
+                                  int32_t num_candidates, double atol, double rtol, int32_t equal_nan, int32_t device)
+{
+    if (ndim < 0 || (ndim > 0 && !shape)) return GEAK_EINVAL;
+    uint64_t numel = 1;
+    for (int i = 0; i < ndim; ++i) {
+        if (shape[i] < 0) return GEAK_EINVAL;
+        const uint64_t e = (uint64_t)shape[i];
+        if (e != 0 && numel > GEAK_MAX_SEGMENT_NUMEL / e) {
+            // keep scanning: a later zero extent makes the tensor empty
+            bool zero_later = false;
+            for (int j = i + 1; j < ndim; ++j) zero_later |= (shape[j] == 0);
+            if (!zero_later) return GEAK_EBOUNDS;
+            numel = 0;
+            break;
+        }
+        numel *= e;
+    }
+    geak_segment seg;
+    seg.byte_offset = 0;
+    seg.numel = numel;
+    seg.dtype = dtype;
+    seg.reserved = 0;
+    return geak_check_plan(out, &seg, 1, num_candidates, atol, rtol, equal_nan, device);
+}
+
+uint64_t geak_check_workspace_bytes(const geak_plan *plan)
+{
+    if (!plan || plan->host.items.empty()) return 0;
+    return kCandTableBytes + (uint64_t)plan->host.slot_begin.back() * (uint64_t)plan->host.num_candidates * sizeof(Partial);
+}
+
+uint64_t geak_check_result_count(const geak_plan *plan)
+{
+    if (!plan) return 0;
+    return (uint64_t)plan->host.segments.size() * (uint64_t)plan->host.num_candidates;
+}
+
+geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                           void *workspace_dev, geak_result *results_dev, void *hip_stream)
+{
+    if (!plan || !cand_dev || !results_dev) return GEAK_EINVAL;
+    if (plan->device < 0) return GEAK_EINVAL;
+    const HostPlan &hp = plan->host;
+    const int K = hp.num_candidates;
+    const bool reads_data = !hp.items.empty();          // a plan of empty segments touches no tensor
+    if (reads_data && !ref_dev) return GEAK_EINVAL;
+    if (((uintptr_t)ref_dev & 15u) || ((uintptr_t)results_dev & 7u)) return GEAK_EALIGN;
+    for (int k = 0; k < K; ++k) {
+        if (reads_data && !cand_dev[k]) return GEAK_EINVAL;
+        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
+    }
+    const uint64_t ws_bytes = geak_check_workspace_bytes(plan);
+    if (ws_bytes && !workspace_dev) return GEAK_EWORKSPACE;
+    if (ws_bytes && ((uintptr_t)workspace_dev & 15u)) return GEAK_EALIGN;
+
+    DeviceGuard g(plan->device);
+    if (!g.ok) return GEAK_EHIP;
+
+    // workspace: [candidate pointer table][partials]
+    const unsigned char **cand_table = hp.items.empty() ? nullptr : (const unsigned char **)workspace_dev;
+    Partial *partials = hp.items.empty() ? nullptr : (Partial *)((unsigned char *)workspace_dev + kCandTableBytes);
+
+    InitArgs ia;
+    ia.results = results_dev;
+    ia.cand_table = cand_table;
+    ia.num_results = geak_check_result_count(plan);
+    ia.num_candidates = (uint32_t)K;
+    ia.reserved = 0;
+    for (int k = 0; k < GEAK_MAX_CANDIDATES; ++k) ia.cand[k] = (k < K) ? (const unsigned char *)cand_dev[k] : nullptr;
+    if (launch_init(ia, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+
+    if (!hp.items.empty()) {
+        CompareArgs ca;
+        ca.items = plan->items_dev;
+        ca.ref = (const unsigned char *)ref_dev;
+        ca.cand_table = cand_table;
+        ca.partials = partials;
+        ca.results = results_dev;
+        ca.num_items = (uint32_t)hp.items.size();
+        ca.num_candidates = (uint32_t)K;
+        ca.atol_f = hp.atol_f;
+        ca.rtol_f = hp.rtol_f;
+        ca.equal_nan = hp.equal_nan;
+        ca.reserved = 0;
+
+        geak_plan *mp = const_cast<geak_plan *>(plan);      // timing ring only; documented as not re-entrant
+        const bool timed = !mp->ev_start.empty();
+        const uint32_t slot = mp->ev_next;
+        if (timed && hipEventRecord(mp->ev_start[slot], (hipStream_t)hip_stream) != hipSuccess) return GEAK_EHIP;
+        if (launch_compare(ca, hp.grid_blocks, plan->lds_bytes, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+        if (timed) {
+            if (hipEventRecord(mp->ev_stop[slot], (hipStream_t)hip_stream) != hipSuccess) return GEAK_EHIP;
+            mp->ev_next = (slot + 1) % (uint32_t)mp->ev_start.size();
+            if (mp->ev_used < mp->ev_start.size()) ++mp->ev_used;
+        }
+
+        ReduceArgs ra;
+        ra.items = plan->items_dev;
+        ra.slot_begin = plan->slot_begin_dev;
+        ra.partials = partials;
+        ra.results = results_dev;
+        ra.ref = (const unsigned char *)ref_dev;
+        ra.cand_table = cand_table;
+        ra.num_segments = (uint32_t)hp.segments.size();
+        ra.num_candidates = (uint32_t)K;
+        ra.atol_f = hp.atol_f;
+        ra.rtol_f = hp.rtol_f;
+        ra.equal_nan = hp.equal_nan;
+        ra.reserved = 0;
+        if (launch_reduce(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+    }
+    return GEAK_OK;
+}
+
+void geak_check_destroy(geak_plan *plan)
+{
+    if (!plan) return;
+    free_device_side(plan);
+    delete plan;
+}
+
+const char *geak_status_string(geak_status status)
+{
+    switch (status) {
+    case GEAK_OK: return "ok";
+    case GEAK_EINVAL: return "invalid argument";
+    case GEAK_EDTYPE: return "unknown dtype";
+    case GEAK_EALIGN: return "misaligned offset or pointer";
+    case GEAK_EBOUNDS: return "segment out of bounds, overlapping or too large";
+    case GEAK_ENOMEM: return "out of memory";
+    case GEAK_EWORKSPACE: return "workspace missing";
+    case GEAK_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out)
+{
+    if (!plan || !out) return GEAK_EINVAL;
+    const HostPlan &hp = plan->host;
+    out->num_segments = hp.segments.size();
+    out->num_items = hp.items.size();
+    out->num_slots = hp.slot_begin.back();
+    out->algorithmic_bytes = hp.algorithmic_bytes;
+    out->num_candidates = (uint32_t)hp.num_candidates;
+    out->grid_blocks = hp.grid_blocks;
+    out->block_threads = kBlockThreads;
+    out->lds_bytes = plan->lds_bytes;
+    out->item_bytes = kItemBytes;
+    out->device = plan->device;
+    return GEAK_OK;
+}
+
+uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t capacity)
+{
+    if (!plan) return 0;
+    const auto &items = plan->host.items;
+    if (out) {
+        const uint64_t n = capacity < items.size() ? capacity : items.size();
+        if (n) std::memcpy(out, items.data(), n * sizeof(geak_item));
+    }
+    return items.size();
+}
+
+geak_status geak_check_profile_enable(geak_plan *plan, uint32_t num_pairs)
+{
+    if (!plan || plan->device < 0) return GEAK_EINVAL;
+    DeviceGuard g(plan->device);
+    if (!g.ok) return GEAK_EHIP;
+    for (auto e : plan->ev_start) (void)hipEventDestroy(e);
+    for (auto e : plan->ev_stop) (void)hipEventDestroy(e);
+    plan->ev_start.clear();
+    plan->ev_stop.clear();
+    plan->ev_next = plan->ev_used = 0;
+    try {
+        for (uint32_t i = 0; i < num_pairs; ++i) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return GEAK_EHIP;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return GEAK_EHIP; }
+            plan->ev_start.push_back(a);
+            plan->ev_stop.push_back(b);
+        }
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    return GEAK_OK;
+}
+
+uint64_t geak_check_profile_read(geak_plan *plan, float *ms_out, uint64_t capacity)
+{
+    if (!plan || !ms_out || plan->ev_start.empty()) return 0;
+    const uint32_t ring = (uint32_t)plan->ev_start.size();
+    const uint32_t used = plan->ev_used;
+    const uint32_t oldest = (plan->ev_next + ring - used) % ring;
+    uint64_t n = 0;
+    for (uint32_t i = 0; i < used && n < capacity; ++i) {
+        const uint32_t s = (oldest + i) % ring;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, plan->ev_start[s], plan->ev_stop[s]) == hipSuccess) ms_out[n++] = ms;
+    }
+    plan->ev_next = plan->ev_used = 0;
+    return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,99 @@
+// Internal definitions shared by the host planner, the API layer and the kernels.
+#pragma once
+#include <cstdint>
+#include <vector>
+#include "geak_check.h"
+
+namespace geak {
+
+constexpr int kWaveSize = 64;
+constexpr int kVecPerLane = 4;                                   // 16-byte vectors per lane, per tensor, per item
+constexpr int kItemBytes = kVecPerLane * kWaveSize * 16;         // 4096 bytes of each tensor per work item
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlockThreads = kWavesPerBlock * kWaveSize;
+constexpr int kDefaultComputeUnits = 256;                        // host-only plans
+constexpr int kDefaultBlocksPerCU = 4;
+constexpr uint32_t kNoItem = 0xFFFFFFFFu;
+
+inline int elem_size(int dtype) { return (dtype == GEAK_F16 || dtype == GEAK_BF16) ? 2 : 4; }
+
+// Partial result of one (worker, segment) run for one candidate; 16 bytes.
+struct Partial {
+    unsigned long long count;   // mismatching elements seen by the run
+    uint32_t first_item;        // least item index of the run that holds a mismatch, kNoItem if none
+    uint32_t reserved;
+};
+
+// LDS bytes one block needs: per wave and candidate a 64-bit count, a 32-bit first-item index
+// and a 32-bit revisit flag.
+inline uint32_t lds_bytes_for(int num_candidates) {
+    return (uint32_t)(kWavesPerBlock * num_candidates * (sizeof(unsigned long long) + 2 * sizeof(uint32_t)));
+}
+
+// Host side of a plan: everything that can be decided without a device.
+struct HostPlan {
+    std::vector<geak_segment> segments;
+    std::vector<geak_item> items;
+    std::vector<uint32_t> slot_begin;      // per segment, size nsegs + 1; slots of a segment are contiguous
+    uint64_t algorithmic_bytes = 0;
+    int num_candidates = 0;
+    float atol_f = 0.f, rtol_f = 0.f;
+    int equal_nan = 0;
+    uint32_t grid_blocks = 1;
+    uint32_t max_blocks = 1;               // compute units x resident blocks per unit
+};
+
+// Validates and builds the work table for a persistent grid of at most `max_blocks` blocks.
+geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nsegs, int32_t num_candidates,
+                            double atol, double rtol, int32_t equal_nan, uint32_t max_blocks);
+
+// Workspace layout: [candidate pointer table, kCandTableBytes][partials: num_slots x K].
+constexpr uint64_t kCandTableBytes = GEAK_MAX_CANDIDATES * sizeof(void *);
+
+// Init kernel: neutral result records, and the candidate base pointers copied from the kernel
+// argument block into the workspace so that the other kernels index them from memory.
+struct InitArgs {
+    geak_result *results;
+    const unsigned char **cand_table;
+    uint64_t num_results;
+    uint32_t num_candidates;
+    uint32_t reserved;
+    const unsigned char *cand[GEAK_MAX_CANDIDATES];
+};
+
+struct CompareArgs {
+    const geak_item *items;
+    const unsigned char *ref;
+    const unsigned char *const *cand_table;
+    Partial *partials;
+    geak_result *results;
+    uint32_t num_items;
+    uint32_t num_candidates;
+    float atol_f;
+    float rtol_f;
+    int equal_nan;
+    int reserved;
+};
+
+struct ReduceArgs {
+    const geak_item *items;
+    const uint32_t *slot_begin;
+    const Partial *partials;
+    geak_result *results;
+    const unsigned char *ref;
+    const unsigned char *const *cand_table;
+    uint32_t num_segments;
+    uint32_t num_candidates;
+    float atol_f;
+    float rtol_f;
+    int equal_nan;
+    int reserved;
+};
+
+// Kernel launchers (kernels.hip).  Return the hipError_t of the launch as int.
+int launch_init(const InitArgs &args, void *stream);
+int launch_compare(const CompareArgs &args, uint32_t grid_blocks, uint32_t lds_bytes, void *stream);
+int launch_reduce(const ReduceArgs &args, void *stream);
+int compare_blocks_per_cu(uint32_t lds_bytes);   // occupancy query on the current device; <= 0 on failure
+
+}  // namespace geak

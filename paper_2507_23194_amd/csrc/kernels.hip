@@ -1,0 +1,690 @@
+// HIP kernels of the output-equivalence check for gfx950 (wave64).
+//
+// The rule (GEAK section 3.1, tolerance-based comparison of output tensors against reference
+// outputs; the reference is ground truth, section 3.3):
+//     d = |a - b|, tol = atol + rtol*|b| (binary32, one rounding per step), close <=> d <= tol,
+//     NaN: close only if equal_nan and both NaN; +-Inf: close only if a == b; int32: a == b.
+//
+// compare kernel -- one wavefront per work item (4 KiB of every tensor).
+//   * The wave loads its slice of the reference once, decodes it to binary32 and keeps b and tol
+//     in registers (lane L holds the same element positions for the reference and every
+//     candidate, so nothing has to be exchanged between lanes); the slice of each of the K
+//     candidates is then streamed past it with 16-byte loads, one candidate ahead of the compute.
+//     HBM traffic is K + 1 tensors.
+//   * Reference elements for which the bare inequality is not the rule (b NaN or +-Inf, or tol
+//     overflowed to +Inf) get tol = -1 ("poisoned"): the inequality then always reports a
+//     suspect, and a per-candidate fix-up applies the NaN / Inf rule to exactly those slots.
+//   * mismatch count: v_cmp -> 64-bit lane mask -> s_bcnt1, accumulated in LDS per (wave, k).
+//   * max_abs_err / max_rel_err: the current global maxima are read from the result records and
+//     used as wave-uniform thresholds.  Per element only `d > max_abs` and `d > c*|b|` (c slightly
+//     below max_rel, so that no division is needed) are evaluated; when any lane trips, a rare
+//     path re-reads the item from memory, evaluates it exactly (true binary32 division) and raises
+//     the global maxima with 64-bit atomic max on the bit patterns of the non-negative doubles.
+//     Rounding is monotone, so the maximum of the rounded quotients is the rounded quotient of a
+//     tripping element.
+//   * Segment heads and tails (items that are not a full, 16-byte aligned 4 KiB) take a compact
+//     element-wise path that applies the full rule straight from memory.
+//   * first_mismatch: the wave only remembers the first of its items that holds a mismatch; the
+//     reduce kernel re-reads that one item and finds the exact index.
+// reduce kernel -- one wavefront per (segment, candidate): sums counts over the segment's slots,
+//   takes the least item index, rescans that item with the full rule, writes pass/count/first.
+//
+// Blocks of the compare kernel start at different candidates (k0 = block % K) so that the first,
+// expensive, visit of a (segment, candidate) pair is spread out and later visitors find the maxima
+// already raised.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include "geak_internal.hpp"
+
+namespace geak {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+
+constexpr float kInfF = __builtin_huge_valf();
+
+// Explicit address spaces.  Tables that are written before the kernel starts and never during it
+// (work items, candidate base pointers) are read through the constant address space, so that a
+// wave-uniform index turns into a scalar load instead of a vector load the wave has to wait for;
+// tensor data is read through the global address space (no flat instructions).
+#define GEAK_AS_GLOBAL   __attribute__((address_space(1)))
+#define GEAK_AS_CONSTANT __attribute__((address_space(4)))
+typedef const GEAK_AS_GLOBAL u32x4 *global_vec_ptr;
+
+// A work item read with scalar loads (four 64-bit words; layout of geak_item).
+__device__ __forceinline__ geak_item load_work_item(const geak_item *items, uint32_t j)
+{
+    static_assert(sizeof(geak_item) == 32, "geak_item is four 64-bit words");
+    const GEAK_AS_CONSTANT unsigned long long *w = (const GEAK_AS_CONSTANT unsigned long long *)(items + j);
+    const unsigned long long w2 = w[2], w3 = w[3];
+    geak_item it;
+    it.byte_offset = w[0];
+    it.elem_start = w[1];
+    it.segment = (uint32_t)w2;
+    it.slot = (uint32_t)(w2 >> 32);
+    it.numel = (uint32_t)w3;
+    it.dtype = (uint8_t)(w3 >> 32);
+    it.flags = (uint8_t)(w3 >> 40);
+    it.reserved = 0;
+    return it;
+}
+
+__device__ __forceinline__ const unsigned char *table_entry(const unsigned char *const *table, uint32_t k)
+{
+    const GEAK_AS_CONSTANT unsigned long long *t = (const GEAK_AS_CONSTANT unsigned long long *)table;
+    return reinterpret_cast<const unsigned char *>(t[k]);
+}
+
+template <int DT> struct Traits;
+template <> struct Traits<GEAK_F32>  { static constexpr int E = 4, W = 4; };
+template <> struct Traits<GEAK_F16>  { static constexpr int E = 8, W = 2; };
+template <> struct Traits<GEAK_BF16> { static constexpr int E = 8, W = 2; };
+template <> struct Traits<GEAK_I32>  { static constexpr int E = 4, W = 4; };
+
+__device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t f_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// Element e (0 .. E-1) of a 16-byte vector, decoded exactly to binary32.
+template <int DT>
+__device__ __forceinline__ float decode(const u32x4 &q, int e)
+{
+    if constexpr (DT == GEAK_F32) {
+        return bits_f(q[e]);
+    } else if constexpr (DT == GEAK_F16) {
+        const uint32_t word = q[e >> 1];
+        const uint16_t h = (e & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xFFFFu);
+        return (float)__builtin_bit_cast(_Float16, h);
+    } else {  // bf16: upper half of a binary32
+        const uint32_t word = q[e >> 1];
+        return bits_f((e & 1) ? (word & 0xFFFF0000u) : (word << 16));
+    }
+}
+
+__device__ __forceinline__ int decode_i32(const u32x4 &q, int e) { return (int)q[e]; }
+
+// ---- loads -------------------------------------------------------------------------------------
+// Full item: 4 coalesced 16-byte loads per lane; vector v of lane L covers bytes (v*64 + L)*16.
+__device__ __forceinline__ void load_full(u32x4 (&dst)[kVecPerLane], const unsigned char *base, int lane)
+{
+    global_vec_ptr p = (global_vec_ptr)base + lane;
+#pragma unroll
+    for (int v = 0; v < kVecPerLane; ++v)
+        dst[v] = __builtin_nontemporal_load(p + v * kWaveSize);
+}
+
+// One element straight from memory, decoded exactly to binary32 (floating dtypes).
+__device__ __forceinline__ float load_elem_f(const unsigned char *base, uint32_t idx, int dtype)
+{
+    if (dtype == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
+    const uint16_t h = reinterpret_cast<const uint16_t *>(base)[idx];
+    if (dtype == GEAK_F16) return (float)__builtin_bit_cast(_Float16, h);
+    return bits_f((uint32_t)h << 16);
+}
+
+// ---- wave reductions (rare paths only) ---------------------------------------------------------
+__device__ __forceinline__ float wave_max_f(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float y = __shfl_xor(x, o, kWaveSize);
+        x = (y > x) ? y : x;
+    }
+    return x;
+}
+__device__ __forceinline__ double wave_max_d(double x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const double y = __shfl_xor(x, o, kWaveSize);
+        x = (y > x) ? y : x;
+    }
+    return x;
+}
+__device__ __forceinline__ uint32_t wave_min_u(uint32_t x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t y = (uint32_t)__shfl_xor((int)x, o, kWaveSize);
+        x = (y < x) ? y : x;
+    }
+    return x;
+}
+
+// Non-negative doubles order like their bit patterns, so the maxima live in the result record
+// itself and are raised with an unsigned 64-bit atomic max.
+__device__ __forceinline__ u64 load_bits(const double *p)
+{
+    return __hip_atomic_load(reinterpret_cast<const u64 *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void raise_max(double *p, double v, u64 seen_bits)
+{
+    const u64 bits = __builtin_bit_cast(u64, v);
+    if (bits > seen_bits) atomicMax(reinterpret_cast<u64 *>(p), bits);
+}
+
+// The full rule for one floating element.
+__device__ __forceinline__ bool close_exact(float a, float b, float atol_f, float rtol_f, int equal_nan)
+{
+    const bool a_nan = a != a, b_nan = b != b;
+    if (a_nan || b_nan) return equal_nan && a_nan && b_nan;
+    if (__builtin_fabsf(a) == kInfF || __builtin_fabsf(b) == kInfF) return a == b;
+    const float d = __builtin_fabsf(a - b);
+    const float prod = rtol_f * __builtin_fabsf(b);
+    const float tol = atol_f + prod;
+    return d <= tol;
+}
+
+// Threshold multiplier for the max_rel filter: c <= r*(1 - 2^-20), so that d <= RN(c*|b|) implies
+// d/|b| < r.  r = +Inf can never be exceeded: c = NaN makes every comparison false.
+__device__ __forceinline__ float rel_filter_scale(float r)
+{
+    if (r == kInfF) return __builtin_nanf("");
+    if (r < 0x1p-100f) return 0.0f;                 // r is 0 here (a non-zero quotient is >= 2^-25)
+    return r * 0.99999809265136718750f;             // 1 - 2^-19, product rounded once
+}
+
+// Conservative per-element threshold for the max_rel filter: not flagged (d <= threshold) implies
+// d <= c*|b| exactly.  The product may be subnormal, where rounding to nearest can round up by
+// half a unit; stepping the bit pattern down by one (saturating at 0) removes that.  binary16
+// inputs keep the product far from the subnormal range, so they skip the step.
+template <bool STEP_DOWN>
+__device__ __forceinline__ float rel_threshold(float c, float babs)
+{
+    const float t = c * babs;
+    if constexpr (STEP_DOWN) return bits_f(__builtin_elementwise_sub_sat(f_bits(t), 1u));
+    else return t;
+}
+
+// ---- exact element-wise evaluation of one item for one candidate, straight from memory ----------
+// Used (a) for segment heads and tails, (b) when the hot loop finds that an item may raise one of
+// the maxima.  Returns the wave-uniform mismatch count and raises the record's maxima.
+__device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsigned char *cand, uint32_t n, int dtype,
+                                            float atol_f, float rtol_f, int equal_nan, geak_result *rec)
+{
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const u64 abs_bits = load_bits(&rec->max_abs_err), rel_bits = load_bits(&rec->max_rel_err);
+    uint32_t bad = 0;
+    if (dtype == GEAK_I32) {
+        const double seen_rel = __builtin_bit_cast(double, rel_bits);
+        // d > c*|b| is implied by d/|b| > seen_rel; the 2^-30 margin covers the product's rounding
+        const double c = (seen_rel == (double)kInfF) ? __builtin_nan("") : seen_rel * (1.0 - 0x1p-30);
+        double dm = 0.0, rm = 0.0;
+        for (uint32_t i = lane; i < n; i += kWaveSize) {
+            const long long a = reinterpret_cast<const int *>(cand)[i], x = reinterpret_cast<const int *>(ref)[i];
+            const long long diff = a - x;
+            bad += (a != x);
+            const double d = (double)(diff < 0 ? -diff : diff);
+            const double babs = (double)(x < 0 ? -x : x);
+            if (d > dm) dm = d;
+            if (d > c * babs) {                                   // implies d > 0
+                const double r = d / babs;                        // binary64, correctly rounded; d/0 = +Inf
+                if (r > rm) rm = r;
+            }
+        }
+        dm = wave_max_d(dm);
+        rm = wave_max_d(rm);
+        if (lane == 0) {
+            raise_max(&rec->max_abs_err, dm, abs_bits);
+            raise_max(&rec->max_rel_err, rm, rel_bits);
+        }
+    } else {
+        const float c = rel_filter_scale((float)__builtin_bit_cast(double, rel_bits));
+        float dm = 0.0f, rm = 0.0f;
+        for (uint32_t i = lane; i < n; i += kWaveSize) {
+            const float a = load_elem_f(cand, i, dtype), b = load_elem_f(ref, i, dtype);
+            bad += !close_exact(a, b, atol_f, rtol_f, equal_nan);
+            const float d = __builtin_fabsf(a - b);
+            const float babs = __builtin_fabsf(b);
+            if (d > dm) dm = d;                                   // false for NaN: skipped
+            if (d > rel_threshold<true>(c, babs)) {               // implies d > 0
+                const float r = d / babs;                         // correctly rounded; d/0 = +Inf; Inf/Inf = NaN
+                if (r > rm) rm = r;                               // false for NaN: skipped
+            }
+        }
+        dm = wave_max_f(dm);
+        rm = wave_max_f(rm);
+        if (lane == 0) {
+            raise_max(&rec->max_abs_err, (double)dm, abs_bits);
+            raise_max(&rec->max_rel_err, (double)rm, rel_bits);
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) bad += (uint32_t)__shfl_xor((int)bad, o, kWaveSize);
+    return bad;
+}
+
+// ---- per-(wave, candidate) running state in LDS ----------------------------------------------
+struct WaveState {
+    u64 *count;          // [K] mismatching elements of the current (worker, segment) run
+    uint32_t *first;     // [K] least item index of the run that holds a mismatch
+    uint32_t *revisit;   // [K] set when the current item must be re-evaluated exactly for candidate k
+};
+
+// Candidates whose maxima the item may raise are only marked inside the candidate loop; the exact
+// evaluation (a function call that re-reads the item) runs after the loop, when the staged
+// reference and the load buffers are dead, so the hot loop carries no call and no spills.
+__device__ __forceinline__ void mark_revisit(const WaveState &st, uint32_t k, int lane)
+{
+    if (lane == 0) st.revisit[k] = 1;
+}
+
+__device__ __forceinline__ void note_mismatches(const WaveState &st, uint32_t k, uint32_t n, uint32_t item, int lane)
+{
+    if (n && lane == 0) {
+        atomicAdd(&st.count[k], (u64)n);
+        atomicMin(&st.first[k], item);
+    }
+}
+
+// ---- full items, floating dtypes: reference slice staged in registers ---------------------------
+template <int DT>
+struct FloatItem {
+    static constexpr int E = Traits<DT>::E;
+    static constexpr int N = kVecPerLane * E;
+    static constexpr bool kStepDown = (DT != GEAK_F16);
+    u32x4 braw[kVecPerLane];        // the reference slice as loaded; decoded on use (free for binary32)
+    float tol[N];
+    uint32_t poisoned_slots;        // wave-uniform: bit i set if any lane's element i is poisoned
+
+    __device__ __forceinline__ void stage(const u32x4 (&q)[kVecPerLane], float atol_f, float rtol_f)
+    {
+        poisoned_slots = 0;
+#pragma unroll
+        for (int v = 0; v < kVecPerLane; ++v) {
+            braw[v] = q[v];
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const int i = v * E + e;
+                const float x = decode<DT>(q[v], e);
+                const float prod = rtol_f * __builtin_fabsf(x);
+                const float t = atol_f + prod;
+                const bool bad = !(t < kInfF);          // b NaN, b +-Inf, or the tolerance overflowed
+                // the poison value also records why: -1 b is NaN, -2 b is +-Inf, -3 finite b, tolerance +Inf
+                const float why = (x != x) ? -1.0f : (__builtin_fabsf(x) == kInfF ? -2.0f : -3.0f);
+                tol[i] = bad ? why : t;
+                if (__builtin_amdgcn_ballot_w64(bad)) poisoned_slots |= (1u << i);
+            }
+        }
+    }
+
+    // Hot loop body for one 16-byte vector of one candidate.  Adds the suspects (elements with
+    // !(d <= tol)) to `suspects` and ORs into `trip` the lanes that may raise one of the two maxima.
+    template <int V>
+    __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float c, uint32_t &suspects, u64 &trip) const
+    {
+        // The reference stays packed in registers and is decoded again for every candidate: one
+        // more conversion per element, half the registers.  The empty asm keeps the decode from
+        // being hoisted out of the candidate loop (which would unpack it for good).
+        u32x4 br = braw[V];
+        if constexpr (Traits<DT>::W == 2) asm volatile("" : "+v"(br));
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int i = V * E + e;
+            const float a = decode<DT>(q, e);
+            const float x = decode<DT>(br, e);
+            const float d = __builtin_fabsf(a - x);
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(d <= tol[i])));
+            trip |= __builtin_amdgcn_ballot_w64(d > max_abs);
+            trip |= __builtin_amdgcn_ballot_w64(d > rel_threshold<kStepDown>(c, __builtin_fabsf(x)));
+            // keep the OR a running chain in one scalar register pair (a balanced tree would
+            // hold every lane mask live at once)
+            asm volatile("" : "+s"(trip));
+        }
+    }
+
+    // Poisoned elements were all reported as suspects; count those that the NaN / Inf rule accepts.
+    template <int V>
+    __device__ __forceinline__ uint32_t false_suspects_vec(const u32x4 &q, int equal_nan) const
+    {
+        uint32_t n = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int i = V * E + e;
+            if (poisoned_slots & (1u << i)) {
+                const float a = decode<DT>(q, e);
+                const float x = decode<DT>(braw[V], e);
+                float why = tol[i];
+                asm volatile("" : "+v"(why));   // evaluate here, per candidate: hoisted lane masks would not fit the scalar file
+                const bool ok = (why == -1.0f) ? (equal_nan && (a != a))
+                              : (why == -2.0f) ? (a == x)
+                              : (why == -3.0f) ? (__builtin_fabsf(a) < kInfF)   // any finite a is within an infinite tolerance
+                              : false;
+                n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok));
+            }
+        }
+        return n;
+    }
+};
+
+struct ItemArgs {
+    const unsigned char *ref;            // buffer base
+    const unsigned char *const *cand;    // device table of K candidate bases
+    geak_result *recs;                   // the segment's K records
+    u64 byte_offset;
+    uint32_t numel;
+    uint32_t item_index;
+    uint32_t K;
+    uint32_t k0;
+    float atol_f;
+    float rtol_f;
+    int equal_nan;
+    int dtype;
+};
+
+__device__ __noinline__ void revisit_marked(const unsigned char *ref_item, const unsigned char *const *cand, u64 byte_offset,
+                                            geak_result *recs, uint32_t *revisit, uint32_t K, uint32_t numel, int dtype,
+                                            float atol_f, float rtol_f, int equal_nan)
+{
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    for (uint32_t base = 0; base < K; base += kWaveSize) {
+        const uint32_t k_lane = base + lane;
+        bool marked = false;
+        if (k_lane < K) {
+            marked = revisit[k_lane] != 0;
+            revisit[k_lane] = 0;
+        }
+        u64 todo = __builtin_amdgcn_ballot_w64(marked);
+        while (todo) {
+            const uint32_t k = base + (uint32_t)__builtin_ctzll(todo);
+            todo &= todo - 1;
+            (void)exact_item(ref_item, table_entry(cand, k) + byte_offset, numel, dtype, atol_f, rtol_f, equal_nan, &recs[k]);
+        }
+    }
+}
+
+// Arguments of a device function arrive in vector registers; everything here is the same for all
+// lanes, so it is moved back to scalar registers once.
+__device__ __forceinline__ uint32_t uniform32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+template <typename T>
+__device__ __forceinline__ T *uniform_ptr(T *p)
+{
+    const u64 v = reinterpret_cast<u64>(p);
+    const u64 lo = uniform32((uint32_t)v), hi = uniform32((uint32_t)(v >> 32));
+    return reinterpret_cast<T *>(lo | (hi << 32));
+}
+__device__ __forceinline__ ItemArgs uniform_args(const ItemArgs &in)
+{
+    ItemArgs p;
+    p.ref = uniform_ptr(in.ref);
+    p.cand = uniform_ptr(in.cand);
+    p.recs = uniform_ptr(in.recs);
+    const u64 off = in.byte_offset;
+    p.byte_offset = (u64)uniform32((uint32_t)off) | ((u64)uniform32((uint32_t)(off >> 32)) << 32);
+    p.numel = uniform32(in.numel);
+    p.item_index = uniform32(in.item_index);
+    p.K = uniform32(in.K);
+    p.k0 = uniform32(in.k0);
+    p.atol_f = bits_f(uniform32(f_bits(in.atol_f)));
+    p.rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
+    p.equal_nan = (int)uniform32((uint32_t)in.equal_nan);
+    p.dtype = (int)uniform32((uint32_t)in.dtype);
+    return p;
+}
+__device__ __forceinline__ WaveState uniform_state(const WaveState &in)
+{
+    WaveState st;
+    st.count = uniform_ptr(in.count);
+    st.first = uniform_ptr(in.first);
+    st.revisit = uniform_ptr(in.revisit);
+    return st;
+}
+
+// One vector step of the candidate loop: compare vector V of the current candidate, then reuse its
+// registers for the same vector of the next candidate.  Four loads per lane stay in flight and
+// each has a whole candidate's worth of compute to land.
+template <int DT, int V>
+__device__ __forceinline__ void float_step(const FloatItem<DT> &ref, u32x4 &slot, global_vec_ptr next, bool has_next,
+                                           float max_abs, float c, int equal_nan, uint32_t &bad, u64 &trip)
+{
+    constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
+    ref.template compare_vec<V>(slot, max_abs, c, bad, trip);
+    if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_vec<V>(slot, equal_nan);
+    if (has_next) slot = __builtin_nontemporal_load(next + V * kWaveSize);
+}
+
+// Each dtype's item routine is a real function, so that its register allocation stands alone
+// instead of being merged with the other dtypes' inside the kernel.
+template <int DT>
+__device__ __noinline__ void process_full_float(const ItemArgs in, const WaveState st_in)
+{
+    const ItemArgs p = uniform_args(in);
+    const WaveState st = uniform_state(st_in);
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t K = p.K;
+    FloatItem<DT> ref;
+    {
+        u32x4 q[kVecPerLane];
+        load_full(q, p.ref + p.byte_offset, lane);
+        ref.stage(q, p.atol_f, p.rtol_f);
+    }
+    u32x4 cur[kVecPerLane];
+    uint32_t k = p.k0;
+    load_full(cur, table_entry(p.cand, k) + p.byte_offset, lane);
+    u64 abs_bits = load_bits(&p.recs[k].max_abs_err), rel_bits = load_bits(&p.recs[k].max_rel_err);
+    bool any_revisit = false;
+
+    for (uint32_t step = 0; step < K; ++step) {
+        const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
+        const bool has_next = step + 1 < K;
+        global_vec_ptr next = (global_vec_ptr)(table_entry(p.cand, kn) + p.byte_offset) + lane;
+
+        const float max_abs = (float)__builtin_bit_cast(double, abs_bits);   // exact: published from binary32
+        const float c = rel_filter_scale((float)__builtin_bit_cast(double, rel_bits));
+        if (has_next) {
+            abs_bits = load_bits(&p.recs[kn].max_abs_err);
+            rel_bits = load_bits(&p.recs[kn].max_rel_err);
+        }
+        uint32_t bad = 0;
+        u64 trip = 0;
+        float_step<DT, 0>(ref, cur[0], next, has_next, max_abs, c, p.equal_nan, bad, trip);
+        float_step<DT, 1>(ref, cur[1], next, has_next, max_abs, c, p.equal_nan, bad, trip);
+        float_step<DT, 2>(ref, cur[2], next, has_next, max_abs, c, p.equal_nan, bad, trip);
+        float_step<DT, 3>(ref, cur[3], next, has_next, max_abs, c, p.equal_nan, bad, trip);
+        note_mismatches(st, k, bad, p.item_index, lane);
+        if (trip) { mark_revisit(st, k, lane); any_revisit = true; }
+        k = kn;
+    }
+    if (any_revisit)
+        revisit_marked(p.ref + p.byte_offset, p.cand, p.byte_offset, p.recs, st.revisit, K, p.numel, p.dtype, p.atol_f, p.rtol_f,
+                       p.equal_nan);
+}
+
+// ---- full items, int32 -----------------------------------------------------------------------------
+__device__ __noinline__ void process_full_int(const ItemArgs in, const WaveState st_in)
+{
+    constexpr int E = 4;
+    const ItemArgs p = uniform_args(in);
+    const WaveState st = uniform_state(st_in);
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t K = p.K;
+    u32x4 b[kVecPerLane];
+    load_full(b, p.ref + p.byte_offset, lane);
+    u32x4 cur[kVecPerLane];
+    uint32_t k = p.k0;
+    load_full(cur, table_entry(p.cand, k) + p.byte_offset, lane);
+    bool any_revisit = false;
+    for (uint32_t step = 0; step < K; ++step) {
+        const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
+        const bool has_next = step + 1 < K;
+        global_vec_ptr next = (global_vec_ptr)(table_entry(p.cand, kn) + p.byte_offset) + lane;
+        uint32_t bad = 0;
+#pragma unroll
+        for (int v = 0; v < kVecPerLane; ++v) {
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                bad += __builtin_popcountll(__builtin_amdgcn_ballot_w64(cur[v][e] != b[v][e]));
+            if (has_next) cur[v] = __builtin_nontemporal_load(next + v * kWaveSize);
+        }
+        note_mismatches(st, k, bad, p.item_index, lane);
+        if (bad) { mark_revisit(st, k, lane); any_revisit = true; }   // equal elements contribute nothing to either maximum
+        k = kn;
+    }
+    if (any_revisit)
+        revisit_marked(p.ref + p.byte_offset, p.cand, p.byte_offset, p.recs, st.revisit, K, p.numel, p.dtype, p.atol_f, p.rtol_f,
+                       p.equal_nan);
+}
+
+// ---- partial items (segment heads and tails) -------------------------------------------------------
+__device__ __forceinline__ void process_partial(const ItemArgs &p, const WaveState &st, int lane)
+{
+    for (uint32_t k = 0; k < p.K; ++k) {
+        const uint32_t bad = exact_item(p.ref + p.byte_offset, table_entry(p.cand, k) + p.byte_offset, p.numel, p.dtype,
+                                        p.atol_f, p.rtol_f, p.equal_nan, &p.recs[k]);
+        note_mismatches(st, k, bad, p.item_index, lane);
+    }
+}
+
+__global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const CompareArgs p)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t K = p.num_candidates;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    WaveState st;
+    st.count = reinterpret_cast<u64 *>(lds) + (size_t)wave * K;
+    st.first = reinterpret_cast<uint32_t *>(lds + sizeof(u64) * kWavesPerBlock * K) + (size_t)wave * K;
+    st.revisit = reinterpret_cast<uint32_t *>(lds + (sizeof(u64) + sizeof(uint32_t)) * kWavesPerBlock * K) + (size_t)wave * K;
+    for (uint32_t k = lane; k < K; k += kWaveSize) st.revisit[k] = 0;
+
+    const uint32_t workers = gridDim.x * kWavesPerBlock;
+    ItemArgs a;
+    a.ref = p.ref;
+    a.cand = p.cand_table;
+    a.K = K;
+    a.k0 = blockIdx.x % K;
+    a.atol_f = p.atol_f;
+    a.rtol_f = p.rtol_f;
+    a.equal_nan = p.equal_nan;
+    for (uint32_t j = blockIdx.x * kWavesPerBlock + wave; j < p.num_items; j += workers) {
+        const geak_item it = load_work_item(p.items, j);
+        if (it.flags & GEAK_ITEM_FIRST) {
+            for (uint32_t k = lane; k < K; k += kWaveSize) { st.count[k] = 0; st.first[k] = kNoItem; }
+        }
+        a.recs = p.results + (u64)it.segment * K;
+        a.byte_offset = it.byte_offset;
+        a.numel = it.numel;
+        a.item_index = j;
+        a.dtype = it.dtype;
+        if (it.flags & GEAK_ITEM_FULL) {
+            switch (it.dtype) {
+            case GEAK_F32:  process_full_float<GEAK_F32>(a, st); break;
+            case GEAK_F16:  process_full_float<GEAK_F16>(a, st); break;
+            case GEAK_BF16: process_full_float<GEAK_BF16>(a, st); break;
+            default:        process_full_int(a, st); break;
+            }
+        } else {
+            process_partial(a, st, lane);
+        }
+        if (it.flags & GEAK_ITEM_LAST) {
+            Partial *out = p.partials + (u64)it.slot * K;
+            for (uint32_t k = lane; k < K; k += kWaveSize) {
+                Partial r;
+                r.count = st.count[k];
+                r.first_item = st.first[k];
+                r.reserved = 0;
+                out[k] = r;
+            }
+        }
+    }
+}
+
+// ---- init: neutral records (also final for empty segments) and the candidate pointer table --------
+__global__ void init_kernel(const InitArgs p)
+{
+    const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < p.num_results) {
+        geak_result r;
+        r.pass = 1;
+        r.reserved = 0;
+        r.mismatch_count = 0;
+        r.first_mismatch = -1;
+        r.max_abs_err = 0.0;
+        r.max_rel_err = 0.0;
+        p.results[i] = r;
+    }
+    if (p.cand_table && i < p.num_candidates) p.cand_table[i] = p.cand[i];
+}
+
+// ---- reduce: one wavefront per (segment, candidate) ----------------------------------------------
+__device__ __forceinline__ bool element_close(const unsigned char *ref, const unsigned char *cand, uint32_t idx,
+                                              int dtype, float atol_f, float rtol_f, int equal_nan)
+{
+    if (dtype == GEAK_I32)
+        return reinterpret_cast<const int *>(ref)[idx] == reinterpret_cast<const int *>(cand)[idx];
+    return close_exact(load_elem_f(cand, idx, dtype), load_elem_f(ref, idx, dtype), atol_f, rtol_f, equal_nan);
+}
+
+__global__ __launch_bounds__(kWaveSize) void reduce_kernel(const ReduceArgs p)
+{
+    const uint32_t K = p.num_candidates;
+    const uint32_t seg = blockIdx.x / K, k = blockIdx.x % K;
+    const int lane = threadIdx.x;
+    const uint32_t sb = p.slot_begin[seg], se = p.slot_begin[seg + 1];
+    if (sb == se) return;                       // empty segment: the neutral record stands
+
+    u64 count = 0;
+    uint32_t first_item = kNoItem;
+    for (uint32_t s = sb + lane; s < se; s += kWaveSize) {
+        const Partial r = p.partials[(u64)s * K + k];
+        count += r.count;
+        first_item = r.first_item < first_item ? r.first_item : first_item;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) count += (u64)__shfl_xor((long long)count, o, kWaveSize);
+    first_item = wave_min_u(first_item);
+
+    long long first = -1;
+    if (first_item != kNoItem) {
+        const geak_item it = p.items[first_item];
+        const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
+        uint32_t best = kNoItem;
+        for (uint32_t i = lane; i < it.numel; i += kWaveSize) {
+            if (!element_close(rb, cb, i, it.dtype, p.atol_f, p.rtol_f, p.equal_nan)) { best = i; break; }
+        }
+        best = wave_min_u(best);
+        first = (long long)it.elem_start + (long long)best;
+    }
+    if (lane == 0) {
+        geak_result *rec = p.results + (u64)seg * K + k;
+        rec->pass = (count == 0);
+        rec->mismatch_count = count;
+        rec->first_mismatch = first;
+    }
+}
+
+}  // namespace
+
+int launch_init(const InitArgs &args, void *stream)
+{
+    const uint64_t n = args.num_results > args.num_candidates ? args.num_results : args.num_candidates;
+    if (!n) return (int)hipSuccess;
+    const uint32_t threads = 256;
+    const uint32_t blocks = (uint32_t)((n + threads - 1) / threads);
+    hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, (hipStream_t)stream, args);
+    return (int)hipGetLastError();
+}
+
+int launch_compare(const CompareArgs &args, uint32_t grid_blocks, uint32_t lds_bytes, void *stream)
+{
+    if (!args.num_items) return (int)hipSuccess;
+    hipLaunchKernelGGL(compare_kernel, dim3(grid_blocks), dim3(kBlockThreads), lds_bytes, (hipStream_t)stream, args);
+    return (int)hipGetLastError();
+}
+
+int launch_reduce(const ReduceArgs &args, void *stream)
+{
+    const uint64_t pairs = (uint64_t)args.num_segments * args.num_candidates;
+    if (!pairs) return (int)hipSuccess;
+    hipLaunchKernelGGL(reduce_kernel, dim3((uint32_t)pairs), dim3(kWaveSize), 0, (hipStream_t)stream, args);
+    return (int)hipGetLastError();
+}
+
+int compare_blocks_per_cu(uint32_t lds_bytes)
+{
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, compare_kernel, kBlockThreads, lds_bytes) != hipSuccess) return -1;
+    return n;
+}
+
+}  // namespace geak

@@ -1,0 +1,128 @@
+// Host planner: argument validation and the work table of the compare kernel.  No HIP calls here,
+// so all of it runs (and is tested) without a device.
+//
+// The evaluator hands over many test outputs per kernel (GEAK section 3.3: a kernel must satisfy
+// all unit tests); they arrive packed in one buffer with a segment table.  Each segment is cut into
+// work items of kItemBytes per tensor; one wavefront takes one item, keeps the reference slice in
+// registers and streams the same slice of every candidate past it.
+#include <algorithm>
+#include <cmath>
+#include <new>
+#include "geak_internal.hpp"
+
+namespace geak {
+
+static bool mul_overflows(uint64_t a, uint64_t b) { return b != 0 && a > UINT64_MAX / b; }
+
+geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nsegs, int32_t num_candidates,
+                            double atol, double rtol, int32_t equal_nan, uint32_t max_blocks)
+{
+    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    if (num_candidates < 1 || num_candidates > GEAK_MAX_CANDIDATES) return GEAK_EINVAL;
+    if (!(atol >= 0.0) || !(rtol >= 0.0) || std::isinf(atol) || std::isinf(rtol)) return GEAK_EINVAL;
+    if (equal_nan != 0 && equal_nan != 1) return GEAK_EINVAL;
+    if (max_blocks == 0) return GEAK_EINVAL;
+    const float atol_f = (float)atol, rtol_f = (float)rtol;
+    if (std::isinf(atol_f) || std::isinf(rtol_f)) return GEAK_EINVAL;   // finite in binary64 but not in binary32
+
+    // per-segment checks
+    uint64_t total_bytes = 0;
+    for (uint64_t s = 0; s < nsegs; ++s) {
+        const geak_segment &g = segs[s];
+        if (g.dtype < GEAK_F32 || g.dtype > GEAK_I32) return GEAK_EDTYPE;
+        if (g.reserved != 0) return GEAK_EINVAL;
+        const uint64_t w = (uint64_t)elem_size(g.dtype);
+        if (g.byte_offset % w != 0) return GEAK_EALIGN;
+        if (g.numel > GEAK_MAX_SEGMENT_NUMEL) return GEAK_EBOUNDS;
+        if (mul_overflows(g.numel, w)) return GEAK_EBOUNDS;
+        const uint64_t bytes = g.numel * w;
+        if (g.byte_offset > UINT64_MAX - bytes) return GEAK_EBOUNDS;
+        if (total_bytes > UINT64_MAX - bytes) return GEAK_EBOUNDS;
+        total_bytes += bytes;
+    }
+    if (mul_overflows(total_bytes, (uint64_t)num_candidates + 1)) return GEAK_EBOUNDS;
+
+    try {
+        // overlap check on the non-empty segments, sorted by start
+        std::vector<std::pair<uint64_t, uint64_t>> spans;
+        spans.reserve(nsegs);
+        for (uint64_t s = 0; s < nsegs; ++s)
+            if (segs[s].numel)
+                spans.emplace_back(segs[s].byte_offset, segs[s].byte_offset + segs[s].numel * elem_size(segs[s].dtype));
+        std::sort(spans.begin(), spans.end());
+        for (size_t i = 1; i < spans.size(); ++i)
+            if (spans[i].first < spans[i - 1].second) return GEAK_EBOUNDS;
+
+        // count items first: head (to the next 16-byte boundary), full tiles, tail
+        uint64_t n_items = 0;
+        for (uint64_t s = 0; s < nsegs; ++s) {
+            const geak_segment &g = segs[s];
+            const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
+            uint64_t n = g.numel;
+            if (!n) continue;
+            const uint64_t head = std::min<uint64_t>(n, ((16 - g.byte_offset % 16) % 16) / w);
+            if (head) { ++n_items; n -= head; }
+            n_items += n / per + (n % per ? 1 : 0);
+        }
+        if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
+
+        hp.segments.assign(segs, segs + nsegs);
+        hp.items.clear();
+        hp.items.reserve(n_items);
+        hp.slot_begin.assign(nsegs + 1, 0);
+        hp.num_candidates = num_candidates;
+        hp.atol_f = atol_f;
+        hp.rtol_f = rtol_f;
+        hp.equal_nan = equal_nan;
+        hp.algorithmic_bytes = total_bytes * ((uint64_t)num_candidates + 1);
+        hp.max_blocks = max_blocks;
+
+        const uint64_t blocks_wanted = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+        hp.grid_blocks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
+        const uint64_t workers = (uint64_t)hp.grid_blocks * kWavesPerBlock;   // item j belongs to worker j % workers
+
+        uint64_t slot_cursor = 0;
+        for (uint64_t s = 0; s < nsegs; ++s) {
+            hp.slot_begin[s] = (uint32_t)slot_cursor;
+            const geak_segment &g = segs[s];
+            const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
+            if (!g.numel) continue;
+            const uint64_t first_item = hp.items.size();
+            uint64_t done = 0;
+            auto push = [&](uint64_t n, bool full) {
+                geak_item it{};
+                it.byte_offset = g.byte_offset + done * w;
+                it.elem_start = done;
+                it.segment = (uint32_t)s;
+                it.numel = (uint32_t)n;
+                it.dtype = (uint8_t)g.dtype;
+                it.flags = full ? GEAK_ITEM_FULL : 0;
+                hp.items.push_back(it);
+                done += n;
+            };
+            const uint64_t head = std::min<uint64_t>(g.numel, ((16 - g.byte_offset % 16) % 16) / w);
+            if (head) push(head, false);
+            while (g.numel - done >= per) push(per, true);
+            if (g.numel - done) push(g.numel - done, false);
+
+            // A worker meets the items of one segment consecutively (they are congruent modulo
+            // `workers`), so each (worker, segment) pair is one run with one slot.
+            const uint64_t last_item = hp.items.size();
+            const uint64_t n_seg_items = last_item - first_item;
+            for (uint64_t j = first_item; j < last_item; ++j) {
+                geak_item &it = hp.items[j];
+                it.slot = (uint32_t)(slot_cursor + (j - first_item) % workers);
+                if (j < first_item + workers) it.flags |= GEAK_ITEM_FIRST;
+                if (j + workers >= last_item) it.flags |= GEAK_ITEM_LAST;
+            }
+            slot_cursor += std::min<uint64_t>(workers, n_seg_items);
+            if (slot_cursor >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
+        }
+        hp.slot_begin[nsegs] = (uint32_t)slot_cursor;
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    return GEAK_OK;
+}
+
+}  // namespace geak

@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same bytes.
+All five result fields must agree bit for bit (doubles compared by bit pattern): every field is an
+order-independent reduction (sum, min, NaN-free max), so no tolerance applies."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import load_pins, record_tuple, expect_tuple, workload_oracle, host_threads
+from paper_2507_23194_amd import binding as B
+from paper_2507_23194_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TORCH_STORAGE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32}
+
+
+def _to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
+    """numpy storage (float32 / uint16 bit patterns / int32) -> device tensor with 16-byte aligned base."""
+    if dtype in ("f16", "bf16"):
+        t = torch.from_numpy(arr.view(np.int16).copy()).view(TORCH_STORAGE[dtype])
+    else:
+        t = torch.from_numpy(arr.copy())
+    out = torch.empty(max(1, t.numel()), dtype=t.dtype, device="cuda")
+    out[:t.numel()].copy_(t)
+    return out[:t.numel()] if t.numel() else out[:0]
+
+
+def _assert_same(gpu, cpu, what):
+    assert gpu.shape == cpu.shape, what
+    bad = [(idx, record_tuple(gpu[idx]), record_tuple(cpu[idx]))
+           for idx in np.ndindex(gpu.shape) if record_tuple(gpu[idx]) != record_tuple(cpu[idx])]
+    assert not bad, f"{what}: {len(bad)} of {gpu.size} records differ; first (index, gpu, oracle): {bad[0]}"
+
+
+def _dense_gpu(ref_np, cand_nps, dtype, atol, rtol, equal_nan):
+    ref = _to_device(ref_np, dtype)
+    cands = [_to_device(c, dtype) for c in cand_nps]
+    ck = B.Checker(dense=(dtype, (ref_np.size,)), num_candidates=len(cands), atol=atol, rtol=rtol,
+                   equal_nan=equal_nan, device=0)
+    try:
+        ck.run(ref, cands)
+        return ck.read().copy()
+    finally:
+        ck.close()
+
+
+PINS = load_pins()
+
+
+@pytest.mark.parametrize("case", PINS, ids=[c["name"] for c in PINS])
+def test_golden_pins_on_gpu(case):
+    print("pin", case["name"], flush=True)
+    rec = _dense_gpu(case["ref"], [case["cand"]], case["dtype"], case["atol"], case["rtol"], case["equal_nan"])
+    assert rec.shape == (1, 1)
+    assert record_tuple(rec[0, 0]) == expect_tuple(case["expect"]), case["name"]
+
+
+def _special_case(rng, dtype, n, special=0.02):
+    """Random tensors rich in NaN, +-Inf, signed zeros, subnormals, huge values and near-boundary pairs."""
+    if dtype == "i32":
+        b = rng.integers(-2 ** 31, 2 ** 31, n).astype(np.int32)
+        b[rng.random(n) < 0.3] = 0
+        a = b.copy()
+        idx = rng.random(n) < 0.01
+        a[idx] = rng.integers(-2 ** 31, 2 ** 31, int(idx.sum())).astype(np.int32)
+        return b, a
+    b32 = (rng.normal(size=n) * 10.0 ** rng.integers(-3, 3, n)).astype(np.float32)
+    a32 = (b32 * (1 + 1e-3 * rng.normal(size=n)) + 1e-4 * rng.normal(size=n) * (rng.random(n) < 0.5)).astype(np.float32)
+    pool = np.array([np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-45, -1e-45, 3e38, -3e38, 1e-40, 65504.0, 6e-8], np.float32)
+    for arr in (a32, b32):
+        sp = rng.random(n) < special
+        arr[sp] = rng.choice(pool, int(sp.sum()))
+    same = rng.random(n) < 0.3
+    a32[same] = b32[same]
+    if dtype == "f32":
+        return b32, a32
+    if dtype == "f16":
+        with np.errstate(over="ignore"):
+            return b32.astype(np.float16).view(np.uint16), a32.astype(np.float16).view(np.uint16)
+    tb = torch.from_numpy(b32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    ta = torch.from_numpy(a32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    return tb, ta
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32"])
+@pytest.mark.parametrize("n", [1, 63, 2048, 4097, 70001, 1 << 20])
+def test_special_values_dense(oracle_mod, dtype, n):
+    print("special", dtype, n, flush=True)
+    rng = np.random.default_rng(1000 + n)
+    b, a0 = _special_case(rng, dtype, n)
+    _, a1 = _special_case(rng, dtype, n, special=0.0)
+    cands = [a0, b.copy(), a1]
+    for equal_nan in (False, True):
+        for (atol, rtol) in ((1e-3, 1e-3), (0.0, 0.0), (1e30, 3.0)):
+            gpu = _dense_gpu(b, cands, dtype, atol, rtol, equal_nan)
+            cpu = oracle_mod.check_dense(b, cands, dtype, atol, rtol, equal_nan, threads=3).reshape(1, -1)
+            _assert_same(gpu, cpu, f"{dtype} n={n} atol={atol} rtol={rtol} equal_nan={equal_nan}")
+
+
+def test_increasing_errors_keep_raising_the_maxima(oracle_mod):
+    """Errors that grow along the tensor make every item raise both maxima (the slow path every time)."""
+    n = 300000
+    b = np.linspace(1.0, 2.0, n, dtype=np.float32)
+    a = (b + np.linspace(0, 1e-2, n, dtype=np.float32)).astype(np.float32)
+    gpu = _dense_gpu(b, [a, a[::-1].copy()], "f32", 1e-5, 1e-5, False)
+    cpu = oracle_mod.check_dense(b, [a, a[::-1].copy()], "f32", 1e-5, 1e-5, False).reshape(1, -1)
+    _assert_same(gpu, cpu, "increasing errors")
+
+
+@pytest.mark.parametrize("K", [1, 2, 5, 64, 65, 256])
+def test_candidate_counts(oracle_mod, K):
+    print("K", K, flush=True)
+    rng = np.random.default_rng(K)
+    n = 9000
+    b, _ = _special_case(rng, "f16", n)
+    cands = [_special_case(rng, "f16", n)[1] if k % 3 else b.copy() for k in range(K)]
+    gpu = _dense_gpu(b, cands, "f16", 1e-2, 1e-2, True)
+    cpu = oracle_mod.check_dense(b, cands, "f16", 1e-2, 1e-2, True, threads=4).reshape(1, -1)
+    _assert_same(gpu, cpu, f"K={K}")
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_small_configs(oracle_mod, cid):
+    print("small config", cid, flush=True)
+    w = synth.small(cid, device="cuda")
+    gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, w.name)
+    for (s, k), e in w.expect.items():
+        assert int(gpu[s, k]["mismatch_count"]) == e["count"] and int(gpu[s, k]["first_mismatch"]) == e["first"]
+
+
+@pytest.mark.parametrize("align", [2, 4, 16])
+def test_ragged_unaligned_starts(oracle_mod, align):
+    print("ragged align", align, flush=True)
+    w = synth.config4(num_segments=160, log2_max=14.0, num_candidates=3, device="cuda", align=align, seed=align)
+    gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, f"ragged align={align}")
+
+
+def test_empty_and_tiny_segments(oracle_mod):
+    segs = [(0, 0, "f32"), (16, 1, "bf16"), (32, 0, "i32"), (48, 3, "i32"), (64, 2049, "f16"), (4176, 0, "f16")]
+    total = 4176 + 16
+    rng = np.random.default_rng(9)
+    ref = torch.from_numpy(rng.integers(0, 256, total, dtype=np.uint8))
+    # keep the fp16 segment finite and the bf16 element ordinary
+    ref[64:64 + 4098] = torch.from_numpy(rng.normal(size=2049).astype(np.float16).view(np.uint8))
+    ref[16:18] = torch.tensor([0x80, 0x3F], dtype=torch.uint8)
+    c0 = ref.clone()
+    c1 = ref.clone()
+    c1[48 + 8] ^= 1                       # third int of segment 3
+    c1[64 + 2 * 2048 + 1] ^= 0x40         # last fp16 element of segment 4
+    w = synth.Workload("tiny", 1e-3, 1e-3, False, ref.cuda(), [c0.cuda(), c1.cuda()], None, None, segs, {})
+    gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, "tiny segments")
+    assert record_tuple(gpu[0, 1]) == (1, 0, -1, 0, 0) and record_tuple(gpu[5, 0]) == (1, 0, -1, 0, 0)
+    assert int(gpu[3, 1]["first_mismatch"]) == 2 and int(gpu[4, 1]["first_mismatch"]) == 2048
+
+
+def test_rerun_and_grid_independence(oracle_mod):
+    """Same plan run twice, and the same data under a different segment cut, give identical records."""
+    w = synth.small(2, device="cuda")
+    ck = B.Checker(dense=(w.dtype, (w.ref.numel(),)), num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol,
+                   equal_nan=w.equal_nan, device=0)
+    ck.run(w.ref, w.cands)
+    r1 = ck.read().copy()
+    ck.run(w.ref, w.cands)
+    r2 = ck.read().copy()
+    ck.close()
+    _assert_same(r1, r2, "rerun")
+    # cut the same tensor into 3 segments; combine and compare counts / maxima
+    n = w.ref.numel()
+    cuts = [0, 1000, n // 2 + 3, n]
+    segs = [(2 * cuts[i], cuts[i + 1] - cuts[i], "f16") for i in range(3)]
+    ref8 = w.ref.view(torch.uint8)
+    c8 = [c.view(torch.uint8) for c in w.cands]
+    w2 = synth.Workload("cut", w.atol, w.rtol, w.equal_nan, ref8, c8, None, None, segs, {})
+    parts = B.check_workload(w2)
+    for k in range(len(w.cands)):
+        assert int(r1[0, k]["mismatch_count"]) == sum(int(parts[s, k]["mismatch_count"]) for s in range(3))
+        assert float(r1[0, k]["max_abs_err"]) == max(float(parts[s, k]["max_abs_err"]) for s in range(3))
+        assert float(r1[0, k]["max_rel_err"]) == max(float(parts[s, k]["max_rel_err"]) for s in range(3))
+
+
+def test_run_argument_errors():
+    ck = B.Checker(dense=("f32", (1024,)), num_candidates=2, atol=0, rtol=0, equal_nan=False, device=0)
+    x = torch.zeros(1024 + 4, device="cuda")
+    ok = x[:1024].data_ptr()
+    assert ok % 16 == 0
+    ws, res = ck.workspace.data_ptr(), ck.results.data_ptr()
+    assert B.geak_check_run(ck.plan, 0, [ok, ok], ws, res, 0) == B.GEAK_EINVAL
+    assert B.geak_check_run(ck.plan, ok, [ok, 0], ws, res, 0) == B.GEAK_EINVAL
+    assert B.geak_check_run(ck.plan, ok + 4, [ok, ok], ws, res, 0) == B.GEAK_EALIGN
+    assert B.geak_check_run(ck.plan, ok, [ok, ok + 8], ws, res, 0) == B.GEAK_EALIGN
+    assert B.geak_check_run(ck.plan, ok, [ok, ok], 0, res, 0) == B.GEAK_EWORKSPACE
+    assert B.geak_check_run(ck.plan, ok, [ok, ok], ws, 0, 0) == B.GEAK_EINVAL
+    assert B.geak_check_run(ck.plan, ok, [ok, ok], ws, res, 0) == B.GEAK_OK
+    assert [record_tuple(r) for r in ck.read()[0]] == [(1, 0, -1, 0, 0)] * 2
+    ck.close()
+    st, plan = B.geak_check_plan([(0, 4, "f32")], 1, 0, 0, 0, 99)       # no such device
+    assert st == B.GEAK_EHIP and plan is None
+
+
+def test_non_default_stream(oracle_mod):
+    w = synth.small(1, device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, "side stream")
+
+
+# ---- full-size configurations, in the launch configuration the benchmark times -------------------
+def _full(oracle_mod, cid, oracle_candidates=None):
+    print("full config", cid, flush=True)
+    w = synth.CONFIGS[cid](device="cuda")
+    print("  generated", w.name, w.algorithmic_bytes() / 1e9, "GB", flush=True)
+    gpu = B.check_workload(w)
+    print("  gpu done", flush=True)
+    for (s, k), e in w.expect.items():                       # closed-form facts, every candidate
+        assert int(gpu[s, k]["mismatch_count"]) == e["count"], (cid, s, k)
+        assert int(gpu[s, k]["first_mismatch"]) == e["first"], (cid, s, k)
+        assert int(gpu[s, k]["pass"]) == int(e["count"] == 0)
+    ks = list(range(len(w.cands))) if oracle_candidates is None else oracle_candidates
+    cpu = workload_oracle(oracle_mod, w, cand_subset=ks)
+    print("  oracle done on candidates", ks, "threads", host_threads(), flush=True)
+    _assert_same(gpu[:, ks], cpu, f"{w.name} candidates {ks}")
+
+
+def test_full_config1(oracle_mod):
+    _full(oracle_mod, 1)
+
+
+def test_full_config2(oracle_mod):
+    # every 5th candidate element by element (both halves of the recipe), all 64 by planted facts
+    _full(oracle_mod, 2, oracle_candidates=list(range(0, 64, 5)))
+
+
+def test_full_config3(oracle_mod):
+    _full(oracle_mod, 3, oracle_candidates=[0, 5, 8, 15])
+
+
+def test_full_config4(oracle_mod):
+    _full(oracle_mod, 4)
+
+
+def test_full_config5(oracle_mod):
+    _full(oracle_mod, 5, oracle_candidates=[0, 17, 31])

@@ -1,0 +1,198 @@
+"""Host-side checks of the C-ABI boundary (no GPU): the library loads, exports every symbol the
+header declares, validates its arguments, and cuts segments into a work table that covers every
+element exactly once."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2507_23194_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        B.build_library()
+    return B.library()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "geak_check.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(geak_[a-z_]+)\s*\(", text))
+    assert declared == set(B.EXPORTED)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_sizes_match_header():
+    assert B.SEGMENT_DTYPE.itemsize == 24
+    assert B.RESULT_DTYPE.itemsize == 40
+    assert B.ITEM_DTYPE.itemsize == 32
+
+
+def _plan(segs, K=2, atol=1e-3, rtol=1e-3, eq=0, device=-1):
+    return B.geak_check_plan(segs, K, atol, rtol, eq, device)
+
+
+def test_status_strings(lib):
+    seen = {B.geak_status_string(s) for s in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+
+
+@pytest.mark.parametrize("kwargs,segs,status", [
+    (dict(K=0), [(0, 4, "f32")], B.GEAK_EINVAL),
+    (dict(K=257), [(0, 4, "f32")], B.GEAK_EINVAL),
+    (dict(atol=-1.0), [(0, 4, "f32")], B.GEAK_EINVAL),
+    (dict(rtol=float("nan")), [(0, 4, "f32")], B.GEAK_EINVAL),
+    (dict(atol=float("inf")), [(0, 4, "f32")], B.GEAK_EINVAL),
+    (dict(rtol=1e300), [(0, 4, "f32")], B.GEAK_EINVAL),          # infinite once converted to binary32
+    (dict(eq=2), [(0, 4, "f32")], B.GEAK_EINVAL),
+    (dict(), [], B.GEAK_EINVAL),
+    (dict(), [(0, 4, 7)], B.GEAK_EDTYPE),
+    (dict(), [(2, 4, "f32")], B.GEAK_EALIGN),
+    (dict(), [(1, 4, "f16")], B.GEAK_EALIGN),
+    (dict(), [(0, 8, "f32"), (16, 4, "f32")], B.GEAK_EBOUNDS),   # overlap
+    (dict(), [(2 ** 63, 2 ** 62, "f32")], B.GEAK_EBOUNDS),       # offset + size overflows
+    (dict(), [(0, 2 ** 41, "f16")], B.GEAK_EBOUNDS),             # above the per-segment limit
+])
+def test_plan_rejects(lib, kwargs, segs, status):
+    st, plan = _plan(segs, **kwargs)
+    assert st == status and plan is None
+
+
+def test_null_arguments(lib):
+    st, plan = B.geak_check_plan_raw(None, 1, 2, 0.0, 0.0, 0, -1)
+    assert st == B.GEAK_EINVAL and plan is None
+    assert lib.geak_check_plan(None, None, 1, 2, 0.0, 0.0, 0, -1) == B.GEAK_EINVAL
+    assert B.geak_check_workspace_bytes(None) == 0
+    assert B.geak_check_result_count(None) == 0
+    B.geak_check_destroy(None)
+
+
+def test_host_only_plan_cannot_run(lib):
+    st, plan = _plan([(0, 1000, "f32")])
+    assert st == B.GEAK_OK
+    try:
+        assert B.geak_check_run(plan, 16, [16, 16], 16, 16, 0) == B.GEAK_EINVAL
+    finally:
+        B.geak_check_destroy(plan)
+
+
+def test_dense_plan_shapes(lib):
+    st, plan = B.geak_check_plan_dense("bf16", [16, 32, 4096, 128], 16, 1e-2, 1.6e-2, 0, -1)
+    assert st == B.GEAK_OK
+    info = B.geak_check_plan_info(plan)
+    n = 16 * 32 * 4096 * 128
+    assert info.num_segments == 1 and info.num_candidates == 16
+    assert info.algorithmic_bytes == 17 * n * 2
+    assert info.num_items == n * 2 // info.item_bytes
+    assert B.geak_check_result_count(plan) == 16
+    B.geak_check_destroy(plan)
+    # scalar and empty shapes
+    st, plan = B.geak_check_plan_dense("f32", [], 1, 0, 0, 0, -1)
+    assert st == B.GEAK_OK and B.geak_check_plan_info(plan).num_items == 1
+    B.geak_check_destroy(plan)
+    st, plan = B.geak_check_plan_dense("f32", [5, 0, 7], 3, 0, 0, 0, -1)
+    assert st == B.GEAK_OK
+    assert B.geak_check_plan_info(plan).num_items == 0 and B.geak_check_workspace_bytes(plan) == 0
+    assert B.geak_check_result_count(plan) == 3
+    B.geak_check_destroy(plan)
+    st, plan = B.geak_check_plan_dense("f32", [4, -1], 3, 0, 0, 0, -1)
+    assert st == B.GEAK_EINVAL
+
+
+def _check_table(segs, K):
+    st, plan = _plan(segs, K=K)
+    assert st == B.GEAK_OK
+    try:
+        info = B.geak_check_plan_info(plan)
+        items = B.geak_check_plan_items(plan)
+        assert len(items) == info.num_items
+        workers = info.grid_blocks * (info.block_threads // 64)
+        esize = {0: 4, 1: 2, 2: 2, 3: 4}
+        # every element of every segment is covered exactly once, in order
+        cursor = {}
+        for j, it in enumerate(items):
+            s = int(it["segment"])
+            off, n, dt = segs[s]
+            code = B.DTYPE_CODE[dt]
+            w = esize[code]
+            assert it["dtype"] == code
+            assert it["elem_start"] == cursor.get(s, 0)
+            assert it["byte_offset"] == off + int(it["elem_start"]) * w
+            assert 1 <= it["numel"] <= info.item_bytes // w
+            if it["flags"] & B.GEAK_ITEM_FULL:
+                assert it["byte_offset"] % 16 == 0 and it["numel"] * w == info.item_bytes
+            cursor[s] = cursor.get(s, 0) + int(it["numel"])
+        for s, (off, n, dt) in enumerate(segs):
+            assert cursor.get(s, 0) == n
+        # items of one segment are contiguous in the table and segments appear in order
+        seg_ids = items["segment"].astype(np.int64)
+        assert (np.diff(seg_ids) >= 0).all()
+        # run structure: following one worker through the table, FIRST opens and LAST closes each
+        # (worker, segment) run, the slot is constant inside a run and unique to it
+        seen_slots = {}
+        for wk in range(min(workers, len(items))):
+            mine = items[wk::workers]
+            open_slot = None
+            for it in mine:
+                if it["flags"] & B.GEAK_ITEM_FIRST:
+                    assert open_slot is None
+                    open_slot = int(it["slot"])
+                    assert open_slot not in seen_slots
+                    seen_slots[open_slot] = int(it["segment"])
+                assert open_slot == int(it["slot"])
+                assert seen_slots[open_slot] == int(it["segment"])
+                if it["flags"] & B.GEAK_ITEM_LAST:
+                    open_slot = None
+            assert open_slot is None
+        assert len(seen_slots) == info.num_slots
+        assert sorted(seen_slots) == list(range(info.num_slots))
+        # slots of a segment are contiguous
+        by_seg = {}
+        for slot, s in seen_slots.items():
+            by_seg.setdefault(s, []).append(slot)
+        for s, sl in by_seg.items():
+            assert max(sl) - min(sl) + 1 == len(sl)
+        assert info.algorithmic_bytes == (K + 1) * sum(n * esize[B.DTYPE_CODE[dt]] for _, n, dt in segs)
+        ws = B.geak_check_workspace_bytes(plan)
+        assert ws == (0 if len(items) == 0 else 256 * 8 + info.num_slots * K * 16)
+    finally:
+        B.geak_check_destroy(plan)
+
+
+def test_work_table_dense(lib):
+    _check_table([(0, 1 << 22, "f32")], 3)               # more items than workers
+    _check_table([(0, 5000, "f16")], 2)                  # ragged tail
+    _check_table([(0, 1, "i32")], 1)
+
+
+def test_work_table_ragged_unaligned(lib):
+    rng = np.random.default_rng(0)
+    segs, off = [], 0
+    for s in range(200):
+        dt = ["f32", "f16", "bf16", "i32"][rng.integers(0, 4)]
+        w = 2 if dt in ("f16", "bf16") else 4
+        off = (off + w - 1) // w * w + w * int(rng.integers(0, 9))
+        n = int(2 ** rng.uniform(0, 17)) if s % 7 else 0
+        segs.append((off, n, dt))
+        off += n * w
+    _check_table(segs, 4)
+    # same table in shuffled order is still legal (segments need not be sorted by offset)
+    perm = rng.permutation(len(segs))
+    _check_table([segs[i] for i in perm], 4)
+
+
+def test_work_table_persistent_grid(lib):
+    # a tensor large enough that every worker gets several items: the grid is capped
+    st, plan = B.geak_check_plan_dense("f32", [1 << 26], 2, 0, 0, 0, -1)
+    info = B.geak_check_plan_info(plan)
+    assert info.num_items == (1 << 28) // info.item_bytes
+    assert info.grid_blocks == 256 * 4                   # host-only plans assume 256 compute units
+    assert info.num_slots == info.grid_blocks * 4
+    B.geak_check_destroy(plan)
