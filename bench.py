@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Benchmark of the output-equivalence check on one MI355X.
+
+A step is one geak_check_run over one batch of synthetic tensors that are already resident in HBM:
+all three kernels (init, compare, reduce), i.e. the whole hot path.  The default workload is the
+fp16 8192 x 8192 tensor with 64 candidates; --config selects one of the other four recipes.
+
+Prints ONE JSON line: throughput in verified GB/s (algorithmic bytes = (K + 1) tensors read once,
+divided by the wall time of a step), the roofline entry of the compare kernel (its duration is
+taken from HIP events recorded around it on the run's stream during the timed steps) and the CPU
+oracle timed on a bounded sample of the same bytes.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+WORKLOADS = {
+    1: "config1: fp32 1024x1024, K=8",
+    2: "config2: fp16 8192x8192 Student-t(3)*0.5 with NaN/Inf, K=64, atol=rtol=1e-3, equal_nan",
+    3: "config3: bf16 [16,32,4096,128], K=16, atol=1e-2, rtol=1.6e-2",
+    4: "config4: ragged 1024 segments, log-uniform sizes to 2^20, mixed f32/f16/bf16/i32, K=4",
+    5: "config5: fp32 2^30 elements, K=32, atol=1e-6, rtol=1e-5",
+}
+
+
+def cpu_baseline(w, max_candidates: int, max_elems: int):
+    """The oracle as it stands, on the host cores, over a bounded sample of the workload."""
+    import numpy as np
+    import oracle
+    from paper_2507_23194_amd import synth
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import oracle_dense_chunked, host_threads
+
+    threads = host_threads()
+    ks = list(range(min(max_candidates, len(w.cands))))
+    if w.segments is None:
+        n = min(w.ref.numel(), max_elems)
+        ref = synth.to_numpy_raw(w.ref[:n])
+        cands = [synth.to_numpy_raw(w.cands[k][:n]) for k in ks]
+        esize = synth.ELEM_SIZE[w.dtype]
+        t0 = time.perf_counter()
+        oracle_dense_chunked(oracle, ref, cands, w.dtype, w.atol, w.rtol, w.equal_nan, threads)
+        dt = time.perf_counter() - t0
+        nbytes = (len(ks) + 1) * n * esize
+        sample = f"first {n} elements of the reference and of candidates 0..{len(ks) - 1}"
+    else:
+        ref = synth.to_numpy_raw(w.ref)
+        cands = [synth.to_numpy_raw(w.cands[k]) for k in ks]
+        t0 = time.perf_counter()
+        oracle.check_ragged(ref, cands, w.segments, w.atol, w.rtol, w.equal_nan, threads=threads)
+        dt = time.perf_counter() - t0
+        nbytes = (len(ks) + 1) * sum(n * synth.ELEM_SIZE[d] for (_, n, d) in w.segments)
+        sample = f"all segments, candidates 0..{len(ks) - 1}"
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle", "sample": sample,
+            "seconds": dt, "candidates_per_s": len(ks) / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per compare launch from rocprofv3 counters (reported as roofline.traffic)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2507_23194_amd import binding as B
+    from paper_2507_23194_amd import synth
+
+    torch.cuda.set_device(0)
+    w = synth.CONFIGS[args.config](device="cuda:0")
+    torch.cuda.synchronize()
+
+    if w.segments is None:
+        ck = B.Checker(dense=(w.dtype, (w.ref.numel(),)), num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol,
+                       equal_nan=w.equal_nan, device=0)
+    else:
+        ck = B.Checker(w.segments, num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol, equal_nan=w.equal_nan,
+                       device=0)
+    info = ck.info()
+    alg_bytes = int(info.algorithmic_bytes)
+    assert alg_bytes == w.algorithmic_bytes()
+
+    for _ in range(args.warmup):
+        ck.run(w.ref, w.cands)
+    torch.cuda.synchronize()
+
+    st = B.geak_check_profile_enable(ck.plan, args.steps)
+    assert st == B.GEAK_OK
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ck.run(w.ref, w.cands)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms = B.geak_check_profile_read(ck.plan, args.steps)
+    B.geak_check_profile_enable(ck.plan, 0)
+
+    rec = ck.read()
+    n_fail = int((rec["pass"] == 0).sum())
+    # the records must agree with what the generator planted (cheap sanity check, outside the timed region)
+    for (s, k), e in w.expect.items():
+        assert int(rec[s, k]["mismatch_count"]) == e["count"] and int(rec[s, k]["first_mismatch"]) == e["first"], (s, k)
+
+    ms_per_step = elapsed / args.steps * 1e3
+    gbps = alg_bytes / (elapsed / args.steps) / 1e9
+    k_ms = float(np.mean(kernel_ms)) if len(kernel_ms) else float("nan")
+    achieved = alg_bytes / (k_ms * 1e-3) / 1e9
+    out = {
+        "metric": "verified_bytes_per_sec",
+        "value": gbps,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.segments is None and w.dtype != "i32" else ("i32" if w.segments is None else "f32+i32"),
+        "data": "synthetic",
+        "config": {"workload": WORKLOADS[args.config], "num_candidates": len(w.cands),
+                   "algorithmic_bytes": alg_bytes, "segments": 1 if w.segments is None else len(w.segments),
+                   "grid_blocks": int(info.grid_blocks), "work_items": int(info.num_items)},
+        "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
+        "candidates_per_sec": len(w.cands) / (elapsed / args.steps),
+        "verdicts_per_sec": rec.size / (elapsed / args.steps),
+        "failing_candidates": n_fail,
+        "roofline": {"kernel": "compare_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": args.traffic_bytes,
+                     "kernel_ms_avg": k_ms, "kernel_ms_min": float(np.min(kernel_ms)) if len(kernel_ms) else None},
+    }
+    if not args.no_cpu_baseline:
+        budget = {1: (8, 1 << 20), 2: (16, 1 << 26), 3: (8, 1 << 27), 4: (4, 0), 5: (4, 1 << 28)}[args.config]
+        out["cpu_baseline"] = cpu_baseline(w, *budget)
+    ck.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

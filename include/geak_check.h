@@ -141,6 +141,9 @@ typedef struct {
     uint32_t lds_bytes;          /* dynamic LDS per block */
     uint32_t item_bytes;         /* bytes of one full work item per tensor */
     int32_t  device;
+    uint32_t items_per_block;    /* block b owns items [b * items_per_block, (b + 1) * items_per_block); wave w of
+                                    the block takes every (block_threads / 64)-th of them, starting at w */
+    uint32_t reserved;
 } geak_plan_info;
 
 /* One work item, as the compare kernel sees it. */

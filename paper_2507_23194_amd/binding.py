@@ -38,7 +38,8 @@ class PlanInfo(ctypes.Structure):
     _fields_ = [("num_segments", ctypes.c_uint64), ("num_items", ctypes.c_uint64), ("num_slots", ctypes.c_uint64),
                 ("algorithmic_bytes", ctypes.c_uint64), ("num_candidates", ctypes.c_uint32),
                 ("grid_blocks", ctypes.c_uint32), ("block_threads", ctypes.c_uint32), ("lds_bytes", ctypes.c_uint32),
-                ("item_bytes", ctypes.c_uint32), ("device", ctypes.c_int32)]
+                ("item_bytes", ctypes.c_uint32), ("device", ctypes.c_int32),
+                ("items_per_block", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class GeakError(RuntimeError):

@@ -179,7 +179,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.atol_f = hp.atol_f;
         ca.rtol_f = hp.rtol_f;
         ca.equal_nan = hp.equal_nan;
-        ca.reserved = 0;
+        ca.items_per_block = hp.items_per_block;
 
         geak_plan *mp = const_cast<geak_plan *>(plan);      // timing ring only; documented as not re-entrant
         const bool timed = !mp->ev_start.empty();
@@ -242,6 +242,7 @@ geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out)
     out->algorithmic_bytes = hp.algorithmic_bytes;
     out->num_candidates = (uint32_t)hp.num_candidates;
     out->grid_blocks = hp.grid_blocks;
+    out->items_per_block = hp.items_per_block;
     out->block_threads = kBlockThreads;
     out->lds_bytes = plan->lds_bytes;
     out->item_bytes = kItemBytes;

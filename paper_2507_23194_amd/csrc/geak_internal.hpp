@@ -40,6 +40,7 @@ struct HostPlan {
     float atol_f = 0.f, rtol_f = 0.f;
     int equal_nan = 0;
     uint32_t grid_blocks = 1;
+    uint32_t items_per_block = 1;          // block b owns items [b * items_per_block, (b + 1) * items_per_block)
     uint32_t max_blocks = 1;               // compute units x resident blocks per unit
 };
 
@@ -72,7 +73,7 @@ struct CompareArgs {
     float atol_f;
     float rtol_f;
     int equal_nan;
-    int reserved;
+    uint32_t items_per_block;
 };
 
 struct ReduceArgs {

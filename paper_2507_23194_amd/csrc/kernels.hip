@@ -175,25 +175,17 @@ __device__ __forceinline__ bool close_exact(float a, float b, float atol_f, floa
     return d <= tol;
 }
 
-// Threshold multiplier for the max_rel filter: c <= r*(1 - 2^-20), so that d <= RN(c*|b|) implies
-// d/|b| < r.  r = +Inf can never be exceeded: c = NaN makes every comparison false.
-__device__ __forceinline__ float rel_filter_scale(float r)
+// max_rel filter.  An element can raise the running maximum r only if d/|b| > r, i.e. d > r*|b| in
+// exact arithmetic.  e = fma(r, |b|, -d) is the correctly rounded value of r*|b| - d, and rounding
+// keeps the sign of the exact value (a tiny negative value becomes -0, an exact tie becomes +0), so
+// "e is negative, -0 included, and not NaN" is exactly the condition, at every magnitude, with no
+// division and without flagging ties.  One v_fma_f32 and one v_cmp_class_f32.
+//   NaN results (d NaN; Inf - Inf; 0 * Inf) mean "cannot raise" and are not flagged.
+//   r = +Inf is handled by the caller (nothing exceeds it); b = 0 gives e = -d: flagged iff d > 0.
+constexpr int kClassNegative = (1 << 2) | (1 << 3) | (1 << 4) | (1 << 5);   // -Inf, -normal, -subnormal, -0
+__device__ __forceinline__ bool may_raise_rel(float r, float babs, float d)
 {
-    if (r == kInfF) return __builtin_nanf("");
-    if (r < 0x1p-100f) return 0.0f;                 // r is 0 here (a non-zero quotient is >= 2^-25)
-    return r * 0.99999809265136718750f;             // 1 - 2^-19, product rounded once
-}
-
-// Conservative per-element threshold for the max_rel filter: not flagged (d <= threshold) implies
-// d <= c*|b| exactly.  The product may be subnormal, where rounding to nearest can round up by
-// half a unit; stepping the bit pattern down by one (saturating at 0) removes that.  binary16
-// inputs keep the product far from the subnormal range, so they skip the step.
-template <bool STEP_DOWN>
-__device__ __forceinline__ float rel_threshold(float c, float babs)
-{
-    const float t = c * babs;
-    if constexpr (STEP_DOWN) return bits_f(__builtin_elementwise_sub_sat(f_bits(t), 1u));
-    else return t;
+    return __builtin_amdgcn_classf(__builtin_fmaf(r, babs, -d), kClassNegative);
 }
 
 // ---- exact element-wise evaluation of one item for one candidate, straight from memory ----------
@@ -229,7 +221,8 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
             raise_max(&rec->max_rel_err, rm, rel_bits);
         }
     } else {
-        const float c = rel_filter_scale((float)__builtin_bit_cast(double, rel_bits));
+        const float seen_rel = (float)__builtin_bit_cast(double, rel_bits);   // exact: published from binary32
+        const bool rel_open = seen_rel < kInfF;
         float dm = 0.0f, rm = 0.0f;
         for (uint32_t i = lane; i < n; i += kWaveSize) {
             const float a = load_elem_f(cand, i, dtype), b = load_elem_f(ref, i, dtype);
@@ -237,7 +230,7 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
             const float d = __builtin_fabsf(a - b);
             const float babs = __builtin_fabsf(b);
             if (d > dm) dm = d;                                   // false for NaN: skipped
-            if (d > rel_threshold<true>(c, babs)) {               // implies d > 0
+            if (rel_open && may_raise_rel(seen_rel, babs, d)) {   // implies d > 0
                 const float r = d / babs;                         // correctly rounded; d/0 = +Inf; Inf/Inf = NaN
                 if (r > rm) rm = r;                               // false for NaN: skipped
             }
@@ -282,7 +275,6 @@ template <int DT>
 struct FloatItem {
     static constexpr int E = Traits<DT>::E;
     static constexpr int N = kVecPerLane * E;
-    static constexpr bool kStepDown = (DT != GEAK_F16);
     u32x4 braw[kVecPerLane];        // the reference slice as loaded; decoded on use (free for binary32)
     float tol[N];
     uint32_t poisoned_slots;        // wave-uniform: bit i set if any lane's element i is poisoned
@@ -309,9 +301,11 @@ struct FloatItem {
     }
 
     // Hot loop body for one 16-byte vector of one candidate.  Adds the suspects (elements with
-    // !(d <= tol)) to `suspects` and ORs into `trip` the lanes that may raise one of the two maxima.
+    // !(d <= tol)) to `suspects` and ORs into `trip_abs` / `trip_rel` the lanes that may raise
+    // max_abs_err / max_rel_err.
     template <int V>
-    __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float c, uint32_t &suspects, u64 &trip) const
+    __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float max_rel, uint32_t &suspects,
+                                                u64 &trip_abs, u64 &trip_rel) const
     {
         // The reference stays packed in registers and is decoded again for every candidate: one
         // more conversion per element, half the registers.  The empty asm keeps the decode from
@@ -325,11 +319,11 @@ struct FloatItem {
             const float x = decode<DT>(br, e);
             const float d = __builtin_fabsf(a - x);
             suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(d <= tol[i])));
-            trip |= __builtin_amdgcn_ballot_w64(d > max_abs);
-            trip |= __builtin_amdgcn_ballot_w64(d > rel_threshold<kStepDown>(c, __builtin_fabsf(x)));
-            // keep the OR a running chain in one scalar register pair (a balanced tree would
+            trip_abs |= __builtin_amdgcn_ballot_w64(d > max_abs);
+            trip_rel |= __builtin_amdgcn_ballot_w64(may_raise_rel(max_rel, __builtin_fabsf(x), d));
+            // keep each OR a running chain in one scalar register pair (a balanced tree would
             // hold every lane mask live at once)
-            asm volatile("" : "+s"(trip));
+            asm volatile("" : "+s"(trip_abs), "+s"(trip_rel));
         }
     }
 
@@ -354,6 +348,38 @@ struct FloatItem {
             }
         }
         return n;
+    }
+
+    // A lane of vector V may raise one of the maxima: evaluate the vector exactly, in registers, and
+    // publish at once, so that the other waves (and this wave's next vectors) see the new thresholds.
+    // Per lane the running maxima start from the wave-uniform ones, so the true division only runs
+    // for elements that really exceed what the lane has seen.
+    template <int V>
+    __device__ __forceinline__ void raise_vec(const u32x4 &q, float &max_abs, float &max_rel, geak_result *rec, int lane) const
+    {
+        const u32x4 br = braw[V];
+        float dm = max_abs, rm = max_rel;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const float a = decode<DT>(q, e);
+            const float x = decode<DT>(br, e);
+            const float d = __builtin_fabsf(a - x);
+            const float babs = __builtin_fabsf(x);
+            dm = (d > dm) ? d : dm;                                          // false for NaN: skipped
+            const bool hit = (rm < kInfF) && may_raise_rel(rm, babs, d);     // implies d > 0
+            if (__builtin_amdgcn_ballot_w64(hit)) {
+                const float r = d / babs;                                    // correctly rounded; d/0 = +Inf
+                rm = (hit && r > rm) ? r : rm;
+            }
+        }
+        dm = wave_max_f(dm);
+        rm = wave_max_f(rm);
+        if (lane == 0) {
+            if (dm > max_abs) atomicMax(reinterpret_cast<u64 *>(&rec->max_abs_err), __builtin_bit_cast(u64, (double)dm));
+            if (rm > max_rel) atomicMax(reinterpret_cast<u64 *>(&rec->max_rel_err), __builtin_bit_cast(u64, (double)rm));
+        }
+        max_abs = dm;
+        max_rel = rm;
     }
 };
 
@@ -435,11 +461,15 @@ __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 // each has a whole candidate's worth of compute to land.
 template <int DT, int V>
 __device__ __forceinline__ void float_step(const FloatItem<DT> &ref, u32x4 &slot, global_vec_ptr next, bool has_next,
-                                           float max_abs, float c, int equal_nan, uint32_t &bad, u64 &trip)
+                                           float &max_abs, float &max_rel, int equal_nan, geak_result *rec, int lane,
+                                           uint32_t &bad)
 {
     constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
-    ref.template compare_vec<V>(slot, max_abs, c, bad, trip);
+    u64 trip_abs = 0, trip_rel = 0;
+    ref.template compare_vec<V>(slot, max_abs, max_rel, bad, trip_abs, trip_rel);
     if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_vec<V>(slot, equal_nan);
+    if (max_rel == kInfF) trip_rel = 0;                  // nothing exceeds +Inf
+    if (trip_abs | trip_rel) ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
     if (has_next) slot = __builtin_nontemporal_load(next + V * kWaveSize);
 }
 
@@ -462,32 +492,26 @@ __device__ __noinline__ void process_full_float(const ItemArgs in, const WaveSta
     uint32_t k = p.k0;
     load_full(cur, table_entry(p.cand, k) + p.byte_offset, lane);
     u64 abs_bits = load_bits(&p.recs[k].max_abs_err), rel_bits = load_bits(&p.recs[k].max_rel_err);
-    bool any_revisit = false;
 
     for (uint32_t step = 0; step < K; ++step) {
         const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
         const bool has_next = step + 1 < K;
         global_vec_ptr next = (global_vec_ptr)(table_entry(p.cand, kn) + p.byte_offset) + lane;
 
-        const float max_abs = (float)__builtin_bit_cast(double, abs_bits);   // exact: published from binary32
-        const float c = rel_filter_scale((float)__builtin_bit_cast(double, rel_bits));
+        float max_abs = (float)__builtin_bit_cast(double, abs_bits);   // exact: published from binary32
+        float max_rel = (float)__builtin_bit_cast(double, rel_bits);
         if (has_next) {
             abs_bits = load_bits(&p.recs[kn].max_abs_err);
             rel_bits = load_bits(&p.recs[kn].max_rel_err);
         }
         uint32_t bad = 0;
-        u64 trip = 0;
-        float_step<DT, 0>(ref, cur[0], next, has_next, max_abs, c, p.equal_nan, bad, trip);
-        float_step<DT, 1>(ref, cur[1], next, has_next, max_abs, c, p.equal_nan, bad, trip);
-        float_step<DT, 2>(ref, cur[2], next, has_next, max_abs, c, p.equal_nan, bad, trip);
-        float_step<DT, 3>(ref, cur[3], next, has_next, max_abs, c, p.equal_nan, bad, trip);
+        float_step<DT, 0>(ref, cur[0], next, has_next, max_abs, max_rel, p.equal_nan, &p.recs[k], lane, bad);
+        float_step<DT, 1>(ref, cur[1], next, has_next, max_abs, max_rel, p.equal_nan, &p.recs[k], lane, bad);
+        float_step<DT, 2>(ref, cur[2], next, has_next, max_abs, max_rel, p.equal_nan, &p.recs[k], lane, bad);
+        float_step<DT, 3>(ref, cur[3], next, has_next, max_abs, max_rel, p.equal_nan, &p.recs[k], lane, bad);
         note_mismatches(st, k, bad, p.item_index, lane);
-        if (trip) { mark_revisit(st, k, lane); any_revisit = true; }
         k = kn;
     }
-    if (any_revisit)
-        revisit_marked(p.ref + p.byte_offset, p.cand, p.byte_offset, p.recs, st.revisit, K, p.numel, p.dtype, p.atol_f, p.rtol_f,
-                       p.equal_nan);
 }
 
 // ---- full items, int32 -----------------------------------------------------------------------------
@@ -547,7 +571,9 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     st.revisit = reinterpret_cast<uint32_t *>(lds + (sizeof(u64) + sizeof(uint32_t)) * kWavesPerBlock * K) + (size_t)wave * K;
     for (uint32_t k = lane; k < K; k += kWaveSize) st.revisit[k] = 0;
 
-    const uint32_t workers = gridDim.x * kWavesPerBlock;
+    const uint32_t block_begin = blockIdx.x * p.items_per_block;
+    if (block_begin >= p.num_items) return;              // the planner launches no such block; never index past the table
+    const uint32_t block_end = (p.num_items - block_begin < p.items_per_block) ? p.num_items : block_begin + p.items_per_block;
     ItemArgs a;
     a.ref = p.ref;
     a.cand = p.cand_table;
@@ -556,7 +582,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     a.atol_f = p.atol_f;
     a.rtol_f = p.rtol_f;
     a.equal_nan = p.equal_nan;
-    for (uint32_t j = blockIdx.x * kWavesPerBlock + wave; j < p.num_items; j += workers) {
+    for (uint32_t j = block_begin + wave; j < block_end; j += kWavesPerBlock) {
         const geak_item it = load_work_item(p.items, j);
         if (it.flags & GEAK_ITEM_FIRST) {
             for (uint32_t k = lane; k < K; k += kWaveSize) { st.count[k] = 0; st.first[k] = kNoItem; }

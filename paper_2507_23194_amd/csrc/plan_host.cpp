@@ -79,15 +79,19 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
 
         const uint64_t blocks_wanted = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
         hp.grid_blocks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
-        const uint64_t workers = (uint64_t)hp.grid_blocks * kWavesPerBlock;   // item j belongs to worker j % workers
+        // Block b owns the contiguous item range [b * items_per_block, (b + 1) * items_per_block); its
+        // four waves interleave inside it (wave w takes every fourth item starting at w).  A wave's
+        // consecutive items are then neighbours in memory and mostly of one segment, so the running
+        // maxima it has just raised are the right thresholds for its next item.
+        hp.items_per_block = (uint32_t)((n_items + hp.grid_blocks - 1) / hp.grid_blocks);
+        if (hp.items_per_block == 0) hp.items_per_block = 1;
+        // no block may start past the end of the table
+        hp.grid_blocks = (uint32_t)std::max<uint64_t>(1, (n_items + hp.items_per_block - 1) / hp.items_per_block);
 
-        uint64_t slot_cursor = 0;
         for (uint64_t s = 0; s < nsegs; ++s) {
-            hp.slot_begin[s] = (uint32_t)slot_cursor;
             const geak_segment &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
             if (!g.numel) continue;
-            const uint64_t first_item = hp.items.size();
             uint64_t done = 0;
             auto push = [&](uint64_t n, bool full) {
                 geak_item it{};
@@ -104,21 +108,34 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
             if (head) push(head, false);
             while (g.numel - done >= per) push(per, true);
             if (g.numel - done) push(g.numel - done, false);
-
-            // A worker meets the items of one segment consecutively (they are congruent modulo
-            // `workers`), so each (worker, segment) pair is one run with one slot.
-            const uint64_t last_item = hp.items.size();
-            const uint64_t n_seg_items = last_item - first_item;
-            for (uint64_t j = first_item; j < last_item; ++j) {
-                geak_item &it = hp.items[j];
-                it.slot = (uint32_t)(slot_cursor + (j - first_item) % workers);
-                if (j < first_item + workers) it.flags |= GEAK_ITEM_FIRST;
-                if (j + workers >= last_item) it.flags |= GEAK_ITEM_LAST;
-            }
-            slot_cursor += std::min<uint64_t>(workers, n_seg_items);
-            if (slot_cursor >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
         }
-        hp.slot_begin[nsegs] = (uint32_t)slot_cursor;
+
+        // Runs and slots.  Scanning the table in order, a wave opens a new run (and a new slot)
+        // whenever the segment of its next item differs from the segment of its previous one.
+        // Items of one segment are contiguous in the table, so the slots opened while scanning a
+        // segment are contiguous too.
+        const uint64_t workers = (uint64_t)hp.grid_blocks * kWavesPerBlock;
+        std::vector<uint32_t> run_segment(workers, 0xFFFFFFFFu), run_slot(workers, 0), last_item(workers, kNoItem);
+        uint64_t slot_cursor = 0;
+        uint64_t seg_cursor = 0;
+        for (uint64_t j = 0; j < hp.items.size(); ++j) {
+            geak_item &it = hp.items[j];
+            while (seg_cursor <= it.segment) hp.slot_begin[seg_cursor++] = (uint32_t)slot_cursor;
+            const uint64_t block = j / hp.items_per_block;
+            const uint64_t worker = block * kWavesPerBlock + (j - block * hp.items_per_block) % kWavesPerBlock;
+            if (run_segment[worker] != it.segment) {
+                if (last_item[worker] != kNoItem) hp.items[last_item[worker]].flags |= GEAK_ITEM_LAST;
+                run_segment[worker] = it.segment;
+                run_slot[worker] = (uint32_t)slot_cursor++;
+                it.flags |= GEAK_ITEM_FIRST;
+                if (slot_cursor >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
+            }
+            it.slot = run_slot[worker];
+            last_item[worker] = (uint32_t)j;
+        }
+        for (uint64_t wk = 0; wk < workers; ++wk)
+            if (last_item[wk] != kNoItem) hp.items[last_item[wk]].flags |= GEAK_ITEM_LAST;
+        while (seg_cursor <= nsegs) hp.slot_begin[seg_cursor++] = (uint32_t)slot_cursor;
     } catch (const std::bad_alloc &) {
         return GEAK_ENOMEM;
     }

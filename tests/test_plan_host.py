@@ -113,7 +113,9 @@ def _check_table(segs, K):
         info = B.geak_check_plan_info(plan)
         items = B.geak_check_plan_items(plan)
         assert len(items) == info.num_items
-        workers = info.grid_blocks * (info.block_threads // 64)
+        waves = info.block_threads // 64
+        ipb = info.items_per_block
+        assert ipb * info.grid_blocks >= len(items) and ipb * (info.grid_blocks - 1) < max(1, len(items))
         esize = {0: 4, 1: 2, 2: 2, 3: 4}
         # every element of every segment is covered exactly once, in order
         cursor = {}
@@ -137,8 +139,9 @@ def _check_table(segs, K):
         # run structure: following one worker through the table, FIRST opens and LAST closes each
         # (worker, segment) run, the slot is constant inside a run and unique to it
         seen_slots = {}
-        for wk in range(min(workers, len(items))):
-            mine = items[wk::workers]
+        sequences = [items[b * ipb:(b + 1) * ipb][w::waves] for b in range(info.grid_blocks) for w in range(waves)]
+        assert sum(len(m) for m in sequences) == len(items)
+        for mine in sequences:
             open_slot = None
             for it in mine:
                 if it["flags"] & B.GEAK_ITEM_FIRST:
@@ -186,6 +189,25 @@ def test_work_table_ragged_unaligned(lib):
     # same table in shuffled order is still legal (segments need not be sorted by offset)
     perm = rng.permutation(len(segs))
     _check_table([segs[i] for i in perm], 4)
+
+
+def test_work_table_many_segments_uneven_blocks(lib):
+    # the ragged benchmark shape: more items than workers, item count not a multiple of the grid
+    rng = np.random.default_rng(3)
+    segs, off = [], 0
+    for s in range(1024):
+        dt = ["f32", "f16", "bf16", "i32"][rng.integers(0, 4)]
+        w = 2 if dt in ("f16", "bf16") else 4
+        n = max(1, int(2 ** (20 * rng.random())))
+        off = (off + 15) // 16 * 16
+        segs.append((off, n, dt))
+        off += n * w
+    _check_table(segs, 4)
+    st, plan = _plan(segs, K=4)
+    info = B.geak_check_plan_info(plan)
+    assert info.num_items % info.grid_blocks != 0
+    assert (info.grid_blocks - 1) * info.items_per_block < info.num_items <= info.grid_blocks * info.items_per_block
+    B.geak_check_destroy(plan)
 
 
 def test_work_table_persistent_grid(lib):
