@@ -271,11 +271,55 @@ __device__ __forceinline__ void note_mismatches(const WaveState &st, uint32_t k,
 }
 
 // ---- full items, floating dtypes: reference slice staged in registers ---------------------------
+// Lane mask of "x is negative (-0 included) and not NaN".  Written as the instruction itself: a
+// ballot of the class builtin is materialised through a vector register and compared again.
+__device__ __forceinline__ u64 negative_mask(float x)
+{
+    u64 m;
+    asm("v_cmp_class_f32_e64 %0, %1, 60" : "=s"(m) : "v"(x));      // 60 = kClassNegative
+    return m;
+}
+
+// binary16 operands are consumed straight from the packed registers by the mixed-precision FMA
+// (f16 sources, f32 arithmetic, one rounding): a*1 - b is RN(a - b), the same value as converting
+// both and subtracting, in one instruction instead of three.
+template <bool HI>
+__device__ __forceinline__ float f16_diff(uint32_t a2, uint32_t b2)
+{
+    float d;
+    if constexpr (HI) asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,1] op_sel_hi:[1,0,1]" : "=v"(d) : "v"(a2), "v"(b2));
+    else              asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,1]" : "=v"(d) : "v"(a2), "v"(b2));
+    return d;
+}
+// r*|b| - |d| with b a binary16 half of b2
+template <bool HI>
+__device__ __forceinline__ float f16_rel_margin(float r, uint32_t b2, float d)
+{
+    float e;
+    if constexpr (HI) asm("v_fma_mix_f32 %0, %1, |%2|, -|%3| op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "=v"(e) : "v"(r), "v"(b2), "v"(d));
+    else              asm("v_fma_mix_f32 %0, %1, |%2|, -|%3| op_sel:[0,0,0] op_sel_hi:[0,1,0]" : "=v"(e) : "v"(r), "v"(b2), "v"(d));
+    return e;
+}
+
+template <int I> struct Index { static constexpr int value = I; };
+template <int N, typename F, int I = 0>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(Index<I>{});
+        static_for<N, F, I + 1>(static_cast<F &&>(f));
+    }
+}
+
 template <int DT>
 struct FloatItem {
     static constexpr int E = Traits<DT>::E;
     static constexpr int N = kVecPerLane * E;
-    u32x4 braw[kVecPerLane];        // the reference slice as loaded; decoded on use (free for binary32)
+    // Reference storage: binary32 and binary16 keep the vectors as loaded (binary32 needs no decode,
+    // binary16 is read in place by the mixed-precision FMA); bfloat16 is unpacked once, because
+    // unpacking it again for every candidate would cost an instruction per element.
+    static constexpr int kRefRegs = (DT == GEAK_BF16) ? N : kVecPerLane * 4;
+    uint32_t bref[kRefRegs];
     float tol[N];
     uint32_t poisoned_slots;        // wave-uniform: bit i set if any lane's element i is poisoned
 
@@ -284,11 +328,15 @@ struct FloatItem {
         poisoned_slots = 0;
 #pragma unroll
         for (int v = 0; v < kVecPerLane; ++v) {
-            braw[v] = q[v];
+            if constexpr (DT != GEAK_BF16) {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) bref[v * 4 + w] = q[v][w];
+            }
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 const int i = v * E + e;
                 const float x = decode<DT>(q[v], e);
+                if constexpr (DT == GEAK_BF16) bref[i] = f_bits(x);
                 const float prod = rtol_f * __builtin_fabsf(x);
                 const float t = atol_f + prod;
                 const bool bad = !(t < kInfF);          // b NaN, b +-Inf, or the tolerance overflowed
@@ -300,31 +348,51 @@ struct FloatItem {
         }
     }
 
+    // reference element i = V*E + e as binary32 (rare paths)
+    template <int V, int e>
+    __device__ __forceinline__ float ref_value() const
+    {
+        if constexpr (DT == GEAK_F32) return bits_f(bref[V * 4 + e]);
+        else if constexpr (DT == GEAK_BF16) return bits_f(bref[V * E + e]);
+        else {
+            const uint32_t word = bref[V * 4 + (e >> 1)];
+            const uint16_t h = (e & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xFFFFu);
+            return (float)__builtin_bit_cast(_Float16, h);
+        }
+    }
+
+    // a - b for element e of vector V, and r*|b| - |a - b|
+    template <int V, int e>
+    __device__ __forceinline__ float diff(const u32x4 &q) const
+    {
+        if constexpr (DT == GEAK_F16) return f16_diff<(e & 1) != 0>(q[e >> 1], bref[V * 4 + (e >> 1)]);
+        else return decode<DT>(q, e) - ref_value<V, e>();
+    }
+    template <int V, int e>
+    __device__ __forceinline__ float rel_margin(float r, float d) const
+    {
+        if constexpr (DT == GEAK_F16) return f16_rel_margin<(e & 1) != 0>(r, bref[V * 4 + (e >> 1)], d);
+        else return __builtin_fmaf(r, __builtin_fabsf(ref_value<V, e>()), -__builtin_fabsf(d));
+    }
+
     // Hot loop body for one 16-byte vector of one candidate.  Adds the suspects (elements with
     // !(d <= tol)) to `suspects` and ORs into `trip_abs` / `trip_rel` the lanes that may raise
-    // max_abs_err / max_rel_err.
+    // max_abs_err / max_rel_err.  Five vector instructions per element (six for bfloat16).
     template <int V>
     __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float max_rel, uint32_t &suspects,
                                                 u64 &trip_abs, u64 &trip_rel) const
     {
-        // The reference stays packed in registers and is decoded again for every candidate: one
-        // more conversion per element, half the registers.  The empty asm keeps the decode from
-        // being hoisted out of the candidate loop (which would unpack it for good).
-        u32x4 br = braw[V];
-        if constexpr (Traits<DT>::W == 2) asm volatile("" : "+v"(br));
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const int i = V * E + e;
-            const float a = decode<DT>(q, e);
-            const float x = decode<DT>(br, e);
-            const float d = __builtin_fabsf(a - x);
-            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(d <= tol[i])));
-            trip_abs |= __builtin_amdgcn_ballot_w64(d > max_abs);
-            trip_rel |= __builtin_amdgcn_ballot_w64(may_raise_rel(max_rel, __builtin_fabsf(x), d));
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            constexpr int i = V * E + e;
+            const float d = diff<V, e>(q);
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d) <= tol[i])));
+            trip_abs |= __builtin_amdgcn_ballot_w64(__builtin_fabsf(d) > max_abs);
+            trip_rel |= negative_mask(rel_margin<V, e>(max_rel, d));
             // keep each OR a running chain in one scalar register pair (a balanced tree would
             // hold every lane mask live at once)
             asm volatile("" : "+s"(trip_abs), "+s"(trip_rel));
-        }
+        });
     }
 
     // Poisoned elements were all reported as suspects; count those that the NaN / Inf rule accepts.
@@ -332,12 +400,12 @@ struct FloatItem {
     __device__ __forceinline__ uint32_t false_suspects_vec(const u32x4 &q, int equal_nan) const
     {
         uint32_t n = 0;
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const int i = V * E + e;
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            constexpr int i = V * E + e;
             if (poisoned_slots & (1u << i)) {
                 const float a = decode<DT>(q, e);
-                const float x = decode<DT>(braw[V], e);
+                const float x = ref_value<V, e>();
                 float why = tol[i];
                 asm volatile("" : "+v"(why));   // evaluate here, per candidate: hoisted lane masks would not fit the scalar file
                 const bool ok = (why == -1.0f) ? (equal_nan && (a != a))
@@ -346,7 +414,7 @@ struct FloatItem {
                               : false;
                 n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok));
             }
-        }
+        });
         return n;
     }
 
@@ -357,13 +425,11 @@ struct FloatItem {
     template <int V>
     __device__ __forceinline__ void raise_vec(const u32x4 &q, float &max_abs, float &max_rel, geak_result *rec, int lane) const
     {
-        const u32x4 br = braw[V];
         float dm = max_abs, rm = max_rel;
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const float a = decode<DT>(q, e);
-            const float x = decode<DT>(br, e);
-            const float d = __builtin_fabsf(a - x);
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            const float x = ref_value<V, e>();
+            const float d = __builtin_fabsf(decode<DT>(q, e) - x);
             const float babs = __builtin_fabsf(x);
             dm = (d > dm) ? d : dm;                                          // false for NaN: skipped
             const bool hit = (rm < kInfF) && may_raise_rel(rm, babs, d);     // implies d > 0
@@ -371,7 +437,7 @@ struct FloatItem {
                 const float r = d / babs;                                    // correctly rounded; d/0 = +Inf
                 rm = (hit && r > rm) ? r : rm;
             }
-        }
+        });
         dm = wave_max_f(dm);
         rm = wave_max_f(rm);
         if (lane == 0) {
