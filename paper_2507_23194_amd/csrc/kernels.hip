@@ -270,6 +270,23 @@ __device__ __forceinline__ void note_mismatches(const WaveState &st, uint32_t k,
     }
 }
 
+// A (worker, segment) run begins: clear the wave's running state.  It ends: write it to the run's slot.
+__device__ __forceinline__ void begin_run(const WaveState &st, uint32_t K, int lane)
+{
+    for (uint32_t k = lane; k < K; k += kWaveSize) { st.count[k] = 0; st.first[k] = kNoItem; }
+}
+__device__ __forceinline__ void end_run(const WaveState &st, Partial *partials, uint32_t slot, uint32_t K, int lane)
+{
+    Partial *out = partials + (u64)slot * K;
+    for (uint32_t k = lane; k < K; k += kWaveSize) {
+        Partial r;
+        r.count = st.count[k];
+        r.first_item = st.first[k];
+        r.reserved = 0;
+        out[k] = r;
+    }
+}
+
 // ---- full items, floating dtypes: reference slice staged in registers ---------------------------
 // Lane mask of "x is negative (-0 included) and not NaN".  Written as the instruction itself: a
 // ballot of the class builtin is materialised through a vector register and compared again.
@@ -323,28 +340,28 @@ struct FloatItem {
     float tol[N];
     uint32_t poisoned_slots;        // wave-uniform: bit i set if any lane's element i is poisoned
 
-    __device__ __forceinline__ void stage(const u32x4 (&q)[kVecPerLane], float atol_f, float rtol_f)
+    // Stage vector V of the reference slice: keep it (packed or unpacked, see above), compute the
+    // tolerance of each of its elements once, and poison the elements the bare inequality cannot judge.
+    template <int V>
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, float atol_f, float rtol_f)
     {
-        poisoned_slots = 0;
+        if constexpr (V == 0) poisoned_slots = 0;
+        if constexpr (DT != GEAK_BF16) {
 #pragma unroll
-        for (int v = 0; v < kVecPerLane; ++v) {
-            if constexpr (DT != GEAK_BF16) {
+            for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
+        }
 #pragma unroll
-                for (int w = 0; w < 4; ++w) bref[v * 4 + w] = q[v][w];
-            }
-#pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const int i = v * E + e;
-                const float x = decode<DT>(q[v], e);
-                if constexpr (DT == GEAK_BF16) bref[i] = f_bits(x);
-                const float prod = rtol_f * __builtin_fabsf(x);
-                const float t = atol_f + prod;
-                const bool bad = !(t < kInfF);          // b NaN, b +-Inf, or the tolerance overflowed
-                // the poison value also records why: -1 b is NaN, -2 b is +-Inf, -3 finite b, tolerance +Inf
-                const float why = (x != x) ? -1.0f : (__builtin_fabsf(x) == kInfF ? -2.0f : -3.0f);
-                tol[i] = bad ? why : t;
-                if (__builtin_amdgcn_ballot_w64(bad)) poisoned_slots |= (1u << i);
-            }
+        for (int e = 0; e < E; ++e) {
+            const int i = V * E + e;
+            const float x = decode<DT>(q, e);
+            if constexpr (DT == GEAK_BF16) bref[i] = f_bits(x);
+            const float prod = rtol_f * __builtin_fabsf(x);
+            const float t = atol_f + prod;
+            const bool bad = !(t < kInfF);          // b NaN, b +-Inf, or the tolerance overflowed
+            // the poison value also records why: -1 b is NaN, -2 b is +-Inf, -3 finite b, tolerance +Inf
+            const float why = (x != x) ? -1.0f : (__builtin_fabsf(x) == kInfF ? -2.0f : -3.0f);
+            tol[i] = bad ? why : t;
+            if (__builtin_amdgcn_ballot_w64(bad)) poisoned_slots |= (1u << i);
         }
     }
 
@@ -522,9 +539,26 @@ __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
     return st;
 }
 
-// One vector step of the candidate loop: compare vector V of the current candidate, then reuse its
-// registers for the same vector of the next candidate.  Four loads per lane stay in flight and
-// each has a whole candidate's worth of compute to land.
+// Arguments of a run of full floating items of one wave.
+struct RunArgs {
+    const geak_item *items;
+    const unsigned char *ref;            // buffer base
+    const unsigned char *const *cand;    // device table of K candidate bases
+    geak_result *results;
+    Partial *partials;
+    uint32_t first_item;                 // index of the run's first item; the wave owns every 4th item up to block_end
+    uint32_t block_end;
+    uint32_t K;
+    uint32_t k0;
+    float atol_f;
+    float rtol_f;
+    int equal_nan;
+};
+
+// One vector step of the stream: compare vector V of the current candidate, then reuse its
+// registers for the same vector of the next element of the wave's stream (the next candidate, or
+// the reference slice of the wave's next item).  Four loads per lane stay in flight and each has a
+// whole element's worth of compute to land.
 template <int DT, int V>
 __device__ __forceinline__ void float_step(const FloatItem<DT> &ref, u32x4 &slot, global_vec_ptr next, bool has_next,
                                            float &max_abs, float &max_rel, int equal_nan, geak_result *rec, int lane,
@@ -539,45 +573,81 @@ __device__ __forceinline__ void float_step(const FloatItem<DT> &ref, u32x4 &slot
     if (has_next) slot = __builtin_nontemporal_load(next + V * kWaveSize);
 }
 
-// Each dtype's item routine is a real function, so that its register allocation stands alone
-// instead of being merged with the other dtypes' inside the kernel.
+// Each dtype's routine is a real function, so that its register allocation stands alone instead of
+// being merged with the other dtypes' inside the kernel.  It processes a whole run of consecutive
+// full items of its dtype: the wave's loads form one stream -- reference slice, K candidate slices,
+// next reference slice, ... -- that never drains at an item boundary.  Returns the index of the
+// wave's first item it did not process.
 template <int DT>
-__device__ __noinline__ void process_full_float(const ItemArgs in, const WaveState st_in)
+__device__ __noinline__ uint32_t process_full_run(const RunArgs in, const WaveState st_in)
 {
-    const ItemArgs p = uniform_args(in);
     const WaveState st = uniform_state(st_in);
+    const geak_item *items = uniform_ptr(in.items);
+    const unsigned char *ref_base = uniform_ptr(in.ref);
+    const unsigned char *const *cand = uniform_ptr(in.cand);
+    geak_result *results = uniform_ptr(in.results);
+    Partial *partials = uniform_ptr(in.partials);
+    const uint32_t block_end = uniform32(in.block_end), K = uniform32(in.K), k0 = uniform32(in.k0);
+    const float atol_f = bits_f(uniform32(f_bits(in.atol_f))), rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
+    const int equal_nan = (int)uniform32((uint32_t)in.equal_nan);
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const uint32_t K = p.K;
+
+    uint32_t j = uniform32(in.first_item);
+    geak_item it = load_work_item(items, j);
     FloatItem<DT> ref;
-    {
-        u32x4 q[kVecPerLane];
-        load_full(q, p.ref + p.byte_offset, lane);
-        ref.stage(q, p.atol_f, p.rtol_f);
-    }
     u32x4 cur[kVecPerLane];
-    uint32_t k = p.k0;
-    load_full(cur, table_entry(p.cand, k) + p.byte_offset, lane);
-    u64 abs_bits = load_bits(&p.recs[k].max_abs_err), rel_bits = load_bits(&p.recs[k].max_rel_err);
+    load_full(cur, ref_base + it.byte_offset, lane);     // the only load of the run that nothing hides
 
-    for (uint32_t step = 0; step < K; ++step) {
-        const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
-        const bool has_next = step + 1 < K;
-        global_vec_ptr next = (global_vec_ptr)(table_entry(p.cand, kn) + p.byte_offset) + lane;
-
-        float max_abs = (float)__builtin_bit_cast(double, abs_bits);   // exact: published from binary32
-        float max_rel = (float)__builtin_bit_cast(double, rel_bits);
-        if (has_next) {
-            abs_bits = load_bits(&p.recs[kn].max_abs_err);
-            rel_bits = load_bits(&p.recs[kn].max_rel_err);
+    for (;;) {
+        // look ahead: does the wave's next item continue the run?
+        const uint32_t jn = j + kWavesPerBlock;
+        bool more = jn < block_end;
+        geak_item nx = it;
+        if (more) {
+            nx = load_work_item(items, jn);
+            more = (nx.flags & GEAK_ITEM_FULL) && nx.dtype == DT;
         }
-        uint32_t bad = 0;
-        float_step<DT, 0>(ref, cur[0], next, has_next, max_abs, max_rel, p.equal_nan, &p.recs[k], lane, bad);
-        float_step<DT, 1>(ref, cur[1], next, has_next, max_abs, max_rel, p.equal_nan, &p.recs[k], lane, bad);
-        float_step<DT, 2>(ref, cur[2], next, has_next, max_abs, max_rel, p.equal_nan, &p.recs[k], lane, bad);
-        float_step<DT, 3>(ref, cur[3], next, has_next, max_abs, max_rel, p.equal_nan, &p.recs[k], lane, bad);
-        note_mismatches(st, k, bad, p.item_index, lane);
-        k = kn;
+        if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
+        geak_result *recs = results + (u64)it.segment * K;
+
+        // reference element: stage it, refilling each vector with the first candidate's
+        uint32_t k = k0;
+        {
+            global_vec_ptr first = (global_vec_ptr)(table_entry(cand, k) + it.byte_offset) + lane;
+            ref.template stage_vec<0>(cur[0], atol_f, rtol_f); cur[0] = __builtin_nontemporal_load(first + 0 * kWaveSize);
+            ref.template stage_vec<1>(cur[1], atol_f, rtol_f); cur[1] = __builtin_nontemporal_load(first + 1 * kWaveSize);
+            ref.template stage_vec<2>(cur[2], atol_f, rtol_f); cur[2] = __builtin_nontemporal_load(first + 2 * kWaveSize);
+            ref.template stage_vec<3>(cur[3], atol_f, rtol_f); cur[3] = __builtin_nontemporal_load(first + 3 * kWaveSize);
+        }
+        u64 abs_bits = load_bits(&recs[k].max_abs_err), rel_bits = load_bits(&recs[k].max_rel_err);
+
+        for (uint32_t step = 0; step < K; ++step) {
+            const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
+            const bool last = step + 1 == K;
+            const bool has_next = !last || more;
+            const unsigned char *next_base = last ? ref_base + nx.byte_offset : table_entry(cand, kn) + it.byte_offset;
+            global_vec_ptr next = (global_vec_ptr)next_base + lane;
+
+            float max_abs = (float)__builtin_bit_cast(double, abs_bits);   // exact: published from binary32
+            float max_rel = (float)__builtin_bit_cast(double, rel_bits);
+            if (!last) {
+                abs_bits = load_bits(&recs[kn].max_abs_err);
+                rel_bits = load_bits(&recs[kn].max_rel_err);
+            }
+            uint32_t bad = 0;
+            float_step<DT, 0>(ref, cur[0], next, has_next, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            float_step<DT, 1>(ref, cur[1], next, has_next, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            float_step<DT, 2>(ref, cur[2], next, has_next, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            float_step<DT, 3>(ref, cur[3], next, has_next, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            note_mismatches(st, k, bad, j, lane);
+            k = kn;
+        }
+        if (it.flags & GEAK_ITEM_LAST) end_run(st, partials, it.slot, K, lane);
+        if (!more) break;
+        it = nx;
+        j = jn;
     }
+    return j + kWavesPerBlock;
 }
 
 // ---- full items, int32 -----------------------------------------------------------------------------
@@ -648,36 +718,44 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     a.atol_f = p.atol_f;
     a.rtol_f = p.rtol_f;
     a.equal_nan = p.equal_nan;
-    for (uint32_t j = block_begin + wave; j < block_end; j += kWavesPerBlock) {
+    RunArgs r;
+    r.items = p.items;
+    r.ref = p.ref;
+    r.cand = p.cand_table;
+    r.results = p.results;
+    r.partials = p.partials;
+    r.block_end = block_end;
+    r.K = K;
+    r.k0 = a.k0;
+    r.atol_f = p.atol_f;
+    r.rtol_f = p.rtol_f;
+    r.equal_nan = p.equal_nan;
+
+    uint32_t j = block_begin + wave;
+    while (j < block_end) {
         const geak_item it = load_work_item(p.items, j);
-        if (it.flags & GEAK_ITEM_FIRST) {
-            for (uint32_t k = lane; k < K; k += kWaveSize) { st.count[k] = 0; st.first[k] = kNoItem; }
+        if ((it.flags & GEAK_ITEM_FULL) && it.dtype != GEAK_I32) {
+            // a run of full floating items: handled, state bookkeeping included, by the dtype's routine
+            r.first_item = j;
+            uint32_t next_j;
+            switch (it.dtype) {
+            case GEAK_F32:  next_j = process_full_run<GEAK_F32>(r, st); break;
+            case GEAK_F16:  next_j = process_full_run<GEAK_F16>(r, st); break;
+            default:        next_j = process_full_run<GEAK_BF16>(r, st); break;
+            }
+            j = __builtin_amdgcn_readfirstlane(next_j);
+            continue;
         }
+        if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
         a.recs = p.results + (u64)it.segment * K;
         a.byte_offset = it.byte_offset;
         a.numel = it.numel;
         a.item_index = j;
         a.dtype = it.dtype;
-        if (it.flags & GEAK_ITEM_FULL) {
-            switch (it.dtype) {
-            case GEAK_F32:  process_full_float<GEAK_F32>(a, st); break;
-            case GEAK_F16:  process_full_float<GEAK_F16>(a, st); break;
-            case GEAK_BF16: process_full_float<GEAK_BF16>(a, st); break;
-            default:        process_full_int(a, st); break;
-            }
-        } else {
-            process_partial(a, st, lane);
-        }
-        if (it.flags & GEAK_ITEM_LAST) {
-            Partial *out = p.partials + (u64)it.slot * K;
-            for (uint32_t k = lane; k < K; k += kWaveSize) {
-                Partial r;
-                r.count = st.count[k];
-                r.first_item = st.first[k];
-                r.reserved = 0;
-                out[k] = r;
-            }
-        }
+        if (it.flags & GEAK_ITEM_FULL) process_full_int(a, st);
+        else process_partial(a, st, lane);
+        if (it.flags & GEAK_ITEM_LAST) end_run(st, p.partials, it.slot, K, lane);
+        j += kWavesPerBlock;
     }
 }
 
