@@ -158,9 +158,10 @@ typedef struct {
     uint16_t reserved;
 } geak_item;
 
-#define GEAK_ITEM_FULL  1u /* 16-byte aligned start and exactly item_bytes long: vector loads */
+#define GEAK_ITEM_FULL  1u /* 16-byte aligned start and exactly item_bytes long: unguarded vector loads */
 #define GEAK_ITEM_FIRST 2u /* first item of its (worker, segment) run: running state is reset */
 #define GEAK_ITEM_LAST  4u /* last item of its run: running state is written to the slot */
+#define GEAK_ITEM_ALIGNED 8u /* 16-byte aligned start (FULL implies it): vector loads, guarded at the end */
 
 geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
 

@@ -24,10 +24,9 @@ struct Partial {
     uint32_t reserved;
 };
 
-// LDS bytes one block needs: per wave and candidate a 64-bit count, a 32-bit first-item index
-// and a 32-bit revisit flag.
+// LDS bytes one block needs: per wave and candidate a 64-bit count and a 32-bit first-item index.
 inline uint32_t lds_bytes_for(int num_candidates) {
-    return (uint32_t)(kWavesPerBlock * num_candidates * (sizeof(unsigned long long) + 2 * sizeof(uint32_t)));
+    return (uint32_t)(kWavesPerBlock * num_candidates * (sizeof(unsigned long long) + sizeof(uint32_t)));
 }
 
 // Host side of a plan: everything that can be decided without a device.

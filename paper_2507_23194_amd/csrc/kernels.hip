@@ -22,8 +22,9 @@
 //     the global maxima with 64-bit atomic max on the bit patterns of the non-negative doubles.
 //     Rounding is monotone, so the maximum of the rounded quotients is the rounded quotient of a
 //     tripping element.
-//   * Segment heads and tails (items that are not a full, 16-byte aligned 4 KiB) take a compact
-//     element-wise path that applies the full rule straight from memory.
+//   * A segment's tail (an item shorter than 4 KiB) takes the same path with guarded loads that
+//     read absent elements as 0; the few elements before a segment's first 16-byte boundary take a
+//     compact element-wise path that applies the full rule straight from memory.
 //   * first_mismatch: the wave only remembers the first of its items that holds a mismatch; the
 //     reduce kernel re-reads that one item and finds the exact index.
 // reduce kernel -- one wavefront per (segment, candidate): sums counts over the segment's slots,
@@ -111,6 +112,37 @@ __device__ __forceinline__ void load_full(u32x4 (&dst)[kVecPerLane], const unsig
 #pragma unroll
     for (int v = 0; v < kVecPerLane; ++v)
         dst[v] = __builtin_nontemporal_load(p + v * kWaveSize);
+}
+
+// Vector V of lane L of an item that starts 16-byte aligned but may be shorter than a full item
+// (a segment's tail): whole vectors inside the item are loaded as such, the one vector that
+// straddles the end element by element, and everything past the end reads as 0 -- in the reference
+// and in every candidate alike, so that those positions compare as close and add nothing to either
+// maximum.  Nothing outside the item's bytes is touched.
+template <int DT>
+__device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, int v, uint32_t n, bool full)
+{
+    constexpr uint32_t E = Traits<DT>::E;
+    global_vec_ptr p = (global_vec_ptr)base + (v * kWaveSize + lane);
+    if (full) return __builtin_nontemporal_load(p);
+    const uint32_t first = (uint32_t)(v * kWaveSize + lane) * E;
+    u32x4 q = {0u, 0u, 0u, 0u};
+    if (first + E <= n) {
+        q = __builtin_nontemporal_load(p);
+    } else if (first < n) {
+        if constexpr (Traits<DT>::W == 4) {
+            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (first + e < n) q[e] = w[e];
+        } else {
+            const GEAK_AS_GLOBAL uint16_t *h = (const GEAK_AS_GLOBAL uint16_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (first + e < n) q[e >> 1] |= (uint32_t)h[e] << ((e & 1) * 16);
+        }
+    }
+    return q;
 }
 
 // One element straight from memory, decoded exactly to binary32 (floating dtypes).
@@ -251,16 +283,7 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
 struct WaveState {
     u64 *count;          // [K] mismatching elements of the current (worker, segment) run
     uint32_t *first;     // [K] least item index of the run that holds a mismatch
-    uint32_t *revisit;   // [K] set when the current item must be re-evaluated exactly for candidate k
 };
-
-// Candidates whose maxima the item may raise are only marked inside the candidate loop; the exact
-// evaluation (a function call that re-reads the item) runs after the loop, when the staged
-// reference and the load buffers are dead, so the hot loop carries no call and no spills.
-__device__ __forceinline__ void mark_revisit(const WaveState &st, uint32_t k, int lane)
-{
-    if (lane == 0) st.revisit[k] = 1;
-}
 
 __device__ __forceinline__ void note_mismatches(const WaveState &st, uint32_t k, uint32_t n, uint32_t item, int lane)
 {
@@ -330,6 +353,8 @@ __device__ __forceinline__ void static_for(F &&f)
 
 template <int DT>
 struct FloatItem {
+    typedef float Hint;                 // the running maxima of floating segments are binary32 values
+    static __device__ __forceinline__ float hint_from_bits(u64 bits) { return (float)__builtin_bit_cast(double, bits); }
     static constexpr int E = Traits<DT>::E;
     static constexpr int N = kVecPerLane * E;
     // Reference storage: binary32 and binary16 keep the vectors as loaded (binary32 needs no decode,
@@ -466,41 +491,64 @@ struct FloatItem {
     }
 };
 
-struct ItemArgs {
-    const unsigned char *ref;            // buffer base
-    const unsigned char *const *cand;    // device table of K candidate bases
-    geak_result *recs;                   // the segment's K records
-    u64 byte_offset;
-    uint32_t numel;
-    uint32_t item_index;
-    uint32_t K;
-    uint32_t k0;
-    float atol_f;
-    float rtol_f;
-    int equal_nan;
-    int dtype;
-};
+// ---- int32: same interface, exact equality ---------------------------------------------------------
+struct IntItem {
+    typedef double Hint;                // |a - b| reaches 2^32 - 1 and the quotient is binary64
+    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
+    static constexpr int E = 4;
+    uint32_t bref[kVecPerLane * 4];
+    static constexpr uint32_t poisoned_slots = 0;
 
-__device__ __noinline__ void revisit_marked(const unsigned char *ref_item, const unsigned char *const *cand, u64 byte_offset,
-                                            geak_result *recs, uint32_t *revisit, uint32_t K, uint32_t numel, int dtype,
-                                            float atol_f, float rtol_f, int equal_nan)
-{
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    for (uint32_t base = 0; base < K; base += kWaveSize) {
-        const uint32_t k_lane = base + lane;
-        bool marked = false;
-        if (k_lane < K) {
-            marked = revisit[k_lane] != 0;
-            revisit[k_lane] = 0;
-        }
-        u64 todo = __builtin_amdgcn_ballot_w64(marked);
-        while (todo) {
-            const uint32_t k = base + (uint32_t)__builtin_ctzll(todo);
-            todo &= todo - 1;
-            (void)exact_item(ref_item, table_entry(cand, k) + byte_offset, numel, dtype, atol_f, rtol_f, equal_nan, &recs[k]);
+    template <int V>
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, float, float)
+    {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
+    }
+    // Any unequal element is a mismatch and the only kind of element that can raise a maximum.
+    template <int V>
+    __device__ __forceinline__ void compare_vec(const u32x4 &q, double, double, uint32_t &suspects, u64 &trip_abs, u64 &) const
+    {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const u64 m = __builtin_amdgcn_ballot_w64(q[e] != bref[V * 4 + e]);
+            suspects += __builtin_popcountll(m);
+            trip_abs |= m;
         }
     }
-}
+    template <int V>
+    __device__ __forceinline__ uint32_t false_suspects_vec(const u32x4 &, int) const { return 0; }
+
+    template <int V>
+    __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, geak_result *rec, int lane) const
+    {
+        double dm = max_abs, rm = max_rel;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const long long a = (int)q[e], x = (int)bref[V * 4 + e];
+            const long long diff = a - x;
+            const double d = (double)(diff < 0 ? -diff : diff);          // exact
+            const double babs = (double)(x < 0 ? -x : x);
+            dm = (d > dm) ? d : dm;
+            // d/|b| > rm implies d > rm*|b|*(1 - 2^-30); the margin covers the product's rounding
+            if (d > 0.0 && (rm < (double)kInfF) && d > rm * (1.0 - 0x1p-30) * babs) {
+                const double r = d / babs;                               // binary64, correctly rounded; d/0 = +Inf
+                rm = (r > rm) ? r : rm;
+            }
+        }
+        dm = wave_max_d(dm);
+        rm = wave_max_d(rm);
+        if (lane == 0) {
+            if (dm > max_abs) atomicMax(reinterpret_cast<u64 *>(&rec->max_abs_err), __builtin_bit_cast(u64, dm));
+            if (rm > max_rel) atomicMax(reinterpret_cast<u64 *>(&rec->max_rel_err), __builtin_bit_cast(u64, rm));
+        }
+        max_abs = dm;
+        max_rel = rm;
+    }
+};
+
+template <int DT> struct ItemOf { typedef FloatItem<DT> type; };
+template <> struct ItemOf<GEAK_I32> { typedef IntItem type; };
 
 // Arguments of a device function arrive in vector registers; everything here is the same for all
 // lanes, so it is moved back to scalar registers once.
@@ -512,34 +560,15 @@ __device__ __forceinline__ T *uniform_ptr(T *p)
     const u64 lo = uniform32((uint32_t)v), hi = uniform32((uint32_t)(v >> 32));
     return reinterpret_cast<T *>(lo | (hi << 32));
 }
-__device__ __forceinline__ ItemArgs uniform_args(const ItemArgs &in)
-{
-    ItemArgs p;
-    p.ref = uniform_ptr(in.ref);
-    p.cand = uniform_ptr(in.cand);
-    p.recs = uniform_ptr(in.recs);
-    const u64 off = in.byte_offset;
-    p.byte_offset = (u64)uniform32((uint32_t)off) | ((u64)uniform32((uint32_t)(off >> 32)) << 32);
-    p.numel = uniform32(in.numel);
-    p.item_index = uniform32(in.item_index);
-    p.K = uniform32(in.K);
-    p.k0 = uniform32(in.k0);
-    p.atol_f = bits_f(uniform32(f_bits(in.atol_f)));
-    p.rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
-    p.equal_nan = (int)uniform32((uint32_t)in.equal_nan);
-    p.dtype = (int)uniform32((uint32_t)in.dtype);
-    return p;
-}
 __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 {
     WaveState st;
     st.count = uniform_ptr(in.count);
     st.first = uniform_ptr(in.first);
-    st.revisit = uniform_ptr(in.revisit);
     return st;
 }
 
-// Arguments of a run of full floating items of one wave.
+// Arguments of a run of vector-loadable items of one wave.
 struct RunArgs {
     const geak_item *items;
     const unsigned char *ref;            // buffer base
@@ -559,28 +588,34 @@ struct RunArgs {
 // registers for the same vector of the next element of the wave's stream (the next candidate, or
 // the reference slice of the wave's next item).  Four loads per lane stay in flight and each has a
 // whole element's worth of compute to land.
-template <int DT, int V>
-__device__ __forceinline__ void float_step(const FloatItem<DT> &ref, u32x4 &slot, global_vec_ptr next, bool has_next,
-                                           float &max_abs, float &max_rel, int equal_nan, geak_result *rec, int lane,
-                                           uint32_t &bad)
+template <int DT, int V, typename Item>
+__device__ __forceinline__ void stream_step(const Item &ref, u32x4 &slot, const unsigned char *next, bool has_next,
+                                            uint32_t next_n, const bool next_full, typename Item::Hint &max_abs,
+                                            typename Item::Hint &max_rel, int equal_nan, geak_result *rec, int lane,
+                                            uint32_t &bad)
 {
     constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
     u64 trip_abs = 0, trip_rel = 0;
     ref.template compare_vec<V>(slot, max_abs, max_rel, bad, trip_abs, trip_rel);
     if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_vec<V>(slot, equal_nan);
-    if (max_rel == kInfF) trip_rel = 0;                  // nothing exceeds +Inf
+    if (max_rel == (typename Item::Hint)kInfF) trip_rel = 0;       // nothing exceeds +Inf
     if (trip_abs | trip_rel) ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
-    if (has_next) slot = __builtin_nontemporal_load(next + V * kWaveSize);
+    if (has_next) slot = load_vec<DT>(next, lane, V, next_n, next_full);
 }
 
 // Each dtype's routine is a real function, so that its register allocation stands alone instead of
-// being merged with the other dtypes' inside the kernel.  It processes a whole run of consecutive
-// full items of its dtype: the wave's loads form one stream -- reference slice, K candidate slices,
-// next reference slice, ... -- that never drains at an item boundary.  Returns the index of the
-// wave's first item it did not process.
-template <int DT>
-__device__ __noinline__ uint32_t process_full_run(const RunArgs in, const WaveState st_in)
+// being merged with the other dtypes' inside the kernel.
+//   TAIL = false: a whole run of consecutive FULL items of the dtype.  The wave's loads form one
+//     stream -- reference slice, K candidate slices, next reference slice, ... -- that never
+//     drains at an item boundary, and every load is an unguarded 16-byte vector load.
+//   TAIL = true: exactly one item that starts aligned but is shorter than a full item (the end of a
+//     segment), with guarded loads.
+// Returns the index of the wave's first item it did not process.
+template <int DT, bool TAIL>
+__device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState st_in)
 {
+    typedef typename ItemOf<DT>::type Item;
+    typedef typename Item::Hint Hint;
     const WaveState st = uniform_state(st_in);
     const geak_item *items = uniform_ptr(in.items);
     const unsigned char *ref_base = uniform_ptr(in.ref);
@@ -594,14 +629,17 @@ __device__ __noinline__ uint32_t process_full_run(const RunArgs in, const WaveSt
 
     uint32_t j = uniform32(in.first_item);
     geak_item it = load_work_item(items, j);
-    FloatItem<DT> ref;
+    Item ref;
     u32x4 cur[kVecPerLane];
-    load_full(cur, ref_base + it.byte_offset, lane);     // the only load of the run that nothing hides
+    constexpr bool full = !TAIL;
+#pragma unroll
+    for (int v = 0; v < kVecPerLane; ++v)                  // the only loads of the run that nothing hides
+        cur[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, it.numel, full);
 
     for (;;) {
         // look ahead: does the wave's next item continue the run?
         const uint32_t jn = j + kWavesPerBlock;
-        bool more = jn < block_end;
+        bool more = !TAIL && jn < block_end;
         geak_item nx = it;
         if (more) {
             nx = load_work_item(items, jn);
@@ -613,11 +651,11 @@ __device__ __noinline__ uint32_t process_full_run(const RunArgs in, const WaveSt
         // reference element: stage it, refilling each vector with the first candidate's
         uint32_t k = k0;
         {
-            global_vec_ptr first = (global_vec_ptr)(table_entry(cand, k) + it.byte_offset) + lane;
-            ref.template stage_vec<0>(cur[0], atol_f, rtol_f); cur[0] = __builtin_nontemporal_load(first + 0 * kWaveSize);
-            ref.template stage_vec<1>(cur[1], atol_f, rtol_f); cur[1] = __builtin_nontemporal_load(first + 1 * kWaveSize);
-            ref.template stage_vec<2>(cur[2], atol_f, rtol_f); cur[2] = __builtin_nontemporal_load(first + 2 * kWaveSize);
-            ref.template stage_vec<3>(cur[3], atol_f, rtol_f); cur[3] = __builtin_nontemporal_load(first + 3 * kWaveSize);
+            const unsigned char *first = table_entry(cand, k) + it.byte_offset;
+            ref.template stage_vec<0>(cur[0], atol_f, rtol_f); cur[0] = load_vec<DT>(first, lane, 0, it.numel, full);
+            ref.template stage_vec<1>(cur[1], atol_f, rtol_f); cur[1] = load_vec<DT>(first, lane, 1, it.numel, full);
+            ref.template stage_vec<2>(cur[2], atol_f, rtol_f); cur[2] = load_vec<DT>(first, lane, 2, it.numel, full);
+            ref.template stage_vec<3>(cur[3], atol_f, rtol_f); cur[3] = load_vec<DT>(first, lane, 3, it.numel, full);
         }
         u64 abs_bits = load_bits(&recs[k].max_abs_err), rel_bits = load_bits(&recs[k].max_rel_err);
 
@@ -625,20 +663,20 @@ __device__ __noinline__ uint32_t process_full_run(const RunArgs in, const WaveSt
             const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
             const bool last = step + 1 == K;
             const bool has_next = !last || more;
-            const unsigned char *next_base = last ? ref_base + nx.byte_offset : table_entry(cand, kn) + it.byte_offset;
-            global_vec_ptr next = (global_vec_ptr)next_base + lane;
+            const unsigned char *next = last ? ref_base + nx.byte_offset : table_entry(cand, kn) + it.byte_offset;
+            const uint32_t next_n = last ? nx.numel : it.numel;
 
-            float max_abs = (float)__builtin_bit_cast(double, abs_bits);   // exact: published from binary32
-            float max_rel = (float)__builtin_bit_cast(double, rel_bits);
+            Hint max_abs = Item::hint_from_bits(abs_bits);      // exact: floating maxima are published from binary32
+            Hint max_rel = Item::hint_from_bits(rel_bits);
             if (!last) {
                 abs_bits = load_bits(&recs[kn].max_abs_err);
                 rel_bits = load_bits(&recs[kn].max_rel_err);
             }
             uint32_t bad = 0;
-            float_step<DT, 0>(ref, cur[0], next, has_next, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
-            float_step<DT, 1>(ref, cur[1], next, has_next, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
-            float_step<DT, 2>(ref, cur[2], next, has_next, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
-            float_step<DT, 3>(ref, cur[3], next, has_next, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            stream_step<DT, 0>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            stream_step<DT, 1>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            stream_step<DT, 2>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            stream_step<DT, 3>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
             note_mismatches(st, k, bad, j, lane);
             k = kn;
         }
@@ -650,48 +688,16 @@ __device__ __noinline__ uint32_t process_full_run(const RunArgs in, const WaveSt
     return j + kWavesPerBlock;
 }
 
-// ---- full items, int32 -----------------------------------------------------------------------------
-__device__ __noinline__ void process_full_int(const ItemArgs in, const WaveState st_in)
+// ---- items that do not start on a 16-byte boundary (a segment's first few elements) ---------------
+__device__ __forceinline__ void process_head(const geak_item &it, uint32_t item_index, const CompareArgs &p,
+                                             const WaveState &st, int lane)
 {
-    constexpr int E = 4;
-    const ItemArgs p = uniform_args(in);
-    const WaveState st = uniform_state(st_in);
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const uint32_t K = p.K;
-    u32x4 b[kVecPerLane];
-    load_full(b, p.ref + p.byte_offset, lane);
-    u32x4 cur[kVecPerLane];
-    uint32_t k = p.k0;
-    load_full(cur, table_entry(p.cand, k) + p.byte_offset, lane);
-    bool any_revisit = false;
-    for (uint32_t step = 0; step < K; ++step) {
-        const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
-        const bool has_next = step + 1 < K;
-        global_vec_ptr next = (global_vec_ptr)(table_entry(p.cand, kn) + p.byte_offset) + lane;
-        uint32_t bad = 0;
-#pragma unroll
-        for (int v = 0; v < kVecPerLane; ++v) {
-#pragma unroll
-            for (int e = 0; e < E; ++e)
-                bad += __builtin_popcountll(__builtin_amdgcn_ballot_w64(cur[v][e] != b[v][e]));
-            if (has_next) cur[v] = __builtin_nontemporal_load(next + v * kWaveSize);
-        }
-        note_mismatches(st, k, bad, p.item_index, lane);
-        if (bad) { mark_revisit(st, k, lane); any_revisit = true; }   // equal elements contribute nothing to either maximum
-        k = kn;
-    }
-    if (any_revisit)
-        revisit_marked(p.ref + p.byte_offset, p.cand, p.byte_offset, p.recs, st.revisit, K, p.numel, p.dtype, p.atol_f, p.rtol_f,
-                       p.equal_nan);
-}
-
-// ---- partial items (segment heads and tails) -------------------------------------------------------
-__device__ __forceinline__ void process_partial(const ItemArgs &p, const WaveState &st, int lane)
-{
-    for (uint32_t k = 0; k < p.K; ++k) {
-        const uint32_t bad = exact_item(p.ref + p.byte_offset, table_entry(p.cand, k) + p.byte_offset, p.numel, p.dtype,
-                                        p.atol_f, p.rtol_f, p.equal_nan, &p.recs[k]);
-        note_mismatches(st, k, bad, p.item_index, lane);
+    const uint32_t K = p.num_candidates;
+    geak_result *recs = p.results + (u64)it.segment * K;
+    for (uint32_t k = 0; k < K; ++k) {
+        const uint32_t bad = exact_item(p.ref + it.byte_offset, table_entry(p.cand_table, k) + it.byte_offset, it.numel,
+                                        it.dtype, p.atol_f, p.rtol_f, p.equal_nan, &recs[k]);
+        note_mismatches(st, k, bad, item_index, lane);
     }
 }
 
@@ -704,20 +710,10 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     WaveState st;
     st.count = reinterpret_cast<u64 *>(lds) + (size_t)wave * K;
     st.first = reinterpret_cast<uint32_t *>(lds + sizeof(u64) * kWavesPerBlock * K) + (size_t)wave * K;
-    st.revisit = reinterpret_cast<uint32_t *>(lds + (sizeof(u64) + sizeof(uint32_t)) * kWavesPerBlock * K) + (size_t)wave * K;
-    for (uint32_t k = lane; k < K; k += kWaveSize) st.revisit[k] = 0;
 
     const uint32_t block_begin = blockIdx.x * p.items_per_block;
     if (block_begin >= p.num_items) return;              // the planner launches no such block; never index past the table
     const uint32_t block_end = (p.num_items - block_begin < p.items_per_block) ? p.num_items : block_begin + p.items_per_block;
-    ItemArgs a;
-    a.ref = p.ref;
-    a.cand = p.cand_table;
-    a.K = K;
-    a.k0 = blockIdx.x % K;
-    a.atol_f = p.atol_f;
-    a.rtol_f = p.rtol_f;
-    a.equal_nan = p.equal_nan;
     RunArgs r;
     r.items = p.items;
     r.ref = p.ref;
@@ -726,7 +722,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.partials = p.partials;
     r.block_end = block_end;
     r.K = K;
-    r.k0 = a.k0;
+    r.k0 = blockIdx.x % K;
     r.atol_f = p.atol_f;
     r.rtol_f = p.rtol_f;
     r.equal_nan = p.equal_nan;
@@ -734,26 +730,30 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     uint32_t j = block_begin + wave;
     while (j < block_end) {
         const geak_item it = load_work_item(p.items, j);
-        if ((it.flags & GEAK_ITEM_FULL) && it.dtype != GEAK_I32) {
-            // a run of full floating items: handled, state bookkeeping included, by the dtype's routine
+        if (it.flags & GEAK_ITEM_ALIGNED) {
+            // a run of vector-loadable items: handled, state bookkeeping included, by the dtype's routine
             r.first_item = j;
             uint32_t next_j;
-            switch (it.dtype) {
-            case GEAK_F32:  next_j = process_full_run<GEAK_F32>(r, st); break;
-            case GEAK_F16:  next_j = process_full_run<GEAK_F16>(r, st); break;
-            default:        next_j = process_full_run<GEAK_BF16>(r, st); break;
+            if (it.flags & GEAK_ITEM_FULL) {
+                switch (it.dtype) {
+                case GEAK_F32:  next_j = process_run<GEAK_F32, false>(r, st); break;
+                case GEAK_F16:  next_j = process_run<GEAK_F16, false>(r, st); break;
+                case GEAK_BF16: next_j = process_run<GEAK_BF16, false>(r, st); break;
+                default:        next_j = process_run<GEAK_I32, false>(r, st); break;
+                }
+            } else {
+                switch (it.dtype) {
+                case GEAK_F32:  next_j = process_run<GEAK_F32, true>(r, st); break;
+                case GEAK_F16:  next_j = process_run<GEAK_F16, true>(r, st); break;
+                case GEAK_BF16: next_j = process_run<GEAK_BF16, true>(r, st); break;
+                default:        next_j = process_run<GEAK_I32, true>(r, st); break;
+                }
             }
             j = __builtin_amdgcn_readfirstlane(next_j);
             continue;
         }
         if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
-        a.recs = p.results + (u64)it.segment * K;
-        a.byte_offset = it.byte_offset;
-        a.numel = it.numel;
-        a.item_index = j;
-        a.dtype = it.dtype;
-        if (it.flags & GEAK_ITEM_FULL) process_full_int(a, st);
-        else process_partial(a, st, lane);
+        process_head(it, j, p, st, lane);
         if (it.flags & GEAK_ITEM_LAST) end_run(st, p.partials, it.slot, K, lane);
         j += kWavesPerBlock;
     }

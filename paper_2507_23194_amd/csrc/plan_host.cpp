@@ -100,7 +100,7 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
                 it.segment = (uint32_t)s;
                 it.numel = (uint32_t)n;
                 it.dtype = (uint8_t)g.dtype;
-                it.flags = full ? GEAK_ITEM_FULL : 0;
+                it.flags = (uint8_t)((full ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0));
                 hp.items.push_back(it);
                 done += n;
             };

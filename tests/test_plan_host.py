@@ -130,6 +130,9 @@ def _check_table(segs, K):
             assert 1 <= it["numel"] <= info.item_bytes // w
             if it["flags"] & B.GEAK_ITEM_FULL:
                 assert it["byte_offset"] % 16 == 0 and it["numel"] * w == info.item_bytes
+            assert bool(it["flags"] & B.GEAK_ITEM_ALIGNED) == (it["byte_offset"] % 16 == 0)
+            if not it["flags"] & B.GEAK_ITEM_ALIGNED:        # an unaligned head never reaches a 16-byte boundary
+                assert it["elem_start"] == 0 and it["numel"] * w < 16
             cursor[s] = cursor.get(s, 0) + int(it["numel"])
         for s, (off, n, dt) in enumerate(segs):
             assert cursor.get(s, 0) == n
