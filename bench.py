@@ -72,12 +72,26 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per compare launch from rocprofv3 counters (reported as roofline.traffic)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain element-wise copy of a known size (2 GiB read, 2 GiB written per launch), "
+                         "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
     import numpy as np
     import torch
+
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        src = torch.ones(1 << 29, dtype=torch.float32, device="cuda:0")       # 2 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)                                       # one element-wise kernel: reads src, writes dst
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "torch.mul(src, 1.0, out=dst)", "bytes_read": src.numel() * 4,
+                          "bytes_written": dst.numel() * 4, "launches": 5}))
+        return
     from paper_2507_23194_amd import binding as B
     from paper_2507_23194_amd import synth
 

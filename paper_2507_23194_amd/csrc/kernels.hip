@@ -27,7 +27,7 @@
 //     compact element-wise path that applies the full rule straight from memory.
 //   * first_mismatch: the wave only remembers the first of its items that holds a mismatch; the
 //     reduce kernel re-reads that one item and finds the exact index.
-// reduce kernel -- one wavefront per (segment, candidate): sums counts over the segment's slots,
+// reduce kernel -- one block per (segment, candidate): sums counts over the segment's slots,
 //   takes the least item index, rescans that item with the full rule, writes pass/count/first.
 //
 // Blocks of the compare kernel start at different candidates (k0 = block % K) so that the first,
@@ -776,7 +776,7 @@ __global__ void init_kernel(const InitArgs p)
     if (p.cand_table && i < p.num_candidates) p.cand_table[i] = p.cand[i];
 }
 
-// ---- reduce: one wavefront per (segment, candidate) ----------------------------------------------
+// ---- reduce: one block per (segment, candidate) ----------------------------------------------
 __device__ __forceinline__ bool element_close(const unsigned char *ref, const unsigned char *cand, uint32_t idx,
                                               int dtype, float atol_f, float rtol_f, int equal_nan)
 {
@@ -785,37 +785,77 @@ __device__ __forceinline__ bool element_close(const unsigned char *ref, const un
     return close_exact(load_elem_f(cand, idx, dtype), load_elem_f(ref, idx, dtype), atol_f, rtol_f, equal_nan);
 }
 
-__global__ __launch_bounds__(kWaveSize) void reduce_kernel(const ReduceArgs p)
+constexpr int kReduceThreads = 256;
+
+__global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs p)
 {
+    __shared__ u64 s_count[kReduceThreads / kWaveSize];
+    __shared__ uint32_t s_first[kReduceThreads / kWaveSize];
+    __shared__ uint32_t s_best[kReduceThreads / kWaveSize];
     const uint32_t K = p.num_candidates;
     const uint32_t seg = blockIdx.x / K, k = blockIdx.x % K;
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWaveSize - 1), wave = tid / kWaveSize;
     const uint32_t sb = p.slot_begin[seg], se = p.slot_begin[seg + 1];
-    if (sb == se) return;                       // empty segment: the neutral record stands
+    if (sb == se) return;                       // empty segment: the neutral record stands (uniform exit)
 
+    // sum of the counts and least first-item index over the segment's slots; eight independent loads
+    // per thread are in flight at a time
     u64 count = 0;
     uint32_t first_item = kNoItem;
-    for (uint32_t s = sb + lane; s < se; s += kWaveSize) {
-        const Partial r = p.partials[(u64)s * K + k];
-        count += r.count;
-        first_item = r.first_item < first_item ? r.first_item : first_item;
+    for (uint32_t s0 = sb + tid; s0 < se; s0 += 8 * kReduceThreads) {
+        Partial r[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t s = s0 + u * kReduceThreads;
+            r[u].count = 0;
+            r[u].first_item = kNoItem;
+            if (s < se) r[u] = p.partials[(u64)s * K + k];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            count += r[u].count;
+            first_item = r[u].first_item < first_item ? r[u].first_item : first_item;
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) count += (u64)__shfl_xor((long long)count, o, kWaveSize);
     first_item = wave_min_u(first_item);
+    if (lane == 0) { s_count[wave] = count; s_first[wave] = first_item; }
+    __syncthreads();
+    count = 0;
+    first_item = kNoItem;
+#pragma unroll
+    for (int w = 0; w < kReduceThreads / kWaveSize; ++w) {
+        count += s_count[w];
+        first_item = s_first[w] < first_item ? s_first[w] : first_item;
+    }
 
+    // exact first index: re-read the first item that holds a mismatch, every thread checking the
+    // elements tid, tid + 256, ... (all of a thread's loads are in flight together)
     long long first = -1;
-    if (first_item != kNoItem) {
+    if (first_item != kNoItem) {                // uniform: every thread holds the same first_item
         const geak_item it = p.items[first_item];
         const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
-        uint32_t best = kNoItem;
-        for (uint32_t i = lane; i < it.numel; i += kWaveSize) {
-            if (!element_close(rb, cb, i, it.dtype, p.atol_f, p.rtol_f, p.equal_nan)) { best = i; break; }
+        constexpr int kPer = (kItemBytes / 2 + kReduceThreads - 1) / kReduceThreads;   // 8: most elements a thread can own
+        bool bad[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const uint32_t i = (uint32_t)tid + u * kReduceThreads;
+            bad[u] = (i < it.numel) && !element_close(rb, cb, i, it.dtype, p.atol_f, p.rtol_f, p.equal_nan);
         }
+        uint32_t best = kNoItem;
+#pragma unroll
+        for (int u = kPer - 1; u >= 0; --u)
+            if (bad[u]) best = (uint32_t)tid + u * kReduceThreads;
         best = wave_min_u(best);
+        if (lane == 0) s_best[wave] = best;
+        __syncthreads();
+        best = kNoItem;
+#pragma unroll
+        for (int w = 0; w < kReduceThreads / kWaveSize; ++w) best = s_best[w] < best ? s_best[w] : best;
         first = (long long)it.elem_start + (long long)best;
     }
-    if (lane == 0) {
+    if (tid == 0) {
         geak_result *rec = p.results + (u64)seg * K + k;
         rec->pass = (count == 0);
         rec->mismatch_count = count;
@@ -846,7 +886,7 @@ int launch_reduce(const ReduceArgs &args, void *stream)
 {
     const uint64_t pairs = (uint64_t)args.num_segments * args.num_candidates;
     if (!pairs) return (int)hipSuccess;
-    hipLaunchKernelGGL(reduce_kernel, dim3((uint32_t)pairs), dim3(kWaveSize), 0, (hipStream_t)stream, args);
+    hipLaunchKernelGGL(reduce_kernel, dim3((uint32_t)pairs), dim3(kReduceThreads), 0, (hipStream_t)stream, args);
     return (int)hipGetLastError();
 }
 
