@@ -141,9 +141,7 @@ typedef struct {
     uint32_t lds_bytes;          /* dynamic LDS per block */
     uint32_t item_bytes;         /* bytes of one full work item per tensor */
     int32_t  device;
-    uint32_t items_per_block;    /* block b owns items [b * items_per_block, (b + 1) * items_per_block); wave w of
-                                    the block takes every (block_threads / 64)-th of them, starting at w */
-    uint32_t reserved;
+    uint32_t reserved[2];
 } geak_plan_info;
 
 /* One work item, as the compare kernel sees it. */
@@ -164,6 +162,11 @@ typedef struct {
 #define GEAK_ITEM_ALIGNED 8u /* 16-byte aligned start (FULL implies it): vector loads, guarded at the end */
 
 geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
+
+/* Copies up to `capacity` entries of the block table into `out` (host); returns its length,
+ * grid_blocks + 1.  Block b of the compare kernel owns items [table[b], table[b + 1]); wave w of the
+ * block takes every (block_threads / 64)-th of them, starting at w. */
+uint64_t geak_check_plan_blocks(const geak_plan *plan, uint32_t *out, uint64_t capacity);
 
 /* Copies up to `capacity` items into `out` (host); returns the total number of items. */
 uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t capacity);

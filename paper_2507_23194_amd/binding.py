@@ -39,7 +39,7 @@ class PlanInfo(ctypes.Structure):
                 ("algorithmic_bytes", ctypes.c_uint64), ("num_candidates", ctypes.c_uint32),
                 ("grid_blocks", ctypes.c_uint32), ("block_threads", ctypes.c_uint32), ("lds_bytes", ctypes.c_uint32),
                 ("item_bytes", ctypes.c_uint32), ("device", ctypes.c_int32),
-                ("items_per_block", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("reserved", ctypes.c_uint32 * 2)]
 
 
 class GeakError(RuntimeError):
@@ -86,6 +86,8 @@ def library() -> ctypes.CDLL:
         lib.geak_status_string.argtypes = [ctypes.c_int]
         lib.geak_check_plan_info.restype = ctypes.c_int
         lib.geak_check_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+        lib.geak_check_plan_blocks.restype = u64
+        lib.geak_check_plan_blocks.argtypes = [vp, vp, u64]
         lib.geak_check_plan_items.restype = u64
         lib.geak_check_plan_items.argtypes = [vp, vp, u64]
         lib.geak_check_profile_enable.restype = ctypes.c_int
@@ -98,7 +100,7 @@ def library() -> ctypes.CDLL:
 
 EXPORTED = ["geak_check_plan", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
-            "geak_check_plan_items", "geak_check_profile_enable", "geak_check_profile_read"]
+            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_profile_enable", "geak_check_profile_read"]
 
 
 # ---- one Python function per C entry point -------------------------------------------------------
@@ -163,6 +165,14 @@ def geak_check_plan_items(plan) -> np.ndarray:
     out = np.zeros(n, dtype=ITEM_DTYPE)
     if n:
         library().geak_check_plan_items(plan, out.ctypes.data, n)
+    return out
+
+
+def geak_check_plan_blocks(plan) -> np.ndarray:
+    n = int(library().geak_check_plan_blocks(plan, None, 0))
+    out = np.zeros(n, dtype=np.uint32)
+    if n:
+        library().geak_check_plan_blocks(plan, out.ctypes.data, n)
     return out
 
 

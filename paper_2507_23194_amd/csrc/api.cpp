@@ -13,6 +13,7 @@ struct geak_plan {
     // device copies of the work table
     geak_item *items_dev = nullptr;
     uint32_t *slot_begin_dev = nullptr;
+    uint32_t *block_first_dev = nullptr;
     // optional timing ring
     std::vector<hipEvent_t> ev_start, ev_stop;
     uint32_t ev_next = 0, ev_used = 0;
@@ -39,10 +40,12 @@ void free_device_side(geak_plan *p)
     DeviceGuard g(p->device);
     if (p->items_dev) (void)hipFree(p->items_dev);
     if (p->slot_begin_dev) (void)hipFree(p->slot_begin_dev);
+    if (p->block_first_dev) (void)hipFree(p->block_first_dev);
     for (auto e : p->ev_start) (void)hipEventDestroy(e);
     for (auto e : p->ev_stop) (void)hipEventDestroy(e);
     p->items_dev = nullptr;
     p->slot_begin_dev = nullptr;
+    p->block_first_dev = nullptr;
     p->ev_start.clear();
     p->ev_stop.clear();
 }
@@ -85,10 +88,13 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
         const size_t slot_bytes = p->host.slot_begin.size() * sizeof(uint32_t);
         bool ok = g.ok;
         if (ok && item_bytes) ok = hipMalloc((void **)&p->items_dev, item_bytes) == hipSuccess;
+        const size_t block_bytes = p->host.block_first.size() * sizeof(uint32_t);
         if (ok) ok = hipMalloc((void **)&p->slot_begin_dev, slot_bytes) == hipSuccess;
+        if (ok) ok = hipMalloc((void **)&p->block_first_dev, block_bytes) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_ENOMEM; }
         if (item_bytes) ok = hipMemcpy(p->items_dev, p->host.items.data(), item_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->slot_begin_dev, p->host.slot_begin.data(), slot_bytes, hipMemcpyHostToDevice) == hipSuccess;
+        if (ok) ok = hipMemcpy(p->block_first_dev, p->host.block_first.data(), block_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_EHIP; }
     }
     *out = p;
@@ -179,7 +185,8 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.atol_f = hp.atol_f;
         ca.rtol_f = hp.rtol_f;
         ca.equal_nan = hp.equal_nan;
-        ca.items_per_block = hp.items_per_block;
+        ca.reserved = 0;
+        ca.block_first = plan->block_first_dev;
 
         geak_plan *mp = const_cast<geak_plan *>(plan);      // timing ring only; documented as not re-entrant
         const bool timed = !mp->ev_start.empty();
@@ -242,12 +249,22 @@ geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out)
     out->algorithmic_bytes = hp.algorithmic_bytes;
     out->num_candidates = (uint32_t)hp.num_candidates;
     out->grid_blocks = hp.grid_blocks;
-    out->items_per_block = hp.items_per_block;
     out->block_threads = kBlockThreads;
     out->lds_bytes = plan->lds_bytes;
     out->item_bytes = kItemBytes;
     out->device = plan->device;
     return GEAK_OK;
+}
+
+uint64_t geak_check_plan_blocks(const geak_plan *plan, uint32_t *out, uint64_t capacity)
+{
+    if (!plan) return 0;
+    const auto &bf = plan->host.block_first;
+    if (out) {
+        const uint64_t n = capacity < bf.size() ? capacity : bf.size();
+        if (n) std::memcpy(out, bf.data(), n * sizeof(uint32_t));
+    }
+    return bf.size();
 }
 
 uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t capacity)

@@ -39,7 +39,7 @@ struct HostPlan {
     float atol_f = 0.f, rtol_f = 0.f;
     int equal_nan = 0;
     uint32_t grid_blocks = 1;
-    uint32_t items_per_block = 1;          // block b owns items [b * items_per_block, (b + 1) * items_per_block)
+    std::vector<uint32_t> block_first;     // size grid_blocks + 1: block b owns items [block_first[b], block_first[b + 1])
     uint32_t max_blocks = 1;               // compute units x resident blocks per unit
 };
 
@@ -72,7 +72,8 @@ struct CompareArgs {
     float atol_f;
     float rtol_f;
     int equal_nan;
-    uint32_t items_per_block;
+    int reserved;
+    const uint32_t *block_first;         // grid_blocks + 1 entries
 };
 
 struct ReduceArgs {

@@ -711,9 +711,10 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     st.count = reinterpret_cast<u64 *>(lds) + (size_t)wave * K;
     st.first = reinterpret_cast<uint32_t *>(lds + sizeof(u64) * kWavesPerBlock * K) + (size_t)wave * K;
 
-    const uint32_t block_begin = blockIdx.x * p.items_per_block;
-    if (block_begin >= p.num_items) return;              // the planner launches no such block; never index past the table
-    const uint32_t block_end = (p.num_items - block_begin < p.items_per_block) ? p.num_items : block_begin + p.items_per_block;
+    const GEAK_AS_CONSTANT uint32_t *block_first = (const GEAK_AS_CONSTANT uint32_t *)p.block_first;
+    const uint32_t block_begin = block_first[blockIdx.x];
+    uint32_t block_end = block_first[blockIdx.x + 1];
+    if (block_end > p.num_items) block_end = p.num_items;    // never index past the table
     RunArgs r;
     r.items = p.items;
     r.ref = p.ref;

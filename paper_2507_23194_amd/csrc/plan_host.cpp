@@ -77,17 +77,6 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
         hp.algorithmic_bytes = total_bytes * ((uint64_t)num_candidates + 1);
         hp.max_blocks = max_blocks;
 
-        const uint64_t blocks_wanted = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
-        hp.grid_blocks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
-        // Block b owns the contiguous item range [b * items_per_block, (b + 1) * items_per_block); its
-        // four waves interleave inside it (wave w takes every fourth item starting at w).  A wave's
-        // consecutive items are then neighbours in memory and mostly of one segment, so the running
-        // maxima it has just raised are the right thresholds for its next item.
-        hp.items_per_block = (uint32_t)((n_items + hp.grid_blocks - 1) / hp.grid_blocks);
-        if (hp.items_per_block == 0) hp.items_per_block = 1;
-        // no block may start past the end of the table
-        hp.grid_blocks = (uint32_t)std::max<uint64_t>(1, (n_items + hp.items_per_block - 1) / hp.items_per_block);
-
         for (uint64_t s = 0; s < nsegs; ++s) {
             const geak_segment &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
@@ -110,6 +99,42 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
             if (g.numel - done) push(g.numel - done, false);
         }
 
+        // Partition of the table over the persistent grid.  Block b owns the contiguous item range
+        // [block_first[b], block_first[b + 1]); its four waves interleave inside it (wave w takes every
+        // fourth item starting at w).  A wave's consecutive items are then neighbours in memory and
+        // mostly of one segment, so the running maxima it has just raised are the right thresholds
+        // for its next item.  Ranges are cut at equal estimated cost, not equal item count: a wave is
+        // latency-bound per 4 KiB slice whatever its length, so an item costs about one unit per slice
+        // it streams (reference + K candidates), a short tail no less than a full item, and a run
+        // that has to start afresh (new segment, tail, head) pays for an empty pipeline.
+        const uint64_t blocks_wanted = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+        const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
+        const uint64_t slices = (uint64_t)num_candidates + 1;
+        auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
+            uint64_t c = slices;
+            if (!(it.flags & GEAK_ITEM_ALIGNED)) c = 2 * slices;       // element-wise path, two dependent loads per candidate
+            if (starts_run || !(it.flags & GEAK_ITEM_FULL)) c += 2;    // pipeline refill
+            return c;
+        };
+        uint64_t total_cost = 0;
+        for (uint64_t j = 0; j < hp.items.size(); ++j)
+            total_cost += item_cost(hp.items[j], j == 0 || hp.items[j - 1].segment != hp.items[j].segment);
+        hp.block_first.clear();
+        hp.block_first.push_back(0);
+        {
+            uint64_t acc = 0;
+            for (uint64_t j = 0; j < hp.items.size(); ++j) {
+                // close the current block before item j once its share of the total cost is reached
+                const uint64_t b = hp.block_first.size();          // blocks opened so far (1-based index of the current one)
+                if (b < target_blocks && j > hp.block_first.back() && acc * target_blocks >= total_cost * b)
+                    hp.block_first.push_back((uint32_t)j);
+                acc += item_cost(hp.items[j], j == 0 || hp.items[j - 1].segment != hp.items[j].segment);
+            }
+        }
+        hp.block_first.push_back((uint32_t)hp.items.size());
+        hp.grid_blocks = (uint32_t)(hp.block_first.size() - 1);    // >= 1; the last entry closes the last block
+        if (hp.items.empty()) hp.grid_blocks = 1;
+
         // Runs and slots.  Scanning the table in order, a wave opens a new run (and a new slot)
         // whenever the segment of its next item differs from the segment of its previous one.
         // Items of one segment are contiguous in the table, so the slots opened while scanning a
@@ -118,11 +143,12 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
         std::vector<uint32_t> run_segment(workers, 0xFFFFFFFFu), run_slot(workers, 0), last_item(workers, kNoItem);
         uint64_t slot_cursor = 0;
         uint64_t seg_cursor = 0;
+        uint64_t block = 0;
         for (uint64_t j = 0; j < hp.items.size(); ++j) {
             geak_item &it = hp.items[j];
             while (seg_cursor <= it.segment) hp.slot_begin[seg_cursor++] = (uint32_t)slot_cursor;
-            const uint64_t block = j / hp.items_per_block;
-            const uint64_t worker = block * kWavesPerBlock + (j - block * hp.items_per_block) % kWavesPerBlock;
+            while (j >= hp.block_first[block + 1]) ++block;
+            const uint64_t worker = block * kWavesPerBlock + (j - hp.block_first[block]) % kWavesPerBlock;
             if (run_segment[worker] != it.segment) {
                 if (last_item[worker] != kNoItem) hp.items[last_item[worker]].flags |= GEAK_ITEM_LAST;
                 run_segment[worker] = it.segment;

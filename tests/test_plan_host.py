@@ -114,8 +114,9 @@ def _check_table(segs, K):
         items = B.geak_check_plan_items(plan)
         assert len(items) == info.num_items
         waves = info.block_threads // 64
-        ipb = info.items_per_block
-        assert ipb * info.grid_blocks >= len(items) and ipb * (info.grid_blocks - 1) < max(1, len(items))
+        blocks = B.geak_check_plan_blocks(plan).astype(np.int64)
+        assert len(blocks) == info.grid_blocks + 1 and blocks[0] == 0 and blocks[-1] == len(items)
+        assert (np.diff(blocks) > 0).all() or len(items) == 0          # no empty block, nothing past the table
         esize = {0: 4, 1: 2, 2: 2, 3: 4}
         # every element of every segment is covered exactly once, in order
         cursor = {}
@@ -142,7 +143,7 @@ def _check_table(segs, K):
         # run structure: following one worker through the table, FIRST opens and LAST closes each
         # (worker, segment) run, the slot is constant inside a run and unique to it
         seen_slots = {}
-        sequences = [items[b * ipb:(b + 1) * ipb][w::waves] for b in range(info.grid_blocks) for w in range(waves)]
+        sequences = [items[blocks[b]:blocks[b + 1]][w::waves] for b in range(info.grid_blocks) for w in range(waves)]
         assert sum(len(m) for m in sequences) == len(items)
         for mine in sequences:
             open_slot = None
@@ -209,7 +210,9 @@ def test_work_table_many_segments_uneven_blocks(lib):
     st, plan = _plan(segs, K=4)
     info = B.geak_check_plan_info(plan)
     assert info.num_items % info.grid_blocks != 0
-    assert (info.grid_blocks - 1) * info.items_per_block < info.num_items <= info.grid_blocks * info.items_per_block
+    # ranges are cut at equal estimated cost: blocks of tails hold fewer items than blocks of full items
+    sizes = np.diff(B.geak_check_plan_blocks(plan).astype(np.int64))
+    assert sizes.min() >= 1 and sizes.max() > sizes.min()
     B.geak_check_destroy(plan)
 
 
@@ -220,4 +223,6 @@ def test_work_table_persistent_grid(lib):
     assert info.num_items == (1 << 28) // info.item_bytes
     assert info.grid_blocks == 256 * 4                   # host-only plans assume 256 compute units
     assert info.num_slots == info.grid_blocks * 4
+    sizes = np.diff(B.geak_check_plan_blocks(plan).astype(np.int64))
+    assert sizes.max() - sizes.min() <= 1                # a dense tensor splits evenly
     B.geak_check_destroy(plan)
