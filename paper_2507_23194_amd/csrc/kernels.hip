@@ -51,6 +51,7 @@ constexpr float kInfF = __builtin_huge_valf();
 // tensor data is read through the global address space (no flat instructions).
 #define GEAK_AS_GLOBAL   __attribute__((address_space(1)))
 #define GEAK_AS_CONSTANT __attribute__((address_space(4)))
+#define GEAK_AS_LDS      __attribute__((address_space(3)))
 typedef const GEAK_AS_GLOBAL u32x4 *global_vec_ptr;
 
 // A work item read with scalar loads (four 64-bit words; layout of geak_item).
@@ -187,12 +188,17 @@ __device__ __forceinline__ uint32_t wave_min_u(uint32_t x)
 // itself and are raised with an unsigned 64-bit atomic max.
 __device__ __forceinline__ u64 load_bits(const double *p)
 {
-    return __hip_atomic_load(reinterpret_cast<const u64 *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // through the global address space: a flat load would also count against the LDS / scalar-load
+    // counter, and the next wait for a scalar load would then wait for this one as well
+    return __hip_atomic_load((const GEAK_AS_GLOBAL u64 *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_max(double *p, double v)
+{
+    (void)__hip_atomic_fetch_max((GEAK_AS_GLOBAL u64 *)p, __builtin_bit_cast(u64, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void raise_max(double *p, double v, u64 seen_bits)
 {
-    const u64 bits = __builtin_bit_cast(u64, v);
-    if (bits > seen_bits) atomicMax(reinterpret_cast<u64 *>(p), bits);
+    if (__builtin_bit_cast(u64, v) > seen_bits) publish_max(p, v);
 }
 
 // The full rule for one floating element.
@@ -281,31 +287,38 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
 
 // ---- per-(wave, candidate) running state in LDS ----------------------------------------------
 struct WaveState {
-    u64 *count;          // [K] mismatching elements of the current (worker, segment) run
-    uint32_t *first;     // [K] least item index of the run that holds a mismatch
+    uint32_t count_off;  // LDS byte offset of u64[K]: mismatching elements of the current (worker, segment) run
+    uint32_t first_off;  // LDS byte offset of u32[K]: least item index of the run that holds a mismatch
 };
+// The state is addressed through the LDS address space (DS instructions), never through flat ones.
+__device__ __forceinline__ GEAK_AS_LDS u64 *state_count(const WaveState &st) { return (GEAK_AS_LDS u64 *)st.count_off; }
+__device__ __forceinline__ GEAK_AS_LDS uint32_t *state_first(const WaveState &st) { return (GEAK_AS_LDS uint32_t *)st.first_off; }
 
 __device__ __forceinline__ void note_mismatches(const WaveState &st, uint32_t k, uint32_t n, uint32_t item, int lane)
 {
     if (n && lane == 0) {
-        atomicAdd(&st.count[k], (u64)n);
-        atomicMin(&st.first[k], item);
+        (void)__hip_atomic_fetch_add(state_count(st) + k, (u64)n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        (void)__hip_atomic_fetch_min(state_first(st) + k, item, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 }
 
 // A (worker, segment) run begins: clear the wave's running state.  It ends: write it to the run's slot.
 __device__ __forceinline__ void begin_run(const WaveState &st, uint32_t K, int lane)
 {
-    for (uint32_t k = lane; k < K; k += kWaveSize) { st.count[k] = 0; st.first[k] = kNoItem; }
+    for (uint32_t k = lane; k < K; k += kWaveSize) { state_count(st)[k] = 0; state_first(st)[k] = kNoItem; }
 }
 __device__ __forceinline__ void end_run(const WaveState &st, Partial *partials, uint32_t slot, uint32_t K, int lane)
 {
-    Partial *out = partials + (u64)slot * K;
+    // one 16-byte record per candidate, written as a vector through the global address space
+    static_assert(sizeof(Partial) == 16, "Partial is one 16-byte vector");
+    GEAK_AS_GLOBAL u32x4 *out = (GEAK_AS_GLOBAL u32x4 *)partials + (u64)slot * K;
     for (uint32_t k = lane; k < K; k += kWaveSize) {
-        Partial r;
-        r.count = st.count[k];
-        r.first_item = st.first[k];
-        r.reserved = 0;
+        const u64 count = state_count(st)[k];
+        u32x4 r;
+        r[0] = (uint32_t)count;
+        r[1] = (uint32_t)(count >> 32);
+        r[2] = state_first(st)[k];
+        r[3] = 0;
         out[k] = r;
     }
 }
@@ -350,6 +363,29 @@ __device__ __forceinline__ void static_for(F &&f)
         static_for<N, F, I + 1>(static_cast<F &&>(f));
     }
 }
+
+// Arguments of a device function arrive in vector registers; everything here is the same for all
+// lanes, so it is moved back to scalar registers once.
+__device__ __forceinline__ uint32_t uniform32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+template <typename T>
+__device__ __forceinline__ T *uniform_ptr(T *p)
+{
+    const u64 v = reinterpret_cast<u64>(p);
+    const u64 lo = uniform32((uint32_t)v), hi = uniform32((uint32_t)(v >> 32));
+    return reinterpret_cast<T *>(lo | (hi << 32));
+}
+// One vector's worth of reference values / tolerances, decoded, as passed to the out-of-line
+// versions of the rare paths (used where code size matters more than the call).
+template <int DT> struct RefVec { float b[Traits<DT>::E]; };
+template <int DT> struct TolVec { float t[Traits<DT>::E]; };
+struct FloatPair { float abs, rel; };
+struct DoublePair { double abs, rel; };
+template <int DT>
+__device__ uint32_t false_suspects_vector(const u32x4 q, const RefVec<DT> ref, const TolVec<DT> tol, const uint32_t slot_mask_in,
+                                          const int equal_nan_in);
+template <int DT>
+__device__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> ref, const float max_abs, const float max_rel, geak_result *rec_in);
+__device__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel, geak_result *rec_in);
 
 template <int DT>
 struct FloatItem {
@@ -483,13 +519,87 @@ struct FloatItem {
         dm = wave_max_f(dm);
         rm = wave_max_f(rm);
         if (lane == 0) {
-            if (dm > max_abs) atomicMax(reinterpret_cast<u64 *>(&rec->max_abs_err), __builtin_bit_cast(u64, (double)dm));
-            if (rm > max_rel) atomicMax(reinterpret_cast<u64 *>(&rec->max_rel_err), __builtin_bit_cast(u64, (double)rm));
+            if (dm > max_abs) publish_max(&rec->max_abs_err, (double)dm);
+            if (rm > max_rel) publish_max(&rec->max_rel_err, (double)rm);
         }
         max_abs = dm;
         max_rel = rm;
     }
+
+    // the same two rare paths through real functions (by-value arguments)
+    template <int V>
+    __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &q, int equal_nan) const
+    {
+        RefVec<DT> r;
+        TolVec<DT> t;
+        static_for<E>([&](auto idx) { constexpr int e = decltype(idx)::value; r.b[e] = ref_value<V, e>(); t.t[e] = tol[V * E + e]; });
+        return false_suspects_vector<DT>(q, r, t, (poisoned_slots >> (V * E)) & ((1u << E) - 1u), equal_nan);
+    }
+    template <int V>
+    __device__ __forceinline__ void raise_call(const u32x4 &q, float &max_abs, float &max_rel, geak_result *rec) const
+    {
+        RefVec<DT> r;
+        static_for<E>([&](auto idx) { constexpr int e = decltype(idx)::value; r.b[e] = ref_value<V, e>(); });
+        const FloatPair out = raise_vector<DT>(q, r, max_abs, max_rel, rec);
+        max_abs = out.abs;
+        max_rel = out.rel;
+    }
 };
+
+template <int DT>
+__device__ __noinline__ uint32_t false_suspects_vector(const u32x4 q, const RefVec<DT> ref, const TolVec<DT> tol,
+                                                       const uint32_t slot_mask_in, const int equal_nan_in)
+{
+    constexpr int E = Traits<DT>::E;
+    const uint32_t slot_mask = uniform32(slot_mask_in);
+    const int equal_nan = (int)uniform32((uint32_t)equal_nan_in);
+    uint32_t n = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        if (slot_mask & (1u << e)) {
+            const float a = decode<DT>(q, e);
+            const float x = ref.b[e];
+            const float why = tol.t[e];     // -1 b is NaN, -2 b is +-Inf, -3 finite b with tolerance +Inf, else not poisoned
+            const bool ok = (why == -1.0f) ? (equal_nan && (a != a))
+                          : (why == -2.0f) ? (a == x)
+                          : (why == -3.0f) ? (__builtin_fabsf(a) < kInfF)
+                          : false;
+            n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok));
+        }
+    }
+    return n;
+}
+
+template <int DT>
+__device__ __noinline__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> ref, const float max_abs, const float max_rel,
+                                               geak_result *rec_in)
+{
+    constexpr int E = Traits<DT>::E;
+    geak_result *rec = uniform_ptr(rec_in);
+    float dm = max_abs, rm = max_rel;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const float x = ref.b[e];
+        const float d = __builtin_fabsf(decode<DT>(q, e) - x);
+        const float babs = __builtin_fabsf(x);
+        dm = (d > dm) ? d : dm;                                          // false for NaN: skipped
+        const bool hit = (rm < kInfF) && may_raise_rel(rm, babs, d);     // implies d > 0
+        if (__builtin_amdgcn_ballot_w64(hit)) {
+            const float r = d / babs;                                    // correctly rounded; d/0 = +Inf
+            rm = (hit && r > rm) ? r : rm;
+        }
+    }
+    dm = wave_max_f(dm);
+    rm = wave_max_f(rm);
+    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
+        if (dm > max_abs) publish_max(&rec->max_abs_err, (double)dm);
+        if (rm > max_rel) publish_max(&rec->max_rel_err, (double)rm);
+    }
+    FloatPair out;
+    out.abs = dm;
+    out.rel = rm;
+    return out;
+}
 
 // ---- int32: same interface, exact equality ---------------------------------------------------------
 struct IntItem {
@@ -518,6 +628,18 @@ struct IntItem {
     }
     template <int V>
     __device__ __forceinline__ uint32_t false_suspects_vec(const u32x4 &, int) const { return 0; }
+    template <int V>
+    __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &, int) const { return 0; }
+    template <int V>
+    __device__ __forceinline__ void raise_call(const u32x4 &q, double &max_abs, double &max_rel, geak_result *rec) const
+    {
+        u32x4 b;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
+        const DoublePair out = raise_vector_int(q, b, max_abs, max_rel, rec);
+        max_abs = out.abs;
+        max_rel = out.rel;
+    }
 
     template <int V>
     __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, geak_result *rec, int lane) const
@@ -539,32 +661,51 @@ struct IntItem {
         dm = wave_max_d(dm);
         rm = wave_max_d(rm);
         if (lane == 0) {
-            if (dm > max_abs) atomicMax(reinterpret_cast<u64 *>(&rec->max_abs_err), __builtin_bit_cast(u64, dm));
-            if (rm > max_rel) atomicMax(reinterpret_cast<u64 *>(&rec->max_rel_err), __builtin_bit_cast(u64, rm));
+            if (dm > max_abs) publish_max(&rec->max_abs_err, dm);
+            if (rm > max_rel) publish_max(&rec->max_rel_err, rm);
         }
         max_abs = dm;
         max_rel = rm;
     }
 };
 
+__device__ __noinline__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
+                                                    geak_result *rec_in)
+{
+    geak_result *rec = uniform_ptr(rec_in);
+    double dm = max_abs, rm = max_rel;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const long long a = (int)q[e], x = (int)b[e];
+        const long long diff = a - x;
+        const double d = (double)(diff < 0 ? -diff : diff);          // exact
+        const double babs = (double)(x < 0 ? -x : x);
+        dm = (d > dm) ? d : dm;
+        if (d > 0.0 && (rm < (double)kInfF) && d > rm * (1.0 - 0x1p-30) * babs) {
+            const double r = d / babs;                               // binary64, correctly rounded; d/0 = +Inf
+            rm = (r > rm) ? r : rm;
+        }
+    }
+    dm = wave_max_d(dm);
+    rm = wave_max_d(rm);
+    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
+        if (dm > max_abs) publish_max(&rec->max_abs_err, dm);
+        if (rm > max_rel) publish_max(&rec->max_rel_err, rm);
+    }
+    DoublePair out;
+    out.abs = dm;
+    out.rel = rm;
+    return out;
+}
+
 template <int DT> struct ItemOf { typedef FloatItem<DT> type; };
 template <> struct ItemOf<GEAK_I32> { typedef IntItem type; };
 
-// Arguments of a device function arrive in vector registers; everything here is the same for all
-// lanes, so it is moved back to scalar registers once.
-__device__ __forceinline__ uint32_t uniform32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
-template <typename T>
-__device__ __forceinline__ T *uniform_ptr(T *p)
-{
-    const u64 v = reinterpret_cast<u64>(p);
-    const u64 lo = uniform32((uint32_t)v), hi = uniform32((uint32_t)(v >> 32));
-    return reinterpret_cast<T *>(lo | (hi << 32));
-}
 __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 {
     WaveState st;
-    st.count = uniform_ptr(in.count);
-    st.first = uniform_ptr(in.first);
+    st.count_off = uniform32(in.count_off);
+    st.first_off = uniform32(in.first_off);
     return st;
 }
 
@@ -588,7 +729,7 @@ struct RunArgs {
 // registers for the same vector of the next element of the wave's stream (the next candidate, or
 // the reference slice of the wave's next item).  Four loads per lane stay in flight and each has a
 // whole element's worth of compute to land.
-template <int DT, int V, typename Item>
+template <int DT, int V, bool OUTLINE = false, typename Item>
 __device__ __forceinline__ void stream_step(const Item &ref, u32x4 &slot, const unsigned char *next, bool has_next,
                                             uint32_t next_n, const bool next_full, typename Item::Hint &max_abs,
                                             typename Item::Hint &max_rel, int equal_nan, geak_result *rec, int lane,
@@ -597,21 +738,24 @@ __device__ __forceinline__ void stream_step(const Item &ref, u32x4 &slot, const 
     constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
     u64 trip_abs = 0, trip_rel = 0;
     ref.template compare_vec<V>(slot, max_abs, max_rel, bad, trip_abs, trip_rel);
-    if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_vec<V>(slot, equal_nan);
+    if (ref.poisoned_slots & kVecMask) {
+        if constexpr (OUTLINE) bad -= ref.template false_suspects_call<V>(slot, equal_nan);
+        else bad -= ref.template false_suspects_vec<V>(slot, equal_nan);
+    }
     if (max_rel == (typename Item::Hint)kInfF) trip_rel = 0;       // nothing exceeds +Inf
-    if (trip_abs | trip_rel) ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
+    if (trip_abs | trip_rel) {
+        if constexpr (OUTLINE) ref.template raise_call<V>(slot, max_abs, max_rel, rec);
+        else ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
+    }
     if (has_next) slot = load_vec<DT>(next, lane, V, next_n, next_full);
 }
 
 // Each dtype's routine is a real function, so that its register allocation stands alone instead of
-// being merged with the other dtypes' inside the kernel.
-//   TAIL = false: a whole run of consecutive FULL items of the dtype.  The wave's loads form one
-//     stream -- reference slice, K candidate slices, next reference slice, ... -- that never
-//     drains at an item boundary, and every load is an unguarded 16-byte vector load.
-//   TAIL = true: exactly one item that starts aligned but is shorter than a full item (the end of a
-//     segment), with guarded loads.
-// Returns the index of the wave's first item it did not process.
-template <int DT, bool TAIL>
+// being merged with the other dtypes' inside the kernel.  It processes a whole run of consecutive
+// FULL items of the dtype: the wave's loads form one stream -- reference slice, K candidate slices,
+// next reference slice, ... -- that never drains at an item boundary, and every load is an
+// unguarded 16-byte vector load.  Returns the index of the wave's first item it did not process.
+template <int DT>
 __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState st_in)
 {
     typedef typename ItemOf<DT>::type Item;
@@ -631,7 +775,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     geak_item it = load_work_item(items, j);
     Item ref;
     u32x4 cur[kVecPerLane];
-    constexpr bool full = !TAIL;
+    constexpr bool full = true;
 #pragma unroll
     for (int v = 0; v < kVecPerLane; ++v)                  // the only loads of the run that nothing hides
         cur[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, it.numel, full);
@@ -639,7 +783,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     for (;;) {
         // look ahead: does the wave's next item continue the run?
         const uint32_t jn = j + kWavesPerBlock;
-        bool more = !TAIL && jn < block_end;
+        bool more = jn < block_end;
         geak_item nx = it;
         if (more) {
             nx = load_work_item(items, jn);
@@ -688,6 +832,115 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     return j + kWavesPerBlock;
 }
 
+// ---- a segment's tail: one item that starts aligned but is shorter than a full item -----------------
+// A wave is latency-bound per load round trip whatever the slice length, so a short tail is not
+// streamed candidate by candidate: the four vector registers per lane are packed with as many
+// candidates as fit (four when the tail needs one vector per lane, two when it needs two), the
+// loads of a batch -- and, for the first batch, of the reference -- are issued together, and the
+// whole batch is compared after a single wait.  Absent elements read as 0 on both sides.
+template <int DT>
+__device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_in)
+{
+    typedef typename ItemOf<DT>::type Item;
+    typedef typename Item::Hint Hint;
+    const WaveState st = uniform_state(st_in);
+    const geak_item *items = uniform_ptr(in.items);
+    const unsigned char *ref_base = uniform_ptr(in.ref);
+    const unsigned char *const *cand = uniform_ptr(in.cand);
+    geak_result *results = uniform_ptr(in.results);
+    Partial *partials = uniform_ptr(in.partials);
+    const uint32_t K = uniform32(in.K);
+    const float atol_f = bits_f(uniform32(f_bits(in.atol_f))), rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
+    const int equal_nan = (int)uniform32((uint32_t)in.equal_nan);
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t j = uniform32(in.first_item);
+    const geak_item it = load_work_item(items, j);
+    const uint32_t n = it.numel;
+    const uint32_t vectors = (n * Traits<DT>::W + kWaveSize * 16 - 1) / (kWaveSize * 16);    // 1..4 per lane
+    const uint32_t per_batch = vectors == 1 ? 4 : (vectors == 2 ? 2 : 1);                       // candidates per batch
+    geak_result *recs = results + (u64)it.segment * K;
+
+    // loads of one batch: candidate kb + c occupies registers [c * (4 / per_batch), ...)
+    u32x4 cur[kVecPerLane];
+    const auto load_batch = [&](uint32_t kb) {
+        if (per_batch == 4) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (kb + c < K) cur[c] = load_vec<DT>(table_entry(cand, kb + c) + it.byte_offset, lane, 0, n, false);
+        } else if (per_batch == 2) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                if (kb + c < K) {
+                    cur[2 * c + 0] = load_vec<DT>(table_entry(cand, kb + c) + it.byte_offset, lane, 0, n, false);
+                    cur[2 * c + 1] = load_vec<DT>(table_entry(cand, kb + c) + it.byte_offset, lane, 1, n, false);
+                }
+        } else {
+#pragma unroll
+            for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_vec<DT>(table_entry(cand, kb) + it.byte_offset, lane, v, n, false);
+        }
+    };
+
+    Item ref;
+    {
+        u32x4 r[kVecPerLane];
+#pragma unroll
+        for (int v = 0; v < kVecPerLane; ++v) r[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, n, false);
+        load_batch(0);                                     // in flight together with the reference
+        ref.template stage_vec<0>(r[0], atol_f, rtol_f);
+        ref.template stage_vec<1>(r[1], atol_f, rtol_f);
+        ref.template stage_vec<2>(r[2], atol_f, rtol_f);
+        ref.template stage_vec<3>(r[3], atol_f, rtol_f);
+    }
+    if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
+
+    // compare register vector `q` as vector V of candidate k, accumulating into bad
+    const auto one = [&](auto vtag, const u32x4 &q, uint32_t k, Hint &max_abs, Hint &max_rel, uint32_t &bad) {
+        constexpr int V = decltype(vtag)::value;
+        u32x4 slot = q;
+        stream_step<DT, V, true>(ref, slot, nullptr, false, 0, false, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+    };
+    const auto hints = [&](uint32_t k, Hint &max_abs, Hint &max_rel) {
+        max_abs = Item::hint_from_bits(load_bits(&recs[k].max_abs_err));
+        max_rel = Item::hint_from_bits(load_bits(&recs[k].max_rel_err));
+    };
+
+    for (uint32_t kb = 0; kb < K; kb += per_batch) {
+        if (kb) load_batch(kb);
+        if (per_batch == 4) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (kb + c < K) {
+                    Hint ma, mr;
+                    hints(kb + c, ma, mr);
+                    uint32_t bad = 0;
+                    one(Index<0>{}, cur[c], kb + c, ma, mr, bad);
+                    note_mismatches(st, kb + c, bad, j, lane);
+                }
+        } else if (per_batch == 2) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                if (kb + c < K) {
+                    Hint ma, mr;
+                    hints(kb + c, ma, mr);
+                    uint32_t bad = 0;
+                    one(Index<0>{}, cur[2 * c + 0], kb + c, ma, mr, bad);
+                    one(Index<1>{}, cur[2 * c + 1], kb + c, ma, mr, bad);
+                    note_mismatches(st, kb + c, bad, j, lane);
+                }
+        } else {
+            Hint ma, mr;
+            hints(kb, ma, mr);
+            uint32_t bad = 0;
+            one(Index<0>{}, cur[0], kb, ma, mr, bad);
+            one(Index<1>{}, cur[1], kb, ma, mr, bad);
+            one(Index<2>{}, cur[2], kb, ma, mr, bad);
+            one(Index<3>{}, cur[3], kb, ma, mr, bad);
+            note_mismatches(st, kb, bad, j, lane);
+        }
+    }
+    if (it.flags & GEAK_ITEM_LAST) end_run(st, partials, it.slot, K, lane);
+}
+
 // ---- items that do not start on a 16-byte boundary (a segment's first few elements) ---------------
 __device__ __forceinline__ void process_head(const geak_item &it, uint32_t item_index, const CompareArgs &p,
                                              const WaveState &st, int lane)
@@ -708,8 +961,9 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     const int lane = threadIdx.x & (kWaveSize - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     WaveState st;
-    st.count = reinterpret_cast<u64 *>(lds) + (size_t)wave * K;
-    st.first = reinterpret_cast<uint32_t *>(lds + sizeof(u64) * kWavesPerBlock * K) + (size_t)wave * K;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(GEAK_AS_LDS unsigned char *)lds;
+    st.count_off = lds_base + (uint32_t)sizeof(u64) * wave * K;
+    st.first_off = lds_base + (uint32_t)sizeof(u64) * kWavesPerBlock * K + (uint32_t)sizeof(uint32_t) * wave * K;
 
     const GEAK_AS_CONSTANT uint32_t *block_first = (const GEAK_AS_CONSTANT uint32_t *)p.block_first;
     const uint32_t block_begin = block_first[blockIdx.x];
@@ -737,18 +991,19 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
             uint32_t next_j;
             if (it.flags & GEAK_ITEM_FULL) {
                 switch (it.dtype) {
-                case GEAK_F32:  next_j = process_run<GEAK_F32, false>(r, st); break;
-                case GEAK_F16:  next_j = process_run<GEAK_F16, false>(r, st); break;
-                case GEAK_BF16: next_j = process_run<GEAK_BF16, false>(r, st); break;
-                default:        next_j = process_run<GEAK_I32, false>(r, st); break;
+                case GEAK_F32:  next_j = process_run<GEAK_F32>(r, st); break;
+                case GEAK_F16:  next_j = process_run<GEAK_F16>(r, st); break;
+                case GEAK_BF16: next_j = process_run<GEAK_BF16>(r, st); break;
+                default:        next_j = process_run<GEAK_I32>(r, st); break;
                 }
             } else {
                 switch (it.dtype) {
-                case GEAK_F32:  next_j = process_run<GEAK_F32, true>(r, st); break;
-                case GEAK_F16:  next_j = process_run<GEAK_F16, true>(r, st); break;
-                case GEAK_BF16: next_j = process_run<GEAK_BF16, true>(r, st); break;
-                default:        next_j = process_run<GEAK_I32, true>(r, st); break;
+                case GEAK_F32:  process_tail<GEAK_F32>(r, st); break;
+                case GEAK_F16:  process_tail<GEAK_F16>(r, st); break;
+                case GEAK_BF16: process_tail<GEAK_BF16>(r, st); break;
+                default:        process_tail<GEAK_I32>(r, st); break;
                 }
+                next_j = j + kWavesPerBlock;
             }
             j = __builtin_amdgcn_readfirstlane(next_j);
             continue;
