@@ -130,7 +130,9 @@ geak_status geak_check_plan_dense(geak_plan **out, int32_t dtype, const int64_t 
 uint64_t geak_check_workspace_bytes(const geak_plan *plan)
 {
     if (!plan || plan->host.items.empty()) return 0;
-    return kCandTableBytes + (uint64_t)plan->host.slot_begin.back() * (uint64_t)plan->host.num_candidates * sizeof(Partial);
+    const HostPlan &hp = plan->host;
+    const uint64_t board = (uint64_t)hp.segments.size() * (uint64_t)hp.num_candidates * hp.replicas * sizeof(MaxPair);
+    return kCandTableBytes + board + (uint64_t)hp.slot_begin.back() * (uint64_t)hp.num_candidates * sizeof(Partial);
 }
 
 uint64_t geak_check_result_count(const geak_plan *plan)
@@ -161,12 +163,16 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
     if (!g.ok) return GEAK_EHIP;
 
     // workspace: [candidate pointer table][partials]
+    const uint64_t num_board = hp.items.empty() ? 0 : (uint64_t)hp.segments.size() * (uint64_t)K * hp.replicas;
     const unsigned char **cand_table = hp.items.empty() ? nullptr : (const unsigned char **)workspace_dev;
-    Partial *partials = hp.items.empty() ? nullptr : (Partial *)((unsigned char *)workspace_dev + kCandTableBytes);
+    MaxPair *board = hp.items.empty() ? nullptr : (MaxPair *)((unsigned char *)workspace_dev + kCandTableBytes);
+    Partial *partials = hp.items.empty() ? nullptr : (Partial *)((unsigned char *)board + num_board * sizeof(MaxPair));
 
     InitArgs ia;
     ia.results = results_dev;
     ia.cand_table = cand_table;
+    ia.board = board;
+    ia.num_board = num_board;
     ia.num_results = geak_check_result_count(plan);
     ia.num_candidates = (uint32_t)K;
     ia.reserved = 0;
@@ -179,7 +185,9 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.ref = (const unsigned char *)ref_dev;
         ca.cand_table = cand_table;
         ca.partials = partials;
-        ca.results = results_dev;
+        ca.board = board;
+        ca.replicas = hp.replicas;
+        ca.reserved0 = 0;
         ca.num_items = (uint32_t)hp.items.size();
         ca.num_candidates = (uint32_t)K;
         ca.atol_f = hp.atol_f;
@@ -203,6 +211,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ra.items = plan->items_dev;
         ra.slot_begin = plan->slot_begin_dev;
         ra.partials = partials;
+        ra.board = board;
         ra.results = results_dev;
         ra.ref = (const unsigned char *)ref_dev;
         ra.cand_table = cand_table;
@@ -211,7 +220,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ra.atol_f = hp.atol_f;
         ra.rtol_f = hp.rtol_f;
         ra.equal_nan = hp.equal_nan;
-        ra.reserved = 0;
+        ra.replicas = hp.replicas;
         if (launch_reduce(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
     }
     return GEAK_OK;

@@ -39,6 +39,7 @@ struct HostPlan {
     float atol_f = 0.f, rtol_f = 0.f;
     int equal_nan = 0;
     uint32_t grid_blocks = 1;
+    uint32_t replicas = 1;                 // replicas of the running maxima per (segment, candidate)
     std::vector<uint32_t> block_first;     // size grid_blocks + 1: block b owns items [block_first[b], block_first[b + 1])
     uint32_t max_blocks = 1;               // compute units x resident blocks per unit
 };
@@ -47,14 +48,27 @@ struct HostPlan {
 geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nsegs, int32_t num_candidates,
                             double atol, double rtol, int32_t equal_nan, uint32_t max_blocks);
 
-// Workspace layout: [candidate pointer table, kCandTableBytes][partials: num_slots x K].
+// Running maxima of one (segment, candidate, replica): non-negative doubles, raised by atomic max on
+// their bit patterns.
+struct MaxPair {
+    double abs;
+    double rel;
+};
+
+// Workspace layout: [candidate pointer table, kCandTableBytes][board: segments x K x replicas MaxPair]
+// [partials: num_slots x K].
 constexpr uint64_t kCandTableBytes = GEAK_MAX_CANDIDATES * sizeof(void *);
+constexpr uint32_t kMaxReplicas = 64;
+constexpr uint32_t kMinReplicas = 4;
+constexpr uint64_t kBoardBudgetBytes = 16ull << 20;      // replicas are halved until the board fits
 
 // Init kernel: neutral result records, and the candidate base pointers copied from the kernel
 // argument block into the workspace so that the other kernels index them from memory.
 struct InitArgs {
     geak_result *results;
     const unsigned char **cand_table;
+    MaxPair *board;
+    uint64_t num_board;                  // segments x K x replicas
     uint64_t num_results;
     uint32_t num_candidates;
     uint32_t reserved;
@@ -66,7 +80,9 @@ struct CompareArgs {
     const unsigned char *ref;
     const unsigned char *const *cand_table;
     Partial *partials;
-    geak_result *results;
+    MaxPair *board;
+    uint32_t replicas;                   // power of two
+    uint32_t reserved0;
     uint32_t num_items;
     uint32_t num_candidates;
     float atol_f;
@@ -80,6 +96,7 @@ struct ReduceArgs {
     const geak_item *items;
     const uint32_t *slot_begin;
     const Partial *partials;
+    const MaxPair *board;
     geak_result *results;
     const unsigned char *ref;
     const unsigned char *const *cand_table;
@@ -88,7 +105,7 @@ struct ReduceArgs {
     float atol_f;
     float rtol_f;
     int equal_nan;
-    int reserved;
+    uint32_t replicas;
 };
 
 // Kernel launchers (kernels.hip).  Return the hipError_t of the launch as int.

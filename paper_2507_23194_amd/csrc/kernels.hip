@@ -15,8 +15,11 @@
 //     overflowed to +Inf) get tol = -1 ("poisoned"): the inequality then always reports a
 //     suspect, and a per-candidate fix-up applies the NaN / Inf rule to exactly those slots.
 //   * mismatch count: v_cmp -> 64-bit lane mask -> s_bcnt1, accumulated in LDS per (wave, k).
-//   * max_abs_err / max_rel_err: the current global maxima are read from the result records and
-//     used as wave-uniform thresholds.  Per element only `d > max_abs` and `d > c*|b|` (c slightly
+//   * max_abs_err / max_rel_err: the current maxima are read from a board of running maxima in the
+//     workspace and used as wave-uniform thresholds.  The board holds R replicas per (segment,
+//     candidate) -- a block reads and raises replica (block mod R), the reduce kernel takes the
+//     maximum over them -- because many waves raising one address serialise at tens of
+//     microseconds per atomic.  Per element only `d > max_abs` and `d > c*|b|` (c slightly
 //     below max_rel, so that no division is needed) are evaluated; when any lane trips, a rare
 //     path re-reads the item from memory, evaluates it exactly (true binary32 division) and raises
 //     the global maxima with 64-bit atomic max on the bit patterns of the non-negative doubles.
@@ -30,9 +33,10 @@
 // reduce kernel -- one block per (segment, candidate): sums counts over the segment's slots,
 //   takes the least item index, rescans that item with the full rule, writes pass/count/first.
 //
-// Blocks of the compare kernel start at different candidates (k0 = block % K) so that the first,
-// expensive, visit of a (segment, candidate) pair is spread out and later visitors find the maxima
-// already raised.
+// Blocks of the compare kernel start at different candidates so that the first, expensive, visit
+// of a (segment, candidate) pair is spread out and later visitors find the maxima already raised:
+// the blocks that share replica r of the board are r, r + R, r + 2R, ... and start at candidates
+// 0, 1, 2, ... (k0 = (block / R) mod K).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include "geak_internal.hpp"
@@ -230,10 +234,10 @@ __device__ __forceinline__ bool may_raise_rel(float r, float babs, float d)
 // Used (a) for segment heads and tails, (b) when the hot loop finds that an item may raise one of
 // the maxima.  Returns the wave-uniform mismatch count and raises the record's maxima.
 __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsigned char *cand, uint32_t n, int dtype,
-                                            float atol_f, float rtol_f, int equal_nan, geak_result *rec)
+                                            float atol_f, float rtol_f, int equal_nan, MaxPair *rec)
 {
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const u64 abs_bits = load_bits(&rec->max_abs_err), rel_bits = load_bits(&rec->max_rel_err);
+    const u64 abs_bits = load_bits(&rec->abs), rel_bits = load_bits(&rec->rel);
     uint32_t bad = 0;
     if (dtype == GEAK_I32) {
         const double seen_rel = __builtin_bit_cast(double, rel_bits);
@@ -255,8 +259,8 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
         dm = wave_max_d(dm);
         rm = wave_max_d(rm);
         if (lane == 0) {
-            raise_max(&rec->max_abs_err, dm, abs_bits);
-            raise_max(&rec->max_rel_err, rm, rel_bits);
+            raise_max(&rec->abs, dm, abs_bits);
+            raise_max(&rec->rel, rm, rel_bits);
         }
     } else {
         const float seen_rel = (float)__builtin_bit_cast(double, rel_bits);   // exact: published from binary32
@@ -276,8 +280,8 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
         dm = wave_max_f(dm);
         rm = wave_max_f(rm);
         if (lane == 0) {
-            raise_max(&rec->max_abs_err, (double)dm, abs_bits);
-            raise_max(&rec->max_rel_err, (double)rm, rel_bits);
+            raise_max(&rec->abs, (double)dm, abs_bits);
+            raise_max(&rec->rel, (double)rm, rel_bits);
         }
     }
 #pragma unroll
@@ -354,6 +358,16 @@ __device__ __forceinline__ float f16_rel_margin(float r, uint32_t b2, float d)
     return e;
 }
 
+// RN(r * |b|) with b a binary16 half of b2 (the added +0 changes nothing: the product is never -0)
+template <bool HI>
+__device__ __forceinline__ float f16_abs_scaled(float r, uint32_t b2)
+{
+    float e;
+    if constexpr (HI) asm("v_fma_mix_f32 %0, %1, |%2|, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "=v"(e) : "v"(r), "v"(b2));
+    else              asm("v_fma_mix_f32 %0, %1, |%2|, 0 op_sel:[0,0,0] op_sel_hi:[0,1,0]" : "=v"(e) : "v"(r), "v"(b2));
+    return e;
+}
+
 template <int I> struct Index { static constexpr int value = I; };
 template <int N, typename F, int I = 0>
 __device__ __forceinline__ void static_for(F &&f)
@@ -384,8 +398,8 @@ template <int DT>
 __device__ uint32_t false_suspects_vector(const u32x4 q, const RefVec<DT> ref, const TolVec<DT> tol, const uint32_t slot_mask_in,
                                           const int equal_nan_in);
 template <int DT>
-__device__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> ref, const float max_abs, const float max_rel, geak_result *rec_in);
-__device__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel, geak_result *rec_in);
+__device__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> ref, const float max_abs, const float max_rel, MaxPair *rec_in);
+__device__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel, MaxPair *rec_in);
 
 template <int DT>
 struct FloatItem {
@@ -411,19 +425,30 @@ struct FloatItem {
 #pragma unroll
             for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
         }
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const int i = V * E + e;
-            const float x = decode<DT>(q, e);
-            if constexpr (DT == GEAK_BF16) bref[i] = f_bits(x);
-            const float prod = rtol_f * __builtin_fabsf(x);
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            constexpr int i = V * E + e;
+            float prod;
+            if constexpr (DT == GEAK_F16) {
+                prod = f16_abs_scaled<(e & 1) != 0>(rtol_f, q[e >> 1]);
+            } else {
+                const float x = decode<DT>(q, e);
+                if constexpr (DT == GEAK_BF16) bref[i] = f_bits(x);
+                prod = rtol_f * __builtin_fabsf(x);
+            }
             const float t = atol_f + prod;
-            const bool bad = !(t < kInfF);          // b NaN, b +-Inf, or the tolerance overflowed
-            // the poison value also records why: -1 b is NaN, -2 b is +-Inf, -3 finite b, tolerance +Inf
-            const float why = (x != x) ? -1.0f : (__builtin_fabsf(x) == kInfF ? -2.0f : -3.0f);
-            tol[i] = bad ? why : t;
-            if (__builtin_amdgcn_ballot_w64(bad)) poisoned_slots |= (1u << i);
-        }
+            tol[i] = t;
+            // b NaN, b +-Inf, or the tolerance overflowed: rare, so the poison value is only worked
+            // out under a wave-uniform branch.  It also records why: -1 b is NaN, -2 b is +-Inf,
+            // -3 finite b with an infinite tolerance.
+            const bool bad = !(t < kInfF);
+            if (__builtin_amdgcn_ballot_w64(bad)) {
+                const float x = decode<DT>(q, e);
+                const float why = (x != x) ? -1.0f : (__builtin_fabsf(x) == kInfF ? -2.0f : -3.0f);
+                tol[i] = bad ? why : t;
+                poisoned_slots |= (1u << i);
+            }
+        });
     }
 
     // reference element i = V*E + e as binary32 (rare paths)
@@ -501,7 +526,7 @@ struct FloatItem {
     // Per lane the running maxima start from the wave-uniform ones, so the true division only runs
     // for elements that really exceed what the lane has seen.
     template <int V>
-    __device__ __forceinline__ void raise_vec(const u32x4 &q, float &max_abs, float &max_rel, geak_result *rec, int lane) const
+    __device__ __forceinline__ void raise_vec(const u32x4 &q, float &max_abs, float &max_rel, MaxPair *rec, int lane) const
     {
         float dm = max_abs, rm = max_rel;
         static_for<E>([&](auto idx) {
@@ -519,8 +544,8 @@ struct FloatItem {
         dm = wave_max_f(dm);
         rm = wave_max_f(rm);
         if (lane == 0) {
-            if (dm > max_abs) publish_max(&rec->max_abs_err, (double)dm);
-            if (rm > max_rel) publish_max(&rec->max_rel_err, (double)rm);
+            if (dm > max_abs) publish_max(&rec->abs, (double)dm);
+            if (rm > max_rel) publish_max(&rec->rel, (double)rm);
         }
         max_abs = dm;
         max_rel = rm;
@@ -536,7 +561,7 @@ struct FloatItem {
         return false_suspects_vector<DT>(q, r, t, (poisoned_slots >> (V * E)) & ((1u << E) - 1u), equal_nan);
     }
     template <int V>
-    __device__ __forceinline__ void raise_call(const u32x4 &q, float &max_abs, float &max_rel, geak_result *rec) const
+    __device__ __forceinline__ void raise_call(const u32x4 &q, float &max_abs, float &max_rel, MaxPair *rec) const
     {
         RefVec<DT> r;
         static_for<E>([&](auto idx) { constexpr int e = decltype(idx)::value; r.b[e] = ref_value<V, e>(); });
@@ -572,10 +597,10 @@ __device__ __noinline__ uint32_t false_suspects_vector(const u32x4 q, const RefV
 
 template <int DT>
 __device__ __noinline__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> ref, const float max_abs, const float max_rel,
-                                               geak_result *rec_in)
+                                               MaxPair *rec_in)
 {
     constexpr int E = Traits<DT>::E;
-    geak_result *rec = uniform_ptr(rec_in);
+    MaxPair *rec = uniform_ptr(rec_in);
     float dm = max_abs, rm = max_rel;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
@@ -592,8 +617,8 @@ __device__ __noinline__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> r
     dm = wave_max_f(dm);
     rm = wave_max_f(rm);
     if ((threadIdx.x & (kWaveSize - 1)) == 0) {
-        if (dm > max_abs) publish_max(&rec->max_abs_err, (double)dm);
-        if (rm > max_rel) publish_max(&rec->max_rel_err, (double)rm);
+        if (dm > max_abs) publish_max(&rec->abs, (double)dm);
+        if (rm > max_rel) publish_max(&rec->rel, (double)rm);
     }
     FloatPair out;
     out.abs = dm;
@@ -631,7 +656,7 @@ struct IntItem {
     template <int V>
     __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &, int) const { return 0; }
     template <int V>
-    __device__ __forceinline__ void raise_call(const u32x4 &q, double &max_abs, double &max_rel, geak_result *rec) const
+    __device__ __forceinline__ void raise_call(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec) const
     {
         u32x4 b;
 #pragma unroll
@@ -642,7 +667,7 @@ struct IntItem {
     }
 
     template <int V>
-    __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, geak_result *rec, int lane) const
+    __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec, int lane) const
     {
         double dm = max_abs, rm = max_rel;
 #pragma unroll
@@ -661,8 +686,8 @@ struct IntItem {
         dm = wave_max_d(dm);
         rm = wave_max_d(rm);
         if (lane == 0) {
-            if (dm > max_abs) publish_max(&rec->max_abs_err, dm);
-            if (rm > max_rel) publish_max(&rec->max_rel_err, rm);
+            if (dm > max_abs) publish_max(&rec->abs, dm);
+            if (rm > max_rel) publish_max(&rec->rel, rm);
         }
         max_abs = dm;
         max_rel = rm;
@@ -670,9 +695,9 @@ struct IntItem {
 };
 
 __device__ __noinline__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
-                                                    geak_result *rec_in)
+                                                    MaxPair *rec_in)
 {
-    geak_result *rec = uniform_ptr(rec_in);
+    MaxPair *rec = uniform_ptr(rec_in);
     double dm = max_abs, rm = max_rel;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -689,8 +714,8 @@ __device__ __noinline__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b
     dm = wave_max_d(dm);
     rm = wave_max_d(rm);
     if ((threadIdx.x & (kWaveSize - 1)) == 0) {
-        if (dm > max_abs) publish_max(&rec->max_abs_err, dm);
-        if (rm > max_rel) publish_max(&rec->max_rel_err, rm);
+        if (dm > max_abs) publish_max(&rec->abs, dm);
+        if (rm > max_rel) publish_max(&rec->rel, rm);
     }
     DoublePair out;
     out.abs = dm;
@@ -714,8 +739,10 @@ struct RunArgs {
     const geak_item *items;
     const unsigned char *ref;            // buffer base
     const unsigned char *const *cand;    // device table of K candidate bases
-    geak_result *results;
+    MaxPair *board;                      // running maxima: [segment][candidate][replica]
     Partial *partials;
+    uint32_t replicas;                   // power of two
+    uint32_t replica;                    // the one this block reads and raises
     uint32_t first_item;                 // index of the run's first item; the wave owns every 4th item up to block_end
     uint32_t block_end;
     uint32_t K;
@@ -732,7 +759,7 @@ struct RunArgs {
 template <int DT, int V, bool OUTLINE = false, typename Item>
 __device__ __forceinline__ void stream_step(const Item &ref, u32x4 &slot, const unsigned char *next, bool has_next,
                                             uint32_t next_n, const bool next_full, typename Item::Hint &max_abs,
-                                            typename Item::Hint &max_rel, int equal_nan, geak_result *rec, int lane,
+                                            typename Item::Hint &max_rel, int equal_nan, MaxPair *rec, int lane,
                                             uint32_t &bad)
 {
     constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
@@ -764,8 +791,9 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     const geak_item *items = uniform_ptr(in.items);
     const unsigned char *ref_base = uniform_ptr(in.ref);
     const unsigned char *const *cand = uniform_ptr(in.cand);
-    geak_result *results = uniform_ptr(in.results);
+    MaxPair *board = uniform_ptr(in.board);
     Partial *partials = uniform_ptr(in.partials);
+    const uint32_t replicas = uniform32(in.replicas), replica = uniform32(in.replica);
     const uint32_t block_end = uniform32(in.block_end), K = uniform32(in.K), k0 = uniform32(in.k0);
     const float atol_f = bits_f(uniform32(f_bits(in.atol_f))), rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
     const int equal_nan = (int)uniform32((uint32_t)in.equal_nan);
@@ -790,7 +818,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
             more = (nx.flags & GEAK_ITEM_FULL) && nx.dtype == DT;
         }
         if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
-        geak_result *recs = results + (u64)it.segment * K;
+        MaxPair *recs = board + (u64)it.segment * K * replicas + replica;     // candidate k: recs[k * replicas]
 
         // reference element: stage it, refilling each vector with the first candidate's
         uint32_t k = k0;
@@ -801,7 +829,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
             ref.template stage_vec<2>(cur[2], atol_f, rtol_f); cur[2] = load_vec<DT>(first, lane, 2, it.numel, full);
             ref.template stage_vec<3>(cur[3], atol_f, rtol_f); cur[3] = load_vec<DT>(first, lane, 3, it.numel, full);
         }
-        u64 abs_bits = load_bits(&recs[k].max_abs_err), rel_bits = load_bits(&recs[k].max_rel_err);
+        u64 abs_bits = load_bits(&recs[k * replicas].abs), rel_bits = load_bits(&recs[k * replicas].rel);
 
         for (uint32_t step = 0; step < K; ++step) {
             const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
@@ -813,14 +841,14 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
             Hint max_abs = Item::hint_from_bits(abs_bits);      // exact: floating maxima are published from binary32
             Hint max_rel = Item::hint_from_bits(rel_bits);
             if (!last) {
-                abs_bits = load_bits(&recs[kn].max_abs_err);
-                rel_bits = load_bits(&recs[kn].max_rel_err);
+                abs_bits = load_bits(&recs[kn * replicas].abs);
+                rel_bits = load_bits(&recs[kn * replicas].rel);
             }
             uint32_t bad = 0;
-            stream_step<DT, 0>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
-            stream_step<DT, 1>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
-            stream_step<DT, 2>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
-            stream_step<DT, 3>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+            stream_step<DT, 0>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
+            stream_step<DT, 1>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
+            stream_step<DT, 2>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
+            stream_step<DT, 3>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
             note_mismatches(st, k, bad, j, lane);
             k = kn;
         }
@@ -847,8 +875,9 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     const geak_item *items = uniform_ptr(in.items);
     const unsigned char *ref_base = uniform_ptr(in.ref);
     const unsigned char *const *cand = uniform_ptr(in.cand);
-    geak_result *results = uniform_ptr(in.results);
+    MaxPair *board = uniform_ptr(in.board);
     Partial *partials = uniform_ptr(in.partials);
+    const uint32_t replicas = uniform32(in.replicas), replica = uniform32(in.replica);
     const uint32_t K = uniform32(in.K);
     const float atol_f = bits_f(uniform32(f_bits(in.atol_f))), rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
     const int equal_nan = (int)uniform32((uint32_t)in.equal_nan);
@@ -858,7 +887,7 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     const uint32_t n = it.numel;
     const uint32_t vectors = (n * Traits<DT>::W + kWaveSize * 16 - 1) / (kWaveSize * 16);    // 1..4 per lane
     const uint32_t per_batch = vectors == 1 ? 4 : (vectors == 2 ? 2 : 1);                       // candidates per batch
-    geak_result *recs = results + (u64)it.segment * K;
+    MaxPair *recs = board + (u64)it.segment * K * replicas + replica;         // candidate k: recs[k * replicas]
 
     // loads of one batch: candidate kb + c occupies registers [c * (4 / per_batch), ...)
     u32x4 cur[kVecPerLane];
@@ -897,11 +926,11 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     const auto one = [&](auto vtag, const u32x4 &q, uint32_t k, Hint &max_abs, Hint &max_rel, uint32_t &bad) {
         constexpr int V = decltype(vtag)::value;
         u32x4 slot = q;
-        stream_step<DT, V, true>(ref, slot, nullptr, false, 0, false, max_abs, max_rel, equal_nan, &recs[k], lane, bad);
+        stream_step<DT, V, true>(ref, slot, nullptr, false, 0, false, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
     };
     const auto hints = [&](uint32_t k, Hint &max_abs, Hint &max_rel) {
-        max_abs = Item::hint_from_bits(load_bits(&recs[k].max_abs_err));
-        max_rel = Item::hint_from_bits(load_bits(&recs[k].max_rel_err));
+        max_abs = Item::hint_from_bits(load_bits(&recs[k * replicas].abs));
+        max_rel = Item::hint_from_bits(load_bits(&recs[k * replicas].rel));
     };
 
     for (uint32_t kb = 0; kb < K; kb += per_batch) {
@@ -946,10 +975,10 @@ __device__ __forceinline__ void process_head(const geak_item &it, uint32_t item_
                                              const WaveState &st, int lane)
 {
     const uint32_t K = p.num_candidates;
-    geak_result *recs = p.results + (u64)it.segment * K;
+    MaxPair *recs = p.board + (u64)it.segment * K * p.replicas + (blockIdx.x & (p.replicas - 1));
     for (uint32_t k = 0; k < K; ++k) {
         const uint32_t bad = exact_item(p.ref + it.byte_offset, table_entry(p.cand_table, k) + it.byte_offset, it.numel,
-                                        it.dtype, p.atol_f, p.rtol_f, p.equal_nan, &recs[k]);
+                                        it.dtype, p.atol_f, p.rtol_f, p.equal_nan, &recs[k * p.replicas]);
         note_mismatches(st, k, bad, item_index, lane);
     }
 }
@@ -973,11 +1002,13 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.items = p.items;
     r.ref = p.ref;
     r.cand = p.cand_table;
-    r.results = p.results;
+    r.board = p.board;
+    r.replicas = p.replicas;
+    r.replica = blockIdx.x & (p.replicas - 1);
     r.partials = p.partials;
     r.block_end = block_end;
     r.K = K;
-    r.k0 = blockIdx.x % K;
+    r.k0 = (blockIdx.x / p.replicas) % K;
     r.atol_f = p.atol_f;
     r.rtol_f = p.rtol_f;
     r.equal_nan = p.equal_nan;
@@ -1030,6 +1061,10 @@ __global__ void init_kernel(const InitArgs p)
         p.results[i] = r;
     }
     if (p.cand_table && i < p.num_candidates) p.cand_table[i] = p.cand[i];
+    for (u64 e = i; e < p.num_board; e += (u64)gridDim.x * blockDim.x) {      // running maxima start at +0
+        p.board[e].abs = 0.0;
+        p.board[e].rel = 0.0;
+    }
 }
 
 // ---- reduce: one block per (segment, candidate) ----------------------------------------------
@@ -1111,11 +1146,29 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
         for (int w = 0; w < kReduceThreads / kWaveSize; ++w) best = s_best[w] < best ? s_best[w] : best;
         first = (long long)it.elem_start + (long long)best;
     }
-    if (tid == 0) {
-        geak_result *rec = p.results + (u64)seg * K + k;
-        rec->pass = (count == 0);
-        rec->mismatch_count = count;
-        rec->first_mismatch = first;
+    if (wave == 0) {
+        // the two maxima: largest bit pattern over the replicas (non-negative doubles order like their bits)
+        const MaxPair *mp = p.board + ((u64)seg * K + k) * p.replicas;
+        u64 a = 0, r = 0;
+        for (uint32_t i = lane; i < p.replicas; i += kWaveSize) {
+            const u64 ai = __builtin_bit_cast(u64, mp[i].abs), ri = __builtin_bit_cast(u64, mp[i].rel);
+            a = ai > a ? ai : a;
+            r = ri > r ? ri : r;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const u64 ao = (u64)__shfl_xor((long long)a, o, kWaveSize), ro = (u64)__shfl_xor((long long)r, o, kWaveSize);
+            a = ao > a ? ao : a;
+            r = ro > r ? ro : r;
+        }
+        if (lane == 0) {
+            geak_result *rec = p.results + (u64)seg * K + k;
+            rec->pass = (count == 0);
+            rec->mismatch_count = count;
+            rec->first_mismatch = first;
+            rec->max_abs_err = __builtin_bit_cast(double, a);
+            rec->max_rel_err = __builtin_bit_cast(double, r);
+        }
     }
 }
 
@@ -1123,11 +1176,14 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
 
 int launch_init(const InitArgs &args, void *stream)
 {
-    const uint64_t n = args.num_results > args.num_candidates ? args.num_results : args.num_candidates;
+    uint64_t n = args.num_results > args.num_candidates ? args.num_results : args.num_candidates;
+    if (args.num_board > n) n = args.num_board;
     if (!n) return (int)hipSuccess;
     const uint32_t threads = 256;
-    const uint32_t blocks = (uint32_t)((n + threads - 1) / threads);
-    hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(threads), 0, (hipStream_t)stream, args);
+    uint64_t blocks = (n + threads - 1) / threads;
+    const uint64_t need = ((args.num_results > args.num_candidates ? args.num_results : args.num_candidates) + threads - 1) / threads;
+    if (blocks > 4096) blocks = 4096 > need ? 4096 : need;     // the board is zeroed with a grid-stride loop
+    hipLaunchKernelGGL(init_kernel, dim3((uint32_t)blocks), dim3(threads), 0, (hipStream_t)stream, args);
     return (int)hipGetLastError();
 }
 

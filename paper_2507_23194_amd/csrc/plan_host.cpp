@@ -76,6 +76,15 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
         hp.equal_nan = equal_nan;
         hp.algorithmic_bytes = total_bytes * ((uint64_t)num_candidates + 1);
         hp.max_blocks = max_blocks;
+        // Replicas of the running maxima.  Many waves raising one address serialise, so few
+        // candidates (few addresses per segment) want many replicas; but every replica has to learn
+        // its maxima by itself, so many candidates want few.  About 512 addresses per segment, within
+        // 4 .. 64 replicas, and fewer when so many (segment, candidate) pairs exist that the board
+        // would outgrow its budget.
+        hp.replicas = kMaxReplicas;
+        while (hp.replicas > kMinReplicas && (uint64_t)hp.replicas * (uint64_t)num_candidates > 512) hp.replicas /= 2;
+        while (hp.replicas > 1 && (uint64_t)nsegs * (uint64_t)num_candidates * hp.replicas * sizeof(MaxPair) > kBoardBudgetBytes)
+            hp.replicas /= 2;
 
         for (uint64_t s = 0; s < nsegs; ++s) {
             const geak_segment &g = segs[s];
