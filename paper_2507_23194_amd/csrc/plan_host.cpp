@@ -112,18 +112,20 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
         // [block_first[b], block_first[b + 1]); its four waves interleave inside it (wave w takes every
         // fourth item starting at w).  A wave's consecutive items are then neighbours in memory and
         // mostly of one segment, so the running maxima it has just raised are the right thresholds
-        // for its next item.  Ranges are cut at equal estimated cost, not equal item count: a wave is
-        // latency-bound per 4 KiB slice whatever its length, so an item costs about one unit per slice
-        // it streams (reference + K candidates), a short tail no less than a full item, and a run
-        // that has to start afresh (new segment, tail, head) pays for an empty pipeline.
+        // for its next item.  Ranges are cut at equal estimated cost, not equal item count.  A wave is
+        // latency-bound per 4 KiB slice, so an item costs about one unit per slice it streams
+        // (reference + K candidates); measured on mixed batches, a slice of a 16-bit dtype (twice the
+        // elements) takes about 1.3 times, and an int32 slice about 0.8 times, as long as a binary32
+        // one.  A tail or a head costs about two full items whatever its length (its loads are
+        // not hidden behind a neighbour's arithmetic), and a run that starts afresh pays for an
+        // empty pipeline.  Units: eighths of a binary32 slice.
         const uint64_t blocks_wanted = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
         const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
         const uint64_t slices = (uint64_t)num_candidates + 1;
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
-            uint64_t c = slices;
-            if (!(it.flags & GEAK_ITEM_ALIGNED)) c = 2 * slices;       // element-wise path, two dependent loads per candidate
-            if (starts_run || !(it.flags & GEAK_ITEM_FULL)) c += 2;    // pipeline refill
-            return c;
+            const uint64_t per_slice = it.dtype == GEAK_I32 ? 6 : (it.dtype == GEAK_F32 ? 8 : 10);
+            if (!(it.flags & GEAK_ITEM_FULL)) return 2 * per_slice * slices;
+            return per_slice * slices + (starts_run ? 16 : 0);
         };
         uint64_t total_cost = 0;
         for (uint64_t j = 0; j < hp.items.size(); ++j)
