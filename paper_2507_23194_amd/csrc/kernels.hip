@@ -19,19 +19,23 @@
 //     workspace and used as wave-uniform thresholds.  The board holds R replicas per (segment,
 //     candidate) -- a block reads and raises replica (block mod R), the reduce kernel takes the
 //     maximum over them -- because many waves raising one address serialise at tens of
-//     microseconds per atomic.  Per element only `d > max_abs` and `d > c*|b|` (c slightly
-//     below max_rel, so that no division is needed) are evaluated; when any lane trips, a rare
-//     path re-reads the item from memory, evaluates it exactly (true binary32 division) and raises
-//     the global maxima with 64-bit atomic max on the bit patterns of the non-negative doubles.
-//     Rounding is monotone, so the maximum of the rounded quotients is the rounded quotient of a
-//     tripping element.
-//   * A segment's tail (an item shorter than 4 KiB) takes the same path with guarded loads that
-//     read absent elements as 0; the few elements before a segment's first 16-byte boundary take a
-//     compact element-wise path that applies the full rule straight from memory.
+//     microseconds per atomic.  Per element only `d > max_abs` and the sign of
+//     fma(max_rel, |b|, -d) are evaluated: the fused result is the correctly rounded value of
+//     max_rel*|b| - d and rounding keeps the sign of the exact value, so "negative" is exactly
+//     "d/|b| would exceed max_rel", with no division.  When any lane trips, that vector is
+//     evaluated exactly in registers (true binary32 division for the lanes that exceed what they
+//     have seen) and the maxima are raised with a 64-bit atomic max on the bit patterns of the
+//     non-negative doubles.  Rounding is monotone, so the maximum of the rounded quotients is the
+//     rounded quotient of a tripping element.
+//   * A segment's tail (an aligned item shorter than 4 KiB) is compared in batches of several
+//     candidates per round of loads, with guarded loads that read absent elements as 0; the few
+//     elements before a segment's first 16-byte boundary take a compact element-wise path that
+//     applies the full rule straight from memory.
 //   * first_mismatch: the wave only remembers the first of its items that holds a mismatch; the
 //     reduce kernel re-reads that one item and finds the exact index.
 // reduce kernel -- one block per (segment, candidate): sums counts over the segment's slots,
-//   takes the least item index, rescans that item with the full rule, writes pass/count/first.
+//   takes the least item index, rescans that item with the full rule, folds the replicas of the
+//   maxima, writes the record.
 //
 // Blocks of the compare kernel start at different candidates so that the first, expensive, visit
 // of a (segment, candidate) pair is spread out and later visitors find the maxima already raised:
