@@ -738,6 +738,22 @@ __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
     return st;
 }
 
+// Instruction issue on a SIMD favours the oldest resident wave, and the four waves that share a
+// SIMD come from four blocks dispatched one after another: with equal work the first-dispatched
+// finishes 10 % ahead of the last, which then sets the kernel's end.  Each wave therefore walks
+// through the four issue priorities, one per candidate slice, starting from a phase that differs
+// between the waves of a SIMD, so that every wave spends the same share of its time at every
+// priority.
+__device__ __forceinline__ void set_issue_priority(uint32_t p)
+{
+    switch (p & 3u) {
+    case 0: __builtin_amdgcn_s_setprio(0); break;
+    case 1: __builtin_amdgcn_s_setprio(1); break;
+    case 2: __builtin_amdgcn_s_setprio(2); break;
+    default: __builtin_amdgcn_s_setprio(3); break;
+    }
+}
+
 // Arguments of a run of vector-loadable items of one wave.
 struct RunArgs {
     const geak_item *items;
@@ -751,6 +767,7 @@ struct RunArgs {
     uint32_t block_end;
     uint32_t K;
     uint32_t k0;
+    uint32_t priority_phase;             // dispatch round of the block: (block * 4) / grid
     float atol_f;
     float rtol_f;
     int equal_nan;
@@ -799,6 +816,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     Partial *partials = uniform_ptr(in.partials);
     const uint32_t replicas = uniform32(in.replicas), replica = uniform32(in.replica);
     const uint32_t block_end = uniform32(in.block_end), K = uniform32(in.K), k0 = uniform32(in.k0);
+    uint32_t priority = uniform32(in.priority_phase);
     const float atol_f = bits_f(uniform32(f_bits(in.atol_f))), rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
     const int equal_nan = (int)uniform32((uint32_t)in.equal_nan);
     const int lane = threadIdx.x & (kWaveSize - 1);
@@ -836,6 +854,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
         u64 abs_bits = load_bits(&recs[k * replicas].abs), rel_bits = load_bits(&recs[k * replicas].rel);
 
         for (uint32_t step = 0; step < K; ++step) {
+            set_issue_priority(priority++);
             const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
             const bool last = step + 1 == K;
             const bool has_next = !last || more;
@@ -1013,6 +1032,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.block_end = block_end;
     r.K = K;
     r.k0 = (blockIdx.x / p.replicas) % K;
+    r.priority_phase = (blockIdx.x * 4u) / gridDim.x;
     r.atol_f = p.atol_f;
     r.rtol_f = p.rtol_f;
     r.equal_nan = p.equal_nan;

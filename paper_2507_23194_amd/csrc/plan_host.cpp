@@ -114,18 +114,19 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
         // mostly of one segment, so the running maxima it has just raised are the right thresholds
         // for its next item.  Ranges are cut at equal estimated cost, not equal item count.  A wave is
         // latency-bound per 4 KiB slice, so an item costs about one unit per slice it streams
-        // (reference + K candidates); measured on mixed batches, a slice of a 16-bit dtype (twice the
-        // elements) takes about 1.3 times, and an int32 slice about 0.8 times, as long as a binary32
-        // one.  A tail or a head costs about two full items whatever its length (its loads are
-        // not hidden behind a neighbour's arithmetic), and a run that starts afresh pays for an
-        // empty pipeline.  Units: eighths of a binary32 slice.
+        // (reference + K candidates); measured per wave on mixed batches, a binary16 slice (twice the
+        // elements) takes about 1.3 times, a bfloat16 slice 1.2 times and an int32 slice 0.8 times as
+        // long as a binary32 one.  Every fresh start of the stream (a new segment, a tail) costs about
+        // three slice times whatever K is, because nothing hides its first loads; a tail costs a full
+        // item on top of that, whatever its length.  Units: sixteenths of a binary32 slice.
         const uint64_t blocks_wanted = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
         const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
         const uint64_t slices = (uint64_t)num_candidates + 1;
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
-            const uint64_t per_slice = it.dtype == GEAK_I32 ? 6 : (it.dtype == GEAK_F32 ? 8 : 10);
-            if (!(it.flags & GEAK_ITEM_FULL)) return 2 * per_slice * slices;
-            return per_slice * slices + (starts_run ? 16 : 0);
+            const uint64_t per_slice = it.dtype == GEAK_I32 ? 13 : it.dtype == GEAK_F32 ? 16 : it.dtype == GEAK_BF16 ? 19 : 21;
+            if (!(it.flags & GEAK_ITEM_ALIGNED)) return 2 * per_slice * slices;      // element-wise path
+            if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 80;
+            return per_slice * slices + (starts_run ? 46 : 0);
         };
         uint64_t total_cost = 0;
         for (uint64_t j = 0; j < hp.items.size(); ++j)

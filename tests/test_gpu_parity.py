@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import load_pins, record_tuple, expect_tuple, workload_oracle, host_threads
+from helpers import load_pins, record_tuple, expect_tuple, workload_oracle, host_threads, oracle_dense_chunked
 from paper_2507_23194_amd import binding as B
 from paper_2507_23194_amd import synth
 
@@ -105,6 +105,26 @@ def test_increasing_errors_keep_raising_the_maxima(oracle_mod):
     gpu = _dense_gpu(b, [a, a[::-1].copy()], "f32", 1e-5, 1e-5, False)
     cpu = oracle_mod.check_dense(b, [a, a[::-1].copy()], "f32", 1e-5, 1e-5, False).reshape(1, -1)
     _assert_same(gpu, cpu, "increasing errors")
+
+
+@pytest.mark.parametrize("second", [1, 300, 4096, 5000])
+def test_relative_error_margin_that_underflows(oracle_mod, second):
+    """max_rel_err is 0.75 after the first element (|7 - 4| / 4).  A later element b = 2^-149, a = 2^-148 has
+    relative error exactly 1, but 0.75 * |b| - |a - b| = -2^-151 is below half the least subnormal: a filter
+    that computes that margin gets -0 and must still count it as "may raise".  The later element sits in the
+    same vector, the same item, or the same wave's next item (4096: the wave has then read 0.75 back)."""
+    n = 1 << 23                                          # two items per wave
+    b = np.ones(n, dtype=np.float32)
+    a = b.copy()
+    b[0], a[0] = 4.0, 7.0
+    b[second] = np.float32(2.0 ** -149)
+    a[second] = np.float32(2.0 ** -148)
+    cpu = oracle_dense_chunked(oracle_mod, b, [a], "f32", 0.0, 0.0, False, host_threads()).reshape(1, -1)
+    # the oracle's own answer is fixed by hand: two mismatches, first at 0, maxima 3 and exactly 1
+    assert record_tuple(cpu[0, 0])[:3] == (0, 2, 0)
+    assert float(cpu[0, 0]["max_abs_err"]) == 3.0 and float(cpu[0, 0]["max_rel_err"]) == 1.0
+    gpu = _dense_gpu(b, [a], "f32", 0.0, 0.0, False)
+    _assert_same(gpu, cpu, f"underflowing margin, second element at {second}")
 
 
 @pytest.mark.parametrize("K", [1, 2, 5, 64, 65, 256])
