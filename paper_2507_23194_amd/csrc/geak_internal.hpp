@@ -24,9 +24,15 @@ struct Partial {
     uint32_t reserved;
 };
 
-// LDS bytes one block needs: per wave and candidate a 64-bit count and a 32-bit first-item index.
+// LDS of one block: per wave and candidate a 64-bit count and a 32-bit first-item index (rounded
+// up to 16 bytes in total), then per wave a region for the staged tolerances of a 16-bit slice
+// (2048 elements x 4 bytes).
+constexpr uint32_t kTolBytesPerWave = kItemBytes / 2 * 4;
+constexpr uint32_t lds_state_bytes(int num_candidates) {
+    return ((uint32_t)(kWavesPerBlock * num_candidates * (sizeof(unsigned long long) + sizeof(uint32_t))) + 15u) & ~15u;
+}
 inline uint32_t lds_bytes_for(int num_candidates) {
-    return (uint32_t)(kWavesPerBlock * num_candidates * (sizeof(unsigned long long) + sizeof(uint32_t)));
+    return lds_state_bytes(num_candidates) + kWavesPerBlock * kTolBytesPerWave;
 }
 
 // Host side of a plan: everything that can be decided without a device.

@@ -297,6 +297,7 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
 struct WaveState {
     uint32_t count_off;  // LDS byte offset of u64[K]: mismatching elements of the current (worker, segment) run
     uint32_t first_off;  // LDS byte offset of u32[K]: least item index of the run that holds a mismatch
+    uint32_t tol_off;    // LDS byte offset of the wave's kTolBytesPerWave region for staged tolerances
 };
 // The state is addressed through the LDS address space (DS instructions), never through flat ones.
 __device__ __forceinline__ GEAK_AS_LDS u64 *state_count(const WaveState &st) { return (GEAK_AS_LDS u64 *)st.count_off; }
@@ -405,6 +406,54 @@ template <int DT>
 __device__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> ref, const float max_abs, const float max_rel, MaxPair *rec_in);
 __device__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel, MaxPair *rec_in);
 
+// Tolerances of the staged reference slice, one per element the lane holds.  The 32-bit dtypes
+// keep them in registers.  The 16-bit dtypes hold twice the elements per slice; their 32
+// tolerances per lane live in the wave's own LDS region instead (the registers go to the loads in
+// flight), laid out in chunks of four so that chunk c of lane L sits at c * 1024 + L * 16: every
+// 16-byte access of the wave covers one contiguous KiB, free of bank conflicts.  A wave only ever
+// reads what it wrote itself, and its DS operations execute in order, so no barrier is involved.
+template <int E, bool IN_LDS> struct TolStore;
+template <int E> struct TolStore<E, false> {
+    float t[kVecPerLane * E];
+    __device__ __forceinline__ void attach(uint32_t, int) {}
+    template <int V> __device__ __forceinline__ void put(const float (&v)[E])
+    {
+#pragma unroll
+        for (int e = 0; e < E; ++e) t[V * E + e] = v[e];
+    }
+    template <int V> __device__ __forceinline__ void get(float (&v)[E]) const
+    {
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[e] = t[V * E + e];
+    }
+    template <int I> __device__ __forceinline__ float one() const { return t[I]; }
+};
+template <int E> struct TolStore<E, true> {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    uint32_t base;                   // LDS byte offset of the lane's chunk 0
+    __device__ __forceinline__ void attach(uint32_t region, int lane) { base = region + (uint32_t)lane * 16u; }
+    template <int V> __device__ __forceinline__ void put(const float (&v)[E])
+    {
+#pragma unroll
+        for (int c = 0; c < E / 4; ++c) {
+            f32x4 x = {v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]};
+            *(GEAK_AS_LDS f32x4 *)(base + (uint32_t)(V * (E / 4) + c) * 1024u) = x;
+        }
+    }
+    template <int V> __device__ __forceinline__ void get(float (&v)[E]) const
+    {
+#pragma unroll
+        for (int c = 0; c < E / 4; ++c) {
+            const f32x4 x = *(const GEAK_AS_LDS f32x4 *)(base + (uint32_t)(V * (E / 4) + c) * 1024u);
+            v[4 * c] = x[0]; v[4 * c + 1] = x[1]; v[4 * c + 2] = x[2]; v[4 * c + 3] = x[3];
+        }
+    }
+    template <int I> __device__ __forceinline__ float one() const
+    {
+        return *(const GEAK_AS_LDS float *)(base + (uint32_t)(I / 4) * 1024u + (uint32_t)(I % 4) * 4u);
+    }
+};
+
 template <int DT>
 struct FloatItem {
     typedef float Hint;                 // the running maxima of floating segments are binary32 values
@@ -416,8 +465,12 @@ struct FloatItem {
     // unpacking it again for every candidate would cost an instruction per element.
     static constexpr int kRefRegs = (DT == GEAK_BF16) ? N : kVecPerLane * 4;
     uint32_t bref[kRefRegs];
-    float tol[N];
+    static constexpr bool kTolInLds = (E == 8);
+    TolStore<E, kTolInLds> tol;
+    float tol_ahead[kTolInLds ? E : 1];     // the next vector's tolerances, on their way from LDS
     uint32_t poisoned_slots;        // wave-uniform: bit i set if any lane's element i is poisoned
+
+    __device__ __forceinline__ void attach_lds(uint32_t region, int lane) { tol.attach(region, lane); }
 
     // Stage vector V of the reference slice: keep it (packed or unpacked, see above), compute the
     // tolerance of each of its elements once, and poison the elements the bare inequality cannot judge.
@@ -429,6 +482,7 @@ struct FloatItem {
 #pragma unroll
             for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
         }
+        float tv[E];
         static_for<E>([&](auto idx) {
             constexpr int e = decltype(idx)::value;
             constexpr int i = V * E + e;
@@ -441,7 +495,7 @@ struct FloatItem {
                 prod = rtol_f * __builtin_fabsf(x);
             }
             const float t = atol_f + prod;
-            tol[i] = t;
+            tv[e] = t;
             // b NaN, b +-Inf, or the tolerance overflowed: rare, so the poison value is only worked
             // out under a wave-uniform branch.  It also records why: -1 b is NaN, -2 b is +-Inf,
             // -3 finite b with an infinite tolerance.
@@ -449,10 +503,12 @@ struct FloatItem {
             if (__builtin_amdgcn_ballot_w64(bad)) {
                 const float x = decode<DT>(q, e);
                 const float why = (x != x) ? -1.0f : (__builtin_fabsf(x) == kInfF ? -2.0f : -3.0f);
-                tol[i] = bad ? why : t;
+                tv[e] = bad ? why : t;
                 poisoned_slots |= (1u << i);
             }
         });
+        tol.template put<V>(tv);
+        if constexpr (kTolInLds && V == kVecPerLane - 1) tol.template get<0>(tol_ahead);    // for the first candidate's vector 0
     }
 
     // reference element i = V*E + e as binary32 (rare paths)
@@ -485,15 +541,25 @@ struct FloatItem {
     // Hot loop body for one 16-byte vector of one candidate.  Adds the suspects (elements with
     // !(d <= tol)) to `suspects` and ORs into `trip_abs` / `trip_rel` the lanes that may raise
     // max_abs_err / max_rel_err.  Five vector instructions per element (six for bfloat16).
-    template <int V>
+    template <int V, bool AHEAD = true>
     __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float max_rel, uint32_t &suspects,
-                                                u64 &trip_abs, u64 &trip_rel) const
+                                                u64 &trip_abs, u64 &trip_rel)
     {
+        // tolerances of this vector; in the streaming routine (AHEAD: vectors 0, 1, 2, 3, 0, ... in
+        // turn) those kept in LDS were fetched one vector ahead, and the next vector's are fetched
+        // now, behind this vector's arithmetic
+        float tv[E];
+        if constexpr (kTolInLds && AHEAD) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) tv[e] = tol_ahead[e];
+            tol.template get<(V + 1) % kVecPerLane>(tol_ahead);
+        } else {
+            tol.template get<V>(tv);
+        }
         static_for<E>([&](auto idx) {
             constexpr int e = decltype(idx)::value;
-            constexpr int i = V * E + e;
             const float d = diff<V, e>(q);
-            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d) <= tol[i])));
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d) <= tv[e])));
             trip_abs |= __builtin_amdgcn_ballot_w64(__builtin_fabsf(d) > max_abs);
             trip_rel |= negative_mask(rel_margin<V, e>(max_rel, d));
             // keep each OR a running chain in one scalar register pair (a balanced tree would
@@ -513,7 +579,7 @@ struct FloatItem {
             if (poisoned_slots & (1u << i)) {
                 const float a = decode<DT>(q, e);
                 const float x = ref_value<V, e>();
-                float why = tol[i];
+                float why = tol.template one<i>();
                 asm volatile("" : "+v"(why));   // evaluate here, per candidate: hoisted lane masks would not fit the scalar file
                 const bool ok = (why == -1.0f) ? (equal_nan && (a != a))
                               : (why == -2.0f) ? (a == x)
@@ -561,7 +627,7 @@ struct FloatItem {
     {
         RefVec<DT> r;
         TolVec<DT> t;
-        static_for<E>([&](auto idx) { constexpr int e = decltype(idx)::value; r.b[e] = ref_value<V, e>(); t.t[e] = tol[V * E + e]; });
+        static_for<E>([&](auto idx) { constexpr int e = decltype(idx)::value; r.b[e] = ref_value<V, e>(); t.t[e] = tol.template one<V * E + e>(); });
         return false_suspects_vector<DT>(q, r, t, (poisoned_slots >> (V * E)) & ((1u << E) - 1u), equal_nan);
     }
     template <int V>
@@ -636,6 +702,7 @@ struct IntItem {
     static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
     static constexpr int E = 4;
     uint32_t bref[kVecPerLane * 4];
+    __device__ __forceinline__ void attach_lds(uint32_t, int) {}
     static constexpr uint32_t poisoned_slots = 0;
 
     template <int V>
@@ -645,7 +712,7 @@ struct IntItem {
         for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
     }
     // Any unequal element is a mismatch and the only kind of element that can raise a maximum.
-    template <int V>
+    template <int V, bool AHEAD = true>
     __device__ __forceinline__ void compare_vec(const u32x4 &q, double, double, uint32_t &suspects, u64 &trip_abs, u64 &) const
     {
 #pragma unroll
@@ -735,6 +802,7 @@ __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
     WaveState st;
     st.count_off = uniform32(in.count_off);
     st.first_off = uniform32(in.first_off);
+    st.tol_off = uniform32(in.tol_off);
     return st;
 }
 
@@ -778,14 +846,14 @@ struct RunArgs {
 // the reference slice of the wave's next item).  Four loads per lane stay in flight and each has a
 // whole element's worth of compute to land.
 template <int DT, int V, bool OUTLINE = false, typename Item>
-__device__ __forceinline__ void stream_step(const Item &ref, u32x4 &slot, const unsigned char *next, bool has_next,
+__device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsigned char *next, bool has_next,
                                             uint32_t next_n, const bool next_full, typename Item::Hint &max_abs,
                                             typename Item::Hint &max_rel, int equal_nan, MaxPair *rec, int lane,
                                             uint32_t &bad)
 {
     constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
     u64 trip_abs = 0, trip_rel = 0;
-    ref.template compare_vec<V>(slot, max_abs, max_rel, bad, trip_abs, trip_rel);
+    ref.template compare_vec<V, !OUTLINE>(slot, max_abs, max_rel, bad, trip_abs, trip_rel);
     if (ref.poisoned_slots & kVecMask) {
         if constexpr (OUTLINE) bad -= ref.template false_suspects_call<V>(slot, equal_nan);
         else bad -= ref.template false_suspects_vec<V>(slot, equal_nan);
@@ -824,6 +892,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     uint32_t j = uniform32(in.first_item);
     geak_item it = load_work_item(items, j);
     Item ref;
+    ref.attach_lds(st.tol_off, lane);
     u32x4 cur[kVecPerLane];
     constexpr bool full = true;
 #pragma unroll
@@ -933,6 +1002,7 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     };
 
     Item ref;
+    ref.attach_lds(st.tol_off, lane);
     {
         u32x4 r[kVecPerLane];
 #pragma unroll
@@ -1016,6 +1086,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     const uint32_t lds_base = (uint32_t)(uintptr_t)(GEAK_AS_LDS unsigned char *)lds;
     st.count_off = lds_base + (uint32_t)sizeof(u64) * wave * K;
     st.first_off = lds_base + (uint32_t)sizeof(u64) * kWavesPerBlock * K + (uint32_t)sizeof(uint32_t) * wave * K;
+    st.tol_off = lds_base + lds_state_bytes((int)K) + kTolBytesPerWave * wave;
 
     const GEAK_AS_CONSTANT uint32_t *block_first = (const GEAK_AS_CONSTANT uint32_t *)p.block_first;
     const uint32_t block_begin = block_first[blockIdx.x];
