@@ -466,6 +466,7 @@ struct FloatItem {
     static constexpr int kRefRegs = (DT == GEAK_BF16) ? N : kVecPerLane * 4;
     uint32_t bref[kRefRegs];
     static constexpr bool kTolInLds = (E == 8);
+    static constexpr bool kRaiseOutOfLine = false;
     TolStore<E, kTolInLds> tol;
     float tol_ahead[kTolInLds ? E : 1];     // the next vector's tolerances, on their way from LDS
     uint32_t poisoned_slots;        // wave-uniform: bit i set if any lane's element i is poisoned
@@ -701,6 +702,9 @@ struct IntItem {
     typedef double Hint;                // |a - b| reaches 2^32 - 1 and the quotient is binary64
     static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
     static constexpr int E = 4;
+    // the exact evaluation is binary64 arithmetic with a division: inlined into the stream it costs
+    // the loop its registers, so it is always called
+    static constexpr bool kRaiseOutOfLine = true;
     uint32_t bref[kVecPerLane * 4];
     __device__ __forceinline__ void attach_lds(uint32_t, int) {}
     static constexpr uint32_t poisoned_slots = 0;
@@ -860,7 +864,7 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
     }
     if (max_rel == (typename Item::Hint)kInfF) trip_rel = 0;       // nothing exceeds +Inf
     if (trip_abs | trip_rel) {
-        if constexpr (OUTLINE) ref.template raise_call<V>(slot, max_abs, max_rel, rec);
+        if constexpr (OUTLINE || Item::kRaiseOutOfLine) ref.template raise_call<V>(slot, max_abs, max_rel, rec);
         else ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
     }
     if (has_next) slot = load_vec<DT>(next, lane, V, next_n, next_full);
