@@ -144,29 +144,35 @@ typedef struct {
     uint32_t reserved[2];
 } geak_plan_info;
 
-/* One work item, as the compare kernel sees it. */
+/* One work item, as the compare kernel sees it.  32 bytes. */
 typedef struct {
     uint64_t byte_offset;  /* of the item's first element, within every packed buffer */
     uint64_t elem_start;   /* flat index of that element within its segment */
     uint32_t segment;
     uint32_t slot;         /* workspace slot its run accumulates into */
-    uint32_t numel;        /* 1 .. item_bytes / element size */
+    uint16_t numel;        /* 1 .. item_bytes / element size */
     uint8_t  dtype;
     uint8_t  flags;        /* GEAK_ITEM_* */
-    uint16_t reserved;
+    uint32_t next;         /* index of the next item of the same wavefront, GEAK_NO_ITEM after its last */
 } geak_item;
 
+#define GEAK_NO_ITEM 0xFFFFFFFFu
 #define GEAK_ITEM_FULL  1u /* 16-byte aligned start and exactly item_bytes long: unguarded vector loads */
-#define GEAK_ITEM_FIRST 2u /* first item of its (worker, segment) run: running state is reset */
+#define GEAK_ITEM_FIRST 2u /* first item of its (wavefront, segment) run: running state is reset */
 #define GEAK_ITEM_LAST  4u /* last item of its run: running state is written to the slot */
 #define GEAK_ITEM_ALIGNED 8u /* 16-byte aligned start (FULL implies it): vector loads, guarded at the end */
 
 geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
 
 /* Copies up to `capacity` entries of the block table into `out` (host); returns its length,
- * grid_blocks + 1.  Block b of the compare kernel owns items [table[b], table[b + 1]); wave w of the
- * block takes every (block_threads / 64)-th of them, starting at w. */
+ * grid_blocks + 1.  Block b of the compare kernel owns items [table[b], table[b + 1]). */
 uint64_t geak_check_plan_blocks(const geak_plan *plan, uint32_t *out, uint64_t capacity);
+
+/* Copies up to `capacity` entries of the wavefront table into `out` (host); returns its length,
+ * grid_blocks * (block_threads / 64).  Entry b * (block_threads / 64) + w is the first item of
+ * wavefront w of block b (GEAK_NO_ITEM if it has none); the wavefront then follows the items'
+ * `next` links, which stay inside the block's range and ascend. */
+uint64_t geak_check_plan_waves(const geak_plan *plan, uint32_t *out, uint64_t capacity);
 
 /* Copies up to `capacity` items into `out` (host); returns the total number of items. */
 uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t capacity);

@@ -31,7 +31,8 @@ SEGMENT_DTYPE = np.dtype([("byte_offset", "<u8"), ("numel", "<u8"), ("dtype", "<
 RESULT_DTYPE = np.dtype([("pass", "<i4"), ("reserved", "<i4"), ("mismatch_count", "<u8"),
                          ("first_mismatch", "<i8"), ("max_abs_err", "<f8"), ("max_rel_err", "<f8")])
 ITEM_DTYPE = np.dtype([("byte_offset", "<u8"), ("elem_start", "<u8"), ("segment", "<u4"), ("slot", "<u4"),
-                       ("numel", "<u4"), ("dtype", "u1"), ("flags", "u1"), ("reserved", "<u2")])
+                       ("numel", "<u2"), ("dtype", "u1"), ("flags", "u1"), ("next", "<u4")])
+GEAK_NO_ITEM = 0xFFFFFFFF
 
 
 class PlanInfo(ctypes.Structure):
@@ -88,6 +89,8 @@ def library() -> ctypes.CDLL:
         lib.geak_check_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
         lib.geak_check_plan_blocks.restype = u64
         lib.geak_check_plan_blocks.argtypes = [vp, vp, u64]
+        lib.geak_check_plan_waves.restype = u64
+        lib.geak_check_plan_waves.argtypes = [vp, vp, u64]
         lib.geak_check_plan_items.restype = u64
         lib.geak_check_plan_items.argtypes = [vp, vp, u64]
         lib.geak_check_profile_enable.restype = ctypes.c_int
@@ -100,7 +103,7 @@ def library() -> ctypes.CDLL:
 
 EXPORTED = ["geak_check_plan", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
-            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_profile_enable", "geak_check_profile_read"]
+            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read"]
 
 
 # ---- one Python function per C entry point -------------------------------------------------------
@@ -173,6 +176,14 @@ def geak_check_plan_blocks(plan) -> np.ndarray:
     out = np.zeros(n, dtype=np.uint32)
     if n:
         library().geak_check_plan_blocks(plan, out.ctypes.data, n)
+    return out
+
+
+def geak_check_plan_waves(plan) -> np.ndarray:
+    n = int(library().geak_check_plan_waves(plan, None, 0))
+    out = np.zeros(n, dtype=np.uint32)
+    if n:
+        library().geak_check_plan_waves(plan, out.ctypes.data, n)
     return out
 
 

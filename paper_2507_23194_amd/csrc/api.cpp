@@ -13,7 +13,7 @@ struct geak_plan {
     // device copies of the work table
     geak_item *items_dev = nullptr;
     uint32_t *slot_begin_dev = nullptr;
-    uint32_t *block_first_dev = nullptr;
+    uint32_t *wave_first_dev = nullptr;
     // optional timing ring
     std::vector<hipEvent_t> ev_start, ev_stop;
     uint32_t ev_next = 0, ev_used = 0;
@@ -40,12 +40,12 @@ void free_device_side(geak_plan *p)
     DeviceGuard g(p->device);
     if (p->items_dev) (void)hipFree(p->items_dev);
     if (p->slot_begin_dev) (void)hipFree(p->slot_begin_dev);
-    if (p->block_first_dev) (void)hipFree(p->block_first_dev);
+    if (p->wave_first_dev) (void)hipFree(p->wave_first_dev);
     for (auto e : p->ev_start) (void)hipEventDestroy(e);
     for (auto e : p->ev_stop) (void)hipEventDestroy(e);
     p->items_dev = nullptr;
     p->slot_begin_dev = nullptr;
-    p->block_first_dev = nullptr;
+    p->wave_first_dev = nullptr;
     p->ev_start.clear();
     p->ev_stop.clear();
 }
@@ -88,13 +88,13 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
         const size_t slot_bytes = p->host.slot_begin.size() * sizeof(uint32_t);
         bool ok = g.ok;
         if (ok && item_bytes) ok = hipMalloc((void **)&p->items_dev, item_bytes) == hipSuccess;
-        const size_t block_bytes = p->host.block_first.size() * sizeof(uint32_t);
+        const size_t wave_bytes = p->host.wave_first.size() * sizeof(uint32_t);
         if (ok) ok = hipMalloc((void **)&p->slot_begin_dev, slot_bytes) == hipSuccess;
-        if (ok) ok = hipMalloc((void **)&p->block_first_dev, block_bytes) == hipSuccess;
+        if (ok) ok = hipMalloc((void **)&p->wave_first_dev, wave_bytes) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_ENOMEM; }
         if (item_bytes) ok = hipMemcpy(p->items_dev, p->host.items.data(), item_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->slot_begin_dev, p->host.slot_begin.data(), slot_bytes, hipMemcpyHostToDevice) == hipSuccess;
-        if (ok) ok = hipMemcpy(p->block_first_dev, p->host.block_first.data(), block_bytes, hipMemcpyHostToDevice) == hipSuccess;
+        if (ok) ok = hipMemcpy(p->wave_first_dev, p->host.wave_first.data(), wave_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_EHIP; }
     }
     *out = p;
@@ -194,7 +194,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.rtol_f = hp.rtol_f;
         ca.equal_nan = hp.equal_nan;
         ca.reserved = 0;
-        ca.block_first = plan->block_first_dev;
+        ca.wave_first = plan->wave_first_dev;
 
         geak_plan *mp = const_cast<geak_plan *>(plan);      // timing ring only; documented as not re-entrant
         const bool timed = !mp->ev_start.empty();
@@ -274,6 +274,17 @@ uint64_t geak_check_plan_blocks(const geak_plan *plan, uint32_t *out, uint64_t c
         if (n) std::memcpy(out, bf.data(), n * sizeof(uint32_t));
     }
     return bf.size();
+}
+
+uint64_t geak_check_plan_waves(const geak_plan *plan, uint32_t *out, uint64_t capacity)
+{
+    if (!plan) return 0;
+    const auto &wf = plan->host.wave_first;
+    if (out) {
+        const uint64_t n = capacity < wf.size() ? capacity : wf.size();
+        if (n) std::memcpy(out, wf.data(), n * sizeof(uint32_t));
+    }
+    return wf.size();
 }
 
 uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t capacity)

@@ -47,6 +47,7 @@ struct HostPlan {
     uint32_t grid_blocks = 1;
     uint32_t replicas = 1;                 // replicas of the running maxima per (segment, candidate)
     std::vector<uint32_t> block_first;     // size grid_blocks + 1: block b owns items [block_first[b], block_first[b + 1])
+    std::vector<uint32_t> wave_first;      // size grid_blocks * kWavesPerBlock: first item of each wave's list (kNoItem: none)
     uint32_t max_blocks = 1;               // compute units x resident blocks per unit
 };
 
@@ -95,7 +96,7 @@ struct CompareArgs {
     float rtol_f;
     int equal_nan;
     int reserved;
-    const uint32_t *block_first;         // grid_blocks + 1 entries
+    const uint32_t *wave_first;          // grid_blocks * kWavesPerBlock entries
 };
 
 struct ReduceArgs {

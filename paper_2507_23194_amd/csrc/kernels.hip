@@ -73,10 +73,10 @@ __device__ __forceinline__ geak_item load_work_item(const geak_item *items, uint
     it.elem_start = w[1];
     it.segment = (uint32_t)w2;
     it.slot = (uint32_t)(w2 >> 32);
-    it.numel = (uint32_t)w3;
-    it.dtype = (uint8_t)(w3 >> 32);
-    it.flags = (uint8_t)(w3 >> 40);
-    it.reserved = 0;
+    it.numel = (uint16_t)w3;
+    it.dtype = (uint8_t)(w3 >> 16);
+    it.flags = (uint8_t)(w3 >> 24);
+    it.next = (uint32_t)(w3 >> 32);
     return it;
 }
 
@@ -835,8 +835,8 @@ struct RunArgs {
     Partial *partials;
     uint32_t replicas;                   // power of two
     uint32_t replica;                    // the one this block reads and raises
-    uint32_t first_item;                 // index of the run's first item; the wave owns every 4th item up to block_end
-    uint32_t block_end;
+    uint32_t first_item;                 // index of the run's first item; the wave follows the items' next links
+    uint32_t num_items;                  // table length: no link is followed past it
     uint32_t K;
     uint32_t k0;
     uint32_t priority_phase;             // dispatch round of the block: (block * 4) / grid
@@ -887,7 +887,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     MaxPair *board = uniform_ptr(in.board);
     Partial *partials = uniform_ptr(in.partials);
     const uint32_t replicas = uniform32(in.replicas), replica = uniform32(in.replica);
-    const uint32_t block_end = uniform32(in.block_end), K = uniform32(in.K), k0 = uniform32(in.k0);
+    const uint32_t num_items = uniform32(in.num_items), K = uniform32(in.K), k0 = uniform32(in.k0);
     uint32_t priority = uniform32(in.priority_phase);
     const float atol_f = bits_f(uniform32(f_bits(in.atol_f))), rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
     const int equal_nan = (int)uniform32((uint32_t)in.equal_nan);
@@ -905,8 +905,8 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
 
     for (;;) {
         // look ahead: does the wave's next item continue the run?
-        const uint32_t jn = j + kWavesPerBlock;
-        bool more = jn < block_end;
+        const uint32_t jn = it.next;
+        bool more = jn < num_items;                 // kNoItem ends the list
         geak_item nx = it;
         if (more) {
             nx = load_work_item(items, jn);
@@ -953,7 +953,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
         it = nx;
         j = jn;
     }
-    return j + kWavesPerBlock;
+    return it.next;
 }
 
 // ---- a segment's tail: one item that starts aligned but is shorter than a full item -----------------
@@ -1092,10 +1092,6 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     st.first_off = lds_base + (uint32_t)sizeof(u64) * kWavesPerBlock * K + (uint32_t)sizeof(uint32_t) * wave * K;
     st.tol_off = lds_base + lds_state_bytes((int)K) + kTolBytesPerWave * wave;
 
-    const GEAK_AS_CONSTANT uint32_t *block_first = (const GEAK_AS_CONSTANT uint32_t *)p.block_first;
-    const uint32_t block_begin = block_first[blockIdx.x];
-    uint32_t block_end = block_first[blockIdx.x + 1];
-    if (block_end > p.num_items) block_end = p.num_items;    // never index past the table
     RunArgs r;
     r.items = p.items;
     r.ref = p.ref;
@@ -1104,7 +1100,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.replicas = p.replicas;
     r.replica = blockIdx.x & (p.replicas - 1);
     r.partials = p.partials;
-    r.block_end = block_end;
+    r.num_items = p.num_items;
     r.K = K;
     r.k0 = (blockIdx.x / p.replicas) % K;
     r.priority_phase = (blockIdx.x * 4u) / gridDim.x;
@@ -1112,8 +1108,10 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.rtol_f = p.rtol_f;
     r.equal_nan = p.equal_nan;
 
-    uint32_t j = block_begin + wave;
-    while (j < block_end) {
+    // the wave's list of items: its first one from the wave table, then along the next links
+    const GEAK_AS_CONSTANT uint32_t *wave_first = (const GEAK_AS_CONSTANT uint32_t *)p.wave_first;
+    uint32_t j = wave_first[blockIdx.x * kWavesPerBlock + wave];
+    while (j < p.num_items) {                                   // kNoItem ends the list; nothing past the table is read
         const geak_item it = load_work_item(p.items, j);
         if (it.flags & GEAK_ITEM_ALIGNED) {
             // a run of vector-loadable items: handled, state bookkeeping included, by the dtype's routine
@@ -1133,7 +1131,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_BF16: process_tail<GEAK_BF16>(r, st); break;
                 default:        process_tail<GEAK_I32>(r, st); break;
                 }
-                next_j = j + kWavesPerBlock;
+                next_j = it.next;
             }
             j = __builtin_amdgcn_readfirstlane(next_j);
             continue;
@@ -1141,7 +1139,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
         if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
         process_head(it, j, p, st, lane);
         if (it.flags & GEAK_ITEM_LAST) end_run(st, p.partials, it.slot, K, lane);
-        j += kWavesPerBlock;
+        j = it.next;
     }
 }
 

@@ -96,7 +96,8 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
                 it.byte_offset = g.byte_offset + done * w;
                 it.elem_start = done;
                 it.segment = (uint32_t)s;
-                it.numel = (uint32_t)n;
+                it.numel = (uint16_t)n;
+                it.next = kNoItem;
                 it.dtype = (uint8_t)g.dtype;
                 it.flags = (uint8_t)((full ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0));
                 hp.items.push_back(it);
@@ -116,8 +117,9 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
         // latency-bound per 4 KiB slice, so an item costs about one unit per slice it streams
         // (reference + K candidates); measured per wave on mixed batches, a binary16 slice (twice the
         // elements) takes about 1.3 times, a bfloat16 slice 1.2 times and an int32 slice 0.8 times as
-        // long as a binary32 one.  Every fresh start of the stream (a new segment, a tail) costs about
-        // three slice times whatever K is, because nothing hides its first loads; a tail costs a full
+        // long as a binary32 one.  Every fresh start of the stream (a new segment, a tail) is priced at
+        // about six slice times whatever K is -- nothing hides its first loads, and waves with many
+        // starts were the last to finish until they were priced this high -- and a tail at a full
         // item on top of that, whatever its length.  Units: sixteenths of a binary32 slice.
         const uint64_t blocks_wanted = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
         const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
@@ -125,12 +127,12 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
             const uint64_t per_slice = it.dtype == GEAK_I32 ? 13 : it.dtype == GEAK_F32 ? 16 : it.dtype == GEAK_BF16 ? 19 : 21;
             if (!(it.flags & GEAK_ITEM_ALIGNED)) return 2 * per_slice * slices;      // element-wise path
-            if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 80;
-            return per_slice * slices + (starts_run ? 46 : 0);
+            if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 140;
+            return per_slice * slices + (starts_run ? 100 : 0);
         };
         uint64_t total_cost = 0;
         for (uint64_t j = 0; j < hp.items.size(); ++j)
-            total_cost += item_cost(hp.items[j], j == 0 || hp.items[j - 1].segment != hp.items[j].segment);
+            total_cost += item_cost(hp.items[j], j > 0 && hp.items[j - 1].segment != hp.items[j].segment);
         hp.block_first.clear();
         hp.block_first.push_back(0);
         {
@@ -140,19 +142,27 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
                 const uint64_t b = hp.block_first.size();          // blocks opened so far (1-based index of the current one)
                 if (b < target_blocks && j > hp.block_first.back() && acc * target_blocks >= total_cost * b)
                     hp.block_first.push_back((uint32_t)j);
-                acc += item_cost(hp.items[j], j == 0 || hp.items[j - 1].segment != hp.items[j].segment);
+                acc += item_cost(hp.items[j], j > 0 && hp.items[j - 1].segment != hp.items[j].segment);
             }
         }
         hp.block_first.push_back((uint32_t)hp.items.size());
         hp.grid_blocks = (uint32_t)(hp.block_first.size() - 1);    // >= 1; the last entry closes the last block
         if (hp.items.empty()) hp.grid_blocks = 1;
 
+        // Inside a block every item goes to the wave that has the least estimated cost so far (in
+        // table order, so a wave's list ascends and neighbouring items mostly go to neighbouring
+        // waves): with equal items that is a plain interleave, and a tail, a head or a heavier dtype
+        // no longer makes one wave of the block finish an item or two after the others.  Each wave
+        // follows its list through the items' `next` links.
+        //
         // Runs and slots.  Scanning the table in order, a wave opens a new run (and a new slot)
         // whenever the segment of its next item differs from the segment of its previous one.
         // Items of one segment are contiguous in the table, so the slots opened while scanning a
         // segment are contiguous too.
         const uint64_t workers = (uint64_t)hp.grid_blocks * kWavesPerBlock;
+        hp.wave_first.assign(workers, kNoItem);
         std::vector<uint32_t> run_segment(workers, 0xFFFFFFFFu), run_slot(workers, 0), last_item(workers, kNoItem);
+        std::vector<uint64_t> load(workers, 0);
         uint64_t slot_cursor = 0;
         uint64_t seg_cursor = 0;
         uint64_t block = 0;
@@ -160,8 +170,14 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
             geak_item &it = hp.items[j];
             while (seg_cursor <= it.segment) hp.slot_begin[seg_cursor++] = (uint32_t)slot_cursor;
             while (j >= hp.block_first[block + 1]) ++block;
-            const uint64_t worker = block * kWavesPerBlock + (j - hp.block_first[block]) % kWavesPerBlock;
-            if (run_segment[worker] != it.segment) {
+            uint64_t worker = block * kWavesPerBlock;
+            for (uint64_t w = worker + 1; w < (block + 1) * kWavesPerBlock; ++w)
+                if (load[w] < load[worker]) worker = w;
+            const bool new_run = run_segment[worker] != it.segment;
+            load[worker] += item_cost(it, new_run);
+            if (last_item[worker] == kNoItem) hp.wave_first[worker] = (uint32_t)j;
+            else hp.items[last_item[worker]].next = (uint32_t)j;
+            if (new_run) {
                 if (last_item[worker] != kNoItem) hp.items[last_item[worker]].flags |= GEAK_ITEM_LAST;
                 run_segment[worker] = it.segment;
                 run_slot[worker] = (uint32_t)slot_cursor++;

@@ -140,11 +140,26 @@ def _check_table(segs, K):
         # items of one segment are contiguous in the table and segments appear in order
         seg_ids = items["segment"].astype(np.int64)
         assert (np.diff(seg_ids) >= 0).all()
-        # run structure: following one worker through the table, FIRST opens and LAST closes each
-        # (worker, segment) run, the slot is constant inside a run and unique to it
+        # every wave's list (its first item, then along the next links) stays inside its block's
+        # range and ascends; together the lists hold every item exactly once
+        first = B.geak_check_plan_waves(plan).astype(np.int64)
+        assert len(first) == info.grid_blocks * waves
+        nxt = items["next"].astype(np.int64)
+        sequences, owner = [], np.full(len(items), -1, dtype=np.int64)
+        for wv, j in enumerate(first):
+            b = wv // waves
+            mine = []
+            while j != B.GEAK_NO_ITEM:
+                assert blocks[b] <= j < blocks[b + 1] and owner[j] == -1
+                assert not mine or j > mine[-1]
+                owner[j] = wv
+                mine.append(int(j))
+                j = nxt[j]
+            sequences.append(items[mine])
+        assert (owner >= 0).all()
+        # run structure: following one wave through its list, FIRST opens and LAST closes each
+        # (wave, segment) run, the slot is constant inside a run and unique to it
         seen_slots = {}
-        sequences = [items[blocks[b]:blocks[b + 1]][w::waves] for b in range(info.grid_blocks) for w in range(waves)]
-        assert sum(len(m) for m in sequences) == len(items)
         for mine in sequences:
             open_slot = None
             for it in mine:
@@ -216,8 +231,22 @@ def test_work_table_many_segments_uneven_blocks(lib):
     info = B.geak_check_plan_info(plan)
     assert info.num_items % info.grid_blocks != 0
     # ranges are cut at equal estimated cost: blocks of tails hold fewer items than blocks of full items
-    sizes = np.diff(B.geak_check_plan_blocks(plan).astype(np.int64))
+    blocks = B.geak_check_plan_blocks(plan).astype(np.int64)
+    sizes = np.diff(blocks)
     assert sizes.min() >= 1 and sizes.max() > sizes.min()
+    # inside a block the items are dealt by cost too; a tail weighs about two and a half items and a
+    # 16-bit item about one and a half int32 items, so the counts of a block's waves stay close
+    items = B.geak_check_plan_items(plan)
+    first = B.geak_check_plan_waves(plan).astype(np.int64)
+    counts = np.zeros(len(first), dtype=np.int64)
+    for wv, j in enumerate(first):
+        while j != B.GEAK_NO_ITEM:
+            counts[wv] += 1
+            j = int(items["next"][j])
+    per_block = counts.reshape(info.grid_blocks, 4)
+    assert counts.sum() == info.num_items
+    assert (per_block.max(axis=1) - per_block.min(axis=1) <= 4).all()
+    assert (per_block.max(axis=1) - per_block.min(axis=1)).mean() < 1.5
     B.geak_check_destroy(plan)
 
 
