@@ -544,7 +544,7 @@ struct FloatItem {
     // max_abs_err / max_rel_err.  Five vector instructions per element (six for bfloat16).
     template <int V, bool AHEAD = true>
     __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float max_rel, uint32_t &suspects,
-                                                u64 &trip_abs, u64 &trip_rel)
+                                                u64 &trip_abs, u64 &trip_rel, int equal_nan)
     {
         // tolerances of this vector; in the streaming routine (AHEAD: vectors 0, 1, 2, 3, 0, ... in
         // turn) those kept in LDS were fetched one vector ahead, and the next vector's are fetched
@@ -567,11 +567,18 @@ struct FloatItem {
             // hold every lane mask live at once)
             asm volatile("" : "+s"(trip_abs), "+s"(trip_rel));
         });
+        // Poisoned elements were all reported as suspects; take off those that the NaN / Inf rule
+        // accepts.  In the streaming routine this happens here, while the vector's tolerances (which
+        // say why an element is poisoned) are at hand.
+        if constexpr (AHEAD) {
+            constexpr uint32_t kVecMask = ((E == 8) ? 0xFFu : 0xFu) << (V * E);
+            if (poisoned_slots & kVecMask) suspects -= false_suspects_vec<V>(q, tv, equal_nan);
+        }
     }
 
-    // Poisoned elements were all reported as suspects; count those that the NaN / Inf rule accepts.
+    // Number of poisoned elements of vector V that the NaN / Inf rule accepts; tv: the vector's tolerances.
     template <int V>
-    __device__ __forceinline__ uint32_t false_suspects_vec(const u32x4 &q, int equal_nan) const
+    __device__ __forceinline__ uint32_t false_suspects_vec(const u32x4 &q, const float (&tv)[E], int equal_nan) const
     {
         uint32_t n = 0;
         static_for<E>([&](auto idx) {
@@ -580,7 +587,7 @@ struct FloatItem {
             if (poisoned_slots & (1u << i)) {
                 const float a = decode<DT>(q, e);
                 const float x = ref_value<V, e>();
-                float why = tol.template one<i>();
+                float why = tv[e];
                 asm volatile("" : "+v"(why));   // evaluate here, per candidate: hoisted lane masks would not fit the scalar file
                 const bool ok = (why == -1.0f) ? (equal_nan && (a != a))
                               : (why == -2.0f) ? (a == x)
@@ -717,7 +724,7 @@ struct IntItem {
     }
     // Any unequal element is a mismatch and the only kind of element that can raise a maximum.
     template <int V, bool AHEAD = true>
-    __device__ __forceinline__ void compare_vec(const u32x4 &q, double, double, uint32_t &suspects, u64 &trip_abs, u64 &) const
+    __device__ __forceinline__ void compare_vec(const u32x4 &q, double, double, uint32_t &suspects, u64 &trip_abs, u64 &, int) const
     {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
@@ -726,8 +733,6 @@ struct IntItem {
             trip_abs |= m;
         }
     }
-    template <int V>
-    __device__ __forceinline__ uint32_t false_suspects_vec(const u32x4 &, int) const { return 0; }
     template <int V>
     __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &, int) const { return 0; }
     template <int V>
@@ -855,12 +860,11 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
                                             typename Item::Hint &max_rel, int equal_nan, MaxPair *rec, int lane,
                                             uint32_t &bad)
 {
-    constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
     u64 trip_abs = 0, trip_rel = 0;
-    ref.template compare_vec<V, !OUTLINE>(slot, max_abs, max_rel, bad, trip_abs, trip_rel);
-    if (ref.poisoned_slots & kVecMask) {
-        if constexpr (OUTLINE) bad -= ref.template false_suspects_call<V>(slot, equal_nan);
-        else bad -= ref.template false_suspects_vec<V>(slot, equal_nan);
+    ref.template compare_vec<V, !OUTLINE>(slot, max_abs, max_rel, bad, trip_abs, trip_rel, equal_nan);
+    if constexpr (OUTLINE) {
+        constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
+        if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_call<V>(slot, equal_nan);
     }
     if (max_rel == (typename Item::Hint)kInfF) trip_rel = 0;       // nothing exceeds +Inf
     if (trip_abs | trip_rel) {
