@@ -150,6 +150,21 @@ def main():
     kernel_ms = B.geak_check_profile_read(ck.plan, args.steps)
     B.geak_check_profile_enable(ck.plan, 0)
 
+    # what a kernel that only reads the same bytes reaches on this machine (not part of the step)
+    probe_gbps = None
+    if len(w.cands) < 256:
+        for _ in range(3):
+            ck.read_probe(w.ref, w.cands)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for a, b in ev:
+            a.record()
+            ck.read_probe(w.ref, w.cands)
+            b.record()
+        torch.cuda.synchronize()
+        probe_ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
+        probe_gbps = alg_bytes / (probe_ms * 1e-3) / 1e9
+        ck.run(w.ref, w.cands)                       # the probe used the workspace: produce the records again
+
     rec = ck.read()
     n_fail = int((rec["pass"] == 0).sum())
     # the records must agree with what the generator planted (cheap sanity check, outside the timed region)
@@ -183,7 +198,9 @@ def main():
         "roofline": {"kernel": "compare_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None else measured_traffic(args.config),
-                     "kernel_ms_avg": k_ms, "kernel_ms_min": float(np.min(kernel_ms)) if len(kernel_ms) else None},
+                     "kernel_ms_avg": k_ms, "kernel_ms_min": float(np.min(kernel_ms)) if len(kernel_ms) else None,
+                     "read_only_kernel_GBps": probe_gbps,
+                     "frac_of_read_only_kernel": (achieved / probe_gbps) if probe_gbps else None},
     }
     if not args.no_cpu_baseline:
         budget = {1: (8, 1 << 20), 2: (32, 1 << 26), 3: (16, 1 << 28), 4: (4, 0), 5: (8, 1 << 28)}[args.config]

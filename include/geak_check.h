@@ -187,6 +187,16 @@ uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t c
 geak_status geak_check_profile_enable(geak_plan *plan, uint32_t num_pairs);
 uint64_t    geak_check_profile_read(geak_plan *plan, float *ms_out, uint64_t capacity);
 
+/* ---- read probe (measurement aid, not part of the check) -------------------------------------
+ * Enqueues a kernel that only reads, with 16-byte loads, the same bytes a run of this plan reads
+ * (the span of the packed reference and of every candidate that the segments cover) and computes
+ * nothing from them: the rate it reaches is what this machine's memory system delivers to any
+ * kernel with this traffic, the yardstick beside the nominal HBM peak.  Arguments as for
+ * geak_check_run (at most GEAK_MAX_CANDIDATES - 1 candidates); the workspace is used as scratch and
+ * no results are produced.  The caller times it on its stream. */
+geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                                  void *workspace_dev, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -93,6 +93,8 @@ def library() -> ctypes.CDLL:
         lib.geak_check_plan_waves.argtypes = [vp, vp, u64]
         lib.geak_check_plan_items.restype = u64
         lib.geak_check_plan_items.argtypes = [vp, vp, u64]
+        lib.geak_check_read_probe.restype = ctypes.c_int
+        lib.geak_check_read_probe.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp]
         lib.geak_check_profile_enable.restype = ctypes.c_int
         lib.geak_check_profile_enable.argtypes = [vp, ctypes.c_uint32]
         lib.geak_check_profile_read.restype = u64
@@ -103,7 +105,7 @@ def library() -> ctypes.CDLL:
 
 EXPORTED = ["geak_check_plan", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
-            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read"]
+            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe"]
 
 
 # ---- one Python function per C entry point -------------------------------------------------------
@@ -149,6 +151,12 @@ def geak_check_run(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: 
     """All pointers are device addresses as integers; stream is a hipStream_t as integer (0 = default)."""
     arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
     return int(library().geak_check_run(plan, ref_ptr, arr, workspace_ptr, results_ptr, stream))
+
+
+def geak_check_read_probe(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: int, stream: int) -> int:
+    """Enqueue the read-only probe over the bytes a run of the plan reads (measurement aid)."""
+    arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
+    return int(library().geak_check_read_probe(plan, ref_ptr, arr, workspace_ptr, stream))
 
 
 def geak_check_destroy(plan) -> None:
@@ -231,6 +239,15 @@ class Checker:
                             self.workspace.data_ptr(), self.results.data_ptr(), stream)
         if st != GEAK_OK:
             raise GeakError(st, "geak_check_run")
+
+    def read_probe(self, ref, cands) -> None:
+        """Enqueue the read-only probe over the same tensors on torch's current stream."""
+        import torch
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        st = geak_check_read_probe(self.plan, ref.data_ptr(), [c.data_ptr() for c in cands],
+                                   self.workspace.data_ptr(), stream)
+        if st != GEAK_OK:
+            raise GeakError(st, "geak_check_read_probe")
 
     def read(self) -> np.ndarray:
         """Synchronise and return the records as a RESULT_DTYPE array of shape (segments, candidates)."""

@@ -1,5 +1,6 @@
 // C-ABI entry points: plan lifetime, argument checks, kernel enqueue.  See include/geak_check.h.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include "geak_internal.hpp"
@@ -296,6 +297,49 @@ uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t c
         if (n) std::memcpy(out, items.data(), n * sizeof(geak_item));
     }
     return items.size();
+}
+
+geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                                  void *workspace_dev, void *hip_stream)
+{
+    if (!plan || !cand_dev) return GEAK_EINVAL;
+    if (plan->device < 0) return GEAK_EINVAL;
+    const HostPlan &hp = plan->host;
+    if (hp.items.empty()) return GEAK_OK;
+    if (!ref_dev || !workspace_dev) return GEAK_EINVAL;
+    if (((uintptr_t)ref_dev & 15u) || ((uintptr_t)workspace_dev & 15u)) return GEAK_EALIGN;
+    const int K = hp.num_candidates;
+    for (int k = 0; k < K; ++k) {
+        if (!cand_dev[k]) return GEAK_EINVAL;
+        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
+    }
+    // the span of the packed buffers that the plan's segments cover
+    uint64_t end = 0;
+    for (const geak_segment &g : hp.segments)
+        if (g.numel) end = std::max<uint64_t>(end, g.byte_offset + g.numel * (uint64_t)elem_size(g.dtype));
+    DeviceGuard g(plan->device);
+    if (!g.ok) return GEAK_EHIP;
+    // the candidate pointer table of a run is reused; the reference pointer goes behind it
+    InitArgs ia;
+    ia.results = nullptr;
+    ia.cand_table = (const unsigned char **)workspace_dev;
+    ia.board = nullptr;
+    ia.num_board = 0;
+    ia.num_results = 0;
+    ia.num_candidates = (uint32_t)K + 1;
+    ia.reserved = 0;
+    if (K + 1 > GEAK_MAX_CANDIDATES) return GEAK_EINVAL;      // the table has room for 256 pointers
+    for (int k = 0; k < GEAK_MAX_CANDIDATES; ++k)
+        ia.cand[k] = (k < K) ? (const unsigned char *)cand_dev[k] : (k == K ? (const unsigned char *)ref_dev : nullptr);
+    if (launch_init(ia, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+    ProbeArgs pa;
+    pa.buffers = (const unsigned char *const *)workspace_dev;
+    pa.sink = (uint32_t *)((unsigned char *)workspace_dev + kCandTableBytes);      // the first queue/board word: scratch
+    pa.bytes_each = end;
+    pa.num_buffers = (uint32_t)K + 1;
+    pa.reserved = 0;
+    if (launch_read_probe(pa, hp.max_blocks * 2, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+    return GEAK_OK;
 }
 
 geak_status geak_check_profile_enable(geak_plan *plan, uint32_t num_pairs)

@@ -115,10 +115,20 @@ struct ReduceArgs {
     uint32_t replicas;
 };
 
+// Read probe: num_buffers device buffers (pointer table in the workspace), bytes_each bytes of each.
+struct ProbeArgs {
+    const unsigned char *const *buffers;
+    uint32_t *sink;
+    uint64_t bytes_each;
+    uint32_t num_buffers;
+    uint32_t reserved;
+};
+
 // Kernel launchers (kernels.hip).  Return the hipError_t of the launch as int.
 int launch_init(const InitArgs &args, void *stream);
 int launch_compare(const CompareArgs &args, uint32_t grid_blocks, uint32_t lds_bytes, void *stream);
 int launch_reduce(const ReduceArgs &args, void *stream);
+int launch_read_probe(const ProbeArgs &args, uint32_t grid_blocks, void *stream);
 int compare_blocks_per_cu(uint32_t lds_bytes);   // occupancy query on the current device; <= 0 on failure
 
 }  // namespace geak
