@@ -5,10 +5,12 @@ The product package never imports it.
 """
 from .oracle import (  # noqa: F401
     RECORD_DTYPE,
+    MISMATCH_DTYPE,
     DTYPE_CODES,
     ELEM_SIZE,
     build,
     check_segment,
+    report_segment,
     check_dense,
     check_ragged,
     decode_f16,

@@ -35,6 +35,9 @@
  *         int32: r_i = (double)d_i / (double)|b_i| in binary64, same conventions
  *     R10 indices are flat, 0-based, within the segment
  *
+ *   mismatch report (oracle_report_segment, below): the first M elements that are not close,
+ *         with index, a, b, d and tol as the rule computed them
+ *
  * Pins (tests/test_oracle_pins.py, tests/golden/): hand-derived records for
  * boundary, NaN, Inf, signed-zero, subnormal and integer cases; an exact
  * rational-arithmetic model of the rounding steps; structural invariants;
@@ -204,6 +207,86 @@ int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int 
     _mm_setcsr(csr_saved);
 #endif
     return 0;
+}
+
+/*
+ * Mismatch report for one (segment, candidate) pair: the first max_records elements that are not
+ * close, in ascending index order, each with what the rule saw.  GEAK section 4.1 feeds the error
+ * trace of a failed functionality test to the Reflector, and section 4.2 (Reflexion) has the agent
+ * analyse it; the paper does not say what the trace holds, so this is the reading: for every
+ * reported element its flat index, a and b widened exactly to binary64, d = |a (-) b| and
+ * tol = atol_f (+) (rtol_f (x) |b|) exactly as rules R1 / R6 compute them (binary32 values widened;
+ * for int32 d is exact and tol is 0).  d and tol may be NaN or infinite when a or b is.
+ * Returns the number of records written (at most max_records), or -1 on a bad argument.
+ */
+typedef struct {
+    int64_t index;
+    double  a;
+    double  b;
+    double  d;
+    double  tol;
+} oracle_mismatch;
+
+int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel, int dtype,
+                              double atol, double rtol, int equal_nan, uint64_t max_records,
+                              oracle_mismatch *out)
+{
+    if ((!out && max_records) || dtype < 0 || dtype > 3)
+        return -1;
+#if defined(__SSE2__)
+    unsigned int csr_saved = _mm_getcsr();
+    _mm_setcsr(csr_saved & ~0x8040u);
+#endif
+    uint64_t written = 0;
+    const float atol_f = (float)atol;
+    const float rtol_f = (float)rtol;
+    for (uint64_t i = 0; i < numel && written < max_records; ++i) {
+        oracle_mismatch m;
+        int close;
+        if (dtype == ORACLE_I32) {
+            int64_t a = ((const int32_t *)cand)[i], b = ((const int32_t *)ref)[i];
+            int64_t diff = a - b;
+            close = (a == b);                                    /* R6 */
+            m.a = (double)a;
+            m.b = (double)b;
+            m.d = (double)(diff < 0 ? -diff : diff);
+            m.tol = 0.0;
+        } else {
+            float a, b;
+            if (dtype == ORACLE_F32) {
+                a = ((const float *)cand)[i];
+                b = ((const float *)ref)[i];
+            } else if (dtype == ORACLE_F16) {
+                a = decode_f16(((const uint16_t *)cand)[i]);
+                b = decode_f16(((const uint16_t *)ref)[i]);
+            } else {
+                a = decode_bf16(((const uint16_t *)cand)[i]);
+                b = decode_bf16(((const uint16_t *)ref)[i]);
+            }
+            float diff = a - b;
+            float d = fabsf(diff);                               /* R1 */
+            float prod = rtol_f * fabsf(b);
+            float tol = atol_f + prod;
+            if (is_nan_f(a) || is_nan_f(b))                      /* R3 */
+                close = equal_nan && is_nan_f(a) && is_nan_f(b);
+            else if (is_inf_f(a) || is_inf_f(b))                 /* R4 */
+                close = (a == b);
+            else
+                close = (d <= tol);
+            m.a = (double)a;
+            m.b = (double)b;
+            m.d = (double)d;
+            m.tol = (double)tol;
+        }
+        if (!close) {
+            m.index = (int64_t)i;
+            out[written++] = m;
+        }
+    }
+#if defined(__SSE2__)
+    _mm_setcsr(csr_saved);
+#endif
+    return (int64_t)written;
 }
 
 /* Decoders exported so the pins can check them on all 65536 bit patterns. */

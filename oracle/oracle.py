@@ -33,6 +33,9 @@ RECORD_DTYPE = np.dtype(
     ]
 )
 
+# One reported mismatch; field meaning as in geak_oracle.c (oracle_report_segment).
+MISMATCH_DTYPE = np.dtype([("index", "<i8"), ("a", "<f8"), ("b", "<f8"), ("d", "<f8"), ("tol", "<f8")])
+
 _lock = threading.Lock()
 _lib = None
 
@@ -58,6 +61,11 @@ def _load():
             lib.oracle_check_segment.argtypes = [
                 ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
                 ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_void_p,
+            ]
+            lib.oracle_report_segment.restype = ctypes.c_int64
+            lib.oracle_report_segment.argtypes = [
+                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
+                ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_uint64, ctypes.c_void_p,
             ]
             lib.oracle_decode_f16.restype = ctypes.c_float
             lib.oracle_decode_f16.argtypes = [ctypes.c_uint16]
@@ -101,6 +109,28 @@ def check_segment(ref, cand, numel: int, dtype: str, atol: float, rtol: float,
     if rc != 0:
         raise RuntimeError("oracle_check_segment failed")
     return out[0]
+
+
+def report_segment(ref, cand, numel: int, dtype: str, atol: float, rtol: float, equal_nan: bool,
+                   max_records: int, ref_byte_offset: int = 0, cand_byte_offset: int | None = None) -> np.ndarray:
+    """The first max_records mismatches of one (segment, candidate) pair, as a MISMATCH_DTYPE array
+    (its length is min(max_records, mismatch count))."""
+    lib = _load()
+    if cand_byte_offset is None:
+        cand_byte_offset = ref_byte_offset
+    rb, cb = _as_bytes(ref), _as_bytes(cand)
+    need = numel * ELEM_SIZE[dtype]
+    if ref_byte_offset + need > rb.size or cand_byte_offset + need > cb.size:
+        raise ValueError("segment exceeds buffer")
+    out = np.zeros(max(1, max_records), dtype=MISMATCH_DTYPE)
+    n = lib.oracle_report_segment(
+        rb.ctypes.data + ref_byte_offset, cb.ctypes.data + cand_byte_offset,
+        numel, DTYPE_CODES[dtype], float(atol), float(rtol), int(bool(equal_nan)),
+        int(max_records), out.ctypes.data,
+    )
+    if n < 0:
+        raise RuntimeError("oracle_report_segment failed")
+    return out[:n].copy()
 
 
 def _run_pairs(jobs, threads: int):
