@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per compare launch from rocprofv3 counters, overriding the recorded figure "
                          "(reported as roofline.traffic)")
+    ap.add_argument("--report", type=int, default=0, metavar="M",
+                    help="also time the mismatch report (first M mismatches per pair) that follows a failed check; "
+                         "reported under \"report\", not part of the step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain element-wise copy of a known size (2 GiB read, 2 GiB written per launch), "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -165,6 +168,16 @@ def main():
         probe_gbps = alg_bytes / (probe_ms * 1e-3) / 1e9
         ck.run(w.ref, w.cands)                       # the probe used the workspace: produce the records again
 
+    report = None
+    if args.report > 0:
+        ck.report(w.ref, w.cands, args.report)                      # warm-up (allocates its buffers)
+        t0 = time.perf_counter()
+        reps = 5
+        for _ in range(reps):
+            rrec, rcnt = ck.report(w.ref, w.cands, args.report)     # synchronises
+        report = {"max_records": args.report, "ms_per_call_incl_copy_back": (time.perf_counter() - t0) / reps * 1e3,
+                  "pairs": int(rcnt.size), "records": int(rcnt.sum())}
+
     rec = ck.read()
     n_fail = int((rec["pass"] == 0).sum())
     # the records must agree with what the generator planted (cheap sanity check, outside the timed region)
@@ -202,6 +215,8 @@ def main():
                      "read_only_kernel_GBps": probe_gbps,
                      "frac_of_read_only_kernel": (achieved / probe_gbps) if probe_gbps else None},
     }
+    if report is not None:
+        out["report"] = report
     if not args.no_cpu_baseline:
         budget = {1: (8, 1 << 20), 2: (32, 1 << 26), 3: (16, 1 << 28), 4: (4, 0), 5: (8, 1 << 28)}[args.config]
         out["cpu_baseline"] = cpu_baseline(w, *budget)

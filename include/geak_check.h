@@ -187,6 +187,42 @@ uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t c
 geak_status geak_check_profile_enable(geak_plan *plan, uint32_t num_pairs);
 uint64_t    geak_check_profile_read(geak_plan *plan, float *ms_out, uint64_t capacity);
 
+/* ---- mismatch report -----------------------------------------------------------------------------
+ * When the functionality test fails, the evaluator hands an error trace to the Reflector, which has
+ * to work out what went wrong (sections 4.1 and 4.2, Reflexion).  The paper does not say what the
+ * trace holds; this library reports, per (segment, candidate), the first elements that are not
+ * close, in ascending index order, each with what the rule saw:
+ *     index  flat 0-based index within the segment
+ *     a, b   candidate and reference element, widened exactly to binary64
+ *     d      |a - b| as the rule computed it (binary32 value widened; exact for int32); NaN when a or
+ *            b is NaN or both are the same infinity, +Inf when one of them is infinite
+ *     tol    atol_f + rtol_f * |b| as the rule computed it (binary32, two roundings, widened; NaN or
+ *            +Inf when b is); 0 for int32
+ * NaN payloads are not specified. */
+typedef struct {
+    int64_t index;
+    double  a;
+    double  b;
+    double  d;
+    double  tol;
+} geak_mismatch; /* 40 bytes */
+
+/*
+ * Enqueue the report of a completed check.  Must follow, on the same stream, the geak_check_run that
+ * produced `results_dev` from the same tensors (its records tell where each pair's mismatches start
+ * and how many there are); the workspace is reused.
+ *   max_records  how many mismatches to report per (segment, candidate) pair, >= 1
+ *   records_dev  device array of geak_check_result_count() x max_records entries; pair p owns
+ *                [p * max_records, (p + 1) * max_records); entries past its count are left untouched
+ *   counts_dev   device array of geak_check_result_count() entries: min(max_records, mismatch_count)
+ * One block per pair scans its segment from the pair's first mismatch and stops as soon as it has
+ * what it needs, so the cost is that of reading the segment up to the last reported element (all
+ * of it when the pair has fewer than max_records mismatches spread to its end).
+ */
+geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                              void *workspace_dev, const geak_result *results_dev, uint32_t max_records,
+                              geak_mismatch *records_dev, uint32_t *counts_dev, void *hip_stream);
+
 /* ---- read probe (measurement aid, not part of the check) -------------------------------------
  * Enqueues a kernel that only reads, with 16-byte loads, the same bytes a run of this plan reads
  * (the span of the packed reference and of every candidate that the segments cover) and computes

@@ -30,6 +30,7 @@ ELEM_SIZE = {GEAK_F32: 4, GEAK_F16: 2, GEAK_BF16: 2, GEAK_I32: 4}
 SEGMENT_DTYPE = np.dtype([("byte_offset", "<u8"), ("numel", "<u8"), ("dtype", "<i4"), ("reserved", "<i4")])
 RESULT_DTYPE = np.dtype([("pass", "<i4"), ("reserved", "<i4"), ("mismatch_count", "<u8"),
                          ("first_mismatch", "<i8"), ("max_abs_err", "<f8"), ("max_rel_err", "<f8")])
+MISMATCH_DTYPE = np.dtype([("index", "<i8"), ("a", "<f8"), ("b", "<f8"), ("d", "<f8"), ("tol", "<f8")])
 ITEM_DTYPE = np.dtype([("byte_offset", "<u8"), ("elem_start", "<u8"), ("segment", "<u4"), ("slot", "<u4"),
                        ("numel", "<u2"), ("dtype", "u1"), ("flags", "u1"), ("next", "<u4")])
 GEAK_NO_ITEM = 0xFFFFFFFF
@@ -93,6 +94,8 @@ def library() -> ctypes.CDLL:
         lib.geak_check_plan_waves.argtypes = [vp, vp, u64]
         lib.geak_check_plan_items.restype = u64
         lib.geak_check_plan_items.argtypes = [vp, vp, u64]
+        lib.geak_check_report.restype = ctypes.c_int
+        lib.geak_check_report.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, ctypes.c_uint32, vp, vp, vp]
         lib.geak_check_read_probe.restype = ctypes.c_int
         lib.geak_check_read_probe.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp]
         lib.geak_check_profile_enable.restype = ctypes.c_int
@@ -105,7 +108,7 @@ def library() -> ctypes.CDLL:
 
 EXPORTED = ["geak_check_plan", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
-            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe"]
+            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report"]
 
 
 # ---- one Python function per C entry point -------------------------------------------------------
@@ -151,6 +154,14 @@ def geak_check_run(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: 
     """All pointers are device addresses as integers; stream is a hipStream_t as integer (0 = default)."""
     arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
     return int(library().geak_check_run(plan, ref_ptr, arr, workspace_ptr, results_ptr, stream))
+
+
+def geak_check_report(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: int, results_ptr: int,
+                      max_records: int, records_ptr: int, counts_ptr: int, stream: int) -> int:
+    """Enqueue the mismatch report of a completed run; all pointers are device addresses."""
+    arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
+    return int(library().geak_check_report(plan, ref_ptr, arr, workspace_ptr, results_ptr, max_records,
+                                           records_ptr, counts_ptr, stream))
 
 
 def geak_check_read_probe(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: int, stream: int) -> int:
@@ -239,6 +250,24 @@ class Checker:
                             self.workspace.data_ptr(), self.results.data_ptr(), stream)
         if st != GEAK_OK:
             raise GeakError(st, "geak_check_run")
+
+    def report(self, ref, cands, max_records: int):
+        """Mismatch report of the last run on the same tensors: (records, counts), records a
+        MISMATCH_DTYPE array of shape (segments, candidates, max_records) of which the first
+        counts[s, k] entries of each pair are valid.  Synchronises."""
+        import torch
+        pairs = self.results.numel() * self.results.element_size() // RESULT_DTYPE.itemsize
+        records = torch.zeros(max(1, pairs * max_records * MISMATCH_DTYPE.itemsize), dtype=torch.uint8, device=self.results.device)
+        counts = torch.zeros(max(1, pairs), dtype=torch.int32, device=self.results.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        st = geak_check_report(self.plan, ref.data_ptr(), [c.data_ptr() for c in cands], self.workspace.data_ptr(),
+                               self.results.data_ptr(), max_records, records.data_ptr(), counts.data_ptr(), stream)
+        if st != GEAK_OK:
+            raise GeakError(st, "geak_check_report")
+        torch.cuda.current_stream(self.device).synchronize()
+        rec = records.cpu().numpy()[:pairs * max_records * MISMATCH_DTYPE.itemsize].view(MISMATCH_DTYPE)
+        return (rec.reshape(-1, self.num_candidates, max_records),
+                counts.cpu().numpy()[:pairs].astype(np.int64).reshape(-1, self.num_candidates))
 
     def read_probe(self, ref, cands) -> None:
         """Enqueue the read-only probe over the same tensors on torch's current stream."""

@@ -15,6 +15,7 @@ struct geak_plan {
     geak_item *items_dev = nullptr;
     uint32_t *slot_begin_dev = nullptr;
     uint32_t *wave_first_dev = nullptr;
+    geak_segment *segments_dev = nullptr;
     // optional timing ring
     std::vector<hipEvent_t> ev_start, ev_stop;
     uint32_t ev_next = 0, ev_used = 0;
@@ -42,11 +43,13 @@ void free_device_side(geak_plan *p)
     if (p->items_dev) (void)hipFree(p->items_dev);
     if (p->slot_begin_dev) (void)hipFree(p->slot_begin_dev);
     if (p->wave_first_dev) (void)hipFree(p->wave_first_dev);
+    if (p->segments_dev) (void)hipFree(p->segments_dev);
     for (auto e : p->ev_start) (void)hipEventDestroy(e);
     for (auto e : p->ev_stop) (void)hipEventDestroy(e);
     p->items_dev = nullptr;
     p->slot_begin_dev = nullptr;
     p->wave_first_dev = nullptr;
+    p->segments_dev = nullptr;
     p->ev_start.clear();
     p->ev_stop.clear();
 }
@@ -92,10 +95,13 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
         const size_t wave_bytes = p->host.wave_first.size() * sizeof(uint32_t);
         if (ok) ok = hipMalloc((void **)&p->slot_begin_dev, slot_bytes) == hipSuccess;
         if (ok) ok = hipMalloc((void **)&p->wave_first_dev, wave_bytes) == hipSuccess;
+        const size_t seg_bytes = p->host.segments.size() * sizeof(geak_segment);
+        if (ok) ok = hipMalloc((void **)&p->segments_dev, seg_bytes) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_ENOMEM; }
         if (item_bytes) ok = hipMemcpy(p->items_dev, p->host.items.data(), item_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->slot_begin_dev, p->host.slot_begin.data(), slot_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->wave_first_dev, p->host.wave_first.data(), wave_bytes, hipMemcpyHostToDevice) == hipSuccess;
+        if (ok) ok = hipMemcpy(p->segments_dev, p->host.segments.data(), seg_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_EHIP; }
     }
     *out = p;
@@ -297,6 +303,59 @@ uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t c
         if (n) std::memcpy(out, items.data(), n * sizeof(geak_item));
     }
     return items.size();
+}
+
+geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                              void *workspace_dev, const geak_result *results_dev, uint32_t max_records,
+                              geak_mismatch *records_dev, uint32_t *counts_dev, void *hip_stream)
+{
+    if (!plan || !cand_dev || !results_dev || !records_dev || !counts_dev || max_records == 0) return GEAK_EINVAL;
+    if (plan->device < 0) return GEAK_EINVAL;
+    const HostPlan &hp = plan->host;
+    const int K = hp.num_candidates;
+    const bool reads_data = !hp.items.empty();
+    if (reads_data && !ref_dev) return GEAK_EINVAL;
+    if (((uintptr_t)ref_dev & 15u) || ((uintptr_t)results_dev & 7u) || ((uintptr_t)records_dev & 7u) ||
+        ((uintptr_t)counts_dev & 3u))
+        return GEAK_EALIGN;
+    for (int k = 0; k < K; ++k) {
+        if (reads_data && !cand_dev[k]) return GEAK_EINVAL;
+        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
+    }
+    const uint64_t ws_bytes = geak_check_workspace_bytes(plan);
+    if (ws_bytes && !workspace_dev) return GEAK_EWORKSPACE;
+    if (ws_bytes && ((uintptr_t)workspace_dev & 15u)) return GEAK_EALIGN;
+    DeviceGuard g(plan->device);
+    if (!g.ok) return GEAK_EHIP;
+
+    // the candidate pointer table is written again (the caller may have reused the workspace)
+    const unsigned char **cand_table = reads_data ? (const unsigned char **)workspace_dev : nullptr;
+    InitArgs ia;
+    ia.results = nullptr;
+    ia.cand_table = cand_table;
+    ia.board = nullptr;
+    ia.num_board = 0;
+    ia.num_results = 0;
+    ia.num_candidates = (uint32_t)K;
+    ia.reserved = 0;
+    for (int k = 0; k < GEAK_MAX_CANDIDATES; ++k) ia.cand[k] = (k < K) ? (const unsigned char *)cand_dev[k] : nullptr;
+    if (reads_data && launch_init(ia, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+
+    ReportArgs ra;
+    ra.segments = plan->segments_dev;
+    ra.results = results_dev;
+    ra.ref = (const unsigned char *)ref_dev;
+    ra.cand_table = cand_table;
+    ra.records = records_dev;
+    ra.counts = counts_dev;
+    ra.num_segments = (uint32_t)hp.segments.size();
+    ra.num_candidates = (uint32_t)K;
+    ra.max_records = max_records;
+    ra.atol_f = hp.atol_f;
+    ra.rtol_f = hp.rtol_f;
+    ra.equal_nan = hp.equal_nan;
+    if (launch_report(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+    return GEAK_OK;
 }
 
 geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,

@@ -124,10 +124,26 @@ struct ProbeArgs {
     uint32_t reserved;
 };
 
+struct ReportArgs {
+    const geak_segment *segments;        // device copy of the segment table
+    const geak_result *results;
+    const unsigned char *ref;
+    const unsigned char *const *cand_table;
+    geak_mismatch *records;
+    uint32_t *counts;
+    uint32_t num_segments;
+    uint32_t num_candidates;
+    uint32_t max_records;
+    float atol_f;
+    float rtol_f;
+    int equal_nan;
+};
+
 // Kernel launchers (kernels.hip).  Return the hipError_t of the launch as int.
 int launch_init(const InitArgs &args, void *stream);
 int launch_compare(const CompareArgs &args, uint32_t grid_blocks, uint32_t lds_bytes, void *stream);
 int launch_reduce(const ReduceArgs &args, void *stream);
+int launch_report(const ReportArgs &args, void *stream);
 int launch_read_probe(const ProbeArgs &args, uint32_t grid_blocks, void *stream);
 int compare_blocks_per_cu(uint32_t lds_bytes);   // occupancy query on the current device; <= 0 on failure
 

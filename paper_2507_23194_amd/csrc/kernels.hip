@@ -155,7 +155,7 @@ __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, i
 }
 
 // One element straight from memory, decoded exactly to binary32 (floating dtypes).
-__device__ __forceinline__ float load_elem_f(const unsigned char *base, uint32_t idx, int dtype)
+__device__ __forceinline__ float load_elem_f(const unsigned char *base, u64 idx, int dtype)
 {
     if (dtype == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
     const uint16_t h = reinterpret_cast<const uint16_t *>(base)[idx];
@@ -1169,7 +1169,7 @@ __global__ void init_kernel(const InitArgs p)
 }
 
 // ---- reduce: one block per (segment, candidate) ----------------------------------------------
-__device__ __forceinline__ bool element_close(const unsigned char *ref, const unsigned char *cand, uint32_t idx,
+__device__ __forceinline__ bool element_close(const unsigned char *ref, const unsigned char *cand, u64 idx,
                                               int dtype, float atol_f, float rtol_f, int equal_nan)
 {
     if (dtype == GEAK_I32)
@@ -1273,6 +1273,120 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
     }
 }
 
+// ---- mismatch report: the first elements of each pair that are not close ----------------------------
+// One block per (segment, candidate).  The pair's record says where its first mismatch is and how
+// many there are; the block walks the segment from there in tiles of 4096 elements (thread t looks
+// at elements t, t + 256, ... of the tile, all of its loads in flight together), ranks the
+// mismatches of a tile in index order with lane masks and one LDS table, writes those that still fit
+// and stops when it has min(max_records, mismatch_count) of them.
+constexpr int kReportThreads = 256;
+constexpr int kReportPerThread = 16;
+
+// one element straight from memory, by compile-time dtype (all of a thread's loads can then be issued together)
+template <int DT>
+__device__ __forceinline__ float elem_f(const unsigned char *base, u64 idx)
+{
+    if constexpr (DT == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
+    else if constexpr (DT == GEAK_F16) return (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t *>(base)[idx]);
+    else return bits_f((uint32_t)reinterpret_cast<const uint16_t *>(base)[idx] << 16);
+}
+
+template <int DT>
+__device__ __forceinline__ void report_pair(const ReportArgs &p, const geak_segment &sg, const geak_result &rec, u64 want,
+                                            const unsigned char *rb, const unsigned char *cb, geak_mismatch *out,
+                                            uint32_t (&s_cnt)[kReportPerThread][kReportThreads / kWaveSize])
+{
+    const int tid = threadIdx.x, lane = tid & (kWaveSize - 1), wave = tid / kWaveSize;
+    u64 found = 0;
+    for (u64 base = (u64)rec.first_mismatch; base < sg.numel && found < want; base += kReportThreads * kReportPerThread) {
+        // all loads of the tile first, then the rule
+        float av[kReportPerThread], bv[kReportPerThread];
+        int ai[kReportPerThread], bi[kReportPerThread];
+#pragma unroll
+        for (int u = 0; u < kReportPerThread; ++u) {
+            const u64 i = base + (u64)u * kReportThreads + tid;
+            const bool in = i < sg.numel;
+            if constexpr (DT == GEAK_I32) {
+                ai[u] = in ? reinterpret_cast<const int *>(cb)[i] : 0;
+                bi[u] = in ? reinterpret_cast<const int *>(rb)[i] : 0;
+            } else {
+                av[u] = in ? elem_f<DT>(cb, i) : 0.0f;
+                bv[u] = in ? elem_f<DT>(rb, i) : 0.0f;
+            }
+        }
+        bool bad[kReportPerThread];
+        int any = 0;
+        uint32_t before[kReportPerThread];               // mismatches of lower lanes of this wave in row u
+#pragma unroll
+        for (int u = 0; u < kReportPerThread; ++u) {
+            const u64 i = base + (u64)u * kReportThreads + tid;
+            if constexpr (DT == GEAK_I32) bad[u] = (i < sg.numel) && ai[u] != bi[u];
+            else bad[u] = (i < sg.numel) && !close_exact(av[u], bv[u], p.atol_f, p.rtol_f, p.equal_nan);
+            const u64 mask = __builtin_amdgcn_ballot_w64(bad[u]);
+            before[u] = (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
+            if (lane == 0) s_cnt[u][wave] = (uint32_t)__builtin_popcountll(mask);
+            any |= bad[u];
+        }
+        if (!__syncthreads_or(any)) continue;                // a clean tile (the common case when mismatches are sparse)
+        u64 rank = found;                                    // mismatches before row u
+        u64 tile_total = 0;
+#pragma unroll
+        for (int u = 0; u < kReportPerThread; ++u) {
+            uint32_t row_before = 0, row_total = 0;
+#pragma unroll
+            for (int w = 0; w < kReportThreads / kWaveSize; ++w) {
+                const uint32_t c = s_cnt[u][w];
+                row_before += (w < wave) ? c : 0u;
+                row_total += c;
+            }
+            const u64 pos = rank + row_before + before[u];
+            if (bad[u] && pos < want) {
+                geak_mismatch m;
+                m.index = (long long)(base + (u64)u * kReportThreads + tid);
+                if constexpr (DT == GEAK_I32) {
+                    const long long a = ai[u], b = bi[u];
+                    const long long diff = a - b;
+                    m.a = (double)a;
+                    m.b = (double)b;
+                    m.d = (double)(diff < 0 ? -diff : diff);
+                    m.tol = 0.0;
+                } else {
+                    const float prod = p.rtol_f * __builtin_fabsf(bv[u]);
+                    m.a = (double)av[u];
+                    m.b = (double)bv[u];
+                    m.d = (double)__builtin_fabsf(av[u] - bv[u]);
+                    m.tol = (double)(p.atol_f + prod);
+                }
+                out[pos] = m;
+            }
+            rank += row_total;
+            tile_total += row_total;
+        }
+        found += tile_total;
+        __syncthreads();                                     // the table is rewritten by the next tile
+    }
+}
+
+__global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs p)
+{
+    __shared__ uint32_t s_cnt[kReportPerThread][kReportThreads / kWaveSize];
+    const uint32_t K = p.num_candidates;
+    const uint32_t seg = blockIdx.x / K, k = blockIdx.x % K;
+    const geak_result rec = p.results[blockIdx.x];
+    const u64 want = rec.mismatch_count < p.max_records ? rec.mismatch_count : (u64)p.max_records;
+    if (threadIdx.x == 0) p.counts[blockIdx.x] = (uint32_t)want;
+    if (want == 0) return;                                   // uniform
+    const geak_segment sg = p.segments[seg];
+    const unsigned char *rb = p.ref + sg.byte_offset, *cb = p.cand_table[k] + sg.byte_offset;
+    geak_mismatch *out = p.records + (u64)blockIdx.x * p.max_records;
+    switch (sg.dtype) {                                      // uniform
+    case GEAK_F32:  report_pair<GEAK_F32>(p, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_F16:  report_pair<GEAK_F16>(p, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_BF16: report_pair<GEAK_BF16>(p, sg, rec, want, rb, cb, out, s_cnt); break;
+    default:        report_pair<GEAK_I32>(p, sg, rec, want, rb, cb, out, s_cnt); break;
+    }
+}
+
 // ---- read probe: what a kernel that only reads the same bytes achieves ---------------------------
 // Every lane keeps eight 16-byte non-temporal loads in flight over a grid-stride walk of each buffer
 // and folds what it reads into one word, which is stored only if it has a value it cannot have.
@@ -1298,6 +1412,14 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const ProbeArgs p)
 }
 
 }  // namespace
+
+int launch_report(const ReportArgs &args, void *stream)
+{
+    const uint64_t pairs = (uint64_t)args.num_segments * args.num_candidates;
+    if (!pairs) return (int)hipSuccess;
+    hipLaunchKernelGGL(report_kernel, dim3((uint32_t)pairs), dim3(kReportThreads), 0, (hipStream_t)stream, args);
+    return (int)hipGetLastError();
+}
 
 int launch_read_probe(const ProbeArgs &args, uint32_t grid_blocks, void *stream)
 {
