@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # They describe the kernel sources whose digest is recorded with them: once a source has changed,
 # the figures no longer apply and roofline.traffic is reported as null until they are retaken.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "9091c6e434d7c5d1819d4faad3583231aca048d9db696ab5710caba6acb137d0",
-    "bytes": {2: 8.7854e9, 3: 9.1848e9, 4: 1.2277e9, 5: 141.8571e9},
+    "sources_sha256": "ef6b9847ca39f0cb85540bad6ca4fb1692e5d73affc04be9d35e52412e3ccc87",
+    "bytes": {2: 8.7897e9, 3: 9.1847e9, 4: 1.2284e9, 5: 141.8569e9},
 }
 KERNEL_SOURCES = ["kernels.hip", "plan_host.cpp", "api.cpp", "geak_internal.hpp"]
 
