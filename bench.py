@@ -106,7 +106,7 @@ def main():
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit("bench.py: the check runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
     import numpy as np
     import torch

@@ -96,6 +96,19 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
                             int32_t num_candidates, double atol, double rtol, int32_t equal_nan,
                             int32_t device);
 
+/* One tolerance pair per segment.  The unit tests of one kernel produce outputs of different
+ * magnitude and precision (section 3.3: a kernel is checked on all of its unit tests), so each
+ * packed output may be judged with its own atol / rtol; int32 segments ignore theirs. */
+typedef struct {
+    double atol;
+    double rtol;
+} geak_tolerance;
+
+/* Like geak_check_plan, with `tols[s]` applying to segment s (host array of nsegs entries, copied;
+ * each value finite and >= 0, also after conversion to binary32). */
+geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs, const geak_tolerance *tols,
+                                       uint64_t nsegs, int32_t num_candidates, int32_t equal_nan, int32_t device);
+
 /* Dense convenience (section 3.1: one output tensor against its reference): a single segment at
  * offset 0 with prod(shape) elements; shape is a host array of ndim >= 0 non-negative extents
  * (ndim == 0 is a scalar).  Only the element count matters: indices are flat, row-major. */

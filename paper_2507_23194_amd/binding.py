@@ -74,6 +74,8 @@ def library() -> ctypes.CDLL:
         vp, u64, i32, dbl = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_double
         lib.geak_check_plan.restype = ctypes.c_int
         lib.geak_check_plan.argtypes = [ctypes.POINTER(vp), vp, u64, i32, dbl, dbl, i32, i32]
+        lib.geak_check_plan_tolerances.restype = ctypes.c_int
+        lib.geak_check_plan_tolerances.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         lib.geak_check_plan_dense.restype = ctypes.c_int
         lib.geak_check_plan_dense.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(ctypes.c_int64), i32, i32, dbl, dbl, i32, i32]
         lib.geak_check_workspace_bytes.restype = u64
@@ -106,7 +108,7 @@ def library() -> ctypes.CDLL:
     return _lib
 
 
-EXPORTED = ["geak_check_plan", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
+EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report"]
 
@@ -123,6 +125,20 @@ def geak_check_plan(segments, num_candidates: int, atol: float, rtol: float, equ
     for i, (off, n, dt) in enumerate(segs):
         arr[i] = (off, n, DTYPE_CODE.get(dt, dt), 0)
     return geak_check_plan_raw(arr, len(segs), num_candidates, atol, rtol, int(equal_nan), device)
+
+
+def geak_check_plan_tolerances(segments, tolerances, num_candidates: int, equal_nan, device: int):
+    """segments as for geak_check_plan; tolerances: one (atol, rtol) pair per segment, or None (null pointer).
+    Returns (status, plan handle or None)."""
+    segs = list(segments)
+    arr = np.zeros(len(segs), dtype=SEGMENT_DTYPE)
+    for i, (off, n, dt) in enumerate(segs):
+        arr[i] = (off, n, DTYPE_CODE.get(dt, dt), 0)
+    tol = None if tolerances is None else np.ascontiguousarray(np.asarray(list(tolerances), dtype=np.float64).reshape(-1, 2))
+    out = ctypes.c_void_p(None)
+    st = library().geak_check_plan_tolerances(ctypes.byref(out), arr.ctypes.data, None if tol is None else tol.ctypes.data,
+                                              len(segs), num_candidates, int(equal_nan), int(device))
+    return st, (out.value if st == GEAK_OK else None)
 
 
 def geak_check_plan_raw(seg_array, nsegs: int, num_candidates: int, atol: float, rtol: float, equal_nan: int, device: int):
@@ -220,10 +236,12 @@ def geak_check_profile_read(plan, capacity: int) -> np.ndarray:
 class Checker:
     """A plan plus its workspace and results buffers (torch tensors on the plan's device)."""
 
-    def __init__(self, segments=None, *, dense=None, num_candidates: int, atol: float, rtol: float,
-                 equal_nan: bool, device: int = 0):
+    def __init__(self, segments=None, *, dense=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
+                 equal_nan: bool, device: int = 0, tolerances=None):
         import torch
-        if dense is not None:
+        if tolerances is not None:
+            st, plan = geak_check_plan_tolerances(segments, tolerances, num_candidates, equal_nan, device)
+        elif dense is not None:
             dtype, shape = dense
             st, plan = geak_check_plan_dense(dtype, list(shape), num_candidates, atol, rtol, equal_nan, device)
         else:

@@ -16,6 +16,7 @@ struct geak_plan {
     uint32_t *slot_begin_dev = nullptr;
     uint32_t *wave_first_dev = nullptr;
     geak_segment *segments_dev = nullptr;
+    SegTol *seg_tol_dev = nullptr;
     // optional timing ring
     std::vector<hipEvent_t> ev_start, ev_stop;
     uint32_t ev_next = 0, ev_used = 0;
@@ -44,12 +45,14 @@ void free_device_side(geak_plan *p)
     if (p->slot_begin_dev) (void)hipFree(p->slot_begin_dev);
     if (p->wave_first_dev) (void)hipFree(p->wave_first_dev);
     if (p->segments_dev) (void)hipFree(p->segments_dev);
+    if (p->seg_tol_dev) (void)hipFree(p->seg_tol_dev);
     for (auto e : p->ev_start) (void)hipEventDestroy(e);
     for (auto e : p->ev_stop) (void)hipEventDestroy(e);
     p->items_dev = nullptr;
     p->slot_begin_dev = nullptr;
     p->wave_first_dev = nullptr;
     p->segments_dev = nullptr;
+    p->seg_tol_dev = nullptr;
     p->ev_start.clear();
     p->ev_stop.clear();
 }
@@ -60,6 +63,19 @@ extern "C" {
 
 geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t nsegs, int32_t num_candidates,
                             double atol, double rtol, int32_t equal_nan, int32_t device)
+{
+    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    std::vector<geak_tolerance> tols;
+    try {
+        tols.assign(nsegs, geak_tolerance{atol, rtol});
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    return geak_check_plan_tolerances(out, segs, tols.data(), nsegs, num_candidates, equal_nan, device);
+}
+
+geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs, const geak_tolerance *tols,
+                                       uint64_t nsegs, int32_t num_candidates, int32_t equal_nan, int32_t device)
 {
     if (!out) return GEAK_EINVAL;
     if (device < -1) return GEAK_EINVAL;
@@ -83,7 +99,7 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
         max_blocks = (uint32_t)prop.multiProcessorCount * (uint32_t)per_cu;
     }
 
-    geak_status st = build_host_plan(p->host, segs, nsegs, num_candidates, atol, rtol, equal_nan, max_blocks);
+    geak_status st = build_host_plan(p->host, segs, tols, nsegs, num_candidates, equal_nan, max_blocks);
     if (st != GEAK_OK) { delete p; return st; }
 
     if (device >= 0) {
@@ -97,11 +113,14 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
         if (ok) ok = hipMalloc((void **)&p->wave_first_dev, wave_bytes) == hipSuccess;
         const size_t seg_bytes = p->host.segments.size() * sizeof(geak_segment);
         if (ok) ok = hipMalloc((void **)&p->segments_dev, seg_bytes) == hipSuccess;
+        const size_t tol_bytes = p->host.seg_tol.size() * sizeof(SegTol);
+        if (ok) ok = hipMalloc((void **)&p->seg_tol_dev, tol_bytes) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_ENOMEM; }
         if (item_bytes) ok = hipMemcpy(p->items_dev, p->host.items.data(), item_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->slot_begin_dev, p->host.slot_begin.data(), slot_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->wave_first_dev, p->host.wave_first.data(), wave_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->segments_dev, p->host.segments.data(), seg_bytes, hipMemcpyHostToDevice) == hipSuccess;
+        if (ok) ok = hipMemcpy(p->seg_tol_dev, p->host.seg_tol.data(), tol_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_EHIP; }
     }
     *out = p;
@@ -197,8 +216,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.reserved0 = 0;
         ca.num_items = (uint32_t)hp.items.size();
         ca.num_candidates = (uint32_t)K;
-        ca.atol_f = hp.atol_f;
-        ca.rtol_f = hp.rtol_f;
+        ca.seg_tol = plan->seg_tol_dev;
         ca.equal_nan = hp.equal_nan;
         ca.reserved = 0;
         ca.wave_first = plan->wave_first_dev;
@@ -224,8 +242,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ra.cand_table = cand_table;
         ra.num_segments = (uint32_t)hp.segments.size();
         ra.num_candidates = (uint32_t)K;
-        ra.atol_f = hp.atol_f;
-        ra.rtol_f = hp.rtol_f;
+        ra.seg_tol = plan->seg_tol_dev;
         ra.equal_nan = hp.equal_nan;
         ra.replicas = hp.replicas;
         if (launch_reduce(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
@@ -351,8 +368,7 @@ geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const 
     ra.num_segments = (uint32_t)hp.segments.size();
     ra.num_candidates = (uint32_t)K;
     ra.max_records = max_records;
-    ra.atol_f = hp.atol_f;
-    ra.rtol_f = hp.rtol_f;
+    ra.seg_tol = plan->seg_tol_dev;
     ra.equal_nan = hp.equal_nan;
     if (launch_report(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
     return GEAK_OK;

@@ -35,6 +35,12 @@ inline uint32_t lds_bytes_for(int num_candidates) {
     return lds_state_bytes(num_candidates) + kWavesPerBlock * kTolBytesPerWave;
 }
 
+// Tolerances of one segment, converted once to binary32.
+struct SegTol {
+    float atol_f;
+    float rtol_f;
+};
+
 // Host side of a plan: everything that can be decided without a device.
 struct HostPlan {
     std::vector<geak_segment> segments;
@@ -42,7 +48,7 @@ struct HostPlan {
     std::vector<uint32_t> slot_begin;      // per segment, size nsegs + 1; slots of a segment are contiguous
     uint64_t algorithmic_bytes = 0;
     int num_candidates = 0;
-    float atol_f = 0.f, rtol_f = 0.f;
+    std::vector<SegTol> seg_tol;          // per segment, already in binary32
     int equal_nan = 0;
     uint32_t grid_blocks = 1;
     uint32_t replicas = 1;                 // replicas of the running maxima per (segment, candidate)
@@ -52,8 +58,8 @@ struct HostPlan {
 };
 
 // Validates and builds the work table for a persistent grid of at most `max_blocks` blocks.
-geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nsegs, int32_t num_candidates,
-                            double atol, double rtol, int32_t equal_nan, uint32_t max_blocks);
+geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_tolerance *tols, uint64_t nsegs,
+                            int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks);
 
 // Running maxima of one (segment, candidate, replica): non-negative doubles, raised by atomic max on
 // their bit patterns.
@@ -92,8 +98,7 @@ struct CompareArgs {
     uint32_t reserved0;
     uint32_t num_items;
     uint32_t num_candidates;
-    float atol_f;
-    float rtol_f;
+    const SegTol *seg_tol;               // device table, one entry per segment
     int equal_nan;
     int reserved;
     const uint32_t *wave_first;          // grid_blocks * kWavesPerBlock entries
@@ -109,8 +114,7 @@ struct ReduceArgs {
     const unsigned char *const *cand_table;
     uint32_t num_segments;
     uint32_t num_candidates;
-    float atol_f;
-    float rtol_f;
+    const SegTol *seg_tol;               // device table, one entry per segment
     int equal_nan;
     uint32_t replicas;
 };
@@ -134,8 +138,7 @@ struct ReportArgs {
     uint32_t num_segments;
     uint32_t num_candidates;
     uint32_t max_records;
-    float atol_f;
-    float rtol_f;
+    const SegTol *seg_tol;               // device table, one entry per segment
     int equal_nan;
 };
 

@@ -86,6 +86,17 @@ __device__ __forceinline__ const unsigned char *table_entry(const unsigned char 
     return reinterpret_cast<const unsigned char *>(t[k]);
 }
 
+// A segment's tolerance pair, read with a scalar load when the segment index is wave-uniform.
+__device__ __forceinline__ SegTol load_tol(const SegTol *table, uint32_t segment)
+{
+    const GEAK_AS_CONSTANT unsigned long long *t = (const GEAK_AS_CONSTANT unsigned long long *)table;
+    const unsigned long long w = t[segment];
+    SegTol out;
+    out.atol_f = __builtin_bit_cast(float, (uint32_t)w);
+    out.rtol_f = __builtin_bit_cast(float, (uint32_t)(w >> 32));
+    return out;
+}
+
 template <int DT> struct Traits;
 template <> struct Traits<GEAK_F32>  { static constexpr int E = 4, W = 4; };
 template <> struct Traits<GEAK_F16>  { static constexpr int E = 8, W = 2; };
@@ -192,8 +203,8 @@ __device__ __forceinline__ uint32_t wave_min_u(uint32_t x)
     return x;
 }
 
-// Non-negative doubles order like their bit patterns, so the maxima live in the result record
-// itself and are raised with an unsigned 64-bit atomic max.
+// Non-negative doubles order like their bit patterns, so the running maxima on the board are
+// raised with an unsigned 64-bit atomic max.
 __device__ __forceinline__ u64 load_bits(const double *p)
 {
     // through the global address space: a flat load would also count against the LDS / scalar-load
@@ -845,8 +856,7 @@ struct RunArgs {
     uint32_t K;
     uint32_t k0;
     uint32_t priority_phase;             // dispatch round of the block: (block * 4) / grid
-    float atol_f;
-    float rtol_f;
+    const SegTol *seg_tol;               // per-segment tolerances
     int equal_nan;
 };
 
@@ -893,12 +903,13 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     const uint32_t replicas = uniform32(in.replicas), replica = uniform32(in.replica);
     const uint32_t num_items = uniform32(in.num_items), K = uniform32(in.K), k0 = uniform32(in.k0);
     uint32_t priority = uniform32(in.priority_phase);
-    const float atol_f = bits_f(uniform32(f_bits(in.atol_f))), rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
+    const SegTol *seg_tol = uniform_ptr(in.seg_tol);
     const int equal_nan = (int)uniform32((uint32_t)in.equal_nan);
     const int lane = threadIdx.x & (kWaveSize - 1);
 
     uint32_t j = uniform32(in.first_item);
     geak_item it = load_work_item(items, j);
+    SegTol tolerance = load_tol(seg_tol, it.segment);
     Item ref;
     ref.attach_lds(st.tol_off, lane);
     u32x4 cur[kVecPerLane];
@@ -916,6 +927,8 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
             nx = load_work_item(items, jn);
             more = (nx.flags & GEAK_ITEM_FULL) && nx.dtype == DT;
         }
+        const float atol_f = tolerance.atol_f, rtol_f = tolerance.rtol_f;
+        if (more) tolerance = load_tol(seg_tol, nx.segment);          // the next item's, a whole item ahead of its use
         if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
         MaxPair *recs = board + (u64)it.segment * K * replicas + replica;     // candidate k: recs[k * replicas]
 
@@ -979,11 +992,13 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     Partial *partials = uniform_ptr(in.partials);
     const uint32_t replicas = uniform32(in.replicas), replica = uniform32(in.replica);
     const uint32_t K = uniform32(in.K);
-    const float atol_f = bits_f(uniform32(f_bits(in.atol_f))), rtol_f = bits_f(uniform32(f_bits(in.rtol_f)));
+    const SegTol *seg_tol = uniform_ptr(in.seg_tol);
     const int equal_nan = (int)uniform32((uint32_t)in.equal_nan);
     const int lane = threadIdx.x & (kWaveSize - 1);
     const uint32_t j = uniform32(in.first_item);
     const geak_item it = load_work_item(items, j);
+    const SegTol tolerance = load_tol(seg_tol, it.segment);
+    const float atol_f = tolerance.atol_f, rtol_f = tolerance.rtol_f;
     const uint32_t n = it.numel;
     const uint32_t vectors = (n * Traits<DT>::W + kWaveSize * 16 - 1) / (kWaveSize * 16);    // 1..4 per lane
     const uint32_t per_batch = vectors == 1 ? 4 : (vectors == 2 ? 2 : 1);                       // candidates per batch
@@ -1077,9 +1092,10 @@ __device__ __forceinline__ void process_head(const geak_item &it, uint32_t item_
 {
     const uint32_t K = p.num_candidates;
     MaxPair *recs = p.board + (u64)it.segment * K * p.replicas + (blockIdx.x & (p.replicas - 1));
+    const SegTol tolerance = load_tol(p.seg_tol, it.segment);
     for (uint32_t k = 0; k < K; ++k) {
         const uint32_t bad = exact_item(p.ref + it.byte_offset, table_entry(p.cand_table, k) + it.byte_offset, it.numel,
-                                        it.dtype, p.atol_f, p.rtol_f, p.equal_nan, &recs[k * p.replicas]);
+                                        it.dtype, tolerance.atol_f, tolerance.rtol_f, p.equal_nan, &recs[k * p.replicas]);
         note_mismatches(st, k, bad, item_index, lane);
     }
 }
@@ -1108,8 +1124,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.K = K;
     r.k0 = (blockIdx.x / p.replicas) % K;
     r.priority_phase = (blockIdx.x * 4u) / gridDim.x;
-    r.atol_f = p.atol_f;
-    r.rtol_f = p.rtol_f;
+    r.seg_tol = p.seg_tol;
     r.equal_nan = p.equal_nan;
 
     // the wave's list of items: its first one from the wave table, then along the next links
@@ -1227,13 +1242,14 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
     long long first = -1;
     if (first_item != kNoItem) {                // uniform: every thread holds the same first_item
         const geak_item it = p.items[first_item];
+        const SegTol tolerance = p.seg_tol[seg];
         const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
         constexpr int kPer = (kItemBytes / 2 + kReduceThreads - 1) / kReduceThreads;   // 8: most elements a thread can own
         bool bad[kPer];
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
             const uint32_t i = (uint32_t)tid + u * kReduceThreads;
-            bad[u] = (i < it.numel) && !element_close(rb, cb, i, it.dtype, p.atol_f, p.rtol_f, p.equal_nan);
+            bad[u] = (i < it.numel) && !element_close(rb, cb, i, it.dtype, tolerance.atol_f, tolerance.rtol_f, p.equal_nan);
         }
         uint32_t best = kNoItem;
 #pragma unroll
@@ -1292,7 +1308,7 @@ __device__ __forceinline__ float elem_f(const unsigned char *base, u64 idx)
 }
 
 template <int DT>
-__device__ __forceinline__ void report_pair(const ReportArgs &p, const geak_segment &sg, const geak_result &rec, u64 want,
+__device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol tolerance, const geak_segment &sg, const geak_result &rec, u64 want,
                                             const unsigned char *rb, const unsigned char *cb, geak_mismatch *out,
                                             uint32_t (&s_cnt)[kReportPerThread][kReportThreads / kWaveSize])
 {
@@ -1321,7 +1337,7 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const geak_segm
         for (int u = 0; u < kReportPerThread; ++u) {
             const u64 i = base + (u64)u * kReportThreads + tid;
             if constexpr (DT == GEAK_I32) bad[u] = (i < sg.numel) && ai[u] != bi[u];
-            else bad[u] = (i < sg.numel) && !close_exact(av[u], bv[u], p.atol_f, p.rtol_f, p.equal_nan);
+            else bad[u] = (i < sg.numel) && !close_exact(av[u], bv[u], tolerance.atol_f, tolerance.rtol_f, p.equal_nan);
             const u64 mask = __builtin_amdgcn_ballot_w64(bad[u]);
             before[u] = (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
             if (lane == 0) s_cnt[u][wave] = (uint32_t)__builtin_popcountll(mask);
@@ -1351,11 +1367,11 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const geak_segm
                     m.d = (double)(diff < 0 ? -diff : diff);
                     m.tol = 0.0;
                 } else {
-                    const float prod = p.rtol_f * __builtin_fabsf(bv[u]);
+                    const float prod = tolerance.rtol_f * __builtin_fabsf(bv[u]);
                     m.a = (double)av[u];
                     m.b = (double)bv[u];
                     m.d = (double)__builtin_fabsf(av[u] - bv[u]);
-                    m.tol = (double)(p.atol_f + prod);
+                    m.tol = (double)(tolerance.atol_f + prod);
                 }
                 out[pos] = m;
             }
@@ -1377,13 +1393,14 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     if (threadIdx.x == 0) p.counts[blockIdx.x] = (uint32_t)want;
     if (want == 0) return;                                   // uniform
     const geak_segment sg = p.segments[seg];
+    const SegTol tolerance = p.seg_tol[seg];
     const unsigned char *rb = p.ref + sg.byte_offset, *cb = p.cand_table[k] + sg.byte_offset;
     geak_mismatch *out = p.records + (u64)blockIdx.x * p.max_records;
     switch (sg.dtype) {                                      // uniform
-    case GEAK_F32:  report_pair<GEAK_F32>(p, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_F16:  report_pair<GEAK_F16>(p, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_BF16: report_pair<GEAK_BF16>(p, sg, rec, want, rb, cb, out, s_cnt); break;
-    default:        report_pair<GEAK_I32>(p, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_F32:  report_pair<GEAK_F32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_F16:  report_pair<GEAK_F16>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_BF16: report_pair<GEAK_BF16>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    default:        report_pair<GEAK_I32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     }
 }
 

@@ -14,16 +14,18 @@ namespace geak {
 
 static bool mul_overflows(uint64_t a, uint64_t b) { return b != 0 && a > UINT64_MAX / b; }
 
-geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nsegs, int32_t num_candidates,
-                            double atol, double rtol, int32_t equal_nan, uint32_t max_blocks)
+geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_tolerance *tols, uint64_t nsegs,
+                            int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks)
 {
-    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    if (!segs || !tols || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
     if (num_candidates < 1 || num_candidates > GEAK_MAX_CANDIDATES) return GEAK_EINVAL;
-    if (!(atol >= 0.0) || !(rtol >= 0.0) || std::isinf(atol) || std::isinf(rtol)) return GEAK_EINVAL;
     if (equal_nan != 0 && equal_nan != 1) return GEAK_EINVAL;
     if (max_blocks == 0) return GEAK_EINVAL;
-    const float atol_f = (float)atol, rtol_f = (float)rtol;
-    if (std::isinf(atol_f) || std::isinf(rtol_f)) return GEAK_EINVAL;   // finite in binary64 but not in binary32
+    for (uint64_t s = 0; s < nsegs; ++s) {
+        const double atol = tols[s].atol, rtol = tols[s].rtol;
+        if (!(atol >= 0.0) || !(rtol >= 0.0) || std::isinf(atol) || std::isinf(rtol)) return GEAK_EINVAL;
+        if (std::isinf((float)atol) || std::isinf((float)rtol)) return GEAK_EINVAL;   // finite in binary64 but not in binary32
+    }
 
     // per-segment checks
     uint64_t total_bytes = 0;
@@ -71,8 +73,8 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, uint64_t nse
         hp.items.reserve(n_items);
         hp.slot_begin.assign(nsegs + 1, 0);
         hp.num_candidates = num_candidates;
-        hp.atol_f = atol_f;
-        hp.rtol_f = rtol_f;
+        hp.seg_tol.resize(nsegs);
+        for (uint64_t s = 0; s < nsegs; ++s) hp.seg_tol[s] = SegTol{(float)tols[s].atol, (float)tols[s].rtol};
         hp.equal_nan = equal_nan;
         hp.algorithmic_bytes = total_bytes * ((uint64_t)num_candidates + 1);
         hp.max_blocks = max_blocks;

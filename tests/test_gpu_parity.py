@@ -159,6 +159,38 @@ def test_ragged_unaligned_starts(oracle_mod, align):
     _assert_same(gpu, cpu, f"ragged align={align}")
 
 
+def test_per_segment_tolerances(oracle_mod):
+    """Every segment judged with its own atol / rtol (tight, loose, zero): records equal the oracle's,
+    called segment by segment with that segment's pair; int32 segments ignore theirs."""
+    rng = np.random.default_rng(77)
+    w = synth.small(4, device="cuda")
+    tols = [(float(10.0 ** rng.uniform(-7, -1)), float(10.0 ** rng.uniform(-7, -1))) if s % 5 else (0.0, 0.0)
+            for s in range(len(w.segments))]
+    ck = B.Checker(w.segments, num_candidates=len(w.cands), equal_nan=w.equal_nan, device=0, tolerances=tols)
+    try:
+        ck.run(w.ref, w.cands)
+        gpu = ck.read().copy()
+        rec, cnt = ck.report(w.ref, w.cands, 3)
+    finally:
+        ck.close()
+    ref = synth.to_numpy_raw(w.ref)
+    cands = [synth.to_numpy_raw(c) for c in w.cands]
+    differs = 0
+    for s, (off, numel, dt) in enumerate(w.segments):
+        atol, rtol = tols[s]
+        for k, c in enumerate(cands):
+            cpu = oracle_mod.check_segment(ref, c, numel, dt, atol, rtol, w.equal_nan, ref_byte_offset=off)
+            assert record_tuple(gpu[s, k]) == record_tuple(cpu), (s, k, dt, numel, atol, rtol)
+            plain = oracle_mod.check_segment(ref, c, numel, dt, w.atol, w.rtol, w.equal_nan, ref_byte_offset=off)
+            differs += int(cpu["mismatch_count"]) != int(plain["mismatch_count"])
+            rep = oracle_mod.report_segment(ref, c, numel, dt, atol, rtol, w.equal_nan, 3, ref_byte_offset=off)
+            assert int(cnt[s, k]) == len(rep)
+            got = rec[s, k][:len(rep)]
+            assert (got["index"] == rep["index"]).all()
+            assert all(np.array_equal(got[f], rep[f], equal_nan=True) for f in ("a", "b", "d", "tol"))
+    assert differs > 20          # the per-segment pairs really change verdicts relative to one plan-wide pair
+
+
 def test_empty_and_tiny_segments(oracle_mod):
     segs = [(0, 0, "f32"), (16, 1, "bf16"), (32, 0, "i32"), (48, 3, "i32"), (64, 2049, "f16"), (4176, 0, "f16")]
     total = 4176 + 16

@@ -33,6 +33,8 @@ def test_struct_sizes_match_header():
     assert B.SEGMENT_DTYPE.itemsize == 24
     assert B.RESULT_DTYPE.itemsize == 40
     assert B.ITEM_DTYPE.itemsize == 32
+    assert B.MISMATCH_DTYPE.itemsize == 40
+    assert ctypes.sizeof(B.PlanInfo) == 64
 
 
 def _plan(segs, K=2, atol=1e-3, rtol=1e-3, eq=0, device=-1):
@@ -260,3 +262,17 @@ def test_work_table_persistent_grid(lib):
     sizes = np.diff(B.geak_check_plan_blocks(plan).astype(np.int64))
     assert sizes.max() - sizes.min() <= 1                # a dense tensor splits evenly
     B.geak_check_destroy(plan)
+
+
+def test_per_segment_tolerances_are_validated(lib):
+    segs = [(0, 100, "f32"), (400, 50, "f16")]
+    st, plan = B.geak_check_plan_tolerances(segs, [(1e-3, 1e-2), (0.0, 0.5)], 2, 0, -1)
+    assert st == B.GEAK_OK
+    assert B.geak_check_result_count(plan) == 4
+    B.geak_check_destroy(plan)
+    for bad in ([(1e-3, 1e-2), (-1.0, 0.0)], [(float("nan"), 0.0), (0.0, 0.0)], [(0.0, float("inf")), (0.0, 0.0)],
+                [(1e300, 0.0), (0.0, 0.0)]):                       # the last: finite in binary64, infinite in binary32
+        st, plan = B.geak_check_plan_tolerances(segs, bad, 2, 0, -1)
+        assert st == B.GEAK_EINVAL and plan is None
+    st, plan = B.geak_check_plan_tolerances(segs, None, 2, 0, -1)
+    assert st == B.GEAK_EINVAL and plan is None
