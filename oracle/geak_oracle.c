@@ -25,6 +25,10 @@
  *     R5  -0 vs +0 gives d = 0, hence close
  *   int32:
  *     R6  close <=> a == b; d = |a - b| exactly (64-bit), tolerances ignored
+ *   int64 (index outputs of sort / argmax-like kernels):
+ *     R6' close <=> a == b; d = |a - b| exactly as an unsigned 64-bit integer (at most 2^64 - 1);
+ *         where a binary64 value is needed (R8, R9, the report) d and |b| (at most 2^63) are each
+ *         converted to binary64 with one rounding to nearest even
  *   reductions per (segment, candidate):
  *     R7  mismatch_count = #{i : not close_i}; first_mismatch = least such i, else -1;
  *         pass = (mismatch_count == 0); an empty segment passes
@@ -54,7 +58,7 @@
 #include <xmmintrin.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2, ORACLE_I32 = 3 };
+enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2, ORACLE_I32 = 3, ORACLE_I64 = 4 };
 
 typedef struct {
     int32_t  pass;
@@ -110,7 +114,7 @@ static int is_inf_f(float x) { return x == INFINITY || x == -INFINITY; }
 int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int dtype,
                          double atol, double rtol, int equal_nan, oracle_record *out)
 {
-    if (!out || dtype < 0 || dtype > 3)
+    if (!out || dtype < 0 || dtype > 4)
         return -1;
 
 #if defined(__SSE2__)
@@ -124,7 +128,29 @@ int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int 
     double   max_abs = 0.0;
     double   max_rel = 0.0;
 
-    if (dtype == ORACLE_I32) {
+    if (dtype == ORACLE_I64) {
+        const int64_t *pb = (const int64_t *)ref;
+        const int64_t *pa = (const int64_t *)cand;
+        for (uint64_t i = 0; i < numel; ++i) {
+            int64_t a = pa[i], b = pb[i];
+            /* |a - b| without overflow: subtract the smaller from the larger in unsigned arithmetic */
+            uint64_t d = (a >= b) ? ((uint64_t)a - (uint64_t)b) : ((uint64_t)b - (uint64_t)a);
+            if (a != b) {                                    /* R6' */
+                ++count;
+                if (first < 0) first = (int64_t)i;
+            }
+            double dd = (double)d;                           /* one rounding */
+            if (dd > max_abs) max_abs = dd;                  /* R8 */
+            double r;
+            if (d == 0) {
+                r = 0.0;
+            } else {
+                uint64_t babs_u = (b < 0) ? (0 - (uint64_t)b) : (uint64_t)b;     /* |INT64_MIN| = 2^63 fits */
+                r = dd / (double)babs_u;                     /* R9, binary64; x/0 = +Inf */
+            }
+            if (r > max_rel) max_rel = r;
+        }
+    } else if (dtype == ORACLE_I32) {
         const int32_t *pb = (const int32_t *)ref;
         const int32_t *pa = (const int32_t *)cand;
         for (uint64_t i = 0; i < numel; ++i) {
@@ -216,7 +242,8 @@ int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int 
  * analyse it; the paper does not say what the trace holds, so this is the reading: for every
  * reported element its flat index, a and b widened exactly to binary64, d = |a (-) b| and
  * tol = atol_f (+) (rtol_f (x) |b|) exactly as rules R1 / R6 compute them (binary32 values widened;
- * for int32 d is exact and tol is 0).  d and tol may be NaN or infinite when a or b is.
+ * for int32 d is exact and tol is 0; for int64 a, b and d are each converted to binary64 with one
+ * rounding).  d and tol may be NaN or infinite when a or b is.
  * Returns the number of records written (at most max_records), or -1 on a bad argument.
  */
 typedef struct {
@@ -231,7 +258,7 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
                               double atol, double rtol, int equal_nan, uint64_t max_records,
                               oracle_mismatch *out)
 {
-    if ((!out && max_records) || dtype < 0 || dtype > 3)
+    if ((!out && max_records) || dtype < 0 || dtype > 4)
         return -1;
 #if defined(__SSE2__)
     unsigned int csr_saved = _mm_getcsr();
@@ -243,7 +270,15 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
     for (uint64_t i = 0; i < numel && written < max_records; ++i) {
         oracle_mismatch m;
         int close;
-        if (dtype == ORACLE_I32) {
+        if (dtype == ORACLE_I64) {
+            int64_t a = ((const int64_t *)cand)[i], b = ((const int64_t *)ref)[i];
+            uint64_t d = (a >= b) ? ((uint64_t)a - (uint64_t)b) : ((uint64_t)b - (uint64_t)a);
+            close = (a == b);                                    /* R6' */
+            m.a = (double)a;                                     /* one rounding each */
+            m.b = (double)b;
+            m.d = (double)d;
+            m.tol = 0.0;
+        } else if (dtype == ORACLE_I32) {
             int64_t a = ((const int32_t *)cand)[i], b = ((const int32_t *)ref)[i];
             int64_t diff = a - b;
             close = (a == b);                                    /* R6 */

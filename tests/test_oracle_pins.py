@@ -200,6 +200,18 @@ def test_fma_contraction_would_be_caught(oracle_mod):
 # structural invariants
 # ------------------------------------------------------------------------------------------
 def _rand_case(rng, dtype, n):
+    if dtype == "i64":
+        # small values, values beyond 2^53 (where the binary64 conversions round) and the two extremes
+        b = rng.integers(-1000, 1001, n).astype(np.int64)
+        big = rng.random(n) < 0.1
+        b[big] = rng.integers(-(2 ** 62), 2 ** 62, int(big.sum()), dtype=np.int64) * 2 + 1
+        b[rng.random(n) < 0.01] = np.iinfo(np.int64).min
+        a = b.copy()
+        idx = rng.random(n) < 0.05
+        a[idx] = (a[idx].astype(np.uint64) + rng.integers(1, 4, int(idx.sum())).astype(np.uint64)).astype(np.int64)   # wraps at the top
+        far = rng.random(n) < 0.01
+        a[far] = np.iinfo(np.int64).max
+        return b, a
     if dtype == "i32":
         b = rng.integers(-1000, 1001, n).astype(np.int32)
         a = b.copy()
@@ -221,7 +233,7 @@ def _rand_case(rng, dtype, n):
     return tb, ta
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64"])
 def test_invariants(oracle_mod, dtype):
     rng = np.random.default_rng(11)
     n = 3001
@@ -230,7 +242,7 @@ def test_invariants(oracle_mod, dtype):
     full = oracle_mod.check_segment(b, a, n, dtype, **kw)
 
     # a bit-identical copy of a NaN-free tensor is the neutral record
-    if dtype == "i32":
+    if dtype in ("i32", "i64"):
         clean = b
     else:
         _, clean = _rand_case(np.random.default_rng(12), dtype, n)
@@ -348,3 +360,30 @@ def test_planted_counts(oracle_mod, cid):
     assert n_fail > 0
     if cid in (1, 3, 4):
         assert n_fail < rec.size            # these recipes contain passing candidates too
+
+
+def test_int64_hand_derived(oracle_mod):
+    """int64 (rule R6'): exact equality; |a - b| exact as an unsigned 64-bit integer, then one rounding
+    to binary64; the relative error divides the rounded d by the rounded |b|."""
+    i64 = np.iinfo(np.int64)
+    b = np.array([5, i64.min, 7, 0, 2 ** 62, -3, 2 ** 53 + 1], dtype=np.int64)
+    a = np.array([5, i64.max, 9, 3, 2 ** 62 + 1, -3, 2 ** 53 + 3], dtype=np.int64)
+    rec = oracle_mod.check_segment(b, a, len(b), "i64", 1e9, 1e9, False)      # tolerances are ignored
+    assert (int(rec["pass"]), int(rec["mismatch_count"]), int(rec["first_mismatch"])) == (0, 5, 1)
+    assert float(rec["max_abs_err"]) == 2.0 ** 64          # 2^64 - 1 rounds up to 2^64
+    assert float(rec["max_rel_err"]) == np.inf             # 3 / 0
+    # without the zero reference: largest ratio is (2^64 - 1 -> 2^64) / 2^63 = 2
+    keep = [0, 1, 2, 4, 5, 6]
+    rec = oracle_mod.check_segment(b[keep], a[keep], len(keep), "i64", 0.0, 0.0, False)
+    assert float(rec["max_rel_err"]) == 2.0 and int(rec["mismatch_count"]) == 4
+    # 2^53 + 1 and 2^53 + 3 differ by exactly 2 although both round when converted: d is taken before any rounding
+    rec = oracle_mod.check_segment(b[6:], a[6:], 1, "i64", 0.0, 0.0, False)
+    assert float(rec["max_abs_err"]) == 2.0
+    assert float(rec["max_rel_err"]) == 2.0 / float(2 ** 53 + 1)               # |b| converted with one rounding (to 2^53)
+    rep = oracle_mod.report_segment(b, a, len(b), "i64", 0.0, 0.0, False, 8)
+    assert [int(r["index"]) for r in rep] == [1, 2, 3, 4, 6]
+    assert float(rep[0]["a"]) == 2.0 ** 63 and float(rep[0]["b"]) == -(2.0 ** 63) and float(rep[0]["d"]) == 2.0 ** 64
+    assert float(rep[3]["d"]) == 1.0 and float(rep[3]["tol"]) == 0.0
+    # equal extremes pass
+    same = np.array([i64.min, i64.max, 0], dtype=np.int64)
+    assert int(oracle_mod.check_segment(same, same.copy(), 3, "i64", 0.0, 0.0, False)["pass"]) == 1
