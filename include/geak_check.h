@@ -14,7 +14,9 @@
  *       d = |a - b|,  tol = atol_f + (rtol_f * |b|),  close <=> d <= tol
  *       a or b NaN   : close <=> equal_nan and both NaN
  *       a or b +-Inf : close <=> a == b
- *   int32:             close <=> a == b   (atol, rtol, equal_nan ignored; d exact)
+ *   int32, int64:      close <=> a == b   (atol, rtol, equal_nan ignored; d = |a - b| exact; for int64
+ *                      d (up to 2^64 - 1) and |b| are each rounded once to binary64 where a double is
+ *                      needed: max_abs_err, max_rel_err, the mismatch report)
  *
  *   and reduces, for every (segment, candidate) pair, the record `geak_result`:
  *       mismatch_count  number of elements that are not close
@@ -22,7 +24,7 @@
  *       pass            1 iff mismatch_count == 0 (an empty segment passes)
  *       max_abs_err     max of d over ALL elements, NaN d skipped, +Inf kept, starting at +0
  *       max_rel_err     max over all elements of (d == 0 ? 0 : d / |b|) (binary32 division for
- *                       floating dtypes, binary64 for int32; x/0 = +Inf; NaN skipped), from +0
+ *                       floating dtypes, binary64 for the integer dtypes; x/0 = +Inf; NaN skipped), from +0
  *   Every field is an order-independent reduction, so results are bit-reproducible.
  *
  * Memory model.  The caller owns every device buffer (reference, candidates, workspace, results)
@@ -50,7 +52,7 @@ typedef enum {
     GEAK_EHIP = 7        /* a HIP runtime call failed (no device, launch error) */
 } geak_status;
 
-typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3 } geak_dtype;
+typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64 = 4 } geak_dtype;
 
 #define GEAK_MAX_CANDIDATES 256
 #define GEAK_MAX_SEGMENT_NUMEL (1ull << 40)

@@ -15,7 +15,7 @@ constexpr int kDefaultComputeUnits = 256;                        // host-only pl
 constexpr int kDefaultBlocksPerCU = 4;
 constexpr uint32_t kNoItem = 0xFFFFFFFFu;
 
-inline int elem_size(int dtype) { return (dtype == GEAK_F16 || dtype == GEAK_BF16) ? 2 : 4; }
+inline int elem_size(int dtype) { return (dtype == GEAK_F16 || dtype == GEAK_BF16) ? 2 : (dtype == GEAK_I64 ? 8 : 4); }
 
 // Partial result of one (worker, segment) run for one candidate; 16 bytes.
 struct Partial {

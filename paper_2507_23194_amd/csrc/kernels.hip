@@ -102,6 +102,7 @@ template <> struct Traits<GEAK_F32>  { static constexpr int E = 4, W = 4; };
 template <> struct Traits<GEAK_F16>  { static constexpr int E = 8, W = 2; };
 template <> struct Traits<GEAK_BF16> { static constexpr int E = 8, W = 2; };
 template <> struct Traits<GEAK_I32>  { static constexpr int E = 4, W = 4; };
+template <> struct Traits<GEAK_I64>  { static constexpr int E = 2, W = 8; };
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t f_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
@@ -150,7 +151,12 @@ __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, i
     if (first + E <= n) {
         q = __builtin_nontemporal_load(p);
     } else if (first < n) {
-        if constexpr (Traits<DT>::W == 4) {
+        if constexpr (Traits<DT>::W == 8) {
+            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (first + e < n) { q[2 * e] = w[2 * e]; q[2 * e + 1] = w[2 * e + 1]; }
+        } else if constexpr (Traits<DT>::W == 4) {
             const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
 #pragma unroll
             for (uint32_t e = 0; e < E; ++e)
@@ -245,6 +251,19 @@ __device__ __forceinline__ bool may_raise_rel(float r, float babs, float d)
     return __builtin_amdgcn_classf(__builtin_fmaf(r, babs, -d), kClassNegative);
 }
 
+// int64 elements: |a - b| exact as an unsigned 64-bit integer and |b| (at most 2^63), each converted to
+// binary64 with one rounding where a double is needed.
+__device__ __forceinline__ double i64_abs_diff(long long a, long long x)
+{
+    const u64 d = (a >= x) ? ((u64)a - (u64)x) : ((u64)x - (u64)a);
+    return (double)d;
+}
+__device__ __forceinline__ double i64_abs(long long x)
+{
+    const u64 m = (x < 0) ? (0ull - (u64)x) : (u64)x;
+    return (double)m;
+}
+
 // ---- exact element-wise evaluation of one item for one candidate, straight from memory ----------
 // Used (a) for segment heads and tails, (b) when the hot loop finds that an item may raise one of
 // the maxima.  Returns the wave-uniform mismatch count and raises the record's maxima.
@@ -254,17 +273,23 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
     const int lane = threadIdx.x & (kWaveSize - 1);
     const u64 abs_bits = load_bits(&rec->abs), rel_bits = load_bits(&rec->rel);
     uint32_t bad = 0;
-    if (dtype == GEAK_I32) {
+    if (dtype == GEAK_I32 || dtype == GEAK_I64) {
         const double seen_rel = __builtin_bit_cast(double, rel_bits);
         // d > c*|b| is implied by d/|b| > seen_rel; the 2^-30 margin covers the product's rounding
         const double c = (seen_rel == (double)kInfF) ? __builtin_nan("") : seen_rel * (1.0 - 0x1p-30);
         double dm = 0.0, rm = 0.0;
         for (uint32_t i = lane; i < n; i += kWaveSize) {
-            const long long a = reinterpret_cast<const int *>(cand)[i], x = reinterpret_cast<const int *>(ref)[i];
-            const long long diff = a - x;
+            long long a, x;
+            if (dtype == GEAK_I32) {
+                a = reinterpret_cast<const int *>(cand)[i];
+                x = reinterpret_cast<const int *>(ref)[i];
+            } else {
+                a = reinterpret_cast<const long long *>(cand)[i];
+                x = reinterpret_cast<const long long *>(ref)[i];
+            }
             bad += (a != x);
-            const double d = (double)(diff < 0 ? -diff : diff);
-            const double babs = (double)(x < 0 ? -x : x);
+            const double d = i64_abs_diff(a, x);                  // exact for int32 operands
+            const double babs = i64_abs(x);
             if (d > dm) dm = d;
             if (d > c * babs) {                                   // implies d > 0
                 const double r = d / babs;                        // binary64, correctly rounded; d/0 = +Inf
@@ -814,8 +839,86 @@ __device__ __noinline__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b
     return out;
 }
 
+// ---- int64: two elements per 16-byte vector, exact equality ------------------------------------------
+__device__ __noinline__ DoublePair raise_vector_int64(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
+                                                      MaxPair *rec_in)
+{
+    MaxPair *rec = uniform_ptr(rec_in);
+    double dm = max_abs, rm = max_rel;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const long long a = (long long)((u64)q[2 * e] | ((u64)q[2 * e + 1] << 32));
+        const long long x = (long long)((u64)b[2 * e] | ((u64)b[2 * e + 1] << 32));
+        const double d = i64_abs_diff(a, x);
+        const double babs = i64_abs(x);
+        dm = (d > dm) ? d : dm;
+        // d/|b| > rm implies d > rm*|b|*(1 - 2^-30); the margin covers the product's rounding
+        if (d > 0.0 && (rm < (double)kInfF) && d > rm * (1.0 - 0x1p-30) * babs) {
+            const double r = d / babs;                               // binary64, correctly rounded; d/0 = +Inf
+            rm = (r > rm) ? r : rm;
+        }
+    }
+    dm = wave_max_d(dm);
+    rm = wave_max_d(rm);
+    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
+        if (dm > max_abs) publish_max(&rec->abs, dm);
+        if (rm > max_rel) publish_max(&rec->rel, rm);
+    }
+    DoublePair out;
+    out.abs = dm;
+    out.rel = rm;
+    return out;
+}
+
+struct Int64Item {
+    typedef double Hint;
+    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
+    static constexpr int E = 2;
+    static constexpr bool kRaiseOutOfLine = true;
+    uint32_t bref[kVecPerLane * 4];
+    __device__ __forceinline__ void attach_lds(uint32_t, int) {}
+    static constexpr uint32_t poisoned_slots = 0;
+
+    template <int V>
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, float, float)
+    {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
+    }
+    // Any unequal element is a mismatch and the only kind of element that can raise a maximum.
+    template <int V, bool AHEAD = true>
+    __device__ __forceinline__ void compare_vec(const u32x4 &q, double, double, uint32_t &suspects, u64 &trip_abs, u64 &, int) const
+    {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const uint32_t differ = (q[2 * e] ^ bref[V * 4 + 2 * e]) | (q[2 * e + 1] ^ bref[V * 4 + 2 * e + 1]);
+            const u64 m = __builtin_amdgcn_ballot_w64(differ != 0);
+            suspects += __builtin_popcountll(m);
+            trip_abs |= m;
+        }
+    }
+    template <int V>
+    __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &, int) const { return 0; }
+    template <int V>
+    __device__ __forceinline__ void raise_call(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec) const
+    {
+        u32x4 b;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
+        const DoublePair out = raise_vector_int64(q, b, max_abs, max_rel, rec);
+        max_abs = out.abs;
+        max_rel = out.rel;
+    }
+    template <int V>
+    __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec, int) const
+    {
+        raise_call<V>(q, max_abs, max_rel, rec);
+    }
+};
+
 template <int DT> struct ItemOf { typedef FloatItem<DT> type; };
 template <> struct ItemOf<GEAK_I32> { typedef IntItem type; };
+template <> struct ItemOf<GEAK_I64> { typedef Int64Item type; };
 
 __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 {
@@ -1141,14 +1244,16 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_F32:  next_j = process_run<GEAK_F32>(r, st); break;
                 case GEAK_F16:  next_j = process_run<GEAK_F16>(r, st); break;
                 case GEAK_BF16: next_j = process_run<GEAK_BF16>(r, st); break;
-                default:        next_j = process_run<GEAK_I32>(r, st); break;
+                case GEAK_I32:  next_j = process_run<GEAK_I32>(r, st); break;
+                default:        next_j = process_run<GEAK_I64>(r, st); break;
                 }
             } else {
                 switch (it.dtype) {
                 case GEAK_F32:  process_tail<GEAK_F32>(r, st); break;
                 case GEAK_F16:  process_tail<GEAK_F16>(r, st); break;
                 case GEAK_BF16: process_tail<GEAK_BF16>(r, st); break;
-                default:        process_tail<GEAK_I32>(r, st); break;
+                case GEAK_I32:  process_tail<GEAK_I32>(r, st); break;
+                default:        process_tail<GEAK_I64>(r, st); break;
                 }
                 next_j = it.next;
             }
@@ -1189,6 +1294,8 @@ __device__ __forceinline__ bool element_close(const unsigned char *ref, const un
 {
     if (dtype == GEAK_I32)
         return reinterpret_cast<const int *>(ref)[idx] == reinterpret_cast<const int *>(cand)[idx];
+    if (dtype == GEAK_I64)
+        return reinterpret_cast<const long long *>(ref)[idx] == reinterpret_cast<const long long *>(cand)[idx];
     return close_exact(load_elem_f(cand, idx, dtype), load_elem_f(ref, idx, dtype), atol_f, rtol_f, equal_nan);
 }
 
@@ -1317,7 +1424,7 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
     for (u64 base = (u64)rec.first_mismatch; base < sg.numel && found < want; base += kReportThreads * kReportPerThread) {
         // all loads of the tile first, then the rule
         float av[kReportPerThread], bv[kReportPerThread];
-        int ai[kReportPerThread], bi[kReportPerThread];
+        long long ai[kReportPerThread], bi[kReportPerThread];
 #pragma unroll
         for (int u = 0; u < kReportPerThread; ++u) {
             const u64 i = base + (u64)u * kReportThreads + tid;
@@ -1325,6 +1432,9 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
             if constexpr (DT == GEAK_I32) {
                 ai[u] = in ? reinterpret_cast<const int *>(cb)[i] : 0;
                 bi[u] = in ? reinterpret_cast<const int *>(rb)[i] : 0;
+            } else if constexpr (DT == GEAK_I64) {
+                ai[u] = in ? reinterpret_cast<const long long *>(cb)[i] : 0;
+                bi[u] = in ? reinterpret_cast<const long long *>(rb)[i] : 0;
             } else {
                 av[u] = in ? elem_f<DT>(cb, i) : 0.0f;
                 bv[u] = in ? elem_f<DT>(rb, i) : 0.0f;
@@ -1336,7 +1446,7 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
 #pragma unroll
         for (int u = 0; u < kReportPerThread; ++u) {
             const u64 i = base + (u64)u * kReportThreads + tid;
-            if constexpr (DT == GEAK_I32) bad[u] = (i < sg.numel) && ai[u] != bi[u];
+            if constexpr (DT == GEAK_I32 || DT == GEAK_I64) bad[u] = (i < sg.numel) && ai[u] != bi[u];
             else bad[u] = (i < sg.numel) && !close_exact(av[u], bv[u], tolerance.atol_f, tolerance.rtol_f, p.equal_nan);
             const u64 mask = __builtin_amdgcn_ballot_w64(bad[u]);
             before[u] = (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
@@ -1359,12 +1469,10 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
             if (bad[u] && pos < want) {
                 geak_mismatch m;
                 m.index = (long long)(base + (u64)u * kReportThreads + tid);
-                if constexpr (DT == GEAK_I32) {
-                    const long long a = ai[u], b = bi[u];
-                    const long long diff = a - b;
-                    m.a = (double)a;
-                    m.b = (double)b;
-                    m.d = (double)(diff < 0 ? -diff : diff);
+                if constexpr (DT == GEAK_I32 || DT == GEAK_I64) {
+                    m.a = (double)ai[u];                     // int64: one rounding each
+                    m.b = (double)bi[u];
+                    m.d = i64_abs_diff(ai[u], bi[u]);
                     m.tol = 0.0;
                 } else {
                     const float prod = tolerance.rtol_f * __builtin_fabsf(bv[u]);
@@ -1400,7 +1508,8 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     case GEAK_F32:  report_pair<GEAK_F32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     case GEAK_F16:  report_pair<GEAK_F16>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     case GEAK_BF16: report_pair<GEAK_BF16>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    default:        report_pair<GEAK_I32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_I32:  report_pair<GEAK_I32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    default:        report_pair<GEAK_I64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     }
 }
 

@@ -25,8 +25,9 @@ from dataclasses import dataclass, field
 import numpy as np
 import torch
 
-ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4}
-TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32}
+ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8}
+TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32,
+               "i64": torch.int64}
 
 _CHUNK = 1 << 25  # elements generated per step, bounds temporary memory
 
@@ -204,14 +205,15 @@ def config3(shape=(16, 32, 4096, 128), num_candidates: int = 16, device="cpu", b
 # config 4: ragged batch of many tensors of mixed dtype, packed with a segment table
 # --------------------------------------------------------------------------------------
 def config4(num_segments: int = 1024, log2_max: float = 20.0, num_candidates: int = 4, device="cpu",
-            align: int = 16, seed: int = 3) -> Workload:
+            align: int = 16, seed: int = 3, dtypes=("f32", "f16", "bf16", "i32")) -> Workload:
     """align: byte alignment of every segment start (16 = the packed layout the benchmark uses;
-    smaller values, down to the element size, exercise unaligned starts)."""
+    smaller values, down to the element size, exercise unaligned starts).  dtypes: the dtypes the
+    segments are drawn from (the benchmark recipe is the default four; tests add "i64")."""
     rng = np.random.default_rng(seed)
     u = rng.random(num_segments)
     sizes = np.maximum(1, np.floor(2.0 ** (log2_max * u))).astype(np.int64)
-    names = ["f32", "f16", "bf16", "i32"]
-    dts = [names[i] for i in rng.integers(0, 4, num_segments)]
+    names = list(dtypes)
+    dts = [names[i] for i in rng.integers(0, len(names), num_segments)]
     segments, off = [], 0
     for s in range(num_segments):
         w = ELEM_SIZE[dts[s]]
@@ -230,12 +232,16 @@ def config4(num_segments: int = 1024, log2_max: float = 20.0, num_candidates: in
         g = _gen(10_000 + s, device)
         if dt == "i32":
             b = torch.randint(-1000, 1001, (n,), generator=g, device=device, dtype=torch.int32)
+        elif dt == "i64":
+            b = torch.randint(-1000, 1001, (n,), generator=g, device=device, dtype=torch.int64)
+            big = torch.rand(n, generator=g, device=device) < 0.05                # values beyond 2^53
+            b = torch.where(big, b * (1 << 52) + 12345, b)
         else:
             b = torch.randn(n, generator=g, device=device).to(TORCH_DTYPE[dt])
         ref[boff:boff + n * w] = b.view(torch.uint8)
         for k in range(num_candidates):
             gk = _gen(1000 * 4 + 7919 * s + k, device)
-            if dt == "i32":
+            if dt in ("i32", "i64"):
                 a = b.clone()
                 if (s + k) % 2 == 1:
                     j = int(torch.randint(0, n, (1,), generator=gk, device=device))

@@ -11,7 +11,8 @@ from paper_2507_23194_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-TORCH_STORAGE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32}
+TORCH_STORAGE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32,
+                 "i64": torch.int64}
 
 
 def _to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
@@ -57,6 +58,18 @@ def test_golden_pins_on_gpu(case):
 
 def _special_case(rng, dtype, n, special=0.02):
     """Random tensors rich in NaN, +-Inf, signed zeros, subnormals, huge values and near-boundary pairs."""
+    if dtype == "i64":
+        b = rng.integers(-2 ** 63, 2 ** 63, n, dtype=np.int64)
+        b[rng.random(n) < 0.3] = 0
+        b[rng.random(n) < 0.2] = rng.integers(-1000, 1000)
+        b[rng.random(n) < 0.01] = np.iinfo(np.int64).min
+        a = b.copy()
+        idx = rng.random(n) < 0.01
+        a[idx] = rng.integers(-2 ** 63, 2 ** 63, int(idx.sum()), dtype=np.int64)
+        near = rng.random(n) < 0.01
+        a[near] = (b[near].astype(np.uint64) + np.uint64(1)).astype(np.int64)
+        a[rng.random(n) < 0.005] = np.iinfo(np.int64).max
+        return b, a
     if dtype == "i32":
         b = rng.integers(-2 ** 31, 2 ** 31, n).astype(np.int32)
         b[rng.random(n) < 0.3] = 0
@@ -82,7 +95,7 @@ def _special_case(rng, dtype, n, special=0.02):
     return tb, ta
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64"])
 @pytest.mark.parametrize("n", [1, 63, 2048, 4097, 70001, 1 << 20])
 def test_special_values_dense(oracle_mod, dtype, n):
     print("special", dtype, n, flush=True)
@@ -189,6 +202,20 @@ def test_per_segment_tolerances(oracle_mod):
             assert (got["index"] == rep["index"]).all()
             assert all(np.array_equal(got[f], rep[f], equal_nan=True) for f in ("a", "b", "d", "tol"))
     assert differs > 20          # the per-segment pairs really change verdicts relative to one plan-wide pair
+
+
+@pytest.mark.parametrize("align", [8, 16])
+def test_ragged_batch_with_int64_segments(oracle_mod, align):
+    """The ragged recipe with int64 segments among the others (index outputs next to value outputs),
+    with segment starts on 16-byte and on bare 8-byte boundaries."""
+    w = synth.config4(num_segments=96, log2_max=15.0, num_candidates=4, device="cuda", align=align, seed=21,
+                      dtypes=("f32", "i64", "bf16", "i64", "i32", "f16"))
+    assert sum(dt == "i64" for _, _, dt in w.segments) > 20
+    gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, f"ragged with int64, align {align}")
+    for (s, k), e in w.expect.items():
+        assert int(gpu[s, k]["mismatch_count"]) == e["count"] and int(gpu[s, k]["first_mismatch"]) == e["first"]
 
 
 def test_empty_and_tiny_segments(oracle_mod):
