@@ -25,6 +25,8 @@
  *     R5  -0 vs +0 gives d = 0, hence close
  *   int32:
  *     R6  close <=> a == b; d = |a - b| exactly (64-bit), tolerances ignored
+ *   uint8 (also the storage of boolean masks) and int8:
+ *     R6" close <=> a == b; d = |a - b| exactly (at most 255); R8 and R9 as for int32
  *   int64 (index outputs of sort / argmax-like kernels):
  *     R6' close <=> a == b; d = |a - b| exactly as an unsigned 64-bit integer (at most 2^64 - 1);
  *         where a binary64 value is needed (R8, R9, the report) d and |b| (at most 2^63) are each
@@ -58,7 +60,7 @@
 #include <xmmintrin.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2, ORACLE_I32 = 3, ORACLE_I64 = 4 };
+enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2, ORACLE_I32 = 3, ORACLE_I64 = 4, ORACLE_U8 = 5, ORACLE_I8 = 6 };
 
 typedef struct {
     int32_t  pass;
@@ -114,7 +116,7 @@ static int is_inf_f(float x) { return x == INFINITY || x == -INFINITY; }
 int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int dtype,
                          double atol, double rtol, int equal_nan, oracle_record *out)
 {
-    if (!out || dtype < 0 || dtype > 4)
+    if (!out || dtype < 0 || dtype > 6)
         return -1;
 
 #if defined(__SSE2__)
@@ -150,11 +152,19 @@ int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int 
             }
             if (r > max_rel) max_rel = r;
         }
-    } else if (dtype == ORACLE_I32) {
-        const int32_t *pb = (const int32_t *)ref;
-        const int32_t *pa = (const int32_t *)cand;
+    } else if (dtype == ORACLE_I32 || dtype == ORACLE_U8 || dtype == ORACLE_I8) {
         for (uint64_t i = 0; i < numel; ++i) {
-            int64_t a = pa[i], b = pb[i];
+            int64_t a, b;
+            if (dtype == ORACLE_I32) {
+                a = ((const int32_t *)cand)[i];
+                b = ((const int32_t *)ref)[i];
+            } else if (dtype == ORACLE_U8) {
+                a = ((const uint8_t *)cand)[i];
+                b = ((const uint8_t *)ref)[i];
+            } else {
+                a = ((const int8_t *)cand)[i];
+                b = ((const int8_t *)ref)[i];
+            }
             int64_t diff = a - b;
             uint64_t d = (uint64_t)(diff < 0 ? -diff : diff);
             if (a != b) {                                    /* R6 */
@@ -258,7 +268,7 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
                               double atol, double rtol, int equal_nan, uint64_t max_records,
                               oracle_mismatch *out)
 {
-    if ((!out && max_records) || dtype < 0 || dtype > 4)
+    if ((!out && max_records) || dtype < 0 || dtype > 6)
         return -1;
 #if defined(__SSE2__)
     unsigned int csr_saved = _mm_getcsr();
@@ -278,8 +288,18 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
             m.b = (double)b;
             m.d = (double)d;
             m.tol = 0.0;
-        } else if (dtype == ORACLE_I32) {
-            int64_t a = ((const int32_t *)cand)[i], b = ((const int32_t *)ref)[i];
+        } else if (dtype == ORACLE_I32 || dtype == ORACLE_U8 || dtype == ORACLE_I8) {
+            int64_t a, b;
+            if (dtype == ORACLE_I32) {
+                a = ((const int32_t *)cand)[i];
+                b = ((const int32_t *)ref)[i];
+            } else if (dtype == ORACLE_U8) {
+                a = ((const uint8_t *)cand)[i];
+                b = ((const uint8_t *)ref)[i];
+            } else {
+                a = ((const int8_t *)cand)[i];
+                b = ((const int8_t *)ref)[i];
+            }
             int64_t diff = a - b;
             close = (a == b);                                    /* R6 */
             m.a = (double)a;

@@ -200,6 +200,15 @@ def test_fma_contraction_would_be_caught(oracle_mod):
 # structural invariants
 # ------------------------------------------------------------------------------------------
 def _rand_case(rng, dtype, n):
+    if dtype in ("u8", "i8"):
+        np_t = np.uint8 if dtype == "u8" else np.int8
+        info = np.iinfo(np_t)
+        b = rng.integers(info.min, info.max + 1, n).astype(np_t)
+        b[rng.random(n) < 0.3] = 0
+        a = b.copy()
+        idx = rng.random(n) < 0.05
+        a[idx] = rng.integers(info.min, info.max + 1, int(idx.sum())).astype(np_t)
+        return b, a
     if dtype == "i64":
         # small values, values beyond 2^53 (where the binary64 conversions round) and the two extremes
         b = rng.integers(-1000, 1001, n).astype(np.int64)
@@ -233,7 +242,7 @@ def _rand_case(rng, dtype, n):
     return tb, ta
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8"])
 def test_invariants(oracle_mod, dtype):
     rng = np.random.default_rng(11)
     n = 3001
@@ -242,7 +251,7 @@ def test_invariants(oracle_mod, dtype):
     full = oracle_mod.check_segment(b, a, n, dtype, **kw)
 
     # a bit-identical copy of a NaN-free tensor is the neutral record
-    if dtype in ("i32", "i64"):
+    if dtype in ("i32", "i64", "u8", "i8"):
         clean = b
     else:
         _, clean = _rand_case(np.random.default_rng(12), dtype, n)
@@ -387,3 +396,32 @@ def test_int64_hand_derived(oracle_mod):
     # equal extremes pass
     same = np.array([i64.min, i64.max, 0], dtype=np.int64)
     assert int(oracle_mod.check_segment(same, same.copy(), 3, "i64", 0.0, 0.0, False)["pass"]) == 1
+
+
+def test_byte_dtypes_hand_derived(oracle_mod):
+    """uint8 (also boolean masks) and int8: exact equality, |a - b| exact, relative error in binary64."""
+    b = np.array([0, 1, 255, 200, 7, 1], dtype=np.uint8)
+    a = np.array([0, 0, 0, 50, 7, 255], dtype=np.uint8)
+    rec = oracle_mod.check_segment(b, a, 6, "u8", 5.0, 5.0, False)            # tolerances are ignored
+    assert (int(rec["pass"]), int(rec["mismatch_count"]), int(rec["first_mismatch"])) == (0, 4, 1)
+    assert float(rec["max_abs_err"]) == 255.0                                  # |0 - 255|, unsigned
+    assert float(rec["max_rel_err"]) == 254.0                                  # |255 - 1| / 1
+    # the same bytes read as int8: 255 is -1, 200 is -56
+    rec = oracle_mod.check_segment(b.view(np.int8), a.view(np.int8), 6, "i8", 0.0, 0.0, False)
+    assert int(rec["mismatch_count"]) == 4 and int(rec["first_mismatch"]) == 1
+    assert float(rec["max_abs_err"]) == 106.0                                  # |50 - (-56)|
+    assert float(rec["max_rel_err"]) == 2.0                                    # |-1 - 1| / 1
+    rep = oracle_mod.report_segment(b.view(np.int8), a.view(np.int8), 6, "i8", 0.0, 0.0, False, 8)
+    assert [int(r["index"]) for r in rep] == [1, 2, 3, 5]
+    assert [float(r["a"]) for r in rep] == [0.0, 0.0, 50.0, -1.0] and [float(r["b"]) for r in rep] == [1.0, -1.0, -56.0, 1.0]
+    assert [float(r["d"]) for r in rep] == [1.0, 1.0, 106.0, 2.0] and all(float(r["tol"]) == 0.0 for r in rep)
+    # a boolean mask with one flipped entry against a zero reference: relative error +Inf
+    mask = np.zeros(100, dtype=np.uint8)
+    flipped = mask.copy()
+    flipped[37] = 1
+    rec = oracle_mod.check_segment(mask, flipped, 100, "u8", 0.0, 0.0, False)
+    assert (int(rec["mismatch_count"]), int(rec["first_mismatch"])) == (1, 37)
+    assert float(rec["max_abs_err"]) == 1.0 and float(rec["max_rel_err"]) == np.inf
+    # int8 extremes
+    rec = oracle_mod.check_segment(np.array([-128], dtype=np.int8), np.array([127], dtype=np.int8), 1, "i8", 0.0, 0.0, False)
+    assert float(rec["max_abs_err"]) == 255.0 and float(rec["max_rel_err"]) == 255.0 / 128.0
