@@ -14,7 +14,8 @@
  *       d = |a - b|,  tol = atol_f + (rtol_f * |b|),  close <=> d <= tol
  *       a or b NaN   : close <=> equal_nan and both NaN
  *       a or b +-Inf : close <=> a == b
- *   int32, int64:      close <=> a == b   (atol, rtol, equal_nan ignored; d = |a - b| exact; for int64
+ *   int32, int64, uint8, int8:
+ *                      close <=> a == b   (atol, rtol, equal_nan ignored; d = |a - b| exact; for int64
  *                      d (up to 2^64 - 1) and |b| are each rounded once to binary64 where a double is
  *                      needed: max_abs_err, max_rel_err, the mismatch report)
  *
@@ -52,7 +53,8 @@ typedef enum {
     GEAK_EHIP = 7        /* a HIP runtime call failed (no device, launch error) */
 } geak_status;
 
-typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64 = 4 } geak_dtype;
+typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64 = 4,
+               GEAK_U8 = 5 /* also boolean masks stored as bytes */, GEAK_I8 = 6 } geak_dtype;
 
 #define GEAK_MAX_CANDIDATES 256
 #define GEAK_MAX_SEGMENT_NUMEL (1ull << 40)
@@ -165,7 +167,7 @@ typedef struct {
     uint64_t elem_start;   /* flat index of that element within its segment */
     uint32_t segment;
     uint32_t slot;         /* workspace slot its run accumulates into */
-    uint16_t numel;        /* 1 .. item_bytes / element size */
+    uint16_t numel;        /* 1 .. item_bytes / element size (at most 4096) */
     uint8_t  dtype;
     uint8_t  flags;        /* GEAK_ITEM_* */
     uint32_t next;         /* index of the next item of the same wavefront, GEAK_NO_ITEM after its last */

@@ -15,7 +15,15 @@ constexpr int kDefaultComputeUnits = 256;                        // host-only pl
 constexpr int kDefaultBlocksPerCU = 4;
 constexpr uint32_t kNoItem = 0xFFFFFFFFu;
 
-inline int elem_size(int dtype) { return (dtype == GEAK_F16 || dtype == GEAK_BF16) ? 2 : (dtype == GEAK_I64 ? 8 : 4); }
+inline int elem_size(int dtype)
+{
+    switch (dtype) {
+    case GEAK_F16: case GEAK_BF16: return 2;
+    case GEAK_I64: return 8;
+    case GEAK_U8: case GEAK_I8: return 1;
+    default: return 4;
+    }
+}
 
 // Partial result of one (worker, segment) run for one candidate; 16 bytes.
 struct Partial {

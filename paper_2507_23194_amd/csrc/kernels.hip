@@ -103,6 +103,8 @@ template <> struct Traits<GEAK_F16>  { static constexpr int E = 8, W = 2; };
 template <> struct Traits<GEAK_BF16> { static constexpr int E = 8, W = 2; };
 template <> struct Traits<GEAK_I32>  { static constexpr int E = 4, W = 4; };
 template <> struct Traits<GEAK_I64>  { static constexpr int E = 2, W = 8; };
+template <> struct Traits<GEAK_U8>   { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_I8>   { static constexpr int E = 16, W = 1; };
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t f_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
@@ -151,7 +153,12 @@ __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, i
     if (first + E <= n) {
         q = __builtin_nontemporal_load(p);
     } else if (first < n) {
-        if constexpr (Traits<DT>::W == 8) {
+        if constexpr (Traits<DT>::W == 1) {
+            const GEAK_AS_GLOBAL unsigned char *c = (const GEAK_AS_GLOBAL unsigned char *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (first + e < n) q[e >> 2] |= (uint32_t)c[e] << ((e & 3) * 8);
+        } else if constexpr (Traits<DT>::W == 8) {
             const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
 #pragma unroll
             for (uint32_t e = 0; e < E; ++e)
@@ -178,6 +185,15 @@ __device__ __forceinline__ float load_elem_f(const unsigned char *base, u64 idx,
     const uint16_t h = reinterpret_cast<const uint16_t *>(base)[idx];
     if (dtype == GEAK_F16) return (float)__builtin_bit_cast(_Float16, h);
     return bits_f((uint32_t)h << 16);
+}
+
+// One integer element straight from memory, widened exactly to 64 bits.
+__device__ __forceinline__ long long load_elem_int(const unsigned char *base, u64 idx, int dtype)
+{
+    if (dtype == GEAK_I32) return reinterpret_cast<const int *>(base)[idx];
+    if (dtype == GEAK_I64) return reinterpret_cast<const long long *>(base)[idx];
+    if (dtype == GEAK_U8) return base[idx];
+    return reinterpret_cast<const signed char *>(base)[idx];
 }
 
 // ---- wave reductions (rare paths only) ---------------------------------------------------------
@@ -273,20 +289,15 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
     const int lane = threadIdx.x & (kWaveSize - 1);
     const u64 abs_bits = load_bits(&rec->abs), rel_bits = load_bits(&rec->rel);
     uint32_t bad = 0;
-    if (dtype == GEAK_I32 || dtype == GEAK_I64) {
+    if (dtype == GEAK_I32 || dtype == GEAK_I64 || dtype == GEAK_U8 || dtype == GEAK_I8) {
         const double seen_rel = __builtin_bit_cast(double, rel_bits);
         // d > c*|b| is implied by d/|b| > seen_rel; the 2^-30 margin covers the product's rounding
         const double c = (seen_rel == (double)kInfF) ? __builtin_nan("") : seen_rel * (1.0 - 0x1p-30);
         double dm = 0.0, rm = 0.0;
         for (uint32_t i = lane; i < n; i += kWaveSize) {
             long long a, x;
-            if (dtype == GEAK_I32) {
-                a = reinterpret_cast<const int *>(cand)[i];
-                x = reinterpret_cast<const int *>(ref)[i];
-            } else {
-                a = reinterpret_cast<const long long *>(cand)[i];
-                x = reinterpret_cast<const long long *>(ref)[i];
-            }
+            a = load_elem_int(cand, i, dtype);
+            x = load_elem_int(ref, i, dtype);
             bad += (a != x);
             const double d = i64_abs_diff(a, x);                  // exact for int32 operands
             const double babs = i64_abs(x);
@@ -916,7 +927,110 @@ struct Int64Item {
     }
 };
 
+// ---- uint8 / int8: sixteen elements per 16-byte vector, exact equality ---------------------------
+__device__ __forceinline__ uint32_t wave_sum_u(uint32_t x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += (uint32_t)__shfl_xor((int)x, o, kWaveSize);
+    return x;
+}
+// number of bytes of x that are not zero
+__device__ __forceinline__ uint32_t nonzero_bytes(uint32_t x)
+{
+    const uint32_t t = (((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u;
+    return (uint32_t)__builtin_popcount(t);
+}
+template <bool SIGNED>
+__device__ __forceinline__ long long byte_value(uint32_t word, int byte)
+{
+    const uint32_t v = (word >> (8 * byte)) & 0xFFu;
+    return SIGNED ? (long long)(signed char)v : (long long)v;
+}
+
+template <bool SIGNED>
+__device__ __noinline__ DoublePair raise_vector_bytes(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
+                                                      MaxPair *rec_in)
+{
+    MaxPair *rec = uniform_ptr(rec_in);
+    double dm = max_abs, rm = max_rel;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if (q[w] == b[w]) continue;                                      // most words of a tripping lane are equal
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const long long a = byte_value<SIGNED>(q[w], e), x = byte_value<SIGNED>(b[w], e);
+            const double d = i64_abs_diff(a, x);                         // exact
+            const double babs = i64_abs(x);
+            dm = (d > dm) ? d : dm;
+            if (d > 0.0 && (rm < (double)kInfF) && d > rm * (1.0 - 0x1p-30) * babs) {
+                const double r = d / babs;                               // binary64, correctly rounded; d/0 = +Inf
+                rm = (r > rm) ? r : rm;
+            }
+        }
+    }
+    dm = wave_max_d(dm);
+    rm = wave_max_d(rm);
+    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
+        if (dm > max_abs) publish_max(&rec->abs, dm);
+        if (rm > max_rel) publish_max(&rec->rel, rm);
+    }
+    DoublePair out;
+    out.abs = dm;
+    out.rel = rm;
+    return out;
+}
+
+template <bool SIGNED>
+struct ByteItem {
+    typedef double Hint;
+    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
+    static constexpr int E = 16;
+    static constexpr bool kRaiseOutOfLine = true;
+    uint32_t bref[kVecPerLane * 4];
+    __device__ __forceinline__ void attach_lds(uint32_t, int) {}
+    static constexpr uint32_t poisoned_slots = 0;
+
+    template <int V>
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, float, float)
+    {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
+    }
+    // A vector whose sixteen bytes all equal the reference's costs four XORs, two ORs and one compare;
+    // only a wave that sees a difference counts the differing bytes (per lane, then summed).
+    template <int V, bool AHEAD = true>
+    __device__ __forceinline__ void compare_vec(const u32x4 &q, double, double, uint32_t &suspects, u64 &trip_abs, u64 &, int) const
+    {
+        const uint32_t x0 = q[0] ^ bref[V * 4 + 0], x1 = q[1] ^ bref[V * 4 + 1];
+        const uint32_t x2 = q[2] ^ bref[V * 4 + 2], x3 = q[3] ^ bref[V * 4 + 3];
+        const u64 m = __builtin_amdgcn_ballot_w64((x0 | x1 | x2 | x3) != 0);
+        if (m) {
+            suspects += wave_sum_u(nonzero_bytes(x0) + nonzero_bytes(x1) + nonzero_bytes(x2) + nonzero_bytes(x3));
+            trip_abs |= m;
+        }
+    }
+    template <int V>
+    __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &, int) const { return 0; }
+    template <int V>
+    __device__ __forceinline__ void raise_call(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec) const
+    {
+        u32x4 b;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
+        const DoublePair out = raise_vector_bytes<SIGNED>(q, b, max_abs, max_rel, rec);
+        max_abs = out.abs;
+        max_rel = out.rel;
+    }
+    template <int V>
+    __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec, int) const
+    {
+        raise_call<V>(q, max_abs, max_rel, rec);
+    }
+};
+
 template <int DT> struct ItemOf { typedef FloatItem<DT> type; };
+template <> struct ItemOf<GEAK_U8> { typedef ByteItem<false> type; };
+template <> struct ItemOf<GEAK_I8> { typedef ByteItem<true> type; };
 template <> struct ItemOf<GEAK_I32> { typedef IntItem type; };
 template <> struct ItemOf<GEAK_I64> { typedef Int64Item type; };
 
@@ -975,7 +1089,7 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
 {
     u64 trip_abs = 0, trip_rel = 0;
     ref.template compare_vec<V, !OUTLINE>(slot, max_abs, max_rel, bad, trip_abs, trip_rel, equal_nan);
-    if constexpr (OUTLINE) {
+    if constexpr (OUTLINE && (DT == GEAK_F32 || DT == GEAK_F16 || DT == GEAK_BF16)) {      // only floating items poison slots
         constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
         if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_call<V>(slot, equal_nan);
     }
@@ -1245,7 +1359,9 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_F16:  next_j = process_run<GEAK_F16>(r, st); break;
                 case GEAK_BF16: next_j = process_run<GEAK_BF16>(r, st); break;
                 case GEAK_I32:  next_j = process_run<GEAK_I32>(r, st); break;
-                default:        next_j = process_run<GEAK_I64>(r, st); break;
+                case GEAK_I64:  next_j = process_run<GEAK_I64>(r, st); break;
+                case GEAK_U8:   next_j = process_run<GEAK_U8>(r, st); break;
+                default:        next_j = process_run<GEAK_I8>(r, st); break;
                 }
             } else {
                 switch (it.dtype) {
@@ -1253,7 +1369,9 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_F16:  process_tail<GEAK_F16>(r, st); break;
                 case GEAK_BF16: process_tail<GEAK_BF16>(r, st); break;
                 case GEAK_I32:  process_tail<GEAK_I32>(r, st); break;
-                default:        process_tail<GEAK_I64>(r, st); break;
+                case GEAK_I64:  process_tail<GEAK_I64>(r, st); break;
+                case GEAK_U8:   process_tail<GEAK_U8>(r, st); break;
+                default:        process_tail<GEAK_I8>(r, st); break;
                 }
                 next_j = it.next;
             }
@@ -1292,10 +1410,8 @@ __global__ void init_kernel(const InitArgs p)
 __device__ __forceinline__ bool element_close(const unsigned char *ref, const unsigned char *cand, u64 idx,
                                               int dtype, float atol_f, float rtol_f, int equal_nan)
 {
-    if (dtype == GEAK_I32)
-        return reinterpret_cast<const int *>(ref)[idx] == reinterpret_cast<const int *>(cand)[idx];
-    if (dtype == GEAK_I64)
-        return reinterpret_cast<const long long *>(ref)[idx] == reinterpret_cast<const long long *>(cand)[idx];
+    if (dtype == GEAK_I32 || dtype == GEAK_I64 || dtype == GEAK_U8 || dtype == GEAK_I8)
+        return load_elem_int(ref, idx, dtype) == load_elem_int(cand, idx, dtype);
     return close_exact(load_elem_f(cand, idx, dtype), load_elem_f(ref, idx, dtype), atol_f, rtol_f, equal_nan);
 }
 
@@ -1351,7 +1467,7 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
         const geak_item it = p.items[first_item];
         const SegTol tolerance = p.seg_tol[seg];
         const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
-        constexpr int kPer = (kItemBytes / 2 + kReduceThreads - 1) / kReduceThreads;   // 8: most elements a thread can own
+        constexpr int kPer = kItemBytes / kReduceThreads;       // 16: most elements (one-byte dtypes) a thread can own
         bool bad[kPer];
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
@@ -1414,6 +1530,8 @@ __device__ __forceinline__ float elem_f(const unsigned char *base, u64 idx)
     else return bits_f((uint32_t)reinterpret_cast<const uint16_t *>(base)[idx] << 16);
 }
 
+template <int DT> constexpr bool kIntegerDtype = (DT == GEAK_I32 || DT == GEAK_I64 || DT == GEAK_U8 || DT == GEAK_I8);
+
 template <int DT>
 __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol tolerance, const geak_segment &sg, const geak_result &rec, u64 want,
                                             const unsigned char *rb, const unsigned char *cb, geak_mismatch *out,
@@ -1435,6 +1553,9 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
             } else if constexpr (DT == GEAK_I64) {
                 ai[u] = in ? reinterpret_cast<const long long *>(cb)[i] : 0;
                 bi[u] = in ? reinterpret_cast<const long long *>(rb)[i] : 0;
+            } else if constexpr (DT == GEAK_U8 || DT == GEAK_I8) {
+                ai[u] = in ? load_elem_int(cb, i, DT) : 0;
+                bi[u] = in ? load_elem_int(rb, i, DT) : 0;
             } else {
                 av[u] = in ? elem_f<DT>(cb, i) : 0.0f;
                 bv[u] = in ? elem_f<DT>(rb, i) : 0.0f;
@@ -1446,7 +1567,7 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
 #pragma unroll
         for (int u = 0; u < kReportPerThread; ++u) {
             const u64 i = base + (u64)u * kReportThreads + tid;
-            if constexpr (DT == GEAK_I32 || DT == GEAK_I64) bad[u] = (i < sg.numel) && ai[u] != bi[u];
+            if constexpr (kIntegerDtype<DT>) bad[u] = (i < sg.numel) && ai[u] != bi[u];
             else bad[u] = (i < sg.numel) && !close_exact(av[u], bv[u], tolerance.atol_f, tolerance.rtol_f, p.equal_nan);
             const u64 mask = __builtin_amdgcn_ballot_w64(bad[u]);
             before[u] = (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
@@ -1469,7 +1590,7 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
             if (bad[u] && pos < want) {
                 geak_mismatch m;
                 m.index = (long long)(base + (u64)u * kReportThreads + tid);
-                if constexpr (DT == GEAK_I32 || DT == GEAK_I64) {
+                if constexpr (kIntegerDtype<DT>) {
                     m.a = (double)ai[u];                     // int64: one rounding each
                     m.b = (double)bi[u];
                     m.d = i64_abs_diff(ai[u], bi[u]);
@@ -1509,7 +1630,9 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     case GEAK_F16:  report_pair<GEAK_F16>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     case GEAK_BF16: report_pair<GEAK_BF16>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     case GEAK_I32:  report_pair<GEAK_I32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    default:        report_pair<GEAK_I64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_I64:  report_pair<GEAK_I64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_U8:   report_pair<GEAK_U8>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    default:        report_pair<GEAK_I8>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     }
 }
 

@@ -31,7 +31,7 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
     uint64_t total_bytes = 0;
     for (uint64_t s = 0; s < nsegs; ++s) {
         const geak_segment &g = segs[s];
-        if (g.dtype < GEAK_F32 || g.dtype > GEAK_I64) return GEAK_EDTYPE;
+        if (g.dtype < GEAK_F32 || g.dtype > GEAK_I8) return GEAK_EDTYPE;
         if (g.reserved != 0) return GEAK_EINVAL;
         const uint64_t w = (uint64_t)elem_size(g.dtype);
         if (g.byte_offset % w != 0) return GEAK_EALIGN;
@@ -127,7 +127,7 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
         const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
         const uint64_t slices = (uint64_t)num_candidates + 1;
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
-            const uint64_t per_slice = (it.dtype == GEAK_I32 || it.dtype == GEAK_I64) ? 13 : it.dtype == GEAK_F32 ? 16 : it.dtype == GEAK_BF16 ? 19 : 21;
+            const uint64_t per_slice = it.dtype == GEAK_F32 ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
             if (!(it.flags & GEAK_ITEM_ALIGNED)) return 2 * per_slice * slices;      // element-wise path
             if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 140;
             return per_slice * slices + (starts_run ? 100 : 0);

@@ -25,9 +25,9 @@ from dataclasses import dataclass, field
 import numpy as np
 import torch
 
-ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8}
+ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1}
 TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32,
-               "i64": torch.int64}
+               "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8}
 
 _CHUNK = 1 << 25  # elements generated per step, bounds temporary memory
 
@@ -232,6 +232,10 @@ def config4(num_segments: int = 1024, log2_max: float = 20.0, num_candidates: in
         g = _gen(10_000 + s, device)
         if dt == "i32":
             b = torch.randint(-1000, 1001, (n,), generator=g, device=device, dtype=torch.int32)
+        elif dt == "u8":
+            b = torch.randint(0, 256, (n,), generator=g, device=device, dtype=torch.int32).to(torch.uint8)
+        elif dt == "i8":
+            b = torch.randint(-128, 128, (n,), generator=g, device=device, dtype=torch.int32).to(torch.int8)
         elif dt == "i64":
             b = torch.randint(-1000, 1001, (n,), generator=g, device=device, dtype=torch.int64)
             big = torch.rand(n, generator=g, device=device) < 0.05                # values beyond 2^53
@@ -241,7 +245,7 @@ def config4(num_segments: int = 1024, log2_max: float = 20.0, num_candidates: in
         ref[boff:boff + n * w] = b.view(torch.uint8)
         for k in range(num_candidates):
             gk = _gen(1000 * 4 + 7919 * s + k, device)
-            if dt in ("i32", "i64"):
+            if dt in ("i32", "i64", "u8", "i8"):
                 a = b.clone()
                 if (s + k) % 2 == 1:
                     j = int(torch.randint(0, n, (1,), generator=gk, device=device))

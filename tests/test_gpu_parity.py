@@ -12,7 +12,7 @@ from paper_2507_23194_amd import synth
 pytestmark = pytest.mark.gpu
 
 TORCH_STORAGE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32,
-                 "i64": torch.int64}
+                 "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8}
 
 
 def _to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
@@ -58,6 +58,15 @@ def test_golden_pins_on_gpu(case):
 
 def _special_case(rng, dtype, n, special=0.02):
     """Random tensors rich in NaN, +-Inf, signed zeros, subnormals, huge values and near-boundary pairs."""
+    if dtype in ("u8", "i8"):
+        np_t = np.uint8 if dtype == "u8" else np.int8
+        info = np.iinfo(np_t)
+        b = rng.integers(info.min, info.max + 1, n).astype(np_t)
+        b[rng.random(n) < 0.3] = 0
+        a = b.copy()
+        idx = rng.random(n) < 0.01
+        a[idx] = rng.integers(info.min, info.max + 1, int(idx.sum())).astype(np_t)
+        return b, a
     if dtype == "i64":
         b = rng.integers(-2 ** 63, 2 ** 63, n, dtype=np.int64)
         b[rng.random(n) < 0.3] = 0
@@ -95,7 +104,7 @@ def _special_case(rng, dtype, n, special=0.02):
     return tb, ta
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8"])
 @pytest.mark.parametrize("n", [1, 63, 2048, 4097, 70001, 1 << 20])
 def test_special_values_dense(oracle_mod, dtype, n):
     print("special", dtype, n, flush=True)
@@ -216,6 +225,31 @@ def test_ragged_batch_with_int64_segments(oracle_mod, align):
     _assert_same(gpu, cpu, f"ragged with int64, align {align}")
     for (s, k), e in w.expect.items():
         assert int(gpu[s, k]["mismatch_count"]) == e["count"] and int(gpu[s, k]["first_mismatch"]) == e["first"]
+
+
+@pytest.mark.parametrize("align", [1, 16])
+def test_ragged_batch_with_byte_segments(oracle_mod, align):
+    """Boolean-mask-like uint8 and int8 segments among the others, with segment starts on any byte."""
+    w = synth.config4(num_segments=96, log2_max=15.0, num_candidates=3, device="cuda", align=align, seed=22,
+                      dtypes=("u8", "f32", "i8", "u8", "f16", "i64"))
+    assert sum(dt in ("u8", "i8") for _, _, dt in w.segments) > 30
+    gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, f"ragged with byte dtypes, align {align}")
+    for (s, k), e in w.expect.items():
+        assert int(gpu[s, k]["mismatch_count"]) == e["count"] and int(gpu[s, k]["first_mismatch"]) == e["first"]
+
+
+def test_dense_mask_with_many_flips(oracle_mod):
+    """A large boolean mask whose candidates differ in many places: every vector of some items trips."""
+    rng = np.random.default_rng(5)
+    n = (1 << 21) + 77
+    b = (rng.random(n) < 0.5).astype(np.uint8)
+    cands = [b.copy(), b ^ (rng.random(n) < 0.2).astype(np.uint8), 1 - b]
+    gpu = _dense_gpu(b, cands, "u8", 0.0, 0.0, False)
+    cpu = oracle_dense_chunked(oracle_mod, b, cands, "u8", 0.0, 0.0, False, host_threads()).reshape(1, -1)
+    _assert_same(gpu, cpu, "dense mask")
+    assert int(gpu[0, 2]["mismatch_count"]) == n and int(gpu[0, 0]["pass"]) == 1
 
 
 def test_empty_and_tiny_segments(oracle_mod):

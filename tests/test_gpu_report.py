@@ -40,7 +40,7 @@ def _dense_report(b, cands, dtype, atol, rtol, equal_nan, M):
         ck.close()
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8"])
 @pytest.mark.parametrize("n", [1, 300, 2049, 70001])
 def test_report_special_values(oracle_mod, dtype, n):
     print("report", dtype, n, flush=True)
@@ -52,7 +52,7 @@ def test_report_special_values(oracle_mod, dtype, n):
             rec, cnt, res = _dense_report(b, cands, dtype, 1e-2, 1e-2, equal_nan, M)
             cpu = [oracle_mod.report_segment(b, c, n, dtype, 1e-2, 1e-2, equal_nan, M) for c in cands]
             _assert_reports_equal(rec, cnt, cpu, f"{dtype} n={n} M={M} equal_nan={equal_nan}")
-            assert int(cnt[1]) == 0 or dtype not in ("i32", "i64")    # an integer copy has nothing to report
+            assert int(cnt[1]) == 0 or dtype not in ("i32", "i64", "u8", "i8")    # an integer copy has nothing to report
             for k in range(3):
                 assert int(cnt[k]) == min(M, int(res[k]["mismatch_count"]))
 

@@ -119,7 +119,7 @@ def _check_table(segs, K):
         blocks = B.geak_check_plan_blocks(plan).astype(np.int64)
         assert len(blocks) == info.grid_blocks + 1 and blocks[0] == 0 and blocks[-1] == len(items)
         assert (np.diff(blocks) > 0).all() or len(items) == 0          # no empty block, nothing past the table
-        esize = {0: 4, 1: 2, 2: 2, 3: 4, 4: 8}
+        esize = {0: 4, 1: 2, 2: 2, 3: 4, 4: 8, 5: 1, 6: 1}
         # every element of every segment is covered exactly once, in order
         cursor = {}
         for j, it in enumerate(items):
@@ -200,6 +200,7 @@ def test_work_table_dense(lib):
     _check_table([(0, 5000, "f16")], 2)                  # ragged tail
     _check_table([(0, 1, "i32")], 1)
     _check_table([(0, 5000, "i64")], 2)                  # 512 elements per item
+    _check_table([(3, 10000, "u8"), (10240, 4096, "i8")], 2)   # 4096 elements per item, a 13-byte head
     _check_table([(8, 700, "i64"), (8192, 3, "i64")], 3)  # a one-element head before the first 16-byte boundary
 
 
