@@ -23,6 +23,10 @@
  *     R3  if a or b is NaN:   close <=> equal_nan and both are NaN
  *     R4  else if a or b is +-Inf: close <=> a == b
  *     R5  -0 vs +0 gives d = 0, hence close
+ *   binary64 inputs:
+ *     R2' the same rules R1, R3, R4, R5, R8, R9 with every operation in IEEE binary64 (one rounding per
+ *         operation, no fused multiply-add) and atol, rtol used as given: converting the inputs to
+ *         binary32 would throw away the precision such outputs are checked for
  *   int32:
  *     R6  close <=> a == b; d = |a - b| exactly (64-bit), tolerances ignored
  *   uint8 (also the storage of boolean masks) and int8:
@@ -60,7 +64,7 @@
 #include <xmmintrin.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2, ORACLE_I32 = 3, ORACLE_I64 = 4, ORACLE_U8 = 5, ORACLE_I8 = 6 };
+enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2, ORACLE_I32 = 3, ORACLE_I64 = 4, ORACLE_U8 = 5, ORACLE_I8 = 6, ORACLE_F64 = 7 };
 
 typedef struct {
     int32_t  pass;
@@ -116,7 +120,7 @@ static int is_inf_f(float x) { return x == INFINITY || x == -INFINITY; }
 int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int dtype,
                          double atol, double rtol, int equal_nan, oracle_record *out)
 {
-    if (!out || dtype < 0 || dtype > 6)
+    if (!out || dtype < 0 || dtype > 7)
         return -1;
 
 #if defined(__SSE2__)
@@ -130,7 +134,40 @@ int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int 
     double   max_abs = 0.0;
     double   max_rel = 0.0;
 
-    if (dtype == ORACLE_I64) {
+    if (dtype == ORACLE_F64) {
+        const double *pb = (const double *)ref;
+        const double *pa = (const double *)cand;
+        for (uint64_t i = 0; i < numel; ++i) {
+            double a = pa[i], b = pb[i];
+            double diff = a - b;                             /* each operation rounded to binary64 on its own */
+            double d = fabs(diff);                           /* R1 */
+            double babs = fabs(b);
+            int close;
+            if (a != a || b != b) {                          /* R3 */
+                close = equal_nan && (a != a) && (b != b);
+            } else if (isinf(a) || isinf(b)) {               /* R4 */
+                close = (a == b);
+            } else {
+                double prod = rtol * babs;                   /* rounded */
+                double tol  = atol + prod;                   /* rounded again: no FMA */
+                close = (d <= tol);
+            }
+            if (!close) {
+                ++count;
+                if (first < 0) first = (int64_t)i;
+            }
+            if (!(d != d) && d > max_abs)                    /* R8 */
+                max_abs = d;
+            double r;
+            if (d == 0.0) {
+                r = 0.0;                                     /* R9 */
+            } else {
+                r = d / babs;                                /* binary64 division */
+            }
+            if (!(r != r) && r > max_rel)
+                max_rel = r;
+        }
+    } else if (dtype == ORACLE_I64) {
         const int64_t *pb = (const int64_t *)ref;
         const int64_t *pa = (const int64_t *)cand;
         for (uint64_t i = 0; i < numel; ++i) {
@@ -268,7 +305,7 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
                               double atol, double rtol, int equal_nan, uint64_t max_records,
                               oracle_mismatch *out)
 {
-    if ((!out && max_records) || dtype < 0 || dtype > 6)
+    if ((!out && max_records) || dtype < 0 || dtype > 7)
         return -1;
 #if defined(__SSE2__)
     unsigned int csr_saved = _mm_getcsr();
@@ -280,7 +317,23 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
     for (uint64_t i = 0; i < numel && written < max_records; ++i) {
         oracle_mismatch m;
         int close;
-        if (dtype == ORACLE_I64) {
+        if (dtype == ORACLE_F64) {
+            double a = ((const double *)cand)[i], b = ((const double *)ref)[i];
+            double diff = a - b;
+            double d = fabs(diff);
+            double prod = rtol * fabs(b);
+            double tol = atol + prod;
+            if (a != a || b != b)                                /* R3 */
+                close = equal_nan && (a != a) && (b != b);
+            else if (isinf(a) || isinf(b))                       /* R4 */
+                close = (a == b);
+            else
+                close = (d <= tol);
+            m.a = a;
+            m.b = b;
+            m.d = d;
+            m.tol = tol;
+        } else if (dtype == ORACLE_I64) {
             int64_t a = ((const int64_t *)cand)[i], b = ((const int64_t *)ref)[i];
             uint64_t d = (a >= b) ? ((uint64_t)a - (uint64_t)b) : ((uint64_t)b - (uint64_t)a);
             close = (a == b);                                    /* R6' */

@@ -18,8 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "geak_oracle.c")
 _LIB = os.path.join(_HERE, "libgeak_oracle.so")
 
-DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2, "i32": 3, "i64": 4, "u8": 5, "i8": 6}
-ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1}
+DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2, "i32": 3, "i64": 4, "u8": 5, "i8": 6, "f64": 7}
+ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1, "f64": 8}
 
 # One record per (segment, candidate); field meaning as in geak_oracle.c (R7-R9).
 RECORD_DTYPE = np.dtype(

@@ -70,9 +70,10 @@ def test_decode_bf16_all_patterns(oracle_mod):
 INF = "inf"
 
 
-def rn32(x):
-    """Round a non-negative exact rational to binary32, nearest-even, subnormals kept,
-    overflow to INF.  Pure integer arithmetic."""
+def rn(x, mant_bits, emin, emax):
+    """Round a non-negative exact rational to the binary format with `mant_bits` significand bits
+    (hidden bit included), least normal exponent emin and greatest exponent emax: nearest-even,
+    subnormals kept, overflow to INF.  Pure integer arithmetic."""
     if x == INF:
         return INF
     assert x >= 0
@@ -82,14 +83,38 @@ def rn32(x):
     e = num.bit_length() - den.bit_length()          # 2^(e-1) < x < 2^(e+1)
     if Fraction(2) ** e > x:
         e -= 1                                        # now 2^e <= x < 2^(e+1)
-    q_exp = max(e, -126) - 23                         # exponent of one unit in the last place
+    q_exp = max(e, emin) - (mant_bits - 1)            # exponent of one unit in the last place
     scaled = x / (Fraction(2) ** q_exp)
     n = scaled.numerator // scaled.denominator
     rem = scaled - n
     if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and n % 2 == 1):
         n += 1
     y = n * Fraction(2) ** q_exp
-    return INF if y >= Fraction(2) ** 128 else y
+    return INF if y >= Fraction(2) ** (emax + 1) else y
+
+
+def rn32(x):
+    return rn(x, 24, -126, 127)
+
+
+def rn64(x):
+    return rn(x, 53, -1022, 1023)
+
+
+def model_element_f64(a: float, b: float, atol: float, rtol: float):
+    """The binary64 rule on finite a, b: each step rounded once to binary64, product and sum separately."""
+    fa, fb = Fraction(a), Fraction(b)
+    d = rn64(abs(fa - fb))
+    prod = rn64(Fraction(rtol) * abs(fb))
+    tol = INF if prod == INF else rn64(Fraction(atol) + prod)
+    close = True if tol == INF else (False if d == INF else d <= tol)
+    if d == 0:
+        r = Fraction(0)
+    elif d == INF or fb == 0:
+        r = INF
+    else:
+        r = rn64(d / abs(fb))
+    return close, d, r
 
 
 def model_element(a: float, b: float, atol_f: float, rtol_f: float):
@@ -196,10 +221,96 @@ def test_fma_contraction_would_be_caught(oracle_mod):
     assert found >= 25
 
 
+def test_rational_model_matches_oracle_f64(oracle_mod):
+    """binary64 segments (rule R2'): the oracle against exact rational arithmetic with explicit rounding to
+    53 bits, on cases placed within a few ulps of the tolerance boundary, subnormal and huge magnitudes
+    included; and a search for (b, rtol, atol) where a fused multiply-add would round differently."""
+    rng = np.random.default_rng(64)
+    hits = 0
+    for _ in range(3000):
+        kind = rng.integers(0, 4)
+        if kind == 0:
+            b = float(rng.normal() * 10.0 ** rng.integers(-3, 4))
+        elif kind == 1:
+            b = float(np.array([rng.integers(0, 1 << 53)], dtype=np.uint64).view(np.float64)[0]) * (1 if rng.random() < 0.5 else -1)
+        elif kind == 2:
+            b = float(rng.normal() * 1e307)
+        else:
+            u = np.uint64(rng.integers(0, 1 << 63)) | (np.uint64(rng.integers(0, 2)) << np.uint64(63))
+            if (int(u) >> 52) & 0x7FF == 0x7FF:
+                u = np.uint64(int(u) & ~(0x7FF << 52))
+            b = float(np.array([u], dtype=np.uint64).view(np.float64)[0])
+        atol = float(10.0 ** rng.uniform(-320, 1)) if rng.random() < 0.8 else 0.0
+        rtol = float(10.0 ** rng.uniform(-17, 0.5)) if rng.random() < 0.8 else 0.0
+        tol = atol + rtol * abs(b)
+        target = b + (tol if rng.random() < 0.5 else -tol)
+        if not math.isfinite(target):
+            target = b
+        ai = np.array([target], dtype=np.float64).view(np.int64) + np.int64(rng.integers(-3, 4))
+        a = float(ai.view(np.float64)[0])
+        if not math.isfinite(a):
+            a = target
+        close, d, r = model_element_f64(a, b, atol, rtol)
+        rec = oracle_mod.check_segment(np.array([b]), np.array([a]), 1, "f64", atol, rtol, False)
+        exp = (int(close), int(not close), -1 if close else 0, _to_float(d), _to_float(r))
+        got = (int(rec["pass"]), int(rec["mismatch_count"]), int(rec["first_mismatch"]),
+               float(rec["max_abs_err"]), float(rec["max_rel_err"]))
+        assert got == exp, (b, a, atol, rtol, got, exp)
+        prod = rn64(Fraction(rtol) * abs(Fraction(b)))
+        if prod != INF and d != INF and d == rn64(Fraction(atol) + prod):
+            hits += 1
+    assert hits > 30
+    found = 0
+    for _ in range(20000):
+        b, rtol, atol = float(rng.uniform(1.0, 2.0)), float(rng.uniform(1e-3, 1e-2)), float(rng.uniform(1e-3, 1e-2))
+        two = rn64(Fraction(atol) + rn64(Fraction(rtol) * Fraction(b)))
+        one = rn64(Fraction(atol) + Fraction(rtol) * Fraction(b))
+        if two == one:
+            continue
+        big = max(two, one)
+        a = float(Fraction(b) + big)
+        if rn64(abs(Fraction(a) - Fraction(b))) != big:
+            continue
+        rec = oracle_mod.check_segment(np.array([b]), np.array([a]), 1, "f64", atol, rtol, False)
+        assert int(rec["pass"]) == int(big == two), (b, a, atol, rtol)
+        found += 1
+        if found >= 25:
+            break
+    assert found >= 25
+
+
+def test_f64_hand_derived(oracle_mod):
+    inf, nan = np.inf, np.nan
+    # atol = rtol = 2^-41, b = 1: tol = 2^-40 exactly; d = 2^-40 passes (inclusive), d = 2^-40 + 2^-52 fails
+    b = np.array([1.0, 1.0, nan, inf, 0.0, nan, 1.0, -0.0])
+    a = np.array([1.0 + 2.0 ** -40, 1.0 + 2.0 ** -40 + 2.0 ** -52, nan, -inf, 5e-324, 1.0, inf, 0.0])
+    rec = oracle_mod.check_segment(b, a, 8, "f64", 2.0 ** -41, 2.0 ** -41, True)
+    assert (int(rec["mismatch_count"]), int(rec["first_mismatch"])) == (4, 1)     # 1, 3, 5, 6
+    assert float(rec["max_abs_err"]) == inf and float(rec["max_rel_err"]) == inf
+    rec = oracle_mod.check_segment(b[:3], a[:3], 3, "f64", 2.0 ** -41, 2.0 ** -41, False)
+    assert (int(rec["mismatch_count"]), int(rec["first_mismatch"])) == (2, 1)     # NaN pair fails without equal_nan
+    assert float(rec["max_abs_err"]) == 2.0 ** -40 + 2.0 ** -52 == float(rec["max_rel_err"])
+    # a difference far below binary32 resolution is still seen
+    rec = oracle_mod.check_segment(np.array([1.0]), np.array([1.0 + 2.0 ** -50]), 1, "f64", 0.0, 2.0 ** -51, False)
+    assert int(rec["pass"]) == 0 and float(rec["max_rel_err"]) == 2.0 ** -50
+    rep = oracle_mod.report_segment(b, a, 8, "f64", 2.0 ** -41, 2.0 ** -41, True, 8)
+    assert [int(r["index"]) for r in rep] == [1, 3, 5, 6]
+    assert float(rep[0]["d"]) == 2.0 ** -40 + 2.0 ** -52 and float(rep[0]["tol"]) == 2.0 ** -40
+    assert float(rep[1]["d"]) == inf and float(rep[1]["tol"]) == inf and np.isnan(rep[2]["d"]) and np.isnan(rep[2]["tol"])
+
+
 # ------------------------------------------------------------------------------------------
 # structural invariants
 # ------------------------------------------------------------------------------------------
 def _rand_case(rng, dtype, n):
+    if dtype == "f64":
+        b = rng.normal(size=n)
+        a = b + 1e-9 * rng.normal(size=n) * (rng.random(n) < 0.3)
+        pool = np.array([np.nan, np.inf, -np.inf, 0.0, -0.0, 5e-324, 1e308])
+        for arr in (a, b):
+            sp = rng.random(n) < 0.02
+            arr[sp] = rng.choice(pool, int(sp.sum()))
+        return b, a
     if dtype in ("u8", "i8"):
         np_t = np.uint8 if dtype == "u8" else np.int8
         info = np.iinfo(np_t)
@@ -242,7 +353,7 @@ def _rand_case(rng, dtype, n):
     return tb, ta
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64"])
 def test_invariants(oracle_mod, dtype):
     rng = np.random.default_rng(11)
     n = 3001
@@ -255,7 +366,9 @@ def test_invariants(oracle_mod, dtype):
         clean = b
     else:
         _, clean = _rand_case(np.random.default_rng(12), dtype, n)
-        store = clean.view(np.uint32) if dtype == "f32" else clean
+        if dtype == "f64":
+            clean = np.where(np.isfinite(clean), clean, 0.0)
+        store = clean.view(np.uint32) if dtype == "f32" else (np.zeros(n, np.uint16) if dtype == "f64" else clean)
         expo = (store & 0x7F800000) == 0x7F800000 if dtype == "f32" else (
             (store & 0x7C00) == 0x7C00 if dtype == "f16" else (store & 0x7F80) == 0x7F80)
         clean = clean.copy()
