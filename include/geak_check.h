@@ -9,11 +9,12 @@
  * (section 3.3); the check runs once per candidate x unit test x refinement iteration x parallel
  * run (sections 4.1, 4.2, 5.2).  The paper gives no formula, so this library fixes one:
  *
- *   floating dtypes, a = candidate element, b = reference element, all steps in IEEE binary32,
+ *   fp32, fp16, bf16: a = candidate element, b = reference element, all steps in IEEE binary32,
  *   round-to-nearest-even, one rounding per step, no fused multiply-add, subnormals honoured:
  *       d = |a - b|,  tol = atol_f + (rtol_f * |b|),  close <=> d <= tol
  *       a or b NaN   : close <=> equal_nan and both NaN
  *       a or b +-Inf : close <=> a == b
+ *   fp64: the same rule with every step in IEEE binary64 and atol, rtol as given (not narrowed)
  *   int32, int64, uint8, int8:
  *                      close <=> a == b   (atol, rtol, equal_nan ignored; d = |a - b| exact; for int64
  *                      d (up to 2^64 - 1) and |b| are each rounded once to binary64 where a double is
@@ -25,7 +26,8 @@
  *       pass            1 iff mismatch_count == 0 (an empty segment passes)
  *       max_abs_err     max of d over ALL elements, NaN d skipped, +Inf kept, starting at +0
  *       max_rel_err     max over all elements of (d == 0 ? 0 : d / |b|) (binary32 division for
- *                       floating dtypes, binary64 for the integer dtypes; x/0 = +Inf; NaN skipped), from +0
+ *                       fp32 / fp16 / bf16, binary64 for fp64 and the integer dtypes; x/0 = +Inf; NaN
+ *                       skipped), from +0
  *   Every field is an order-independent reduction, so results are bit-reproducible.
  *
  * Memory model.  The caller owns every device buffer (reference, candidates, workspace, results)
@@ -54,7 +56,7 @@ typedef enum {
 } geak_status;
 
 typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64 = 4,
-               GEAK_U8 = 5 /* also boolean masks stored as bytes */, GEAK_I8 = 6 } geak_dtype;
+               GEAK_U8 = 5 /* also boolean masks stored as bytes */, GEAK_I8 = 6, GEAK_F64 = 7 } geak_dtype;
 
 #define GEAK_MAX_CANDIDATES 256
 #define GEAK_MAX_SEGMENT_NUMEL (1ull << 40)
@@ -90,7 +92,7 @@ typedef struct geak_plan geak_plan; /* opaque */
  *   out            receives the plan; untouched on failure
  *   segs, nsegs    host array, copied; nsegs >= 1
  *   num_candidates 1 .. GEAK_MAX_CANDIDATES
- *   atol, rtol     finite, >= 0; converted once to binary32
+ *   atol, rtol     finite, >= 0; converted once to binary32 (fp64 segments use them as given)
  *   equal_nan      0 or 1
  *   device         HIP device ordinal that geak_check_run will use; -1 builds a host-only plan
  *                  (for inspection; geak_check_run then returns GEAK_EINVAL) laid out for 256 compute units
@@ -102,14 +104,14 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
 
 /* One tolerance pair per segment.  The unit tests of one kernel produce outputs of different
  * magnitude and precision (section 3.3: a kernel is checked on all of its unit tests), so each
- * packed output may be judged with its own atol / rtol; int32 segments ignore theirs. */
+ * packed output may be judged with its own atol / rtol; integer segments ignore theirs. */
 typedef struct {
     double atol;
     double rtol;
 } geak_tolerance;
 
 /* Like geak_check_plan, with `tols[s]` applying to segment s (host array of nsegs entries, copied;
- * each value finite and >= 0, also after conversion to binary32). */
+ * each value finite and >= 0, for every dtype but fp64 also after conversion to binary32). */
 geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs, const geak_tolerance *tols,
                                        uint64_t nsegs, int32_t num_candidates, int32_t equal_nan, int32_t device);
 
@@ -211,10 +213,11 @@ uint64_t    geak_check_profile_read(geak_plan *plan, float *ms_out, uint64_t cap
  * close, in ascending index order, each with what the rule saw:
  *     index  flat 0-based index within the segment
  *     a, b   candidate and reference element, widened exactly to binary64
- *     d      |a - b| as the rule computed it (binary32 value widened; exact for int32); NaN when a or
- *            b is NaN or both are the same infinity, +Inf when one of them is infinite
- *     tol    atol_f + rtol_f * |b| as the rule computed it (binary32, two roundings, widened; NaN or
- *            +Inf when b is); 0 for int32
+ *     d      |a - b| as the rule computed it (binary32 value widened, binary64 for fp64; exact for
+ *            integers up to the one rounding of int64); NaN when a or b is NaN or both are the same
+ *            infinity, +Inf when one of them is infinite
+ *     tol    atol + rtol * |b| as the rule computed it (two roundings, in binary32 and widened, or in
+ *            binary64 for fp64; NaN or +Inf when b is); 0 for integers
  * NaN payloads are not specified. */
 typedef struct {
     int64_t index;

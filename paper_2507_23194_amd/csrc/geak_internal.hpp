@@ -19,7 +19,7 @@ inline int elem_size(int dtype)
 {
     switch (dtype) {
     case GEAK_F16: case GEAK_BF16: return 2;
-    case GEAK_I64: return 8;
+    case GEAK_I64: case GEAK_F64: return 8;
     case GEAK_U8: case GEAK_I8: return 1;
     default: return 4;
     }
@@ -43,11 +43,15 @@ inline uint32_t lds_bytes_for(int num_candidates) {
     return lds_state_bytes(num_candidates) + kWavesPerBlock * kTolBytesPerWave;
 }
 
-// Tolerances of one segment, converted once to binary32.
+// Tolerances of one segment: converted once to binary32 for the dtypes whose rule runs in binary32,
+// and as given for binary64 segments.  Three 64-bit words.
 struct SegTol {
     float atol_f;
     float rtol_f;
+    double atol;
+    double rtol;
 };
+static_assert(sizeof(SegTol) == 24, "SegTol is read as three 64-bit words");
 
 // Host side of a plan: everything that can be decided without a device.
 struct HostPlan {
@@ -56,7 +60,7 @@ struct HostPlan {
     std::vector<uint32_t> slot_begin;      // per segment, size nsegs + 1; slots of a segment are contiguous
     uint64_t algorithmic_bytes = 0;
     int num_candidates = 0;
-    std::vector<SegTol> seg_tol;          // per segment, already in binary32
+    std::vector<SegTol> seg_tol;          // per segment
     int equal_nan = 0;
     uint32_t grid_blocks = 1;
     uint32_t replicas = 1;                 // replicas of the running maxima per (segment, candidate)

@@ -52,6 +52,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
 constexpr float kInfF = __builtin_huge_valf();
+constexpr double kInfD = __builtin_huge_val();
 
 // Explicit address spaces.  Tables that are written before the kernel starts and never during it
 // (work items, candidate base pointers) are read through the constant address space, so that a
@@ -86,14 +87,16 @@ __device__ __forceinline__ const unsigned char *table_entry(const unsigned char 
     return reinterpret_cast<const unsigned char *>(t[k]);
 }
 
-// A segment's tolerance pair, read with a scalar load when the segment index is wave-uniform.
+// A segment's tolerances, read with scalar loads when the segment index is wave-uniform.
 __device__ __forceinline__ SegTol load_tol(const SegTol *table, uint32_t segment)
 {
-    const GEAK_AS_CONSTANT unsigned long long *t = (const GEAK_AS_CONSTANT unsigned long long *)table;
-    const unsigned long long w = t[segment];
+    const GEAK_AS_CONSTANT unsigned long long *t = (const GEAK_AS_CONSTANT unsigned long long *)(table + segment);
+    const unsigned long long w = t[0];
     SegTol out;
     out.atol_f = __builtin_bit_cast(float, (uint32_t)w);
     out.rtol_f = __builtin_bit_cast(float, (uint32_t)(w >> 32));
+    out.atol = __builtin_bit_cast(double, t[1]);
+    out.rtol = __builtin_bit_cast(double, t[2]);
     return out;
 }
 
@@ -105,8 +108,10 @@ template <> struct Traits<GEAK_I32>  { static constexpr int E = 4, W = 4; };
 template <> struct Traits<GEAK_I64>  { static constexpr int E = 2, W = 8; };
 template <> struct Traits<GEAK_U8>   { static constexpr int E = 16, W = 1; };
 template <> struct Traits<GEAK_I8>   { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_F64>  { static constexpr int E = 2, W = 8; };
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ double bits_d(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(double, (u64)lo | ((u64)hi << 32)); }
 __device__ __forceinline__ uint32_t f_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
 
 // Element e (0 .. E-1) of a 16-byte vector, decoded exactly to binary32.
@@ -254,6 +259,17 @@ __device__ __forceinline__ bool close_exact(float a, float b, float atol_f, floa
     return d <= tol;
 }
 
+__device__ __forceinline__ bool close_exact_d(double a, double b, double atol, double rtol, int equal_nan)
+{
+    const bool a_nan = a != a, b_nan = b != b;
+    if (a_nan || b_nan) return equal_nan && a_nan && b_nan;
+    if (__builtin_fabs(a) == kInfD || __builtin_fabs(b) == kInfD) return a == b;
+    const double d = __builtin_fabs(a - b);
+    const double prod = rtol * __builtin_fabs(b);
+    const double tol = atol + prod;
+    return d <= tol;
+}
+
 // max_rel filter.  An element can raise the running maximum r only if d/|b| > r, i.e. d > r*|b| in
 // exact arithmetic.  e = fma(r, |b|, -d) is the correctly rounded value of r*|b| - d, and rounding
 // keeps the sign of the exact value (a tiny negative value becomes -0, an exact tie becomes +0), so
@@ -265,6 +281,11 @@ constexpr int kClassNegative = (1 << 2) | (1 << 3) | (1 << 4) | (1 << 5);   // -
 __device__ __forceinline__ bool may_raise_rel(float r, float babs, float d)
 {
     return __builtin_amdgcn_classf(__builtin_fmaf(r, babs, -d), kClassNegative);
+}
+// the same test in binary64 (v_fma_f64, v_cmp_class_f64)
+__device__ __forceinline__ bool may_raise_rel_d(double r, double babs, double d)
+{
+    return __builtin_amdgcn_class(__builtin_fma(r, babs, -d), kClassNegative);
 }
 
 // int64 elements: |a - b| exact as an unsigned 64-bit integer and |b| (at most 2^63), each converted to
@@ -284,12 +305,33 @@ __device__ __forceinline__ double i64_abs(long long x)
 // Used (a) for segment heads and tails, (b) when the hot loop finds that an item may raise one of
 // the maxima.  Returns the wave-uniform mismatch count and raises the record's maxima.
 __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsigned char *cand, uint32_t n, int dtype,
-                                            float atol_f, float rtol_f, int equal_nan, MaxPair *rec)
+                                            const SegTol tolerance, int equal_nan, MaxPair *rec)
 {
     const int lane = threadIdx.x & (kWaveSize - 1);
     const u64 abs_bits = load_bits(&rec->abs), rel_bits = load_bits(&rec->rel);
     uint32_t bad = 0;
-    if (dtype == GEAK_I32 || dtype == GEAK_I64 || dtype == GEAK_U8 || dtype == GEAK_I8) {
+    if (dtype == GEAK_F64) {
+        const double seen_rel = __builtin_bit_cast(double, rel_bits);
+        const bool rel_open = seen_rel < kInfD;
+        double dm = 0.0, rm = 0.0;
+        for (uint32_t i = lane; i < n; i += kWaveSize) {
+            const double a = reinterpret_cast<const double *>(cand)[i], b = reinterpret_cast<const double *>(ref)[i];
+            bad += !close_exact_d(a, b, tolerance.atol, tolerance.rtol, equal_nan);
+            const double d = __builtin_fabs(a - b);
+            const double babs = __builtin_fabs(b);
+            if (d > dm) dm = d;                                   // false for NaN: skipped
+            if (rel_open && may_raise_rel_d(seen_rel, babs, d)) { // implies d > 0
+                const double r = d / babs;                        // correctly rounded; d/0 = +Inf; Inf/Inf = NaN
+                if (r > rm) rm = r;                               // false for NaN: skipped
+            }
+        }
+        dm = wave_max_d(dm);
+        rm = wave_max_d(rm);
+        if (lane == 0) {
+            raise_max(&rec->abs, dm, abs_bits);
+            raise_max(&rec->rel, rm, rel_bits);
+        }
+    } else if (dtype == GEAK_I32 || dtype == GEAK_I64 || dtype == GEAK_U8 || dtype == GEAK_I8) {
         const double seen_rel = __builtin_bit_cast(double, rel_bits);
         // d > c*|b| is implied by d/|b| > seen_rel; the 2^-30 margin covers the product's rounding
         const double c = (seen_rel == (double)kInfF) ? __builtin_nan("") : seen_rel * (1.0 - 0x1p-30);
@@ -319,7 +361,7 @@ __device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsi
         float dm = 0.0f, rm = 0.0f;
         for (uint32_t i = lane; i < n; i += kWaveSize) {
             const float a = load_elem_f(cand, i, dtype), b = load_elem_f(ref, i, dtype);
-            bad += !close_exact(a, b, atol_f, rtol_f, equal_nan);
+            bad += !close_exact(a, b, tolerance.atol_f, tolerance.rtol_f, equal_nan);
             const float d = __builtin_fabsf(a - b);
             const float babs = __builtin_fabsf(b);
             if (d > dm) dm = d;                                   // false for NaN: skipped
@@ -523,8 +565,9 @@ struct FloatItem {
     // Stage vector V of the reference slice: keep it (packed or unpacked, see above), compute the
     // tolerance of each of its elements once, and poison the elements the bare inequality cannot judge.
     template <int V>
-    __device__ __forceinline__ void stage_vec(const u32x4 &q, float atol_f, float rtol_f)
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &tolerance)
     {
+        const float atol_f = tolerance.atol_f, rtol_f = tolerance.rtol_f;
         if constexpr (V == 0) poisoned_slots = 0;
         if constexpr (DT != GEAK_BF16) {
 #pragma unroll
@@ -764,7 +807,7 @@ struct IntItem {
     static constexpr uint32_t poisoned_slots = 0;
 
     template <int V>
-    __device__ __forceinline__ void stage_vec(const u32x4 &q, float, float)
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &)
     {
 #pragma unroll
         for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
@@ -891,7 +934,7 @@ struct Int64Item {
     static constexpr uint32_t poisoned_slots = 0;
 
     template <int V>
-    __device__ __forceinline__ void stage_vec(const u32x4 &q, float, float)
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &)
     {
 #pragma unroll
         for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
@@ -917,6 +960,142 @@ struct Int64Item {
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
         const DoublePair out = raise_vector_int64(q, b, max_abs, max_rel, rec);
+        max_abs = out.abs;
+        max_rel = out.rel;
+    }
+    template <int V>
+    __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec, int) const
+    {
+        raise_call<V>(q, max_abs, max_rel, rec);
+    }
+};
+
+// ---- binary64: two elements per 16-byte vector, the floating rule in binary64 arithmetic -----------
+// Lane mask of "x is negative (-0 included) and not NaN", binary64.
+__device__ __forceinline__ u64 negative_mask_d(double x)
+{
+    u64 m;
+    asm("v_cmp_class_f64_e64 %0, %1, 60" : "=s"(m) : "v"(x));      // 60 = kClassNegative
+    return m;
+}
+
+__device__ __noinline__ DoublePair raise_vector_f64(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
+                                                    MaxPair *rec_in)
+{
+    MaxPair *rec = uniform_ptr(rec_in);
+    double dm = max_abs, rm = max_rel;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const double x = bits_d(b[2 * e], b[2 * e + 1]);
+        const double d = __builtin_fabs(bits_d(q[2 * e], q[2 * e + 1]) - x);
+        const double babs = __builtin_fabs(x);
+        dm = (d > dm) ? d : dm;                                          // false for NaN: skipped
+        const bool hit = (rm < kInfD) && may_raise_rel_d(rm, babs, d);   // implies d > 0
+        if (__builtin_amdgcn_ballot_w64(hit)) {
+            const double r = d / babs;                                   // correctly rounded; d/0 = +Inf
+            rm = (hit && r > rm) ? r : rm;
+        }
+    }
+    dm = wave_max_d(dm);
+    rm = wave_max_d(rm);
+    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
+        if (dm > max_abs) publish_max(&rec->abs, dm);
+        if (rm > max_rel) publish_max(&rec->rel, rm);
+    }
+    DoublePair out;
+    out.abs = dm;
+    out.rel = rm;
+    return out;
+}
+
+struct DoubleItem {
+    typedef double Hint;
+    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
+    static constexpr int E = 2;
+    static constexpr bool kRaiseOutOfLine = true;    // binary64 division: kept out of the stream, like the integer items'
+    uint32_t bref[kVecPerLane * 4];
+    double tol[kVecPerLane * E];
+    uint32_t poisoned_slots;        // wave-uniform: bit i set if any lane's element i is poisoned
+    __device__ __forceinline__ void attach_lds(uint32_t, int) {}
+
+    template <int V, int e>
+    __device__ __forceinline__ double ref_value() const { return bits_d(bref[V * 4 + 2 * e], bref[V * 4 + 2 * e + 1]); }
+
+    // Stage vector V of the reference slice: the tolerance of each element, computed once with two
+    // roundings, or a poison value where the bare inequality cannot judge (-1 b is NaN, -2 b is
+    // +-Inf, -3 finite b with an infinite tolerance).
+    template <int V>
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &tolerance)
+    {
+        if constexpr (V == 0) poisoned_slots = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            constexpr int i = V * E + e;
+            const double x = bits_d(q[2 * e], q[2 * e + 1]);
+            const double prod = tolerance.rtol * __builtin_fabs(x);
+            const double t = tolerance.atol + prod;
+            tol[i] = t;
+            const bool bad = !(t < kInfD);
+            if (__builtin_amdgcn_ballot_w64(bad)) {
+                const double why = (x != x) ? -1.0 : (__builtin_fabs(x) == kInfD ? -2.0 : -3.0);
+                tol[i] = bad ? why : t;
+                poisoned_slots |= (1u << i);
+            }
+        });
+    }
+
+    // Hot loop body for one 16-byte vector of one candidate: suspects (elements with !(d <= tol)) and
+    // the lanes that may raise one of the maxima.  Five binary64 instructions per element.
+    template <int V, bool AHEAD = true>
+    __device__ __forceinline__ void compare_vec(const u32x4 &q, double max_abs, double max_rel, uint32_t &suspects,
+                                                u64 &trip_abs, u64 &trip_rel, int equal_nan) const
+    {
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            const double x = ref_value<V, e>();
+            const double d = bits_d(q[2 * e], q[2 * e + 1]) - x;
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabs(d) <= tol[V * E + e])));
+            trip_abs |= __builtin_amdgcn_ballot_w64(__builtin_fabs(d) > max_abs);
+            trip_rel |= negative_mask_d(__builtin_fma(max_rel, __builtin_fabs(x), -__builtin_fabs(d)));
+        });
+        // poisoned elements were all reported as suspects; take off those that the NaN / Inf rule accepts
+        if constexpr (AHEAD) {
+            constexpr uint32_t kVecMask = ((1u << E) - 1u) << (V * E);
+            if (poisoned_slots & kVecMask) suspects -= false_suspects_call<V>(q, equal_nan);
+        }
+    }
+
+    // Number of poisoned elements of vector V that the NaN / Inf rule accepts.
+    template <int V>
+    __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &q, int equal_nan) const
+    {
+        uint32_t n = 0;
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            constexpr int i = V * E + e;
+            if (poisoned_slots & (1u << i)) {
+                const double a = bits_d(q[2 * e], q[2 * e + 1]);
+                const double x = ref_value<V, e>();
+                const double why = tol[i];
+                const bool ok = (why == -1.0) ? (equal_nan && (a != a))
+                              : (why == -2.0) ? (a == x)
+                              : (why == -3.0) ? (__builtin_fabs(a) < kInfD)   // any finite a is within an infinite tolerance
+                              : false;
+                n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok));
+            }
+        });
+        return n;
+    }
+
+    template <int V>
+    __device__ __forceinline__ void raise_call(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec) const
+    {
+        u32x4 b;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
+        const DoublePair out = raise_vector_f64(q, b, max_abs, max_rel, rec);
         max_abs = out.abs;
         max_rel = out.rel;
     }
@@ -991,7 +1170,7 @@ struct ByteItem {
     static constexpr uint32_t poisoned_slots = 0;
 
     template <int V>
-    __device__ __forceinline__ void stage_vec(const u32x4 &q, float, float)
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &)
     {
 #pragma unroll
         for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
@@ -1033,6 +1212,7 @@ template <> struct ItemOf<GEAK_U8> { typedef ByteItem<false> type; };
 template <> struct ItemOf<GEAK_I8> { typedef ByteItem<true> type; };
 template <> struct ItemOf<GEAK_I32> { typedef IntItem type; };
 template <> struct ItemOf<GEAK_I64> { typedef Int64Item type; };
+template <> struct ItemOf<GEAK_F64> { typedef DoubleItem type; };
 
 __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 {
@@ -1089,8 +1269,8 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
 {
     u64 trip_abs = 0, trip_rel = 0;
     ref.template compare_vec<V, !OUTLINE>(slot, max_abs, max_rel, bad, trip_abs, trip_rel, equal_nan);
-    if constexpr (OUTLINE && (DT == GEAK_F32 || DT == GEAK_F16 || DT == GEAK_BF16)) {      // only floating items poison slots
-        constexpr uint32_t kVecMask = ((Traits<DT>::E == 8) ? 0xFFu : 0xFu) << (V * Traits<DT>::E);
+    if constexpr (OUTLINE && (DT == GEAK_F32 || DT == GEAK_F16 || DT == GEAK_BF16 || DT == GEAK_F64)) {      // only floating items poison slots
+        constexpr uint32_t kVecMask = ((1u << Traits<DT>::E) - 1u) << (V * Traits<DT>::E);
         if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_call<V>(slot, equal_nan);
     }
     if (max_rel == (typename Item::Hint)kInfF) trip_rel = 0;       // nothing exceeds +Inf
@@ -1144,7 +1324,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
             nx = load_work_item(items, jn);
             more = (nx.flags & GEAK_ITEM_FULL) && nx.dtype == DT;
         }
-        const float atol_f = tolerance.atol_f, rtol_f = tolerance.rtol_f;
+        const SegTol cur_tol = tolerance;
         if (more) tolerance = load_tol(seg_tol, nx.segment);          // the next item's, a whole item ahead of its use
         if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
         MaxPair *recs = board + (u64)it.segment * K * replicas + replica;     // candidate k: recs[k * replicas]
@@ -1153,10 +1333,10 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
         uint32_t k = k0;
         {
             const unsigned char *first = table_entry(cand, k) + it.byte_offset;
-            ref.template stage_vec<0>(cur[0], atol_f, rtol_f); cur[0] = load_vec<DT>(first, lane, 0, it.numel, full);
-            ref.template stage_vec<1>(cur[1], atol_f, rtol_f); cur[1] = load_vec<DT>(first, lane, 1, it.numel, full);
-            ref.template stage_vec<2>(cur[2], atol_f, rtol_f); cur[2] = load_vec<DT>(first, lane, 2, it.numel, full);
-            ref.template stage_vec<3>(cur[3], atol_f, rtol_f); cur[3] = load_vec<DT>(first, lane, 3, it.numel, full);
+            ref.template stage_vec<0>(cur[0], cur_tol); cur[0] = load_vec<DT>(first, lane, 0, it.numel, full);
+            ref.template stage_vec<1>(cur[1], cur_tol); cur[1] = load_vec<DT>(first, lane, 1, it.numel, full);
+            ref.template stage_vec<2>(cur[2], cur_tol); cur[2] = load_vec<DT>(first, lane, 2, it.numel, full);
+            ref.template stage_vec<3>(cur[3], cur_tol); cur[3] = load_vec<DT>(first, lane, 3, it.numel, full);
         }
         u64 abs_bits = load_bits(&recs[k * replicas].abs), rel_bits = load_bits(&recs[k * replicas].rel);
 
@@ -1215,7 +1395,6 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     const uint32_t j = uniform32(in.first_item);
     const geak_item it = load_work_item(items, j);
     const SegTol tolerance = load_tol(seg_tol, it.segment);
-    const float atol_f = tolerance.atol_f, rtol_f = tolerance.rtol_f;
     const uint32_t n = it.numel;
     const uint32_t vectors = (n * Traits<DT>::W + kWaveSize * 16 - 1) / (kWaveSize * 16);    // 1..4 per lane
     const uint32_t per_batch = vectors == 1 ? 4 : (vectors == 2 ? 2 : 1);                       // candidates per batch
@@ -1248,10 +1427,10 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
 #pragma unroll
         for (int v = 0; v < kVecPerLane; ++v) r[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, n, false);
         load_batch(0);                                     // in flight together with the reference
-        ref.template stage_vec<0>(r[0], atol_f, rtol_f);
-        ref.template stage_vec<1>(r[1], atol_f, rtol_f);
-        ref.template stage_vec<2>(r[2], atol_f, rtol_f);
-        ref.template stage_vec<3>(r[3], atol_f, rtol_f);
+        ref.template stage_vec<0>(r[0], tolerance);
+        ref.template stage_vec<1>(r[1], tolerance);
+        ref.template stage_vec<2>(r[2], tolerance);
+        ref.template stage_vec<3>(r[3], tolerance);
     }
     if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
 
@@ -1312,7 +1491,7 @@ __device__ __forceinline__ void process_head(const geak_item &it, uint32_t item_
     const SegTol tolerance = load_tol(p.seg_tol, it.segment);
     for (uint32_t k = 0; k < K; ++k) {
         const uint32_t bad = exact_item(p.ref + it.byte_offset, table_entry(p.cand_table, k) + it.byte_offset, it.numel,
-                                        it.dtype, tolerance.atol_f, tolerance.rtol_f, p.equal_nan, &recs[k * p.replicas]);
+                                        it.dtype, tolerance, p.equal_nan, &recs[k * p.replicas]);
         note_mismatches(st, k, bad, item_index, lane);
     }
 }
@@ -1361,6 +1540,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_I32:  next_j = process_run<GEAK_I32>(r, st); break;
                 case GEAK_I64:  next_j = process_run<GEAK_I64>(r, st); break;
                 case GEAK_U8:   next_j = process_run<GEAK_U8>(r, st); break;
+                case GEAK_F64:  next_j = process_run<GEAK_F64>(r, st); break;
                 default:        next_j = process_run<GEAK_I8>(r, st); break;
                 }
             } else {
@@ -1371,6 +1551,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_I32:  process_tail<GEAK_I32>(r, st); break;
                 case GEAK_I64:  process_tail<GEAK_I64>(r, st); break;
                 case GEAK_U8:   process_tail<GEAK_U8>(r, st); break;
+                case GEAK_F64:  process_tail<GEAK_F64>(r, st); break;
                 default:        process_tail<GEAK_I8>(r, st); break;
                 }
                 next_j = it.next;
@@ -1408,11 +1589,14 @@ __global__ void init_kernel(const InitArgs p)
 
 // ---- reduce: one block per (segment, candidate) ----------------------------------------------
 __device__ __forceinline__ bool element_close(const unsigned char *ref, const unsigned char *cand, u64 idx,
-                                              int dtype, float atol_f, float rtol_f, int equal_nan)
+                                              int dtype, const SegTol &tolerance, int equal_nan)
 {
+    if (dtype == GEAK_F64)
+        return close_exact_d(reinterpret_cast<const double *>(cand)[idx], reinterpret_cast<const double *>(ref)[idx],
+                             tolerance.atol, tolerance.rtol, equal_nan);
     if (dtype == GEAK_I32 || dtype == GEAK_I64 || dtype == GEAK_U8 || dtype == GEAK_I8)
         return load_elem_int(ref, idx, dtype) == load_elem_int(cand, idx, dtype);
-    return close_exact(load_elem_f(cand, idx, dtype), load_elem_f(ref, idx, dtype), atol_f, rtol_f, equal_nan);
+    return close_exact(load_elem_f(cand, idx, dtype), load_elem_f(ref, idx, dtype), tolerance.atol_f, tolerance.rtol_f, equal_nan);
 }
 
 constexpr int kReduceThreads = 256;
@@ -1472,7 +1656,7 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
             const uint32_t i = (uint32_t)tid + u * kReduceThreads;
-            bad[u] = (i < it.numel) && !element_close(rb, cb, i, it.dtype, tolerance.atol_f, tolerance.rtol_f, p.equal_nan);
+            bad[u] = (i < it.numel) && !element_close(rb, cb, i, it.dtype, tolerance, p.equal_nan);
         }
         uint32_t best = kNoItem;
 #pragma unroll
@@ -1550,7 +1734,7 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
             if constexpr (DT == GEAK_I32) {
                 ai[u] = in ? reinterpret_cast<const int *>(cb)[i] : 0;
                 bi[u] = in ? reinterpret_cast<const int *>(rb)[i] : 0;
-            } else if constexpr (DT == GEAK_I64) {
+            } else if constexpr (DT == GEAK_I64 || DT == GEAK_F64) {     // binary64 travels as its bit pattern
                 ai[u] = in ? reinterpret_cast<const long long *>(cb)[i] : 0;
                 bi[u] = in ? reinterpret_cast<const long long *>(rb)[i] : 0;
             } else if constexpr (DT == GEAK_U8 || DT == GEAK_I8) {
@@ -1568,6 +1752,9 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
         for (int u = 0; u < kReportPerThread; ++u) {
             const u64 i = base + (u64)u * kReportThreads + tid;
             if constexpr (kIntegerDtype<DT>) bad[u] = (i < sg.numel) && ai[u] != bi[u];
+            else if constexpr (DT == GEAK_F64)
+                bad[u] = (i < sg.numel) && !close_exact_d(__builtin_bit_cast(double, ai[u]), __builtin_bit_cast(double, bi[u]),
+                                                          tolerance.atol, tolerance.rtol, p.equal_nan);
             else bad[u] = (i < sg.numel) && !close_exact(av[u], bv[u], tolerance.atol_f, tolerance.rtol_f, p.equal_nan);
             const u64 mask = __builtin_amdgcn_ballot_w64(bad[u]);
             before[u] = (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
@@ -1595,6 +1782,13 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
                     m.b = (double)bi[u];
                     m.d = i64_abs_diff(ai[u], bi[u]);
                     m.tol = 0.0;
+                } else if constexpr (DT == GEAK_F64) {
+                    const double a = __builtin_bit_cast(double, ai[u]), b = __builtin_bit_cast(double, bi[u]);
+                    const double prod = tolerance.rtol * __builtin_fabs(b);
+                    m.a = a;
+                    m.b = b;
+                    m.d = __builtin_fabs(a - b);
+                    m.tol = tolerance.atol + prod;
                 } else {
                     const float prod = tolerance.rtol_f * __builtin_fabsf(bv[u]);
                     m.a = (double)av[u];
@@ -1632,6 +1826,7 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     case GEAK_I32:  report_pair<GEAK_I32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     case GEAK_I64:  report_pair<GEAK_I64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     case GEAK_U8:   report_pair<GEAK_U8>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_F64:  report_pair<GEAK_F64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     default:        report_pair<GEAK_I8>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     }
 }

@@ -24,15 +24,16 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
     for (uint64_t s = 0; s < nsegs; ++s) {
         const double atol = tols[s].atol, rtol = tols[s].rtol;
         if (!(atol >= 0.0) || !(rtol >= 0.0) || std::isinf(atol) || std::isinf(rtol)) return GEAK_EINVAL;
-        if (std::isinf((float)atol) || std::isinf((float)rtol)) return GEAK_EINVAL;   // finite in binary64 but not in binary32
     }
 
     // per-segment checks
     uint64_t total_bytes = 0;
     for (uint64_t s = 0; s < nsegs; ++s) {
         const geak_segment &g = segs[s];
-        if (g.dtype < GEAK_F32 || g.dtype > GEAK_I8) return GEAK_EDTYPE;
+        if (g.dtype < GEAK_F32 || g.dtype > GEAK_F64) return GEAK_EDTYPE;
         if (g.reserved != 0) return GEAK_EINVAL;
+        // the rule of every dtype but binary64 runs in binary32: its tolerances must be finite there too
+        if (g.dtype != GEAK_F64 && (std::isinf((float)tols[s].atol) || std::isinf((float)tols[s].rtol))) return GEAK_EINVAL;
         const uint64_t w = (uint64_t)elem_size(g.dtype);
         if (g.byte_offset % w != 0) return GEAK_EALIGN;
         if (g.numel > GEAK_MAX_SEGMENT_NUMEL) return GEAK_EBOUNDS;
@@ -74,7 +75,7 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
         hp.slot_begin.assign(nsegs + 1, 0);
         hp.num_candidates = num_candidates;
         hp.seg_tol.resize(nsegs);
-        for (uint64_t s = 0; s < nsegs; ++s) hp.seg_tol[s] = SegTol{(float)tols[s].atol, (float)tols[s].rtol};
+        for (uint64_t s = 0; s < nsegs; ++s) hp.seg_tol[s] = SegTol{(float)tols[s].atol, (float)tols[s].rtol, tols[s].atol, tols[s].rtol};
         hp.equal_nan = equal_nan;
         hp.algorithmic_bytes = total_bytes * ((uint64_t)num_candidates + 1);
         hp.max_blocks = max_blocks;
@@ -127,7 +128,7 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
         const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
         const uint64_t slices = (uint64_t)num_candidates + 1;
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
-            const uint64_t per_slice = it.dtype == GEAK_F32 ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
+            const uint64_t per_slice = (it.dtype == GEAK_F32 || it.dtype == GEAK_F64) ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
             if (!(it.flags & GEAK_ITEM_ALIGNED)) return 2 * per_slice * slices;      // element-wise path
             if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 140;
             return per_slice * slices + (starts_run ? 100 : 0);

@@ -25,9 +25,9 @@ from dataclasses import dataclass, field
 import numpy as np
 import torch
 
-ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1}
+ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1, "f64": 8}
 TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32,
-               "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8}
+               "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8, "f64": torch.float64}
 
 _CHUNK = 1 << 25  # elements generated per step, bounds temporary memory
 
@@ -240,6 +240,8 @@ def config4(num_segments: int = 1024, log2_max: float = 20.0, num_candidates: in
             b = torch.randint(-1000, 1001, (n,), generator=g, device=device, dtype=torch.int64)
             big = torch.rand(n, generator=g, device=device) < 0.05                # values beyond 2^53
             b = torch.where(big, b * (1 << 52) + 12345, b)
+        elif dt == "f64":
+            b = torch.randn(n, generator=g, device=device, dtype=torch.float64)
         else:
             b = torch.randn(n, generator=g, device=device).to(TORCH_DTYPE[dt])
         ref[boff:boff + n * w] = b.view(torch.uint8)
@@ -254,9 +256,10 @@ def config4(num_segments: int = 1024, log2_max: float = 20.0, num_candidates: in
                 else:
                     expect[(s, k)] = {"count": 0, "first": -1}
             else:
-                x = b.float() + 1e-6 * torch.randn(n, generator=gk, device=device)
+                wide = b if dt == "f64" else b.float()
+                x = wide + 1e-6 * torch.randn(n, generator=gk, device=device, dtype=wide.dtype)
                 om = torch.rand(n, generator=gk, device=device) < 0.005
-                x = torch.where(om, b.float() + 0.5, x)
+                x = torch.where(om, wide + 0.5, x)
                 a = x.to(TORCH_DTYPE[dt])
                 expect[(s, k)] = {"count": int(om.sum()), "first": _first_true(om, 0)}
             cands[k][boff:boff + n * w] = a.view(torch.uint8)

@@ -12,7 +12,7 @@ from paper_2507_23194_amd import synth
 pytestmark = pytest.mark.gpu
 
 TORCH_STORAGE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32,
-                 "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8}
+                 "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8, "f64": torch.float64}
 
 
 def _to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
@@ -86,6 +86,20 @@ def _special_case(rng, dtype, n, special=0.02):
         idx = rng.random(n) < 0.01
         a[idx] = rng.integers(-2 ** 31, 2 ** 31, int(idx.sum())).astype(np.int32)
         return b, a
+    if dtype == "f64":
+        b = rng.normal(size=n) * 10.0 ** rng.integers(-3, 3, n)
+        a = b * (1 + 1e-3 * rng.normal(size=n)) + 1e-4 * rng.normal(size=n) * (rng.random(n) < 0.5)
+        # pairs within a few units in the last place of the 1e-3 / 1e-3 boundary
+        edge = rng.random(n) < 0.2
+        tol = 1e-3 + 1e-3 * np.abs(b)
+        a[edge] = b[edge] + tol[edge] * (1.0 + rng.integers(-4, 5, int(edge.sum())) * 2.0 ** -52) * rng.choice([-1.0, 1.0], int(edge.sum()))
+        pool = np.array([np.nan, np.inf, -np.inf, 0.0, -0.0, 5e-324, -5e-324, 1.7e308, -1.7e308, 1e-310, 3e38, 1e-45, 0.9e308])
+        for arr in (a, b):
+            sp = rng.random(n) < special
+            arr[sp] = rng.choice(pool, int(sp.sum()))
+        same = rng.random(n) < 0.3
+        a[same] = b[same]
+        return b, a
     b32 = (rng.normal(size=n) * 10.0 ** rng.integers(-3, 3, n)).astype(np.float32)
     a32 = (b32 * (1 + 1e-3 * rng.normal(size=n)) + 1e-4 * rng.normal(size=n) * (rng.random(n) < 0.5)).astype(np.float32)
     pool = np.array([np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-45, -1e-45, 3e38, -3e38, 1e-40, 65504.0, 6e-8], np.float32)
@@ -104,7 +118,7 @@ def _special_case(rng, dtype, n, special=0.02):
     return tb, ta
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64"])
 @pytest.mark.parametrize("n", [1, 63, 2048, 4097, 70001, 1 << 20])
 def test_special_values_dense(oracle_mod, dtype, n):
     print("special", dtype, n, flush=True)
@@ -225,6 +239,52 @@ def test_ragged_batch_with_int64_segments(oracle_mod, align):
     _assert_same(gpu, cpu, f"ragged with int64, align {align}")
     for (s, k), e in w.expect.items():
         assert int(gpu[s, k]["mismatch_count"]) == e["count"] and int(gpu[s, k]["first_mismatch"]) == e["first"]
+
+
+@pytest.mark.parametrize("align", [8, 16])
+def test_ragged_batch_with_f64_segments(oracle_mod, align):
+    """binary64 segments (reference outputs computed in double precision) among the others, with
+    segment starts on 16-byte and on bare 8-byte boundaries."""
+    w = synth.config4(num_segments=96, log2_max=15.0, num_candidates=4, device="cuda", align=align, seed=23,
+                      dtypes=("f64", "f32", "f64", "bf16", "i64", "f16"))
+    assert sum(dt == "f64" for _, _, dt in w.segments) > 20
+    gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, f"ragged with binary64, align {align}")
+    for (s, k), e in w.expect.items():
+        assert int(gpu[s, k]["mismatch_count"]) == e["count"] and int(gpu[s, k]["first_mismatch"]) == e["first"]
+
+
+@pytest.mark.parametrize("atol,rtol", [(1e300, 0.0), (0.0, 1e200), (5e-324, 1e-320), (1e-12, 1e-12), (1.7e308, 1.7e308)])
+def test_f64_tolerances_outside_binary32(oracle_mod, atol, rtol):
+    """binary64 segments take atol / rtol as given: values that overflow, underflow or round in binary32."""
+    rng = np.random.default_rng(31)
+    n = 50000
+    b, a0 = _special_case(rng, "f64", n)
+    _, a1 = _special_case(rng, "f64", n, special=0.0)
+    a2 = b + rng.choice([-1.0, 1.0], n) * (atol + rtol * np.abs(b)) * (1.0 + rng.integers(-2, 3, n) * 2.0 ** -52) \
+        if np.isfinite(atol + rtol * 1e3) else a1.copy()
+    for equal_nan in (False, True):
+        gpu = _dense_gpu(b, [a0, a1, a2], "f64", atol, rtol, equal_nan)
+        cpu = oracle_mod.check_dense(b, [a0, a1, a2], "f64", atol, rtol, equal_nan, threads=3).reshape(1, -1)
+        _assert_same(gpu, cpu, f"f64 atol={atol} rtol={rtol} equal_nan={equal_nan}")
+
+
+@pytest.mark.parametrize("second", [1, 300, 512, 5000])
+def test_relative_error_margin_that_underflows_f64(oracle_mod, second):
+    """The binary64 form of the underflowing margin: after max_rel_err = 0.75, an element b = 2^-1074,
+    a = 2^-1073 has relative error exactly 1 while 0.75 * |b| - |a - b| rounds to -0."""
+    n = 1 << 21
+    b = np.ones(n, dtype=np.float64)
+    a = b.copy()
+    b[0], a[0] = 4.0, 7.0
+    b[second] = 2.0 ** -1074
+    a[second] = 2.0 ** -1073
+    cpu = oracle_dense_chunked(oracle_mod, b, [a], "f64", 0.0, 0.0, False, host_threads()).reshape(1, -1)
+    assert record_tuple(cpu[0, 0])[:3] == (0, 2, 0)
+    assert float(cpu[0, 0]["max_abs_err"]) == 3.0 and float(cpu[0, 0]["max_rel_err"]) == 1.0
+    gpu = _dense_gpu(b, [a], "f64", 0.0, 0.0, False)
+    _assert_same(gpu, cpu, f"underflowing margin in binary64, second element at {second}")
 
 
 @pytest.mark.parametrize("align", [1, 16])
