@@ -11,6 +11,8 @@ from .oracle import (  # noqa: F401
     build,
     check_segment,
     report_segment,
+    ulp_histogram_segment,
+    ULP_BINS,
     check_dense,
     check_ragged,
     decode_f16,

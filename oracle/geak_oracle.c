@@ -47,6 +47,8 @@
  *
  *   mismatch report (oracle_report_segment, below): the first M elements that are not close,
  *         with index, a, b, d and tol as the rule computed them
+ *   ulp histogram (oracle_ulp_histogram_segment, below): per pair, how many elements lie how many
+ *         steps of the storage format apart (rules U1-U4 there)
  *
  * Pins (tests/test_oracle_pins.py, tests/golden/): hand-derived records for
  * boundary, NaN, Inf, signed-zero, subnormal and integer cases; an exact
@@ -395,6 +397,82 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
     _mm_setcsr(csr_saved);
 #endif
     return (int64_t)written;
+}
+
+/*
+ * Histogram of unit-in-the-last-place distances for one (segment, candidate) pair: the second half
+ * of the numeric error trace (GEAK sections 4.1 / 4.2: the Reflector analyses why the functionality
+ * test failed).  It separates rounding-level deviations (a few steps of the format) from structural
+ * ones (wrong values).  The paper does not define it; the reading:
+ *
+ *   U1  floating dtypes: the distance of a and b is the number of steps between them on the ladder
+ *       of the values of the tensor's OWN storage format (binary16, bfloat16, binary32, binary64),
+ *       ordered by value, -0 and +0 being one rung, +-Inf the rung after the largest finite value.
+ *       For values of one sign that is the difference of the magnitudes' bit patterns, for values of
+ *       opposite sign their sum (both exact in 64 bits unsigned).
+ *   U2  integer dtypes: the distance is |a - b|, exact (at most 2^64 - 1).
+ *   U3  bins: 0 holds distance 0; bin j, 1 <= j <= 64, holds 2^(j-1) <= distance < 2^j;
+ *       bin 65 holds every element where a or b is NaN (equal_nan plays no part).
+ *   U4  out[66] counts all elements of the segment: the bins sum to numel.
+ * Returns 0, or -1 on a bad argument.
+ */
+#define ORACLE_ULP_BINS 66
+
+static int bit_length_u64(uint64_t x)
+{
+    int n = 0;
+    while (x) { ++n; x >>= 1; }
+    return n;
+}
+
+int oracle_ulp_histogram_segment(const void *ref, const void *cand, uint64_t numel, int dtype,
+                                 uint64_t *out)
+{
+    if (!out || dtype < 0 || dtype > 7)
+        return -1;
+    for (int j = 0; j < ORACLE_ULP_BINS; ++j) out[j] = 0;
+    for (uint64_t i = 0; i < numel; ++i) {
+        uint64_t distance;
+        if (dtype == ORACLE_I32 || dtype == ORACLE_U8 || dtype == ORACLE_I8 || dtype == ORACLE_I64) {
+            int64_t a, b;                                        /* U2 */
+            if (dtype == ORACLE_I32) {
+                a = ((const int32_t *)cand)[i];  b = ((const int32_t *)ref)[i];
+            } else if (dtype == ORACLE_U8) {
+                a = ((const uint8_t *)cand)[i];  b = ((const uint8_t *)ref)[i];
+            } else if (dtype == ORACLE_I8) {
+                a = ((const int8_t *)cand)[i];   b = ((const int8_t *)ref)[i];
+            } else {
+                a = ((const int64_t *)cand)[i];  b = ((const int64_t *)ref)[i];
+            }
+            distance = (a >= b) ? ((uint64_t)a - (uint64_t)b) : ((uint64_t)b - (uint64_t)a);
+        } else {
+            /* sign, magnitude pattern and NaN test in the format's own fields (U1) */
+            uint64_t pa, pb, sign_bit, inf_pattern;
+            if (dtype == ORACLE_F64) {
+                pa = ((const uint64_t *)cand)[i];  pb = ((const uint64_t *)ref)[i];
+                sign_bit = 1ull << 63;  inf_pattern = 0x7FF0000000000000ull;
+            } else if (dtype == ORACLE_F32) {
+                pa = ((const uint32_t *)cand)[i];  pb = ((const uint32_t *)ref)[i];
+                sign_bit = 1ull << 31;  inf_pattern = 0x7F800000ull;
+            } else {
+                pa = ((const uint16_t *)cand)[i];  pb = ((const uint16_t *)ref)[i];
+                sign_bit = 1ull << 15;
+                inf_pattern = (dtype == ORACLE_F16) ? 0x7C00ull : 0x7F80ull;
+            }
+            uint64_t ma = pa & (sign_bit - 1), mb = pb & (sign_bit - 1);
+            if (ma > inf_pattern || mb > inf_pattern) {          /* U3: NaN */
+                out[65] += 1;
+                continue;
+            }
+            int neg_a = (pa & sign_bit) != 0, neg_b = (pb & sign_bit) != 0;
+            if (neg_a == neg_b)
+                distance = (ma >= mb) ? (ma - mb) : (mb - ma);
+            else
+                distance = ma + mb;                              /* across zero; +-0 add nothing */
+        }
+        out[bit_length_u64(distance)] += 1;                      /* U3 */
+    }
+    return 0;
 }
 
 /* Decoders exported so the pins can check them on all 65536 bit patterns. */

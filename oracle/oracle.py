@@ -67,6 +67,10 @@ def _load():
                 ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int,
                 ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_uint64, ctypes.c_void_p,
             ]
+            lib.oracle_ulp_histogram_segment.restype = ctypes.c_int
+            lib.oracle_ulp_histogram_segment.argtypes = [
+                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p,
+            ]
             lib.oracle_decode_f16.restype = ctypes.c_float
             lib.oracle_decode_f16.argtypes = [ctypes.c_uint16]
             lib.oracle_decode_bf16.restype = ctypes.c_float
@@ -131,6 +135,28 @@ def report_segment(ref, cand, numel: int, dtype: str, atol: float, rtol: float, 
     if n < 0:
         raise RuntimeError("oracle_report_segment failed")
     return out[:n].copy()
+
+
+ULP_BINS = 66
+
+
+def ulp_histogram_segment(ref, cand, numel: int, dtype: str, ref_byte_offset: int = 0,
+                          cand_byte_offset: int | None = None) -> np.ndarray:
+    """Counts of the elements of one (segment, candidate) pair by ulp distance (rules U1-U4 of
+    geak_oracle.c): uint64 array of ULP_BINS entries."""
+    lib = _load()
+    if cand_byte_offset is None:
+        cand_byte_offset = ref_byte_offset
+    rb, cb = _as_bytes(ref), _as_bytes(cand)
+    need = numel * ELEM_SIZE[dtype]
+    if ref_byte_offset + need > rb.size or cand_byte_offset + need > cb.size:
+        raise ValueError("segment exceeds buffer")
+    out = np.zeros(ULP_BINS, dtype=np.uint64)
+    rc = lib.oracle_ulp_histogram_segment(rb.ctypes.data + ref_byte_offset, cb.ctypes.data + cand_byte_offset,
+                                          numel, DTYPE_CODES[dtype], out.ctypes.data)
+    if rc != 0:
+        raise RuntimeError("oracle_ulp_histogram_segment failed")
+    return out
 
 
 def _run_pairs(jobs, threads: int):
