@@ -243,6 +243,39 @@ geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const 
                               void *workspace_dev, const geak_result *results_dev, uint32_t max_records,
                               geak_mismatch *records_dev, uint32_t *counts_dev, void *hip_stream);
 
+/* ---- ulp-distance histogram ------------------------------------------------------------------------
+ * The other half of the numeric error trace for the Reflector (sections 4.1 and 4.2): whether a
+ * failing candidate is off by rounding or by wrong values.  The paper does not define it; this
+ * library counts, per (segment, candidate), ALL elements of the pair by their distance in units in
+ * the last place of the tensor's own storage format:
+ *     floating dtypes  distance = number of steps between a and b on the ladder of the format's
+ *                      values ordered by value, -0 and +0 being one rung and +-Inf the rung after
+ *                      the largest finite value
+ *     integer dtypes   distance = |a - b|, exact
+ *     bin 0            distance 0
+ *     bin j, 1..64     2^(j-1) <= distance < 2^j
+ *     bin 65           a or b is NaN (equal_nan plays no part)
+ * The bins of a pair sum to the segment's numel.  A full pass over the reference and every
+ * candidate; candidates are counted in passes of as many as fit the per-wave rows in LDS (the
+ * reference is read once per pass). */
+#define GEAK_ULP_BINS 66
+
+/* Bytes of device scratch the histogram needs (its own, not the workspace of geak_check_run);
+ * 0 for a null plan. */
+uint64_t geak_check_ulp_workspace_bytes(const geak_plan *plan);
+
+/*
+ * Enqueue the histogram on `hip_stream`.  Independent of geak_check_run (no results are needed).
+ *   ref_dev, cand_dev   as for geak_check_run
+ *   ulp_workspace_dev   device scratch of geak_check_ulp_workspace_bytes() bytes, 16-byte aligned;
+ *                       contents need not be preserved or cleared
+ *   hist_dev            device array of geak_check_result_count() x GEAK_ULP_BINS 64-bit counts,
+ *                       row-major [segment][candidate][bin], 8-byte aligned; every entry is written
+ * Returns GEAK_OK or an error code; asynchronous, never allocates.
+ */
+geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                                     void *ulp_workspace_dev, uint64_t *hist_dev, void *hip_stream);
+
 /* ---- read probe (measurement aid, not part of the check) -------------------------------------
  * Enqueues a kernel that only reads, with 16-byte loads, the same bytes a run of this plan reads
  * (the span of the packed reference and of every candidate that the segments cover) and computes

@@ -23,6 +23,7 @@ GEAK_EINVAL, GEAK_EDTYPE, GEAK_EALIGN, GEAK_EBOUNDS, GEAK_ENOMEM, GEAK_EWORKSPAC
 GEAK_F32, GEAK_F16, GEAK_BF16, GEAK_I32, GEAK_I64, GEAK_U8, GEAK_I8, GEAK_F64 = 0, 1, 2, 3, 4, 5, 6, 7
 GEAK_MAX_CANDIDATES = 256
 GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED = 1, 2, 4, 8
+GEAK_ULP_BINS = 66
 
 DTYPE_CODE = {"f32": GEAK_F32, "f16": GEAK_F16, "bf16": GEAK_BF16, "i32": GEAK_I32, "i64": GEAK_I64,
               "u8": GEAK_U8, "i8": GEAK_I8, "f64": GEAK_F64}
@@ -99,6 +100,10 @@ def library() -> ctypes.CDLL:
         lib.geak_check_plan_items.argtypes = [vp, vp, u64]
         lib.geak_check_report.restype = ctypes.c_int
         lib.geak_check_report.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, ctypes.c_uint32, vp, vp, vp]
+        lib.geak_check_ulp_workspace_bytes.restype = u64
+        lib.geak_check_ulp_workspace_bytes.argtypes = [vp]
+        lib.geak_check_ulp_histogram.restype = ctypes.c_int
+        lib.geak_check_ulp_histogram.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, vp]
         lib.geak_check_read_probe.restype = ctypes.c_int
         lib.geak_check_read_probe.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp]
         lib.geak_check_profile_enable.restype = ctypes.c_int
@@ -111,7 +116,8 @@ def library() -> ctypes.CDLL:
 
 EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
-            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report"]
+            "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
+            "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram"]
 
 
 # ---- one Python function per C entry point -------------------------------------------------------
@@ -179,6 +185,16 @@ def geak_check_report(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_pt
     arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
     return int(library().geak_check_report(plan, ref_ptr, arr, workspace_ptr, results_ptr, max_records,
                                            records_ptr, counts_ptr, stream))
+
+
+def geak_check_ulp_workspace_bytes(plan) -> int:
+    return int(library().geak_check_ulp_workspace_bytes(plan))
+
+
+def geak_check_ulp_histogram(plan, ref_ptr: int, cand_ptrs: Sequence[int], ulp_workspace_ptr: int, hist_ptr: int, stream: int) -> int:
+    """Enqueue the ulp-distance histogram; all pointers are device addresses."""
+    arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
+    return int(library().geak_check_ulp_histogram(plan, ref_ptr, arr, ulp_workspace_ptr, hist_ptr, stream))
 
 
 def geak_check_read_probe(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: int, stream: int) -> int:
@@ -287,6 +303,29 @@ class Checker:
         rec = records.cpu().numpy()[:pairs * max_records * MISMATCH_DTYPE.itemsize].view(MISMATCH_DTYPE)
         return (rec.reshape(-1, self.num_candidates, max_records),
                 counts.cpu().numpy()[:pairs].astype(np.int64).reshape(-1, self.num_candidates))
+
+    def ulp_histogram_enqueue(self, ref, cands):
+        """Enqueue the ulp-distance histogram on torch's current stream; returns the device tensor
+        (segments * candidates * GEAK_ULP_BINS int64 counts) that it fills.  Asynchronous."""
+        import torch
+        if getattr(self, "ulp_workspace", None) is None:
+            dev = self.results.device
+            self.ulp_workspace = torch.empty(max(16, geak_check_ulp_workspace_bytes(self.plan)), dtype=torch.uint8, device=dev)
+            self.ulp_hist = torch.empty(max(1, self.n_results * GEAK_ULP_BINS), dtype=torch.int64, device=dev)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        st = geak_check_ulp_histogram(self.plan, ref.data_ptr(), [c.data_ptr() for c in cands],
+                                      self.ulp_workspace.data_ptr(), self.ulp_hist.data_ptr(), stream)
+        if st != GEAK_OK:
+            raise GeakError(st, "geak_check_ulp_histogram")
+        return self.ulp_hist
+
+    def ulp_histogram(self, ref, cands) -> np.ndarray:
+        """Counts by ulp distance, uint64 array of shape (segments, candidates, GEAK_ULP_BINS).  Synchronises."""
+        import torch
+        hist = self.ulp_histogram_enqueue(ref, cands)
+        torch.cuda.current_stream(self.device).synchronize()
+        host = hist.cpu().numpy()[:self.n_results * GEAK_ULP_BINS].view(np.uint64)
+        return host.reshape(-1, self.num_candidates, GEAK_ULP_BINS)
 
     def read_probe(self, ref, cands) -> None:
         """Enqueue the read-only probe over the same tensors on torch's current stream."""

@@ -374,6 +374,83 @@ geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const 
     return GEAK_OK;
 }
 
+static uint32_t ulp_slots(const HostPlan &hp)
+{
+    uint32_t n = 0;
+    for (const geak_segment &g : hp.segments) n = std::max(n, ulp_slots_of(g.dtype));
+    return n;
+}
+
+uint64_t geak_check_ulp_workspace_bytes(const geak_plan *plan)
+{
+    if (!plan) return 0;
+    const HostPlan &hp = plan->host;
+    return kCandTableBytes + (uint64_t)hp.slot_begin.back() * (uint64_t)hp.num_candidates * ulp_slots(hp) * sizeof(uint32_t);
+}
+
+geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                                     void *ulp_workspace_dev, uint64_t *hist_dev, void *hip_stream)
+{
+    if (!plan || !cand_dev || !hist_dev || !ulp_workspace_dev) return GEAK_EINVAL;
+    if (plan->device < 0) return GEAK_EINVAL;
+    const HostPlan &hp = plan->host;
+    const int K = hp.num_candidates;
+    const bool reads_data = !hp.items.empty();
+    if (reads_data && !ref_dev) return GEAK_EINVAL;
+    if (((uintptr_t)ref_dev & 15u) || ((uintptr_t)ulp_workspace_dev & 15u) || ((uintptr_t)hist_dev & 7u)) return GEAK_EALIGN;
+    for (int k = 0; k < K; ++k) {
+        if (reads_data && !cand_dev[k]) return GEAK_EINVAL;
+        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
+    }
+    DeviceGuard g(plan->device);
+    if (!g.ok) return GEAK_EHIP;
+
+    const uint32_t nslots = ulp_slots(hp);
+    const unsigned char **cand_table = (const unsigned char **)ulp_workspace_dev;
+    uint32_t *partials = (uint32_t *)((unsigned char *)ulp_workspace_dev + kCandTableBytes);
+    if (reads_data) {
+        InitArgs ia;
+        ia.results = nullptr;
+        ia.cand_table = cand_table;
+        ia.board = nullptr;
+        ia.num_board = 0;
+        ia.num_results = 0;
+        ia.num_candidates = (uint32_t)K;
+        ia.reserved = 0;
+        for (int k = 0; k < GEAK_MAX_CANDIDATES; ++k) ia.cand[k] = (k < K) ? (const unsigned char *)cand_dev[k] : nullptr;
+        if (launch_init(ia, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+
+        // candidates per pass: what fits the per-wave rows
+        const uint32_t per_pass = std::max<uint32_t>(1u, std::min<uint32_t>((uint32_t)K, kUlpLdsBudgetPerWave / (nslots * 4u)));
+        for (uint32_t k0 = 0; k0 < (uint32_t)K; k0 += per_pass) {
+            UlpArgs ua;
+            ua.items = plan->items_dev;
+            ua.ref = (const unsigned char *)ref_dev;
+            ua.cand_table = cand_table;
+            ua.partials = partials;
+            ua.wave_first = plan->wave_first_dev;
+            ua.num_items = (uint32_t)hp.items.size();
+            ua.num_candidates = (uint32_t)K;
+            ua.k_begin = k0;
+            ua.k_count = std::min<uint32_t>(per_pass, (uint32_t)K - k0);
+            ua.nslots = nslots;
+            ua.reserved = 0;
+            const uint32_t lds = kWavesPerBlock * ua.k_count * nslots * 4u;
+            if (launch_ulp_histogram(ua, hp.grid_blocks, lds, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+        }
+    }
+    UlpReduceArgs ra;
+    ra.slot_begin = plan->slot_begin_dev;
+    ra.partials = partials;
+    ra.hist = (unsigned long long *)hist_dev;
+    ra.num_segments = (uint32_t)hp.segments.size();
+    ra.num_candidates = (uint32_t)K;
+    ra.nslots = nslots;
+    ra.reserved = 0;
+    if (launch_ulp_reduce(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+    return GEAK_OK;
+}
+
 geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
                                   void *workspace_dev, void *hip_stream)
 {

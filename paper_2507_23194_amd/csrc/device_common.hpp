@@ -1,0 +1,164 @@
+// Device-side helpers shared by the kernel files: vector and address-space types, scalar reads of
+// the plan's tables, per-dtype vector geometry, and the guarded 16-byte loads.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "geak_internal.hpp"
+
+namespace geak {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+
+constexpr float kInfF = __builtin_huge_valf();
+constexpr double kInfD = __builtin_huge_val();
+
+// Explicit address spaces.  Tables that are written before the kernel starts and never during it
+// (work items, candidate base pointers) are read through the constant address space, so that a
+// wave-uniform index turns into a scalar load instead of a vector load the wave has to wait for;
+// tensor data is read through the global address space (no flat instructions).
+#define GEAK_AS_GLOBAL   __attribute__((address_space(1)))
+#define GEAK_AS_CONSTANT __attribute__((address_space(4)))
+#define GEAK_AS_LDS      __attribute__((address_space(3)))
+typedef const GEAK_AS_GLOBAL u32x4 *global_vec_ptr;
+
+// A work item read with scalar loads (four 64-bit words; layout of geak_item).
+__device__ __forceinline__ geak_item load_work_item(const geak_item *items, uint32_t j)
+{
+    static_assert(sizeof(geak_item) == 32, "geak_item is four 64-bit words");
+    const GEAK_AS_CONSTANT unsigned long long *w = (const GEAK_AS_CONSTANT unsigned long long *)(items + j);
+    const unsigned long long w2 = w[2], w3 = w[3];
+    geak_item it;
+    it.byte_offset = w[0];
+    it.elem_start = w[1];
+    it.segment = (uint32_t)w2;
+    it.slot = (uint32_t)(w2 >> 32);
+    it.numel = (uint16_t)w3;
+    it.dtype = (uint8_t)(w3 >> 16);
+    it.flags = (uint8_t)(w3 >> 24);
+    it.next = (uint32_t)(w3 >> 32);
+    return it;
+}
+
+__device__ __forceinline__ const unsigned char *table_entry(const unsigned char *const *table, uint32_t k)
+{
+    const GEAK_AS_CONSTANT unsigned long long *t = (const GEAK_AS_CONSTANT unsigned long long *)table;
+    return reinterpret_cast<const unsigned char *>(t[k]);
+}
+
+// A segment's tolerances, read with scalar loads when the segment index is wave-uniform.
+__device__ __forceinline__ SegTol load_tol(const SegTol *table, uint32_t segment)
+{
+    const GEAK_AS_CONSTANT unsigned long long *t = (const GEAK_AS_CONSTANT unsigned long long *)(table + segment);
+    const unsigned long long w = t[0];
+    SegTol out;
+    out.atol_f = __builtin_bit_cast(float, (uint32_t)w);
+    out.rtol_f = __builtin_bit_cast(float, (uint32_t)(w >> 32));
+    out.atol = __builtin_bit_cast(double, t[1]);
+    out.rtol = __builtin_bit_cast(double, t[2]);
+    return out;
+}
+
+template <int DT> struct Traits;
+template <> struct Traits<GEAK_F32>  { static constexpr int E = 4, W = 4; };
+template <> struct Traits<GEAK_F16>  { static constexpr int E = 8, W = 2; };
+template <> struct Traits<GEAK_BF16> { static constexpr int E = 8, W = 2; };
+template <> struct Traits<GEAK_I32>  { static constexpr int E = 4, W = 4; };
+template <> struct Traits<GEAK_I64>  { static constexpr int E = 2, W = 8; };
+template <> struct Traits<GEAK_U8>   { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_I8>   { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_F64>  { static constexpr int E = 2, W = 8; };
+
+__device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ double bits_d(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(double, (u64)lo | ((u64)hi << 32)); }
+__device__ __forceinline__ uint32_t f_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// Element e (0 .. E-1) of a 16-byte vector, decoded exactly to binary32.
+template <int DT>
+__device__ __forceinline__ float decode(const u32x4 &q, int e)
+{
+    if constexpr (DT == GEAK_F32) {
+        return bits_f(q[e]);
+    } else if constexpr (DT == GEAK_F16) {
+        const uint32_t word = q[e >> 1];
+        const uint16_t h = (e & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xFFFFu);
+        return (float)__builtin_bit_cast(_Float16, h);
+    } else {  // bf16: upper half of a binary32
+        const uint32_t word = q[e >> 1];
+        return bits_f((e & 1) ? (word & 0xFFFF0000u) : (word << 16));
+    }
+}
+
+__device__ __forceinline__ int decode_i32(const u32x4 &q, int e) { return (int)q[e]; }
+
+// ---- loads -------------------------------------------------------------------------------------
+// Full item: 4 coalesced 16-byte loads per lane; vector v of lane L covers bytes (v*64 + L)*16.
+__device__ __forceinline__ void load_full(u32x4 (&dst)[kVecPerLane], const unsigned char *base, int lane)
+{
+    global_vec_ptr p = (global_vec_ptr)base + lane;
+#pragma unroll
+    for (int v = 0; v < kVecPerLane; ++v)
+        dst[v] = __builtin_nontemporal_load(p + v * kWaveSize);
+}
+
+// Vector V of lane L of an item that starts 16-byte aligned but may be shorter than a full item
+// (a segment's tail): whole vectors inside the item are loaded as such, the one vector that
+// straddles the end element by element, and everything past the end reads as 0 -- in the reference
+// and in every candidate alike, so that those positions compare as close and add nothing to either
+// maximum.  Nothing outside the item's bytes is touched.
+template <int DT>
+__device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, int v, uint32_t n, bool full)
+{
+    constexpr uint32_t E = Traits<DT>::E;
+    global_vec_ptr p = (global_vec_ptr)base + (v * kWaveSize + lane);
+    if (full) return __builtin_nontemporal_load(p);
+    const uint32_t first = (uint32_t)(v * kWaveSize + lane) * E;
+    u32x4 q = {0u, 0u, 0u, 0u};
+    if (first + E <= n) {
+        q = __builtin_nontemporal_load(p);
+    } else if (first < n) {
+        if constexpr (Traits<DT>::W == 1) {
+            const GEAK_AS_GLOBAL unsigned char *c = (const GEAK_AS_GLOBAL unsigned char *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (first + e < n) q[e >> 2] |= (uint32_t)c[e] << ((e & 3) * 8);
+        } else if constexpr (Traits<DT>::W == 8) {
+            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (first + e < n) { q[2 * e] = w[2 * e]; q[2 * e + 1] = w[2 * e + 1]; }
+        } else if constexpr (Traits<DT>::W == 4) {
+            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (first + e < n) q[e] = w[e];
+        } else {
+            const GEAK_AS_GLOBAL uint16_t *h = (const GEAK_AS_GLOBAL uint16_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (first + e < n) q[e >> 1] |= (uint32_t)h[e] << ((e & 1) * 16);
+        }
+    }
+    return q;
+}
+
+// One element straight from memory, decoded exactly to binary32 (floating dtypes).
+__device__ __forceinline__ float load_elem_f(const unsigned char *base, u64 idx, int dtype)
+{
+    if (dtype == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
+    const uint16_t h = reinterpret_cast<const uint16_t *>(base)[idx];
+    if (dtype == GEAK_F16) return (float)__builtin_bit_cast(_Float16, h);
+    return bits_f((uint32_t)h << 16);
+}
+
+// One integer element straight from memory, widened exactly to 64 bits.
+__device__ __forceinline__ long long load_elem_int(const unsigned char *base, u64 idx, int dtype)
+{
+    if (dtype == GEAK_I32) return reinterpret_cast<const int *>(base)[idx];
+    if (dtype == GEAK_I64) return reinterpret_cast<const long long *>(base)[idx];
+    if (dtype == GEAK_U8) return base[idx];
+    return reinterpret_cast<const signed char *>(base)[idx];
+}
+
+}  // namespace
+}  // namespace geak

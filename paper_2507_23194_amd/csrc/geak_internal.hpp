@@ -154,6 +154,48 @@ struct ReportArgs {
     int equal_nan;
 };
 
+// ---- ulp-distance histogram ------------------------------------------------------------------------
+// Slots of a histogram row for one dtype: the bins its distances can reach (0 .. bit length of the
+// largest distance) plus one for NaN.  A plan uses the largest over its segments.
+inline uint32_t ulp_slots_of(int dtype)
+{
+    switch (dtype) {
+    case GEAK_F16: case GEAK_BF16: return 18;            // distances below 2^16
+    case GEAK_U8: case GEAK_I8: return 10;               // at most 255
+    case GEAK_F64: case GEAK_I64: return 66;             // below 2^64
+    default: return 34;                                  // binary32, int32: below 2^32
+    }
+}
+constexpr uint32_t kUlpLdsBudgetPerWave = 10u << 10;     // rows of one pass: candidates x slots x 4 bytes
+
+// Workspace of the histogram: [candidate pointer table, kCandTableBytes][partial rows: slots x K x nslots, 32-bit].
+struct UlpArgs {
+    const geak_item *items;
+    const unsigned char *ref;
+    const unsigned char *const *cand_table;
+    uint32_t *partials;
+    const uint32_t *wave_first;
+    uint32_t num_items;
+    uint32_t num_candidates;
+    uint32_t k_begin;                    // candidates [k_begin, k_begin + k_count) are counted by this pass
+    uint32_t k_count;
+    uint32_t nslots;
+    uint32_t reserved;
+};
+
+struct UlpReduceArgs {
+    const uint32_t *slot_begin;
+    const uint32_t *partials;
+    unsigned long long *hist;            // [segment][candidate][GEAK_ULP_BINS]
+    uint32_t num_segments;
+    uint32_t num_candidates;
+    uint32_t nslots;
+    uint32_t reserved;
+};
+
+int launch_ulp_histogram(const UlpArgs &args, uint32_t grid_blocks, uint32_t lds_bytes, void *stream);   // ulp_kernels.hip
+int launch_ulp_reduce(const UlpReduceArgs &args, void *stream);
+
 // Kernel launchers (kernels.hip).  Return the hipError_t of the launch as int.
 int launch_init(const InitArgs &args, void *stream);
 int launch_compare(const CompareArgs &args, uint32_t grid_blocks, uint32_t lds_bytes, void *stream);

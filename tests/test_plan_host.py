@@ -294,3 +294,17 @@ def test_per_segment_tolerances_are_validated(lib):
     B.geak_check_destroy(plan)
     st, plan = B.geak_check_plan(segs, 2, 1e300, 0.0, 0, -1)
     assert st == B.GEAK_EINVAL and plan is None
+
+
+def test_ulp_histogram_workspace(lib):
+    """Scratch of the ulp histogram: the pointer table plus one 32-bit row per (slot, candidate),
+    as long as the widest dtype of the plan needs (18 slots for the 16-bit dtypes, 66 for the 64-bit ones)."""
+    st, plan = B.geak_check_plan_dense("f16", [1 << 20], 3, 0, 0, 0, -1)
+    info = B.geak_check_plan_info(plan)
+    assert B.geak_check_ulp_workspace_bytes(plan) == 2048 + info.num_slots * 3 * 18 * 4
+    B.geak_check_destroy(plan)
+    st, plan = _plan([(0, 100, "u8"), (128, 10, "f64")], K=2)
+    info = B.geak_check_plan_info(plan)
+    assert B.geak_check_ulp_workspace_bytes(plan) == 2048 + info.num_slots * 2 * 66 * 4
+    B.geak_check_destroy(plan)
+    assert B.geak_check_ulp_workspace_bytes(None) == 0
