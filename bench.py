@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--report", type=int, default=0, metavar="M",
                     help="also time the mismatch report (first M mismatches per pair) that follows a failed check; "
                          "reported under \"report\", not part of the step")
+    ap.add_argument("--ulp-histogram", action="store_true",
+                    help="also time the ulp-distance histogram pass (a second read of all tensors, part of the error "
+                         "trace of a failed check); reported under \"ulp_histogram\", not part of the step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain element-wise copy of a known size (2 GiB read, 2 GiB written per launch), "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -178,6 +181,24 @@ def main():
         report = {"max_records": args.report, "ms_per_call_incl_copy_back": (time.perf_counter() - t0) / reps * 1e3,
                   "pairs": int(rcnt.size), "records": int(rcnt.sum())}
 
+    ulp = None
+    if args.ulp_histogram:
+        for _ in range(3):
+            ck.ulp_histogram_enqueue(w.ref, w.cands)                # warm-up (allocates its buffers on the first call)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for a, b in ev:
+            a.record()
+            ck.ulp_histogram_enqueue(w.ref, w.cands)
+            b.record()
+        torch.cuda.synchronize()
+        ulp_ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
+        hist = ck.ulp_histogram(w.ref, w.cands)
+        numels = np.array([w.ref.numel()] if w.segments is None else [n for _, n, _ in w.segments], dtype=np.uint64)
+        assert (hist.sum(axis=2) == numels[:, None]).all()           # every element counted once per pair
+        ulp = {"ms_per_call": ulp_ms, "GBps": alg_bytes / (ulp_ms * 1e-3) / 1e9,
+               "frac_of_hbm_peak": alg_bytes / (ulp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+               "elements_within_1_ulp": float(hist[:, :, :2].sum() / max(1, hist.sum()))}
+
     rec = ck.read()
     n_fail = int((rec["pass"] == 0).sum())
     # the records must agree with what the generator planted (cheap sanity check, outside the timed region)
@@ -217,6 +238,8 @@ def main():
     }
     if report is not None:
         out["report"] = report
+    if ulp is not None:
+        out["ulp_histogram"] = ulp
     if not args.no_cpu_baseline:
         budget = {1: (8, 1 << 20), 2: (32, 1 << 26), 3: (16, 1 << 28), 4: (4, 0), 5: (8, 1 << 28)}[args.config]
         out["cpu_baseline"] = cpu_baseline(w, *budget)

@@ -96,43 +96,89 @@ __device__ __forceinline__ GEAK_AS_LDS uint32_t *ulp_row(const UlpState &st, uin
     return (GEAK_AS_LDS uint32_t *)(st.rows_off + kk * st.nslots * 4u);
 }
 
-// Counters of one (item, candidate): cumulative classes in scalar registers.
+// Counters of one (item, candidate): cumulative classes (distance < 1, < 2, < 4, < 8) in scalar registers.
 struct UlpCounts {
-    uint32_t lt1, lt2, lt4, lt8, nan;
+    uint32_t lt1, lt2, lt4, lt8;
 };
 
-// One element position of all 64 lanes.
-template <int DT>
-__device__ __forceinline__ void ulp_element(typename UlpTraits<DT>::Ord oa, typename UlpTraits<DT>::Ord ob, bool ref_may_be_nan,
-                                            UlpCounts &c, GEAK_AS_LDS uint32_t *row, int lane)
+// Floating elements where a or b is NaN carry the distance "all ones", a value no pair of numbers
+// reaches (the largest distance, -Inf to +Inf, is twice the pattern of Inf).  Such lanes fall
+// through the four classes like any far lane and are sorted out where the LDS row is addressed.
+template <typename D, bool FLOATING>
+__device__ __forceinline__ uint32_t ulp_slot(D d, uint32_t nslots)
 {
-    typedef typename UlpTraits<DT>::Dist D;
-    const D d = ulp_dist<DT>(oa, ob);
-    u64 m1 = __builtin_amdgcn_ballot_w64(d < (D)1), m2 = __builtin_amdgcn_ballot_w64(d < (D)2);
-    u64 m4 = __builtin_amdgcn_ballot_w64(d < (D)4), m8 = __builtin_amdgcn_ballot_w64(d < (D)8);
-    u64 mn = 0;
-    if constexpr (kUlpFloating<DT>) {
-        mn = __builtin_amdgcn_ballot_w64(ulp_is_nan<DT>(oa));
-        if (ref_may_be_nan) mn |= __builtin_amdgcn_ballot_w64(ulp_is_nan<DT>(ob));
-        if (mn) {
-            m1 &= ~mn; m2 &= ~mn; m4 &= ~mn; m8 &= ~mn;
-            c.nan += (uint32_t)__builtin_popcountll(mn);
-        }
-    }
-    c.lt1 += (uint32_t)__builtin_popcountll(m1);
-    c.lt2 += (uint32_t)__builtin_popcountll(m2);
-    c.lt4 += (uint32_t)__builtin_popcountll(m4);
+    if (FLOATING && d == (D)~(D)0) return nslots - 1;
+    // only lanes 8 or more steps away come here: d is not 0
+    if constexpr (sizeof(D) == 8) return 64u - (uint32_t)__builtin_clzll((u64)d);
+    else return 32u - (uint32_t)__builtin_clz((uint32_t)d);
+}
+
+// One element position of all 64 lanes: the four classes by lane mask, lanes beyond them straight
+// into the LDS row (one atomic add per lane; equal addresses are serialised by the LDS).
+template <typename D, bool FLOATING>
+__device__ __forceinline__ void ulp_classify(D d, UlpCounts &c, GEAK_AS_LDS uint32_t *row, uint32_t nslots)
+{
+    const bool near = d < (D)8;
+    const u64 m8 = __builtin_amdgcn_ballot_w64(near);
+    c.lt1 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d < (D)1));
+    c.lt2 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d < (D)2));
+    c.lt4 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d < (D)4));
     c.lt8 += (uint32_t)__builtin_popcountll(m8);
-    const u64 rest = ~(m8 | mn);
-    if (rest) {                                             // distance >= 8: straight into the LDS row
-        if ((rest >> lane) & 1ull)
-            (void)__hip_atomic_fetch_add(row + bit_length(d), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (~m8) {
+        if (!near) (void)__hip_atomic_fetch_add(row + ulp_slot<D, FLOATING>(d, nslots), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
+    // one element's lane masks at a time: the counters are a running chain in four scalar registers
+    asm volatile("" : "+s"(c.lt1), "+s"(c.lt2), "+s"(c.lt4), "+s"(c.lt8));
+}
+
+// ---- 16-bit floating dtypes: both halves of a word at once, with packed 16-bit integer arithmetic ----
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
+__device__ __forceinline__ s16x2 as_s16x2(uint32_t w) { return __builtin_bit_cast(s16x2, w); }
+__device__ __forceinline__ uint32_t as_word(u16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ uint32_t as_word(s16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+
+// ord of both halves (as two's-complement 16-bit integers: the magnitudes are below 2^15)
+__device__ __forceinline__ uint32_t ulp_ord_pair(uint32_t w)
+{
+    const uint32_t mag = w & 0x7FFF7FFFu;
+    const uint32_t sign = as_word(as_s16x2(w) >> (short)15);              // all ones in a negative half
+    return as_word(as_u16x2(mag ^ sign) - as_u16x2(sign));               // negated there
+}
+// all ones in every half that holds a NaN: magnitude above the pattern of Inf
+template <int DT>
+__device__ __forceinline__ uint32_t ulp_nan_mark_pair(uint32_t w)
+{
+    constexpr uint32_t kUp = 0x7FFFu - (DT == GEAK_F16 ? 0x7C00u : 0x7F80u);   // lifts exactly the NaN magnitudes to bit 15
+    const uint32_t lifted = (w & 0x7FFF7FFFu) + kUp * 0x00010001u;           // no carry between the halves
+    return as_word(as_s16x2(lifted) >> (short)15);
+}
+// distances of both halves: max - min of the ord values; the difference is below 2^16, so the
+// wrapping 16-bit subtraction is exact
+__device__ __forceinline__ uint32_t ulp_dist_pair(uint32_t oa2, uint32_t ob2)
+{
+    const s16x2 a = as_s16x2(oa2), b = as_s16x2(ob2);
+    const s16x2 hi = __builtin_elementwise_max(a, b), lo = __builtin_elementwise_min(a, b);
+    return as_word(as_u16x2(as_word(hi)) - as_u16x2(as_word(lo)));
+}
+
+// ---- the other dtypes: element by element ------------------------------------------------------------
+// all ones if the ord value is that of a NaN
+template <int DT>
+__device__ __forceinline__ typename UlpTraits<DT>::Dist ulp_nan_mark(typename UlpTraits<DT>::Ord o)
+{
+    typedef typename UlpTraits<DT>::Ord Ord;
+    typedef typename UlpTraits<DT>::Dist D;
+    const Ord mag = o < 0 ? -o : o;
+    // magnitudes above the pattern of Inf reach the sign bit when lifted by (largest magnitude - Inf)
+    const D lifted = (D)mag + ((D)(~(D)0 >> 1) - (D)ulp_inf<DT>());
+    return (D)((Ord)lifted >> (sizeof(Ord) * 8 - 1));
 }
 
 // the scalar counters of one (item, candidate) go into the row; `pad` absent elements of a tail
 // were read as 0 on both sides and counted as distance 0
-__device__ __forceinline__ void ulp_commit(const UlpCounts &c, uint32_t pad, GEAK_AS_LDS uint32_t *row, uint32_t nslots, int lane)
+__device__ __forceinline__ void ulp_commit(const UlpCounts &c, uint32_t pad, GEAK_AS_LDS uint32_t *row, int lane)
 {
     if (lane == 0) {
         const uint32_t b0 = c.lt1 - pad, b1 = c.lt2 - c.lt1, b2 = c.lt4 - c.lt2, b3 = c.lt8 - c.lt4;
@@ -140,7 +186,6 @@ __device__ __forceinline__ void ulp_commit(const UlpCounts &c, uint32_t pad, GEA
         if (b1) (void)__hip_atomic_fetch_add(row + 1, b1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (b2) (void)__hip_atomic_fetch_add(row + 2, b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (b3) (void)__hip_atomic_fetch_add(row + 3, b3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (c.nan) (void)__hip_atomic_fetch_add(row + (nslots - 1), c.nan, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 }
 
@@ -176,15 +221,186 @@ __device__ __forceinline__ T *uniform_ptr(T *p)
     return reinterpret_cast<T *>(lo | (hi << 32));
 }
 
-// A run of consecutive vector-loadable items of one dtype in the wave's list (FULL items: the whole
-// run; a tail: that one item).  Returns the index of the wave's first item it did not process.
-template <int DT>
+// The staged reference slice of one item and the comparison of one candidate vector against it.
+template <int DT> struct UlpRef {
+    typedef typename UlpTraits<DT>::Ord Ord;
+    typedef typename UlpTraits<DT>::Dist D;
+    static constexpr int E = Traits<DT>::E;
+    typedef UlpCounts Counts;
+    Ord ob[kVecPerLane * E];
+    uint32_t nan_vectors;                                    // bit v: some lane's reference vector v holds a NaN
+    static __device__ __forceinline__ Counts zero() { return Counts{0u, 0u, 0u, 0u}; }
+    static __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane)
+    {
+        ulp_commit(c, (uint32_t)(kWaveSize * kVecPerLane * E) - elements, row, lane);
+    }
+
+    template <int V> __device__ __forceinline__ void stage(const u32x4 &q)
+    {
+        if constexpr (V == 0) nan_vectors = 0;
+        bool any_nan = false;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const Ord o = ulp_ord<DT>(q, e);
+            ob[V * E + e] = o;
+            if constexpr (kUlpFloating<DT>) any_nan |= ulp_is_nan<DT>(o);
+        }
+        if constexpr (kUlpFloating<DT>)
+            if (__builtin_amdgcn_ballot_w64(any_nan)) nan_vectors |= 1u << V;
+    }
+    template <int V> __device__ __forceinline__ void compare(const u32x4 &q, UlpCounts &c, GEAK_AS_LDS uint32_t *row, uint32_t nslots) const
+    {
+        const bool ref_nan = kUlpFloating<DT> && ((nan_vectors >> V) & 1u);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const Ord oa = ulp_ord<DT>(q, e);
+            D d = ulp_dist<DT>(oa, ob[V * E + e]);
+            if constexpr (kUlpFloating<DT>) {
+                d |= ulp_nan_mark<DT>(oa);
+                if (ref_nan) d |= ulp_nan_mark<DT>(ob[V * E + e]);
+            }
+            ulp_classify<D, kUlpFloating<DT>>(d, c, row, nslots);
+        }
+    }
+};
+
+// 16-bit floating dtypes: packed ord values, one register per two elements.  The classes are not
+// counted with lane masks (two scalar instructions per class and element, and the scalar unit
+// issues no faster than the vector unit) but per lane, with packed 16-bit arithmetic on both halves
+// at once: min(d >> s, 1) is 1 exactly where d >= 2^s, and four packed accumulators sum these.  They
+// are added up over the wave once per candidate slice.
+struct UlpLaneCounts {
+    uint32_t ge1, ge2, ge4, ge8;          // per half: elements of this lane with distance >= 1, 2, 4, 8
+};
+// Sum over the wave, wave-uniform result: four data-parallel-primitive steps inside each row of 16
+// lanes (neighbour, other pair, other quad mirrored, other half mirrored), then one lane of each row.
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
+{
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);     // quad_perm [1,0,3,2]
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false);     // quad_perm [2,3,0,1]
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, false);    // row_half_mirror
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, false);    // row_mirror
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 0) + (uint32_t)__builtin_amdgcn_readlane((int)x, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)x, 32) + (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+}
+
+template <int DT> struct UlpRef16 {
+    typedef UlpLaneCounts Counts;
+    uint32_t ob2[kVecPerLane * 4];
+    uint32_t nan_vectors;
+
+    static __device__ __forceinline__ Counts zero() { return Counts{0u, 0u, 0u, 0u}; }
+
+    template <int V> __device__ __forceinline__ void stage(const u32x4 &q)
+    {
+        if constexpr (V == 0) nan_vectors = 0;
+        uint32_t marks = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            ob2[V * 4 + w] = ulp_ord_pair(q[w]);
+            marks |= ulp_nan_mark_pair<DT>(q[w]);
+        }
+        if (__builtin_amdgcn_ballot_w64(marks != 0)) nan_vectors |= 1u << V;
+    }
+    template <int V> __device__ __forceinline__ void compare(const u32x4 &q, Counts &c, GEAK_AS_LDS uint32_t *row, uint32_t nslots) const
+    {
+        const bool ref_nan = (nan_vectors >> V) & 1u;
+        constexpr uint32_t kOnes = 0x00010001u;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            uint32_t d2 = ulp_dist_pair(ulp_ord_pair(q[w]), ob2[V * 4 + w]) | ulp_nan_mark_pair<DT>(q[w]);
+            if (ref_nan) {
+                // the magnitudes of the staged ord values, as patterns: |ord| per half
+                const s16x2 o = as_s16x2(ob2[V * 4 + w]);
+                const uint32_t mag = as_word(__builtin_elementwise_max(o, (s16x2)(-o)));
+                d2 |= ulp_nan_mark_pair<DT>(mag);
+            }
+            // ge_s += min(d >> s, 1) for s = 0 .. 3 on both halves; the last indicator is kept.  Packed 16-bit
+            // instructions write whole registers, so the sequence needs no wait states between its steps.
+            uint32_t far2;
+            asm("v_pk_min_u16 %4, %5, %6\n\t"
+                "v_pk_add_u16 %0, %0, %4\n\t"
+                "v_pk_lshrrev_b16 %4, 1, %5 op_sel_hi:[0,1]\n\t"
+                "v_pk_min_u16 %4, %4, %6\n\t"
+                "v_pk_add_u16 %1, %1, %4\n\t"
+                "v_pk_lshrrev_b16 %4, 2, %5 op_sel_hi:[0,1]\n\t"
+                "v_pk_min_u16 %4, %4, %6\n\t"
+                "v_pk_add_u16 %2, %2, %4\n\t"
+                "v_pk_lshrrev_b16 %4, 3, %5 op_sel_hi:[0,1]\n\t"
+                "v_pk_min_u16 %4, %4, %6\n\t"
+                "v_pk_add_u16 %3, %3, %4"
+                : "+v"(c.ge1), "+v"(c.ge2), "+v"(c.ge4), "+v"(c.ge8), "=&v"(far2)
+                : "v"(d2), "v"(kOnes));
+            if (__builtin_amdgcn_ballot_w64(far2 != 0)) {      // some lane is 8 or more steps away: straight into the LDS row
+                if (far2 & 0xFFFFu)
+                    (void)__hip_atomic_fetch_add(row + ulp_slot<uint16_t, true>((uint16_t)d2, nslots), 1u, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (far2 >> 16)
+                    (void)__hip_atomic_fetch_add(row + ulp_slot<uint16_t, true>((uint16_t)(d2 >> 16), nslots), 1u, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+    }
+    // `elements` of the slice (absent ones of a tail not counted) were compared
+    static __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane)
+    {
+        const uint32_t g1 = (c.ge1 & 0xFFFFu) + (c.ge1 >> 16), g2 = (c.ge2 & 0xFFFFu) + (c.ge2 >> 16);
+        const uint32_t g4 = (c.ge4 & 0xFFFFu) + (c.ge4 >> 16), g8 = (c.ge8 & 0xFFFFu) + (c.ge8 >> 16);
+        // at most 32 per lane and class: two classes share a register through the wave sum (below 2^16 each)
+        const uint32_t s12 = wave_sum_u32(g1 | (g2 << 16)), s48 = wave_sum_u32(g4 | (g8 << 16));
+        if (lane == 0) {
+            const uint32_t n1 = s12 & 0xFFFFu, n2 = s12 >> 16, n4 = s48 & 0xFFFFu, n8 = s48 >> 16;
+            const uint32_t b0 = elements - n1, b1 = n1 - n2, b2 = n2 - n4, b3 = n4 - n8;
+            if (b0) (void)__hip_atomic_fetch_add(row + 0, b0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (b1) (void)__hip_atomic_fetch_add(row + 1, b1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (b2) (void)__hip_atomic_fetch_add(row + 2, b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (b3) (void)__hip_atomic_fetch_add(row + 3, b3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    }
+};
+
+// bytes: nothing staged but the vector itself; words that are equal in every lane are counted at once
+template <int DT> struct UlpRefBytes {
+    typedef UlpCounts Counts;
+    u32x4 raw[kVecPerLane];
+    static __device__ __forceinline__ Counts zero() { return Counts{0u, 0u, 0u, 0u}; }
+    static __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane)
+    {
+        ulp_commit(c, (uint32_t)(kWaveSize * kVecPerLane * 16) - elements, row, lane);
+    }
+    template <int V> __device__ __forceinline__ void stage(const u32x4 &q) { raw[V] = q; }
+    template <int V> __device__ __forceinline__ void compare(const u32x4 &q, UlpCounts &c, GEAK_AS_LDS uint32_t *row, uint32_t nslots) const
+    {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (__builtin_amdgcn_ballot_w64(q[w] != raw[V][w]) == 0) {
+                c.lt1 += 4 * kWaveSize; c.lt2 += 4 * kWaveSize; c.lt4 += 4 * kWaveSize; c.lt8 += 4 * kWaveSize;
+                continue;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t va = (q[w] >> (8 * e)) & 0xFFu, vb = (raw[V][w] >> (8 * e)) & 0xFFu;
+                const int a = (DT == GEAK_I8) ? (int)(signed char)va : (int)va, b = (DT == GEAK_I8) ? (int)(signed char)vb : (int)vb;
+                ulp_classify<uint32_t, false>(ulp_dist<DT>(a, b), c, row, nslots);
+            }
+        }
+    }
+};
+
+template <int DT> struct UlpRefOf { typedef UlpRef<DT> type; };
+template <> struct UlpRefOf<GEAK_F16> { typedef UlpRef16<GEAK_F16> type; };
+template <> struct UlpRefOf<GEAK_BF16> { typedef UlpRef16<GEAK_BF16> type; };
+template <> struct UlpRefOf<GEAK_U8> { typedef UlpRefBytes<GEAK_U8> type; };
+template <> struct UlpRefOf<GEAK_I8> { typedef UlpRefBytes<GEAK_I8> type; };
+
+// TAIL = false: a run of consecutive FULL items of one dtype in the wave's list, every load an
+// unguarded 16-byte load, the next item's reference slice fetched behind the last candidate.
+// TAIL = true: one aligned item shorter than 4 KiB, guarded loads.
+// Returns the index of the wave's first item it did not process.
+template <int DT, bool TAIL>
 __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_in)
 {
-    typedef typename UlpTraits<DT>::Ord Ord;
-    constexpr int E = Traits<DT>::E;
-    constexpr int N = kVecPerLane * E;
-    constexpr bool kStageOrd = (N <= 32);                    // byte dtypes decode the reference again per candidate
+    constexpr bool full = !TAIL;
     UlpState st;
     st.rows_off = uniform32(st_in.rows_off);
     st.nslots = uniform32(st_in.nslots);
@@ -199,63 +415,40 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
     uint32_t j = uniform32(in.first_item);
     geak_item it = load_work_item(items, j);
     u32x4 cur[kVecPerLane];
-    {
-        const bool full = (it.flags & GEAK_ITEM_FULL) != 0;
 #pragma unroll
-        for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, it.numel, full);
-    }
+    for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, it.numel, full);
+    typedef typename UlpRefOf<DT>::type Ref;
+    Ref ref;
     for (;;) {
-        const bool full = (it.flags & GEAK_ITEM_FULL) != 0;
-        const uint32_t pad = (uint32_t)(kWaveSize * N) - it.numel;
-        // does the wave's next item continue the run?  (only FULL items do: a tail ends it)
         const uint32_t jn = it.next;
-        bool more = full && jn < num_items;
+        bool more = !TAIL && jn < num_items;
         geak_item nx = it;
         if (more) {
             nx = load_work_item(items, jn);
-            more = nx.dtype == DT && (nx.flags & GEAK_ITEM_ALIGNED);
+            more = nx.dtype == DT && (nx.flags & GEAK_ITEM_FULL);
         }
         // stage the reference slice; its registers are refilled with the pass's first candidate
-        Ord ob[kStageOrd ? N : 1];
-        u32x4 raw[kStageOrd ? 1 : kVecPerLane];
-        u64 ref_nan = 0;                                     // bit i: some lane's reference element i is NaN
         {
             const unsigned char *first = table_entry(cand, k_begin) + it.byte_offset;
-#pragma unroll
-            for (int v = 0; v < kVecPerLane; ++v) {
-                if constexpr (kStageOrd) {
-#pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        const Ord o = ulp_ord<DT>(cur[v], e);
-                        ob[v * E + e] = o;
-                        if constexpr (kUlpFloating<DT>)
-                            if (__builtin_amdgcn_ballot_w64(ulp_is_nan<DT>(o))) ref_nan |= 1ull << (v * E + e);
-                    }
-                } else {
-                    raw[v] = cur[v];
-                }
-                cur[v] = load_vec<DT>(first, lane, v, it.numel, full);
-            }
+            ref.template stage<0>(cur[0]); cur[0] = load_vec<DT>(first, lane, 0, it.numel, full);
+            ref.template stage<1>(cur[1]); cur[1] = load_vec<DT>(first, lane, 1, it.numel, full);
+            ref.template stage<2>(cur[2]); cur[2] = load_vec<DT>(first, lane, 2, it.numel, full);
+            ref.template stage<3>(cur[3]); cur[3] = load_vec<DT>(first, lane, 3, it.numel, full);
         }
         for (uint32_t kk = 0; kk < k_count; ++kk) {
             const bool last = kk + 1 == k_count;
-            const bool has_next = !last || more;
-            const unsigned char *next = last ? ref_base + nx.byte_offset : table_entry(cand, k_begin + kk + 1) + it.byte_offset;
-            const uint32_t next_n = last ? nx.numel : it.numel;
-            const bool next_full = last ? (nx.flags & GEAK_ITEM_FULL) != 0 : full;
+            // Every step refills its registers, so that the number of loads in flight is known at each wait:
+            // behind the run's very last slice the same slice is simply read again (from the cache).
+            const unsigned char *next = !last ? table_entry(cand, k_begin + kk + 1) + it.byte_offset
+                                      : more ? ref_base + nx.byte_offset
+                                             : table_entry(cand, k_begin + kk) + it.byte_offset;
             GEAK_AS_LDS uint32_t *row = ulp_row(st, kk);
-            UlpCounts c = {0u, 0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int v = 0; v < kVecPerLane; ++v) {
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    const Ord oa = ulp_ord<DT>(cur[v], e);
-                    if constexpr (kStageOrd) ulp_element<DT>(oa, ob[v * E + e], (ref_nan >> (v * E + e)) & 1ull, c, row, lane);
-                    else ulp_element<DT>(oa, ulp_ord<DT>(raw[v], e), false, c, row, lane);
-                }
-                if (has_next) cur[v] = load_vec<DT>(next, lane, v, next_n, next_full);
-            }
-            ulp_commit(c, pad, row, st.nslots, lane);
+            typename Ref::Counts c = Ref::zero();
+            ref.template compare<0>(cur[0], c, row, st.nslots); cur[0] = load_vec<DT>(next, lane, 0, it.numel, full);
+            ref.template compare<1>(cur[1], c, row, st.nslots); cur[1] = load_vec<DT>(next, lane, 1, it.numel, full);
+            ref.template compare<2>(cur[2], c, row, st.nslots); cur[2] = load_vec<DT>(next, lane, 2, it.numel, full);
+            ref.template compare<3>(cur[3], c, row, st.nslots); cur[3] = load_vec<DT>(next, lane, 3, it.numel, full);
+            Ref::commit(c, it.numel, row, lane);
         }
         if (it.flags & GEAK_ITEM_LAST) ulp_end_run(st, partials, it.slot, K, k_begin, k_count, lane);
         if (!more) break;
@@ -337,15 +530,28 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
         if (it.flags & GEAK_ITEM_ALIGNED) {
             r.first_item = j;
             uint32_t next_j;
-            switch (it.dtype) {
-            case GEAK_F32:  next_j = ulp_run<GEAK_F32>(r, st); break;
-            case GEAK_F16:  next_j = ulp_run<GEAK_F16>(r, st); break;
-            case GEAK_BF16: next_j = ulp_run<GEAK_BF16>(r, st); break;
-            case GEAK_I32:  next_j = ulp_run<GEAK_I32>(r, st); break;
-            case GEAK_I64:  next_j = ulp_run<GEAK_I64>(r, st); break;
-            case GEAK_U8:   next_j = ulp_run<GEAK_U8>(r, st); break;
-            case GEAK_F64:  next_j = ulp_run<GEAK_F64>(r, st); break;
-            default:        next_j = ulp_run<GEAK_I8>(r, st); break;
+            if (it.flags & GEAK_ITEM_FULL) {
+                switch (it.dtype) {
+                case GEAK_F32:  next_j = ulp_run<GEAK_F32, false>(r, st); break;
+                case GEAK_F16:  next_j = ulp_run<GEAK_F16, false>(r, st); break;
+                case GEAK_BF16: next_j = ulp_run<GEAK_BF16, false>(r, st); break;
+                case GEAK_I32:  next_j = ulp_run<GEAK_I32, false>(r, st); break;
+                case GEAK_I64:  next_j = ulp_run<GEAK_I64, false>(r, st); break;
+                case GEAK_U8:   next_j = ulp_run<GEAK_U8, false>(r, st); break;
+                case GEAK_F64:  next_j = ulp_run<GEAK_F64, false>(r, st); break;
+                default:        next_j = ulp_run<GEAK_I8, false>(r, st); break;
+                }
+            } else {
+                switch (it.dtype) {
+                case GEAK_F32:  next_j = ulp_run<GEAK_F32, true>(r, st); break;
+                case GEAK_F16:  next_j = ulp_run<GEAK_F16, true>(r, st); break;
+                case GEAK_BF16: next_j = ulp_run<GEAK_BF16, true>(r, st); break;
+                case GEAK_I32:  next_j = ulp_run<GEAK_I32, true>(r, st); break;
+                case GEAK_I64:  next_j = ulp_run<GEAK_I64, true>(r, st); break;
+                case GEAK_U8:   next_j = ulp_run<GEAK_U8, true>(r, st); break;
+                case GEAK_F64:  next_j = ulp_run<GEAK_F64, true>(r, st); break;
+                default:        next_j = ulp_run<GEAK_I8, true>(r, st); break;
+                }
             }
             j = __builtin_amdgcn_readfirstlane(next_j);
             continue;
