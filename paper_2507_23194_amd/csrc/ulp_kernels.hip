@@ -125,42 +125,10 @@ __device__ __forceinline__ void ulp_classify(D d, UlpCounts &c, GEAK_AS_LDS uint
     c.lt4 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d < (D)4));
     c.lt8 += (uint32_t)__builtin_popcountll(m8);
     if (~m8) {
-        if (!near) (void)__hip_atomic_fetch_add(row + ulp_slot<D, FLOATING>(d, nslots), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (__builtin_amdgcn_inverse_ballot_w64(~m8)) (void)__hip_atomic_fetch_add(row + ulp_slot<D, FLOATING>(d, nslots), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     // one element's lane masks at a time: the counters are a running chain in four scalar registers
     asm volatile("" : "+s"(c.lt1), "+s"(c.lt2), "+s"(c.lt4), "+s"(c.lt8));
-}
-
-// ---- 16-bit floating dtypes: both halves of a word at once, with packed 16-bit integer arithmetic ----
-typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
-typedef short s16x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
-__device__ __forceinline__ s16x2 as_s16x2(uint32_t w) { return __builtin_bit_cast(s16x2, w); }
-__device__ __forceinline__ uint32_t as_word(u16x2 v) { return __builtin_bit_cast(uint32_t, v); }
-__device__ __forceinline__ uint32_t as_word(s16x2 v) { return __builtin_bit_cast(uint32_t, v); }
-
-// ord of both halves (as two's-complement 16-bit integers: the magnitudes are below 2^15)
-__device__ __forceinline__ uint32_t ulp_ord_pair(uint32_t w)
-{
-    const uint32_t mag = w & 0x7FFF7FFFu;
-    const uint32_t sign = as_word(as_s16x2(w) >> (short)15);              // all ones in a negative half
-    return as_word(as_u16x2(mag ^ sign) - as_u16x2(sign));               // negated there
-}
-// all ones in every half that holds a NaN: magnitude above the pattern of Inf
-template <int DT>
-__device__ __forceinline__ uint32_t ulp_nan_mark_pair(uint32_t w)
-{
-    constexpr uint32_t kUp = 0x7FFFu - (DT == GEAK_F16 ? 0x7C00u : 0x7F80u);   // lifts exactly the NaN magnitudes to bit 15
-    const uint32_t lifted = (w & 0x7FFF7FFFu) + kUp * 0x00010001u;           // no carry between the halves
-    return as_word(as_s16x2(lifted) >> (short)15);
-}
-// distances of both halves: max - min of the ord values; the difference is below 2^16, so the
-// wrapping 16-bit subtraction is exact
-__device__ __forceinline__ uint32_t ulp_dist_pair(uint32_t oa2, uint32_t ob2)
-{
-    const s16x2 a = as_s16x2(oa2), b = as_s16x2(ob2);
-    const s16x2 hi = __builtin_elementwise_max(a, b), lo = __builtin_elementwise_min(a, b);
-    return as_word(as_u16x2(as_word(hi)) - as_u16x2(as_word(lo)));
 }
 
 // ---- the other dtypes: element by element ------------------------------------------------------------
@@ -264,97 +232,103 @@ template <int DT> struct UlpRef {
     }
 };
 
-// 16-bit floating dtypes: packed ord values, one register per two elements.  The classes are not
-// counted with lane masks (two scalar instructions per class and element, and the scalar unit
-// issues no faster than the vector unit) but per lane, with packed 16-bit arithmetic on both halves
-// at once: min(d >> s, 1) is 1 exactly where d >= 2^s, and four packed accumulators sum these.  They
-// are added up over the wave once per candidate slice.
-struct UlpLaneCounts {
-    uint32_t ge1, ge2, ge4, ge8;          // per half: elements of this lane with distance >= 1, 2, 4, 8
-};
-// Sum over the wave, wave-uniform result: four data-parallel-primitive steps inside each row of 16
-// lanes (neighbour, other pair, other quad mirrored, other half mirrored), then one lane of each row.
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
+// 16-bit floating dtypes.  Both halves of a word are turned into keys with ordinary 32-bit
+// instructions (the packed 16-bit integer instructions run at half rate): key = ord + 0x8000, i.e.
+// pattern + 0x8000 for a non-negative half and the two's complement of the pattern for a negative
+// one; neither addition carries out of its half.  The absolute difference of the isolated halves is
+// one v_sad_u32 each; the upper one stays in the upper half and is compared with shifted thresholds.
+// A NaN in the candidate needs no test of its own while the reference vector holds nothing within
+// 8 steps of Inf or beyond: its distance is then at least 8, and the far path, which looks at the
+// pattern again, sorts it out.  Reference vectors that do hold such a value take the plain path.
+__device__ __forceinline__ uint32_t abs_diff_u32(uint32_t a, uint32_t b)
 {
-    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);     // quad_perm [1,0,3,2]
-    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false);     // quad_perm [2,3,0,1]
-    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, false);    // row_half_mirror
-    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, false);    // row_mirror
-    return (uint32_t)__builtin_amdgcn_readlane((int)x, 0) + (uint32_t)__builtin_amdgcn_readlane((int)x, 16) +
-           (uint32_t)__builtin_amdgcn_readlane((int)x, 32) + (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+    uint32_t r;
+    asm("v_sad_u32 %0, %1, %2, 0" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t ulp_key_pair(uint32_t w)
+{
+    const uint32_t neg = (w >> 15) & 0x00010001u;            // 1 in a negative half
+    const uint32_t flip = neg * 0xFFFFu;                     // all ones there
+    const uint32_t add = (neg * 0x8001u) ^ 0x80008000u;      // 1 there, 0x8000 in a non-negative half
+    return (w ^ flip) + add;
 }
 
 template <int DT> struct UlpRef16 {
-    typedef UlpLaneCounts Counts;
-    uint32_t ob2[kVecPerLane * 4];
-    uint32_t nan_vectors;
+    typedef UlpCounts Counts;
+    static constexpr uint32_t kInf = (DT == GEAK_F16) ? 0x7C00u : 0x7F80u;
+    uint32_t kb_lo[kVecPerLane * 4], kb_hi[kVecPerLane * 4];   // the reference keys, each in its own half, the other half 0
+    uint32_t edge_vectors;                                     // bit v: some lane's reference vector v holds a magnitude >= Inf - 8
 
     static __device__ __forceinline__ Counts zero() { return Counts{0u, 0u, 0u, 0u}; }
+    static __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane)
+    {
+        ulp_commit(c, (uint32_t)(kWaveSize * kVecPerLane * 8) - elements, row, lane);
+    }
 
     template <int V> __device__ __forceinline__ void stage(const u32x4 &q)
     {
-        if constexpr (V == 0) nan_vectors = 0;
-        uint32_t marks = 0;
+        if constexpr (V == 0) edge_vectors = 0;
+        bool edge = false;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            ob2[V * 4 + w] = ulp_ord_pair(q[w]);
-            marks |= ulp_nan_mark_pair<DT>(q[w]);
+            const uint32_t key = ulp_key_pair(q[w]);
+            kb_lo[V * 4 + w] = key & 0xFFFFu;
+            kb_hi[V * 4 + w] = key & 0xFFFF0000u;
+            edge |= (q[w] & 0x7FFFu) >= kInf - 8u || ((q[w] >> 16) & 0x7FFFu) >= kInf - 8u;
         }
-        if (__builtin_amdgcn_ballot_w64(marks != 0)) nan_vectors |= 1u << V;
+        if (__builtin_amdgcn_ballot_w64(edge)) edge_vectors |= 1u << V;
     }
+
+    // far path of one half: the lanes 8 or more steps away
+    static __device__ __forceinline__ void far(uint32_t pattern, uint32_t d, GEAK_AS_LDS uint32_t *row, uint32_t nslots)
+    {
+        const uint32_t slot = ((pattern & 0x7FFFu) > kInf) ? nslots - 1 : 32u - (uint32_t)__builtin_clz(d);
+        (void)__hip_atomic_fetch_add(row + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+
     template <int V> __device__ __forceinline__ void compare(const u32x4 &q, Counts &c, GEAK_AS_LDS uint32_t *row, uint32_t nslots) const
     {
-        const bool ref_nan = (nan_vectors >> V) & 1u;
-        constexpr uint32_t kOnes = 0x00010001u;
+        if ((edge_vectors >> V) & 1u) {                      // rare: element by element, NaN tested on both sides
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int oa = ulp_ord<DT>(q, e);
+                const uint32_t kb = (e & 1) ? (kb_hi[V * 4 + (e >> 1)] >> 16) : kb_lo[V * 4 + (e >> 1)];
+                const int ob = (int)kb - 0x8000;
+                const uint32_t d = ulp_dist<DT>(oa, ob) | ulp_nan_mark<DT>(oa) | ulp_nan_mark<DT>(ob);
+                ulp_classify<uint32_t, true>(d, c, row, nslots);
+            }
+            return;
+        }
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            uint32_t d2 = ulp_dist_pair(ulp_ord_pair(q[w]), ob2[V * 4 + w]) | ulp_nan_mark_pair<DT>(q[w]);
-            if (ref_nan) {
-                // the magnitudes of the staged ord values, as patterns: |ord| per half
-                const s16x2 o = as_s16x2(ob2[V * 4 + w]);
-                const uint32_t mag = as_word(__builtin_elementwise_max(o, (s16x2)(-o)));
-                d2 |= ulp_nan_mark_pair<DT>(mag);
+            const uint32_t key = ulp_key_pair(q[w]);
+            const uint32_t d_lo = abs_diff_u32(key & 0xFFFFu, kb_lo[V * 4 + w]);
+            const uint32_t d_hi = abs_diff_u32(key & 0xFFFF0000u, kb_hi[V * 4 + w]);       // the distance, times 2^16
+            {
+                const bool near = d_lo < 8u;
+                const u64 m8 = __builtin_amdgcn_ballot_w64(near);
+                c.lt1 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_lo < 1u));
+                c.lt2 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_lo < 2u));
+                c.lt4 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_lo < 4u));
+                c.lt8 += (uint32_t)__builtin_popcountll(m8);
+                if (~m8) {
+                    if (__builtin_amdgcn_inverse_ballot_w64(~m8)) far(q[w], d_lo, row, nslots);
+                }
+                asm volatile("" : "+s"(c.lt1), "+s"(c.lt2), "+s"(c.lt4), "+s"(c.lt8));
             }
-            // ge_s += min(d >> s, 1) for s = 0 .. 3 on both halves; the last indicator is kept.  Packed 16-bit
-            // instructions write whole registers, so the sequence needs no wait states between its steps.
-            uint32_t far2;
-            asm("v_pk_min_u16 %4, %5, %6\n\t"
-                "v_pk_add_u16 %0, %0, %4\n\t"
-                "v_pk_lshrrev_b16 %4, 1, %5 op_sel_hi:[0,1]\n\t"
-                "v_pk_min_u16 %4, %4, %6\n\t"
-                "v_pk_add_u16 %1, %1, %4\n\t"
-                "v_pk_lshrrev_b16 %4, 2, %5 op_sel_hi:[0,1]\n\t"
-                "v_pk_min_u16 %4, %4, %6\n\t"
-                "v_pk_add_u16 %2, %2, %4\n\t"
-                "v_pk_lshrrev_b16 %4, 3, %5 op_sel_hi:[0,1]\n\t"
-                "v_pk_min_u16 %4, %4, %6\n\t"
-                "v_pk_add_u16 %3, %3, %4"
-                : "+v"(c.ge1), "+v"(c.ge2), "+v"(c.ge4), "+v"(c.ge8), "=&v"(far2)
-                : "v"(d2), "v"(kOnes));
-            if (__builtin_amdgcn_ballot_w64(far2 != 0)) {      // some lane is 8 or more steps away: straight into the LDS row
-                if (far2 & 0xFFFFu)
-                    (void)__hip_atomic_fetch_add(row + ulp_slot<uint16_t, true>((uint16_t)d2, nslots), 1u, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
-                if (far2 >> 16)
-                    (void)__hip_atomic_fetch_add(row + ulp_slot<uint16_t, true>((uint16_t)(d2 >> 16), nslots), 1u, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+            {
+                const bool near = d_hi < (8u << 16);
+                const u64 m8 = __builtin_amdgcn_ballot_w64(near);
+                c.lt1 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_hi < (1u << 16)));
+                c.lt2 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_hi < (2u << 16)));
+                c.lt4 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_hi < (4u << 16)));
+                c.lt8 += (uint32_t)__builtin_popcountll(m8);
+                if (~m8) {
+                    if (__builtin_amdgcn_inverse_ballot_w64(~m8)) far(q[w] >> 16, d_hi >> 16, row, nslots);
+                }
+                asm volatile("" : "+s"(c.lt1), "+s"(c.lt2), "+s"(c.lt4), "+s"(c.lt8));
             }
-        }
-    }
-    // `elements` of the slice (absent ones of a tail not counted) were compared
-    static __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane)
-    {
-        const uint32_t g1 = (c.ge1 & 0xFFFFu) + (c.ge1 >> 16), g2 = (c.ge2 & 0xFFFFu) + (c.ge2 >> 16);
-        const uint32_t g4 = (c.ge4 & 0xFFFFu) + (c.ge4 >> 16), g8 = (c.ge8 & 0xFFFFu) + (c.ge8 >> 16);
-        // at most 32 per lane and class: two classes share a register through the wave sum (below 2^16 each)
-        const uint32_t s12 = wave_sum_u32(g1 | (g2 << 16)), s48 = wave_sum_u32(g4 | (g8 << 16));
-        if (lane == 0) {
-            const uint32_t n1 = s12 & 0xFFFFu, n2 = s12 >> 16, n4 = s48 & 0xFFFFu, n8 = s48 >> 16;
-            const uint32_t b0 = elements - n1, b1 = n1 - n2, b2 = n2 - n4, b3 = n4 - n8;
-            if (b0) (void)__hip_atomic_fetch_add(row + 0, b0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (b1) (void)__hip_atomic_fetch_add(row + 1, b1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (b2) (void)__hip_atomic_fetch_add(row + 2, b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (b3) (void)__hip_atomic_fetch_add(row + 3, b3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
 };
@@ -562,23 +536,47 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
     }
 }
 
-// ---- reduce: one block per (segment, candidate); thread t sums bin t over the segment's slots -----------
-constexpr int kUlpReduceThreads = 128;
+// ---- reduce: one block per (segment, candidate) ----------------------------------------------------
+// The pair's partial rows (one per slot of the segment) are summed by 16 waves: a wave takes every
+// 16th row, its lanes the row's slots (a row is contiguous), eight rows in flight at a time; the
+// waves' sums meet in LDS.
+constexpr int kUlpReduceThreads = 1024;
+constexpr int kUlpReduceWaves = kUlpReduceThreads / kWaveSize;
 __global__ __launch_bounds__(kUlpReduceThreads) void ulp_reduce_kernel(const UlpReduceArgs p)
 {
-    const uint32_t K = p.num_candidates;
+    __shared__ u64 sums[kUlpReduceWaves][2 * kWaveSize];
+    const uint32_t K = p.num_candidates, nslots = p.nslots;
     const uint32_t seg = blockIdx.x / K, k = blockIdx.x % K;
-    const uint32_t bin = threadIdx.x;
-    if (bin >= GEAK_ULP_BINS) return;
-    // bin -> slot of the partial rows: the NaN bin is the last slot; bins the plan's dtypes cannot reach hold nothing
-    const bool reachable = (bin == GEAK_ULP_BINS - 1) || (bin < p.nslots - 1);
-    const uint32_t slot_in_row = (bin == GEAK_ULP_BINS - 1) ? p.nslots - 1 : bin;
-    u64 sum = 0;
-    if (reachable) {
-        const uint32_t s0 = p.slot_begin[seg], s1 = p.slot_begin[seg + 1];
-        for (uint32_t s = s0; s < s1; ++s) sum += p.partials[((u64)s * K + k) * p.nslots + slot_in_row];
+    const uint32_t lane = threadIdx.x & (kWaveSize - 1), wave = threadIdx.x / kWaveSize;
+    const uint32_t s0 = p.slot_begin[seg], s1 = p.slot_begin[seg + 1];
+    const bool has0 = lane < nslots, has1 = lane + kWaveSize < nslots;          // nslots <= 66: two slots per lane at most
+    u64 acc0 = 0, acc1 = 0;
+    constexpr uint32_t kAhead = 8;
+    for (uint32_t s = s0 + wave; s < s1; s += kUlpReduceWaves * kAhead) {
+        uint32_t v0[kAhead], v1[kAhead];
+#pragma unroll
+        for (uint32_t u = 0; u < kAhead; ++u) {
+            const uint32_t row = s + u * kUlpReduceWaves;
+            const uint32_t *r = p.partials + ((u64)row * K + k) * nslots;
+            v0[u] = (row < s1 && has0) ? r[lane] : 0u;
+            v1[u] = (row < s1 && has1) ? r[lane + kWaveSize] : 0u;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < kAhead; ++u) { acc0 += v0[u]; acc1 += v1[u]; }
     }
-    p.hist[(u64)blockIdx.x * GEAK_ULP_BINS + bin] = sum;
+    sums[wave][lane] = acc0;
+    sums[wave][lane + kWaveSize] = acc1;
+    __syncthreads();
+    const uint32_t bin = threadIdx.x;
+    if (bin < GEAK_ULP_BINS) {
+        // bin -> slot of the partial rows: the NaN bin is the last slot; bins the plan's dtypes cannot reach hold nothing
+        const bool reachable = (bin == GEAK_ULP_BINS - 1) || (bin < nslots - 1);
+        const uint32_t slot_in_row = (bin == GEAK_ULP_BINS - 1) ? nslots - 1 : bin;
+        u64 sum = 0;
+        if (reachable)
+            for (int w = 0; w < kUlpReduceWaves; ++w) sum += sums[w][slot_in_row];
+        p.hist[(u64)blockIdx.x * GEAK_ULP_BINS + bin] = sum;
+    }
 }
 
 }  // namespace
