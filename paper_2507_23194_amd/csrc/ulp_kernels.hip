@@ -232,39 +232,70 @@ template <int DT> struct UlpRef {
     }
 };
 
-// 16-bit floating dtypes.  Both halves of a word are turned into keys with ordinary 32-bit
-// instructions (the packed 16-bit integer instructions run at half rate): key = ord + 0x8000, i.e.
-// pattern + 0x8000 for a non-negative half and the two's complement of the pattern for a negative
-// one; neither addition carries out of its half.  The absolute difference of the isolated halves is
-// one v_sad_u32 each; the upper one stays in the upper half and is compared with shifted thresholds.
-// A NaN in the candidate needs no test of its own while the reference vector holds nothing within
-// 8 steps of Inf or beyond: its distance is then at least 8, and the far path, which looks at the
-// pattern again, sorts it out.  Reference vectors that do hold such a value take the plain path.
-__device__ __forceinline__ uint32_t abs_diff_u32(uint32_t a, uint32_t b)
+// 16-bit floating dtypes: both halves of a word at once, with packed 16-bit integer arithmetic.
+//   ord      magnitude, negated (two's complement, 16 bits) in a negative half
+//   distance max - min of the two ord values; it is below 2^16, so the wrapping subtraction is exact
+//   classes  t = min(d, 8) per half selects, as a byte selector of v_perm_b32, an entry of an 8-byte
+//            table: 1 for d = 1 and 32 for d = 2, 3 in the first table, 1 for d = 4 .. 7 in the second;
+//            d = 0 selects 0 and so does t = 8 (selector 8 yields the sign of table byte 1).  The upper
+//            byte of each half of t is 0 and selects entry 0 as well.  Adding the results to two
+//            per-lane accumulators counts the three classes in 5-bit fields of each half (a lane
+//            sees 16 words per slice); they are summed over the wave once per candidate slice.
+//   NaN      a NaN in the candidate needs no test while the reference vector holds nothing within 8
+//            steps of Inf or beyond: its distance is then at least 8, and the far path, which looks
+//            at the pattern again, sorts it out.  Reference vectors that do hold such a value take
+//            the plain path, element by element.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
+__device__ __forceinline__ s16x2 as_s16x2(uint32_t w) { return __builtin_bit_cast(s16x2, w); }
+__device__ __forceinline__ uint32_t as_word(u16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ uint32_t as_word(s16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+
+__device__ __forceinline__ uint32_t ulp_ord_pair(uint32_t w)
 {
-    uint32_t r;
-    asm("v_sad_u32 %0, %1, %2, 0" : "=v"(r) : "v"(a), "v"(b));
+    const uint32_t mag = w & 0x7FFF7FFFu;
+    const uint32_t sign = as_word(as_s16x2(w) >> (short)15);              // all ones in a negative half
+    return as_word(as_u16x2(mag ^ sign) - as_u16x2(sign));               // negated there
+}
+__device__ __forceinline__ uint32_t ulp_dist_pair(uint32_t oa2, uint32_t ob2)
+{
+    const s16x2 a = as_s16x2(oa2), b = as_s16x2(ob2);
+    const s16x2 hi = __builtin_elementwise_max(a, b), lo = __builtin_elementwise_min(a, b);
+    return as_word(as_u16x2(as_word(hi)) - as_u16x2(as_word(lo)));
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b)
+{
+    uint32_t r;                       // as the instruction itself: from min() the compiler derives a compare and select per half
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
     return r;
 }
-__device__ __forceinline__ uint32_t ulp_key_pair(uint32_t w)
+// Sum over the wave, wave-uniform result: four data-parallel-primitive steps inside each row of 16
+// lanes (neighbour, other pair, other quad mirrored, other half mirrored), then one lane of each row.
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
 {
-    const uint32_t neg = (w >> 15) & 0x00010001u;            // 1 in a negative half
-    const uint32_t flip = neg * 0xFFFFu;                     // all ones there
-    const uint32_t add = (neg * 0x8001u) ^ 0x80008000u;      // 1 there, 0x8000 in a non-negative half
-    return (w ^ flip) + add;
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);     // quad_perm [1,0,3,2]
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false);     // quad_perm [2,3,0,1]
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, false);    // row_half_mirror
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, false);    // row_mirror
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 0) + (uint32_t)__builtin_amdgcn_readlane((int)x, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)x, 32) + (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
 }
 
+struct UlpCounts16 {
+    uint32_t near12;          // per half, 5-bit fields: elements of this lane with d = 1 (bits 0-4) and d = 2, 3 (bits 5-9)
+    uint32_t near4;           // per half: d = 4 .. 7 (bits 0-4)
+    UlpCounts plain;          // what the plain path (reference vectors near Inf) counted, cumulative classes
+    uint32_t far_lane;        // elements of this lane sent down the far path
+};
+
 template <int DT> struct UlpRef16 {
-    typedef UlpCounts Counts;
+    typedef UlpCounts16 Counts;
     static constexpr uint32_t kInf = (DT == GEAK_F16) ? 0x7C00u : 0x7F80u;
-    uint32_t kb_lo[kVecPerLane * 4], kb_hi[kVecPerLane * 4];   // the reference keys, each in its own half, the other half 0
+    uint32_t ob2[kVecPerLane * 4];
     uint32_t edge_vectors;                                     // bit v: some lane's reference vector v holds a magnitude >= Inf - 8
 
-    static __device__ __forceinline__ Counts zero() { return Counts{0u, 0u, 0u, 0u}; }
-    static __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane)
-    {
-        ulp_commit(c, (uint32_t)(kWaveSize * kVecPerLane * 8) - elements, row, lane);
-    }
+    static __device__ __forceinline__ Counts zero() { return Counts{0u, 0u, UlpCounts{0u, 0u, 0u, 0u}, 0u}; }
 
     template <int V> __device__ __forceinline__ void stage(const u32x4 &q)
     {
@@ -272,19 +303,26 @@ template <int DT> struct UlpRef16 {
         bool edge = false;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const uint32_t key = ulp_key_pair(q[w]);
-            kb_lo[V * 4 + w] = key & 0xFFFFu;
-            kb_hi[V * 4 + w] = key & 0xFFFF0000u;
+            ob2[V * 4 + w] = ulp_ord_pair(q[w]);
             edge |= (q[w] & 0x7FFFu) >= kInf - 8u || ((q[w] >> 16) & 0x7FFFu) >= kInf - 8u;
         }
         if (__builtin_amdgcn_ballot_w64(edge)) edge_vectors |= 1u << V;
     }
 
-    // far path of one half: the lanes 8 or more steps away
+    // far path of one half: the lanes 8 or more steps away.  The slot is the distance's bit length,
+    // addressed as (row + 32 slots) - 4 * leading zeros; a NaN among these lanes is the exception.
     static __device__ __forceinline__ void far(uint32_t pattern, uint32_t d, GEAK_AS_LDS uint32_t *row, uint32_t nslots)
     {
-        const uint32_t slot = ((pattern & 0x7FFFu) > kInf) ? nslots - 1 : 32u - (uint32_t)__builtin_clz(d);
-        (void)__hip_atomic_fetch_add(row + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const uint32_t row_bytes = (uint32_t)(uintptr_t)row;
+        const uint32_t by_length = row_bytes + 128u - 4u * (uint32_t)__builtin_clz(d);
+        const bool is_nan = (pattern & 0x7FFFu) > kInf;
+        if (__builtin_amdgcn_ballot_w64(is_nan) == 0) {
+            (void)__hip_atomic_fetch_add((GEAK_AS_LDS uint32_t *)by_length, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        } else {
+            uint32_t addr = is_nan ? row_bytes + 4u * (nslots - 1) : by_length;
+            asm volatile("" : "+v"(addr));          // keeps the two cases apart: merged, both would pay for the selection
+            (void)__hip_atomic_fetch_add((GEAK_AS_LDS uint32_t *)addr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
     }
 
     template <int V> __device__ __forceinline__ void compare(const u32x4 &q, Counts &c, GEAK_AS_LDS uint32_t *row, uint32_t nslots) const
@@ -293,42 +331,62 @@ template <int DT> struct UlpRef16 {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int oa = ulp_ord<DT>(q, e);
-                const uint32_t kb = (e & 1) ? (kb_hi[V * 4 + (e >> 1)] >> 16) : kb_lo[V * 4 + (e >> 1)];
-                const int ob = (int)kb - 0x8000;
+                const uint32_t pair = ob2[V * 4 + (e >> 1)];
+                const int ob = (e & 1) ? ((int)pair >> 16) : (int)(short)(pair & 0xFFFFu);
                 const uint32_t d = ulp_dist<DT>(oa, ob) | ulp_nan_mark<DT>(oa) | ulp_nan_mark<DT>(ob);
-                ulp_classify<uint32_t, true>(d, c, row, nslots);
+                ulp_classify<uint32_t, true>(d, c.plain, row, nslots);
             }
             return;
         }
+        uint32_t d2[4], t2[4];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const uint32_t key = ulp_key_pair(q[w]);
-            const uint32_t d_lo = abs_diff_u32(key & 0xFFFFu, kb_lo[V * 4 + w]);
-            const uint32_t d_hi = abs_diff_u32(key & 0xFFFF0000u, kb_hi[V * 4 + w]);       // the distance, times 2^16
-            {
-                const bool near = d_lo < 8u;
-                const u64 m8 = __builtin_amdgcn_ballot_w64(near);
-                c.lt1 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_lo < 1u));
-                c.lt2 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_lo < 2u));
-                c.lt4 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_lo < 4u));
-                c.lt8 += (uint32_t)__builtin_popcountll(m8);
-                if (~m8) {
-                    if (__builtin_amdgcn_inverse_ballot_w64(~m8)) far(q[w], d_lo, row, nslots);
+            d2[w] = ulp_dist_pair(ulp_ord_pair(q[w]), ob2[V * 4 + w]);
+            t2[w] = pk_min_u16(d2[w], 0x00080008u);
+            c.near12 += __builtin_amdgcn_perm(0u, 0x20200100u, t2[w]);       // table bytes 0 .. 7: 0, 1, 32, 32, 0, 0, 0, 0
+            c.near4 += __builtin_amdgcn_perm(0x01010101u, 0u, t2[w]);        //                     0, 0, 0, 0, 1, 1, 1, 1
+        }
+        if (__builtin_amdgcn_ballot_w64(((t2[0] | t2[1] | t2[2] | t2[3]) & 0x00080008u) != 0)) {
+            // Some lane has elements 8 or more steps away.  Every lane walks through its own (bit i of
+            // `todo`: half i of the vector), so the wave issues as many rounds of LDS atomics as the
+            // worst lane has such elements, not one round per element position.
+            uint32_t todo = 0;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) todo |= (((t2[w] >> 3) & 1u) | ((t2[w] >> 18) & 2u)) << (2 * w);
+            c.far_lane += (uint32_t)__builtin_popcount(todo);
+            while (__builtin_amdgcn_ballot_w64(todo != 0)) {
+                if (todo != 0) {
+                    const uint32_t i = (uint32_t)__builtin_ctz(todo);
+                    todo &= todo - 1u;
+                    const uint32_t word = i >> 1, shift = (i & 1u) * 16u;
+                    const uint32_t dd = word == 0 ? d2[0] : word == 1 ? d2[1] : word == 2 ? d2[2] : d2[3];
+                    const uint32_t qq = word == 0 ? q[0] : word == 1 ? q[1] : word == 2 ? q[2] : q[3];
+                    far(qq >> shift, (dd >> shift) & 0xFFFFu, row, nslots);
                 }
-                asm volatile("" : "+s"(c.lt1), "+s"(c.lt2), "+s"(c.lt4), "+s"(c.lt8));
             }
-            {
-                const bool near = d_hi < (8u << 16);
-                const u64 m8 = __builtin_amdgcn_ballot_w64(near);
-                c.lt1 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_hi < (1u << 16)));
-                c.lt2 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_hi < (2u << 16)));
-                c.lt4 += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(d_hi < (4u << 16)));
-                c.lt8 += (uint32_t)__builtin_popcountll(m8);
-                if (~m8) {
-                    if (__builtin_amdgcn_inverse_ballot_w64(~m8)) far(q[w] >> 16, d_hi >> 16, row, nslots);
-                }
-                asm volatile("" : "+s"(c.lt1), "+s"(c.lt2), "+s"(c.lt4), "+s"(c.lt8));
-            }
+        }
+    }
+
+    // `elements` of the slice (absent ones of a tail not counted) were compared.  Elements at distance 0
+    // were counted nowhere on the packed path: they are what is left.  Of a plain-path vector's 512
+    // positions (absent ones included, at distance 0) those outside its four classes went to the row there.
+    __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane) const
+    {
+        const uint32_t n1 = (c.near12 & 0x1Fu) + ((c.near12 >> 16) & 0x1Fu);
+        const uint32_t n2 = ((c.near12 >> 5) & 0x1Fu) + ((c.near12 >> 21) & 0x1Fu);
+        const uint32_t n4 = (c.near4 & 0x1Fu) + ((c.near4 >> 16) & 0x1Fu);
+        // at most 32 per lane and class: two classes share a register through the wave sum (below 2^16 each)
+        const uint32_t s12 = wave_sum_u32(n1 | (n2 << 16)), s4f = wave_sum_u32(n4 | (c.far_lane << 16));
+        const uint32_t s4 = s4f & 0xFFFFu, far_total = s4f >> 16;
+        if (lane == 0) {
+            const uint32_t b1 = (s12 & 0xFFFFu) + (c.plain.lt2 - c.plain.lt1), b2 = (s12 >> 16) + (c.plain.lt4 - c.plain.lt2);
+            const uint32_t b3 = s4 + (c.plain.lt8 - c.plain.lt4);
+            const uint32_t plain_far = (uint32_t)__builtin_popcount(edge_vectors) * (uint32_t)(kWaveSize * 8) - c.plain.lt8;
+            const uint32_t b0 = elements - b1 - b2 - b3 - far_total - plain_far;
+            if (b0) (void)__hip_atomic_fetch_add(row + 0, b0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (b1) (void)__hip_atomic_fetch_add(row + 1, b1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (b2) (void)__hip_atomic_fetch_add(row + 2, b2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (b3) (void)__hip_atomic_fetch_add(row + 3, b3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
 };
@@ -422,7 +480,7 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
             ref.template compare<1>(cur[1], c, row, st.nslots); cur[1] = load_vec<DT>(next, lane, 1, it.numel, full);
             ref.template compare<2>(cur[2], c, row, st.nslots); cur[2] = load_vec<DT>(next, lane, 2, it.numel, full);
             ref.template compare<3>(cur[3], c, row, st.nslots); cur[3] = load_vec<DT>(next, lane, 3, it.numel, full);
-            Ref::commit(c, it.numel, row, lane);
+            ref.commit(c, it.numel, row, lane);
         }
         if (it.flags & GEAK_ITEM_LAST) ulp_end_run(st, partials, it.slot, K, k_begin, k_count, lane);
         if (!more) break;
