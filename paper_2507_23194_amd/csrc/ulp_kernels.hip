@@ -11,11 +11,14 @@
 //
 // histogram kernel -- the plan's work items and per-wave item lists are reused.  A wave keeps the
 // ord values of its reference slice in registers and streams the candidates of the pass past them,
-// one candidate's loads ahead of the compute.  Per element four cumulative classes (distance < 1,
-// < 2, < 4, < 8) are counted with lane masks in scalar registers; only lanes beyond them (or NaN)
-// touch the wave's histogram in LDS, one atomic add per lane.  Per (wave, segment run, candidate)
-// the LDS rows are written, without atomics, to a partial table; the reduce kernel sums the
-// partial rows of a segment.  A pass covers as many candidates as fit the wave's LDS rows.
+// four 16-byte loads per lane in flight.  The low bins are counted without touching memory: for the
+// 32- and 64-bit dtypes four cumulative classes (distance < 1, < 2, < 4, < 8) with lane masks in
+// scalar registers; for the 16-bit dtypes, whose budget of instructions per byte is half as large,
+// both halves of a word at once with packed arithmetic and two byte-permute tables that turn
+// min(d, 8) into increments of per-lane counters.  Only lanes 8 or more steps away (or NaN) touch
+// the wave's histogram rows in LDS, one atomic add per lane.  Per (wave, segment run, candidate) the
+// rows are written, without atomics, to a partial table; the reduce kernel sums the partial rows of
+// a segment.  A pass covers as many candidates as fit the wave's LDS rows.
 #include <hip/hip_runtime.h>
 #include "geak_internal.hpp"
 #include "device_common.hpp"
