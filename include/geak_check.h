@@ -276,6 +276,35 @@ uint64_t geak_check_ulp_workspace_bytes(const geak_plan *plan);
 geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
                                      void *ulp_workspace_dev, uint64_t *hist_dev, void *hip_stream);
 
+/* ---- verdicts and the evaluation metrics built on them --------------------------------------------
+ * A kernel is correct only if it satisfies all of its unit tests (section 3.3); the metrics of the
+ * paper's "Evaluation Metrics" section are computed from these verdicts. */
+
+/* Enqueue, after the geak_check_run that produced `results_dev` and on the same stream:
+ *   verdicts_dev[k]      1 iff every segment's record of candidate k passes (device, num_candidates int32)
+ *   failed_tests_dev[k]  number of segments candidate k fails (device, num_candidates uint32); may be null */
+geak_status geak_check_verdicts(const geak_plan *plan, const geak_result *results_dev, int32_t *verdicts_dev,
+                                uint32_t *failed_tests_dev, void *hip_stream);
+
+/* Host arithmetic, host pointers.
+ * Call accuracy = kernels that compile and run / all kernels; execution accuracy = kernels that
+ * satisfy all unit tests / kernels that compile (NaN when the denominator is 0).  compiled[i] and
+ * correct[i] are flags of kernel i; `correct` only counts where `compiled` is set. */
+geak_status geak_metrics_accuracy(const int32_t *compiled, const int32_t *correct, uint64_t n,
+                                  double *call_accuracy, double *execution_accuracy);
+
+/* Speedup of one correct kernel: the mean over its unit tests of (median reference latency of the
+ * test / median generated latency of the test), accumulated in test order in binary64.  Latencies are
+ * row-major [test][repetition]; the median of an even count is the mean of the two middle values.
+ * NaN when there is no test or no repetition. */
+geak_status geak_metrics_speedup(const double *ref_latencies, uint64_t ref_reps, const double *gen_latencies,
+                                 uint64_t gen_reps, uint64_t num_tests, double *speedup);
+
+/* pass@k (section 4.2: accuracy under parallel scaling is estimated with pass@k; the paper prints no
+ * formula, this is the usual unbiased estimator): the probability 1 - C(n - c, k) / C(n, k) that a
+ * k-subset of n samples, c of them correct, holds a correct one.  GEAK_EINVAL unless c <= n, 1 <= k <= n. */
+geak_status geak_metrics_pass_at_k(uint64_t n, uint64_t c, uint64_t k, double *out);
+
 /* ---- read probe (measurement aid, not part of the check) -------------------------------------
  * Enqueues a kernel that only reads, with 16-byte loads, the same bytes a run of this plan reads
  * (the span of the packed reference and of every candidate that the segments cover) and computes

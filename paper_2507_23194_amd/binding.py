@@ -104,6 +104,15 @@ def library() -> ctypes.CDLL:
         lib.geak_check_ulp_workspace_bytes.argtypes = [vp]
         lib.geak_check_ulp_histogram.restype = ctypes.c_int
         lib.geak_check_ulp_histogram.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, vp]
+        lib.geak_check_verdicts.restype = ctypes.c_int
+        lib.geak_check_verdicts.argtypes = [vp, vp, vp, vp, vp]
+        dp = ctypes.POINTER(ctypes.c_double)
+        lib.geak_metrics_accuracy.restype = ctypes.c_int
+        lib.geak_metrics_accuracy.argtypes = [vp, vp, u64, dp, dp]
+        lib.geak_metrics_speedup.restype = ctypes.c_int
+        lib.geak_metrics_speedup.argtypes = [vp, u64, vp, u64, u64, dp]
+        lib.geak_metrics_pass_at_k.restype = ctypes.c_int
+        lib.geak_metrics_pass_at_k.argtypes = [u64, u64, u64, dp]
         lib.geak_check_read_probe.restype = ctypes.c_int
         lib.geak_check_read_probe.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp]
         lib.geak_check_profile_enable.restype = ctypes.c_int
@@ -117,7 +126,8 @@ def library() -> ctypes.CDLL:
 EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
-            "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram"]
+            "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram", "geak_check_verdicts",
+            "geak_metrics_accuracy", "geak_metrics_speedup", "geak_metrics_pass_at_k"]
 
 
 # ---- one Python function per C entry point -------------------------------------------------------
@@ -195,6 +205,40 @@ def geak_check_ulp_histogram(plan, ref_ptr: int, cand_ptrs: Sequence[int], ulp_w
     """Enqueue the ulp-distance histogram; all pointers are device addresses."""
     arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
     return int(library().geak_check_ulp_histogram(plan, ref_ptr, arr, ulp_workspace_ptr, hist_ptr, stream))
+
+
+def geak_check_verdicts(plan, results_ptr: int, verdicts_ptr: int, failed_tests_ptr: int, stream: int) -> int:
+    """Enqueue the per-candidate verdicts (all unit tests pass) of a completed run; device addresses."""
+    return int(library().geak_check_verdicts(plan, results_ptr, verdicts_ptr, failed_tests_ptr or None, stream))
+
+
+def geak_metrics_accuracy(compiled, correct):
+    """(status, call accuracy, execution accuracy) of flag sequences of equal length (host arithmetic)."""
+    a = np.ascontiguousarray(np.asarray(compiled, dtype=np.int32))
+    b = np.ascontiguousarray(np.asarray(correct, dtype=np.int32))
+    if a.shape != b.shape:
+        raise ValueError("compiled and correct must have the same length")
+    call, execution = ctypes.c_double(), ctypes.c_double()
+    st = int(library().geak_metrics_accuracy(a.ctypes.data, b.ctypes.data, a.size, ctypes.byref(call), ctypes.byref(execution)))
+    return st, call.value, execution.value
+
+
+def geak_metrics_speedup(ref_latencies, gen_latencies):
+    """(status, speedup) of two [test][repetition] latency tables (host arithmetic)."""
+    r = np.ascontiguousarray(np.asarray(ref_latencies, dtype=np.float64))
+    g = np.ascontiguousarray(np.asarray(gen_latencies, dtype=np.float64))
+    if r.ndim != 2 or g.ndim != 2 or r.shape[0] != g.shape[0]:
+        raise ValueError("latency tables must be [test][repetition] with the same number of tests")
+    out = ctypes.c_double()
+    st = int(library().geak_metrics_speedup(r.ctypes.data, r.shape[1], g.ctypes.data, g.shape[1], r.shape[0], ctypes.byref(out)))
+    return st, out.value
+
+
+def geak_metrics_pass_at_k(n: int, c: int, k: int):
+    """(status, pass@k)."""
+    out = ctypes.c_double()
+    st = int(library().geak_metrics_pass_at_k(n, c, k, ctypes.byref(out)))
+    return st, out.value
 
 
 def geak_check_read_probe(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: int, stream: int) -> int:
@@ -326,6 +370,18 @@ class Checker:
         torch.cuda.current_stream(self.device).synchronize()
         host = hist.cpu().numpy()[:self.n_results * GEAK_ULP_BINS].view(np.uint64)
         return host.reshape(-1, self.num_candidates, GEAK_ULP_BINS)
+
+    def verdicts(self):
+        """Per candidate: (all unit tests pass, number of failing tests) of the last run.  Synchronises."""
+        import torch
+        v = torch.empty(max(1, self.num_candidates), dtype=torch.int32, device=self.results.device)
+        f = torch.empty(max(1, self.num_candidates), dtype=torch.int32, device=self.results.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        st = geak_check_verdicts(self.plan, self.results.data_ptr(), v.data_ptr(), f.data_ptr(), stream)
+        if st != GEAK_OK:
+            raise GeakError(st, "geak_check_verdicts")
+        torch.cuda.current_stream(self.device).synchronize()
+        return v.cpu().numpy()[:self.num_candidates].astype(bool), f.cpu().numpy()[:self.num_candidates].astype(np.int64)
 
     def read_probe(self, ref, cands) -> None:
         """Enqueue the read-only probe over the same tensors on torch's current stream."""

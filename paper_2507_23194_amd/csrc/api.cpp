@@ -451,6 +451,24 @@ geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev,
     return GEAK_OK;
 }
 
+geak_status geak_check_verdicts(const geak_plan *plan, const geak_result *results_dev, int32_t *verdicts_dev,
+                                uint32_t *failed_tests_dev, void *hip_stream)
+{
+    if (!plan || !results_dev || !verdicts_dev) return GEAK_EINVAL;
+    if (plan->device < 0) return GEAK_EINVAL;
+    if (((uintptr_t)results_dev & 7u) || ((uintptr_t)verdicts_dev & 3u) || ((uintptr_t)failed_tests_dev & 3u)) return GEAK_EALIGN;
+    DeviceGuard g(plan->device);
+    if (!g.ok) return GEAK_EHIP;
+    VerdictArgs va;
+    va.results = results_dev;
+    va.verdicts = verdicts_dev;
+    va.failed_tests = failed_tests_dev;
+    va.num_segments = (uint32_t)plan->host.segments.size();
+    va.num_candidates = (uint32_t)plan->host.num_candidates;
+    if (launch_verdicts(va, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
+    return GEAK_OK;
+}
+
 geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
                                   void *workspace_dev, void *hip_stream)
 {

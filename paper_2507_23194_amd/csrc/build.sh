@@ -10,6 +10,6 @@ hipcc --offload-arch=gfx950 -O3 -std=c++17 -fPIC -shared -ffp-contract=off \
       -Xclang -target-feature -Xclang -packed-fp32-ops \
       -Wall -Wno-unused-function \
       -I"$root/include" -I"$here" \
-      "$here/kernels.hip" "$here/ulp_kernels.hip" "$here/api.cpp" "$here/plan_host.cpp" \
+      "$here/kernels.hip" "$here/ulp_kernels.hip" "$here/verdict_kernel.hip" "$here/metrics_host.cpp" "$here/api.cpp" "$here/plan_host.cpp" \
       -o "$out" "$@"
 echo "built $out"

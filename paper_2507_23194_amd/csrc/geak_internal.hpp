@@ -196,6 +196,16 @@ struct UlpReduceArgs {
 int launch_ulp_histogram(const UlpArgs &args, uint32_t grid_blocks, uint32_t lds_bytes, void *stream);   // ulp_kernels.hip
 int launch_ulp_reduce(const UlpReduceArgs &args, void *stream);
 
+// Per-candidate verdict over all segments (verdict_kernel.hip).
+struct VerdictArgs {
+    const geak_result *results;          // [segment][candidate]
+    int32_t *verdicts;                   // [candidate]: 1 iff every segment passes
+    uint32_t *failed_tests;              // [candidate]: segments that fail; may be null
+    uint32_t num_segments;
+    uint32_t num_candidates;
+};
+int launch_verdicts(const VerdictArgs &args, void *stream);
+
 // Kernel launchers (kernels.hip).  Return the hipError_t of the launch as int.
 int launch_init(const InitArgs &args, void *stream);
 int launch_compare(const CompareArgs &args, uint32_t grid_blocks, uint32_t lds_bytes, void *stream);

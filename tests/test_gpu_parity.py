@@ -422,3 +422,33 @@ def test_full_config4(oracle_mod):
 
 def test_full_config5(oracle_mod):
     _full(oracle_mod, 5, oracle_candidates=[0, 17, 31])
+
+
+def test_verdicts_over_all_unit_tests(oracle_mod):
+    """A candidate is correct only if every segment passes: the device verdicts against the oracle's
+    AND over its own records, with the count of failing segments."""
+    from oracle import metrics as M
+    w = synth.small(4, device="cuda")
+    ck = B.Checker(w.segments, num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol, equal_nan=w.equal_nan, device=0)
+    try:
+        ck.run(w.ref, w.cands)
+        gpu = ck.read().copy()
+        verdict, failed = ck.verdicts()
+    finally:
+        ck.close()
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, "records under the verdicts")
+    assert verdict.tolist() == M.verdicts(cpu).tolist()
+    assert failed.tolist() == [(cpu[:, k]["pass"] == 0).sum() for k in range(len(w.cands))]
+    # a dense plan with a clean copy among the candidates: exactly that one is correct
+    rng = np.random.default_rng(3)
+    b, a = _special_case(rng, "f32", 5000, special=0.0)
+    ref = _to_device(b, "f32")
+    cands = [_to_device(a, "f32"), _to_device(b.copy(), "f32"), _to_device(a, "f32")]
+    ck = B.Checker(dense=("f32", (b.size,)), num_candidates=3, atol=0.0, rtol=0.0, equal_nan=False, device=0)
+    try:
+        ck.run(ref, cands)
+        verdict, failed = ck.verdicts()
+    finally:
+        ck.close()
+    assert verdict.tolist() == [False, True, False] and failed.tolist() == [1, 0, 1]
