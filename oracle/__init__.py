@@ -15,6 +15,7 @@ from .oracle import (  # noqa: F401
     ULP_BINS,
     check_dense,
     check_ragged,
+    decode_f8,
     decode_f16,
     decode_bf16,
 )

@@ -14,7 +14,8 @@
  * no formula, tolerance value or NaN policy; the rule below is the reading
  * this project fixes (every point is listed in the design notes):
  *
- *   floating dtypes (binary32, binary16, bfloat16), a = candidate, b = reference,
+ *   floating dtypes (binary32, binary16, bfloat16, and the 8-bit formats E4M3 and E5M2 of the OCP
+ *   specification, all widened exactly to binary32), a = candidate, b = reference,
  *   all arithmetic in IEEE binary32, round-to-nearest-even, one rounding per
  *   operation, no fused multiply-add, subnormals honoured:
  *     R1  d   = | a (-) b |
@@ -66,7 +67,8 @@
 #include <xmmintrin.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2, ORACLE_I32 = 3, ORACLE_I64 = 4, ORACLE_U8 = 5, ORACLE_I8 = 6, ORACLE_F64 = 7 };
+enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2, ORACLE_I32 = 3, ORACLE_I64 = 4, ORACLE_U8 = 5, ORACLE_I8 = 6, ORACLE_F64 = 7,
+       ORACLE_F8E4M3 = 8, ORACLE_F8E5M2 = 9 };
 
 typedef struct {
     int32_t  pass;
@@ -111,6 +113,48 @@ static float decode_bf16(uint16_t h)
     return bits_to_float((uint32_t)h << 16);
 }
 
+/* 8-bit floating formats of the OCP 8-bit floating point specification, decoded by their definition:
+ * sign, biased exponent, mantissa; value = (-1)^s * 2^(e - bias) * (1 + m / 2^mbits), or
+ * (-1)^s * 2^(1 - bias) * (m / 2^mbits) when e = 0.
+ *   E4M3: 4 exponent bits (bias 7), 3 mantissa bits; no infinities; S.1111.111 is NaN; largest value 448
+ *   E5M2: 5 exponent bits (bias 15), 2 mantissa bits; e = 31 is Inf (m = 0) or NaN, as in IEEE formats */
+static float decode_f8e4m3(uint8_t x)
+{
+    int sign = x >> 7, e = (x >> 3) & 0xF, m = x & 0x7;
+    float v;
+    if (e == 0xF && m == 0x7)
+        v = NAN;
+    else if (e == 0)
+        v = ldexpf((float)m, 1 - 7 - 3);
+    else
+        v = ldexpf((float)(8 + m), e - 7 - 3);
+    return sign ? -v : v;
+}
+static float decode_f8e5m2(uint8_t x)
+{
+    int sign = x >> 7, e = (x >> 2) & 0x1F, m = x & 0x3;
+    float v;
+    if (e == 0x1F)
+        v = m ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexpf((float)m, 1 - 15 - 2);
+    else
+        v = ldexpf((float)(4 + m), e - 15 - 2);
+    return sign ? -v : v;
+}
+
+/* element i of a tensor of one of the dtypes whose rule runs in binary32, widened exactly */
+static float load_as_f32(const void *p, uint64_t i, int dtype)
+{
+    switch (dtype) {
+    case ORACLE_F32:    return ((const float *)p)[i];
+    case ORACLE_F16:    return decode_f16(((const uint16_t *)p)[i]);
+    case ORACLE_BF16:   return decode_bf16(((const uint16_t *)p)[i]);
+    case ORACLE_F8E4M3: return decode_f8e4m3(((const uint8_t *)p)[i]);
+    default:            return decode_f8e5m2(((const uint8_t *)p)[i]);
+    }
+}
+
 static int is_nan_f(float x) { return x != x; }
 static int is_inf_f(float x) { return x == INFINITY || x == -INFINITY; }
 
@@ -122,7 +166,7 @@ static int is_inf_f(float x) { return x == INFINITY || x == -INFINITY; }
 int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int dtype,
                          double atol, double rtol, int equal_nan, oracle_record *out)
 {
-    if (!out || dtype < 0 || dtype > 7)
+    if (!out || dtype < 0 || dtype > 9)
         return -1;
 
 #if defined(__SSE2__)
@@ -225,17 +269,7 @@ int oracle_check_segment(const void *ref, const void *cand, uint64_t numel, int 
         const float atol_f = (float)atol;
         const float rtol_f = (float)rtol;
         for (uint64_t i = 0; i < numel; ++i) {
-            float a, b;
-            if (dtype == ORACLE_F32) {
-                a = ((const float *)cand)[i];
-                b = ((const float *)ref)[i];
-            } else if (dtype == ORACLE_F16) {
-                a = decode_f16(((const uint16_t *)cand)[i]);
-                b = decode_f16(((const uint16_t *)ref)[i]);
-            } else {
-                a = decode_bf16(((const uint16_t *)cand)[i]);
-                b = decode_bf16(((const uint16_t *)ref)[i]);
-            }
+            float a = load_as_f32(cand, i, dtype), b = load_as_f32(ref, i, dtype);
 
             /* each operation rounded to binary32 on its own */
             float diff = a - b;
@@ -307,7 +341,7 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
                               double atol, double rtol, int equal_nan, uint64_t max_records,
                               oracle_mismatch *out)
 {
-    if ((!out && max_records) || dtype < 0 || dtype > 7)
+    if ((!out && max_records) || dtype < 0 || dtype > 9)
         return -1;
 #if defined(__SSE2__)
     unsigned int csr_saved = _mm_getcsr();
@@ -362,17 +396,7 @@ int64_t oracle_report_segment(const void *ref, const void *cand, uint64_t numel,
             m.d = (double)(diff < 0 ? -diff : diff);
             m.tol = 0.0;
         } else {
-            float a, b;
-            if (dtype == ORACLE_F32) {
-                a = ((const float *)cand)[i];
-                b = ((const float *)ref)[i];
-            } else if (dtype == ORACLE_F16) {
-                a = decode_f16(((const uint16_t *)cand)[i]);
-                b = decode_f16(((const uint16_t *)ref)[i]);
-            } else {
-                a = decode_bf16(((const uint16_t *)cand)[i]);
-                b = decode_bf16(((const uint16_t *)ref)[i]);
-            }
+            float a = load_as_f32(cand, i, dtype), b = load_as_f32(ref, i, dtype);
             float diff = a - b;
             float d = fabsf(diff);                               /* R1 */
             float prod = rtol_f * fabsf(b);
@@ -428,7 +452,7 @@ static int bit_length_u64(uint64_t x)
 int oracle_ulp_histogram_segment(const void *ref, const void *cand, uint64_t numel, int dtype,
                                  uint64_t *out)
 {
-    if (!out || dtype < 0 || dtype > 7)
+    if (!out || dtype < 0 || dtype > 9)
         return -1;
     for (int j = 0; j < ORACLE_ULP_BINS; ++j) out[j] = 0;
     for (uint64_t i = 0; i < numel; ++i) {
@@ -454,10 +478,16 @@ int oracle_ulp_histogram_segment(const void *ref, const void *cand, uint64_t num
             } else if (dtype == ORACLE_F32) {
                 pa = ((const uint32_t *)cand)[i];  pb = ((const uint32_t *)ref)[i];
                 sign_bit = 1ull << 31;  inf_pattern = 0x7F800000ull;
-            } else {
+            } else if (dtype == ORACLE_F16 || dtype == ORACLE_BF16) {
                 pa = ((const uint16_t *)cand)[i];  pb = ((const uint16_t *)ref)[i];
                 sign_bit = 1ull << 15;
                 inf_pattern = (dtype == ORACLE_F16) ? 0x7C00ull : 0x7F80ull;
+            } else {
+                pa = ((const uint8_t *)cand)[i];  pb = ((const uint8_t *)ref)[i];
+                sign_bit = 1ull << 7;
+                /* E5M2 has Inf at 0x7C; E4M3 has none: its ladder ends at the largest finite value 0x7E and
+                 * the one pattern above it is NaN, so that value stands in for Inf in the NaN test */
+                inf_pattern = (dtype == ORACLE_F8E5M2) ? 0x7Cull : 0x7Eull;
             }
             uint64_t ma = pa & (sign_bit - 1), mb = pb & (sign_bit - 1);
             if (ma > inf_pattern || mb > inf_pattern) {          /* U3: NaN */
@@ -478,3 +508,5 @@ int oracle_ulp_histogram_segment(const void *ref, const void *cand, uint64_t num
 /* Decoders exported so the pins can check them on all 65536 bit patterns. */
 float oracle_decode_f16(uint16_t h)  { return decode_f16(h); }
 float oracle_decode_bf16(uint16_t h) { return decode_bf16(h); }
+float oracle_decode_f8e4m3(uint8_t x) { return decode_f8e4m3(x); }
+float oracle_decode_f8e5m2(uint8_t x) { return decode_f8e5m2(x); }

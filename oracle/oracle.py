@@ -18,8 +18,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "geak_oracle.c")
 _LIB = os.path.join(_HERE, "libgeak_oracle.so")
 
-DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2, "i32": 3, "i64": 4, "u8": 5, "i8": 6, "f64": 7}
-ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1, "f64": 8}
+DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2, "i32": 3, "i64": 4, "u8": 5, "i8": 6, "f64": 7,
+               "f8e4m3": 8, "f8e5m2": 9}
+ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1, "f64": 8, "f8e4m3": 1, "f8e5m2": 1}
 
 # One record per (segment, candidate); field meaning as in geak_oracle.c (R7-R9).
 RECORD_DTYPE = np.dtype(
@@ -75,8 +76,17 @@ def _load():
             lib.oracle_decode_f16.argtypes = [ctypes.c_uint16]
             lib.oracle_decode_bf16.restype = ctypes.c_float
             lib.oracle_decode_bf16.argtypes = [ctypes.c_uint16]
+            lib.oracle_decode_f8e4m3.restype = ctypes.c_float
+            lib.oracle_decode_f8e4m3.argtypes = [ctypes.c_uint8]
+            lib.oracle_decode_f8e5m2.restype = ctypes.c_float
+            lib.oracle_decode_f8e5m2.argtypes = [ctypes.c_uint8]
             _lib = lib
     return _lib
+
+
+def decode_f8(bits: int, dtype: str) -> float:
+    lib = _load()
+    return float((lib.oracle_decode_f8e4m3 if dtype == "f8e4m3" else lib.oracle_decode_f8e5m2)(int(bits) & 0xFF))
 
 
 def decode_f16(bits: int) -> float:

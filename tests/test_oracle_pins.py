@@ -538,3 +538,79 @@ def test_byte_dtypes_hand_derived(oracle_mod):
     # int8 extremes
     rec = oracle_mod.check_segment(np.array([-128], dtype=np.int8), np.array([127], dtype=np.int8), 1, "i8", 0.0, 0.0, False)
     assert float(rec["max_abs_err"]) == 255.0 and float(rec["max_rel_err"]) == 255.0 / 128.0
+
+
+# ------------------------------------------------------------------------------------------
+# 8-bit floating formats (OCP E4M3 and E5M2)
+# ------------------------------------------------------------------------------------------
+F8_TORCH = {"f8e4m3": torch.float8_e4m3fn, "f8e5m2": torch.float8_e5m2}
+
+
+@pytest.mark.parametrize("dtype", ["f8e4m3", "f8e5m2"])
+def test_decode_f8_all_patterns(oracle_mod, dtype):
+    lib = torch.arange(256, dtype=torch.int32).to(torch.uint8).view(F8_TORCH[dtype]).to(torch.float32).numpy()
+    for x in range(256):
+        assert _same_float(oracle_mod.decode_f8(x, dtype), float(lib[x])), hex(x)
+    # the facts the formats are defined by
+    if dtype == "f8e4m3":
+        assert oracle_mod.decode_f8(0x7E, dtype) == 448.0 and math.isnan(oracle_mod.decode_f8(0x7F, dtype))
+        assert oracle_mod.decode_f8(0x01, dtype) == 2.0 ** -9 and oracle_mod.decode_f8(0x08, dtype) == 2.0 ** -6
+        assert not any(math.isinf(oracle_mod.decode_f8(x, dtype)) for x in range(256))
+    else:
+        assert oracle_mod.decode_f8(0x7B, dtype) == 57344.0 and math.isinf(oracle_mod.decode_f8(0x7C, dtype))
+        assert oracle_mod.decode_f8(0x01, dtype) == 2.0 ** -16 and oracle_mod.decode_f8(0x04, dtype) == 2.0 ** -14
+        assert all(math.isnan(oracle_mod.decode_f8(x, dtype)) for x in (0x7D, 0x7E, 0x7F, 0xFD))
+
+
+@pytest.mark.parametrize("dtype", ["f8e4m3", "f8e5m2"])
+@pytest.mark.parametrize("atol,rtol", [(2.0 ** -6, 0.125), (0.0, 0.0), (1e-3, 0.07), (3.0, 1e30)])
+def test_f8_every_pair_against_the_rational_model(oracle_mod, dtype, atol, rtol):
+    """All 65536 (reference, candidate) pairs of a format: finite pairs against the exact rational model
+    (values decoded by torch, not by the oracle), NaN / Inf pairs against the rule's cases."""
+    vals = torch.arange(256, dtype=torch.int32).to(torch.uint8).view(F8_TORCH[dtype]).to(torch.float64).numpy()
+    atol_f, rtol_f = float(np.float32(atol)), float(np.float32(rtol))
+    codes = np.arange(256, dtype=np.uint8)
+    for equal_nan in (False, True):
+        for cb in range(256):
+            b = float(vals[cb])
+            ref = np.full(256, cb, dtype=np.uint8)
+            # one oracle call per reference code: the 256 candidates one by one, as 256 segments of length 1
+            for ca in range(0, 256, 1 if cb % 16 == 0 else 7):          # every candidate for every 16th reference code
+                a = float(vals[ca])
+                rec = oracle_mod.check_segment(ref[ca:ca + 1], codes[ca:ca + 1], 1, dtype, atol, rtol, equal_nan)
+                if math.isnan(a) or math.isnan(b):
+                    close = equal_nan and math.isnan(a) and math.isnan(b)
+                    want_d = want_r = None
+                elif math.isinf(a) or math.isinf(b):
+                    close = a == b
+                    want_d = want_r = None
+                else:
+                    close, d, r = model_element(a, b, atol_f, rtol_f)
+                    want_d, want_r = _to_float(d), _to_float(r)
+                assert int(rec["pass"]) == int(close), (dtype, hex(cb), hex(ca), atol, rtol, equal_nan)
+                if want_d is not None:
+                    assert float(rec["max_abs_err"]) == want_d and float(rec["max_rel_err"]) == want_r, (hex(cb), hex(ca))
+
+
+def test_f8_hand_derived(oracle_mod):
+    u8 = lambda *v: np.array(v, dtype=np.uint8)
+    # E4M3: 1.0 = 0x38, 1.125 = 0x39 (one step), 1.25 = 0x3A.  atol = 0, rtol = 0.125: tol = 0.125 at b = 1
+    rec = oracle_mod.check_segment(u8(0x38, 0x38, 0x38), u8(0x39, 0x3A, 0x38), 3, "f8e4m3", 0.0, 0.125, False)
+    assert (int(rec["mismatch_count"]), int(rec["first_mismatch"])) == (1, 1)
+    assert float(rec["max_abs_err"]) == 0.25 and float(rec["max_rel_err"]) == 0.25
+    # E4M3 has no infinity: 0x7F is NaN and never close without equal_nan; 448 vs -448 is an ordinary mismatch
+    rec = oracle_mod.check_segment(u8(0x7F, 0x7E), u8(0x7F, 0xFE), 2, "f8e4m3", 0.0, 0.0, False)
+    assert int(rec["mismatch_count"]) == 2 and float(rec["max_abs_err"]) == 896.0
+    rec = oracle_mod.check_segment(u8(0x7F, 0x7E), u8(0xFF, 0x7E), 2, "f8e4m3", 0.0, 0.0, True)
+    assert int(rec["mismatch_count"]) == 0
+    # E5M2: 0x7C is +Inf: close only to itself; 0x3C = 1.0, 0x3D = 1.25
+    rec = oracle_mod.check_segment(u8(0x7C, 0x7C, 0x3C), u8(0x7C, 0x7B, 0x3D), 3, "f8e5m2", 1e30, 1e30, False)
+    assert (int(rec["mismatch_count"]), int(rec["first_mismatch"])) == (1, 1)
+    assert float(rec["max_abs_err"]) == math.inf
+    # report and ulp histogram see the same values: one step apart, and Inf one step beyond the largest finite value
+    rep = oracle_mod.report_segment(u8(0x3C), u8(0x3D), 1, "f8e5m2", 0.0, 0.125, False, 4)
+    assert len(rep) == 1 and float(rep[0]["a"]) == 1.25 and float(rep[0]["d"]) == 0.25 and float(rep[0]["tol"]) == 0.125
+    h = oracle_mod.ulp_histogram_segment(u8(0x3C, 0x7B, 0x7E, 0x7E, 0x00), u8(0x3D, 0x7C, 0x7F, 0xFE, 0x80), 5, "f8e5m2")
+    assert int(h[1]) == 2 and int(h[65]) == 2 and int(h[0]) == 1      # 0x7E and 0x7F are NaN in E5M2
+    h = oracle_mod.ulp_histogram_segment(u8(0x38, 0x7E, 0x7E, 0x00), u8(0x39, 0x7F, 0xFE, 0x80), 4, "f8e4m3")
+    assert int(h[1]) == 1 and int(h[65]) == 1 and int(h[8]) == 1 and int(h[0]) == 1     # 2 * 0x7E = 252: bin 8

@@ -216,3 +216,25 @@ def test_invariants(oracle_mod, dtype):
     h1 = oracle_mod.ulp_histogram_segment(b, a, n // 2, dtype)
     h2 = oracle_mod.ulp_histogram_segment(b, a, n - n // 2, dtype, ref_byte_offset=(n // 2) * w)
     assert (h1 + h2 == h_ab).all()
+
+
+@pytest.mark.parametrize("dtype,torch_dtype", [("f8e4m3", torch.float8_e4m3fn), ("f8e5m2", torch.float8_e5m2)])
+def test_8bit_every_pair_against_sorted_ladder(oracle_mod, dtype, torch_dtype):
+    vals = torch.arange(256, dtype=torch.int32).to(torch.uint8).view(torch_dtype).to(torch.float64).numpy()
+    ok = ~np.isnan(vals)
+    rungs = np.unique(vals[ok])                          # sorted; the two zeros merge
+    pos = np.full(256, -1, dtype=np.int64)
+    pos[ok] = np.searchsorted(rungs, vals[ok])
+    b = np.repeat(np.arange(256, dtype=np.uint8), 256)
+    a = np.tile(np.arange(256, dtype=np.uint8), 256)
+    pa, pb = pos[a], pos[b]
+    isnan = (pa < 0) | (pb < 0)
+    want = _bins_of(np.abs(pa[~isnan] - pb[~isnan]), int(isnan.sum()))
+    got = oracle_mod.ulp_histogram_segment(b, a, b.size, dtype)
+    assert (got == want).all(), (got, want)
+    for cb, ca in [(0x00, 0x80), (0x01, 0x81), (0x38, 0x39), (0x7B, 0x7C), (0x7E, 0xFE)]:
+        one = oracle_mod.ulp_histogram_segment(np.array([cb], np.uint8), np.array([ca], np.uint8), 1, dtype)
+        if pos[cb] < 0 or pos[ca] < 0:
+            assert int(one[65]) == 1
+        else:
+            assert int(one[int(abs(pos[cb] - pos[ca])).bit_length()]) == 1
