@@ -9,7 +9,9 @@
  * (section 3.3); the check runs once per candidate x unit test x refinement iteration x parallel
  * run (sections 4.1, 4.2, 5.2).  The paper gives no formula, so this library fixes one:
  *
- *   fp32, fp16, bf16: a = candidate element, b = reference element, all steps in IEEE binary32,
+ *   fp32, fp16, bf16 and the 8-bit formats E4M3 (no infinities, one NaN pattern per sign, largest value
+ *   448) and E5M2 (an IEEE-like format), each widened exactly to binary32: a = candidate element,
+ *   b = reference element, all steps in IEEE binary32,
  *   round-to-nearest-even, one rounding per step, no fused multiply-add, subnormals honoured:
  *       d = |a - b|,  tol = atol_f + (rtol_f * |b|),  close <=> d <= tol
  *       a or b NaN   : close <=> equal_nan and both NaN
@@ -56,7 +58,8 @@ typedef enum {
 } geak_status;
 
 typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64 = 4,
-               GEAK_U8 = 5 /* also boolean masks stored as bytes */, GEAK_I8 = 6, GEAK_F64 = 7 } geak_dtype;
+               GEAK_U8 = 5 /* also boolean masks stored as bytes */, GEAK_I8 = 6, GEAK_F64 = 7,
+               GEAK_F8E4M3 = 8, GEAK_F8E5M2 = 9 /* the 8-bit formats of the OCP 8-bit floating point specification */ } geak_dtype;
 
 #define GEAK_MAX_CANDIDATES 256
 #define GEAK_MAX_SEGMENT_NUMEL (1ull << 40)

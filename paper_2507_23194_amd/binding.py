@@ -21,13 +21,14 @@ BUILD_SCRIPT = os.path.join(_HERE, "csrc", "build.sh")
 GEAK_OK = 0
 GEAK_EINVAL, GEAK_EDTYPE, GEAK_EALIGN, GEAK_EBOUNDS, GEAK_ENOMEM, GEAK_EWORKSPACE, GEAK_EHIP = 1, 2, 3, 4, 5, 6, 7
 GEAK_F32, GEAK_F16, GEAK_BF16, GEAK_I32, GEAK_I64, GEAK_U8, GEAK_I8, GEAK_F64 = 0, 1, 2, 3, 4, 5, 6, 7
+GEAK_F8E4M3, GEAK_F8E5M2 = 8, 9
 GEAK_MAX_CANDIDATES = 256
 GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED = 1, 2, 4, 8
 GEAK_ULP_BINS = 66
 
 DTYPE_CODE = {"f32": GEAK_F32, "f16": GEAK_F16, "bf16": GEAK_BF16, "i32": GEAK_I32, "i64": GEAK_I64,
-              "u8": GEAK_U8, "i8": GEAK_I8, "f64": GEAK_F64}
-ELEM_SIZE = {GEAK_F32: 4, GEAK_F16: 2, GEAK_BF16: 2, GEAK_I32: 4, GEAK_I64: 8, GEAK_U8: 1, GEAK_I8: 1, GEAK_F64: 8}
+              "u8": GEAK_U8, "i8": GEAK_I8, "f64": GEAK_F64, "f8e4m3": GEAK_F8E4M3, "f8e5m2": GEAK_F8E5M2}
+ELEM_SIZE = {GEAK_F32: 4, GEAK_F16: 2, GEAK_BF16: 2, GEAK_I32: 4, GEAK_I64: 8, GEAK_U8: 1, GEAK_I8: 1, GEAK_F64: 8, GEAK_F8E4M3: 1, GEAK_F8E5M2: 1}
 
 SEGMENT_DTYPE = np.dtype([("byte_offset", "<u8"), ("numel", "<u8"), ("dtype", "<i4"), ("reserved", "<i4")])
 RESULT_DTYPE = np.dtype([("pass", "<i4"), ("reserved", "<i4"), ("mismatch_count", "<u8"),

@@ -68,6 +68,8 @@ template <> struct Traits<GEAK_I64>  { static constexpr int E = 2, W = 8; };
 template <> struct Traits<GEAK_U8>   { static constexpr int E = 16, W = 1; };
 template <> struct Traits<GEAK_I8>   { static constexpr int E = 16, W = 1; };
 template <> struct Traits<GEAK_F64>  { static constexpr int E = 2, W = 8; };
+template <> struct Traits<GEAK_F8E4M3> { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_F8E5M2> { static constexpr int E = 16, W = 1; };
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ double bits_d(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(double, (u64)lo | ((u64)hi << 32)); }
@@ -142,10 +144,22 @@ __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, i
     return q;
 }
 
+// The 8-bit floating formats are widened by the conversion instructions (v_cvt_f32_fp8 for E4M3,
+// v_cvt_f32_bf8 for E5M2), which on gfx950 implement the OCP formats: NaN and, for E5M2, the
+// infinities arrive as such.  BYTE selects the byte of the word.
+template <int DT, int BYTE>
+__device__ __forceinline__ float f8_to_f32(uint32_t word)
+{
+    if constexpr (DT == GEAK_F8E4M3) return __builtin_amdgcn_cvt_f32_fp8((int)word, BYTE);
+    else return __builtin_amdgcn_cvt_f32_bf8((int)word, BYTE);
+}
+
 // One element straight from memory, decoded exactly to binary32 (floating dtypes).
 __device__ __forceinline__ float load_elem_f(const unsigned char *base, u64 idx, int dtype)
 {
     if (dtype == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
+    if (dtype == GEAK_F8E4M3) return f8_to_f32<GEAK_F8E4M3, 0>(base[idx]);
+    if (dtype == GEAK_F8E5M2) return f8_to_f32<GEAK_F8E5M2, 0>(base[idx]);
     const uint16_t h = reinterpret_cast<const uint16_t *>(base)[idx];
     if (dtype == GEAK_F16) return (float)__builtin_bit_cast(_Float16, h);
     return bits_f((uint32_t)h << 16);

@@ -20,7 +20,7 @@ inline int elem_size(int dtype)
     switch (dtype) {
     case GEAK_F16: case GEAK_BF16: return 2;
     case GEAK_I64: case GEAK_F64: return 8;
-    case GEAK_U8: case GEAK_I8: return 1;
+    case GEAK_U8: case GEAK_I8: case GEAK_F8E4M3: case GEAK_F8E5M2: return 1;
     default: return 4;
     }
 }
@@ -161,7 +161,7 @@ inline uint32_t ulp_slots_of(int dtype)
 {
     switch (dtype) {
     case GEAK_F16: case GEAK_BF16: return 18;            // distances below 2^16
-    case GEAK_U8: case GEAK_I8: return 10;               // at most 255
+    case GEAK_U8: case GEAK_I8: case GEAK_F8E4M3: case GEAK_F8E5M2: return 10;     // at most 255
     case GEAK_F64: case GEAK_I64: return 66;             // below 2^64
     default: return 34;                                  // binary32, int32: below 2^32
     }

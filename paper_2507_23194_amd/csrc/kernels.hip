@@ -955,6 +955,139 @@ struct DoubleItem {
     }
 };
 
+// ---- 8-bit floating formats: sixteen elements per 16-byte vector, the binary32 rule ----------------------
+// A lane holds 64 elements of the slice: neither the decoded reference nor its tolerances fit the
+// registers (nor, with four blocks per compute unit, the LDS).  The reference stays packed, is widened
+// again for every candidate (one conversion instruction per element) and the tolerance is computed
+// again (one multiplication, one addition): nine vector instructions per element, against five for
+// the wider dtypes, and a budget of 4.9 per byte at the memory's speed -- this path is bound by
+// arithmetic.  Elements the bare inequality cannot judge (b NaN, b +-Inf, tolerance overflowed) are
+// only marked when the slice is staged; vectors that hold one are counted again with the full rule.
+template <int DT> struct F8Vec { u32x4 q; };
+template <int DT>
+__device__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel, MaxPair *rec_in);
+
+template <int DT>
+struct Fp8Item {
+    typedef float Hint;
+    static __device__ __forceinline__ float hint_from_bits(u64 bits) { return (float)__builtin_bit_cast(double, bits); }
+    static constexpr int E = 16;
+    static constexpr bool kRaiseOutOfLine = true;
+    uint32_t bref[kVecPerLane * 4];
+    float atol_f, rtol_f;           // wave-uniform
+    u64 poisoned_slots;             // wave-uniform: bit i set if any lane's element i is poisoned
+    __device__ __forceinline__ void attach_lds(uint32_t, int) {}
+
+    template <int e> static __device__ __forceinline__ float value(const uint32_t *words) { return f8_to_f32<DT, e & 3>(words[e >> 2]); }
+    template <int e> static __device__ __forceinline__ float value(const u32x4 &q) { return f8_to_f32<DT, e & 3>(q[e >> 2]); }
+
+    template <int V>
+    __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &tolerance)
+    {
+        if constexpr (V == 0) { poisoned_slots = 0; atol_f = tolerance.atol_f; rtol_f = tolerance.rtol_f; }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            const float x = value<e>(q);
+            const float prod = rtol_f * __builtin_fabsf(x);
+            const float t = atol_f + prod;
+            if (__builtin_amdgcn_ballot_w64(!(t < kInfF))) poisoned_slots |= 1ull << (V * E + e);
+        });
+    }
+
+    template <int V, bool AHEAD = true>
+    __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float max_rel, uint32_t &suspects,
+                                                u64 &trip_abs, u64 &trip_rel, int equal_nan) const
+    {
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            const float x = value<e>(bref + V * 4);
+            const float d = value<e>(q) - x;
+            const float prod = rtol_f * __builtin_fabsf(x);
+            const float t = atol_f + prod;
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d) <= t)));
+            trip_abs |= __builtin_amdgcn_ballot_w64(__builtin_fabsf(d) > max_abs);
+            trip_rel |= negative_mask(__builtin_fmaf(max_rel, __builtin_fabsf(x), -__builtin_fabsf(d)));
+            asm volatile("" : "+s"(trip_abs), "+s"(trip_rel));
+        });
+        if constexpr (AHEAD) {
+            if ((poisoned_slots >> (V * E)) & 0xFFFFull) suspects += (uint32_t)recount<V>(q, equal_nan);
+        }
+    }
+
+    // For the marked element positions of vector V: what the full rule counts minus what the bare
+    // inequality counted above.
+    template <int V>
+    __device__ __forceinline__ int recount(const u32x4 &q, int equal_nan) const
+    {
+        int delta = 0;
+        static_for<E>([&](auto idx) {
+            constexpr int e = decltype(idx)::value;
+            if ((poisoned_slots >> (V * E + e)) & 1ull) {
+                const float x = value<e>(bref + V * 4), a = value<e>(q);
+                const float prod = rtol_f * __builtin_fabsf(x);
+                const float t = atol_f + prod;
+                const float d = __builtin_fabsf(a - x);
+                delta += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!close_exact(a, x, atol_f, rtol_f, equal_nan)));
+                delta -= __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(d <= t)));
+            }
+        });
+        return delta;
+    }
+    template <int V>
+    __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &q, int equal_nan) const
+    {
+        return (uint32_t)(-recount<V>(q, equal_nan));        // the caller subtracts
+    }
+
+    template <int V>
+    __device__ __forceinline__ void raise_call(const u32x4 &q, float &max_abs, float &max_rel, MaxPair *rec) const
+    {
+        u32x4 b;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
+        const FloatPair out = raise_vector_f8<DT>(q, b, max_abs, max_rel, rec);
+        max_abs = out.abs;
+        max_rel = out.rel;
+    }
+    template <int V>
+    __device__ __forceinline__ void raise_vec(const u32x4 &q, float &max_abs, float &max_rel, MaxPair *rec, int) const
+    {
+        raise_call<V>(q, max_abs, max_rel, rec);
+    }
+};
+
+template <int DT>
+__device__ __noinline__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel,
+                                                  MaxPair *rec_in)
+{
+    MaxPair *rec = uniform_ptr(rec_in);
+    float dm = max_abs, rm = max_rel;
+    static_for<16>([&](auto idx) {
+        constexpr int e = decltype(idx)::value;
+        const float x = f8_to_f32<DT, e & 3>(b[e >> 2]);
+        const float d = __builtin_fabsf(f8_to_f32<DT, e & 3>(q[e >> 2]) - x);
+        const float babs = __builtin_fabsf(x);
+        dm = (d > dm) ? d : dm;                                          // false for NaN: skipped
+        const bool hit = (rm < kInfF) && may_raise_rel(rm, babs, d);     // implies d > 0
+        if (__builtin_amdgcn_ballot_w64(hit)) {
+            const float r = d / babs;                                    // correctly rounded; d/0 = +Inf
+            rm = (hit && r > rm) ? r : rm;
+        }
+    });
+    dm = wave_max_f(dm);
+    rm = wave_max_f(rm);
+    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
+        if (dm > max_abs) publish_max(&rec->abs, (double)dm);
+        if (rm > max_rel) publish_max(&rec->rel, (double)rm);
+    }
+    FloatPair out;
+    out.abs = dm;
+    out.rel = rm;
+    return out;
+}
+
 // ---- uint8 / int8: sixteen elements per 16-byte vector, exact equality ---------------------------
 __device__ __forceinline__ uint32_t wave_sum_u(uint32_t x)
 {
@@ -1062,6 +1195,8 @@ template <> struct ItemOf<GEAK_I8> { typedef ByteItem<true> type; };
 template <> struct ItemOf<GEAK_I32> { typedef IntItem type; };
 template <> struct ItemOf<GEAK_I64> { typedef Int64Item type; };
 template <> struct ItemOf<GEAK_F64> { typedef DoubleItem type; };
+template <> struct ItemOf<GEAK_F8E4M3> { typedef Fp8Item<GEAK_F8E4M3> type; };
+template <> struct ItemOf<GEAK_F8E5M2> { typedef Fp8Item<GEAK_F8E5M2> type; };
 
 __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 {
@@ -1118,8 +1253,9 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
 {
     u64 trip_abs = 0, trip_rel = 0;
     ref.template compare_vec<V, !OUTLINE>(slot, max_abs, max_rel, bad, trip_abs, trip_rel, equal_nan);
-    if constexpr (OUTLINE && (DT == GEAK_F32 || DT == GEAK_F16 || DT == GEAK_BF16 || DT == GEAK_F64)) {      // only floating items poison slots
-        constexpr uint32_t kVecMask = ((1u << Traits<DT>::E) - 1u) << (V * Traits<DT>::E);
+    if constexpr (OUTLINE && (DT == GEAK_F32 || DT == GEAK_F16 || DT == GEAK_BF16 || DT == GEAK_F64 || DT == GEAK_F8E4M3 ||
+                              DT == GEAK_F8E5M2)) {      // only floating items poison slots
+        constexpr u64 kVecMask = ((Traits<DT>::E == 16) ? 0xFFFFull : ((1ull << Traits<DT>::E) - 1ull)) << (V * Traits<DT>::E);
         if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_call<V>(slot, equal_nan);
     }
     if (max_rel == (typename Item::Hint)kInfF) trip_rel = 0;       // nothing exceeds +Inf
@@ -1390,6 +1526,8 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_I64:  next_j = process_run<GEAK_I64>(r, st); break;
                 case GEAK_U8:   next_j = process_run<GEAK_U8>(r, st); break;
                 case GEAK_F64:  next_j = process_run<GEAK_F64>(r, st); break;
+                case GEAK_F8E4M3: next_j = process_run<GEAK_F8E4M3>(r, st); break;
+                case GEAK_F8E5M2: next_j = process_run<GEAK_F8E5M2>(r, st); break;
                 default:        next_j = process_run<GEAK_I8>(r, st); break;
                 }
             } else {
@@ -1401,6 +1539,8 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_I64:  process_tail<GEAK_I64>(r, st); break;
                 case GEAK_U8:   process_tail<GEAK_U8>(r, st); break;
                 case GEAK_F64:  process_tail<GEAK_F64>(r, st); break;
+                case GEAK_F8E4M3: process_tail<GEAK_F8E4M3>(r, st); break;
+                case GEAK_F8E5M2: process_tail<GEAK_F8E5M2>(r, st); break;
                 default:        process_tail<GEAK_I8>(r, st); break;
                 }
                 next_j = it.next;
@@ -1559,6 +1699,7 @@ template <int DT>
 __device__ __forceinline__ float elem_f(const unsigned char *base, u64 idx)
 {
     if constexpr (DT == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
+    else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2) return f8_to_f32<DT, 0>(base[idx]);
     else if constexpr (DT == GEAK_F16) return (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t *>(base)[idx]);
     else return bits_f((uint32_t)reinterpret_cast<const uint16_t *>(base)[idx] << 16);
 }
@@ -1676,6 +1817,8 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     case GEAK_I64:  report_pair<GEAK_I64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     case GEAK_U8:   report_pair<GEAK_U8>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     case GEAK_F64:  report_pair<GEAK_F64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_F8E4M3: report_pair<GEAK_F8E4M3>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
+    case GEAK_F8E5M2: report_pair<GEAK_F8E5M2>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     default:        report_pair<GEAK_I8>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
     }
 }

@@ -30,7 +30,7 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
     uint64_t total_bytes = 0;
     for (uint64_t s = 0; s < nsegs; ++s) {
         const geak_segment &g = segs[s];
-        if (g.dtype < GEAK_F32 || g.dtype > GEAK_F64) return GEAK_EDTYPE;
+        if (g.dtype < GEAK_F32 || g.dtype > GEAK_F8E5M2) return GEAK_EDTYPE;
         if (g.reserved != 0) return GEAK_EINVAL;
         // the rule of every dtype but binary64 runs in binary32: its tolerances must be finite there too
         if (g.dtype != GEAK_F64 && (std::isinf((float)tols[s].atol) || std::isinf((float)tols[s].rtol))) return GEAK_EINVAL;
@@ -128,7 +128,7 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
         const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
         const uint64_t slices = (uint64_t)num_candidates + 1;
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
-            const uint64_t per_slice = (it.dtype == GEAK_F32 || it.dtype == GEAK_F64) ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
+            const uint64_t per_slice = (it.dtype == GEAK_F8E4M3 || it.dtype == GEAK_F8E5M2) ? 40 : (it.dtype == GEAK_F32 || it.dtype == GEAK_F64) ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
             if (!(it.flags & GEAK_ITEM_ALIGNED)) return 2 * per_slice * slices;      // element-wise path
             if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 140;
             return per_slice * slices + (starts_run ? 100 : 0);

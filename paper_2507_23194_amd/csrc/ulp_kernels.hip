@@ -34,7 +34,8 @@ template <int DT> struct UlpTraits {
 template <> struct UlpTraits<GEAK_F64> { typedef long long Ord; typedef u64 Dist; };
 template <> struct UlpTraits<GEAK_I64> { typedef long long Ord; typedef u64 Dist; };
 
-template <int DT> constexpr bool kUlpFloating = (DT == GEAK_F32 || DT == GEAK_F16 || DT == GEAK_BF16 || DT == GEAK_F64);
+template <int DT> constexpr bool kUlpFloating = (DT == GEAK_F32 || DT == GEAK_F16 || DT == GEAK_BF16 || DT == GEAK_F64 ||
+                                                DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2);
 
 // the magnitude pattern of +Inf, in the ord type
 template <int DT> __device__ __forceinline__ typename UlpTraits<DT>::Ord ulp_inf()
@@ -42,6 +43,8 @@ template <int DT> __device__ __forceinline__ typename UlpTraits<DT>::Ord ulp_inf
     if constexpr (DT == GEAK_F32) return 0x7F800000;
     else if constexpr (DT == GEAK_F16) return 0x7C00;
     else if constexpr (DT == GEAK_BF16) return 0x7F80;
+    else if constexpr (DT == GEAK_F8E5M2) return 0x7C;
+    else if constexpr (DT == GEAK_F8E4M3) return 0x7E;      // no infinities: the ladder ends at the largest finite value, the pattern above it is NaN
     else return 0x7FF0000000000000ll;
 }
 
@@ -61,6 +64,10 @@ __device__ __forceinline__ typename UlpTraits<DT>::Ord ulp_ord(const u32x4 &q, i
         const u64 bits = (u64)q[2 * e] | ((u64)q[2 * e + 1] << 32);
         const long long mag = (long long)(bits & 0x7FFFFFFFFFFFFFFFull);
         return ((long long)bits < 0) ? -mag : mag;
+    } else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2) {
+        const uint32_t v = (q[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+        const int mag = (int)(v & 0x7Fu);
+        return (v & 0x80u) ? -mag : mag;
     } else if constexpr (DT == GEAK_I32) {
         return (int)q[e];
     } else if constexpr (DT == GEAK_I64) {
@@ -394,29 +401,44 @@ template <int DT> struct UlpRef16 {
     }
 };
 
-// bytes: nothing staged but the vector itself; words that are equal in every lane are counted at once
+// bytes (integers and the 8-bit floating formats): nothing staged but the vector itself; words that
+// are equal in every lane are counted at once -- unless the reference vector holds a NaN, whose
+// equal copy in a candidate is not at distance 0 but in the NaN bin.
 template <int DT> struct UlpRefBytes {
     typedef UlpCounts Counts;
     u32x4 raw[kVecPerLane];
+    uint32_t nan_vectors;
     static __device__ __forceinline__ Counts zero() { return Counts{0u, 0u, 0u, 0u}; }
     static __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane)
     {
         ulp_commit(c, (uint32_t)(kWaveSize * kVecPerLane * 16) - elements, row, lane);
     }
-    template <int V> __device__ __forceinline__ void stage(const u32x4 &q) { raw[V] = q; }
-    template <int V> __device__ __forceinline__ void compare(const u32x4 &q, UlpCounts &c, GEAK_AS_LDS uint32_t *row, uint32_t nslots) const
+    template <int V> __device__ __forceinline__ void stage(const u32x4 &q)
     {
+        raw[V] = q;
+        if constexpr (V == 0) nan_vectors = 0;
+        if constexpr (kUlpFloating<DT>) {
+            bool any_nan = false;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) any_nan |= ulp_is_nan<DT>(ulp_ord<DT>(q, e));
+            if (__builtin_amdgcn_ballot_w64(any_nan)) nan_vectors |= 1u << V;
+        }
+    }
+    template <int V> __device__ __forceinline__ void compare(const u32x4 &q, Counts &c, GEAK_AS_LDS uint32_t *row, uint32_t nslots) const
+    {
+        const bool ref_nan = kUlpFloating<DT> && ((nan_vectors >> V) & 1u);
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            if (__builtin_amdgcn_ballot_w64(q[w] != raw[V][w]) == 0) {
+            if (!ref_nan && __builtin_amdgcn_ballot_w64(q[w] != raw[V][w]) == 0) {
                 c.lt1 += 4 * kWaveSize; c.lt2 += 4 * kWaveSize; c.lt4 += 4 * kWaveSize; c.lt8 += 4 * kWaveSize;
                 continue;
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t va = (q[w] >> (8 * e)) & 0xFFu, vb = (raw[V][w] >> (8 * e)) & 0xFFu;
-                const int a = (DT == GEAK_I8) ? (int)(signed char)va : (int)va, b = (DT == GEAK_I8) ? (int)(signed char)vb : (int)vb;
-                ulp_classify<uint32_t, false>(ulp_dist<DT>(a, b), c, row, nslots);
+                const int a = ulp_ord<DT>(q, 4 * w + e), b = ulp_ord<DT>(raw[V], 4 * w + e);
+                uint32_t d = ulp_dist<DT>(a, b);
+                if constexpr (kUlpFloating<DT>) d |= ulp_nan_mark<DT>(a) | ulp_nan_mark<DT>(b);
+                ulp_classify<uint32_t, kUlpFloating<DT>>(d, c, row, nslots);
             }
         }
     }
@@ -427,6 +449,8 @@ template <> struct UlpRefOf<GEAK_F16> { typedef UlpRef16<GEAK_F16> type; };
 template <> struct UlpRefOf<GEAK_BF16> { typedef UlpRef16<GEAK_BF16> type; };
 template <> struct UlpRefOf<GEAK_U8> { typedef UlpRefBytes<GEAK_U8> type; };
 template <> struct UlpRefOf<GEAK_I8> { typedef UlpRefBytes<GEAK_I8> type; };
+template <> struct UlpRefOf<GEAK_F8E4M3> { typedef UlpRefBytes<GEAK_F8E4M3> type; };
+template <> struct UlpRefOf<GEAK_F8E5M2> { typedef UlpRefBytes<GEAK_F8E5M2> type; };
 
 // TAIL = false: a run of consecutive FULL items of one dtype in the wave's list, every load an
 // unguarded 16-byte load, the next item's reference slice fetched behind the last candidate.
@@ -504,12 +528,13 @@ __device__ __forceinline__ void ulp_head(const geak_item &it, const unsigned cha
         for (uint32_t i = lane; i < it.numel; i += kWaveSize) {
             uint32_t slot;
             switch (it.dtype) {
-            case GEAK_F32: case GEAK_F16: case GEAK_BF16: {
-                const uint32_t width = it.dtype == GEAK_F32 ? 4u : 2u;
-                const uint32_t pa = width == 4 ? reinterpret_cast<const uint32_t *>(cb)[i] : reinterpret_cast<const uint16_t *>(cb)[i];
-                const uint32_t pb = width == 4 ? reinterpret_cast<const uint32_t *>(rb)[i] : reinterpret_cast<const uint16_t *>(rb)[i];
-                const uint32_t sign = width == 4 ? 0x80000000u : 0x8000u;
-                const uint32_t inf = it.dtype == GEAK_F32 ? 0x7F800000u : (it.dtype == GEAK_F16 ? 0x7C00u : 0x7F80u);
+            case GEAK_F32: case GEAK_F16: case GEAK_BF16: case GEAK_F8E4M3: case GEAK_F8E5M2: {
+                const uint32_t width = it.dtype == GEAK_F32 ? 4u : (it.dtype == GEAK_F16 || it.dtype == GEAK_BF16) ? 2u : 1u;
+                const uint32_t pa = width == 4 ? reinterpret_cast<const uint32_t *>(cb)[i] : width == 2 ? reinterpret_cast<const uint16_t *>(cb)[i] : cb[i];
+                const uint32_t pb = width == 4 ? reinterpret_cast<const uint32_t *>(rb)[i] : width == 2 ? reinterpret_cast<const uint16_t *>(rb)[i] : rb[i];
+                const uint32_t sign = width == 4 ? 0x80000000u : width == 2 ? 0x8000u : 0x80u;
+                const uint32_t inf = it.dtype == GEAK_F32 ? 0x7F800000u : it.dtype == GEAK_F16 ? 0x7C00u : it.dtype == GEAK_BF16 ? 0x7F80u
+                                   : it.dtype == GEAK_F8E5M2 ? 0x7Cu : 0x7Eu;
                 const int ma = (int)(pa & (sign - 1u)), mb = (int)(pb & (sign - 1u));
                 const int oa = (pa & sign) ? -ma : ma, ob = (pb & sign) ? -mb : mb;
                 const uint32_t d = (oa > ob) ? (uint32_t)oa - (uint32_t)ob : (uint32_t)ob - (uint32_t)oa;
@@ -574,6 +599,8 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
                 case GEAK_I64:  next_j = ulp_run<GEAK_I64, false>(r, st); break;
                 case GEAK_U8:   next_j = ulp_run<GEAK_U8, false>(r, st); break;
                 case GEAK_F64:  next_j = ulp_run<GEAK_F64, false>(r, st); break;
+                case GEAK_F8E4M3: next_j = ulp_run<GEAK_F8E4M3, false>(r, st); break;
+                case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, false>(r, st); break;
                 default:        next_j = ulp_run<GEAK_I8, false>(r, st); break;
                 }
             } else {
@@ -585,6 +612,8 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
                 case GEAK_I64:  next_j = ulp_run<GEAK_I64, true>(r, st); break;
                 case GEAK_U8:   next_j = ulp_run<GEAK_U8, true>(r, st); break;
                 case GEAK_F64:  next_j = ulp_run<GEAK_F64, true>(r, st); break;
+                case GEAK_F8E4M3: next_j = ulp_run<GEAK_F8E4M3, true>(r, st); break;
+                case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, true>(r, st); break;
                 default:        next_j = ulp_run<GEAK_I8, true>(r, st); break;
                 }
             }

@@ -25,9 +25,10 @@ from dataclasses import dataclass, field
 import numpy as np
 import torch
 
-ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1, "f64": 8}
+ELEM_SIZE = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1, "f64": 8, "f8e4m3": 1, "f8e5m2": 1}
 TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32,
-               "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8, "f64": torch.float64}
+               "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8, "f64": torch.float64,
+               "f8e4m3": torch.float8_e4m3fn, "f8e5m2": torch.float8_e5m2}
 
 _CHUNK = 1 << 25  # elements generated per step, bounds temporary memory
 

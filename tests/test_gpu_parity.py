@@ -12,7 +12,8 @@ from paper_2507_23194_amd import synth
 pytestmark = pytest.mark.gpu
 
 TORCH_STORAGE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32,
-                 "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8, "f64": torch.float64}
+                 "i64": torch.int64, "u8": torch.uint8, "i8": torch.int8, "f64": torch.float64,
+                 "f8e4m3": torch.uint8, "f8e5m2": torch.uint8}
 
 
 def _to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
@@ -58,6 +59,22 @@ def test_golden_pins_on_gpu(case):
 
 def _special_case(rng, dtype, n, special=0.02):
     """Random tensors rich in NaN, +-Inf, signed zeros, subnormals, huge values and near-boundary pairs."""
+    if dtype in ("f8e4m3", "f8e5m2"):
+        # byte codes: every pattern occurs (NaN, and for E5M2 the infinities, among them); candidates are
+        # copies with some codes moved by a step or two, some replaced, some sign-flipped
+        b = rng.integers(0, 256, n).astype(np.uint8)
+        b[rng.random(n) < 0.2] = rng.choice(np.array([0x00, 0x80, 0x01, 0x7B, 0x7C, 0x7E, 0x7F, 0xFC, 0xFF], np.uint8))
+        a = b.copy()
+        step = rng.random(n) < 0.3
+        a[step] = (b[step].astype(np.int64) + rng.integers(-2, 3, int(step.sum()))).astype(np.uint8)
+        repl = rng.random(n) < 0.05
+        a[repl] = rng.integers(0, 256, int(repl.sum())).astype(np.uint8)
+        flip = rng.random(n) < 0.02
+        a[flip] ^= 0x80
+        if special > 0:
+            sp = rng.random(n) < special
+            a[sp] = rng.choice(np.array([0x7C, 0x7F, 0xFC, 0xFF, 0x7E, 0x00], np.uint8), int(sp.sum()))
+        return b, a
     if dtype in ("u8", "i8"):
         np_t = np.uint8 if dtype == "u8" else np.int8
         info = np.iinfo(np_t)
@@ -118,7 +135,7 @@ def _special_case(rng, dtype, n, special=0.02):
     return tb, ta
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64", "f8e4m3", "f8e5m2"])
 @pytest.mark.parametrize("n", [1, 63, 2048, 4097, 70001, 1 << 20])
 def test_special_values_dense(oracle_mod, dtype, n):
     print("special", dtype, n, flush=True)
@@ -285,6 +302,34 @@ def test_relative_error_margin_that_underflows_f64(oracle_mod, second):
     assert float(cpu[0, 0]["max_abs_err"]) == 3.0 and float(cpu[0, 0]["max_rel_err"]) == 1.0
     gpu = _dense_gpu(b, [a], "f64", 0.0, 0.0, False)
     _assert_same(gpu, cpu, f"underflowing margin in binary64, second element at {second}")
+
+
+@pytest.mark.parametrize("align", [1, 16])
+def test_ragged_batch_with_f8_segments(oracle_mod, align):
+    """Segments in the 8-bit floating formats (outputs of quantising kernels) among the others, starting on
+    any byte.  (The recipe's planted counts are not asserted here: where the format's spacing reaches 1,
+    the planted +0.5 is a tie that may round back to the reference.)"""
+    w = synth.config4(num_segments=96, log2_max=15.0, num_candidates=3, device="cuda", align=align, seed=24,
+                      dtypes=("f8e4m3", "f32", "f8e5m2", "f16", "f8e4m3", "u8"))
+    assert sum(dt.startswith("f8") for _, _, dt in w.segments) > 30
+    gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, f"ragged with 8-bit floats, align {align}")
+    assert sum(int(gpu[s, k]["mismatch_count"]) > 0 for s in range(gpu.shape[0]) for k in range(gpu.shape[1])) > 30
+
+
+@pytest.mark.parametrize("dtype", ["f8e4m3", "f8e5m2"])
+@pytest.mark.parametrize("atol,rtol", [(0.0, 0.0), (2.0 ** -6, 0.125), (1.0, 3e38), (0.3, 0.0)])
+def test_f8_tolerance_sweep(oracle_mod, dtype, atol, rtol):
+    """Coarse formats make exact boundaries common (d = tol with both exactly representable)."""
+    rng = np.random.default_rng(41)
+    n = 300000
+    b, a0 = _special_case(rng, dtype, n)
+    _, a1 = _special_case(rng, dtype, n, special=0.0)
+    for equal_nan in (False, True):
+        gpu = _dense_gpu(b, [a0, b.copy(), a1], dtype, atol, rtol, equal_nan)
+        cpu = oracle_mod.check_dense(b, [a0, b.copy(), a1], dtype, atol, rtol, equal_nan, threads=3).reshape(1, -1)
+        _assert_same(gpu, cpu, f"{dtype} atol={atol} rtol={rtol} equal_nan={equal_nan}")
 
 
 @pytest.mark.parametrize("align", [1, 16])

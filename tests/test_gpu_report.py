@@ -40,7 +40,7 @@ def _dense_report(b, cands, dtype, atol, rtol, equal_nan, M):
         ck.close()
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64", "f8e4m3", "f8e5m2"])
 @pytest.mark.parametrize("n", [1, 300, 2049, 70001])
 def test_report_special_values(oracle_mod, dtype, n):
     print("report", dtype, n, flush=True)

@@ -33,7 +33,7 @@ def _assert_hist(gpu, cpu, what):
                              f"gpu row {gpu[tuple(bad[:-1])]}\noracle row {cpu[tuple(bad[:-1])]}")
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64", "f8e4m3", "f8e5m2"])
 @pytest.mark.parametrize("n", [1, 63, 2049, 70001, (1 << 20) + 5])
 def test_histogram_special_values(oracle_mod, dtype, n):
     print("ulp", dtype, n, flush=True)
@@ -63,7 +63,7 @@ def test_histogram_candidate_passes(oracle_mod, dtype, K):
     _assert_hist(gpu, cpu, f"{dtype} K={K}")
 
 
-@pytest.mark.parametrize("align,dtypes", [(16, ("f32", "f16", "bf16", "i32")), (1, ("u8", "f32", "i8", "f16", "i64", "f64")),
+@pytest.mark.parametrize("align,dtypes", [(16, ("f32", "f16", "bf16", "i32")), (1, ("u8", "f32", "i8", "f16", "i64", "f64")), (1, ("f8e4m3", "f16", "f8e5m2", "u8")),
                                           (8, ("f64", "i64", "bf16"))])
 def test_histogram_ragged(oracle_mod, align, dtypes):
     print("ulp ragged", align, dtypes, flush=True)

@@ -55,7 +55,7 @@ def test_status_strings(lib):
     (dict(rtol=1e300), [(0, 4, "f32")], B.GEAK_EINVAL),          # infinite once converted to binary32
     (dict(eq=2), [(0, 4, "f32")], B.GEAK_EINVAL),
     (dict(), [], B.GEAK_EINVAL),
-    (dict(), [(0, 4, 8)], B.GEAK_EDTYPE),
+    (dict(), [(0, 4, 10)], B.GEAK_EDTYPE),
     (dict(), [(0, 4, -1)], B.GEAK_EDTYPE),
     (dict(), [(4, 4, "f64")], B.GEAK_EALIGN),
     (dict(), [(2, 4, "f32")], B.GEAK_EALIGN),
@@ -121,7 +121,7 @@ def _check_table(segs, K):
         blocks = B.geak_check_plan_blocks(plan).astype(np.int64)
         assert len(blocks) == info.grid_blocks + 1 and blocks[0] == 0 and blocks[-1] == len(items)
         assert (np.diff(blocks) > 0).all() or len(items) == 0          # no empty block, nothing past the table
-        esize = {0: 4, 1: 2, 2: 2, 3: 4, 4: 8, 5: 1, 6: 1, 7: 8}
+        esize = {0: 4, 1: 2, 2: 2, 3: 4, 4: 8, 5: 1, 6: 1, 7: 8, 8: 1, 9: 1}
         # every element of every segment is covered exactly once, in order
         cursor = {}
         for j, it in enumerate(items):
@@ -205,6 +205,7 @@ def test_work_table_dense(lib):
     _check_table([(3, 10000, "u8"), (10240, 4096, "i8")], 2)   # 4096 elements per item, a 13-byte head
     _check_table([(8, 700, "i64"), (8192, 3, "i64")], 3)  # a one-element head before the first 16-byte boundary
     _check_table([(8, 700, "f64"), (8192, 3, "f64"), (16384, 5000, "f64")], 3)
+    _check_table([(5, 9000, "f8e4m3"), (16384, 4096, "f8e5m2")], 2)
 
 
 def test_work_table_ragged_unaligned(lib):
