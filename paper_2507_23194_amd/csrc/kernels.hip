@@ -966,6 +966,9 @@ struct DoubleItem {
 template <int DT> struct F8Vec { u32x4 q; };
 template <int DT>
 __device__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel, MaxPair *rec_in);
+template <int DT>
+__device__ int recount_vector_f8(const u32x4 q, const u32x4 b, const uint32_t marked_in, const float atol_in, const float rtol_in,
+                                 const int equal_nan_in);
 
 template <int DT>
 struct Fp8Item {
@@ -1000,9 +1003,17 @@ struct Fp8Item {
     __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float max_rel, uint32_t &suspects,
                                                 u64 &trip_abs, u64 &trip_rel, int equal_nan) const
     {
+        // The packed reference words are made opaque for each candidate: otherwise the 64 widened values
+        // and their 64 tolerances are computed once per item and kept -- in scratch memory.
+        uint32_t words[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            words[w] = bref[V * 4 + w];
+            asm volatile("" : "+v"(words[w]));
+        }
         static_for<E>([&](auto idx) {
             constexpr int e = decltype(idx)::value;
-            const float x = value<e>(bref + V * 4);
+            const float x = value<e>(words);
             const float d = value<e>(q) - x;
             const float prod = rtol_f * __builtin_fabsf(x);
             const float t = atol_f + prod;
@@ -1017,23 +1028,15 @@ struct Fp8Item {
     }
 
     // For the marked element positions of vector V: what the full rule counts minus what the bare
-    // inequality counted above.
+    // inequality counted above.  A real function: inlined, its sixteen rarely taken branches cost the
+    // stream its registers.
     template <int V>
     __device__ __forceinline__ int recount(const u32x4 &q, int equal_nan) const
     {
-        int delta = 0;
-        static_for<E>([&](auto idx) {
-            constexpr int e = decltype(idx)::value;
-            if ((poisoned_slots >> (V * E + e)) & 1ull) {
-                const float x = value<e>(bref + V * 4), a = value<e>(q);
-                const float prod = rtol_f * __builtin_fabsf(x);
-                const float t = atol_f + prod;
-                const float d = __builtin_fabsf(a - x);
-                delta += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!close_exact(a, x, atol_f, rtol_f, equal_nan)));
-                delta -= __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(d <= t)));
-            }
-        });
-        return delta;
+        u32x4 b;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
+        return recount_vector_f8<DT>(q, b, (uint32_t)(poisoned_slots >> (V * E)) & 0xFFFFu, atol_f, rtol_f, equal_nan);
     }
     template <int V>
     __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &q, int equal_nan) const
@@ -1057,6 +1060,28 @@ struct Fp8Item {
         raise_call<V>(q, max_abs, max_rel, rec);
     }
 };
+
+template <int DT>
+__device__ __noinline__ int recount_vector_f8(const u32x4 q, const u32x4 b, const uint32_t marked_in, const float atol_in,
+                                              const float rtol_in, const int equal_nan_in)
+{
+    const uint32_t marked = uniform32(marked_in);
+    const float atol_f = bits_f(uniform32(f_bits(atol_in))), rtol_f = bits_f(uniform32(f_bits(rtol_in)));
+    const int equal_nan = (int)uniform32((uint32_t)equal_nan_in);
+    int delta = 0;
+    static_for<16>([&](auto idx) {
+        constexpr int e = decltype(idx)::value;
+        if (marked & (1u << e)) {
+            const float x = f8_to_f32<DT, e & 3>(b[e >> 2]), a = f8_to_f32<DT, e & 3>(q[e >> 2]);
+            const float prod = rtol_f * __builtin_fabsf(x);
+            const float t = atol_f + prod;
+            const float d = __builtin_fabsf(a - x);
+            delta += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!close_exact(a, x, atol_f, rtol_f, equal_nan)));
+            delta -= __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(d <= t)));
+        }
+    });
+    return delta;
+}
 
 template <int DT>
 __device__ __noinline__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel,
