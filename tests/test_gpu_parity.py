@@ -421,6 +421,49 @@ def test_run_argument_errors():
     assert st == B.GEAK_EHIP and plan is None
 
 
+def test_argument_errors_of_the_other_entry_points():
+    """Report, ulp histogram and verdicts reject null and misaligned pointers before anything is launched."""
+    ck = B.Checker(dense=("f16", (4096,)), num_candidates=2, atol=0, rtol=0, equal_nan=False, device=0)
+    x = torch.zeros(4096 + 16, dtype=torch.float16, device="cuda")
+    ok = x[:4096].data_ptr()
+    ws, res = ck.workspace.data_ptr(), ck.results.data_ptr()
+    assert B.geak_check_run(ck.plan, ok, [ok, ok], ws, res, 0) == B.GEAK_OK
+    scratch = torch.zeros(B.geak_check_ulp_workspace_bytes(ck.plan) + 16, dtype=torch.uint8, device="cuda")
+    hist = torch.zeros(2 * B.GEAK_ULP_BINS + 2, dtype=torch.int64, device="cuda")
+    sp, hp = scratch.data_ptr(), hist.data_ptr()
+    assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], 0, hp, 0) == B.GEAK_EINVAL
+    assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], sp, 0, 0) == B.GEAK_EINVAL
+    assert B.geak_check_ulp_histogram(ck.plan, 0, [ok, ok], sp, hp, 0) == B.GEAK_EINVAL
+    assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, 0], sp, hp, 0) == B.GEAK_EINVAL
+    assert B.geak_check_ulp_histogram(ck.plan, ok + 2, [ok, ok], sp, hp, 0) == B.GEAK_EALIGN
+    assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], sp + 4, hp, 0) == B.GEAK_EALIGN
+    assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], sp, hp + 4, 0) == B.GEAK_EALIGN
+    assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], sp, hp, 0) == B.GEAK_OK
+    torch.cuda.synchronize()
+    assert hist[:2 * B.GEAK_ULP_BINS].view(2, -1)[:, 0].tolist() == [4096, 4096]       # identical tensors: all at distance 0
+    verdict = torch.zeros(4, dtype=torch.int32, device="cuda")
+    assert B.geak_check_verdicts(ck.plan, 0, verdict.data_ptr(), 0, 0) == B.GEAK_EINVAL
+    assert B.geak_check_verdicts(ck.plan, res, 0, 0, 0) == B.GEAK_EINVAL
+    assert B.geak_check_verdicts(ck.plan, res, verdict.data_ptr() + 2, 0, 0) == B.GEAK_EALIGN
+    assert B.geak_check_verdicts(ck.plan, res, verdict.data_ptr(), 0, 0) == B.GEAK_OK
+    torch.cuda.synchronize()
+    assert verdict[:2].tolist() == [1, 1]
+    rec = torch.zeros(2 * 4 * 40, dtype=torch.uint8, device="cuda")
+    cnt = torch.zeros(2, dtype=torch.int32, device="cuda")
+    assert B.geak_check_report(ck.plan, ok, [ok, ok], ws, res, 0, rec.data_ptr(), cnt.data_ptr(), 0) == B.GEAK_EINVAL   # M = 0
+    assert B.geak_check_report(ck.plan, ok, [ok, ok], ws, res, 4, 0, cnt.data_ptr(), 0) == B.GEAK_EINVAL
+    assert B.geak_check_report(ck.plan, ok, [ok, ok], ws, res, 4, rec.data_ptr(), cnt.data_ptr(), 0) == B.GEAK_OK
+    torch.cuda.synchronize()
+    assert cnt.tolist() == [0, 0]
+    ck.close()
+    # host-only plans run nothing
+    st, plan = B.geak_check_plan([(0, 4, "f32")], 1, 0, 0, 0, -1)
+    assert st == B.GEAK_OK
+    assert B.geak_check_ulp_histogram(plan, ok, [ok], sp, hp, 0) == B.GEAK_EINVAL
+    assert B.geak_check_verdicts(plan, res, verdict.data_ptr(), 0, 0) == B.GEAK_EINVAL
+    B.geak_check_destroy(plan)
+
+
 def test_non_default_stream(oracle_mod):
     w = synth.small(1, device="cuda")
     s = torch.cuda.Stream()
