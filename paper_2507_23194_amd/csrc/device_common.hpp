@@ -174,5 +174,17 @@ __device__ __forceinline__ long long load_elem_int(const unsigned char *base, u6
     return reinterpret_cast<const signed char *>(base)[idx];
 }
 
+// Compile-time loop: f is called with Index<0>, Index<1>, ... so that the index can select a register
+// or an instruction's byte selector.
+template <int I> struct Index { static constexpr int value = I; };
+template <int N, typename F, int I = 0>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(Index<I>{});
+        static_for<N, F, I + 1>(static_cast<F &&>(f));
+    }
+}
+
 }  // namespace
 }  // namespace geak

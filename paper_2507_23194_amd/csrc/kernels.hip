@@ -311,15 +311,6 @@ __device__ __forceinline__ float f16_abs_scaled(float r, uint32_t b2)
     return e;
 }
 
-template <int I> struct Index { static constexpr int value = I; };
-template <int N, typename F, int I = 0>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(Index<I>{});
-        static_for<N, F, I + 1>(static_cast<F &&>(f));
-    }
-}
 
 // Arguments of a device function arrive in vector registers; everything here is the same for all
 // lanes, so it is moved back to scalar registers once.

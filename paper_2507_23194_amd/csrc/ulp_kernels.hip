@@ -262,12 +262,6 @@ __device__ __forceinline__ s16x2 as_s16x2(uint32_t w) { return __builtin_bit_cas
 __device__ __forceinline__ uint32_t as_word(u16x2 v) { return __builtin_bit_cast(uint32_t, v); }
 __device__ __forceinline__ uint32_t as_word(s16x2 v) { return __builtin_bit_cast(uint32_t, v); }
 
-__device__ __forceinline__ uint32_t ulp_ord_pair(uint32_t w)
-{
-    const uint32_t mag = w & 0x7FFF7FFFu;
-    const uint32_t sign = as_word(as_s16x2(w) >> (short)15);              // all ones in a negative half
-    return as_word(as_u16x2(mag ^ sign) - as_u16x2(sign));               // negated there
-}
 __device__ __forceinline__ uint32_t ulp_dist_pair(uint32_t oa2, uint32_t ob2)
 {
     const s16x2 a = as_s16x2(oa2), b = as_s16x2(ob2);
@@ -293,29 +287,50 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
 }
 
 struct UlpCounts16 {
-    uint32_t near12;          // per half, 5-bit fields: elements of this lane with d = 1 (bits 0-4) and d = 2, 3 (bits 5-9)
-    uint32_t near4;           // per half: d = 4 .. 7 (bits 0-4)
+    uint32_t near12;          // per half, 6-bit fields: elements of this lane with d = 1 (bits 0-5) and d = 2, 3 (bits 6-11)
+    uint32_t near4;           // per half: d = 4 .. 7 (bits 0-5)
     UlpCounts plain;          // what the plain path (reference vectors near Inf) counted, cumulative classes
     uint32_t far_lane;        // elements of this lane sent down the far path
 };
 
-template <int DT> struct UlpRef16 {
+// The same machinery serves the 8-bit floating formats: two bytes at a time are spread into the
+// halves of a word (one byte permute), after which only the position of the sign bit differs.
+template <int DT> struct UlpRefPacked {
     typedef UlpCounts16 Counts;
-    static constexpr uint32_t kInf = (DT == GEAK_F16) ? 0x7C00u : 0x7F80u;
-    uint32_t ob2[kVecPerLane * 4];
+    static constexpr bool kBytes = (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2);
+    static constexpr int E = Traits<DT>::E;
+    static constexpr int kPairs = E / 2;                       // pair words per vector
+    static constexpr uint32_t kMag = kBytes ? 0x7Fu : 0x7FFFu;
+    static constexpr uint32_t kInf = (DT == GEAK_F16) ? 0x7C00u : (DT == GEAK_BF16) ? 0x7F80u : (DT == GEAK_F8E5M2) ? 0x7Cu : 0x7Eu;
+    uint32_t ob2[kVecPerLane * kPairs];
     uint32_t edge_vectors;                                     // bit v: some lane's reference vector v holds a magnitude >= Inf - 8
 
     static __device__ __forceinline__ Counts zero() { return Counts{0u, 0u, UlpCounts{0u, 0u, 0u, 0u}, 0u}; }
+
+    // elements 2j and 2j + 1 of a vector, one per half of a word
+    template <int j> static __device__ __forceinline__ uint32_t pair_word(const u32x4 &q)
+    {
+        if constexpr (!kBytes) return q[j];
+        else return __builtin_amdgcn_perm(0u, q[j >> 1], (j & 1) ? 0x0C030C02u : 0x0C010C00u);     // selector 0x0C yields 0
+    }
+    static __device__ __forceinline__ uint32_t ord_pair(uint32_t pw)
+    {
+        const uint32_t mag = pw & (kMag * 0x00010001u);
+        const uint32_t up = kBytes ? as_word(as_u16x2(pw) << (unsigned short)8) : pw;     // sign bit to bit 15 of its half
+        const uint32_t sign = as_word(as_s16x2(up) >> (short)15);                            // all ones in a negative half
+        return as_word(as_u16x2(mag ^ sign) - as_u16x2(sign));                               // negated there
+    }
 
     template <int V> __device__ __forceinline__ void stage(const u32x4 &q)
     {
         if constexpr (V == 0) edge_vectors = 0;
         bool edge = false;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            ob2[V * 4 + w] = ulp_ord_pair(q[w]);
-            edge |= (q[w] & 0x7FFFu) >= kInf - 8u || ((q[w] >> 16) & 0x7FFFu) >= kInf - 8u;
-        }
+        static_for<kPairs>([&](auto idx) {
+            constexpr int j = decltype(idx)::value;
+            const uint32_t pw = pair_word<j>(q);
+            ob2[V * kPairs + j] = ord_pair(pw);
+            edge |= (pw & kMag) >= kInf - 8u || ((pw >> 16) & kMag) >= kInf - 8u;
+        });
         if (__builtin_amdgcn_ballot_w64(edge)) edge_vectors |= 1u << V;
     }
 
@@ -325,7 +340,7 @@ template <int DT> struct UlpRef16 {
     {
         const uint32_t row_bytes = (uint32_t)(uintptr_t)row;
         const uint32_t by_length = row_bytes + 128u - 4u * (uint32_t)__builtin_clz(d);
-        const bool is_nan = (pattern & 0x7FFFu) > kInf;
+        const bool is_nan = (pattern & kMag) > kInf;
         if (__builtin_amdgcn_ballot_w64(is_nan) == 0) {
             (void)__hip_atomic_fetch_add((GEAK_AS_LDS uint32_t *)by_length, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         } else {
@@ -339,38 +354,44 @@ template <int DT> struct UlpRef16 {
     {
         if ((edge_vectors >> V) & 1u) {                      // rare: element by element, NaN tested on both sides
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < E; ++e) {
                 const int oa = ulp_ord<DT>(q, e);
-                const uint32_t pair = ob2[V * 4 + (e >> 1)];
+                const uint32_t pair = ob2[V * kPairs + (e >> 1)];
                 const int ob = (e & 1) ? ((int)pair >> 16) : (int)(short)(pair & 0xFFFFu);
                 const uint32_t d = ulp_dist<DT>(oa, ob) | ulp_nan_mark<DT>(oa) | ulp_nan_mark<DT>(ob);
                 ulp_classify<uint32_t, true>(d, c.plain, row, nslots);
             }
             return;
         }
-        uint32_t d2[4], t2[4];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            d2[w] = ulp_dist_pair(ulp_ord_pair(q[w]), ob2[V * 4 + w]);
-            t2[w] = pk_min_u16(d2[w], 0x00080008u);
-            c.near12 += __builtin_amdgcn_perm(0u, 0x20200100u, t2[w]);       // table bytes 0 .. 7: 0, 1, 32, 32, 0, 0, 0, 0
-            c.near4 += __builtin_amdgcn_perm(0x01010101u, 0u, t2[w]);        //                     0, 0, 0, 0, 1, 1, 1, 1
-        }
-        if (__builtin_amdgcn_ballot_w64(((t2[0] | t2[1] | t2[2] | t2[3]) & 0x00080008u) != 0)) {
+        uint32_t pw[kPairs], d2[kPairs], t2[kPairs], any = 0;
+        static_for<kPairs>([&](auto idx) {
+            constexpr int j = decltype(idx)::value;
+            pw[j] = pair_word<j>(q);
+            d2[j] = ulp_dist_pair(ord_pair(pw[j]), ob2[V * kPairs + j]);
+            t2[j] = pk_min_u16(d2[j], 0x00080008u);
+            c.near12 += __builtin_amdgcn_perm(0u, 0x40400100u, t2[j]);       // table bytes 0 .. 7: 0, 1, 64, 64, 0, 0, 0, 0
+            c.near4 += __builtin_amdgcn_perm(0x01010101u, 0u, t2[j]);        //                     0, 0, 0, 0, 1, 1, 1, 1
+            any |= t2[j];
+        });
+        if (__builtin_amdgcn_ballot_w64((any & 0x00080008u) != 0)) {
             // Some lane has elements 8 or more steps away.  Every lane walks through its own (bit i of
             // `todo`: half i of the vector), so the wave issues as many rounds of LDS atomics as the
             // worst lane has such elements, not one round per element position.
             uint32_t todo = 0;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) todo |= (((t2[w] >> 3) & 1u) | ((t2[w] >> 18) & 2u)) << (2 * w);
+            for (int j = 0; j < kPairs; ++j) todo |= (((t2[j] >> 3) & 1u) | ((t2[j] >> 18) & 2u)) << (2 * j);
             c.far_lane += (uint32_t)__builtin_popcount(todo);
             while (__builtin_amdgcn_ballot_w64(todo != 0)) {
                 if (todo != 0) {
                     const uint32_t i = (uint32_t)__builtin_ctz(todo);
                     todo &= todo - 1u;
                     const uint32_t word = i >> 1, shift = (i & 1u) * 16u;
-                    const uint32_t dd = word == 0 ? d2[0] : word == 1 ? d2[1] : word == 2 ? d2[2] : d2[3];
-                    const uint32_t qq = word == 0 ? q[0] : word == 1 ? q[1] : word == 2 ? q[2] : q[3];
+                    uint32_t dd = d2[0], qq = pw[0];
+#pragma unroll
+                    for (int j = 1; j < kPairs; ++j) {
+                        dd = word == (uint32_t)j ? d2[j] : dd;
+                        qq = word == (uint32_t)j ? pw[j] : qq;
+                    }
                     far(qq >> shift, (dd >> shift) & 0xFFFFu, row, nslots);
                 }
             }
@@ -378,20 +399,20 @@ template <int DT> struct UlpRef16 {
     }
 
     // `elements` of the slice (absent ones of a tail not counted) were compared.  Elements at distance 0
-    // were counted nowhere on the packed path: they are what is left.  Of a plain-path vector's 512
+    // were counted nowhere on the packed path: they are what is left.  Of a plain-path vector's
     // positions (absent ones included, at distance 0) those outside its four classes went to the row there.
     __device__ __forceinline__ void commit(const Counts &c, uint32_t elements, GEAK_AS_LDS uint32_t *row, int lane) const
     {
-        const uint32_t n1 = (c.near12 & 0x1Fu) + ((c.near12 >> 16) & 0x1Fu);
-        const uint32_t n2 = ((c.near12 >> 5) & 0x1Fu) + ((c.near12 >> 21) & 0x1Fu);
-        const uint32_t n4 = (c.near4 & 0x1Fu) + ((c.near4 >> 16) & 0x1Fu);
-        // at most 32 per lane and class: two classes share a register through the wave sum (below 2^16 each)
+        const uint32_t n1 = (c.near12 & 0x3Fu) + ((c.near12 >> 16) & 0x3Fu);
+        const uint32_t n2 = ((c.near12 >> 6) & 0x3Fu) + ((c.near12 >> 22) & 0x3Fu);
+        const uint32_t n4 = (c.near4 & 0x3Fu) + ((c.near4 >> 16) & 0x3Fu);
+        // at most 64 per lane and class: two counts share a register through the wave sum (below 2^16 each)
         const uint32_t s12 = wave_sum_u32(n1 | (n2 << 16)), s4f = wave_sum_u32(n4 | (c.far_lane << 16));
         const uint32_t s4 = s4f & 0xFFFFu, far_total = s4f >> 16;
         if (lane == 0) {
             const uint32_t b1 = (s12 & 0xFFFFu) + (c.plain.lt2 - c.plain.lt1), b2 = (s12 >> 16) + (c.plain.lt4 - c.plain.lt2);
             const uint32_t b3 = s4 + (c.plain.lt8 - c.plain.lt4);
-            const uint32_t plain_far = (uint32_t)__builtin_popcount(edge_vectors) * (uint32_t)(kWaveSize * 8) - c.plain.lt8;
+            const uint32_t plain_far = (uint32_t)__builtin_popcount(edge_vectors) * (uint32_t)(kWaveSize * E) - c.plain.lt8;
             const uint32_t b0 = elements - b1 - b2 - b3 - far_total - plain_far;
             if (b0) (void)__hip_atomic_fetch_add(row + 0, b0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             if (b1) (void)__hip_atomic_fetch_add(row + 1, b1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -445,12 +466,12 @@ template <int DT> struct UlpRefBytes {
 };
 
 template <int DT> struct UlpRefOf { typedef UlpRef<DT> type; };
-template <> struct UlpRefOf<GEAK_F16> { typedef UlpRef16<GEAK_F16> type; };
-template <> struct UlpRefOf<GEAK_BF16> { typedef UlpRef16<GEAK_BF16> type; };
+template <> struct UlpRefOf<GEAK_F16> { typedef UlpRefPacked<GEAK_F16> type; };
+template <> struct UlpRefOf<GEAK_BF16> { typedef UlpRefPacked<GEAK_BF16> type; };
 template <> struct UlpRefOf<GEAK_U8> { typedef UlpRefBytes<GEAK_U8> type; };
 template <> struct UlpRefOf<GEAK_I8> { typedef UlpRefBytes<GEAK_I8> type; };
-template <> struct UlpRefOf<GEAK_F8E4M3> { typedef UlpRefBytes<GEAK_F8E4M3> type; };
-template <> struct UlpRefOf<GEAK_F8E5M2> { typedef UlpRefBytes<GEAK_F8E5M2> type; };
+template <> struct UlpRefOf<GEAK_F8E4M3> { typedef UlpRefPacked<GEAK_F8E4M3> type; };
+template <> struct UlpRefOf<GEAK_F8E5M2> { typedef UlpRefPacked<GEAK_F8E5M2> type; };
 
 // TAIL = false: a run of consecutive FULL items of one dtype in the wave's list, every load an
 // unguarded 16-byte load, the next item's reference slice fetched behind the last candidate.
