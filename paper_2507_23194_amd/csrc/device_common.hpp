@@ -91,18 +91,7 @@ __device__ __forceinline__ float decode(const u32x4 &q, int e)
     }
 }
 
-__device__ __forceinline__ int decode_i32(const u32x4 &q, int e) { return (int)q[e]; }
-
 // ---- loads -------------------------------------------------------------------------------------
-// Full item: 4 coalesced 16-byte loads per lane; vector v of lane L covers bytes (v*64 + L)*16.
-__device__ __forceinline__ void load_full(u32x4 (&dst)[kVecPerLane], const unsigned char *base, int lane)
-{
-    global_vec_ptr p = (global_vec_ptr)base + lane;
-#pragma unroll
-    for (int v = 0; v < kVecPerLane; ++v)
-        dst[v] = __builtin_nontemporal_load(p + v * kWaveSize);
-}
-
 // Vector V of lane L of an item that starts 16-byte aligned but may be shorter than a full item
 // (a segment's tail): whole vectors inside the item are loaded as such, the one vector that
 // straddles the end element by element, and everything past the end reads as 0 -- in the reference

@@ -3,7 +3,9 @@
 // The rule (GEAK section 3.1, tolerance-based comparison of output tensors against reference
 // outputs; the reference is ground truth, section 3.3):
 //     d = |a - b|, tol = atol + rtol*|b| (binary32, one rounding per step), close <=> d <= tol,
-//     NaN: close only if equal_nan and both NaN; +-Inf: close only if a == b; int32: a == b.
+//     NaN: close only if equal_nan and both NaN; +-Inf: close only if a == b; integers: a == b.
+//     fp16, bf16 and the 8-bit formats are widened exactly to binary32 first; binary64 runs the same
+//     rule in binary64 arithmetic.
 //
 // compare kernel -- one wavefront per work item (4 KiB of every tensor).
 //   * The wave loads its slice of the reference once, decodes it to binary32 and keeps b and tol
@@ -954,7 +956,6 @@ struct DoubleItem {
 // the wider dtypes, and a budget of 4.9 per byte at the memory's speed -- this path is bound by
 // arithmetic.  Elements the bare inequality cannot judge (b NaN, b +-Inf, tolerance overflowed) are
 // only marked when the slice is staged; vectors that hold one are counted again with the full rule.
-template <int DT> struct F8Vec { u32x4 q; };
 template <int DT>
 __device__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel, MaxPair *rec_in);
 template <int DT>
