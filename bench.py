@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--report", type=int, default=0, metavar="M",
                     help="also time the mismatch report (first M mismatches per pair) that follows a failed check; "
                          "reported under \"report\", not part of the step")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (the three launches of geak_check_run captured "
+                         "once); reported under \"graph_replay\", the headline value stays the eager one")
     ap.add_argument("--ulp-histogram", action="store_true",
                     help="also time the ulp-distance histogram pass (a second read of all tensors, part of the error "
                          "trace of a failed check); reported under \"ulp_histogram\", not part of the step")
@@ -181,6 +184,27 @@ def main():
         report = {"max_records": args.report, "ms_per_call_incl_copy_back": (time.perf_counter() - t0) / reps * 1e3,
                   "pairs": int(rcnt.size), "records": int(rcnt.sum())}
 
+    graph_replay = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            ck.run(w.ref, w.cands)                                   # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ck.run(w.ref, w.cands)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_el = (time.perf_counter() - t0) / args.steps
+        graph_replay = {"ms_per_step": g_el * 1e3, "GBps": alg_bytes / g_el / 1e9}
+
     ulp = None
     if args.ulp_histogram:
         for _ in range(3):
@@ -240,6 +264,8 @@ def main():
         out["report"] = report
     if ulp is not None:
         out["ulp_histogram"] = ulp
+    if graph_replay is not None:
+        out["graph_replay"] = graph_replay
     if not args.no_cpu_baseline:
         budget = {1: (8, 1 << 20), 2: (32, 1 << 26), 3: (16, 1 << 28), 4: (4, 0), 5: (8, 1 << 28)}[args.config]
         out["cpu_baseline"] = cpu_baseline(w, *budget)
