@@ -1607,6 +1607,43 @@ __device__ __forceinline__ bool element_close(const unsigned char *ref, const un
 
 constexpr int kReduceThreads = 256;
 
+// Least element of one 16-byte vector pair that is not close, or kNoItem: the rescan of an item's
+// first mismatch, one vector per thread.  `valid` elements of the vector lie inside the item.
+template <int DT>
+__device__ __forceinline__ uint32_t first_bad_in_vector(const u32x4 &qa, const u32x4 &qb, uint32_t valid, const SegTol &tolerance,
+                                                        int equal_nan)
+{
+    constexpr int E = Traits<DT>::E;
+    uint32_t best = kNoItem;
+    static_for<E>([&](auto idx) {
+        constexpr int e = E - 1 - decltype(idx)::value;                 // downwards, so that the least index is kept
+        bool close;
+        if constexpr (DT == GEAK_I32) close = qa[e] == qb[e];
+        else if constexpr (DT == GEAK_I64) close = qa[2 * e] == qb[2 * e] && qa[2 * e + 1] == qb[2 * e + 1];
+        else if constexpr (DT == GEAK_U8 || DT == GEAK_I8) close = ((qa[e >> 2] ^ qb[e >> 2]) >> (8 * (e & 3)) & 0xFFu) == 0;
+        else if constexpr (DT == GEAK_F64)
+            close = close_exact_d(bits_d(qa[2 * e], qa[2 * e + 1]), bits_d(qb[2 * e], qb[2 * e + 1]), tolerance.atol, tolerance.rtol, equal_nan);
+        else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2)
+            close = close_exact(f8_to_f32<DT, e & 3>(qa[e >> 2]), f8_to_f32<DT, e & 3>(qb[e >> 2]), tolerance.atol_f, tolerance.rtol_f, equal_nan);
+        else close = close_exact(decode<DT>(qa, e), decode<DT>(qb, e), tolerance.atol_f, tolerance.rtol_f, equal_nan);
+        if ((uint32_t)e < valid && !close) best = (uint32_t)e;
+    });
+    return best;
+}
+template <int DT>
+__device__ __forceinline__ uint32_t first_bad_of_thread(const unsigned char *rb, const unsigned char *cb, int tid, uint32_t numel,
+                                                        const SegTol &tolerance, int equal_nan)
+{
+    constexpr uint32_t E = Traits<DT>::E;
+    const uint32_t begin = (uint32_t)tid * E;
+    if (begin >= numel) return kNoItem;
+    const bool full = begin + E <= numel;
+    const u32x4 qb = load_vec<DT>(rb, tid & (kWaveSize - 1), tid >> 6, numel, full);
+    const u32x4 qa = load_vec<DT>(cb, tid & (kWaveSize - 1), tid >> 6, numel, full);
+    const uint32_t e = first_bad_in_vector<DT>(qa, qb, numel - begin, tolerance, equal_nan);
+    return e == kNoItem ? kNoItem : begin + e;
+}
+
 __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs p)
 {
     __shared__ u64 s_count[kReduceThreads / kWaveSize];
@@ -1650,24 +1687,31 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
         first_item = s_first[w] < first_item ? s_first[w] : first_item;
     }
 
-    // exact first index: re-read the first item that holds a mismatch, every thread checking the
-    // elements tid, tid + 256, ... (all of a thread's loads are in flight together)
+    // exact first index: re-read the first item that holds a mismatch, every thread one 16-byte vector of
+    // the reference and of the candidate (256 threads x 16 bytes: the whole item)
     long long first = -1;
     if (first_item != kNoItem) {                // uniform: every thread holds the same first_item
         const geak_item it = p.items[first_item];
         const SegTol tolerance = p.seg_tol[seg];
         const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
-        constexpr int kPer = kItemBytes / kReduceThreads;       // 16: most elements (one-byte dtypes) a thread can own
-        bool bad[kPer];
-#pragma unroll
-        for (int u = 0; u < kPer; ++u) {
-            const uint32_t i = (uint32_t)tid + u * kReduceThreads;
-            bad[u] = (i < it.numel) && !element_close(rb, cb, i, it.dtype, tolerance, p.equal_nan);
-        }
         uint32_t best = kNoItem;
-#pragma unroll
-        for (int u = kPer - 1; u >= 0; --u)
-            if (bad[u]) best = (uint32_t)tid + u * kReduceThreads;
+        if (it.flags & GEAK_ITEM_ALIGNED) {      // one 16-byte vector of each tensor per thread (uniform branch)
+            switch (it.dtype) {
+            case GEAK_F32:  best = first_bad_of_thread<GEAK_F32>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_F16:  best = first_bad_of_thread<GEAK_F16>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_BF16: best = first_bad_of_thread<GEAK_BF16>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_I32:  best = first_bad_of_thread<GEAK_I32>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_I64:  best = first_bad_of_thread<GEAK_I64>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_U8:   best = first_bad_of_thread<GEAK_U8>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_I8:   best = first_bad_of_thread<GEAK_I8>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_F64:  best = first_bad_of_thread<GEAK_F64>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_F8E4M3: best = first_bad_of_thread<GEAK_F8E4M3>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            default:        best = first_bad_of_thread<GEAK_F8E5M2>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            }
+        } else {                                 // a segment's few elements before its first 16-byte boundary
+            const uint32_t i = (uint32_t)tid;
+            if (i < it.numel && !element_close(rb, cb, i, it.dtype, tolerance, p.equal_nan)) best = i;
+        }
         best = wave_min_u(best);
         if (lane == 0) s_best[wave] = best;
         __syncthreads();
