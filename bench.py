@@ -134,12 +134,15 @@ def main():
     w = synth.CONFIGS[args.config](device="cuda:0")
     torch.cuda.synchronize()
 
+    t_plan = time.perf_counter()
     if w.segments is None:
         ck = B.Checker(dense=(w.dtype, (w.ref.numel(),)), num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol,
                        equal_nan=w.equal_nan, device=0)
     else:
         ck = B.Checker(w.segments, num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol, equal_nan=w.equal_nan,
                        device=0)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t_plan) * 1e3          # host planning, upload of the work table, workspace allocation: once per shape, untimed
     info = ck.info()
     alg_bytes = int(info.algorithmic_bytes)
     assert alg_bytes == w.algorithmic_bytes()
@@ -248,7 +251,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": WORKLOADS[args.config], "num_candidates": len(w.cands),
                    "algorithmic_bytes": alg_bytes, "segments": 1 if w.segments is None else len(w.segments),
-                   "grid_blocks": int(info.grid_blocks), "work_items": int(info.num_items)},
+                   "grid_blocks": int(info.grid_blocks), "work_items": int(info.num_items), "plan_ms": plan_ms},
         "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
         "candidates_per_sec": len(w.cands) / (elapsed / args.steps),
         "verdicts_per_sec": rec.size / (elapsed / args.steps),
