@@ -1,0 +1,76 @@
+"""Seeded random plans: segment tables of random length, dtypes, sizes, alignments and tolerances,
+checked, reported and histogrammed on the GPU and compared with the oracle segment by segment."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import record_tuple
+from paper_2507_23194_amd import binding as B
+from paper_2507_23194_amd import synth
+from test_gpu_parity import _special_case
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = ["f32", "f16", "bf16", "i32", "i64", "u8", "i8", "f64", "f8e4m3", "f8e5m2"]
+
+
+def _random_case(seed):
+    rng = np.random.default_rng(seed)
+    nsegs = int(rng.integers(1, 40))
+    K = int(rng.integers(1, 10))
+    align = int(rng.choice([1, 2, 4, 8, 16]))
+    segs, tols, parts, off = [], [], [], 0
+    for _ in range(nsegs):
+        dt = DTYPES[int(rng.integers(0, len(DTYPES)))]
+        w = synth.ELEM_SIZE[dt]
+        n = int(rng.choice([0, 1, int(rng.integers(2, 70)), int(rng.integers(70, 5000)), int(rng.integers(5000, 40000))]))
+        a = max(align, w)
+        off = (off + a - 1) // a * a + w * int(rng.integers(0, 3)) * (align < 16)
+        off = (off + w - 1) // w * w
+        segs.append((off, n, dt))
+        tols.append((float(rng.choice([0.0, 1e-6, 1e-3, 0.25, 1e30])), float(rng.choice([0.0, 1e-5, 1e-2, 0.125, 3.0]))))
+        if n:
+            b, _ = _special_case(rng, dt, n)
+            cands = [(_special_case(rng, dt, n)[1] if rng.random() < 0.7 else b.copy()) for _ in range(K)]
+            parts.append((off, b, cands))
+        off += n * w
+    total = (off + 15) // 16 * 16 + 16
+    ref = np.zeros(total, dtype=np.uint8)
+    cbufs = [np.zeros(total, dtype=np.uint8) for _ in range(K)]
+    for off, b, cands in parts:
+        ref[off:off + b.nbytes] = b.view(np.uint8)
+        for k in range(K):
+            cbufs[k][off:off + b.nbytes] = cands[k].view(np.uint8)
+    return segs, tols, K, bool(rng.integers(0, 2)), ref, cbufs
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_plan(oracle_mod, seed):
+    segs, tols, K, equal_nan, ref, cbufs = _random_case(seed)
+    print("random plan", seed, len(segs), "segments", K, "candidates", flush=True)
+    dref = torch.from_numpy(ref).cuda()
+    dc = [torch.from_numpy(c).cuda() for c in cbufs]
+    ck = B.Checker(segs, num_candidates=K, equal_nan=equal_nan, device=0, tolerances=tols)
+    try:
+        ck.run(dref, dc)
+        gpu = ck.read().copy()
+        rec, cnt = ck.report(dref, dc, 5)
+        verdict, failed = ck.verdicts()
+        hist = ck.ulp_histogram(dref, dc)
+    finally:
+        ck.close()
+    for s, (off, n, dt) in enumerate(segs):
+        atol, rtol = tols[s]
+        for k in range(K):
+            cpu = oracle_mod.check_segment(ref, cbufs[k], n, dt, atol, rtol, equal_nan, ref_byte_offset=off)
+            assert record_tuple(gpu[s, k]) == record_tuple(cpu), (seed, s, k, dt, n, off, atol, rtol, equal_nan)
+            rep = oracle_mod.report_segment(ref, cbufs[k], n, dt, atol, rtol, equal_nan, 5, ref_byte_offset=off)
+            assert int(cnt[s, k]) == len(rep), (seed, s, k, dt)
+            got = rec[s, k][:len(rep)]
+            assert (got["index"] == rep["index"]).all(), (seed, s, k, dt)
+            for f in ("a", "b", "d", "tol"):
+                assert np.array_equal(got[f], rep[f], equal_nan=True), (seed, s, k, dt, f)
+            want = oracle_mod.ulp_histogram_segment(ref, cbufs[k], n, dt, ref_byte_offset=off)
+            assert (hist[s, k] == want).all(), (seed, s, k, dt, n, hist[s, k], want)
+    assert verdict.tolist() == [bool((gpu[:, k]["pass"] == 1).all()) for k in range(K)]
+    assert failed.tolist() == [int((gpu[:, k]["pass"] == 0).sum()) for k in range(K)]
