@@ -118,6 +118,27 @@ typedef struct {
 geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs, const geak_tolerance *tols,
                                        uint64_t nsegs, int32_t num_candidates, int32_t equal_nan, int32_t device);
 
+/* A segment stored as `rows` rows of `row_elems` elements, row r starting pitch_bytes * r behind byte_offset:
+ * outputs that kernels write into padded buffers (section 3.3: every unit-test output is checked; repacking
+ * them first would cost another pass over the data).  The reference and every candidate use the same layout.
+ * Indices (first_mismatch, the report) are flat and row-major over the rows * row_elems elements, padding
+ * not counted.  pitch_bytes must be a multiple of the element size and at least one row long; segments may not
+ * interleave (their spans from first to last byte must not overlap).  Rows that start 16-byte aligned and are at
+ * least 4 KiB long run at the speed of contiguous data; short rows are handled one by one. */
+typedef struct {
+    uint64_t byte_offset;
+    uint64_t rows;
+    uint64_t row_elems;
+    uint64_t pitch_bytes;
+    int32_t  dtype;
+    int32_t  reserved;   /* must be 0 */
+} geak_segment2d;
+
+/* Like geak_check_plan_tolerances for pitched segments; `tols` may be null, then atol / rtol apply to all. */
+geak_status geak_check_plan_pitched(geak_plan **out, const geak_segment2d *segs, const geak_tolerance *tols,
+                                    uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
+                                    int32_t equal_nan, int32_t device);
+
 /* Dense convenience (section 3.1: one output tensor against its reference): a single segment at
  * offset 0 with prod(shape) elements; shape is a host array of ndim >= 0 non-negative extents
  * (ndim == 0 is a scalar).  Only the element count matters: indices are flat, row-major. */

@@ -31,6 +31,8 @@ DTYPE_CODE = {"f32": GEAK_F32, "f16": GEAK_F16, "bf16": GEAK_BF16, "i32": GEAK_I
 ELEM_SIZE = {GEAK_F32: 4, GEAK_F16: 2, GEAK_BF16: 2, GEAK_I32: 4, GEAK_I64: 8, GEAK_U8: 1, GEAK_I8: 1, GEAK_F64: 8, GEAK_F8E4M3: 1, GEAK_F8E5M2: 1}
 
 SEGMENT_DTYPE = np.dtype([("byte_offset", "<u8"), ("numel", "<u8"), ("dtype", "<i4"), ("reserved", "<i4")])
+SEGMENT2D_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_elems", "<u8"), ("pitch_bytes", "<u8"),
+                            ("dtype", "<i4"), ("reserved", "<i4")])
 RESULT_DTYPE = np.dtype([("pass", "<i4"), ("reserved", "<i4"), ("mismatch_count", "<u8"),
                          ("first_mismatch", "<i8"), ("max_abs_err", "<f8"), ("max_rel_err", "<f8")])
 MISMATCH_DTYPE = np.dtype([("index", "<i8"), ("a", "<f8"), ("b", "<f8"), ("d", "<f8"), ("tol", "<f8")])
@@ -79,6 +81,9 @@ def library() -> ctypes.CDLL:
         lib.geak_check_plan.argtypes = [ctypes.POINTER(vp), vp, u64, i32, dbl, dbl, i32, i32]
         lib.geak_check_plan_tolerances.restype = ctypes.c_int
         lib.geak_check_plan_tolerances.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        lib.geak_check_plan_pitched.restype = ctypes.c_int
+        lib.geak_check_plan_pitched.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                                                ctypes.c_int32, ctypes.c_int32]
         lib.geak_check_plan_dense.restype = ctypes.c_int
         lib.geak_check_plan_dense.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(ctypes.c_int64), i32, i32, dbl, dbl, i32, i32]
         lib.geak_check_workspace_bytes.restype = u64
@@ -124,7 +129,7 @@ def library() -> ctypes.CDLL:
     return _lib
 
 
-EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
+EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
             "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram", "geak_check_verdicts",
@@ -156,6 +161,20 @@ def geak_check_plan_tolerances(segments, tolerances, num_candidates: int, equal_
     out = ctypes.c_void_p(None)
     st = library().geak_check_plan_tolerances(ctypes.byref(out), arr.ctypes.data, None if tol is None else tol.ctypes.data,
                                               len(segs), num_candidates, int(equal_nan), int(device))
+    return st, (out.value if st == GEAK_OK else None)
+
+
+def geak_check_plan_pitched(segments, tolerances, num_candidates: int, atol: float, rtol: float, equal_nan, device: int):
+    """segments: iterable of (byte_offset, rows, row_elems, pitch_bytes, dtype name); tolerances: one (atol, rtol)
+    pair per segment or None, then atol / rtol apply to all.  Returns (status, plan handle or None)."""
+    segs = list(segments)
+    arr = np.zeros(len(segs), dtype=SEGMENT2D_DTYPE)
+    for i, (off, rows, row_elems, pitch, dt) in enumerate(segs):
+        arr[i] = (off, rows, row_elems, pitch, DTYPE_CODE.get(dt, dt), 0)
+    tol = None if tolerances is None else np.ascontiguousarray(np.asarray(list(tolerances), dtype=np.float64).reshape(-1, 2))
+    out = ctypes.c_void_p(None)
+    st = library().geak_check_plan_pitched(ctypes.byref(out), arr.ctypes.data, None if tol is None else tol.ctypes.data,
+                                           len(segs), num_candidates, float(atol), float(rtol), int(equal_nan), int(device))
     return st, (out.value if st == GEAK_OK else None)
 
 
@@ -298,10 +317,12 @@ def geak_check_profile_read(plan, capacity: int) -> np.ndarray:
 class Checker:
     """A plan plus its workspace and results buffers (torch tensors on the plan's device)."""
 
-    def __init__(self, segments=None, *, dense=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
+    def __init__(self, segments=None, *, dense=None, pitched=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
                  equal_nan: bool, device: int = 0, tolerances=None):
         import torch
-        if tolerances is not None:
+        if pitched is not None:
+            st, plan = geak_check_plan_pitched(pitched, tolerances, num_candidates, atol, rtol, equal_nan, device)
+        elif tolerances is not None:
             st, plan = geak_check_plan_tolerances(segments, tolerances, num_candidates, equal_nan, device)
         elif dense is not None:
             dtype, shape = dense

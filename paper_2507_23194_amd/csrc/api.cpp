@@ -15,7 +15,7 @@ struct geak_plan {
     geak_item *items_dev = nullptr;
     uint32_t *slot_begin_dev = nullptr;
     uint32_t *wave_first_dev = nullptr;
-    geak_segment *segments_dev = nullptr;
+    SegDesc *segments_dev = nullptr;
     SegTol *seg_tol_dev = nullptr;
     // optional timing ring
     std::vector<hipEvent_t> ev_start, ev_stop;
@@ -74,8 +74,57 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
     return geak_check_plan_tolerances(out, segs, tols.data(), nsegs, num_candidates, equal_nan, device);
 }
 
+static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
+                                   int32_t num_candidates, int32_t equal_nan, int32_t device);
+
 geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs, const geak_tolerance *tols,
                                        uint64_t nsegs, int32_t num_candidates, int32_t equal_nan, int32_t device)
+{
+    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    std::vector<SegDesc> descs;
+    try {
+        descs.resize(nsegs);
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    for (uint64_t s = 0; s < nsegs; ++s) {                 // a contiguous segment is one row
+        const geak_segment &g = segs[s];
+        const uint64_t w = (g.dtype >= GEAK_F32 && g.dtype <= GEAK_F8E5M2) ? (uint64_t)elem_size(g.dtype) : 1;
+        descs[s] = SegDesc{g.byte_offset, g.numel, g.numel ? g.numel : 1, g.numel <= UINT64_MAX / w ? g.numel * w : 0, g.dtype, g.reserved};
+    }
+    return plan_from_descs(out, descs.data(), tols, nsegs, num_candidates, equal_nan, device);
+}
+
+geak_status geak_check_plan_pitched(geak_plan **out, const geak_segment2d *segs, const geak_tolerance *tols, uint64_t nsegs,
+                                    int32_t num_candidates, double atol, double rtol, int32_t equal_nan, int32_t device)
+{
+    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    std::vector<SegDesc> descs;
+    std::vector<geak_tolerance> same;
+    try {
+        descs.resize(nsegs);
+        if (!tols) same.assign(nsegs, geak_tolerance{atol, rtol});
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    for (uint64_t s = 0; s < nsegs; ++s) {
+        const geak_segment2d &g = segs[s];
+        if (g.rows && g.row_elems > GEAK_MAX_SEGMENT_NUMEL / g.rows) return GEAK_EBOUNDS;
+        const uint64_t numel = g.rows * g.row_elems;
+        const uint64_t w = (g.dtype >= GEAK_F32 && g.dtype <= GEAK_F8E5M2) ? (uint64_t)elem_size(g.dtype) : 1;
+        SegDesc d{g.byte_offset, numel, numel ? g.row_elems : 1, g.pitch_bytes, g.dtype, g.reserved};
+        if (numel && g.row_elems <= UINT64_MAX / w && g.pitch_bytes == g.row_elems * w) {    // rows back to back: one row
+            d.row_elems = numel;
+            d.pitch_bytes = numel * w;                  // numel <= 2^40
+        }
+        if (!numel) d.pitch_bytes = 0;
+        descs[s] = d;
+    }
+    return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
+}
+
+static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
+                                   int32_t num_candidates, int32_t equal_nan, int32_t device)
 {
     if (!out) return GEAK_EINVAL;
     if (device < -1) return GEAK_EINVAL;
@@ -111,7 +160,7 @@ geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs
         const size_t wave_bytes = p->host.wave_first.size() * sizeof(uint32_t);
         if (ok) ok = hipMalloc((void **)&p->slot_begin_dev, slot_bytes) == hipSuccess;
         if (ok) ok = hipMalloc((void **)&p->wave_first_dev, wave_bytes) == hipSuccess;
-        const size_t seg_bytes = p->host.segments.size() * sizeof(geak_segment);
+        const size_t seg_bytes = p->host.segments.size() * sizeof(SegDesc);
         if (ok) ok = hipMalloc((void **)&p->segments_dev, seg_bytes) == hipSuccess;
         const size_t tol_bytes = p->host.seg_tol.size() * sizeof(SegTol);
         if (ok) ok = hipMalloc((void **)&p->seg_tol_dev, tol_bytes) == hipSuccess;
@@ -377,7 +426,7 @@ geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const 
 static uint32_t ulp_slots(const HostPlan &hp)
 {
     uint32_t n = 0;
-    for (const geak_segment &g : hp.segments) n = std::max(n, ulp_slots_of(g.dtype));
+    for (const SegDesc &g : hp.segments) n = std::max(n, ulp_slots_of(g.dtype));
     return n;
 }
 
@@ -485,8 +534,8 @@ geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, co
     }
     // the span of the packed buffers that the plan's segments cover
     uint64_t end = 0;
-    for (const geak_segment &g : hp.segments)
-        if (g.numel) end = std::max<uint64_t>(end, g.byte_offset + g.numel * (uint64_t)elem_size(g.dtype));
+    for (const SegDesc &g : hp.segments)
+        if (g.numel) end = std::max<uint64_t>(end, g.byte_offset + seg_span(g));
     DeviceGuard g(plan->device);
     if (!g.ok) return GEAK_EHIP;
     // the candidate pointer table of a run is reused; the reference pointer goes behind it

@@ -53,9 +53,26 @@ struct SegTol {
 };
 static_assert(sizeof(SegTol) == 24, "SegTol is read as three 64-bit words");
 
+// A segment as the planner and the report kernel see it: `numel` elements in rows of `row_elems`, row r starting
+// pitch_bytes * r behind byte_offset.  A contiguous segment is one row.
+struct SegDesc {
+    uint64_t byte_offset;
+    uint64_t numel;
+    uint64_t row_elems;                  // >= 1
+    uint64_t pitch_bytes;
+    int32_t dtype;
+    int32_t reserved;
+};
+inline uint64_t seg_rows(const SegDesc &g) { return g.numel / g.row_elems; }
+// bytes from the segment's first to behind its last element
+inline uint64_t seg_span(const SegDesc &g)
+{
+    return g.numel ? (seg_rows(g) - 1) * g.pitch_bytes + g.row_elems * (uint64_t)elem_size(g.dtype) : 0;
+}
+
 // Host side of a plan: everything that can be decided without a device.
 struct HostPlan {
-    std::vector<geak_segment> segments;
+    std::vector<SegDesc> segments;
     std::vector<geak_item> items;
     std::vector<uint32_t> slot_begin;      // per segment, size nsegs + 1; slots of a segment are contiguous
     uint64_t algorithmic_bytes = 0;
@@ -70,7 +87,7 @@ struct HostPlan {
 };
 
 // Validates and builds the work table for a persistent grid of at most `max_blocks` blocks.
-geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_tolerance *tols, uint64_t nsegs,
+geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
                             int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks);
 
 // Running maxima of one (segment, candidate, replica): non-negative doubles, raised by atomic max on
@@ -141,7 +158,7 @@ struct ProbeArgs {
 };
 
 struct ReportArgs {
-    const geak_segment *segments;        // device copy of the segment table
+    const SegDesc *segments;             // device copy of the segment table
     const geak_result *results;
     const unsigned char *ref;
     const unsigned char *const *cand_table;

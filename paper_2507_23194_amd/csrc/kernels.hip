@@ -1768,11 +1768,14 @@ __device__ __forceinline__ float elem_f(const unsigned char *base, u64 idx)
 template <int DT> constexpr bool kIntegerDtype = (DT == GEAK_I32 || DT == GEAK_I64 || DT == GEAK_U8 || DT == GEAK_I8);
 
 template <int DT>
-__device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol tolerance, const geak_segment &sg, const geak_result &rec, u64 want,
+__device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol tolerance, const SegDesc &sg, const geak_result &rec, u64 want,
                                             const unsigned char *rb, const unsigned char *cb, geak_mismatch *out,
                                             uint32_t (&s_cnt)[kReportPerThread][kReportThreads / kWaveSize])
 {
     const int tid = threadIdx.x, lane = tid & (kWaveSize - 1), wave = tid / kWaveSize;
+    // a pitched segment: flat index i sits in row i / row_elems; in units of elements the rows are pitch_elems apart
+    const bool pitched = sg.row_elems != sg.numel;
+    const u64 pitch_elems = sg.pitch_bytes / (u64)Traits<DT>::W;
     u64 found = 0;
     for (u64 base = (u64)rec.first_mismatch; base < sg.numel && found < want; base += kReportThreads * kReportPerThread) {
         // all loads of the tile first, then the rule
@@ -1782,18 +1785,19 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
         for (int u = 0; u < kReportPerThread; ++u) {
             const u64 i = base + (u64)u * kReportThreads + tid;
             const bool in = i < sg.numel;
+            const u64 j = (pitched && in) ? (i / sg.row_elems) * pitch_elems + i % sg.row_elems : i;     // where element i is stored
             if constexpr (DT == GEAK_I32) {
-                ai[u] = in ? reinterpret_cast<const int *>(cb)[i] : 0;
-                bi[u] = in ? reinterpret_cast<const int *>(rb)[i] : 0;
+                ai[u] = in ? reinterpret_cast<const int *>(cb)[j] : 0;
+                bi[u] = in ? reinterpret_cast<const int *>(rb)[j] : 0;
             } else if constexpr (DT == GEAK_I64 || DT == GEAK_F64) {     // binary64 travels as its bit pattern
-                ai[u] = in ? reinterpret_cast<const long long *>(cb)[i] : 0;
-                bi[u] = in ? reinterpret_cast<const long long *>(rb)[i] : 0;
+                ai[u] = in ? reinterpret_cast<const long long *>(cb)[j] : 0;
+                bi[u] = in ? reinterpret_cast<const long long *>(rb)[j] : 0;
             } else if constexpr (DT == GEAK_U8 || DT == GEAK_I8) {
-                ai[u] = in ? load_elem_int(cb, i, DT) : 0;
-                bi[u] = in ? load_elem_int(rb, i, DT) : 0;
+                ai[u] = in ? load_elem_int(cb, j, DT) : 0;
+                bi[u] = in ? load_elem_int(rb, j, DT) : 0;
             } else {
-                av[u] = in ? elem_f<DT>(cb, i) : 0.0f;
-                bv[u] = in ? elem_f<DT>(rb, i) : 0.0f;
+                av[u] = in ? elem_f<DT>(cb, j) : 0.0f;
+                bv[u] = in ? elem_f<DT>(rb, j) : 0.0f;
             }
         }
         bool bad[kReportPerThread];
@@ -1866,7 +1870,7 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     const u64 want = rec.mismatch_count < p.max_records ? rec.mismatch_count : (u64)p.max_records;
     if (threadIdx.x == 0) p.counts[blockIdx.x] = (uint32_t)want;
     if (want == 0) return;                                   // uniform
-    const geak_segment sg = p.segments[seg];
+    const SegDesc sg = p.segments[seg];
     const SegTol tolerance = p.seg_tol[seg];
     const unsigned char *rb = p.ref + sg.byte_offset, *cb = p.cand_table[k] + sg.byte_offset;
     geak_mismatch *out = p.records + (u64)blockIdx.x * p.max_records;

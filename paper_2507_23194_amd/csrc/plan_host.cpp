@@ -14,7 +14,7 @@ namespace geak {
 
 static bool mul_overflows(uint64_t a, uint64_t b) { return b != 0 && a > UINT64_MAX / b; }
 
-geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_tolerance *tols, uint64_t nsegs,
+geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
                             int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks)
 {
     if (!segs || !tols || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
@@ -29,17 +29,25 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
     // per-segment checks
     uint64_t total_bytes = 0;
     for (uint64_t s = 0; s < nsegs; ++s) {
-        const geak_segment &g = segs[s];
+        const SegDesc &g = segs[s];
         if (g.dtype < GEAK_F32 || g.dtype > GEAK_F8E5M2) return GEAK_EDTYPE;
         if (g.reserved != 0) return GEAK_EINVAL;
+        if (g.row_elems == 0 || g.numel % g.row_elems != 0) return GEAK_EINVAL;
         // the rule of every dtype but binary64 runs in binary32: its tolerances must be finite there too
         if (g.dtype != GEAK_F64 && (std::isinf((float)tols[s].atol) || std::isinf((float)tols[s].rtol))) return GEAK_EINVAL;
         const uint64_t w = (uint64_t)elem_size(g.dtype);
-        if (g.byte_offset % w != 0) return GEAK_EALIGN;
+        if (g.byte_offset % w != 0 || g.pitch_bytes % w != 0) return GEAK_EALIGN;
         if (g.numel > GEAK_MAX_SEGMENT_NUMEL) return GEAK_EBOUNDS;
         if (mul_overflows(g.numel, w)) return GEAK_EBOUNDS;
         const uint64_t bytes = g.numel * w;
-        if (g.byte_offset > UINT64_MAX - bytes) return GEAK_EBOUNDS;
+        // rows must not run into each other, and the last one must end inside the address space
+        if (g.numel) {
+            const uint64_t row_bytes = g.row_elems * w;             // <= bytes: no overflow
+            if (g.pitch_bytes < row_bytes) return GEAK_EBOUNDS;
+            if (mul_overflows(seg_rows(g) - 1, g.pitch_bytes)) return GEAK_EBOUNDS;
+            if ((seg_rows(g) - 1) * g.pitch_bytes > UINT64_MAX - row_bytes) return GEAK_EBOUNDS;
+            if (g.byte_offset > UINT64_MAX - seg_span(g)) return GEAK_EBOUNDS;
+        }
         if (total_bytes > UINT64_MAX - bytes) return GEAK_EBOUNDS;
         total_bytes += bytes;
     }
@@ -51,7 +59,7 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
         spans.reserve(nsegs);
         for (uint64_t s = 0; s < nsegs; ++s)
             if (segs[s].numel)
-                spans.emplace_back(segs[s].byte_offset, segs[s].byte_offset + segs[s].numel * elem_size(segs[s].dtype));
+                spans.emplace_back(segs[s].byte_offset, segs[s].byte_offset + seg_span(segs[s]));   // pitched segments: first to last byte
         std::sort(spans.begin(), spans.end());
         for (size_t i = 1; i < spans.size(); ++i)
             if (spans[i].first < spans[i - 1].second) return GEAK_EBOUNDS;
@@ -59,13 +67,17 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
         // count items first: head (to the next 16-byte boundary), full tiles, tail
         uint64_t n_items = 0;
         for (uint64_t s = 0; s < nsegs; ++s) {
-            const geak_segment &g = segs[s];
+            const SegDesc &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
-            uint64_t n = g.numel;
-            if (!n) continue;
-            const uint64_t head = std::min<uint64_t>(n, ((16 - g.byte_offset % 16) % 16) / w);
-            if (head) { ++n_items; n -= head; }
-            n_items += n / per + (n % per ? 1 : 0);
+            if (!g.numel) continue;
+            for (uint64_t r = 0; r < seg_rows(g); ++r) {
+                uint64_t n = g.row_elems;
+                const uint64_t start = g.byte_offset + r * g.pitch_bytes;
+                const uint64_t head = std::min<uint64_t>(n, ((16 - start % 16) % 16) / w);
+                if (head) { ++n_items; n -= head; }
+                n_items += n / per + (n % per ? 1 : 0);
+                if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
+            }
         }
         if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
 
@@ -90,26 +102,30 @@ geak_status build_host_plan(HostPlan &hp, const geak_segment *segs, const geak_t
             hp.replicas /= 2;
 
         for (uint64_t s = 0; s < nsegs; ++s) {
-            const geak_segment &g = segs[s];
+            const SegDesc &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
             if (!g.numel) continue;
-            uint64_t done = 0;
-            auto push = [&](uint64_t n, bool full) {
-                geak_item it{};
-                it.byte_offset = g.byte_offset + done * w;
-                it.elem_start = done;
-                it.segment = (uint32_t)s;
-                it.numel = (uint16_t)n;
-                it.next = kNoItem;
-                it.dtype = (uint8_t)g.dtype;
-                it.flags = (uint8_t)((full ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0));
-                hp.items.push_back(it);
-                done += n;
-            };
-            const uint64_t head = std::min<uint64_t>(g.numel, ((16 - g.byte_offset % 16) % 16) / w);
-            if (head) push(head, false);
-            while (g.numel - done >= per) push(per, true);
-            if (g.numel - done) push(g.numel - done, false);
+            // row by row (a contiguous segment is one row): head up to the next 16-byte boundary, full items, tail
+            for (uint64_t r = 0; r < seg_rows(g); ++r) {
+                const uint64_t row_start = g.byte_offset + r * g.pitch_bytes;
+                uint64_t done = 0;
+                auto push = [&](uint64_t n, bool full) {
+                    geak_item it{};
+                    it.byte_offset = row_start + done * w;
+                    it.elem_start = r * g.row_elems + done;
+                    it.segment = (uint32_t)s;
+                    it.numel = (uint16_t)n;
+                    it.next = kNoItem;
+                    it.dtype = (uint8_t)g.dtype;
+                    it.flags = (uint8_t)((full ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0));
+                    hp.items.push_back(it);
+                    done += n;
+                };
+                const uint64_t head = std::min<uint64_t>(g.row_elems, ((16 - row_start % 16) % 16) / w);
+                if (head) push(head, false);
+                while (g.row_elems - done >= per) push(per, true);
+                if (g.row_elems - done) push(g.row_elems - done, false);
+            }
         }
 
         // Partition of the table over the persistent grid.  Block b owns the contiguous item range

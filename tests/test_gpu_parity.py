@@ -540,3 +540,62 @@ def test_verdicts_over_all_unit_tests(oracle_mod):
     finally:
         ck.close()
     assert verdict.tolist() == [False, True, False] and failed.tolist() == [1, 0, 1]
+
+
+@pytest.mark.parametrize("case", ["long_rows", "short_rows", "odd_bytes", "mixed"])
+def test_pitched_segments(oracle_mod, case):
+    """Outputs in padded buffers: rows `pitch_bytes` apart, the padding between them filled with different
+    garbage in every tensor.  Records, report, verdicts and ulp histograms equal the oracle's on contiguous
+    copies of the same elements (indices flat and row-major, padding not counted)."""
+    rng = np.random.default_rng(sum(map(ord, case)))
+    layouts = {
+        "long_rows": [(0, 5, 9000, 9000 * 2 + 64, "f16")],                       # rows of more than two items, 16-byte aligned
+        "short_rows": [(16, 300, 100, 416, "f32")],                              # every row a tail item
+        "odd_bytes": [(3, 40, 1000, 1003, "u8"), (50000, 9, 700, 712, "f8e4m3")],  # rows start on any byte
+        "mixed": [(0, 6, 5000, 20480, "f32"), (131072, 3, 3000, 24064, "f64"), (204800, 17, 33, 80, "bf16"), (208000, 0, 5, 64, "i32"),
+                  (208000, 2, 4097, 16400, "i32")],
+    }[case]
+    K = 3
+    total = max(off + (rows - 1) * pitch + re * synth.ELEM_SIZE[dt] if rows else off for off, rows, re, pitch, dt in layouts)
+    total = (total + 31) // 16 * 16
+    ref = rng.integers(0, 256, total, dtype=np.uint8)                            # garbage everywhere, also in the padding
+    cbufs = [rng.integers(0, 256, total, dtype=np.uint8) for _ in range(K)]
+    flat = []                                                                     # contiguous copies for the oracle
+    for off, rows, re, pitch, dt in layouts:
+        n = rows * re
+        w = synth.ELEM_SIZE[dt]
+        if n:
+            b, _ = _special_case(rng, dt, n)
+            cs = [(_special_case(rng, dt, n)[1] if k else b.copy()) for k in range(K)]
+            cs[1][: n // 2] = b[: n // 2]                                         # a first mismatch somewhere inside
+            for r in range(rows):
+                lo = off + r * pitch
+                ref[lo:lo + re * w] = b[r * re:(r + 1) * re].view(np.uint8)
+                for k in range(K):
+                    cbufs[k][lo:lo + re * w] = cs[k][r * re:(r + 1) * re].view(np.uint8)
+        else:
+            b, cs = np.zeros(0, np.uint8), [np.zeros(0, np.uint8)] * K
+        flat.append((b, cs, n, dt))
+    dref = torch.from_numpy(ref).cuda()
+    dc = [torch.from_numpy(c).cuda() for c in cbufs]
+    ck = B.Checker(pitched=layouts, num_candidates=K, atol=1e-3, rtol=1e-2, equal_nan=True, device=0)
+    try:
+        ck.run(dref, dc)
+        gpu = ck.read().copy()
+        rec, cnt = ck.report(dref, dc, 6)
+        verdict, _ = ck.verdicts()
+        hist = ck.ulp_histogram(dref, dc)
+    finally:
+        ck.close()
+    for s, (b, cs, n, dt) in enumerate(flat):
+        for k in range(K):
+            cpu = oracle_mod.check_segment(b, cs[k], n, dt, 1e-3, 1e-2, True)
+            assert record_tuple(gpu[s, k]) == record_tuple(cpu), (case, s, k, dt)
+            rep = oracle_mod.report_segment(b, cs[k], n, dt, 1e-3, 1e-2, True, 6)
+            assert int(cnt[s, k]) == len(rep)
+            got = rec[s, k][:len(rep)]
+            assert (got["index"] == rep["index"]).all(), (case, s, k)
+            assert all(np.array_equal(got[f], rep[f], equal_nan=True) for f in ("a", "b", "d", "tol"))
+            assert (hist[s, k] == oracle_mod.ulp_histogram_segment(b, cs[k], n, dt)).all(), (case, s, k)
+    assert verdict.tolist() == [bool((gpu[:, k]["pass"] == 1).all()) for k in range(K)]
+    assert verdict[0]                                                             # candidate 0 is a copy (NaN equal to NaN)

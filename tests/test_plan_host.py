@@ -309,3 +309,51 @@ def test_ulp_histogram_workspace(lib):
     assert B.geak_check_ulp_workspace_bytes(plan) == 2048 + info.num_slots * 2 * 66 * 4
     B.geak_check_destroy(plan)
     assert B.geak_check_ulp_workspace_bytes(None) == 0
+
+
+def test_pitched_segments_table(lib):
+    """Rows of a pitched segment are cut like segments of their own, with flat row-major element indices;
+    rows that lie back to back collapse into the contiguous layout."""
+    esize = {"f32": 4, "f16": 2, "u8": 1, "f64": 8}
+    segs = [(0, 3, 5000, 5000 * 2 + 32, "f16"), (40000, 7, 100, 416, "f32"), (50003, 4, 1000, 1003, "u8"), (60000, 0, 9, 72, "f64")]
+    st, plan = B.geak_check_plan_pitched(segs, None, 2, 1e-3, 1e-3, 0, -1)
+    assert st == B.GEAK_OK
+    items = B.geak_check_plan_items(plan)
+    info = B.geak_check_plan_info(plan)
+    assert info.num_segments == 4 and B.geak_check_result_count(plan) == 8
+    assert info.algorithmic_bytes == 3 * (3 * 5000 * 2 + 7 * 100 * 4 + 4 * 1000)
+    covered = {}
+    for it in items:
+        s = int(it["segment"])
+        off, rows, row_elems, pitch, dt = segs[s]
+        w = esize[dt]
+        e0, n = int(it["elem_start"]), int(it["numel"])
+        r, c = divmod(e0, row_elems)
+        assert c + n <= row_elems                                       # an item never crosses a row
+        assert int(it["byte_offset"]) == off + r * pitch + c * w
+        assert bool(it["flags"] & B.GEAK_ITEM_ALIGNED) == (int(it["byte_offset"]) % 16 == 0)
+        assert e0 == covered.get(s, 0)                                  # in order, no gaps
+        covered[s] = e0 + n
+    assert covered == {0: 15000, 1: 700, 2: 4000}
+    B.geak_check_destroy(plan)
+    # rows back to back are the contiguous layout
+    st, p1 = B.geak_check_plan_pitched([(64, 10, 3000, 12000, "f32")], None, 2, 0, 0, 0, -1)
+    st2, p2 = B.geak_check_plan([(64, 30000, "f32")], 2, 0, 0, 0, -1)
+    assert st == st2 == B.GEAK_OK
+    assert (B.geak_check_plan_items(p1) == B.geak_check_plan_items(p2)).all()
+    B.geak_check_destroy(p1)
+    B.geak_check_destroy(p2)
+
+
+@pytest.mark.parametrize("segs,status", [
+    ([(0, 4, 100, 396, "f32")], B.GEAK_EBOUNDS),                       # rows overlap: pitch shorter than a row
+    ([(0, 4, 100, 402, "f32")], B.GEAK_EALIGN),                        # pitch not a multiple of the element size
+    ([(2, 4, 100, 400, "f32")], B.GEAK_EALIGN),
+    ([(0, 4, 100, 800, "f32"), (400, 4, 100, 800, "f32")], B.GEAK_EBOUNDS),   # interleaved: spans overlap
+    ([(0, 2 ** 30, 2 ** 30, 2 ** 32, "f32")], B.GEAK_EBOUNDS),         # too many elements
+    ([(0, 2 ** 20, 16, 2 ** 62, "f32")], B.GEAK_EBOUNDS),              # the last row lies beyond the address space
+    ([(0, 4, 100, 400, 12)], B.GEAK_EDTYPE),
+])
+def test_pitched_plan_rejects(lib, segs, status):
+    st, plan = B.geak_check_plan_pitched(segs, None, 2, 0, 0, 0, -1)
+    assert st == status and plan is None
