@@ -143,6 +143,18 @@ __device__ __forceinline__ float f8_to_f32(uint32_t word)
     else return __builtin_amdgcn_cvt_f32_bf8((int)word, BYTE);
 }
 
+// Two neighbouring bytes of the word (the low pair, or with HI the high pair) widened by one instruction.
+struct F32Pair { float lo, hi; };
+template <int DT, bool HI>
+__device__ __forceinline__ F32Pair f8_pair_to_f32(uint32_t word)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    f32x2 v;
+    if constexpr (DT == GEAK_F8E4M3) v = __builtin_amdgcn_cvt_pk_f32_fp8((int)word, HI);
+    else v = __builtin_amdgcn_cvt_pk_f32_bf8((int)word, HI);
+    return F32Pair{v[0], v[1]};
+}
+
 // One element straight from memory, decoded exactly to binary32 (floating dtypes).
 __device__ __forceinline__ float load_elem_f(const unsigned char *base, u64 idx, int dtype)
 {

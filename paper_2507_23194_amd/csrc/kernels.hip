@@ -473,7 +473,7 @@ struct FloatItem {
 
     // Hot loop body for one 16-byte vector of one candidate.  Adds the suspects (elements with
     // !(d <= tol)) to `suspects` and ORs into `trip_abs` / `trip_rel` the lanes that may raise
-    // max_abs_err / max_rel_err.  Five vector instructions per element (six for bfloat16).
+    // max_abs_err / max_rel_err.  Four vector instructions per element (five for bfloat16).
     template <int V, bool AHEAD = true>
     __device__ __forceinline__ void compare_vec(const u32x4 &q, float max_abs, float max_rel, uint32_t &suspects,
                                                 u64 &trip_abs, u64 &trip_rel, int equal_nan)
@@ -489,16 +489,20 @@ struct FloatItem {
         } else {
             tol.template get<V>(tv);
         }
-        static_for<E>([&](auto idx) {
-            constexpr int e = decltype(idx)::value;
-            const float d = diff<V, e>(q);
-            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d) <= tv[e])));
-            trip_abs |= __builtin_amdgcn_ballot_w64(__builtin_fabsf(d) > max_abs);
-            trip_rel |= negative_mask(rel_margin<V, e>(max_rel, d));
-            // keep each OR a running chain in one scalar register pair (a balanced tree would
-            // hold every lane mask live at once)
-            asm volatile("" : "+s"(trip_abs), "+s"(trip_rel));
+        // The two "may raise a maximum" tests are folded over the vector: a running greatest |d| and a
+        // running least margin r|b| - |d| (three-operand max / min, which skip NaN as the comparisons
+        // they stand for do), each tested once.
+        float d_most = 0.0f, margin_least = kInfF;
+        static_for<E / 2>([&](auto idx) {
+            constexpr int e = 2 * decltype(idx)::value;
+            const float d0 = diff<V, e>(q), d1 = diff<V, e + 1>(q);
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d0) <= tv[e])));
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d1) <= tv[e + 1])));
+            d_most = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(d0), __builtin_fabsf(d1)), d_most);
+            margin_least = __builtin_fminf(__builtin_fminf(rel_margin<V, e>(max_rel, d0), rel_margin<V, e + 1>(max_rel, d1)), margin_least);
         });
+        trip_abs |= __builtin_amdgcn_ballot_w64(d_most > max_abs);
+        trip_rel |= negative_mask(margin_least);
         // Poisoned elements were all reported as suspects; take off those that the NaN / Inf rule
         // accepts.  In the streaming routine this happens here, while the vector's tolerances (which
         // say why an element is poisoned) are at hand.
@@ -951,10 +955,10 @@ struct DoubleItem {
 // ---- 8-bit floating formats: sixteen elements per 16-byte vector, the binary32 rule ----------------------
 // A lane holds 64 elements of the slice: neither the decoded reference nor its tolerances fit the
 // registers (nor, with four blocks per compute unit, the LDS).  The reference stays packed, is widened
-// again for every candidate (one conversion instruction per element) and the tolerance is computed
-// again (one multiplication, one addition): nine vector instructions per element, against five for
-// the wider dtypes, and a budget of 4.9 per byte at the memory's speed -- this path is bound by
-// arithmetic.  Elements the bare inequality cannot judge (b NaN, b +-Inf, tolerance overflowed) are
+// again for every candidate and the tolerance is computed
+// again (one multiplication, one addition): seven vector instructions per element (the conversion
+// widens two at a time), against four for the wider dtypes, and a budget of 4.9 per byte at the
+// memory's speed -- this path is bound by arithmetic.  Elements the bare inequality cannot judge (b NaN, b +-Inf, tolerance overflowed) are
 // only marked when the slice is staged; vectors that hold one are counted again with the full rule.
 template <int DT>
 __device__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel, MaxPair *rec_in);
@@ -1003,17 +1007,26 @@ struct Fp8Item {
             words[w] = bref[V * 4 + w];
             asm volatile("" : "+v"(words[w]));
         }
-        static_for<E>([&](auto idx) {
-            constexpr int e = decltype(idx)::value;
-            const float x = value<e>(words);
-            const float d = value<e>(q) - x;
-            const float prod = rtol_f * __builtin_fabsf(x);
-            const float t = atol_f + prod;
-            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d) <= t)));
-            trip_abs |= __builtin_amdgcn_ballot_w64(__builtin_fabsf(d) > max_abs);
-            trip_rel |= negative_mask(__builtin_fmaf(max_rel, __builtin_fabsf(x), -__builtin_fabsf(d)));
-            asm volatile("" : "+s"(trip_abs), "+s"(trip_rel));
+        // Two elements per step: one conversion widens both, and the two "may raise a maximum" tests
+        // are folded into a running greatest |d| and a running least margin r|b| - |d| (three-operand
+        // max / min, which skip NaN as the comparisons they replace did), tested once per vector.
+        float d_most = 0.0f, margin_least = kInfF;
+        static_for<E / 2>([&](auto idx) {
+            constexpr int p = decltype(idx)::value;
+            const F32Pair x = f8_pair_to_f32<DT, (p & 1) != 0>(words[p >> 1]);
+            const F32Pair a = f8_pair_to_f32<DT, (p & 1) != 0>(q[p >> 1]);
+            const float d0 = a.lo - x.lo, d1 = a.hi - x.hi;
+            const float prod0 = rtol_f * __builtin_fabsf(x.lo), prod1 = rtol_f * __builtin_fabsf(x.hi);
+            const float t0 = atol_f + prod0, t1 = atol_f + prod1;
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d0) <= t0)));
+            suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d1) <= t1)));
+            d_most = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(d0), __builtin_fabsf(d1)), d_most);
+            const float m0 = __builtin_fmaf(max_rel, __builtin_fabsf(x.lo), -__builtin_fabsf(d0));
+            const float m1 = __builtin_fmaf(max_rel, __builtin_fabsf(x.hi), -__builtin_fabsf(d1));
+            margin_least = __builtin_fminf(__builtin_fminf(m0, m1), margin_least);
         });
+        trip_abs |= __builtin_amdgcn_ballot_w64(d_most > max_abs);
+        trip_rel |= negative_mask(margin_least);
         if constexpr (AHEAD) {
             if ((poisoned_slots >> (V * E)) & 0xFFFFull) suspects += (uint32_t)recount<V>(q, equal_nan);
         }
