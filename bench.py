@@ -130,6 +130,7 @@ def main():
     from paper_2507_23194_amd import binding as B
     from paper_2507_23194_amd import synth
 
+    B.ensure_library()                  # loads what is built; compiles only when nothing is
     torch.cuda.set_device(0)
     w = synth.CONFIGS[args.config](device="cuda:0")
     torch.cuda.synchronize()

@@ -68,6 +68,13 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def ensure_library() -> str:
+    """Build the library only when none is there; what is built is loaded as it is."""
+    if not os.path.exists(LIB_PATH):
+        build_library()
+    return LIB_PATH
+
+
 def library() -> ctypes.CDLL:
     """The loaded C library; raises if it has not been built (no fallback path exists)."""
     global _lib

@@ -12,6 +12,13 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+@pytest.fixture(scope="session", autouse=True)
+def built_library():
+    """The in-tree library is loaded as built; it is compiled here only when none is there."""
+    from paper_2507_23194_amd import binding
+    return binding.ensure_library()
+
+
 @pytest.fixture(scope="session")
 def oracle_mod():
     import oracle

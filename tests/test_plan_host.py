@@ -15,8 +15,6 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 @pytest.fixture(scope="module")
 def lib():
-    if not os.path.exists(B.LIB_PATH):
-        B.build_library()
     return B.library()
 
 
