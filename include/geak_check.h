@@ -204,6 +204,9 @@ typedef struct {
 #define GEAK_ITEM_FIRST 2u /* first item of its (wavefront, segment) run: running state is reset */
 #define GEAK_ITEM_LAST  4u /* last item of its run: running state is written to the slot */
 #define GEAK_ITEM_ALIGNED 8u /* 16-byte aligned start (FULL implies it): vector loads, guarded at the end */
+#define GEAK_ITEM_ROWS 16u /* several whole rows of a pitched segment whose rows are short and start on 16-byte
+                              boundaries: numel / row_elems rows, pitch_bytes apart, the first at byte_offset;
+                              elem_start is the flat index of the first row's first element (ALIGNED is set) */
 
 geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
 

@@ -23,7 +23,7 @@ GEAK_EINVAL, GEAK_EDTYPE, GEAK_EALIGN, GEAK_EBOUNDS, GEAK_ENOMEM, GEAK_EWORKSPAC
 GEAK_F32, GEAK_F16, GEAK_BF16, GEAK_I32, GEAK_I64, GEAK_U8, GEAK_I8, GEAK_F64 = 0, 1, 2, 3, 4, 5, 6, 7
 GEAK_F8E4M3, GEAK_F8E5M2 = 8, 9
 GEAK_MAX_CANDIDATES = 256
-GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED = 1, 2, 4, 8
+GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED, GEAK_ITEM_ROWS = 1, 2, 4, 8, 16
 GEAK_ULP_BINS = 66
 
 DTYPE_CODE = {"f32": GEAK_F32, "f16": GEAK_F16, "bf16": GEAK_BF16, "i32": GEAK_I32, "i64": GEAK_I64,

@@ -269,6 +269,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.equal_nan = hp.equal_nan;
         ca.reserved = 0;
         ca.wave_first = plan->wave_first_dev;
+        ca.segments = plan->segments_dev;
 
         geak_plan *mp = const_cast<geak_plan *>(plan);      // timing ring only; documented as not re-entrant
         const bool timed = !mp->ev_start.empty();
@@ -294,6 +295,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ra.seg_tol = plan->seg_tol_dev;
         ra.equal_nan = hp.equal_nan;
         ra.replicas = hp.replicas;
+        ra.segments = plan->segments_dev;
         if (launch_reduce(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
     }
     return GEAK_OK;
@@ -484,6 +486,7 @@ geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev,
             ua.k_count = std::min<uint32_t>(per_pass, (uint32_t)K - k0);
             ua.nslots = nslots;
             ua.reserved = 0;
+            ua.segments = plan->segments_dev;
             const uint32_t lds = kWavesPerBlock * ua.k_count * nslots * 4u;
             if (launch_ulp_histogram(ua, hp.grid_blocks, lds, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
         }

@@ -92,6 +92,42 @@ __device__ __forceinline__ float decode(const u32x4 &q, int e)
 }
 
 // ---- loads -------------------------------------------------------------------------------------
+// The first `valid` elements (0 .. E) of the 16-byte vector at p; the rest reads as 0.  A whole
+// vector is one load, a partial one is read element by element: nothing past the valid elements is
+// touched.
+template <int DT>
+__device__ __forceinline__ u32x4 load_partial(global_vec_ptr p, uint32_t valid)
+{
+    constexpr uint32_t E = Traits<DT>::E;
+    u32x4 q = {0u, 0u, 0u, 0u};
+    if (valid >= E) {
+        q = __builtin_nontemporal_load(p);
+    } else if (valid) {
+        if constexpr (Traits<DT>::W == 1) {
+            const GEAK_AS_GLOBAL unsigned char *c = (const GEAK_AS_GLOBAL unsigned char *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (e < valid) q[e >> 2] |= (uint32_t)c[e] << ((e & 3) * 8);
+        } else if constexpr (Traits<DT>::W == 8) {
+            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (e < valid) { q[2 * e] = w[2 * e]; q[2 * e + 1] = w[2 * e + 1]; }
+        } else if constexpr (Traits<DT>::W == 4) {
+            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (e < valid) q[e] = w[e];
+        } else {
+            const GEAK_AS_GLOBAL uint16_t *h = (const GEAK_AS_GLOBAL uint16_t *)p;
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e)
+                if (e < valid) q[e >> 1] |= (uint32_t)h[e] << ((e & 1) * 16);
+        }
+    }
+    return q;
+}
+
 // Vector V of lane L of an item that starts 16-byte aligned but may be shorter than a full item
 // (a segment's tail): whole vectors inside the item are loaded as such, the one vector that
 // straddles the end element by element, and everything past the end reads as 0 -- in the reference
@@ -104,33 +140,67 @@ __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, i
     global_vec_ptr p = (global_vec_ptr)base + (v * kWaveSize + lane);
     if (full) return __builtin_nontemporal_load(p);
     const uint32_t first = (uint32_t)(v * kWaveSize + lane) * E;
-    u32x4 q = {0u, 0u, 0u, 0u};
-    if (first + E <= n) {
-        q = __builtin_nontemporal_load(p);
-    } else if (first < n) {
-        if constexpr (Traits<DT>::W == 1) {
-            const GEAK_AS_GLOBAL unsigned char *c = (const GEAK_AS_GLOBAL unsigned char *)p;
-#pragma unroll
-            for (uint32_t e = 0; e < E; ++e)
-                if (first + e < n) q[e >> 2] |= (uint32_t)c[e] << ((e & 3) * 8);
-        } else if constexpr (Traits<DT>::W == 8) {
-            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
-#pragma unroll
-            for (uint32_t e = 0; e < E; ++e)
-                if (first + e < n) { q[2 * e] = w[2 * e]; q[2 * e + 1] = w[2 * e + 1]; }
-        } else if constexpr (Traits<DT>::W == 4) {
-            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
-#pragma unroll
-            for (uint32_t e = 0; e < E; ++e)
-                if (first + e < n) q[e] = w[e];
-        } else {
-            const GEAK_AS_GLOBAL uint16_t *h = (const GEAK_AS_GLOBAL uint16_t *)p;
-#pragma unroll
-            for (uint32_t e = 0; e < E; ++e)
-                if (first + e < n) q[e >> 1] |= (uint32_t)h[e] << ((e & 1) * 16);
-        }
+    return load_partial<DT>(p, first < n ? n - first : 0u);
+}
+
+// Where the vectors of an aligned item that is not a full one lie.  A plain tail is contiguous:
+// vector i at byte 16 i.  A row group (GEAK_ITEM_ROWS: several short rows of a pitched segment, each
+// starting on a 16-byte boundary) gives every row `vpr` vectors, the last of them partial when the
+// row's bytes are no multiple of 16, and puts row r at byte r * pitch; vector slot i is vector
+// i % vpr of row i / vpr, so the slots still ascend with the element index.  All fields wave-uniform.
+struct ItemShape {
+    uint32_t rows;          // 0: a plain tail
+    uint32_t vpr;           // vectors per row
+    uint32_t inv;           // ceil(2^16 / vpr): (i * inv) >> 16 == i / vpr for i < 256
+    uint32_t row_elems;
+    u64 pitch;              // bytes from one row to the next
+};
+
+template <int DT>
+__device__ __forceinline__ ItemShape item_shape(const geak_item &it, const SegDesc *segments)
+{
+    ItemShape sh{0u, 1u, 0u, 0u, 0ull};
+    if (it.flags & GEAK_ITEM_ROWS) {
+        const GEAK_AS_CONSTANT unsigned long long *g = (const GEAK_AS_CONSTANT unsigned long long *)(segments + it.segment);
+        sh.row_elems = (uint32_t)g[2];                    // SegDesc: byte_offset, numel, row_elems, pitch_bytes, ...
+        sh.pitch = g[3];
+        sh.vpr = (sh.row_elems + Traits<DT>::E - 1) / Traits<DT>::E;
+        sh.inv = (65536u + sh.vpr - 1u) / sh.vpr;
+        sh.rows = (uint32_t)it.numel / sh.row_elems;
     }
-    return q;
+    return sh;
+}
+
+// Number of vector slots per lane (1 .. 4) that an item of this shape with n elements occupies.
+template <int DT>
+__device__ __forceinline__ uint32_t shape_vectors(const ItemShape &sh, uint32_t n)
+{
+    const uint32_t slots = sh.rows ? sh.rows * sh.vpr : (n + Traits<DT>::E - 1) / Traits<DT>::E;
+    return (slots + kWaveSize - 1) / kWaveSize;
+}
+
+// Vector slot `slot` (= v * 64 + lane) of a row group: its elements' index within the item in
+// `first` (meaningless when nothing is valid), loaded as load_vec loads a tail.
+template <int DT>
+__device__ __forceinline__ u32x4 load_row_slot(const unsigned char *base, uint32_t slot, const ItemShape &sh, uint32_t &first)
+{
+    constexpr uint32_t E = Traits<DT>::E;
+    const uint32_t row = (slot * sh.inv) >> 16, vec = slot - row * sh.vpr, col = vec * E;
+    first = row * sh.row_elems + col;
+    const uint32_t valid = row < sh.rows ? sh.row_elems - col : 0u;        // col < row_elems by construction of vpr
+    return load_partial<DT>((global_vec_ptr)(base + (u64)row * sh.pitch) + vec, valid);
+}
+// Vector v of this lane of an aligned item that is not a full one: a plain tail (ROWS false: exactly
+// load_vec's guarded load) or a row group.
+template <int DT, bool ROWS>
+__device__ __forceinline__ u32x4 load_shaped(const unsigned char *base, int lane, int v, uint32_t n, const ItemShape &sh)
+{
+    if constexpr (!ROWS) {
+        return load_vec<DT>(base, lane, v, n, false);
+    } else {
+        uint32_t first;
+        return load_row_slot<DT>(base, (uint32_t)(v * kWaveSize + lane), sh, first);
+    }
 }
 
 // The 8-bit floating formats are widened by the conversion instructions (v_cvt_f32_fp8 for E4M3,

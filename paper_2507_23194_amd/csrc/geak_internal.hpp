@@ -131,6 +131,7 @@ struct CompareArgs {
     int equal_nan;
     int reserved;
     const uint32_t *wave_first;          // grid_blocks * kWavesPerBlock entries
+    const SegDesc *segments;             // device table: the row geometry of row-group items
 };
 
 struct ReduceArgs {
@@ -146,6 +147,7 @@ struct ReduceArgs {
     const SegTol *seg_tol;               // device table, one entry per segment
     int equal_nan;
     uint32_t replicas;
+    const SegDesc *segments;             // device table: the row geometry of row-group items
 };
 
 // Read probe: num_buffers device buffers (pointer table in the workspace), bytes_each bytes of each.
@@ -198,6 +200,7 @@ struct UlpArgs {
     uint32_t k_count;
     uint32_t nslots;
     uint32_t reserved;
+    const SegDesc *segments;             // device table: the row geometry of row-group items
 };
 
 struct UlpReduceArgs {

@@ -1268,6 +1268,7 @@ struct RunArgs {
     uint32_t k0;
     uint32_t priority_phase;             // dispatch round of the block: (block * 4) / grid
     const SegTol *seg_tol;               // per-segment tolerances
+    const SegDesc *segments;             // row geometry of row-group items
     int equal_nan;
 };
 
@@ -1390,8 +1391,10 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
 // streamed candidate by candidate: the four vector registers per lane are packed with as many
 // candidates as fit (four when the tail needs one vector per lane, two when it needs two), the
 // loads of a batch -- and, for the first batch, of the reference -- are issued together, and the
-// whole batch is compared after a single wait.  Absent elements read as 0 on both sides.
-template <int DT>
+// whole batch is compared after a single wait.  Absent elements read as 0 on both sides.  A row
+// group (short rows of a pitched segment, a pitch apart) goes the same way: only the address and the
+// number of valid elements of a lane's vector differ.
+template <int DT, bool ROWS>
 __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_in)
 {
     typedef typename ItemOf<DT>::type Item;
@@ -1410,8 +1413,10 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     const uint32_t j = uniform32(in.first_item);
     const geak_item it = load_work_item(items, j);
     const SegTol tolerance = load_tol(seg_tol, it.segment);
+    ItemShape shape{0u, 1u, 0u, 0u, 0ull};
+    if constexpr (ROWS) shape = item_shape<DT>(it, uniform_ptr(in.segments));
     const uint32_t n = it.numel;
-    const uint32_t vectors = (n * Traits<DT>::W + kWaveSize * 16 - 1) / (kWaveSize * 16);    // 1..4 per lane
+    const uint32_t vectors = shape_vectors<DT>(shape, n);                                   // 1..4 per lane
     const uint32_t per_batch = vectors == 1 ? 4 : (vectors == 2 ? 2 : 1);                       // candidates per batch
     MaxPair *recs = board + (u64)it.segment * K * replicas + replica;         // candidate k: recs[k * replicas]
 
@@ -1421,17 +1426,17 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
         if (per_batch == 4) {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (kb + c < K) cur[c] = load_vec<DT>(table_entry(cand, kb + c) + it.byte_offset, lane, 0, n, false);
+                if (kb + c < K) cur[c] = load_shaped<DT, ROWS>(table_entry(cand, kb + c) + it.byte_offset, lane, 0, n, shape);
         } else if (per_batch == 2) {
 #pragma unroll
             for (int c = 0; c < 2; ++c)
                 if (kb + c < K) {
-                    cur[2 * c + 0] = load_vec<DT>(table_entry(cand, kb + c) + it.byte_offset, lane, 0, n, false);
-                    cur[2 * c + 1] = load_vec<DT>(table_entry(cand, kb + c) + it.byte_offset, lane, 1, n, false);
+                    cur[2 * c + 0] = load_shaped<DT, ROWS>(table_entry(cand, kb + c) + it.byte_offset, lane, 0, n, shape);
+                    cur[2 * c + 1] = load_shaped<DT, ROWS>(table_entry(cand, kb + c) + it.byte_offset, lane, 1, n, shape);
                 }
         } else {
 #pragma unroll
-            for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_vec<DT>(table_entry(cand, kb) + it.byte_offset, lane, v, n, false);
+            for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_shaped<DT, ROWS>(table_entry(cand, kb) + it.byte_offset, lane, v, n, shape);
         }
     };
 
@@ -1440,7 +1445,7 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     {
         u32x4 r[kVecPerLane];
 #pragma unroll
-        for (int v = 0; v < kVecPerLane; ++v) r[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, n, false);
+        for (int v = 0; v < kVecPerLane; ++v) r[v] = load_shaped<DT, ROWS>(ref_base + it.byte_offset, lane, v, n, shape);
         load_batch(0);                                     // in flight together with the reference
         ref.template stage_vec<0>(r[0], tolerance);
         ref.template stage_vec<1>(r[1], tolerance);
@@ -1536,6 +1541,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.k0 = (blockIdx.x / p.replicas) % K;
     r.priority_phase = (blockIdx.x * 4u) / gridDim.x;
     r.seg_tol = p.seg_tol;
+    r.segments = p.segments;
     r.equal_nan = p.equal_nan;
 
     // the wave's list of items: its first one from the wave table, then along the next links
@@ -1560,18 +1566,32 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
                 case GEAK_F8E5M2: next_j = process_run<GEAK_F8E5M2>(r, st); break;
                 default:        next_j = process_run<GEAK_I8>(r, st); break;
                 }
+            } else if (it.flags & GEAK_ITEM_ROWS) {
+                switch (it.dtype) {
+                case GEAK_F32: process_tail<GEAK_F32, true>(r, st); break;
+                case GEAK_F16: process_tail<GEAK_F16, true>(r, st); break;
+                case GEAK_BF16: process_tail<GEAK_BF16, true>(r, st); break;
+                case GEAK_I32: process_tail<GEAK_I32, true>(r, st); break;
+                case GEAK_I64: process_tail<GEAK_I64, true>(r, st); break;
+                case GEAK_U8: process_tail<GEAK_U8, true>(r, st); break;
+                case GEAK_F64: process_tail<GEAK_F64, true>(r, st); break;
+                case GEAK_F8E4M3: process_tail<GEAK_F8E4M3, true>(r, st); break;
+                case GEAK_F8E5M2: process_tail<GEAK_F8E5M2, true>(r, st); break;
+                default: process_tail<GEAK_I8, true>(r, st); break;
+                }
+                next_j = it.next;
             } else {
                 switch (it.dtype) {
-                case GEAK_F32:  process_tail<GEAK_F32>(r, st); break;
-                case GEAK_F16:  process_tail<GEAK_F16>(r, st); break;
-                case GEAK_BF16: process_tail<GEAK_BF16>(r, st); break;
-                case GEAK_I32:  process_tail<GEAK_I32>(r, st); break;
-                case GEAK_I64:  process_tail<GEAK_I64>(r, st); break;
-                case GEAK_U8:   process_tail<GEAK_U8>(r, st); break;
-                case GEAK_F64:  process_tail<GEAK_F64>(r, st); break;
-                case GEAK_F8E4M3: process_tail<GEAK_F8E4M3>(r, st); break;
-                case GEAK_F8E5M2: process_tail<GEAK_F8E5M2>(r, st); break;
-                default:        process_tail<GEAK_I8>(r, st); break;
+                case GEAK_F32: process_tail<GEAK_F32, false>(r, st); break;
+                case GEAK_F16: process_tail<GEAK_F16, false>(r, st); break;
+                case GEAK_BF16: process_tail<GEAK_BF16, false>(r, st); break;
+                case GEAK_I32: process_tail<GEAK_I32, false>(r, st); break;
+                case GEAK_I64: process_tail<GEAK_I64, false>(r, st); break;
+                case GEAK_U8: process_tail<GEAK_U8, false>(r, st); break;
+                case GEAK_F64: process_tail<GEAK_F64, false>(r, st); break;
+                case GEAK_F8E4M3: process_tail<GEAK_F8E4M3, false>(r, st); break;
+                case GEAK_F8E5M2: process_tail<GEAK_F8E5M2, false>(r, st); break;
+                default: process_tail<GEAK_I8, false>(r, st); break;
                 }
                 next_j = it.next;
             }
@@ -1644,17 +1664,23 @@ __device__ __forceinline__ uint32_t first_bad_in_vector(const u32x4 &qa, const u
     return best;
 }
 template <int DT>
-__device__ __forceinline__ uint32_t first_bad_of_thread(const unsigned char *rb, const unsigned char *cb, int tid, uint32_t numel,
-                                                        const SegTol &tolerance, int equal_nan)
+__device__ __forceinline__ uint32_t first_bad_of_thread(const unsigned char *rb, const unsigned char *cb, int tid, const geak_item &it,
+                                                        const SegDesc *segments, const SegTol &tolerance, int equal_nan)
 {
-    constexpr uint32_t E = Traits<DT>::E;
-    const uint32_t begin = (uint32_t)tid * E;
-    if (begin >= numel) return kNoItem;
-    const bool full = begin + E <= numel;
-    const u32x4 qb = load_vec<DT>(rb, tid & (kWaveSize - 1), tid >> 6, numel, full);
-    const u32x4 qa = load_vec<DT>(cb, tid & (kWaveSize - 1), tid >> 6, numel, full);
-    const uint32_t e = first_bad_in_vector<DT>(qa, qb, numel - begin, tolerance, equal_nan);
-    return e == kNoItem ? kNoItem : begin + e;
+    u32x4 qa, qb;
+    uint32_t first;
+    if (it.flags & GEAK_ITEM_ROWS) {                       // uniform
+        const ItemShape shape = item_shape<DT>(it, segments);
+        qb = load_row_slot<DT>(rb, (uint32_t)tid, shape, first);
+        qa = load_row_slot<DT>(cb, (uint32_t)tid, shape, first);
+    } else {
+        first = (uint32_t)tid * (uint32_t)Traits<DT>::E;
+        qb = load_vec<DT>(rb, tid & (kWaveSize - 1), tid >> 6, it.numel, false);
+        qa = load_vec<DT>(cb, tid & (kWaveSize - 1), tid >> 6, it.numel, false);
+    }
+    // positions outside the item read as 0 on both sides and are close under every rule
+    const uint32_t e = first_bad_in_vector<DT>(qa, qb, (uint32_t)Traits<DT>::E, tolerance, equal_nan);
+    return e == kNoItem ? kNoItem : first + e;
 }
 
 __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs p)
@@ -1701,7 +1727,8 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
     }
 
     // exact first index: re-read the first item that holds a mismatch, every thread one 16-byte vector of
-    // the reference and of the candidate (256 threads x 16 bytes: the whole item)
+    // the reference and of the candidate (256 threads x 16 bytes: the whole item; a row group's vector
+    // slots ascend with the element index like a contiguous item's)
     long long first = -1;
     if (first_item != kNoItem) {                // uniform: every thread holds the same first_item
         const geak_item it = p.items[first_item];
@@ -1710,16 +1737,16 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
         uint32_t best = kNoItem;
         if (it.flags & GEAK_ITEM_ALIGNED) {      // one 16-byte vector of each tensor per thread (uniform branch)
             switch (it.dtype) {
-            case GEAK_F32:  best = first_bad_of_thread<GEAK_F32>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            case GEAK_F16:  best = first_bad_of_thread<GEAK_F16>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            case GEAK_BF16: best = first_bad_of_thread<GEAK_BF16>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            case GEAK_I32:  best = first_bad_of_thread<GEAK_I32>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            case GEAK_I64:  best = first_bad_of_thread<GEAK_I64>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            case GEAK_U8:   best = first_bad_of_thread<GEAK_U8>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            case GEAK_I8:   best = first_bad_of_thread<GEAK_I8>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            case GEAK_F64:  best = first_bad_of_thread<GEAK_F64>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            case GEAK_F8E4M3: best = first_bad_of_thread<GEAK_F8E4M3>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
-            default:        best = first_bad_of_thread<GEAK_F8E5M2>(rb, cb, tid, it.numel, tolerance, p.equal_nan); break;
+            case GEAK_F32:  best = first_bad_of_thread<GEAK_F32>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_F16:  best = first_bad_of_thread<GEAK_F16>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_BF16: best = first_bad_of_thread<GEAK_BF16>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_I32:  best = first_bad_of_thread<GEAK_I32>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_I64:  best = first_bad_of_thread<GEAK_I64>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_U8:   best = first_bad_of_thread<GEAK_U8>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_I8:   best = first_bad_of_thread<GEAK_I8>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_F64:  best = first_bad_of_thread<GEAK_F64>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_F8E4M3: best = first_bad_of_thread<GEAK_F8E4M3>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
+            default:        best = first_bad_of_thread<GEAK_F8E5M2>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
             }
         } else {                                 // a segment's few elements before its first 16-byte boundary
             const uint32_t i = (uint32_t)tid;

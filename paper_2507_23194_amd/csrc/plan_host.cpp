@@ -105,6 +105,26 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
             const SegDesc &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
             if (!g.numel) continue;
+            // Short rows of a pitched segment that all start on 16-byte boundaries: whole rows are
+            // grouped into one item, as many as its 256 vector slots hold (a row takes
+            // ceil(row bytes / 16) of them), instead of one mostly idle item per row.
+            const uint64_t row_vectors = (g.row_elems * w + 15) / 16;
+            if (seg_rows(g) > 1 && g.byte_offset % 16 == 0 && g.pitch_bytes % 16 == 0 && row_vectors <= kItemBytes / 32) {
+                const uint64_t group = (kItemBytes / 16) / row_vectors;             // >= 2 rows per item
+                for (uint64_t r = 0; r < seg_rows(g); r += group) {
+                    const uint64_t rows_here = std::min<uint64_t>(group, seg_rows(g) - r);
+                    geak_item it{};
+                    it.byte_offset = g.byte_offset + r * g.pitch_bytes;
+                    it.elem_start = r * g.row_elems;
+                    it.segment = (uint32_t)s;
+                    it.numel = (uint16_t)(rows_here * g.row_elems);                 // at most 4096 / w elements
+                    it.next = kNoItem;
+                    it.dtype = (uint8_t)g.dtype;
+                    it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS);
+                    hp.items.push_back(it);
+                }
+                continue;
+            }
             // row by row (a contiguous segment is one row): head up to the next 16-byte boundary, full items, tail
             for (uint64_t r = 0; r < seg_rows(g); ++r) {
                 const uint64_t row_start = g.byte_offset + r * g.pitch_bytes;

@@ -188,6 +188,7 @@ struct UlpRunArgs {
     uint32_t first_item;
     uint32_t num_items;
     uint32_t K, k_begin, k_count;
+    const SegDesc *segments;
 };
 
 __device__ __forceinline__ uint32_t uniform32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -475,9 +476,10 @@ template <> struct UlpRefOf<GEAK_F8E5M2> { typedef UlpRefPacked<GEAK_F8E5M2> typ
 
 // TAIL = false: a run of consecutive FULL items of one dtype in the wave's list, every load an
 // unguarded 16-byte load, the next item's reference slice fetched behind the last candidate.
-// TAIL = true: one aligned item shorter than 4 KiB, guarded loads.
+// TAIL = true: one aligned item that is not a full one (a segment's tail, or a group of short rows of a
+// pitched segment), guarded loads.
 // Returns the index of the wave's first item it did not process.
-template <int DT, bool TAIL>
+template <int DT, bool TAIL, bool ROWS = false>
 __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_in)
 {
     constexpr bool full = !TAIL;
@@ -494,9 +496,16 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
 
     uint32_t j = uniform32(in.first_item);
     geak_item it = load_work_item(items, j);
+    ItemShape shape{0u, 1u, 0u, 0u, 0ull};
+    if constexpr (ROWS) shape = item_shape<DT>(it, uniform_ptr(in.segments));
+    // vector v of this lane: unguarded inside a run of full items, by the item's shape (tail or row group) otherwise
+    const auto fetch = [&](const unsigned char *base, int v, uint32_t n) {
+        if constexpr (TAIL) return load_shaped<DT, ROWS>(base, lane, v, n, shape);
+        else return load_vec<DT>(base, lane, v, n, full);
+    };
     u32x4 cur[kVecPerLane];
 #pragma unroll
-    for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, it.numel, full);
+    for (int v = 0; v < kVecPerLane; ++v) cur[v] = fetch(ref_base + it.byte_offset, v, it.numel);
     typedef typename UlpRefOf<DT>::type Ref;
     Ref ref;
     for (;;) {
@@ -510,10 +519,10 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
         // stage the reference slice; its registers are refilled with the pass's first candidate
         {
             const unsigned char *first = table_entry(cand, k_begin) + it.byte_offset;
-            ref.template stage<0>(cur[0]); cur[0] = load_vec<DT>(first, lane, 0, it.numel, full);
-            ref.template stage<1>(cur[1]); cur[1] = load_vec<DT>(first, lane, 1, it.numel, full);
-            ref.template stage<2>(cur[2]); cur[2] = load_vec<DT>(first, lane, 2, it.numel, full);
-            ref.template stage<3>(cur[3]); cur[3] = load_vec<DT>(first, lane, 3, it.numel, full);
+            ref.template stage<0>(cur[0]); cur[0] = fetch(first, 0, it.numel);
+            ref.template stage<1>(cur[1]); cur[1] = fetch(first, 1, it.numel);
+            ref.template stage<2>(cur[2]); cur[2] = fetch(first, 2, it.numel);
+            ref.template stage<3>(cur[3]); cur[3] = fetch(first, 3, it.numel);
         }
         for (uint32_t kk = 0; kk < k_count; ++kk) {
             const bool last = kk + 1 == k_count;
@@ -524,10 +533,10 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
                                              : table_entry(cand, k_begin + kk) + it.byte_offset;
             GEAK_AS_LDS uint32_t *row = ulp_row(st, kk);
             typename Ref::Counts c = Ref::zero();
-            ref.template compare<0>(cur[0], c, row, st.nslots); cur[0] = load_vec<DT>(next, lane, 0, it.numel, full);
-            ref.template compare<1>(cur[1], c, row, st.nslots); cur[1] = load_vec<DT>(next, lane, 1, it.numel, full);
-            ref.template compare<2>(cur[2], c, row, st.nslots); cur[2] = load_vec<DT>(next, lane, 2, it.numel, full);
-            ref.template compare<3>(cur[3], c, row, st.nslots); cur[3] = load_vec<DT>(next, lane, 3, it.numel, full);
+            ref.template compare<0>(cur[0], c, row, st.nslots); cur[0] = fetch(next, 0, it.numel);
+            ref.template compare<1>(cur[1], c, row, st.nslots); cur[1] = fetch(next, 1, it.numel);
+            ref.template compare<2>(cur[2], c, row, st.nslots); cur[2] = fetch(next, 2, it.numel);
+            ref.template compare<3>(cur[3], c, row, st.nslots); cur[3] = fetch(next, 3, it.numel);
             ref.commit(c, it.numel, row, lane);
         }
         if (it.flags & GEAK_ITEM_LAST) ulp_end_run(st, partials, it.slot, K, k_begin, k_count, lane);
@@ -603,6 +612,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
     r.K = p.num_candidates;
     r.k_begin = p.k_begin;
     r.k_count = p.k_count;
+    r.segments = p.segments;
 
     const GEAK_AS_CONSTANT uint32_t *wave_first = (const GEAK_AS_CONSTANT uint32_t *)p.wave_first;
     uint32_t j = wave_first[blockIdx.x * kWavesPerBlock + wave];
@@ -624,18 +634,31 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
                 case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, false>(r, st); break;
                 default:        next_j = ulp_run<GEAK_I8, false>(r, st); break;
                 }
+            } else if (it.flags & GEAK_ITEM_ROWS) {
+                switch (it.dtype) {
+                case GEAK_F32: next_j = ulp_run<GEAK_F32, true, true>(r, st); break;
+                case GEAK_F16: next_j = ulp_run<GEAK_F16, true, true>(r, st); break;
+                case GEAK_BF16: next_j = ulp_run<GEAK_BF16, true, true>(r, st); break;
+                case GEAK_I32: next_j = ulp_run<GEAK_I32, true, true>(r, st); break;
+                case GEAK_I64: next_j = ulp_run<GEAK_I64, true, true>(r, st); break;
+                case GEAK_U8: next_j = ulp_run<GEAK_U8, true, true>(r, st); break;
+                case GEAK_F64: next_j = ulp_run<GEAK_F64, true, true>(r, st); break;
+                case GEAK_F8E4M3: next_j = ulp_run<GEAK_F8E4M3, true, true>(r, st); break;
+                case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, true, true>(r, st); break;
+                default: next_j = ulp_run<GEAK_I8, true, true>(r, st); break;
+                }
             } else {
                 switch (it.dtype) {
-                case GEAK_F32:  next_j = ulp_run<GEAK_F32, true>(r, st); break;
-                case GEAK_F16:  next_j = ulp_run<GEAK_F16, true>(r, st); break;
-                case GEAK_BF16: next_j = ulp_run<GEAK_BF16, true>(r, st); break;
-                case GEAK_I32:  next_j = ulp_run<GEAK_I32, true>(r, st); break;
-                case GEAK_I64:  next_j = ulp_run<GEAK_I64, true>(r, st); break;
-                case GEAK_U8:   next_j = ulp_run<GEAK_U8, true>(r, st); break;
-                case GEAK_F64:  next_j = ulp_run<GEAK_F64, true>(r, st); break;
-                case GEAK_F8E4M3: next_j = ulp_run<GEAK_F8E4M3, true>(r, st); break;
-                case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, true>(r, st); break;
-                default:        next_j = ulp_run<GEAK_I8, true>(r, st); break;
+                case GEAK_F32: next_j = ulp_run<GEAK_F32, true, false>(r, st); break;
+                case GEAK_F16: next_j = ulp_run<GEAK_F16, true, false>(r, st); break;
+                case GEAK_BF16: next_j = ulp_run<GEAK_BF16, true, false>(r, st); break;
+                case GEAK_I32: next_j = ulp_run<GEAK_I32, true, false>(r, st); break;
+                case GEAK_I64: next_j = ulp_run<GEAK_I64, true, false>(r, st); break;
+                case GEAK_U8: next_j = ulp_run<GEAK_U8, true, false>(r, st); break;
+                case GEAK_F64: next_j = ulp_run<GEAK_F64, true, false>(r, st); break;
+                case GEAK_F8E4M3: next_j = ulp_run<GEAK_F8E4M3, true, false>(r, st); break;
+                case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, true, false>(r, st); break;
+                default: next_j = ulp_run<GEAK_I8, true, false>(r, st); break;
                 }
             }
             j = __builtin_amdgcn_readfirstlane(next_j);

@@ -542,7 +542,16 @@ def test_verdicts_over_all_unit_tests(oracle_mod):
     assert verdict.tolist() == [False, True, False] and failed.tolist() == [1, 0, 1]
 
 
-@pytest.mark.parametrize("case", ["long_rows", "short_rows", "odd_bytes", "mixed"])
+def _stacked(rows_specs, start=0):
+    """Pitched segments one after the other, each starting on the next 16-byte boundary."""
+    out, off = [], start
+    for rows, row_elems, pitch, dt in rows_specs:
+        out.append((off, rows, row_elems, pitch, dt))
+        off = (off + rows * pitch + 15) // 16 * 16
+    return out
+
+
+@pytest.mark.parametrize("case", ["long_rows", "short_rows", "odd_bytes", "mixed", "row_groups"])
 def test_pitched_segments(oracle_mod, case):
     """Outputs in padded buffers: rows `pitch_bytes` apart, the padding between them filled with different
     garbage in every tensor.  Records, report, verdicts and ulp histograms equal the oracle's on contiguous
@@ -554,6 +563,12 @@ def test_pitched_segments(oracle_mod, case):
         "odd_bytes": [(3, 40, 1000, 1003, "u8"), (50000, 9, 700, 712, "f8e4m3")],  # rows start on any byte
         "mixed": [(0, 6, 5000, 20480, "f32"), (131072, 3, 3000, 24064, "f64"), (204800, 17, 33, 80, "bf16"), (208000, 0, 5, 64, "i32"),
                   (208000, 2, 4097, 16400, "i32")],
+        # short rows on 16-byte boundaries, grouped into items: every dtype, rows of one vector up to 128 vectors,
+        # partial last vectors, row counts that leave a short last group
+        "row_groups": _stacked([(1000, 64, 256, "bf16"), (77, 33, 80, "bf16"), (300, 100, 112, "u8"), (9, 3, 32, "f64"),
+                                (130, 50, 64, "f8e4m3"), (200, 17, 80, "f32"), (40, 100, 816, "i64"), (333, 7, 16, "f16"),
+                                (50, 500, 2016, "i32"), (64, 1000, 1008, "i8"), (20, 2048, 2064, "f8e5m2"), (3, 5, 48, "f32"),
+                                (515, 31, 128, "f32")], start=64),
     }[case]
     K = 3
     total = max(off + (rows - 1) * pitch + re * synth.ELEM_SIZE[dt] if rows else off for off, rows, re, pitch, dt in layouts)

@@ -327,12 +327,20 @@ def test_pitched_segments_table(lib):
         w = esize[dt]
         e0, n = int(it["elem_start"]), int(it["numel"])
         r, c = divmod(e0, row_elems)
-        assert c + n <= row_elems                                       # an item never crosses a row
+        if it["flags"] & B.GEAK_ITEM_ROWS:                              # whole short rows, grouped
+            assert c == 0 and n % row_elems == 0 and n // row_elems >= 1
+            assert off % 16 == 0 and pitch % 16 == 0
+            assert (n // row_elems) * -(-row_elems * w // 16) <= 256   # the rows' vectors fit the item's 256 slots
+            assert not it["flags"] & B.GEAK_ITEM_FULL
+        else:
+            assert c + n <= row_elems                                   # otherwise an item never crosses a row
         assert int(it["byte_offset"]) == off + r * pitch + c * w
         assert bool(it["flags"] & B.GEAK_ITEM_ALIGNED) == (int(it["byte_offset"]) % 16 == 0)
         assert e0 == covered.get(s, 0)                                  # in order, no gaps
         covered[s] = e0 + n
     assert covered == {0: 15000, 1: 700, 2: 4000}
+    assert [int(i["numel"]) for i in items if i["segment"] == 1] == [700]      # seven rows of 400 bytes: one group
+    assert not any(i["flags"] & B.GEAK_ITEM_ROWS for i in items if i["segment"] != 1)   # long rows, or rows on odd bytes
     B.geak_check_destroy(plan)
     # rows back to back are the contiguous layout
     st, p1 = B.geak_check_plan_pitched([(64, 10, 3000, 12000, "f32")], None, 2, 0, 0, 0, -1)
@@ -341,6 +349,33 @@ def test_pitched_segments_table(lib):
     assert (B.geak_check_plan_items(p1) == B.geak_check_plan_items(p2)).all()
     B.geak_check_destroy(p1)
     B.geak_check_destroy(p2)
+
+
+@pytest.mark.parametrize("rows,row_elems,pitch,dt,group", [
+    (1000, 64, 256, "bf16", 32),          # 128-byte rows: 8 vectors each, 32 rows per item
+    (77, 33, 80, "bf16", 51),             # 66 bytes: 5 vectors (the last partial), 51 rows per item
+    (10, 512, 2064, "f32", 2),            # 2048 bytes: the longest rows that are grouped
+    (10, 513, 2064, "f32", 0),            # one element more: row by row, each a tail
+    (300, 100, 112, "u8", 36),            # 100 bytes: 7 vectors
+    (9, 3, 32, "f64", 128),               # 24 bytes: 2 vectors
+    (5, 64, 264, "bf16", 0),              # pitch no multiple of 16: rows start off the boundary, row by row
+])
+def test_row_group_items(lib, rows, row_elems, pitch, dt, group):
+    """Short rows that start on 16-byte boundaries are grouped, as many whole rows as 256 vector slots hold."""
+    st, plan = B.geak_check_plan_pitched([(32, rows, row_elems, pitch, dt)], None, 2, 0, 0, 0, -1)
+    assert st == B.GEAK_OK
+    items = B.geak_check_plan_items(plan)
+    grouped = [bool(i["flags"] & B.GEAK_ITEM_ROWS) for i in items]
+    if not group:
+        assert not any(grouped)
+    else:
+        assert all(grouped)
+        counts = [int(i["numel"]) // row_elems for i in items]
+        assert counts == [group] * (rows // group) + ([rows % group] if rows % group else [])
+        assert [int(i["elem_start"]) for i in items] == [g * group * row_elems for g in range(len(items))]
+        assert [int(i["byte_offset"]) for i in items] == [32 + g * group * pitch for g in range(len(items))]
+    assert sum(int(i["numel"]) for i in items) == rows * row_elems
+    B.geak_check_destroy(plan)
 
 
 @pytest.mark.parametrize("segs,status", [
