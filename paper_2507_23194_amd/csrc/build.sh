@@ -2,14 +2,21 @@
 # Builds libgeakcheck.so for gfx950 next to the package (in-tree, no JIT cache).
 #   -ffp-contract=off                 the rule's product and sum are rounded separately
 #   -packed-fp32-ops (target feature) no packed-FP32 VALU forms
+# The translation units are compiled side by side, then linked.
 set -euo pipefail
 here="$(cd "$(dirname "${BASH_SOURCE[0]}")" && pwd)"
 root="$(cd "$here/../.." && pwd)"
 out="$here/../libgeakcheck.so"
-hipcc --offload-arch=gfx950 -O3 -std=c++17 -fPIC -shared -ffp-contract=off \
-      -Xclang -target-feature -Xclang -packed-fp32-ops \
-      -Wall -Wno-unused-function \
-      -I"$root/include" -I"$here" \
-      "$here/kernels.hip" "$here/ulp_kernels.hip" "$here/verdict_kernel.hip" "$here/metrics_host.cpp" "$here/api.cpp" "$here/plan_host.cpp" \
-      -o "$out" "$@"
+obj="$(mktemp -d)"
+trap 'rm -rf "$obj"' EXIT
+flags=(--offload-arch=gfx950 -O3 -std=c++17 -fPIC -ffp-contract=off
+       -Xclang -target-feature -Xclang -packed-fp32-ops
+       -Wall -Wno-unused-function -I"$root/include" -I"$here" "$@")
+pids=()
+for src in kernels.hip ulp_kernels.hip verdict_kernel.hip metrics_host.cpp api.cpp plan_host.cpp; do
+    hipcc "${flags[@]}" -c "$here/$src" -o "$obj/${src%.*}.o" &
+    pids+=($!)
+done
+for pid in "${pids[@]}"; do wait "$pid"; done
+hipcc --offload-arch=gfx950 -shared -fPIC "$obj"/*.o -o "$out"
 echo "built $out"
