@@ -1639,6 +1639,7 @@ __device__ __forceinline__ bool element_close(const unsigned char *ref, const un
 }
 
 constexpr int kReduceThreads = 256;
+constexpr uint64_t kReduceWavePairs = 1024;        // from this many (segment, candidate) pairs on, one wave per pair
 
 // Least element of one 16-byte vector pair that is not close, or kNoItem: the rescan of an item's
 // first mismatch, one vector per thread.  `valid` elements of the vector lie inside the item.
@@ -1783,6 +1784,106 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
             rec->max_abs_err = __builtin_bit_cast(double, a);
             rec->max_rel_err = __builtin_bit_cast(double, r);
         }
+    }
+}
+
+// The same reduction with one wave per (segment, candidate) and no barrier: for plans with many pairs
+// (ragged batches), where a whole block per pair leaves most of its threads without a slot to read
+// and the number of blocks, not the work, sets the time.  A lane takes four vector slots of the
+// item that is scanned again.
+template <int DT>
+__device__ __forceinline__ uint32_t first_bad_of_lane(const unsigned char *rb, const unsigned char *cb, int lane, const geak_item &it,
+                                                      const SegDesc *segments, const SegTol &tolerance, int equal_nan)
+{
+    uint32_t best = kNoItem;
+#pragma unroll
+    for (int v = kVecPerLane - 1; v >= 0; --v) {            // downwards, so that the least index is kept
+        const uint32_t b = first_bad_of_thread<DT>(rb, cb, v * kWaveSize + lane, it, segments, tolerance, equal_nan);
+        best = b < best ? b : best;
+    }
+    return best;
+}
+
+__global__ __launch_bounds__(kReduceThreads) void reduce_wave_kernel(const ReduceArgs p)
+{
+    const uint32_t K = p.num_candidates;
+    const int tid = threadIdx.x, lane = tid & (kWaveSize - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane((uint32_t)tid / kWaveSize);
+    const u64 pair = (u64)blockIdx.x * (kReduceThreads / kWaveSize) + wave;
+    if (pair >= (u64)p.num_segments * K) return;
+    const uint32_t seg = (uint32_t)(pair / K), k = (uint32_t)(pair % K);
+    const uint32_t sb = p.slot_begin[seg], se = p.slot_begin[seg + 1];
+    if (sb == se) return;                       // empty segment: the neutral record stands
+
+    // the two maxima: asked for first, used last
+    const MaxPair *mp = p.board + ((u64)seg * K + k) * p.replicas;
+    u64 a = 0, r = 0;
+    for (uint32_t i = lane; i < p.replicas; i += kWaveSize) {
+        const u64 ai = __builtin_bit_cast(u64, mp[i].abs), ri = __builtin_bit_cast(u64, mp[i].rel);
+        a = ai > a ? ai : a;
+        r = ri > r ? ri : r;
+    }
+
+    u64 count = 0;
+    uint32_t first_item = kNoItem;
+    for (uint32_t s0 = sb + lane; s0 < se; s0 += 8 * kWaveSize) {
+        Partial q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t s = s0 + u * kWaveSize;
+            q[u].count = 0;
+            q[u].first_item = kNoItem;
+            if (s < se) q[u] = p.partials[(u64)s * K + k];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            count += q[u].count;
+            first_item = q[u].first_item < first_item ? q[u].first_item : first_item;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) count += (u64)__shfl_xor((long long)count, o, kWaveSize);
+    first_item = wave_min_u(first_item);
+
+    long long first = -1;
+    if (first_item != kNoItem) {                // uniform over the wave
+        const geak_item it = p.items[first_item];
+        const SegTol tolerance = p.seg_tol[seg];
+        const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
+        uint32_t best = kNoItem;
+        if (it.flags & GEAK_ITEM_ALIGNED) {
+            switch (it.dtype) {
+            case GEAK_F32:  best = first_bad_of_lane<GEAK_F32>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_F16:  best = first_bad_of_lane<GEAK_F16>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_BF16: best = first_bad_of_lane<GEAK_BF16>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_I32:  best = first_bad_of_lane<GEAK_I32>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_I64:  best = first_bad_of_lane<GEAK_I64>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_U8:   best = first_bad_of_lane<GEAK_U8>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_I8:   best = first_bad_of_lane<GEAK_I8>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_F64:  best = first_bad_of_lane<GEAK_F64>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            case GEAK_F8E4M3: best = first_bad_of_lane<GEAK_F8E4M3>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            default:        best = first_bad_of_lane<GEAK_F8E5M2>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
+            }
+        } else {                                 // a segment's few elements before its first 16-byte boundary
+            const uint32_t i = (uint32_t)lane;
+            if (i < it.numel && !element_close(rb, cb, i, it.dtype, tolerance, p.equal_nan)) best = i;
+        }
+        best = wave_min_u(best);
+        first = (long long)it.elem_start + (long long)best;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const u64 ao = (u64)__shfl_xor((long long)a, o, kWaveSize), ro = (u64)__shfl_xor((long long)r, o, kWaveSize);
+        a = ao > a ? ao : a;
+        r = ro > r ? ro : r;
+    }
+    if (lane == 0) {
+        geak_result *rec = p.results + pair;
+        rec->pass = (count == 0);
+        rec->mismatch_count = count;
+        rec->first_mismatch = first;
+        rec->max_abs_err = __builtin_bit_cast(double, a);
+        rec->max_rel_err = __builtin_bit_cast(double, r);
     }
 }
 
@@ -1993,7 +2094,14 @@ int launch_reduce(const ReduceArgs &args, void *stream)
 {
     const uint64_t pairs = (uint64_t)args.num_segments * args.num_candidates;
     if (!pairs) return (int)hipSuccess;
-    hipLaunchKernelGGL(reduce_kernel, dim3((uint32_t)pairs), dim3(kReduceThreads), 0, (hipStream_t)stream, args);
+    // Few pairs: a block each, so that a pair's many slots are read by many threads.  Many pairs: a wave each.
+    if (pairs < kReduceWavePairs) {
+        hipLaunchKernelGGL(reduce_kernel, dim3((uint32_t)pairs), dim3(kReduceThreads), 0, (hipStream_t)stream, args);
+    } else {
+        const uint64_t per_block = kReduceThreads / kWaveSize;
+        hipLaunchKernelGGL(reduce_wave_kernel, dim3((uint32_t)((pairs + per_block - 1) / per_block)), dim3(kReduceThreads), 0,
+                           (hipStream_t)stream, args);
+    }
     return (int)hipGetLastError();
 }
 

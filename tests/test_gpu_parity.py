@@ -212,6 +212,21 @@ def test_ragged_unaligned_starts(oracle_mod, align):
     _assert_same(gpu, cpu, f"ragged align={align}")
 
 
+@pytest.mark.parametrize("align,dtypes", [(1, ("u8", "f32", "i8", "f16", "i64", "f64", "f8e4m3", "bf16", "f8e5m2", "i32")),
+                                          (16, ("f32", "f16", "bf16", "i32"))])
+def test_ragged_many_pairs(oracle_mod, align, dtypes):
+    """Plans with more than a thousand (segment, candidate) pairs are reduced by one wave per pair: every
+    dtype, segment starts on any byte, mismatches in heads, full items and tails."""
+    print("ragged, many pairs", align, flush=True)
+    w = synth.config4(num_segments=420, log2_max=13.0, num_candidates=3, device="cuda", align=align, seed=300 + align, dtypes=dtypes)
+    assert len(w.segments) * len(w.cands) >= 1024
+    gpu = B.check_workload(w)
+    cpu = workload_oracle(oracle_mod, w)
+    _assert_same(gpu, cpu, f"ragged, many pairs, align={align}")
+    for (s, k), e in w.expect.items():
+        assert int(gpu[s, k]["mismatch_count"]) == e["count"] and int(gpu[s, k]["first_mismatch"]) == e["first"]
+
+
 def test_per_segment_tolerances(oracle_mod):
     """Every segment judged with its own atol / rtol (tight, loose, zero): records equal the oracle's,
     called segment by segment with that segment's pair; int32 segments ignore theirs."""

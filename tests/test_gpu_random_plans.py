@@ -154,3 +154,50 @@ def test_random_pitched_plan(oracle_mod, seed):
                 assert np.array_equal(got[f], rep[f], equal_nan=True), (seed, s, k, layouts[s], f)
             want = oracle_mod.ulp_histogram_segment(b, cands[k], n, dt)
             assert (hist[s, k] == want).all(), (seed, s, k, layouts[s], hist[s, k], want)
+
+
+def test_many_short_pitched_segments(oracle_mod):
+    """Several hundred small pitched segments (row groups, tails, rows off the 16-byte grid) with four
+    candidates: more than a thousand pairs, so one wave reduces each, rescans of row groups included."""
+    rng = np.random.default_rng(4242)
+    K, layouts, flat, off = 4, [], [], 0
+    for s in range(300):
+        dt = DTYPES[s % len(DTYPES)]
+        w = synth.ELEM_SIZE[dt]
+        rows, row_elems = int(rng.integers(1, 30)), int(rng.integers(1, 600 // w + 2))
+        if s % 3:
+            pitch = (row_elems * w + 15) // 16 * 16 + 16 * int(rng.integers(0, 2))
+            off = (off + 15) // 16 * 16
+        else:
+            pitch = row_elems * w + w * int(rng.integers(1, 4))
+            off = (off + w - 1) // w * w + w
+        layouts.append((off, rows, row_elems, pitch, dt))
+        n = rows * row_elems
+        b, _ = _special_case(rng, dt, n)
+        cands = [b.copy(), _special_case(rng, dt, n)[1], b.copy(), b.copy()]
+        cands[1][: n // 2] = b[: n // 2]
+        cands[3][n - 1:] = _special_case(rng, dt, n)[1][n - 1:]              # at most the last element differs
+        flat.append((b, cands, n, dt))
+        off += (rows - 1) * pitch + row_elems * w
+    total = (off + 31) // 16 * 16
+    ref = rng.integers(0, 256, total, dtype=np.uint8)
+    cbufs = [rng.integers(0, 256, total, dtype=np.uint8) for _ in range(K)]
+    for (off, rows, row_elems, pitch, dt), (b, cands, n, _) in zip(layouts, flat):
+        w = synth.ELEM_SIZE[dt]
+        for r in range(rows):
+            lo = off + r * pitch
+            ref[lo:lo + row_elems * w] = b[r * row_elems:(r + 1) * row_elems].view(np.uint8)
+            for k in range(K):
+                cbufs[k][lo:lo + row_elems * w] = cands[k][r * row_elems:(r + 1) * row_elems].view(np.uint8)
+    dref = torch.from_numpy(ref).cuda()
+    dc = [torch.from_numpy(c).cuda() for c in cbufs]
+    ck = B.Checker(pitched=layouts, num_candidates=K, atol=1e-3, rtol=1e-2, equal_nan=True, device=0)
+    try:
+        ck.run(dref, dc)
+        gpu = ck.read().copy()
+    finally:
+        ck.close()
+    for s, (b, cands, n, dt) in enumerate(flat):
+        for k in range(K):
+            cpu = oracle_mod.check_segment(b, cands[k], n, dt, 1e-3, 1e-2, True)
+            assert record_tuple(gpu[s, k]) == record_tuple(cpu), (s, k, layouts[s])
