@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # They describe the kernel sources whose digest is recorded with them: once a source has changed,
 # the figures no longer apply and roofline.traffic is reported as null until they are retaken.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "2e6c06a6facabbf748f2e27255bfb2da8fe97ea8343908545ba0e3e08c8446e3",
-    "bytes": {2: 8.7997e9, 3: 9.2011e9, 4: 1.2454e9, 5: 141.8711e9},
+    "sources_sha256": "59c485ec83ddfbe12f5f4bf65006ad976d14ebd2c8bc53a9b3fae192c1e9b3c2",
+    "bytes": {2: 8.7998e9, 3: 9.2010e9, 4: 1.2453e9, 5: 141.8713e9},
 }
 KERNEL_SOURCES = ["kernels.hip", "device_common.hpp", "plan_host.cpp", "api.cpp", "geak_internal.hpp"]
 
