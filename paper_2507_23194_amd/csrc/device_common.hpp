@@ -257,5 +257,24 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
+// Calls f(Index<DT>{}) for the dtype code `dtype` (validated when the plan is built): the one place
+// where a run-time dtype selects a routine's instantiation.
+template <typename F>
+__device__ __forceinline__ void for_dtype(int dtype, F &&f)
+{
+    switch (dtype) {
+    case GEAK_F32:    f(Index<GEAK_F32>{}); break;
+    case GEAK_F16:    f(Index<GEAK_F16>{}); break;
+    case GEAK_BF16:   f(Index<GEAK_BF16>{}); break;
+    case GEAK_I32:    f(Index<GEAK_I32>{}); break;
+    case GEAK_I64:    f(Index<GEAK_I64>{}); break;
+    case GEAK_U8:     f(Index<GEAK_U8>{}); break;
+    case GEAK_I8:     f(Index<GEAK_I8>{}); break;
+    case GEAK_F64:    f(Index<GEAK_F64>{}); break;
+    case GEAK_F8E4M3: f(Index<GEAK_F8E4M3>{}); break;
+    default:          f(Index<GEAK_F8E5M2>{}); break;
+    }
+}
+
 }  // namespace
 }  // namespace geak

@@ -1554,45 +1554,12 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
             r.first_item = j;
             uint32_t next_j;
             if (it.flags & GEAK_ITEM_FULL) {
-                switch (it.dtype) {
-                case GEAK_F32:  next_j = process_run<GEAK_F32>(r, st); break;
-                case GEAK_F16:  next_j = process_run<GEAK_F16>(r, st); break;
-                case GEAK_BF16: next_j = process_run<GEAK_BF16>(r, st); break;
-                case GEAK_I32:  next_j = process_run<GEAK_I32>(r, st); break;
-                case GEAK_I64:  next_j = process_run<GEAK_I64>(r, st); break;
-                case GEAK_U8:   next_j = process_run<GEAK_U8>(r, st); break;
-                case GEAK_F64:  next_j = process_run<GEAK_F64>(r, st); break;
-                case GEAK_F8E4M3: next_j = process_run<GEAK_F8E4M3>(r, st); break;
-                case GEAK_F8E5M2: next_j = process_run<GEAK_F8E5M2>(r, st); break;
-                default:        next_j = process_run<GEAK_I8>(r, st); break;
-                }
+                for_dtype(it.dtype, [&](auto dt) { next_j = process_run<decltype(dt)::value>(r, st); });
             } else if (it.flags & GEAK_ITEM_ROWS) {
-                switch (it.dtype) {
-                case GEAK_F32: process_tail<GEAK_F32, true>(r, st); break;
-                case GEAK_F16: process_tail<GEAK_F16, true>(r, st); break;
-                case GEAK_BF16: process_tail<GEAK_BF16, true>(r, st); break;
-                case GEAK_I32: process_tail<GEAK_I32, true>(r, st); break;
-                case GEAK_I64: process_tail<GEAK_I64, true>(r, st); break;
-                case GEAK_U8: process_tail<GEAK_U8, true>(r, st); break;
-                case GEAK_F64: process_tail<GEAK_F64, true>(r, st); break;
-                case GEAK_F8E4M3: process_tail<GEAK_F8E4M3, true>(r, st); break;
-                case GEAK_F8E5M2: process_tail<GEAK_F8E5M2, true>(r, st); break;
-                default: process_tail<GEAK_I8, true>(r, st); break;
-                }
+                for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, true>(r, st); });
                 next_j = it.next;
             } else {
-                switch (it.dtype) {
-                case GEAK_F32: process_tail<GEAK_F32, false>(r, st); break;
-                case GEAK_F16: process_tail<GEAK_F16, false>(r, st); break;
-                case GEAK_BF16: process_tail<GEAK_BF16, false>(r, st); break;
-                case GEAK_I32: process_tail<GEAK_I32, false>(r, st); break;
-                case GEAK_I64: process_tail<GEAK_I64, false>(r, st); break;
-                case GEAK_U8: process_tail<GEAK_U8, false>(r, st); break;
-                case GEAK_F64: process_tail<GEAK_F64, false>(r, st); break;
-                case GEAK_F8E4M3: process_tail<GEAK_F8E4M3, false>(r, st); break;
-                case GEAK_F8E5M2: process_tail<GEAK_F8E5M2, false>(r, st); break;
-                default: process_tail<GEAK_I8, false>(r, st); break;
-                }
+                for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, false>(r, st); });
                 next_j = it.next;
             }
             j = __builtin_amdgcn_readfirstlane(next_j);
@@ -1737,18 +1704,9 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
         const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
         uint32_t best = kNoItem;
         if (it.flags & GEAK_ITEM_ALIGNED) {      // one 16-byte vector of each tensor per thread (uniform branch)
-            switch (it.dtype) {
-            case GEAK_F32:  best = first_bad_of_thread<GEAK_F32>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_F16:  best = first_bad_of_thread<GEAK_F16>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_BF16: best = first_bad_of_thread<GEAK_BF16>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_I32:  best = first_bad_of_thread<GEAK_I32>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_I64:  best = first_bad_of_thread<GEAK_I64>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_U8:   best = first_bad_of_thread<GEAK_U8>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_I8:   best = first_bad_of_thread<GEAK_I8>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_F64:  best = first_bad_of_thread<GEAK_F64>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_F8E4M3: best = first_bad_of_thread<GEAK_F8E4M3>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            default:        best = first_bad_of_thread<GEAK_F8E5M2>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan); break;
-            }
+            for_dtype(it.dtype, [&](auto dt) {
+                best = first_bad_of_thread<decltype(dt)::value>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan);
+            });
         } else {                                 // a segment's few elements before its first 16-byte boundary
             const uint32_t i = (uint32_t)tid;
             if (i < it.numel && !element_close(rb, cb, i, it.dtype, tolerance, p.equal_nan)) best = i;
@@ -1852,18 +1810,9 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_wave_kernel(const Reduc
         const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
         uint32_t best = kNoItem;
         if (it.flags & GEAK_ITEM_ALIGNED) {
-            switch (it.dtype) {
-            case GEAK_F32:  best = first_bad_of_lane<GEAK_F32>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_F16:  best = first_bad_of_lane<GEAK_F16>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_BF16: best = first_bad_of_lane<GEAK_BF16>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_I32:  best = first_bad_of_lane<GEAK_I32>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_I64:  best = first_bad_of_lane<GEAK_I64>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_U8:   best = first_bad_of_lane<GEAK_U8>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_I8:   best = first_bad_of_lane<GEAK_I8>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_F64:  best = first_bad_of_lane<GEAK_F64>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            case GEAK_F8E4M3: best = first_bad_of_lane<GEAK_F8E4M3>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            default:        best = first_bad_of_lane<GEAK_F8E5M2>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan); break;
-            }
+            for_dtype(it.dtype, [&](auto dt) {
+                best = first_bad_of_lane<decltype(dt)::value>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan);
+            });
         } else {                                 // a segment's few elements before its first 16-byte boundary
             const uint32_t i = (uint32_t)lane;
             if (i < it.numel && !element_close(rb, cb, i, it.dtype, tolerance, p.equal_nan)) best = i;
@@ -2015,18 +1964,9 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     const SegTol tolerance = p.seg_tol[seg];
     const unsigned char *rb = p.ref + sg.byte_offset, *cb = p.cand_table[k] + sg.byte_offset;
     geak_mismatch *out = p.records + (u64)blockIdx.x * p.max_records;
-    switch (sg.dtype) {                                      // uniform
-    case GEAK_F32:  report_pair<GEAK_F32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_F16:  report_pair<GEAK_F16>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_BF16: report_pair<GEAK_BF16>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_I32:  report_pair<GEAK_I32>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_I64:  report_pair<GEAK_I64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_U8:   report_pair<GEAK_U8>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_F64:  report_pair<GEAK_F64>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_F8E4M3: report_pair<GEAK_F8E4M3>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    case GEAK_F8E5M2: report_pair<GEAK_F8E5M2>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    default:        report_pair<GEAK_I8>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); break;
-    }
+    for_dtype(sg.dtype, [&](auto dt) {                     // uniform
+        report_pair<decltype(dt)::value>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt);
+    });
 }
 
 // ---- read probe: what a kernel that only reads the same bytes achieves ---------------------------

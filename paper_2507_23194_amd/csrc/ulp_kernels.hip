@@ -622,44 +622,11 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
             r.first_item = j;
             uint32_t next_j;
             if (it.flags & GEAK_ITEM_FULL) {
-                switch (it.dtype) {
-                case GEAK_F32:  next_j = ulp_run<GEAK_F32, false>(r, st); break;
-                case GEAK_F16:  next_j = ulp_run<GEAK_F16, false>(r, st); break;
-                case GEAK_BF16: next_j = ulp_run<GEAK_BF16, false>(r, st); break;
-                case GEAK_I32:  next_j = ulp_run<GEAK_I32, false>(r, st); break;
-                case GEAK_I64:  next_j = ulp_run<GEAK_I64, false>(r, st); break;
-                case GEAK_U8:   next_j = ulp_run<GEAK_U8, false>(r, st); break;
-                case GEAK_F64:  next_j = ulp_run<GEAK_F64, false>(r, st); break;
-                case GEAK_F8E4M3: next_j = ulp_run<GEAK_F8E4M3, false>(r, st); break;
-                case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, false>(r, st); break;
-                default:        next_j = ulp_run<GEAK_I8, false>(r, st); break;
-                }
+                for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, false>(r, st); });
             } else if (it.flags & GEAK_ITEM_ROWS) {
-                switch (it.dtype) {
-                case GEAK_F32: next_j = ulp_run<GEAK_F32, true, true>(r, st); break;
-                case GEAK_F16: next_j = ulp_run<GEAK_F16, true, true>(r, st); break;
-                case GEAK_BF16: next_j = ulp_run<GEAK_BF16, true, true>(r, st); break;
-                case GEAK_I32: next_j = ulp_run<GEAK_I32, true, true>(r, st); break;
-                case GEAK_I64: next_j = ulp_run<GEAK_I64, true, true>(r, st); break;
-                case GEAK_U8: next_j = ulp_run<GEAK_U8, true, true>(r, st); break;
-                case GEAK_F64: next_j = ulp_run<GEAK_F64, true, true>(r, st); break;
-                case GEAK_F8E4M3: next_j = ulp_run<GEAK_F8E4M3, true, true>(r, st); break;
-                case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, true, true>(r, st); break;
-                default: next_j = ulp_run<GEAK_I8, true, true>(r, st); break;
-                }
+                for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, true, true>(r, st); });
             } else {
-                switch (it.dtype) {
-                case GEAK_F32: next_j = ulp_run<GEAK_F32, true, false>(r, st); break;
-                case GEAK_F16: next_j = ulp_run<GEAK_F16, true, false>(r, st); break;
-                case GEAK_BF16: next_j = ulp_run<GEAK_BF16, true, false>(r, st); break;
-                case GEAK_I32: next_j = ulp_run<GEAK_I32, true, false>(r, st); break;
-                case GEAK_I64: next_j = ulp_run<GEAK_I64, true, false>(r, st); break;
-                case GEAK_U8: next_j = ulp_run<GEAK_U8, true, false>(r, st); break;
-                case GEAK_F64: next_j = ulp_run<GEAK_F64, true, false>(r, st); break;
-                case GEAK_F8E4M3: next_j = ulp_run<GEAK_F8E4M3, true, false>(r, st); break;
-                case GEAK_F8E5M2: next_j = ulp_run<GEAK_F8E5M2, true, false>(r, st); break;
-                default: next_j = ulp_run<GEAK_I8, true, false>(r, st); break;
-                }
+                for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, true, false>(r, st); });
             }
             j = __builtin_amdgcn_readfirstlane(next_j);
             continue;
