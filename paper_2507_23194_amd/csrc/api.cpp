@@ -216,6 +216,20 @@ uint64_t geak_check_result_count(const geak_plan *plan)
     return (uint64_t)plan->host.segments.size() * (uint64_t)plan->host.num_candidates;
 }
 
+// The tensor arguments of a call: the reference and the K candidate base pointers must be there
+// when the plan reads any data, and 16-byte aligned (the kernels' vector loads rely on it).
+static geak_status check_tensor_pointers(const HostPlan &hp, const void *ref_dev, const void *const *cand_dev)
+{
+    const bool reads_data = !hp.items.empty();          // a plan of empty segments touches no tensor
+    if (reads_data && !ref_dev) return GEAK_EINVAL;
+    if ((uintptr_t)ref_dev & 15u) return GEAK_EALIGN;
+    for (int k = 0; k < hp.num_candidates; ++k) {
+        if (reads_data && !cand_dev[k]) return GEAK_EINVAL;
+        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
+    }
+    return GEAK_OK;
+}
+
 geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
                            void *workspace_dev, geak_result *results_dev, void *hip_stream)
 {
@@ -223,13 +237,8 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
     if (plan->device < 0) return GEAK_EINVAL;
     const HostPlan &hp = plan->host;
     const int K = hp.num_candidates;
-    const bool reads_data = !hp.items.empty();          // a plan of empty segments touches no tensor
-    if (reads_data && !ref_dev) return GEAK_EINVAL;
-    if (((uintptr_t)ref_dev & 15u) || ((uintptr_t)results_dev & 7u)) return GEAK_EALIGN;
-    for (int k = 0; k < K; ++k) {
-        if (reads_data && !cand_dev[k]) return GEAK_EINVAL;
-        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
-    }
+    if (const geak_status st = check_tensor_pointers(hp, ref_dev, cand_dev)) return st;
+    if ((uintptr_t)results_dev & 7u) return GEAK_EALIGN;
     const uint64_t ws_bytes = geak_check_workspace_bytes(plan);
     if (ws_bytes && !workspace_dev) return GEAK_EWORKSPACE;
     if (ws_bytes && ((uintptr_t)workspace_dev & 15u)) return GEAK_EALIGN;
@@ -382,14 +391,8 @@ geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const 
     const HostPlan &hp = plan->host;
     const int K = hp.num_candidates;
     const bool reads_data = !hp.items.empty();
-    if (reads_data && !ref_dev) return GEAK_EINVAL;
-    if (((uintptr_t)ref_dev & 15u) || ((uintptr_t)results_dev & 7u) || ((uintptr_t)records_dev & 7u) ||
-        ((uintptr_t)counts_dev & 3u))
-        return GEAK_EALIGN;
-    for (int k = 0; k < K; ++k) {
-        if (reads_data && !cand_dev[k]) return GEAK_EINVAL;
-        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
-    }
+    if (const geak_status st = check_tensor_pointers(hp, ref_dev, cand_dev)) return st;
+    if (((uintptr_t)results_dev & 7u) || ((uintptr_t)records_dev & 7u) || ((uintptr_t)counts_dev & 3u)) return GEAK_EALIGN;
     const uint64_t ws_bytes = geak_check_workspace_bytes(plan);
     if (ws_bytes && !workspace_dev) return GEAK_EWORKSPACE;
     if (ws_bytes && ((uintptr_t)workspace_dev & 15u)) return GEAK_EALIGN;
@@ -447,12 +450,8 @@ geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev,
     const HostPlan &hp = plan->host;
     const int K = hp.num_candidates;
     const bool reads_data = !hp.items.empty();
-    if (reads_data && !ref_dev) return GEAK_EINVAL;
-    if (((uintptr_t)ref_dev & 15u) || ((uintptr_t)ulp_workspace_dev & 15u) || ((uintptr_t)hist_dev & 7u)) return GEAK_EALIGN;
-    for (int k = 0; k < K; ++k) {
-        if (reads_data && !cand_dev[k]) return GEAK_EINVAL;
-        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
-    }
+    if (const geak_status st = check_tensor_pointers(hp, ref_dev, cand_dev)) return st;
+    if (((uintptr_t)ulp_workspace_dev & 15u) || ((uintptr_t)hist_dev & 7u)) return GEAK_EALIGN;
     DeviceGuard g(plan->device);
     if (!g.ok) return GEAK_EHIP;
 
@@ -528,13 +527,10 @@ geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, co
     if (plan->device < 0) return GEAK_EINVAL;
     const HostPlan &hp = plan->host;
     if (hp.items.empty()) return GEAK_OK;
-    if (!ref_dev || !workspace_dev) return GEAK_EINVAL;
-    if (((uintptr_t)ref_dev & 15u) || ((uintptr_t)workspace_dev & 15u)) return GEAK_EALIGN;
+    if (!workspace_dev) return GEAK_EINVAL;
+    if (const geak_status st = check_tensor_pointers(hp, ref_dev, cand_dev)) return st;
+    if ((uintptr_t)workspace_dev & 15u) return GEAK_EALIGN;
     const int K = hp.num_candidates;
-    for (int k = 0; k < K; ++k) {
-        if (!cand_dev[k]) return GEAK_EINVAL;
-        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
-    }
     // the span of the packed buffers that the plan's segments cover
     uint64_t end = 0;
     for (const SegDesc &g : hp.segments)

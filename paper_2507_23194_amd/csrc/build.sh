@@ -2,6 +2,7 @@
 # Builds libgeakcheck.so for gfx950 next to the package (in-tree, no JIT cache).
 #   -ffp-contract=off                 the rule's product and sum are rounded separately
 #   -packed-fp32-ops (target feature) no packed-FP32 VALU forms
+#   -Wno-int-to-pointer-cast          LDS addresses are 32-bit offsets; the host pass of the kernel files sees 64-bit pointers
 # The translation units are compiled side by side, then linked.
 set -euo pipefail
 here="$(cd "$(dirname "${BASH_SOURCE[0]}")" && pwd)"
@@ -11,7 +12,7 @@ obj="$(mktemp -d)"
 trap 'rm -rf "$obj"' EXIT
 flags=(--offload-arch=gfx950 -O3 -std=c++17 -fPIC -ffp-contract=off
        -Xclang -target-feature -Xclang -packed-fp32-ops
-       -Wall -Wno-unused-function -I"$root/include" -I"$here" "$@")
+       -Wall -Wno-unused-function -Wno-int-to-pointer-cast -I"$root/include" -I"$here" "$@")
 pids=()
 for src in kernels.hip ulp_kernels.hip verdict_kernel.hip metrics_host.cpp api.cpp plan_host.cpp; do
     hipcc "${flags[@]}" -c "$here/$src" -o "$obj/${src%.*}.o" &

@@ -650,7 +650,7 @@ struct IntItem {
     static constexpr bool kRaiseOutOfLine = true;
     uint32_t bref[kVecPerLane * 4];
     __device__ __forceinline__ void attach_lds(uint32_t, int) {}
-    static constexpr uint32_t poisoned_slots = 0;
+    [[maybe_unused]] static constexpr uint32_t poisoned_slots = 0;
 
     template <int V>
     __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &)
@@ -777,7 +777,7 @@ struct Int64Item {
     static constexpr bool kRaiseOutOfLine = true;
     uint32_t bref[kVecPerLane * 4];
     __device__ __forceinline__ void attach_lds(uint32_t, int) {}
-    static constexpr uint32_t poisoned_slots = 0;
+    [[maybe_unused]] static constexpr uint32_t poisoned_slots = 0;
 
     template <int V>
     __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &)
@@ -1179,7 +1179,7 @@ struct ByteItem {
     static constexpr bool kRaiseOutOfLine = true;
     uint32_t bref[kVecPerLane * 4];
     __device__ __forceinline__ void attach_lds(uint32_t, int) {}
-    static constexpr uint32_t poisoned_slots = 0;
+    [[maybe_unused]] static constexpr uint32_t poisoned_slots = 0;
 
     template <int V>
     __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &)
