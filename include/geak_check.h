@@ -124,7 +124,9 @@ geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs
  * Indices (first_mismatch, the report) are flat and row-major over the rows * row_elems elements, padding
  * not counted.  pitch_bytes must be a multiple of the element size and at least one row long; segments may not
  * interleave (their spans from first to last byte must not overlap).  Rows that start 16-byte aligned and are at
- * least 4 KiB long run at the speed of contiguous data; short rows are handled one by one. */
+ * least 4 KiB long run at the speed of contiguous data; rows of at most 2 KiB that all start 16-byte aligned
+ * (byte_offset and pitch_bytes multiples of 16) are grouped, several whole rows to a work item; other short rows
+ * are handled one by one. */
 typedef struct {
     uint64_t byte_offset;
     uint64_t rows;
