@@ -152,87 +152,6 @@ __device__ __forceinline__ double i64_abs(long long x)
     return (double)m;
 }
 
-// ---- exact element-wise evaluation of one item for one candidate, straight from memory ----------
-// Used (a) for segment heads and tails, (b) when the hot loop finds that an item may raise one of
-// the maxima.  Returns the wave-uniform mismatch count and raises the record's maxima.
-__device__ __noinline__ uint32_t exact_item(const unsigned char *ref, const unsigned char *cand, uint32_t n, int dtype,
-                                            const SegTol tolerance, int equal_nan, MaxPair *rec)
-{
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const u64 abs_bits = load_bits(&rec->abs), rel_bits = load_bits(&rec->rel);
-    uint32_t bad = 0;
-    if (dtype == GEAK_F64) {
-        const double seen_rel = __builtin_bit_cast(double, rel_bits);
-        const bool rel_open = seen_rel < kInfD;
-        double dm = 0.0, rm = 0.0;
-        for (uint32_t i = lane; i < n; i += kWaveSize) {
-            const double a = reinterpret_cast<const double *>(cand)[i], b = reinterpret_cast<const double *>(ref)[i];
-            bad += !close_exact_d(a, b, tolerance.atol, tolerance.rtol, equal_nan);
-            const double d = __builtin_fabs(a - b);
-            const double babs = __builtin_fabs(b);
-            if (d > dm) dm = d;                                   // false for NaN: skipped
-            if (rel_open && may_raise_rel_d(seen_rel, babs, d)) { // implies d > 0
-                const double r = d / babs;                        // correctly rounded; d/0 = +Inf; Inf/Inf = NaN
-                if (r > rm) rm = r;                               // false for NaN: skipped
-            }
-        }
-        dm = wave_max_d(dm);
-        rm = wave_max_d(rm);
-        if (lane == 0) {
-            raise_max(&rec->abs, dm, abs_bits);
-            raise_max(&rec->rel, rm, rel_bits);
-        }
-    } else if (dtype == GEAK_I32 || dtype == GEAK_I64 || dtype == GEAK_U8 || dtype == GEAK_I8) {
-        const double seen_rel = __builtin_bit_cast(double, rel_bits);
-        // d > c*|b| is implied by d/|b| > seen_rel; the 2^-30 margin covers the product's rounding
-        const double c = (seen_rel == (double)kInfF) ? __builtin_nan("") : seen_rel * (1.0 - 0x1p-30);
-        double dm = 0.0, rm = 0.0;
-        for (uint32_t i = lane; i < n; i += kWaveSize) {
-            long long a, x;
-            a = load_elem_int(cand, i, dtype);
-            x = load_elem_int(ref, i, dtype);
-            bad += (a != x);
-            const double d = i64_abs_diff(a, x);                  // exact for int32 operands
-            const double babs = i64_abs(x);
-            if (d > dm) dm = d;
-            if (d > c * babs) {                                   // implies d > 0
-                const double r = d / babs;                        // binary64, correctly rounded; d/0 = +Inf
-                if (r > rm) rm = r;
-            }
-        }
-        dm = wave_max_d(dm);
-        rm = wave_max_d(rm);
-        if (lane == 0) {
-            raise_max(&rec->abs, dm, abs_bits);
-            raise_max(&rec->rel, rm, rel_bits);
-        }
-    } else {
-        const float seen_rel = (float)__builtin_bit_cast(double, rel_bits);   // exact: published from binary32
-        const bool rel_open = seen_rel < kInfF;
-        float dm = 0.0f, rm = 0.0f;
-        for (uint32_t i = lane; i < n; i += kWaveSize) {
-            const float a = load_elem_f(cand, i, dtype), b = load_elem_f(ref, i, dtype);
-            bad += !close_exact(a, b, tolerance.atol_f, tolerance.rtol_f, equal_nan);
-            const float d = __builtin_fabsf(a - b);
-            const float babs = __builtin_fabsf(b);
-            if (d > dm) dm = d;                                   // false for NaN: skipped
-            if (rel_open && may_raise_rel(seen_rel, babs, d)) {   // implies d > 0
-                const float r = d / babs;                         // correctly rounded; d/0 = +Inf; Inf/Inf = NaN
-                if (r > rm) rm = r;                               // false for NaN: skipped
-            }
-        }
-        dm = wave_max_f(dm);
-        rm = wave_max_f(rm);
-        if (lane == 0) {
-            raise_max(&rec->abs, (double)dm, abs_bits);
-            raise_max(&rec->rel, (double)rm, rel_bits);
-        }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) bad += (uint32_t)__shfl_xor((int)bad, o, kWaveSize);
-    return bad;
-}
-
 // ---- per-(wave, candidate) running state in LDS ----------------------------------------------
 struct WaveState {
     uint32_t count_off;  // LDS byte offset of u64[K]: mismatching elements of the current (worker, segment) run
@@ -1502,17 +1421,65 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     if (it.flags & GEAK_ITEM_LAST) end_run(st, partials, it.slot, K, lane);
 }
 
-// ---- items that do not start on a 16-byte boundary (a segment's first few elements) ---------------
-__device__ __forceinline__ void process_head(const geak_item &it, uint32_t item_index, const CompareArgs &p,
-                                             const WaveState &st, int lane)
+// ---- items that do not start on a 16-byte boundary (a segment's or a row's first few elements) ------
+// At most 15 elements, so the wave takes four candidates per pass: lane 16 c + e applies the full rule
+// to element e of candidate k0 + c straight from memory, true division included (one element per
+// lane: nothing to filter), and each row of 16 lanes folds its candidate's count and maxima.
+__device__ __noinline__ void process_head(const geak_item it, const uint32_t item_index, const unsigned char *ref,
+                                          const unsigned char *const *cand_table, MaxPair *recs_in, const uint32_t replicas_in,
+                                          const uint32_t K_in, const SegTol tolerance, const int equal_nan, const WaveState st_in)
 {
-    const uint32_t K = p.num_candidates;
-    MaxPair *recs = p.board + (u64)it.segment * K * p.replicas + (blockIdx.x & (p.replicas - 1));
-    const SegTol tolerance = load_tol(p.seg_tol, it.segment);
-    for (uint32_t k = 0; k < K; ++k) {
-        const uint32_t bad = exact_item(p.ref + it.byte_offset, table_entry(p.cand_table, k) + it.byte_offset, it.numel,
-                                        it.dtype, tolerance, p.equal_nan, &recs[k * p.replicas]);
-        note_mismatches(st, k, bad, item_index, lane);
+    const WaveState st = uniform_state(st_in);
+    const uint32_t K = uniform32(K_in), replicas = uniform32(replicas_in), n = it.numel;
+    MaxPair *recs = uniform_ptr(recs_in);
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t e = (uint32_t)lane & 15u, c = (uint32_t)lane >> 4;
+    const unsigned char *rb = ref + it.byte_offset;
+    const bool integer = it.dtype == GEAK_I32 || it.dtype == GEAK_I64 || it.dtype == GEAK_U8 || it.dtype == GEAK_I8;
+    for (uint32_t k0 = 0; k0 < K; k0 += 4) {
+        const uint32_t k = k0 + c;
+        const bool on = k < K && e < n;
+        bool bad = false;
+        double d = 0.0, r = 0.0;                             // binary32 values widen exactly
+        if (on) {
+            const unsigned char *cb = reinterpret_cast<const unsigned char *>(((const GEAK_AS_GLOBAL u64 *)cand_table)[k]) + it.byte_offset;
+            if (it.dtype == GEAK_F64) {
+                const double a = reinterpret_cast<const double *>(cb)[e], x = reinterpret_cast<const double *>(rb)[e];
+                bad = !close_exact_d(a, x, tolerance.atol, tolerance.rtol, equal_nan);
+                d = __builtin_fabs(a - x);
+                if (d > 0.0) r = d / __builtin_fabs(x);       // correctly rounded; d/0 = +Inf; Inf/Inf = NaN
+            } else if (integer) {
+                const long long a = load_elem_int(cb, e, it.dtype), x = load_elem_int(rb, e, it.dtype);
+                bad = a != x;
+                d = i64_abs_diff(a, x);
+                if (d > 0.0) r = d / i64_abs(x);              // binary64, correctly rounded; d/0 = +Inf
+            } else {
+                const float a = load_elem_f(cb, e, it.dtype), x = load_elem_f(rb, e, it.dtype);
+                bad = !close_exact(a, x, tolerance.atol_f, tolerance.rtol_f, equal_nan);
+                const float df = __builtin_fabsf(a - x);
+                d = (double)df;
+                if (df > 0.0f) r = (double)(df / __builtin_fabsf(x));   // binary32 division, correctly rounded
+            }
+        }
+        // NaN (an operand NaN, Inf - Inf, Inf / Inf) takes no part in either maximum
+        u64 dm = (d > 0.0) ? __builtin_bit_cast(u64, d) : 0ull, rm = (r > 0.0) ? __builtin_bit_cast(u64, r) : 0ull;
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) {                    // within the row of 16 lanes; non-negative doubles order like their bits
+            const u64 dn = (u64)__shfl_xor((long long)dm, o, kWaveSize), rn = (u64)__shfl_xor((long long)rm, o, kWaveSize);
+            dm = dn > dm ? dn : dm;
+            rm = rn > rm ? rn : rm;
+        }
+        const u64 bad_mask = __builtin_amdgcn_ballot_w64(bad);
+        const uint32_t count = (uint32_t)__builtin_popcountll((bad_mask >> (16u * c)) & 0xFFFFull);
+        if (e == 0 && k < K) {
+            MaxPair *rec = recs + (u64)k * replicas;
+            if (dm) raise_max(&rec->abs, __builtin_bit_cast(double, dm), load_bits(&rec->abs));
+            if (rm) raise_max(&rec->rel, __builtin_bit_cast(double, rm), load_bits(&rec->rel));
+            if (count) {
+                (void)__hip_atomic_fetch_add(state_count(st) + k, (u64)count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                (void)__hip_atomic_fetch_min(state_first(st) + k, item_index, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
     }
 }
 
@@ -1566,7 +1533,8 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
             continue;
         }
         if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
-        process_head(it, j, p, st, lane);
+        process_head(it, j, p.ref, p.cand_table, p.board + (u64)it.segment * K * p.replicas + (blockIdx.x & (p.replicas - 1)), p.replicas, K,
+                     load_tol(p.seg_tol, it.segment), p.equal_nan, st);
         if (it.flags & GEAK_ITEM_LAST) end_run(st, p.partials, it.slot, K, lane);
         j = it.next;
     }
