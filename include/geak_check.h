@@ -65,9 +65,9 @@ typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64
 #define GEAK_MAX_SEGMENT_NUMEL (1ull << 40)
 
 /* One tensor of a packed (ragged) batch.  Every buffer -- the reference and each candidate -- is
- * packed with the same table.  byte_offset must be a multiple of the element size; 16-byte aligned
- * starts take the vector path from the first element, other starts peel a short head.  numel == 0 is
- * legal.  Segments must not overlap. */
+ * packed with the same table.  byte_offset must be a multiple of the element size; a start off the
+ * 16-byte grid costs the segment one shorter first work item, read from the boundary before it.
+ * numel == 0 is legal.  Segments must not overlap. */
 typedef struct {
     uint64_t byte_offset;
     uint64_t numel;
@@ -205,7 +205,9 @@ typedef struct {
 #define GEAK_ITEM_FULL  1u /* 16-byte aligned start and exactly item_bytes long: unguarded vector loads */
 #define GEAK_ITEM_FIRST 2u /* first item of its (wavefront, segment) run: running state is reset */
 #define GEAK_ITEM_LAST  4u /* last item of its run: running state is written to the slot */
-#define GEAK_ITEM_ALIGNED 8u /* 16-byte aligned start (FULL implies it): vector loads, guarded at the end */
+#define GEAK_ITEM_ALIGNED 8u /* 16-byte aligned start (FULL implies it): vector loads, guarded at the end.  Not set: the
+                                first item of a segment or row that starts off the 16-byte grid; it ends where a full
+                                item read from the boundary before it would end, or with the segment or row */
 #define GEAK_ITEM_ROWS 16u /* several whole rows of a pitched segment whose rows are short and start on 16-byte
                               boundaries: numel / row_elems rows, pitch_bytes apart, the first at byte_offset;
                               elem_start is the flat index of the first row's first element (ALIGNED is set) */

@@ -92,47 +92,55 @@ __device__ __forceinline__ float decode(const u32x4 &q, int e)
 }
 
 // ---- loads -------------------------------------------------------------------------------------
-// The first `valid` elements (0 .. E) of the 16-byte vector at p; the rest reads as 0.  A whole
-// vector is one load, a partial one is read element by element: nothing past the valid elements is
-// touched.
+// Elements [lo, valid) of the 16-byte vector at p (p on a 16-byte boundary), the rest 0.  A vector
+// that holds any element of the item is loaded whole and the bytes of the other elements are
+// cleared: the vector is one aligned 16-byte granule of the buffer, so it lies in the same page as
+// the item's own bytes in it and the load touches nothing the item's bytes do not already map.  A
+// vector without any element of the item is not loaded at all.
+// Bytes [first_byte, end_byte) of the vector kept, the others cleared.
+__device__ __forceinline__ u32x4 cut_vector_inline(u32x4 q, const int first_byte, const int end_byte)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int keep_from = first_byte - 4 * j, keep_to = end_byte - 4 * j;          // relative to word j
+        const uint32_t below_to = keep_to <= 0 ? 0u : (keep_to >= 4 ? 0xFFFFFFFFu : (1u << (8 * keep_to)) - 1u);
+        const uint32_t below_from = keep_from <= 0 ? 0u : (keep_from >= 4 ? 0xFFFFFFFFu : (1u << (8 * keep_from)) - 1u);
+        q[j] &= below_to & ~below_from;
+    }
+    return q;
+}
+__device__ __noinline__ u32x4 cut_vector_call(const u32x4 q, const int first_byte, const int end_byte)
+{
+    return cut_vector_inline(q, first_byte, end_byte);
+}
+
+template <int DT>
+__device__ __forceinline__ u32x4 load_partial_from(global_vec_ptr p, uint32_t lo, uint32_t valid)
+{
+    constexpr uint32_t E = Traits<DT>::E, W = Traits<DT>::W;
+    u32x4 q = {0u, 0u, 0u, 0u};
+    if (valid > lo) q = __builtin_nontemporal_load(p);
+    // The wave branches around the cut as a whole (in a tail only one lane of the last vector needs
+    // it); inside, a lane whose vector is whole keeps all of it.  The routines of the 16-bit dtypes
+    // have no registers to spare, so there the cut is a call.
+    if (__builtin_amdgcn_ballot_w64(valid > lo && (lo != 0 || valid < E))) {
+        const int first_byte = (int)(lo * W), end_byte = (int)((valid < E ? valid : E) * W);
+        if constexpr (E == 8) q = cut_vector_call(q, first_byte, end_byte);
+        else q = cut_vector_inline(q, first_byte, end_byte);
+    }
+    return q;
+}
 template <int DT>
 __device__ __forceinline__ u32x4 load_partial(global_vec_ptr p, uint32_t valid)
 {
-    constexpr uint32_t E = Traits<DT>::E;
-    u32x4 q = {0u, 0u, 0u, 0u};
-    if (valid >= E) {
-        q = __builtin_nontemporal_load(p);
-    } else if (valid) {
-        if constexpr (Traits<DT>::W == 1) {
-            const GEAK_AS_GLOBAL unsigned char *c = (const GEAK_AS_GLOBAL unsigned char *)p;
-#pragma unroll
-            for (uint32_t e = 0; e < E; ++e)
-                if (e < valid) q[e >> 2] |= (uint32_t)c[e] << ((e & 3) * 8);
-        } else if constexpr (Traits<DT>::W == 8) {
-            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
-#pragma unroll
-            for (uint32_t e = 0; e < E; ++e)
-                if (e < valid) { q[2 * e] = w[2 * e]; q[2 * e + 1] = w[2 * e + 1]; }
-        } else if constexpr (Traits<DT>::W == 4) {
-            const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)p;
-#pragma unroll
-            for (uint32_t e = 0; e < E; ++e)
-                if (e < valid) q[e] = w[e];
-        } else {
-            const GEAK_AS_GLOBAL uint16_t *h = (const GEAK_AS_GLOBAL uint16_t *)p;
-#pragma unroll
-            for (uint32_t e = 0; e < E; ++e)
-                if (e < valid) q[e >> 1] |= (uint32_t)h[e] << ((e & 1) * 16);
-        }
-    }
-    return q;
+    return load_partial_from<DT>(p, 0u, valid);
 }
 
 // Vector V of lane L of an item that starts 16-byte aligned but may be shorter than a full item
 // (a segment's tail): whole vectors inside the item are loaded as such, the one vector that
-// straddles the end element by element, and everything past the end reads as 0 -- in the reference
-// and in every candidate alike, so that those positions compare as close and add nothing to either
-// maximum.  Nothing outside the item's bytes is touched.
+// straddles the end is loaded and cut, vectors past the end are not loaded, and everything past the
+// end reads as 0 -- in the reference and in every candidate alike, so that those positions compare
+// as close and add nothing to either maximum.
 template <int DT>
 __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, int v, uint32_t n, bool full)
 {
@@ -143,30 +151,38 @@ __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, i
     return load_partial<DT>(p, first < n ? n - first : 0u);
 }
 
-// Where the vectors of an aligned item that is not a full one lie.  A plain tail is contiguous:
-// vector i at byte 16 i.  A row group (GEAK_ITEM_ROWS: several short rows of a pitched segment, each
-// starting on a 16-byte boundary) gives every row `vpr` vectors, the last of them partial when the
-// row's bytes are no multiple of 16, and puts row r at byte r * pitch; vector slot i is vector
-// i % vpr of row i / vpr, so the slots still ascend with the element index.  All fields wave-uniform.
+// Where the vectors of an item that is not a full one lie; three kinds.
+//   plain    a tail: starts on a 16-byte boundary, contiguous, vector slot i at byte 16 i.
+//   rows     a row group (GEAK_ITEM_ROWS: several short rows of a pitched segment, each starting on a
+//            16-byte boundary): every row takes `vpr` slots, the last of them partial when the row's bytes
+//            are no multiple of 16, and row r lies at byte r * pitch; slot i is vector i % vpr of row i / vpr.
+//   shifted  an item that starts off the 16-byte grid (GEAK_ITEM_ALIGNED not set): read from the
+//            boundary before it, so that slot 0 holds `skip` foreign elements in front, which read as 0
+//            like everything behind the item's end.
+// In all three the slots ascend with the element index.  All fields wave-uniform.
+enum TailKind { kTailPlain = 0, kTailRows = 1, kTailShifted = 2 };
 struct ItemShape {
-    uint32_t rows;          // 0: a plain tail
-    uint32_t vpr;           // vectors per row
-    uint32_t inv;           // ceil(2^16 / vpr): (i * inv) >> 16 == i / vpr for i < 256
-    uint32_t row_elems;
-    u64 pitch;              // bytes from one row to the next
+    uint32_t rows;          // rows: their number
+    uint32_t vpr;           // rows: vectors per row
+    uint32_t inv;           // rows: ceil(2^16 / vpr): (i * inv) >> 16 == i / vpr for i < 256
+    uint32_t row_elems;     // rows
+    u64 pitch;              // rows: bytes from one row to the next
+    uint32_t skip;          // shifted: elements between the 16-byte boundary and the item's first
 };
 
-template <int DT>
+template <int DT, int KIND>
 __device__ __forceinline__ ItemShape item_shape(const geak_item &it, const SegDesc *segments)
 {
-    ItemShape sh{0u, 1u, 0u, 0u, 0ull};
-    if (it.flags & GEAK_ITEM_ROWS) {
+    ItemShape sh{0u, 1u, 0u, 0u, 0ull, 0u};
+    if constexpr (KIND == kTailRows) {
         const GEAK_AS_CONSTANT unsigned long long *g = (const GEAK_AS_CONSTANT unsigned long long *)(segments + it.segment);
         sh.row_elems = (uint32_t)g[2];                    // SegDesc: byte_offset, numel, row_elems, pitch_bytes, ...
         sh.pitch = g[3];
         sh.vpr = (sh.row_elems + Traits<DT>::E - 1) / Traits<DT>::E;
         sh.inv = (65536u + sh.vpr - 1u) / sh.vpr;
         sh.rows = (uint32_t)it.numel / sh.row_elems;
+    } else if constexpr (KIND == kTailShifted) {
+        sh.skip = ((uint32_t)it.byte_offset & 15u) / (uint32_t)Traits<DT>::W;
     }
     return sh;
 }
@@ -175,32 +191,38 @@ __device__ __forceinline__ ItemShape item_shape(const geak_item &it, const SegDe
 template <int DT>
 __device__ __forceinline__ uint32_t shape_vectors(const ItemShape &sh, uint32_t n)
 {
-    const uint32_t slots = sh.rows ? sh.rows * sh.vpr : (n + Traits<DT>::E - 1) / Traits<DT>::E;
+    const uint32_t slots = sh.rows ? sh.rows * sh.vpr : (sh.skip + n + Traits<DT>::E - 1) / Traits<DT>::E;
     return (slots + kWaveSize - 1) / kWaveSize;
 }
 
-// Vector slot `slot` (= v * 64 + lane) of a row group: its elements' index within the item in
-// `first` (meaningless when nothing is valid), loaded as load_vec loads a tail.
-template <int DT>
-__device__ __forceinline__ u32x4 load_row_slot(const unsigned char *base, uint32_t slot, const ItemShape &sh, uint32_t &first)
+// Vector slot `slot` (= v * 64 + lane) of an item of n elements whose first slot lies at `base` (for
+// a shifted item: the boundary before its first element).  `first`: index within the item of the
+// slot's element 0 (meaningless when nothing is valid; for slot 0 of a shifted item it wraps below
+// zero, and first + e is right again for every valid e).
+template <int DT, int KIND>
+__device__ __forceinline__ u32x4 load_slot(const unsigned char *base, uint32_t slot, uint32_t n, const ItemShape &sh, uint32_t &first)
 {
     constexpr uint32_t E = Traits<DT>::E;
-    const uint32_t row = (slot * sh.inv) >> 16, vec = slot - row * sh.vpr, col = vec * E;
-    first = row * sh.row_elems + col;
-    const uint32_t valid = row < sh.rows ? sh.row_elems - col : 0u;        // col < row_elems by construction of vpr
-    return load_partial<DT>((global_vec_ptr)(base + (u64)row * sh.pitch) + vec, valid);
+    if constexpr (KIND == kTailRows) {
+        const uint32_t row = (slot * sh.inv) >> 16, vec = slot - row * sh.vpr, col = vec * E;
+        first = row * sh.row_elems + col;
+        const uint32_t valid = row < sh.rows ? sh.row_elems - col : 0u;    // col < row_elems by construction of vpr
+        return load_partial<DT>((global_vec_ptr)(base + (u64)row * sh.pitch) + vec, valid);
+    } else if constexpr (KIND == kTailShifted) {
+        first = slot * E - sh.skip;
+        const uint32_t end = sh.skip + n;                                  // in slot positions
+        return load_partial_from<DT>((global_vec_ptr)base + slot, slot == 0 ? sh.skip : 0u, slot * E < end ? end - slot * E : 0u);
+    } else {
+        first = slot * E;
+        return load_partial<DT>((global_vec_ptr)base + slot, first < n ? n - first : 0u);
+    }
 }
-// Vector v of this lane of an aligned item that is not a full one: a plain tail (ROWS false: exactly
-// load_vec's guarded load) or a row group.
-template <int DT, bool ROWS>
+// Vector v of this lane.
+template <int DT, int KIND>
 __device__ __forceinline__ u32x4 load_shaped(const unsigned char *base, int lane, int v, uint32_t n, const ItemShape &sh)
 {
-    if constexpr (!ROWS) {
-        return load_vec<DT>(base, lane, v, n, false);
-    } else {
-        uint32_t first;
-        return load_row_slot<DT>(base, (uint32_t)(v * kWaveSize + lane), sh, first);
-    }
+    uint32_t first;
+    return load_slot<DT, KIND>(base, (uint32_t)(v * kWaveSize + lane), n, sh, first);
 }
 
 // The 8-bit floating formats are widened by the conversion instructions (v_cvt_f32_fp8 for E4M3,

@@ -1312,8 +1312,9 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
 // loads of a batch -- and, for the first batch, of the reference -- are issued together, and the
 // whole batch is compared after a single wait.  Absent elements read as 0 on both sides.  A row
 // group (short rows of a pitched segment, a pitch apart) goes the same way: only the address and the
-// number of valid elements of a lane's vector differ.
-template <int DT, bool ROWS>
+// number of valid elements of a lane's vector differ.  So does an item that starts off the 16-byte
+// grid (a segment's or a row's first item): it is read from the boundary before it.
+template <int DT, int KIND>
 __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_in)
 {
     typedef typename ItemOf<DT>::type Item;
@@ -1332,9 +1333,9 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     const uint32_t j = uniform32(in.first_item);
     const geak_item it = load_work_item(items, j);
     const SegTol tolerance = load_tol(seg_tol, it.segment);
-    ItemShape shape{0u, 1u, 0u, 0u, 0ull};
-    if constexpr (ROWS) shape = item_shape<DT>(it, uniform_ptr(in.segments));
+    const ItemShape shape = item_shape<DT, KIND>(it, uniform_ptr(in.segments));
     const uint32_t n = it.numel;
+    const u64 offset = it.byte_offset - (u64)shape.skip * Traits<DT>::W;                    // of vector slot 0
     const uint32_t vectors = shape_vectors<DT>(shape, n);                                   // 1..4 per lane
     const uint32_t per_batch = vectors == 1 ? 4 : (vectors == 2 ? 2 : 1);                       // candidates per batch
     MaxPair *recs = board + (u64)it.segment * K * replicas + replica;         // candidate k: recs[k * replicas]
@@ -1345,17 +1346,17 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
         if (per_batch == 4) {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (kb + c < K) cur[c] = load_shaped<DT, ROWS>(table_entry(cand, kb + c) + it.byte_offset, lane, 0, n, shape);
+                if (kb + c < K) cur[c] = load_shaped<DT, KIND>(table_entry(cand, kb + c) + offset, lane, 0, n, shape);
         } else if (per_batch == 2) {
 #pragma unroll
             for (int c = 0; c < 2; ++c)
                 if (kb + c < K) {
-                    cur[2 * c + 0] = load_shaped<DT, ROWS>(table_entry(cand, kb + c) + it.byte_offset, lane, 0, n, shape);
-                    cur[2 * c + 1] = load_shaped<DT, ROWS>(table_entry(cand, kb + c) + it.byte_offset, lane, 1, n, shape);
+                    cur[2 * c + 0] = load_shaped<DT, KIND>(table_entry(cand, kb + c) + offset, lane, 0, n, shape);
+                    cur[2 * c + 1] = load_shaped<DT, KIND>(table_entry(cand, kb + c) + offset, lane, 1, n, shape);
                 }
         } else {
 #pragma unroll
-            for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_shaped<DT, ROWS>(table_entry(cand, kb) + it.byte_offset, lane, v, n, shape);
+            for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_shaped<DT, KIND>(table_entry(cand, kb) + offset, lane, v, n, shape);
         }
     };
 
@@ -1364,7 +1365,7 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     {
         u32x4 r[kVecPerLane];
 #pragma unroll
-        for (int v = 0; v < kVecPerLane; ++v) r[v] = load_shaped<DT, ROWS>(ref_base + it.byte_offset, lane, v, n, shape);
+        for (int v = 0; v < kVecPerLane; ++v) r[v] = load_shaped<DT, KIND>(ref_base + offset, lane, v, n, shape);
         load_batch(0);                                     // in flight together with the reference
         ref.template stage_vec<0>(r[0], tolerance);
         ref.template stage_vec<1>(r[1], tolerance);
@@ -1421,73 +1422,10 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     if (it.flags & GEAK_ITEM_LAST) end_run(st, partials, it.slot, K, lane);
 }
 
-// ---- items that do not start on a 16-byte boundary (a segment's or a row's first few elements) ------
-// At most 15 elements, so the wave takes four candidates per pass: lane 16 c + e applies the full rule
-// to element e of candidate k0 + c straight from memory, true division included (one element per
-// lane: nothing to filter), and each row of 16 lanes folds its candidate's count and maxima.
-__device__ __noinline__ void process_head(const geak_item it, const uint32_t item_index, const unsigned char *ref,
-                                          const unsigned char *const *cand_table, MaxPair *recs_in, const uint32_t replicas_in,
-                                          const uint32_t K_in, const SegTol tolerance, const int equal_nan, const WaveState st_in)
-{
-    const WaveState st = uniform_state(st_in);
-    const uint32_t K = uniform32(K_in), replicas = uniform32(replicas_in), n = it.numel;
-    MaxPair *recs = uniform_ptr(recs_in);
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const uint32_t e = (uint32_t)lane & 15u, c = (uint32_t)lane >> 4;
-    const unsigned char *rb = ref + it.byte_offset;
-    const bool integer = it.dtype == GEAK_I32 || it.dtype == GEAK_I64 || it.dtype == GEAK_U8 || it.dtype == GEAK_I8;
-    for (uint32_t k0 = 0; k0 < K; k0 += 4) {
-        const uint32_t k = k0 + c;
-        const bool on = k < K && e < n;
-        bool bad = false;
-        double d = 0.0, r = 0.0;                             // binary32 values widen exactly
-        if (on) {
-            const unsigned char *cb = reinterpret_cast<const unsigned char *>(((const GEAK_AS_GLOBAL u64 *)cand_table)[k]) + it.byte_offset;
-            if (it.dtype == GEAK_F64) {
-                const double a = reinterpret_cast<const double *>(cb)[e], x = reinterpret_cast<const double *>(rb)[e];
-                bad = !close_exact_d(a, x, tolerance.atol, tolerance.rtol, equal_nan);
-                d = __builtin_fabs(a - x);
-                if (d > 0.0) r = d / __builtin_fabs(x);       // correctly rounded; d/0 = +Inf; Inf/Inf = NaN
-            } else if (integer) {
-                const long long a = load_elem_int(cb, e, it.dtype), x = load_elem_int(rb, e, it.dtype);
-                bad = a != x;
-                d = i64_abs_diff(a, x);
-                if (d > 0.0) r = d / i64_abs(x);              // binary64, correctly rounded; d/0 = +Inf
-            } else {
-                const float a = load_elem_f(cb, e, it.dtype), x = load_elem_f(rb, e, it.dtype);
-                bad = !close_exact(a, x, tolerance.atol_f, tolerance.rtol_f, equal_nan);
-                const float df = __builtin_fabsf(a - x);
-                d = (double)df;
-                if (df > 0.0f) r = (double)(df / __builtin_fabsf(x));   // binary32 division, correctly rounded
-            }
-        }
-        // NaN (an operand NaN, Inf - Inf, Inf / Inf) takes no part in either maximum
-        u64 dm = (d > 0.0) ? __builtin_bit_cast(u64, d) : 0ull, rm = (r > 0.0) ? __builtin_bit_cast(u64, r) : 0ull;
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) {                    // within the row of 16 lanes; non-negative doubles order like their bits
-            const u64 dn = (u64)__shfl_xor((long long)dm, o, kWaveSize), rn = (u64)__shfl_xor((long long)rm, o, kWaveSize);
-            dm = dn > dm ? dn : dm;
-            rm = rn > rm ? rn : rm;
-        }
-        const u64 bad_mask = __builtin_amdgcn_ballot_w64(bad);
-        const uint32_t count = (uint32_t)__builtin_popcountll((bad_mask >> (16u * c)) & 0xFFFFull);
-        if (e == 0 && k < K) {
-            MaxPair *rec = recs + (u64)k * replicas;
-            if (dm) raise_max(&rec->abs, __builtin_bit_cast(double, dm), load_bits(&rec->abs));
-            if (rm) raise_max(&rec->rel, __builtin_bit_cast(double, rm), load_bits(&rec->rel));
-            if (count) {
-                (void)__hip_atomic_fetch_add(state_count(st) + k, (u64)count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                (void)__hip_atomic_fetch_min(state_first(st) + k, item_index, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
-        }
-    }
-}
-
 __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const CompareArgs p)
 {
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t K = p.num_candidates;
-    const int lane = threadIdx.x & (kWaveSize - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     WaveState st;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(GEAK_AS_LDS unsigned char *)lds;
@@ -1516,27 +1454,19 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     uint32_t j = wave_first[blockIdx.x * kWavesPerBlock + wave];
     while (j < p.num_items) {                                   // kNoItem ends the list; nothing past the table is read
         const geak_item it = load_work_item(p.items, j);
-        if (it.flags & GEAK_ITEM_ALIGNED) {
-            // a run of vector-loadable items: handled, state bookkeeping included, by the dtype's routine
-            r.first_item = j;
-            uint32_t next_j;
-            if (it.flags & GEAK_ITEM_FULL) {
-                for_dtype(it.dtype, [&](auto dt) { next_j = process_run<decltype(dt)::value>(r, st); });
-            } else if (it.flags & GEAK_ITEM_ROWS) {
-                for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, true>(r, st); });
-                next_j = it.next;
-            } else {
-                for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, false>(r, st); });
-                next_j = it.next;
-            }
-            j = __builtin_amdgcn_readfirstlane(next_j);
-            continue;
+        // a run of full items, or one item of another shape: handled, state bookkeeping included, by the dtype's routine
+        r.first_item = j;
+        uint32_t next_j = it.next;
+        if (it.flags & GEAK_ITEM_FULL) {
+            for_dtype(it.dtype, [&](auto dt) { next_j = process_run<decltype(dt)::value>(r, st); });
+        } else if (it.flags & GEAK_ITEM_ROWS) {
+            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailRows>(r, st); });
+        } else if (it.flags & GEAK_ITEM_ALIGNED) {
+            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailPlain>(r, st); });
+        } else {
+            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailShifted>(r, st); });
         }
-        if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
-        process_head(it, j, p.ref, p.cand_table, p.board + (u64)it.segment * K * p.replicas + (blockIdx.x & (p.replicas - 1)), p.replicas, K,
-                     load_tol(p.seg_tol, it.segment), p.equal_nan, st);
-        if (it.flags & GEAK_ITEM_LAST) end_run(st, p.partials, it.slot, K, lane);
-        j = it.next;
+        j = __builtin_amdgcn_readfirstlane(next_j);
     }
 }
 
@@ -1562,17 +1492,6 @@ __global__ void init_kernel(const InitArgs p)
 }
 
 // ---- reduce: one block per (segment, candidate) ----------------------------------------------
-__device__ __forceinline__ bool element_close(const unsigned char *ref, const unsigned char *cand, u64 idx,
-                                              int dtype, const SegTol &tolerance, int equal_nan)
-{
-    if (dtype == GEAK_F64)
-        return close_exact_d(reinterpret_cast<const double *>(cand)[idx], reinterpret_cast<const double *>(ref)[idx],
-                             tolerance.atol, tolerance.rtol, equal_nan);
-    if (dtype == GEAK_I32 || dtype == GEAK_I64 || dtype == GEAK_U8 || dtype == GEAK_I8)
-        return load_elem_int(ref, idx, dtype) == load_elem_int(cand, idx, dtype);
-    return close_exact(load_elem_f(cand, idx, dtype), load_elem_f(ref, idx, dtype), tolerance.atol_f, tolerance.rtol_f, equal_nan);
-}
-
 constexpr int kReduceThreads = 256;
 constexpr uint64_t kReduceWavePairs = 1024;        // from this many (segment, candidate) pairs on, one wave per pair
 
@@ -1600,19 +1519,24 @@ __device__ __forceinline__ uint32_t first_bad_in_vector(const u32x4 &qa, const u
     return best;
 }
 template <int DT>
-__device__ __forceinline__ uint32_t first_bad_of_thread(const unsigned char *rb, const unsigned char *cb, int tid, const geak_item &it,
+__device__ __forceinline__ uint32_t first_bad_of_thread(const unsigned char *ref, const unsigned char *cand, int tid, const geak_item &it,
                                                         const SegDesc *segments, const SegTol &tolerance, int equal_nan)
 {
     u32x4 qa, qb;
     uint32_t first;
-    if (it.flags & GEAK_ITEM_ROWS) {                       // uniform
-        const ItemShape shape = item_shape<DT>(it, segments);
-        qb = load_row_slot<DT>(rb, (uint32_t)tid, shape, first);
-        qa = load_row_slot<DT>(cb, (uint32_t)tid, shape, first);
+    if (it.flags & GEAK_ITEM_ROWS) {                       // the three branches are uniform
+        const ItemShape shape = item_shape<DT, kTailRows>(it, segments);
+        qb = load_slot<DT, kTailRows>(ref + it.byte_offset, (uint32_t)tid, it.numel, shape, first);
+        qa = load_slot<DT, kTailRows>(cand + it.byte_offset, (uint32_t)tid, it.numel, shape, first);
+    } else if (it.flags & GEAK_ITEM_ALIGNED) {
+        const ItemShape shape = item_shape<DT, kTailPlain>(it, segments);
+        qb = load_slot<DT, kTailPlain>(ref + it.byte_offset, (uint32_t)tid, it.numel, shape, first);
+        qa = load_slot<DT, kTailPlain>(cand + it.byte_offset, (uint32_t)tid, it.numel, shape, first);
     } else {
-        first = (uint32_t)tid * (uint32_t)Traits<DT>::E;
-        qb = load_vec<DT>(rb, tid & (kWaveSize - 1), tid >> 6, it.numel, false);
-        qa = load_vec<DT>(cb, tid & (kWaveSize - 1), tid >> 6, it.numel, false);
+        const ItemShape shape = item_shape<DT, kTailShifted>(it, segments);
+        const u64 offset = it.byte_offset - (u64)shape.skip * Traits<DT>::W;
+        qb = load_slot<DT, kTailShifted>(ref + offset, (uint32_t)tid, it.numel, shape, first);
+        qa = load_slot<DT, kTailShifted>(cand + offset, (uint32_t)tid, it.numel, shape, first);
     }
     // positions outside the item read as 0 on both sides and are close under every rule
     const uint32_t e = first_bad_in_vector<DT>(qa, qb, (uint32_t)Traits<DT>::E, tolerance, equal_nan);
@@ -1663,22 +1587,16 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
     }
 
     // exact first index: re-read the first item that holds a mismatch, every thread one 16-byte vector of
-    // the reference and of the candidate (256 threads x 16 bytes: the whole item; a row group's vector
-    // slots ascend with the element index like a contiguous item's)
+    // the reference and of the candidate (256 threads x 16 bytes: the whole item; whatever the item's shape,
+    // its vector slots ascend with the element index)
     long long first = -1;
     if (first_item != kNoItem) {                // uniform: every thread holds the same first_item
         const geak_item it = p.items[first_item];
         const SegTol tolerance = p.seg_tol[seg];
-        const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
         uint32_t best = kNoItem;
-        if (it.flags & GEAK_ITEM_ALIGNED) {      // one 16-byte vector of each tensor per thread (uniform branch)
-            for_dtype(it.dtype, [&](auto dt) {
-                best = first_bad_of_thread<decltype(dt)::value>(rb, cb, tid, it, p.segments, tolerance, p.equal_nan);
-            });
-        } else {                                 // a segment's few elements before its first 16-byte boundary
-            const uint32_t i = (uint32_t)tid;
-            if (i < it.numel && !element_close(rb, cb, i, it.dtype, tolerance, p.equal_nan)) best = i;
-        }
+        for_dtype(it.dtype, [&](auto dt) {
+            best = first_bad_of_thread<decltype(dt)::value>(p.ref, p.cand_table[k], tid, it, p.segments, tolerance, p.equal_nan);
+        });
         best = wave_min_u(best);
         if (lane == 0) s_best[wave] = best;
         __syncthreads();
@@ -1718,13 +1636,13 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
 // and the number of blocks, not the work, sets the time.  A lane takes four vector slots of the
 // item that is scanned again.
 template <int DT>
-__device__ __forceinline__ uint32_t first_bad_of_lane(const unsigned char *rb, const unsigned char *cb, int lane, const geak_item &it,
+__device__ __forceinline__ uint32_t first_bad_of_lane(const unsigned char *ref, const unsigned char *cand, int lane, const geak_item &it,
                                                       const SegDesc *segments, const SegTol &tolerance, int equal_nan)
 {
     uint32_t best = kNoItem;
 #pragma unroll
     for (int v = kVecPerLane - 1; v >= 0; --v) {            // downwards, so that the least index is kept
-        const uint32_t b = first_bad_of_thread<DT>(rb, cb, v * kWaveSize + lane, it, segments, tolerance, equal_nan);
+        const uint32_t b = first_bad_of_thread<DT>(ref, cand, v * kWaveSize + lane, it, segments, tolerance, equal_nan);
         best = b < best ? b : best;
     }
     return best;
@@ -1775,16 +1693,10 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_wave_kernel(const Reduc
     if (first_item != kNoItem) {                // uniform over the wave
         const geak_item it = p.items[first_item];
         const SegTol tolerance = p.seg_tol[seg];
-        const unsigned char *rb = p.ref + it.byte_offset, *cb = p.cand_table[k] + it.byte_offset;
         uint32_t best = kNoItem;
-        if (it.flags & GEAK_ITEM_ALIGNED) {
-            for_dtype(it.dtype, [&](auto dt) {
-                best = first_bad_of_lane<decltype(dt)::value>(rb, cb, lane, it, p.segments, tolerance, p.equal_nan);
-            });
-        } else {                                 // a segment's few elements before its first 16-byte boundary
-            const uint32_t i = (uint32_t)lane;
-            if (i < it.numel && !element_close(rb, cb, i, it.dtype, tolerance, p.equal_nan)) best = i;
-        }
+        for_dtype(it.dtype, [&](auto dt) {
+            best = first_bad_of_lane<decltype(dt)::value>(p.ref, p.cand_table[k], lane, it, p.segments, tolerance, p.equal_nan);
+        });
         best = wave_min_u(best);
         first = (long long)it.elem_start + (long long)best;
     }

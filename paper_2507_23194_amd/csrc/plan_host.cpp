@@ -64,7 +64,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         for (size_t i = 1; i < spans.size(); ++i)
             if (spans[i].first < spans[i - 1].second) return GEAK_EBOUNDS;
 
-        // count items first: head (to the next 16-byte boundary), full tiles, tail
+        // count items first: a shorter first item where a row starts off the 16-byte grid, full items, tail
         uint64_t n_items = 0;
         for (uint64_t s = 0; s < nsegs; ++s) {
             const SegDesc &g = segs[s];
@@ -73,8 +73,8 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
             for (uint64_t r = 0; r < seg_rows(g); ++r) {
                 uint64_t n = g.row_elems;
                 const uint64_t start = g.byte_offset + r * g.pitch_bytes;
-                const uint64_t head = std::min<uint64_t>(n, ((16 - start % 16) % 16) / w);
-                if (head) { ++n_items; n -= head; }
+                const uint64_t skip = (start % 16) / w;               // a start off the 16-byte grid: one shorter first item
+                if (skip) { ++n_items; n -= std::min<uint64_t>(n, per - skip); }
                 n_items += n / per + (n % per ? 1 : 0);
                 if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
             }
@@ -125,7 +125,10 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                 }
                 continue;
             }
-            // row by row (a contiguous segment is one row): head up to the next 16-byte boundary, full items, tail
+            // Row by row (a contiguous segment is one row): full items and a tail.  A row that starts off the
+            // 16-byte grid begins with one item that ends where a full item read from the boundary before
+            // it would end (the kernels read it from that boundary and ignore the foreign elements in
+            // front), so that everything behind it is aligned again.
             for (uint64_t r = 0; r < seg_rows(g); ++r) {
                 const uint64_t row_start = g.byte_offset + r * g.pitch_bytes;
                 uint64_t done = 0;
@@ -141,8 +144,8 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     hp.items.push_back(it);
                     done += n;
                 };
-                const uint64_t head = std::min<uint64_t>(g.row_elems, ((16 - row_start % 16) % 16) / w);
-                if (head) push(head, false);
+                const uint64_t skip = (row_start % 16) / w;
+                if (skip) push(std::min<uint64_t>(g.row_elems, per - skip), false);
                 while (g.row_elems - done >= per) push(per, true);
                 if (g.row_elems - done) push(g.row_elems - done, false);
             }
@@ -165,8 +168,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         const uint64_t slices = (uint64_t)num_candidates + 1;
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
             const uint64_t per_slice = (it.dtype == GEAK_F8E4M3 || it.dtype == GEAK_F8E5M2) ? 40 : (it.dtype == GEAK_F32 || it.dtype == GEAK_F64) ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
-            if (!(it.flags & GEAK_ITEM_ALIGNED)) return 2 * per_slice * slices;      // element-wise path
-            if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 140;
+            if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 140;       // tails, row groups, starts off the grid
             return per_slice * slices + (starts_run ? 100 : 0);
         };
         uint64_t total_cost = 0;
@@ -190,7 +192,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
 
         // Inside a block every item goes to the wave that has the least estimated cost so far (in
         // table order, so a wave's list ascends and neighbouring items mostly go to neighbouring
-        // waves): with equal items that is a plain interleave, and a tail, a head or a heavier dtype
+        // waves): with equal items that is a plain interleave, and a tail, a start off the grid or a heavier dtype
         // no longer makes one wave of the block finish an item or two after the others.  Each wave
         // follows its list through the items' `next` links.
         //

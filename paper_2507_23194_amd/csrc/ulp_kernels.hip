@@ -479,7 +479,7 @@ template <> struct UlpRefOf<GEAK_F8E5M2> { typedef UlpRefPacked<GEAK_F8E5M2> typ
 // TAIL = true: one aligned item that is not a full one (a segment's tail, or a group of short rows of a
 // pitched segment), guarded loads.
 // Returns the index of the wave's first item it did not process.
-template <int DT, bool TAIL, bool ROWS = false>
+template <int DT, bool TAIL, int KIND = kTailPlain>
 __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_in)
 {
     constexpr bool full = !TAIL;
@@ -496,11 +496,11 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
 
     uint32_t j = uniform32(in.first_item);
     geak_item it = load_work_item(items, j);
-    ItemShape shape{0u, 1u, 0u, 0u, 0ull};
-    if constexpr (ROWS) shape = item_shape<DT>(it, uniform_ptr(in.segments));
+    const ItemShape shape = item_shape<DT, KIND>(it, uniform_ptr(in.segments));
+    const u64 shift_bytes = (u64)shape.skip * Traits<DT>::W;       // a shifted item is read from the boundary before it
     // vector v of this lane: unguarded inside a run of full items, by the item's shape (tail or row group) otherwise
     const auto fetch = [&](const unsigned char *base, int v, uint32_t n) {
-        if constexpr (TAIL) return load_shaped<DT, ROWS>(base, lane, v, n, shape);
+        if constexpr (TAIL) return load_shaped<DT, KIND>(base - shift_bytes, lane, v, n, shape);
         else return load_vec<DT>(base, lane, v, n, full);
     };
     u32x4 cur[kVecPerLane];
@@ -547,50 +547,6 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
     return it.next;
 }
 
-// the few elements before a segment's first 16-byte boundary: element by element, every lane adding
-// into the row itself
-__device__ __forceinline__ void ulp_head(const geak_item &it, const unsigned char *ref, const unsigned char *const *cand,
-                                         const UlpState &st, uint32_t k_begin, uint32_t k_count, int lane)
-{
-    for (uint32_t kk = 0; kk < k_count; ++kk) {
-        const unsigned char *rb = ref + it.byte_offset, *cb = table_entry(cand, k_begin + kk) + it.byte_offset;
-        GEAK_AS_LDS uint32_t *row = ulp_row(st, kk);
-        for (uint32_t i = lane; i < it.numel; i += kWaveSize) {
-            uint32_t slot;
-            switch (it.dtype) {
-            case GEAK_F32: case GEAK_F16: case GEAK_BF16: case GEAK_F8E4M3: case GEAK_F8E5M2: {
-                const uint32_t width = it.dtype == GEAK_F32 ? 4u : (it.dtype == GEAK_F16 || it.dtype == GEAK_BF16) ? 2u : 1u;
-                const uint32_t pa = width == 4 ? reinterpret_cast<const uint32_t *>(cb)[i] : width == 2 ? reinterpret_cast<const uint16_t *>(cb)[i] : cb[i];
-                const uint32_t pb = width == 4 ? reinterpret_cast<const uint32_t *>(rb)[i] : width == 2 ? reinterpret_cast<const uint16_t *>(rb)[i] : rb[i];
-                const uint32_t sign = width == 4 ? 0x80000000u : width == 2 ? 0x8000u : 0x80u;
-                const uint32_t inf = it.dtype == GEAK_F32 ? 0x7F800000u : it.dtype == GEAK_F16 ? 0x7C00u : it.dtype == GEAK_BF16 ? 0x7F80u
-                                   : it.dtype == GEAK_F8E5M2 ? 0x7Cu : 0x7Eu;
-                const int ma = (int)(pa & (sign - 1u)), mb = (int)(pb & (sign - 1u));
-                const int oa = (pa & sign) ? -ma : ma, ob = (pb & sign) ? -mb : mb;
-                const uint32_t d = (oa > ob) ? (uint32_t)oa - (uint32_t)ob : (uint32_t)ob - (uint32_t)oa;
-                slot = ((uint32_t)ma > inf || (uint32_t)mb > inf) ? st.nslots - 1 : bit_length(d);
-                break;
-            }
-            case GEAK_F64: {
-                const u64 pa = reinterpret_cast<const u64 *>(cb)[i], pb = reinterpret_cast<const u64 *>(rb)[i];
-                const long long ma = (long long)(pa & 0x7FFFFFFFFFFFFFFFull), mb = (long long)(pb & 0x7FFFFFFFFFFFFFFFull);
-                const long long oa = ((long long)pa < 0) ? -ma : ma, ob = ((long long)pb < 0) ? -mb : mb;
-                const u64 d = (oa > ob) ? (u64)oa - (u64)ob : (u64)ob - (u64)oa;
-                slot = (ma > 0x7FF0000000000000ll || mb > 0x7FF0000000000000ll) ? st.nslots - 1 : bit_length(d);
-                break;
-            }
-            default: {
-                const long long a = load_elem_int(cb, i, it.dtype), b = load_elem_int(rb, i, it.dtype);
-                const u64 d = (a > b) ? (u64)a - (u64)b : (u64)b - (u64)a;
-                slot = bit_length(d);
-                break;
-            }
-            }
-            (void)__hip_atomic_fetch_add(row + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
-    }
-}
-
 __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const UlpArgs p)
 {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -618,22 +574,18 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
     uint32_t j = wave_first[blockIdx.x * kWavesPerBlock + wave];
     while (j < p.num_items) {                                   // kNoItem ends the list
         const geak_item it = load_work_item(p.items, j);
-        if (it.flags & GEAK_ITEM_ALIGNED) {
-            r.first_item = j;
-            uint32_t next_j;
-            if (it.flags & GEAK_ITEM_FULL) {
-                for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, false>(r, st); });
-            } else if (it.flags & GEAK_ITEM_ROWS) {
-                for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, true, true>(r, st); });
-            } else {
-                for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, true, false>(r, st); });
-            }
-            j = __builtin_amdgcn_readfirstlane(next_j);
-            continue;
+        r.first_item = j;
+        uint32_t next_j = it.next;
+        if (it.flags & GEAK_ITEM_FULL) {
+            for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, false>(r, st); });
+        } else if (it.flags & GEAK_ITEM_ROWS) {
+            for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, true, kTailRows>(r, st); });
+        } else if (it.flags & GEAK_ITEM_ALIGNED) {
+            for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, true, kTailPlain>(r, st); });
+        } else {
+            for_dtype(it.dtype, [&](auto dt) { next_j = ulp_run<decltype(dt)::value, true, kTailShifted>(r, st); });
         }
-        ulp_head(it, p.ref, p.cand_table, st, p.k_begin, p.k_count, lane);
-        if (it.flags & GEAK_ITEM_LAST) ulp_end_run(st, p.partials, it.slot, p.num_candidates, p.k_begin, p.k_count, lane);
-        j = it.next;
+        j = __builtin_amdgcn_readfirstlane(next_j);
     }
 }
 

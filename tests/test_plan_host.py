@@ -134,8 +134,12 @@ def _check_table(segs, K):
             if it["flags"] & B.GEAK_ITEM_FULL:
                 assert it["byte_offset"] % 16 == 0 and it["numel"] * w == info.item_bytes
             assert bool(it["flags"] & B.GEAK_ITEM_ALIGNED) == (it["byte_offset"] % 16 == 0)
-            if not it["flags"] & B.GEAK_ITEM_ALIGNED:        # an unaligned head never reaches a 16-byte boundary
-                assert it["elem_start"] == 0 and it["numel"] * w < 16
+            if not it["flags"] & B.GEAK_ITEM_ALIGNED:
+                # a start off the 16-byte grid: the segment's first item, which ends where a full item read
+                # from the boundary before it would end (or with the segment), so that the next one is aligned
+                skip = int(it["byte_offset"]) % 16
+                assert it["elem_start"] == 0 and skip % w == 0
+                assert int(it["numel"]) * w == min(n * w, info.item_bytes - skip)
             cursor[s] = cursor.get(s, 0) + int(it["numel"])
         for s, (off, n, dt) in enumerate(segs):
             assert cursor.get(s, 0) == n
@@ -200,8 +204,8 @@ def test_work_table_dense(lib):
     _check_table([(0, 5000, "f16")], 2)                  # ragged tail
     _check_table([(0, 1, "i32")], 1)
     _check_table([(0, 5000, "i64")], 2)                  # 512 elements per item
-    _check_table([(3, 10000, "u8"), (10240, 4096, "i8")], 2)   # 4096 elements per item, a 13-byte head
-    _check_table([(8, 700, "i64"), (8192, 3, "i64")], 3)  # a one-element head before the first 16-byte boundary
+    _check_table([(3, 10000, "u8"), (10240, 4096, "i8")], 2)   # 4096 elements per item, the first one 3 bytes off the grid
+    _check_table([(8, 700, "i64"), (8192, 3, "i64")], 3)  # a start 8 bytes off the grid
     _check_table([(8, 700, "f64"), (8192, 3, "f64"), (16384, 5000, "f64")], 3)
     _check_table([(5, 9000, "f8e4m3"), (16384, 4096, "f8e5m2")], 2)
 
