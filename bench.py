@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # They describe the kernel sources whose digest is recorded with them: once a source has changed,
 # the figures no longer apply and roofline.traffic is reported as null until they are retaken.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "6236b129d7a592e235144e363e6bef5e34a2c5b60e8d317617d220e5d4b7e331",
-    "bytes": {2: 8.7997e9, 3: 9.2010e9, 4: 1.2352e9, 5: 141.8710e9},
+    "sources_sha256": "4437ea7922fd8d69ecc646a0a2ec9e099aab6b8f69a8a4dfb855362c1313d270",
+    "bytes": {2: 8.7894e9, 3: 9.1911e9, 4: 1.2223e9, 5: 141.8606e9},
 }
 KERNEL_SOURCES = ["kernels.hip", "device_common.hpp", "plan_host.cpp", "api.cpp", "geak_internal.hpp"]
 
