@@ -216,7 +216,7 @@ def test_ragged_unaligned_starts(oracle_mod, align):
                                           (16, ("f32", "f16", "bf16", "i32"))])
 def test_ragged_many_pairs(oracle_mod, align, dtypes):
     """Plans with more than a thousand (segment, candidate) pairs are reduced by one wave per pair: every
-    dtype, segment starts on any byte, mismatches in heads, full items and tails."""
+    dtype, segment starts on any byte, mismatches in first items off the 16-byte grid, full items and tails."""
     print("ragged, many pairs", align, flush=True)
     w = synth.config4(num_segments=420, log2_max=13.0, num_candidates=3, device="cuda", align=align, seed=300 + align, dtypes=dtypes)
     assert len(w.segments) * len(w.cands) >= 1024
