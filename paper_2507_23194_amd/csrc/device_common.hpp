@@ -247,17 +247,6 @@ __device__ __forceinline__ F32Pair f8_pair_to_f32(uint32_t word)
     return F32Pair{v[0], v[1]};
 }
 
-// One element straight from memory, decoded exactly to binary32 (floating dtypes).
-__device__ __forceinline__ float load_elem_f(const unsigned char *base, u64 idx, int dtype)
-{
-    if (dtype == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
-    if (dtype == GEAK_F8E4M3) return f8_to_f32<GEAK_F8E4M3, 0>(base[idx]);
-    if (dtype == GEAK_F8E5M2) return f8_to_f32<GEAK_F8E5M2, 0>(base[idx]);
-    const uint16_t h = reinterpret_cast<const uint16_t *>(base)[idx];
-    if (dtype == GEAK_F16) return (float)__builtin_bit_cast(_Float16, h);
-    return bits_f((uint32_t)h << 16);
-}
-
 // One integer element straight from memory, widened exactly to 64 bits.
 __device__ __forceinline__ long long load_elem_int(const unsigned char *base, u64 idx, int dtype)
 {

@@ -22,22 +22,23 @@
 //     candidate) -- a block reads and raises replica (block mod R), the reduce kernel takes the
 //     maximum over them -- because many waves raising one address serialise at tens of
 //     microseconds per atomic.  Per element only `d > max_abs` and the sign of
-//     fma(max_rel, |b|, -d) are evaluated: the fused result is the correctly rounded value of
+//     fma(max_rel, |b|, -d) matter (both folded over a lane's vector with three-operand max / min
+//     and tested once): the fused result is the correctly rounded value of
 //     max_rel*|b| - d and rounding keeps the sign of the exact value, so "negative" is exactly
 //     "d/|b| would exceed max_rel", with no division.  When any lane trips, that vector is
 //     evaluated exactly in registers (true binary32 division for the lanes that exceed what they
 //     have seen) and the maxima are raised with a 64-bit atomic max on the bit patterns of the
 //     non-negative doubles.  Rounding is monotone, so the maximum of the rounded quotients is the
 //     rounded quotient of a tripping element.
-//   * A segment's tail (an aligned item shorter than 4 KiB) is compared in batches of several
-//     candidates per round of loads, with guarded loads that read absent elements as 0; the few
-//     elements before a segment's first 16-byte boundary take a compact element-wise path that
-//     applies the full rule straight from memory.
+//   * An item that is not a full one -- a segment's tail, a group of short rows of a pitched
+//     segment, or the first item of a segment that starts off the 16-byte grid (read from the
+//     boundary before it) -- is compared in batches of several candidates per round of loads, with
+//     guarded loads that read everything outside the item as 0.
 //   * first_mismatch: the wave only remembers the first of its items that holds a mismatch; the
 //     reduce kernel re-reads that one item and finds the exact index.
-// reduce kernel -- one block per (segment, candidate): sums counts over the segment's slots,
-//   takes the least item index, rescans that item with the full rule, folds the replicas of the
-//   maxima, writes the record.
+// reduce kernel -- one block per (segment, candidate), or one wave when there are many pairs: sums
+//   counts over the segment's slots, takes the least item index, rescans that item with the full
+//   rule, folds the replicas of the maxima, writes the record.
 //
 // Blocks of the compare kernel start at different candidates so that the first, expensive, visit
 // of a (segment, candidate) pair is spread out and later visitors find the maxima already raised:
@@ -92,10 +93,6 @@ __device__ __forceinline__ u64 load_bits(const double *p)
 __device__ __forceinline__ void publish_max(double *p, double v)
 {
     (void)__hip_atomic_fetch_max((GEAK_AS_GLOBAL u64 *)p, __builtin_bit_cast(u64, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void raise_max(double *p, double v, u64 seen_bits)
-{
-    if (__builtin_bit_cast(u64, v) > seen_bits) publish_max(p, v);
 }
 
 // The full rule for one floating element.
