@@ -67,7 +67,9 @@ typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64
 /* One tensor of a packed (ragged) batch.  Every buffer -- the reference and each candidate -- is
  * packed with the same table.  byte_offset must be a multiple of the element size; a start off the
  * 16-byte grid costs the segment one shorter first work item, read from the boundary before it.
- * numel == 0 is legal.  Segments must not overlap. */
+ * numel == 0 is legal.  Segments must not overlap.  The kernels load whole 16-byte aligned vectors: the
+ * up to 15 bytes between such a boundary and a segment's first byte, and between its last byte and the
+ * next boundary, may be read (never compared, never written); they lie in pages the segment occupies. */
 typedef struct {
     uint64_t byte_offset;
     uint64_t numel;
