@@ -28,8 +28,8 @@
  *       pass            1 iff mismatch_count == 0 (an empty segment passes)
  *       max_abs_err     max of d over ALL elements, NaN d skipped, +Inf kept, starting at +0
  *       max_rel_err     max over all elements of (d == 0 ? 0 : d / |b|) (binary32 division for
- *                       fp32 / fp16 / bf16, binary64 for fp64 and the integer dtypes; x/0 = +Inf; NaN
- *                       skipped), from +0
+ *                       fp32 / fp16 / bf16 / E4M3 / E5M2, binary64 for fp64 and the integer dtypes;
+ *                       x/0 = +Inf; NaN skipped), from +0
  *   Every field is an order-independent reduction, so results are bit-reproducible.
  *
  * Memory model.  The caller owns every device buffer (reference, candidates, workspace, results)
