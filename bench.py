@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # They describe the kernel sources whose digest is recorded with them: once a source has changed,
 # the figures no longer apply and roofline.traffic is reported as null until they are retaken.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "02286be6a5515bf29b010f21ef6e8c399a4f1393c5d2068577e36eff86099a99",
-    "bytes": {2: 8.7894e9, 3: 9.1911e9, 4: 1.2224e9, 5: 141.8606e9},
+    "sources_sha256": "b8f66a181d3fda321554ade729e5bda440c40778edd24db82fed6286a55307d1",
+    "bytes": {2: 8.7896e9, 3: 9.1909e9, 4: 1.2226e9, 5: 141.8606e9},
 }
 KERNEL_SOURCES = ["kernels.hip", "device_common.hpp", "plan_host.cpp", "api.cpp", "geak_internal.hpp"]
 

@@ -869,13 +869,15 @@ struct DoubleItem {
 };
 
 // ---- 8-bit floating formats: sixteen elements per 16-byte vector, the binary32 rule ----------------------
-// A lane holds 64 elements of the slice: neither the decoded reference nor its tolerances fit the
-// registers (nor, with four blocks per compute unit, the LDS).  The reference stays packed, is widened
-// again for every candidate and the tolerance is computed
-// again (one multiplication, one addition): seven vector instructions per element (the conversion
-// widens two at a time), against four for the wider dtypes, and a budget of 4.9 per byte at the
-// memory's speed -- this path is bound by arithmetic.  Elements the bare inequality cannot judge (b NaN, b +-Inf, tolerance overflowed) are
-// only marked when the slice is staged; vectors that hold one are counted again with the full rule.
+// A lane holds 64 elements of the slice: the decoded reference does not fit the registers, and of its
+// tolerances only half fit the wave's LDS region (four blocks per compute unit share the LDS).  The
+// reference stays packed and is widened again for every candidate (one conversion per two
+// elements); the tolerances of vectors 0 and 1 are staged in LDS, those of vectors 2 and 3 computed
+// again (one multiplication, one addition): five and seven vector instructions per element,
+// against four for the wider dtypes, and a budget of 4.9 per byte at the memory's speed -- this
+// path is bound by arithmetic.  Elements the bare inequality cannot judge (b NaN, b +-Inf, tolerance
+// overflowed) are only marked when the slice is staged; vectors that hold one are counted again
+// with the full rule.
 template <int DT>
 __device__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel, MaxPair *rec_in);
 template <int DT>
@@ -891,7 +893,11 @@ struct Fp8Item {
     uint32_t bref[kVecPerLane * 4];
     float atol_f, rtol_f;           // wave-uniform
     u64 poisoned_slots;             // wave-uniform: bit i set if any lane's element i is poisoned
-    __device__ __forceinline__ void attach_lds(uint32_t, int) {}
+    // The wave's LDS region holds the tolerances of half the slice (vectors 0 and 1: 32 per lane);
+    // those of the other half are computed again for every candidate.
+    static constexpr int kStoredVectors = 2;
+    TolStore<E, true> tol;
+    __device__ __forceinline__ void attach_lds(uint32_t region, int lane) { tol.attach(region, lane); }
 
     template <int e> static __device__ __forceinline__ float value(const uint32_t *words) { return f8_to_f32<DT, e & 3>(words[e >> 2]); }
     template <int e> static __device__ __forceinline__ float value(const u32x4 &q) { return f8_to_f32<DT, e & 3>(q[e >> 2]); }
@@ -902,13 +908,16 @@ struct Fp8Item {
         if constexpr (V == 0) { poisoned_slots = 0; atol_f = tolerance.atol_f; rtol_f = tolerance.rtol_f; }
 #pragma unroll
         for (int w = 0; w < 4; ++w) bref[V * 4 + w] = q[w];
+        float tv[E];
         static_for<E>([&](auto idx) {
             constexpr int e = decltype(idx)::value;
             const float x = value<e>(q);
             const float prod = rtol_f * __builtin_fabsf(x);
             const float t = atol_f + prod;
+            tv[e] = t;
             if (__builtin_amdgcn_ballot_w64(!(t < kInfF))) poisoned_slots |= 1ull << (V * E + e);
         });
+        if constexpr (V < kStoredVectors) tol.template put<V>(tv);
     }
 
     template <int V, bool AHEAD = true>
@@ -927,13 +936,22 @@ struct Fp8Item {
         // are folded into a running greatest |d| and a running least margin r|b| - |d| (three-operand
         // max / min, which skip NaN as the comparisons they replace did), tested once per vector.
         float d_most = 0.0f, margin_least = kInfF;
+        [[maybe_unused]] float tv[E];
+        if constexpr (V < kStoredVectors) tol.template get<V>(tv);
         static_for<E / 2>([&](auto idx) {
             constexpr int p = decltype(idx)::value;
             const F32Pair x = f8_pair_to_f32<DT, (p & 1) != 0>(words[p >> 1]);
             const F32Pair a = f8_pair_to_f32<DT, (p & 1) != 0>(q[p >> 1]);
             const float d0 = a.lo - x.lo, d1 = a.hi - x.hi;
-            const float prod0 = rtol_f * __builtin_fabsf(x.lo), prod1 = rtol_f * __builtin_fabsf(x.hi);
-            const float t0 = atol_f + prod0, t1 = atol_f + prod1;
+            float t0, t1;
+            if constexpr (V < kStoredVectors) {
+                t0 = tv[2 * p];
+                t1 = tv[2 * p + 1];
+            } else {
+                const float prod0 = rtol_f * __builtin_fabsf(x.lo), prod1 = rtol_f * __builtin_fabsf(x.hi);
+                t0 = atol_f + prod0;
+                t1 = atol_f + prod1;
+            }
             suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d0) <= t0)));
             suspects += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d1) <= t1)));
             d_most = __builtin_fmaxf(__builtin_fmaxf(__builtin_fabsf(d0), __builtin_fabsf(d1)), d_most);
