@@ -171,6 +171,22 @@ uint64_t geak_check_result_count(const geak_plan *plan);
 geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
                            void *workspace_dev, geak_result *results_dev, void *hip_stream);
 
+/*
+ * geak_check_run for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The workspace is a static device array of
+ * GEAK_STATIC_SCRATCH_BYTES that is part of the library (every GPU the library runs on holds its own copy
+ * until the process ends); the call itself allocates nothing.  Arguments and results as for
+ * geak_check_run, without the workspace.  GEAK_EWORKSPACE when geak_check_workspace_bytes(plan) exceeds
+ * GEAK_STATIC_SCRATCH_BYTES (8 MiB hold the five benchmark workloads, up to 2^30 elements x 32 candidates).
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams or
+ * threads) race; calls on one stream, one after the other, are fine -- nothing is carried over from
+ * one call to the next, every byte a call reads from the array it has written before.  The array's
+ * address is looked up when a plan is built for the device, so the run itself makes no such call.
+ */
+#define GEAK_STATIC_SCRATCH_BYTES (8u << 20)
+geak_status geak_check_run_static(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
+                                  geak_result *results_dev, void *hip_stream);
+
 void geak_check_destroy(geak_plan *plan);
 
 const char *geak_status_string(geak_status status);

@@ -25,6 +25,7 @@ GEAK_F8E4M3, GEAK_F8E5M2 = 8, 9
 GEAK_MAX_CANDIDATES = 256
 GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED, GEAK_ITEM_ROWS = 1, 2, 4, 8, 16
 GEAK_ULP_BINS = 66
+GEAK_STATIC_SCRATCH_BYTES = 8 << 20
 
 DTYPE_CODE = {"f32": GEAK_F32, "f16": GEAK_F16, "bf16": GEAK_BF16, "i32": GEAK_I32, "i64": GEAK_I64,
               "u8": GEAK_U8, "i8": GEAK_I8, "f64": GEAK_F64, "f8e4m3": GEAK_F8E4M3, "f8e5m2": GEAK_F8E5M2}
@@ -99,6 +100,8 @@ def library() -> ctypes.CDLL:
         lib.geak_check_result_count.argtypes = [vp]
         lib.geak_check_run.restype = ctypes.c_int
         lib.geak_check_run.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp, vp]
+        lib.geak_check_run_static.restype = ctypes.c_int
+        lib.geak_check_run_static.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp]
         lib.geak_check_destroy.restype = None
         lib.geak_check_destroy.argtypes = [vp]
         lib.geak_status_string.restype = ctypes.c_char_p
@@ -137,7 +140,7 @@ def library() -> ctypes.CDLL:
 
 
 EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
-            "geak_check_run", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
+            "geak_check_run", "geak_check_run_static", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
             "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram", "geak_check_verdicts",
             "geak_metrics_accuracy", "geak_metrics_speedup", "geak_metrics_pass_at_k"]
@@ -214,6 +217,12 @@ def geak_check_run(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: 
     """All pointers are device addresses as integers; stream is a hipStream_t as integer (0 = default)."""
     arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
     return int(library().geak_check_run(plan, ref_ptr, arr, workspace_ptr, results_ptr, stream))
+
+
+def geak_check_run_static(plan, ref_ptr: int, cand_ptrs: Sequence[int], results_ptr: int, stream: int) -> int:
+    """geak_check_run on the library's static scratch array: no workspace argument, no allocation."""
+    arr = (ctypes.c_void_p * max(1, len(cand_ptrs)))(*cand_ptrs)
+    return int(library().geak_check_run_static(plan, ref_ptr, arr, results_ptr, stream))
 
 
 def geak_check_report(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: int, results_ptr: int,

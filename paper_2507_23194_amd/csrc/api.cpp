@@ -171,6 +171,9 @@ static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const g
         if (ok) ok = hipMemcpy(p->segments_dev, p->host.segments.data(), seg_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->seg_tol_dev, p->host.seg_tol.data(), tol_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_EHIP; }
+        // set-up is the place to look up the device's copy of the static scratch array: geak_check_run_static
+        // then finds the address there (a failure here only surfaces if that entry point is used)
+        (void)static_scratch_address(device, nullptr);
     }
     *out = p;
     return GEAK_OK;

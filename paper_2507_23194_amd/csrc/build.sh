@@ -14,7 +14,7 @@ flags=(--offload-arch=gfx950 -O3 -std=c++17 -fPIC -ffp-contract=off
        -Xclang -target-feature -Xclang -packed-fp32-ops
        -Wall -Wno-unused-function -Wno-int-to-pointer-cast -I"$root/include" -I"$here" "$@")
 pids=()
-for src in kernels.hip ulp_kernels.hip verdict_kernel.hip metrics_host.cpp api.cpp plan_host.cpp; do
+for src in kernels.hip ulp_kernels.hip verdict_kernel.hip static_scratch.hip metrics_host.cpp api.cpp plan_host.cpp; do
     hipcc "${flags[@]}" -c "$here/$src" -o "$obj/${src%.*}.o" &
     pids+=($!)
 done

@@ -233,5 +233,7 @@ int launch_reduce(const ReduceArgs &args, void *stream);
 int launch_report(const ReportArgs &args, void *stream);
 int launch_read_probe(const ProbeArgs &args, uint32_t grid_blocks, void *stream);
 int compare_blocks_per_cu(uint32_t lds_bytes);   // occupancy query on the current device; <= 0 on failure
+// Address of `device`'s copy of the library's static scratch array (static_scratch.hip); hipError_t as int.
+int static_scratch_address(int device, void **out);
 
 }  // namespace geak
