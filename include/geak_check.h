@@ -191,6 +191,11 @@ void geak_check_destroy(geak_plan *plan);
 
 const char *geak_status_string(geak_status status);
 
+/* Digest (16 hex digits of a SHA-256) of the source files the loaded library was built from: the build script,
+ * this header and every file of csrc/, concatenated in bytewise path order.  A harness compares it with the
+ * digest of the sources it sits beside and refuses a library that was built from other sources. */
+const char *geak_check_build_id(void);
+
 /* ---- inspection (host only; used by tests and the benchmark's reporting) ---------------------- */
 
 typedef struct {

@@ -15,6 +15,9 @@ from .oracle import (  # noqa: F401
     ULP_BINS,
     check_dense,
     check_ragged,
+    check_dense_chunked,
+    combine_records,
+    host_cores,
     decode_f8,
     decode_f16,
     decode_bf16,

@@ -189,6 +189,50 @@ def check_dense(ref, cands, dtype: str, atol: float, rtol: float, equal_nan: boo
     return np.array(_run_pairs(jobs, threads), dtype=RECORD_DTYPE)
 
 
+def combine_records(parts, offsets):
+    """Fold the records of consecutive chunks of one tensor (chunk i starts at flat index offsets[i]) into the
+    record of the whole tensor.  Every field of the record is a sum, a least index or a maximum over the
+    elements (R7-R9 of geak_oracle.c), so the fold is: counts add, the first index is that of the first chunk
+    that has one, shifted by the chunk's start, and each maximum is the maximum of the chunks' maxima."""
+    out = np.zeros(1, dtype=RECORD_DTYPE)[0]
+    count, first, ma, mr = 0, -1, 0.0, 0.0
+    for rec, off in zip(parts, offsets):
+        count += int(rec["mismatch_count"])
+        if first < 0 and int(rec["first_mismatch"]) >= 0:
+            first = int(rec["first_mismatch"]) + off
+        ma = max(ma, float(rec["max_abs_err"]))
+        mr = max(mr, float(rec["max_rel_err"]))
+    out["pass"] = int(count == 0)
+    out["mismatch_count"] = count
+    out["first_mismatch"] = first
+    out["max_abs_err"] = ma
+    out["max_rel_err"] = mr
+    return out
+
+
+def check_dense_chunked(ref, cands, dtype: str, atol: float, rtol: float, equal_nan: bool, threads: int = 1,
+                        chunk: int = 1 << 22) -> np.ndarray:
+    """check_dense for large tensors: the element range is cut into chunks, each chunk is one plain
+    check_segment call (so that the C loop can run on several host threads), and the chunks' records are
+    folded with combine_records.  ref / cands: numpy arrays of the raw storage, one element per entry."""
+    n = ref.size
+    bounds = list(range(0, n, chunk)) or [0]
+    jobs = [(lambda k=k, lo=lo: check_segment(ref[lo:min(n, lo + chunk)], cands[k][lo:min(n, lo + chunk)],
+                                              min(n, lo + chunk) - lo, dtype, atol, rtol, equal_nan))
+            for k in range(len(cands)) for lo in bounds]
+    recs = _run_pairs(jobs, threads)
+    out = [combine_records(recs[k * len(bounds):(k + 1) * len(bounds)], bounds) for k in range(len(cands))]
+    return np.array(out, dtype=RECORD_DTYPE)
+
+
+def host_cores() -> int:
+    """Host cores this process may run on."""
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
 def check_ragged(ref_buf, cand_bufs, segments, atol: float, rtol: float, equal_nan: bool,
                  threads: int = 1) -> np.ndarray:
     """Ragged case.  segments: iterable of (byte_offset, numel, dtype_name); every candidate

@@ -70,10 +70,40 @@ def build_library(verbose: bool = False) -> str:
 
 
 def ensure_library() -> str:
-    """Build the library only when none is there; what is built is loaded as it is."""
+    """Build the library only when none is there; what is built is loaded as it is -- and must have been
+    built from the sources beside it (check_build_id raises otherwise)."""
     if not os.path.exists(LIB_PATH):
         build_library()
+    check_build_id()
     return LIB_PATH
+
+
+def source_digest() -> str:
+    """Digest of the sources the library is built from, computed as csrc/build.sh does: the header and every
+    file of csrc/, concatenated in bytewise path order; 16 hex digits of the SHA-256."""
+    import glob
+    import hashlib
+    root = os.path.dirname(_HERE)
+    paths = glob.glob(os.path.join(root, "include", "*.h")) + glob.glob(os.path.join(_HERE, "csrc", "*"))
+    rel = sorted(os.path.relpath(p, root).encode() for p in paths if os.path.isfile(p))
+    h = hashlib.sha256()
+    for r in rel:
+        with open(os.path.join(root, r.decode()), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def geak_check_build_id() -> str:
+    return library().geak_check_build_id().decode()
+
+
+def check_build_id() -> str:
+    """Raises unless the loaded library was built from the sources in this tree; returns the id."""
+    built, here = geak_check_build_id(), source_digest()
+    if built != here:
+        raise RuntimeError(f"{LIB_PATH} was built from other sources (build id {built}, sources here {here}): "
+                           "run paper_2507_23194_amd/csrc/build.sh (or __graft_entry__.build()) again")
+    return built
 
 
 def library() -> ctypes.CDLL:
@@ -104,6 +134,8 @@ def library() -> ctypes.CDLL:
         lib.geak_check_run_static.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp]
         lib.geak_check_destroy.restype = None
         lib.geak_check_destroy.argtypes = [vp]
+        lib.geak_check_build_id.restype = ctypes.c_char_p
+        lib.geak_check_build_id.argtypes = []
         lib.geak_status_string.restype = ctypes.c_char_p
         lib.geak_status_string.argtypes = [ctypes.c_int]
         lib.geak_check_plan_info.restype = ctypes.c_int
@@ -140,7 +172,7 @@ def library() -> ctypes.CDLL:
 
 
 EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
-            "geak_check_run", "geak_check_run_static", "geak_check_destroy", "geak_status_string", "geak_check_plan_info",
+            "geak_check_run", "geak_check_run_static", "geak_check_destroy", "geak_status_string", "geak_check_build_id", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
             "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram", "geak_check_verdicts",
             "geak_metrics_accuracy", "geak_metrics_speedup", "geak_metrics_pass_at_k"]

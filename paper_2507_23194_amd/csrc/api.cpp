@@ -320,6 +320,11 @@ void geak_check_destroy(geak_plan *plan)
     delete plan;
 }
 
+#ifndef GEAK_BUILD_ID
+#define GEAK_BUILD_ID "unknown"
+#endif
+const char *geak_check_build_id(void) { return GEAK_BUILD_ID; }
+
 const char *geak_status_string(geak_status status)
 {
     switch (status) {

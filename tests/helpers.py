@@ -67,55 +67,23 @@ def expect_tuple(e):
     return (e["pass"], e["mismatch_count"], e["first_mismatch"], f64_bits(e["max_abs_err"]), f64_bits(e["max_rel_err"]))
 
 
-# ---- oracle drivers used by the GPU parity tests and the benchmark's baseline leg --------------
+# ---- oracle drivers used by the GPU parity tests -------------------------------------------------
 def combine_records(parts, offsets):
-    """Fold the records of consecutive chunks of one tensor (chunk i starts at flat index
-    offsets[i]) into the record of the whole tensor: counts add, first index is the least,
-    both maxima are maxima.  (Pinned by the concatenation invariant in test_oracle_pins.)"""
-    out = np.zeros(1, dtype=parts[0].dtype)[0]
-    count, first, ma, mr = 0, -1, 0.0, 0.0
-    for rec, off in zip(parts, offsets):
-        count += int(rec["mismatch_count"])
-        if first < 0 and int(rec["first_mismatch"]) >= 0:
-            first = int(rec["first_mismatch"]) + off
-        ma = max(ma, float(rec["max_abs_err"]))
-        mr = max(mr, float(rec["max_rel_err"]))
-    out["pass"] = int(count == 0)
-    out["mismatch_count"] = count
-    out["first_mismatch"] = first
-    out["max_abs_err"] = ma
-    out["max_rel_err"] = mr
-    return out
+    import oracle
+    return oracle.combine_records(parts, offsets)
 
 
 def oracle_dense_chunked(oracle_mod, ref_np, cand_nps, dtype, atol, rtol, equal_nan, threads, chunk=1 << 22):
-    """Oracle records of a large dense tensor, with the element range cut into chunks so that the
-    plain C loop can run on several host threads."""
-    from concurrent.futures import ThreadPoolExecutor
-    n = ref_np.size
-    bounds = list(range(0, n, chunk)) or [0]
-    jobs = [(k, lo) for k in range(len(cand_nps)) for lo in bounds]
-
-    def run(job):
-        k, lo = job
-        hi = min(n, lo + chunk)
-        return oracle_mod.check_segment(ref_np[lo:hi], cand_nps[k][lo:hi], hi - lo, dtype, atol, rtol, equal_nan)
-
-    with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
-        recs = list(ex.map(run, jobs))
-    out = []
-    for k in range(len(cand_nps)):
-        out.append(combine_records(recs[k * len(bounds):(k + 1) * len(bounds)], bounds))
-    return np.array(out, dtype=recs[0].dtype)
+    """Oracle records of a large dense tensor: oracle.check_dense_chunked (pinned against one plain
+    check_segment call in test_oracle_pins.py::test_chunked_driver_equals_one_plain_call)."""
+    return oracle_mod.check_dense_chunked(ref_np, cand_nps, dtype, atol, rtol, equal_nan, threads=threads, chunk=chunk)
 
 
 def host_threads() -> int:
-    import os
-    try:
-        n = len(os.sched_getaffinity(0))
-    except AttributeError:
-        n = os.cpu_count() or 1
-    return max(1, min(16, n))
+    """Worker threads for the oracle: the host cores this process may use, at most the 16 that are a
+    one-GPU machine's share."""
+    import oracle
+    return max(1, min(16, oracle.host_cores()))
 
 
 def workload_oracle(oracle_mod, w, threads=None, cand_subset=None):

@@ -409,6 +409,35 @@ def test_invariants(oracle_mod, dtype):
     assert int(one["pass"]) == 0
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i32"])
+def test_chunked_driver_equals_one_plain_call(oracle_mod, dtype):
+    """The driver the full-size parity tests and the benchmark's baseline use for large dense tensors
+    (oracle.check_dense_chunked: chunks on host threads, records folded by oracle.combine_records) gives the
+    record of ONE plain check_segment call over the whole tensor -- on about 1e7 elements, with mismatches,
+    NaN and infinities in several chunks, a chunk size that does not divide the length, and candidates whose
+    first mismatch lies in the first, a middle and the last chunk."""
+    rng = np.random.default_rng(21)
+    n = 10_000_019
+    b, a = _rand_case(rng, dtype, n)
+    chunk = 1 << 20                                             # 10 chunks, the last one ragged
+
+    def planted(idx):
+        """A copy of the reference with the top exponent bit (integers: bit 30) of element idx flipped."""
+        c = b.copy()
+        bits = c.view(np.uint32) if c.itemsize == 4 else c.view(np.uint16)
+        bits[idx] ^= 0x40000000 if c.itemsize == 4 else 0x4000
+        return c
+
+    cands = [a, planted(n - 3), planted(5 * chunk + 17), b.copy()]
+    kw = dict(atol=1e-4, rtol=1e-3, equal_nan=True)
+    whole = [oracle_mod.check_segment(b, c, n, dtype, **kw) for c in cands]
+    chunked = oracle_mod.check_dense_chunked(b, cands, dtype, kw["atol"], kw["rtol"], kw["equal_nan"], threads=4, chunk=chunk)
+    assert [record_tuple(r) for r in chunked] == [record_tuple(r) for r in whole]
+    firsts = [int(r["first_mismatch"]) for r in whole]
+    assert 0 <= firsts[0] < chunk and firsts[1] == n - 3 and firsts[2] == 5 * chunk + 17 and firsts[3] == -1
+    assert int(whole[0]["mismatch_count"]) > 1000
+
+
 def test_ragged_offsets_and_index_space(oracle_mod):
     """Ragged records are indexed [segment, candidate] and first_mismatch is segment-relative."""
     rng = np.random.default_rng(5)
