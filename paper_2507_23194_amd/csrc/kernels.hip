@@ -53,15 +53,43 @@ namespace geak {
 namespace {
 
 
+// A value every lane holds alike (it came from a load all lanes made at one address), moved to scalar
+// registers: what depends on it -- the threshold tests of every vector -- then runs on the scalar unit
+// and as uniform branches instead of per-lane masks.
+__device__ __forceinline__ u64 uniform64(u64 v)
+{
+    const u64 lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)v), hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return lo | (hi << 32);
+}
+__device__ __forceinline__ float uniform_f(float x)
+{
+    return __builtin_bit_cast(float, (uint32_t)__builtin_amdgcn_readfirstlane(__builtin_bit_cast(uint32_t, x)));
+}
+__device__ __forceinline__ double uniform_d(double x) { return __builtin_bit_cast(double, uniform64(__builtin_bit_cast(u64, x))); }
+__device__ __forceinline__ float uniform_of(float x) { return uniform_f(x); }
+__device__ __forceinline__ double uniform_of(double x) { return uniform_d(x); }
+
 // ---- wave reductions (rare paths only) ---------------------------------------------------------
+// Maximum over the wave, returned in every lane.  Data-parallel-primitive row shifts and the two
+// row broadcasts of wave64 leave the maximum in lane 63 without going through LDS (a shuffle is an
+// LDS-path instruction with a wait behind it: six of those per value made a trip of the maxima
+// filters cost most of a microsecond).  Lanes that a shift gives no source keep their own value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float max_with_dpp(float x)
+{
+    const int self = __builtin_bit_cast(int, x);
+    const float y = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(self, self, CTRL, ROW_MASK, 0xF, false));
+    return (y > x) ? y : x;
+}
 __device__ __forceinline__ float wave_max_f(float x)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const float y = __shfl_xor(x, o, kWaveSize);
-        x = (y > x) ? y : x;
-    }
-    return x;
+    x = max_with_dpp<0x111, 0xF>(x);          // row_shr:1
+    x = max_with_dpp<0x112, 0xF>(x);          // row_shr:2
+    x = max_with_dpp<0x114, 0xF>(x);          // row_shr:4
+    x = max_with_dpp<0x118, 0xF>(x);          // row_shr:8: lane 15 of each row holds the row's maximum
+    x = max_with_dpp<0x142, 0xA>(x);          // row_bcast:15 into rows 1 and 3
+    x = max_with_dpp<0x143, 0xC>(x);          // row_bcast:31 into rows 2 and 3: lane 63 holds the wave's maximum
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 __device__ __forceinline__ double wave_max_d(double x)
 {
@@ -304,7 +332,7 @@ template <int E> struct TolStore<E, true> {
 template <int DT>
 struct FloatItem {
     typedef float Hint;                 // the running maxima of floating segments are binary32 values
-    static __device__ __forceinline__ float hint_from_bits(u64 bits) { return (float)__builtin_bit_cast(double, bits); }
+    static __device__ __forceinline__ float hint_from_bits(u64 bits) { return uniform_f((float)__builtin_bit_cast(double, bits)); }
     static constexpr int E = Traits<DT>::E;
     static constexpr int N = kVecPerLane * E;
     // Reference storage: binary32 and binary16 keep the vectors as loaded (binary32 needs no decode,
@@ -477,8 +505,8 @@ struct FloatItem {
             if (dm > max_abs) publish_max(&rec->abs, (double)dm);
             if (rm > max_rel) publish_max(&rec->rel, (double)rm);
         }
-        max_abs = dm;
-        max_rel = rm;
+        max_abs = uniform_of(dm);           // all lanes hold the wave's maximum: back to scalar registers
+        max_rel = uniform_of(rm);
     }
 
     // the same two rare paths through real functions (by-value arguments)
@@ -496,8 +524,8 @@ struct FloatItem {
         RefVec<DT> r;
         static_for<E>([&](auto idx) { constexpr int e = decltype(idx)::value; r.b[e] = ref_value<V, e>(); });
         const FloatPair out = raise_vector<DT>(q, r, max_abs, max_rel, rec);
-        max_abs = out.abs;
-        max_rel = out.rel;
+        max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
+        max_rel = uniform_of(out.rel);
     }
 };
 
@@ -559,7 +587,7 @@ __device__ __noinline__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> r
 // ---- int32: same interface, exact equality ---------------------------------------------------------
 struct IntItem {
     typedef double Hint;                // |a - b| reaches 2^32 - 1 and the quotient is binary64
-    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
+    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, uniform64(bits)); }
     static constexpr int E = 4;
     // the exact evaluation is binary64 arithmetic with a division: inlined into the stream it costs
     // the loop its registers, so it is always called
@@ -594,8 +622,8 @@ struct IntItem {
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
         const DoublePair out = raise_vector_int(q, b, max_abs, max_rel, rec);
-        max_abs = out.abs;
-        max_rel = out.rel;
+        max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
+        max_rel = uniform_of(out.rel);
     }
 
     template <int V>
@@ -621,8 +649,8 @@ struct IntItem {
             if (dm > max_abs) publish_max(&rec->abs, dm);
             if (rm > max_rel) publish_max(&rec->rel, rm);
         }
-        max_abs = dm;
-        max_rel = rm;
+        max_abs = uniform_of(dm);           // all lanes hold the wave's maximum: back to scalar registers
+        max_rel = uniform_of(rm);
     }
 };
 
@@ -688,7 +716,7 @@ __device__ __noinline__ DoublePair raise_vector_int64(const u32x4 q, const u32x4
 
 struct Int64Item {
     typedef double Hint;
-    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
+    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, uniform64(bits)); }
     static constexpr int E = 2;
     static constexpr bool kRaiseOutOfLine = true;
     uint32_t bref[kVecPerLane * 4];
@@ -722,8 +750,8 @@ struct Int64Item {
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
         const DoublePair out = raise_vector_int64(q, b, max_abs, max_rel, rec);
-        max_abs = out.abs;
-        max_rel = out.rel;
+        max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
+        max_rel = uniform_of(out.rel);
     }
     template <int V>
     __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec, int) const
@@ -772,7 +800,7 @@ __device__ __noinline__ DoublePair raise_vector_f64(const u32x4 q, const u32x4 b
 
 struct DoubleItem {
     typedef double Hint;
-    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
+    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, uniform64(bits)); }
     static constexpr int E = 2;
     static constexpr bool kRaiseOutOfLine = true;    // binary64 division: kept out of the stream, like the integer items'
     uint32_t bref[kVecPerLane * 4];
@@ -858,8 +886,8 @@ struct DoubleItem {
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
         const DoublePair out = raise_vector_f64(q, b, max_abs, max_rel, rec);
-        max_abs = out.abs;
-        max_rel = out.rel;
+        max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
+        max_rel = uniform_of(out.rel);
     }
     template <int V>
     __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec, int) const
@@ -887,7 +915,7 @@ __device__ int recount_vector_f8(const u32x4 q, const u32x4 b, const uint32_t ma
 template <int DT>
 struct Fp8Item {
     typedef float Hint;
-    static __device__ __forceinline__ float hint_from_bits(u64 bits) { return (float)__builtin_bit_cast(double, bits); }
+    static __device__ __forceinline__ float hint_from_bits(u64 bits) { return uniform_f((float)__builtin_bit_cast(double, bits)); }
     static constexpr int E = 16;
     static constexpr bool kRaiseOutOfLine = true;
     uint32_t bref[kVecPerLane * 4];
@@ -990,8 +1018,8 @@ struct Fp8Item {
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
         const FloatPair out = raise_vector_f8<DT>(q, b, max_abs, max_rel, rec);
-        max_abs = out.abs;
-        max_rel = out.rel;
+        max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
+        max_rel = uniform_of(out.rel);
     }
     template <int V>
     __device__ __forceinline__ void raise_vec(const u32x4 &q, float &max_abs, float &max_rel, MaxPair *rec, int) const
@@ -1108,7 +1136,7 @@ __device__ __noinline__ DoublePair raise_vector_bytes(const u32x4 q, const u32x4
 template <bool SIGNED>
 struct ByteItem {
     typedef double Hint;
-    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, bits); }
+    static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, uniform64(bits)); }
     static constexpr int E = 16;
     static constexpr bool kRaiseOutOfLine = true;
     uint32_t bref[kVecPerLane * 4];
@@ -1143,8 +1171,8 @@ struct ByteItem {
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
         const DoublePair out = raise_vector_bytes<SIGNED>(q, b, max_abs, max_rel, rec);
-        max_abs = out.abs;
-        max_rel = out.rel;
+        max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
+        max_rel = uniform_of(out.rel);
     }
     template <int V>
     __device__ __forceinline__ void raise_vec(const u32x4 &q, double &max_abs, double &max_rel, MaxPair *rec, int) const
