@@ -250,8 +250,8 @@ uint64_t geak_check_plan_waves(const geak_plan *plan, uint32_t *out, uint64_t ca
 /* Copies up to `capacity` items into `out` (host); returns the total number of items. */
 uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t capacity);
 
-/* ---- optional device timing of the compare kernel (section 4.1: the evaluator also measures
- * latency; here the check times itself) ---------------------------------------------------------
+/* ---- optional device timing of the compare kernel (a measurement aid of this library, used by its
+ * benchmark; not something the paper describes) -------------------------------------------------
  * After geak_check_profile_enable(plan, n) every geak_check_run records a HIP event pair around the
  * compare kernel on the run's stream, into a ring of n pairs (no synchronisation is added).
  * geak_check_profile_read must be called after the caller has synchronised the stream(s); it

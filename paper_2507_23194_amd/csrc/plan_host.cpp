@@ -64,20 +64,31 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         for (size_t i = 1; i < spans.size(); ++i)
             if (spans[i].first < spans[i - 1].second) return GEAK_EBOUNDS;
 
-        // count items first: a shorter first item where a row starts off the 16-byte grid, full items, tail
+        // Count items first, in closed form (a segment may have 2^40 one-element rows): a group of short rows
+        // is one item; otherwise a row gives a shorter first item where it starts off the 16-byte grid, full
+        // items and a tail, and the rows' starts repeat modulo 16 with a period of at most 16 rows.
         uint64_t n_items = 0;
         for (uint64_t s = 0; s < nsegs; ++s) {
             const SegDesc &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
             if (!g.numel) continue;
-            for (uint64_t r = 0; r < seg_rows(g); ++r) {
-                uint64_t n = g.row_elems;
-                const uint64_t start = g.byte_offset + r * g.pitch_bytes;
-                const uint64_t skip = (start % 16) / w;               // a start off the 16-byte grid: one shorter first item
-                if (skip) { ++n_items; n -= std::min<uint64_t>(n, per - skip); }
-                n_items += n / per + (n % per ? 1 : 0);
-                if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
+            const uint64_t rows = seg_rows(g);
+            const uint64_t row_vectors = (g.row_elems * w + 15) / 16;
+            if (rows > 1 && g.byte_offset % 16 == 0 && g.pitch_bytes % 16 == 0 && row_vectors <= kItemBytes / 32) {
+                const uint64_t group = (kItemBytes / 16) / row_vectors;
+                n_items += (rows + group - 1) / group;
+            } else {
+                uint64_t period = 1;
+                while ((g.pitch_bytes * period) % 16 != 0) period *= 2;        // 1, 2, 4, 8 or 16
+                for (uint64_t r = 0; r < period && r < rows; ++r) {
+                    uint64_t n = g.row_elems, count = 0;
+                    const uint64_t skip = ((g.byte_offset + r * g.pitch_bytes) % 16) / w;
+                    if (skip) { ++count; n -= std::min<uint64_t>(n, per - skip); }
+                    count += n / per + (n % per ? 1 : 0);
+                    n_items += count * ((rows - r + period - 1) / period);     // rows r, r + period, r + 2 period, ...
+                }
             }
+            if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
         }
         if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
 
@@ -150,6 +161,8 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                 if (g.row_elems - done) push(g.row_elems - done, false);
             }
         }
+
+        if (hp.items.size() != n_items) return GEAK_EINVAL;     // the closed-form count and the table must agree
 
         // Partition of the table over the persistent grid.  Block b owns the contiguous item range
         // [block_first[b], block_first[b + 1]); its four waves interleave inside it (wave w takes every

@@ -247,10 +247,10 @@ template <int DT> struct UlpRef {
 //   ord      magnitude, negated (two's complement, 16 bits) in a negative half
 //   distance max - min of the two ord values; it is below 2^16, so the wrapping subtraction is exact
 //   classes  t = min(d, 8) per half selects, as a byte selector of v_perm_b32, an entry of an 8-byte
-//            table: 1 for d = 1 and 32 for d = 2, 3 in the first table, 1 for d = 4 .. 7 in the second;
+//            table: 1 for d = 1 and 64 for d = 2, 3 in the first table, 1 for d = 4 .. 7 in the second;
 //            d = 0 selects 0 and so does t = 8 (selector 8 yields the sign of table byte 1).  The upper
 //            byte of each half of t is 0 and selects entry 0 as well.  Adding the results to two
-//            per-lane accumulators counts the three classes in 5-bit fields of each half (a lane
+//            per-lane accumulators counts the three classes in 6-bit fields of each half (a lane
 //            sees 16 words per slice); they are summed over the wave once per candidate slice.
 //   NaN      a NaN in the candidate needs no test while the reference vector holds nothing within 8
 //            steps of Inf or beyond: its distance is then at least 8, and the far path, which looks

@@ -109,7 +109,7 @@ def _oracle_hist_chunked(oracle_mod, ref, cand, numel, dtype, off, chunk=1 << 22
     return np.sum(parts, axis=0, dtype=np.uint64)
 
 
-@pytest.mark.parametrize("cid,ks", [(2, [0, 40]), (4, None), (5, [3])])
+@pytest.mark.parametrize("cid,ks", [(2, [0, 40]), (3, [1, 9]), (4, None), (5, [3])])
 def test_histogram_full_configs(oracle_mod, cid, ks):
     """The benchmark's workloads at full size: all 66 counts of the sampled candidates against the oracle,
     and the sum of every pair's bins against the segment length."""

@@ -394,3 +394,31 @@ def test_row_group_items(lib, rows, row_elems, pitch, dt, group):
 def test_pitched_plan_rejects(lib, segs, status):
     st, plan = B.geak_check_plan_pitched(segs, None, 2, 0, 0, 0, -1)
     assert st == status and plan is None
+
+
+def test_item_count_in_closed_form(lib):
+    """The planner sizes its table before it builds it, without walking the rows: the count must equal the
+    number of items it then makes (a smaller count would overflow the reservation unnoticed, a larger one
+    would refuse plans that fit), for rows on and off the 16-byte grid, grouped and not."""
+    rng = np.random.default_rng(9)
+    esize = {"f32": 4, "f16": 2, "u8": 1, "f64": 8}
+    for _ in range(60):
+        dt = ["f32", "f16", "u8", "f64"][int(rng.integers(0, 4))]
+        w = esize[dt]
+        rows = int(rng.integers(1, 40))
+        row_elems = int(rng.integers(1, 6000))
+        pitch = (row_elems + int(rng.integers(0, 40))) * w
+        off = int(rng.integers(0, 64)) * w
+        st, plan = B.geak_check_plan_pitched([(off, rows, row_elems, pitch, dt)], None, 2, 0.0, 0.0, False, -1)
+        assert st == B.GEAK_OK
+        try:
+            items = B.geak_check_plan_items(plan)
+            assert len(items) == B.geak_check_plan_info(plan).num_items
+            assert int(items["numel"].astype(np.int64).sum()) == rows * row_elems
+        finally:
+            B.geak_check_destroy(plan)
+    # 2^31 short rows that start on 16-byte boundaries are 2^23 row groups: planned, not refused
+    st, plan = B.geak_check_plan_pitched([(0, 1 << 31, 16, 32, "u8")], None, 1, 0.0, 0.0, False, -1)
+    assert st == B.GEAK_OK
+    assert B.geak_check_plan_info(plan).num_items == (1 << 31) // 256
+    B.geak_check_destroy(plan)
