@@ -50,7 +50,7 @@ typedef enum {
     GEAK_OK = 0,
     GEAK_EINVAL = 1,     /* null pointer, nsegs == 0, K out of range, bad atol/rtol/equal_nan, host-only plan run */
     GEAK_EDTYPE = 2,     /* unknown dtype code */
-    GEAK_EALIGN = 3,     /* byte_offset not a multiple of the element size; base pointer not 16-byte aligned */
+    GEAK_EALIGN = 3,     /* byte_offset or a tensor's base pointer not a multiple of the element size; workspace or results misaligned */
     GEAK_EBOUNDS = 4,    /* byte_offset + numel * size overflows, segments overlap, or too many elements */
     GEAK_ENOMEM = 5,     /* host or device allocation failed while planning */
     GEAK_EWORKSPACE = 6, /* workspace pointer missing although geak_check_workspace_bytes() > 0 */
@@ -67,9 +67,11 @@ typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64
 /* One tensor of a packed (ragged) batch.  Every buffer -- the reference and each candidate -- is
  * packed with the same table.  byte_offset must be a multiple of the element size; a start off the
  * 16-byte grid costs the segment one shorter first work item, read from the boundary before it.
- * numel == 0 is legal.  Segments must not overlap.  The kernels load whole 16-byte aligned vectors: the
- * up to 15 bytes between such a boundary and a segment's first byte, and between its last byte and the
- * next boundary, may be read (never compared, never written); they lie in pages the segment occupies. */
+ * numel == 0 is legal.  Segments must not overlap.  In a tensor whose base pointer is 16-byte aligned the
+ * kernels load whole 16-byte aligned vectors: the up to 15 bytes between such a boundary and a segment's first
+ * byte, and between its last byte and the next boundary, may be read (never compared, never written); they lie
+ * in pages the segment occupies.  In a tensor whose base pointer is only element-aligned nothing outside the
+ * segments is read. */
 typedef struct {
     uint64_t byte_offset;
     uint64_t numel;
@@ -159,9 +161,12 @@ uint64_t geak_check_result_count(const geak_plan *plan);
 /*
  * Run the planned check (the comparison of section 3.1 for all candidates in one pass: the
  * reference is read once and every candidate once).
- *   ref_dev      device pointer, packed reference buffer, 16-byte aligned (may be NULL, like the
- *                candidate pointers, when every segment is empty: nothing is read then)
- *   cand_dev     HOST array of num_candidates DEVICE pointers, each 16-byte aligned and packed like ref_dev
+ *   ref_dev      device pointer, packed reference buffer, aligned to the largest element size among the
+ *                plan's segments -- a slice of a larger tensor will do; 16-byte aligned bases are read a
+ *                little faster (may be NULL, like the candidate pointers, when every segment is empty:
+ *                nothing is read then)
+ *   cand_dev     HOST array of num_candidates DEVICE pointers, each aligned and packed like ref_dev (the
+ *                tensors need not share an alignment)
  *   workspace    device pointer to geak_check_workspace_bytes() bytes (ignored when that is 0)
  *   results_dev  device pointer to geak_check_result_count() records; fully overwritten
  *   hip_stream   hipStream_t (NULL = default stream); three kernels are enqueued on it

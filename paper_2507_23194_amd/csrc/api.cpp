@@ -220,15 +220,19 @@ uint64_t geak_check_result_count(const geak_plan *plan)
 }
 
 // The tensor arguments of a call: the reference and the K candidate base pointers must be there
-// when the plan reads any data, and 16-byte aligned (the kernels' vector loads rely on it).
+// when the plan reads any data, and aligned to the largest element size among the plan's segments
+// (every element then sits at a multiple of its size).  Nothing more: a base off the 16-byte grid --
+// a slice of a larger tensor -- is read with vector loads at odd addresses.
 static geak_status check_tensor_pointers(const HostPlan &hp, const void *ref_dev, const void *const *cand_dev)
 {
     const bool reads_data = !hp.items.empty();          // a plan of empty segments touches no tensor
+    uintptr_t mask = 0;
+    for (const SegDesc &g : hp.segments) mask |= (uintptr_t)elem_size(g.dtype) - 1u;
     if (reads_data && !ref_dev) return GEAK_EINVAL;
-    if ((uintptr_t)ref_dev & 15u) return GEAK_EALIGN;
+    if ((uintptr_t)ref_dev & mask) return GEAK_EALIGN;
     for (int k = 0; k < hp.num_candidates; ++k) {
         if (reads_data && !cand_dev[k]) return GEAK_EINVAL;
-        if ((uintptr_t)cand_dev[k] & 15u) return GEAK_EALIGN;
+        if ((uintptr_t)cand_dev[k] & mask) return GEAK_EALIGN;
     }
     return GEAK_OK;
 }

@@ -92,11 +92,15 @@ __device__ __forceinline__ float decode(const u32x4 &q, int e)
 }
 
 // ---- loads -------------------------------------------------------------------------------------
-// Elements [lo, valid) of the 16-byte vector at p (p on a 16-byte boundary), the rest 0.  A vector
-// that holds any element of the item is loaded whole and the bytes of the other elements are
-// cleared: the vector is one aligned 16-byte granule of the buffer, so it lies in the same page as
-// the item's own bytes in it and the load touches nothing the item's bytes do not already map.  A
-// vector without any element of the item is not loaded at all.
+// Elements [lo, valid) of the 16-byte vector at p, the rest 0.  With p on a 16-byte boundary (the
+// tensor's base pointer is 16-byte aligned) a vector that holds any element of the item is loaded
+// whole and the bytes of the other elements are cleared: the vector is one aligned 16-byte granule
+// of the buffer, so it lies in the same page as the item's own bytes in it and the load touches
+// nothing the item's bytes do not already map.  With p off the grid (a base pointer that is only
+// element-aligned, such as a slice of a larger tensor) a vector that lies wholly inside the item is
+// still one 16-byte load -- the hardware takes global loads at any address -- and a vector that holds
+// only part of the item is read byte by byte.  A vector without any element of the item is not loaded
+// at all.
 // Bytes [first_byte, end_byte) of the vector kept, the others cleared.
 __device__ __forceinline__ u32x4 cut_vector_inline(u32x4 q, const int first_byte, const int end_byte)
 {
@@ -114,12 +118,31 @@ __device__ __noinline__ u32x4 cut_vector_call(const u32x4 q, const int first_byt
     return cut_vector_inline(q, first_byte, end_byte);
 }
 
+// Bytes [first_byte, end_byte) of the 16 bytes at p, read one by one, the others 0: for a vector that holds
+// only part of an item in a tensor whose base pointer is not 16-byte aligned.  There the vector is no
+// aligned granule, may straddle a page, and nothing outside the item's own bytes may be touched.  Rare
+// (the first and last vector of an item that is not a full one, in such a tensor only): a real function.
+__device__ __noinline__ u32x4 load_bytes_call(const GEAK_AS_GLOBAL unsigned char *p, const int first_byte, const int end_byte)
+{
+    u32x4 q = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int b = 0; b < 16; ++b)
+        if (b >= first_byte && b < end_byte) q[b >> 2] |= (uint32_t)p[b] << (8 * (b & 3));
+    return q;
+}
+
 template <int DT>
 __device__ __forceinline__ u32x4 load_partial_from(global_vec_ptr p, uint32_t lo, uint32_t valid)
 {
     constexpr uint32_t E = Traits<DT>::E, W = Traits<DT>::W;
     u32x4 q = {0u, 0u, 0u, 0u};
-    if (valid > lo) q = __builtin_nontemporal_load(p);
+    const bool partial = valid > lo && (lo != 0 || valid < E);
+    const bool off_grid = ((uint32_t)reinterpret_cast<u64>(p) & 15u) != 0;       // the same for every lane: a property of the tensor's base
+    if (valid > lo && !(partial && off_grid)) q = __builtin_nontemporal_load(p);
+    if (__builtin_amdgcn_ballot_w64(partial && off_grid)) {
+        if (partial && off_grid)
+            q = load_bytes_call((const GEAK_AS_GLOBAL unsigned char *)p, (int)(lo * W), (int)((valid < E ? valid : E) * W));
+    }
     // The wave branches around the cut as a whole (in a tail only one lane of the last vector needs
     // it); inside, a lane whose vector is whole keeps all of it.  The routines of the 16-bit dtypes
     // have no registers to spare, so there the cut is a call.

@@ -17,7 +17,8 @@ TORCH_STORAGE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloa
 
 
 def _to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
-    """numpy storage (float32 / uint16 bit patterns / int32) -> device tensor with 16-byte aligned base."""
+    """numpy storage (float32 / uint16 bit patterns / int32) -> device tensor with 16-byte aligned base
+    (bases off the grid: test_gpu_unaligned_bases.py)."""
     if dtype in ("f16", "bf16"):
         t = torch.from_numpy(arr.view(np.int16).copy()).view(TORCH_STORAGE[dtype])
     else:
@@ -425,8 +426,9 @@ def test_run_argument_errors():
     ws, res = ck.workspace.data_ptr(), ck.results.data_ptr()
     assert B.geak_check_run(ck.plan, 0, [ok, ok], ws, res, 0) == B.GEAK_EINVAL
     assert B.geak_check_run(ck.plan, ok, [ok, 0], ws, res, 0) == B.GEAK_EINVAL
-    assert B.geak_check_run(ck.plan, ok + 4, [ok, ok], ws, res, 0) == B.GEAK_EALIGN
-    assert B.geak_check_run(ck.plan, ok, [ok, ok + 8], ws, res, 0) == B.GEAK_EALIGN
+    assert B.geak_check_run(ck.plan, ok + 2, [ok, ok], ws, res, 0) == B.GEAK_EALIGN      # not a multiple of the element size
+    assert B.geak_check_run(ck.plan, ok, [ok, ok + 1], ws, res, 0) == B.GEAK_EALIGN
+    assert B.geak_check_run(ck.plan, ok + 4, [ok, ok + 8], ws, res, 0) == B.GEAK_OK        # element-aligned bases will do
     assert B.geak_check_run(ck.plan, ok, [ok, ok], 0, res, 0) == B.GEAK_EWORKSPACE
     assert B.geak_check_run(ck.plan, ok, [ok, ok], ws, 0, 0) == B.GEAK_EINVAL
     assert B.geak_check_run(ck.plan, ok, [ok, ok], ws, res, 0) == B.GEAK_OK
@@ -450,7 +452,7 @@ def test_argument_errors_of_the_other_entry_points():
     assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], sp, 0, 0) == B.GEAK_EINVAL
     assert B.geak_check_ulp_histogram(ck.plan, 0, [ok, ok], sp, hp, 0) == B.GEAK_EINVAL
     assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, 0], sp, hp, 0) == B.GEAK_EINVAL
-    assert B.geak_check_ulp_histogram(ck.plan, ok + 2, [ok, ok], sp, hp, 0) == B.GEAK_EALIGN
+    assert B.geak_check_ulp_histogram(ck.plan, ok + 1, [ok, ok], sp, hp, 0) == B.GEAK_EALIGN
     assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], sp + 4, hp, 0) == B.GEAK_EALIGN
     assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], sp, hp + 4, 0) == B.GEAK_EALIGN
     assert B.geak_check_ulp_histogram(ck.plan, ok, [ok, ok], sp, hp, 0) == B.GEAK_OK

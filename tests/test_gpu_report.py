@@ -106,6 +106,6 @@ def test_report_argument_errors():
     assert B.geak_check_report(plan, t.data_ptr(), ptrs, ws.data_ptr(), res.data_ptr(), 0, recs.data_ptr(), cnt.data_ptr(), 0) == B.GEAK_EINVAL
     assert B.geak_check_report(plan, t.data_ptr(), ptrs, ws.data_ptr(), 0, 4, recs.data_ptr(), cnt.data_ptr(), 0) == B.GEAK_EINVAL
     assert B.geak_check_report(plan, t.data_ptr(), ptrs, 0, res.data_ptr(), 4, recs.data_ptr(), cnt.data_ptr(), 0) == B.GEAK_EWORKSPACE
-    assert B.geak_check_report(plan, t.data_ptr() + 4, ptrs, ws.data_ptr(), res.data_ptr(), 4, recs.data_ptr(), cnt.data_ptr(), 0) == B.GEAK_EALIGN
+    assert B.geak_check_report(plan, t.data_ptr() + 2, ptrs, ws.data_ptr(), res.data_ptr(), 4, recs.data_ptr(), cnt.data_ptr(), 0) == B.GEAK_EALIGN      # off the element grid
     torch.cuda.synchronize()
     B.geak_check_destroy(plan)
