@@ -359,6 +359,28 @@ geak_status geak_metrics_accuracy(const int32_t *compiled, const int32_t *correc
 geak_status geak_metrics_speedup(const double *ref_latencies, uint64_t ref_reps, const double *gen_latencies,
                                  uint64_t gen_reps, uint64_t num_tests, double *speedup);
 
+/* ---- latencies for the speedup ---------------------------------------------------------------------
+ * Code that passes the functionality test goes on to the performance test, which measures its latency
+ * (section 4.1); the speedup compares the median latency of the reference kernel and of the generated
+ * kernel on every unit test (section 3.3).  The paper does not say how a latency is taken.  Here every
+ * repetition starts from cold caches and is bracketed by two events on the caller's stream. */
+
+/* Enqueue, on `hip_stream`, a kernel that overwrites scratch_bytes (>= 16; a multiple of 16 is used) of
+ * `scratch_dev` (device, 16-byte aligned, the caller's): with a buffer larger than the last-level cache
+ * (512 MiB on this part: twice its 256 MB) whatever the next kernel reads comes from memory. */
+geak_status geak_timing_flush(void *scratch_dev, uint64_t scratch_bytes, void *hip_stream);
+
+/* The kernel under test, enqueued by the caller on the stream it is handed; returns 0 on success. */
+typedef int (*geak_launch_fn)(void *user, void *hip_stream);
+
+/* warmup + repetitions times: flush the caches (skipped when flush_scratch_dev is null: warm measurement),
+ * record an event, call launch(user, hip_stream), record an event, wait for it.  The elapsed times of the
+ * last `repetitions` rounds are written to latency_ms_out (host, `repetitions` doubles), in order: one
+ * row of the [test][repetition] tables geak_metrics_speedup takes.  Synchronises the stream once per round;
+ * creates and destroys two events.  GEAK_EINVAL for null launch / output, repetitions == 0, or a launch that fails. */
+geak_status geak_timing_measure(geak_launch_fn launch, void *user, uint32_t warmup, uint32_t repetitions, void *flush_scratch_dev,
+                                uint64_t flush_bytes, void *hip_stream, double *latency_ms_out);
+
 /* pass@k (section 4.2: accuracy under parallel scaling is estimated with pass@k; the paper prints no
  * formula, this is the usual unbiased estimator): the probability 1 - C(n - c, k) / C(n, k) that a
  * k-subset of n samples, c of them correct, holds a correct one.  GEAK_EINVAL unless c <= n, 1 <= k <= n. */

@@ -50,6 +50,9 @@ class PlanInfo(ctypes.Structure):
                 ("reserved", ctypes.c_uint32 * 2)]
 
 
+LAUNCH_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p)     # geak_launch_fn(user, hip_stream)
+
+
 class GeakError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -161,6 +164,10 @@ def library() -> ctypes.CDLL:
         lib.geak_metrics_speedup.argtypes = [vp, u64, vp, u64, u64, dp]
         lib.geak_metrics_pass_at_k.restype = ctypes.c_int
         lib.geak_metrics_pass_at_k.argtypes = [u64, u64, u64, dp]
+        lib.geak_timing_flush.restype = ctypes.c_int
+        lib.geak_timing_flush.argtypes = [vp, u64, vp]
+        lib.geak_timing_measure.restype = ctypes.c_int
+        lib.geak_timing_measure.argtypes = [LAUNCH_FN, vp, ctypes.c_uint32, ctypes.c_uint32, vp, u64, vp, dp]
         lib.geak_check_read_probe.restype = ctypes.c_int
         lib.geak_check_read_probe.argtypes = [vp, vp, ctypes.POINTER(vp), vp, vp]
         lib.geak_check_profile_enable.restype = ctypes.c_int
@@ -175,7 +182,7 @@ EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pi
             "geak_check_run", "geak_check_run_static", "geak_check_destroy", "geak_status_string", "geak_check_build_id", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
             "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram", "geak_check_verdicts",
-            "geak_metrics_accuracy", "geak_metrics_speedup", "geak_metrics_pass_at_k"]
+            "geak_metrics_accuracy", "geak_metrics_speedup", "geak_metrics_pass_at_k", "geak_timing_flush", "geak_timing_measure"]
 
 
 # ---- one Python function per C entry point -------------------------------------------------------
@@ -307,6 +314,27 @@ def geak_metrics_pass_at_k(n: int, c: int, k: int):
     out = ctypes.c_double()
     st = int(library().geak_metrics_pass_at_k(n, c, k, ctypes.byref(out)))
     return st, out.value
+
+
+def geak_timing_flush(scratch_ptr: int, scratch_bytes: int, stream: int) -> int:
+    """Enqueue the cache flush (an overwrite of the caller's scratch buffer) on the stream."""
+    return int(library().geak_timing_flush(scratch_ptr, scratch_bytes, stream))
+
+
+def geak_timing_measure(launch, warmup: int, repetitions: int, flush_scratch_ptr: int, flush_bytes: int, stream: int):
+    """(status, latencies in ms) of `repetitions` timed calls of launch(stream), each after a cache flush when a
+    flush buffer is given.  `launch` is a Python callable taking the stream (an integer) and enqueuing the kernel
+    under test on it."""
+    def trampoline(_user, hip_stream):
+        try:
+            launch(hip_stream or 0)
+            return 0
+        except Exception:
+            return 1
+    cb = LAUNCH_FN(trampoline)
+    out = (ctypes.c_double * max(1, repetitions))()
+    st = int(library().geak_timing_measure(cb, None, warmup, repetitions, flush_scratch_ptr or None, flush_bytes, stream or None, out))
+    return st, np.array(out[:repetitions], dtype=np.float64)
 
 
 def geak_check_read_probe(plan, ref_ptr: int, cand_ptrs: Sequence[int], workspace_ptr: int, stream: int) -> int:

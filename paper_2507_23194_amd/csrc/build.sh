@@ -19,7 +19,7 @@ flags=(--offload-arch=gfx950 -O3 -std=c++17 -fPIC -ffp-contract=off
        -Wall -Wno-unused-function -Wno-int-to-pointer-cast -I"$root/include" -I"$here"
        -DGEAK_BUILD_ID="\"$build_id\"" "$@")
 pids=()
-for src in kernels.hip ulp_kernels.hip verdict_kernel.hip static_scratch.hip metrics_host.cpp api.cpp plan_host.cpp; do
+for src in kernels.hip ulp_kernels.hip verdict_kernel.hip static_scratch.hip timing.hip metrics_host.cpp api.cpp plan_host.cpp; do
     hipcc "${flags[@]}" -c "$here/$src" -o "$obj/${src%.*}.o" &
     pids+=($!)
 done
