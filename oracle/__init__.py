@@ -16,6 +16,8 @@ from .oracle import (  # noqa: F401
     check_dense,
     check_ragged,
     check_dense_chunked,
+    check_segment_mapped,
+    gather_rows,
     combine_records,
     host_cores,
     decode_f8,

@@ -189,6 +189,35 @@ def check_dense(ref, cands, dtype: str, atol: float, rtol: float, equal_nan: boo
     return np.array(_run_pairs(jobs, threads), dtype=RECORD_DTYPE)
 
 
+def gather_rows(buf, rows: int, row_elems: int, dtype: str, byte_offset: int, pitch_bytes: int, elem_stride: int = 1) -> np.ndarray:
+    """The rows * row_elems elements of a 2-D layout, gathered into one contiguous array of raw storage
+    (row-major): element (r, c) is read at byte_offset + r * pitch_bytes + c * elem_stride * (element size).
+    pitch_bytes == 0 repeats one row for every r, elem_stride == 0 repeats one element along a row -- how a
+    reference that is broadcast against the candidates is laid out.  Plain index arithmetic, nothing else."""
+    w = ELEM_SIZE[dtype]
+    raw = _as_bytes(buf)
+    if byte_offset % w or pitch_bytes % w:
+        raise ValueError("offsets must be multiples of the element size")
+    store = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[w]
+    elems = raw[: raw.size // w * w].view(store)
+    out = np.zeros(rows * row_elems, dtype=store)
+    for r in range(rows):
+        for c in range(row_elems):
+            out[r * row_elems + c] = elems[(byte_offset + r * pitch_bytes) // w + c * elem_stride]
+    return out
+
+
+def check_segment_mapped(ref, cand, rows: int, row_elems: int, dtype: str, atol: float, rtol: float, equal_nan: bool,
+                         cand_byte_offset: int, cand_pitch_bytes: int, ref_byte_offset: int, ref_pitch_bytes: int,
+                         ref_elem_stride: int = 1):
+    """One (segment, candidate) pair whose reference has a layout of its own: the candidate's element (r, c)
+    is judged against the reference element that gather_rows finds for (r, c); indices are flat and row-major
+    over rows * row_elems.  The rule itself is check_segment's, unchanged."""
+    b = gather_rows(ref, rows, row_elems, dtype, ref_byte_offset, ref_pitch_bytes, ref_elem_stride)
+    a = gather_rows(cand, rows, row_elems, dtype, cand_byte_offset, cand_pitch_bytes, 1)
+    return check_segment(b, a, rows * row_elems, dtype, atol, rtol, equal_nan)
+
+
 def combine_records(parts, offsets):
     """Fold the records of consecutive chunks of one tensor (chunk i starts at flat index offsets[i]) into the
     record of the whole tensor.  Every field of the record is a sum, a least index or a maximum over the

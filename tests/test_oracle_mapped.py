@@ -1,0 +1,61 @@
+"""Pins of the oracle's reference-with-its-own-layout front end (oracle.gather_rows / check_segment_mapped):
+hand-derived records for the four layouts -- own pitch, one row for all rows, one element per row, one
+element for everything -- and the tie to the plain check on the same elements."""
+import numpy as np
+import pytest
+
+from helpers import record_tuple
+
+
+def test_gather_is_plain_index_arithmetic(oracle_mod):
+    buf = np.arange(40, dtype=np.float32)                     # element i holds the value i
+    g = lambda **kw: oracle_mod.gather_rows(buf, dtype="f32", **kw).view(np.float32).tolist()
+    assert g(rows=2, row_elems=3, byte_offset=8, pitch_bytes=20) == [2, 3, 4, 7, 8, 9]          # rows five elements apart
+    assert g(rows=3, row_elems=2, byte_offset=4, pitch_bytes=0) == [1, 2, 1, 2, 1, 2]           # one row for all
+    assert g(rows=2, row_elems=3, byte_offset=0, pitch_bytes=16, elem_stride=0) == [0, 0, 0, 4, 4, 4]   # one element per row
+    assert g(rows=2, row_elems=2, byte_offset=12, pitch_bytes=0, elem_stride=0) == [3, 3, 3, 3]         # one element in all
+    assert g(rows=0, row_elems=5, byte_offset=0, pitch_bytes=0) == []
+    with pytest.raises(ValueError):
+        oracle_mod.gather_rows(buf, 1, 1, "f32", 2, 0)
+
+
+def test_hand_derived_records(oracle_mod):
+    kw = dict(atol=0.25, rtol=0.0, equal_nan=False)
+    # candidates: two rows of three, the second row 16 bytes behind the first (one float of padding)
+    cand = np.array([1.0, 2.0, 3.0, 99.0, 1.0, 2.5, 3.0, 99.0], np.float32)
+    # one reference row for both rows: [1, 2, 3]; flat index 4 (row 1, column 1) is off by 0.5
+    ref_row = np.array([7.0, 1.0, 2.0, 3.0], np.float32)
+    rec = oracle_mod.check_segment_mapped(ref_row, cand, 2, 3, "f32", cand_byte_offset=0, cand_pitch_bytes=16,
+                                          ref_byte_offset=4, ref_pitch_bytes=0, **kw)
+    assert record_tuple(rec) == record_tuple(dict(zip(("pass", "mismatch_count", "first_mismatch", "max_abs_err", "max_rel_err"),
+                                                      (0, 1, 4, 0.5, 0.25))))
+    # one reference element per row: row 0 against 2, row 1 against 1 -> d = [1,0,1 | 0,1.5,2]
+    ref_col = np.array([2.0, 1.0], np.float32)
+    rec = oracle_mod.check_segment_mapped(ref_col, cand, 2, 3, "f32", cand_byte_offset=0, cand_pitch_bytes=16,
+                                          ref_byte_offset=0, ref_pitch_bytes=4, ref_elem_stride=0, **kw)
+    assert (int(rec["mismatch_count"]), int(rec["first_mismatch"]), float(rec["max_abs_err"]), float(rec["max_rel_err"])) == (4, 0, 2.0, 2.0)
+    # a reference with rows of its own pitch (three floats of padding) and an offset: equal to the candidates but one element
+    ref_own = np.array([5.0, 5.0, 1.0, 2.0, 3.0, 0.0, 0.0, 0.0, 1.0, 2.0, 3.0], np.float32)
+    rec = oracle_mod.check_segment_mapped(ref_own, cand, 2, 3, "f32", cand_byte_offset=0, cand_pitch_bytes=16,
+                                          ref_byte_offset=8, ref_pitch_bytes=24, **kw)
+    assert (int(rec["mismatch_count"]), int(rec["first_mismatch"]), float(rec["max_abs_err"])) == (1, 4, 0.5)
+    # one reference element for everything, integer dtype: exact equality
+    ci = np.array([7, 7, 8, 7], np.int32)
+    rec = oracle_mod.check_segment_mapped(np.array([0, 7], np.int32), ci, 2, 2, "i32", cand_byte_offset=0, cand_pitch_bytes=8,
+                                          ref_byte_offset=4, ref_pitch_bytes=0, ref_elem_stride=0, atol=9.0, rtol=9.0, equal_nan=False)
+    assert (int(rec["mismatch_count"]), int(rec["first_mismatch"]), float(rec["max_abs_err"]), float(rec["max_rel_err"])) == (1, 2, 1.0, 1.0 / 7.0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "u8", "f64", "i64"])
+def test_same_layout_on_both_sides_is_the_plain_check(oracle_mod, dtype):
+    rng = np.random.default_rng(3)
+    w = oracle_mod.ELEM_SIZE[dtype]
+    rows, row_elems, pitch = 7, 33, (33 + 5) * w
+    raw_ref = rng.integers(0, 256, rows * pitch + 64, dtype=np.uint8)
+    raw_cand = raw_ref.copy()
+    raw_cand[rng.integers(0, raw_cand.size, 40)] ^= 0x11
+    a = oracle_mod.gather_rows(raw_cand, rows, row_elems, dtype, 16, pitch)
+    b = oracle_mod.gather_rows(raw_ref, rows, row_elems, dtype, 16, pitch)
+    plain = oracle_mod.check_segment(b, a, rows * row_elems, dtype, 1e-3, 1e-3, True)
+    mapped = oracle_mod.check_segment_mapped(raw_ref, raw_cand, rows, row_elems, dtype, 1e-3, 1e-3, True, 16, pitch, 16, pitch)
+    assert record_tuple(plain) == record_tuple(mapped)
