@@ -145,6 +145,41 @@ geak_status geak_check_plan_pitched(geak_plan **out, const geak_segment2d *segs,
                                     uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
                                     int32_t equal_nan, int32_t device);
 
+/* A segment whose reference has a layout of its own.  The candidates store it like a geak_segment2d (rows x
+ * row_elems elements, rows pitch_bytes apart, the first at byte_offset of every candidate buffer); the reference
+ * buffer holds the value that candidate element (r, c) is compared with at
+ *     ref_byte_offset + r * ref_pitch_bytes + c * ref_elem_stride * element size.
+ * The paper's benchmark kernels include reductions, normalisations and elementwise kernels (section 4.1, Table 1)
+ * whose expected output is naturally one row, one column or one value for the whole output; the rule of section 3.1
+ * is unchanged, only where b is read differs.
+ *   ref_pitch_bytes   bytes between the reference's rows; any multiple of the element size, also one below a row's
+ *                     length (overlapping rows) and 0: one reference row for all rows
+ *   ref_elem_stride   1: the reference's row is contiguous; 0: one reference element for the whole row
+ *                     (with ref_pitch_bytes == 0: one element for the whole segment)
+ * Reference regions of different segments may overlap each other; the candidates' spans may not, as for every
+ * other plan.  Indices in the results are flat over the candidates' rows * row_elems elements.  A reference element
+ * that several candidate elements share is read once per work item that needs it: the algorithmic bytes of such a
+ * plan count the candidates' elements K times and the reference's distinct elements once.  Every work item of
+ * such a segment takes the guarded path of a segment's tail (about half the rate of contiguous segments). */
+typedef struct {
+    uint64_t byte_offset;
+    uint64_t rows;
+    uint64_t row_elems;
+    uint64_t pitch_bytes;
+    uint64_t ref_byte_offset;
+    uint64_t ref_pitch_bytes;
+    int32_t  ref_elem_stride;    /* 0 or 1 */
+    int32_t  dtype;
+} geak_segment_mapped;
+
+/* Like geak_check_plan_pitched for segments whose reference has its own layout; `tols` may be null, then
+ * atol / rtol apply to all.  GEAK_EINVAL for a stride other than 0 or 1, GEAK_EALIGN for reference offsets or
+ * pitches that are no multiple of the element size, GEAK_EBOUNDS when the reference region leaves the address
+ * space. */
+geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *segs, const geak_tolerance *tols,
+                                   uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
+                                   int32_t equal_nan, int32_t device);
+
 /* Dense convenience (section 3.1: one output tensor against its reference): a single segment at
  * offset 0 with prod(shape) elements; shape is a host array of ndim >= 0 non-negative extents
  * (ndim == 0 is a scalar).  Only the element count matters: indices are flat, row-major. */
@@ -207,7 +242,8 @@ typedef struct {
     uint64_t num_segments;
     uint64_t num_items;          /* work items (one wavefront processes one item against all candidates) */
     uint64_t num_slots;          /* partial-result slots in the workspace */
-    uint64_t algorithmic_bytes;  /* (K + 1) * sum(numel * element size): every element of every tensor once */
+    uint64_t algorithmic_bytes;  /* (K + 1) * sum(numel * element size): every element of every tensor once (a mapped
+                                    segment's reference: its distinct elements once) */
     uint32_t num_candidates;
     uint32_t grid_blocks;        /* persistent grid of the compare kernel */
     uint32_t block_threads;
@@ -239,6 +275,9 @@ typedef struct {
 #define GEAK_ITEM_ROWS 16u /* several whole rows of a pitched segment whose rows are short and start on 16-byte
                               boundaries: numel / row_elems rows, pitch_bytes apart, the first at byte_offset;
                               elem_start is the flat index of the first row's first element (ALIGNED is set) */
+#define GEAK_ITEM_REFMAP 32u /* the segment's reference has a layout of its own (geak_segment_mapped): the item's
+                                reference elements are found through the segment's mapping, not at byte_offset;
+                                never set together with FULL */
 
 geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
 
@@ -254,6 +293,11 @@ uint64_t geak_check_plan_waves(const geak_plan *plan, uint32_t *out, uint64_t ca
 
 /* Copies up to `capacity` items into `out` (host); returns the total number of items. */
 uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t capacity);
+
+/* For a plan built by geak_check_plan_mapped: copies up to `capacity` entries of the per-item table of reference
+ * offsets into `out` (host) and returns its length, the number of items; entry i is the byte offset in the
+ * reference buffer of the element that item i's first element is compared with.  Returns 0 for every other plan. */
+uint64_t geak_check_plan_ref_offsets(const geak_plan *plan, uint64_t *out, uint64_t capacity);
 
 /* ---- optional device timing of the compare kernel (a measurement aid of this library, used by its
  * benchmark; not something the paper describes) -------------------------------------------------

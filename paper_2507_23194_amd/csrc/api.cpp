@@ -17,6 +17,7 @@ struct geak_plan {
     uint32_t *wave_first_dev = nullptr;
     SegDesc *segments_dev = nullptr;
     SegTol *seg_tol_dev = nullptr;
+    uint64_t *ref_item_offset_dev = nullptr;     // only when a segment's reference has a layout of its own
     // optional timing ring
     std::vector<hipEvent_t> ev_start, ev_stop;
     uint32_t ev_next = 0, ev_used = 0;
@@ -46,6 +47,7 @@ void free_device_side(geak_plan *p)
     if (p->wave_first_dev) (void)hipFree(p->wave_first_dev);
     if (p->segments_dev) (void)hipFree(p->segments_dev);
     if (p->seg_tol_dev) (void)hipFree(p->seg_tol_dev);
+    if (p->ref_item_offset_dev) (void)hipFree(p->ref_item_offset_dev);
     for (auto e : p->ev_start) (void)hipEventDestroy(e);
     for (auto e : p->ev_stop) (void)hipEventDestroy(e);
     p->items_dev = nullptr;
@@ -53,6 +55,7 @@ void free_device_side(geak_plan *p)
     p->wave_first_dev = nullptr;
     p->segments_dev = nullptr;
     p->seg_tol_dev = nullptr;
+    p->ref_item_offset_dev = nullptr;
     p->ev_start.clear();
     p->ev_stop.clear();
 }
@@ -90,7 +93,8 @@ geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs
     for (uint64_t s = 0; s < nsegs; ++s) {                 // a contiguous segment is one row
         const geak_segment &g = segs[s];
         const uint64_t w = (g.dtype >= GEAK_F32 && g.dtype <= GEAK_F8E5M2) ? (uint64_t)elem_size(g.dtype) : 1;
-        descs[s] = SegDesc{g.byte_offset, g.numel, g.numel ? g.numel : 1, g.numel <= UINT64_MAX / w ? g.numel * w : 0, g.dtype, g.reserved};
+        descs[s] = SegDesc{g.byte_offset, g.numel, g.numel ? g.numel : 1, g.numel <= UINT64_MAX / w ? g.numel * w : 0, g.dtype, 0, 0, 0};
+        if (g.reserved != 0) return GEAK_EINVAL;
     }
     return plan_from_descs(out, descs.data(), tols, nsegs, num_candidates, equal_nan, device);
 }
@@ -112,12 +116,38 @@ geak_status geak_check_plan_pitched(geak_plan **out, const geak_segment2d *segs,
         if (g.rows && g.row_elems > GEAK_MAX_SEGMENT_NUMEL / g.rows) return GEAK_EBOUNDS;
         const uint64_t numel = g.rows * g.row_elems;
         const uint64_t w = (g.dtype >= GEAK_F32 && g.dtype <= GEAK_F8E5M2) ? (uint64_t)elem_size(g.dtype) : 1;
-        SegDesc d{g.byte_offset, numel, numel ? g.row_elems : 1, g.pitch_bytes, g.dtype, g.reserved};
+        if (g.reserved != 0) return GEAK_EINVAL;
+        SegDesc d{g.byte_offset, numel, numel ? g.row_elems : 1, g.pitch_bytes, g.dtype, 0, 0, 0};
         if (numel && g.row_elems <= UINT64_MAX / w && g.pitch_bytes == g.row_elems * w) {    // rows back to back: one row
             d.row_elems = numel;
             d.pitch_bytes = numel * w;                  // numel <= 2^40
         }
         if (!numel) d.pitch_bytes = 0;
+        descs[s] = d;
+    }
+    return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
+}
+
+geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *segs, const geak_tolerance *tols, uint64_t nsegs,
+                                   int32_t num_candidates, double atol, double rtol, int32_t equal_nan, int32_t device)
+{
+    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    std::vector<SegDesc> descs;
+    std::vector<geak_tolerance> same;
+    try {
+        descs.resize(nsegs);
+        if (!tols) same.assign(nsegs, geak_tolerance{atol, rtol});
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    for (uint64_t s = 0; s < nsegs; ++s) {
+        const geak_segment_mapped &g = segs[s];
+        if (g.ref_elem_stride != 0 && g.ref_elem_stride != 1) return GEAK_EINVAL;
+        if (g.rows && g.row_elems > GEAK_MAX_SEGMENT_NUMEL / g.rows) return GEAK_EBOUNDS;
+        const uint64_t numel = g.rows * g.row_elems;
+        // the rows stay rows, also when the candidates store them back to back: the reference's row differs
+        SegDesc d{g.byte_offset, numel, numel ? g.row_elems : 1, numel ? g.pitch_bytes : 0, g.dtype,
+                  kRefMapped | (g.ref_elem_stride == 0 ? kRefSplat : 0), g.ref_byte_offset, numel ? g.ref_pitch_bytes : 0};
         descs[s] = d;
     }
     return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
@@ -164,12 +194,16 @@ static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const g
         if (ok) ok = hipMalloc((void **)&p->segments_dev, seg_bytes) == hipSuccess;
         const size_t tol_bytes = p->host.seg_tol.size() * sizeof(SegTol);
         if (ok) ok = hipMalloc((void **)&p->seg_tol_dev, tol_bytes) == hipSuccess;
+        const size_t ref_off_bytes = p->host.ref_item_offset.size() * sizeof(uint64_t);
+        if (ok && ref_off_bytes) ok = hipMalloc((void **)&p->ref_item_offset_dev, ref_off_bytes) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_ENOMEM; }
         if (item_bytes) ok = hipMemcpy(p->items_dev, p->host.items.data(), item_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->slot_begin_dev, p->host.slot_begin.data(), slot_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->wave_first_dev, p->host.wave_first.data(), wave_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->segments_dev, p->host.segments.data(), seg_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->seg_tol_dev, p->host.seg_tol.data(), tol_bytes, hipMemcpyHostToDevice) == hipSuccess;
+        if (ok && ref_off_bytes)
+            ok = hipMemcpy(p->ref_item_offset_dev, p->host.ref_item_offset.data(), ref_off_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_EHIP; }
         // set-up is the place to look up the device's copy of the static scratch array: geak_check_run_static
         // then finds the address there (a failure here only surfaces if that entry point is used)
@@ -286,6 +320,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.reserved = 0;
         ca.wave_first = plan->wave_first_dev;
         ca.segments = plan->segments_dev;
+        ca.ref_item_offset = plan->ref_item_offset_dev;
 
         geak_plan *mp = const_cast<geak_plan *>(plan);      // timing ring only; documented as not re-entrant
         const bool timed = !mp->ev_start.empty();
@@ -312,6 +347,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ra.equal_nan = hp.equal_nan;
         ra.replicas = hp.replicas;
         ra.segments = plan->segments_dev;
+        ra.ref_item_offset = plan->ref_item_offset_dev;
         if (launch_reduce(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
     }
     return GEAK_OK;
@@ -392,6 +428,17 @@ uint64_t geak_check_plan_items(const geak_plan *plan, geak_item *out, uint64_t c
         if (n) std::memcpy(out, items.data(), n * sizeof(geak_item));
     }
     return items.size();
+}
+
+uint64_t geak_check_plan_ref_offsets(const geak_plan *plan, uint64_t *out, uint64_t capacity)
+{
+    if (!plan) return 0;
+    const auto &table = plan->host.ref_item_offset;
+    if (out) {
+        const uint64_t n = capacity < table.size() ? capacity : table.size();
+        if (n) std::memcpy(out, table.data(), n * sizeof(uint64_t));
+    }
+    return table.size();
 }
 
 geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
@@ -498,6 +545,7 @@ geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev,
             ua.nslots = nslots;
             ua.reserved = 0;
             ua.segments = plan->segments_dev;
+            ua.ref_item_offset = plan->ref_item_offset_dev;
             const uint32_t lds = kWavesPerBlock * ua.k_count * nslots * 4u;
             if (launch_ulp_histogram(ua, hp.grid_blocks, lds, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
         }

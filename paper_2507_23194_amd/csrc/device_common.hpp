@@ -137,7 +137,7 @@ __device__ __forceinline__ u32x4 load_partial_from(global_vec_ptr p, uint32_t lo
     constexpr uint32_t E = Traits<DT>::E, W = Traits<DT>::W;
     u32x4 q = {0u, 0u, 0u, 0u};
     const bool partial = valid > lo && (lo != 0 || valid < E);
-    const bool off_grid = ((uint32_t)reinterpret_cast<u64>(p) & 15u) != 0;       // the same for every lane: a property of the tensor's base
+    const bool off_grid = ((uint32_t)reinterpret_cast<u64>(p) & 15u) != 0;       // a property of the tensor's base (and, for a mapped reference, of its rows' pitch)
     if (valid > lo && !(partial && off_grid)) q = __builtin_nontemporal_load(p);
     if (__builtin_amdgcn_ballot_w64(partial && off_grid)) {
         if (partial && off_grid)
@@ -222,23 +222,78 @@ __device__ __forceinline__ uint32_t shape_vectors(const ItemShape &sh, uint32_t 
 // a shifted item: the boundary before its first element).  `first`: index within the item of the
 // slot's element 0 (meaningless when nothing is valid; for slot 0 of a shifted item it wraps below
 // zero, and first + e is right again for every valid e).
+struct SlotPlace {
+    uint32_t row, vec;       // the slot is vector `vec` of row `row` (one row unless the item is a row group)
+    uint32_t lo, valid;      // elements [lo, valid) of the vector belong to the item (valid may exceed the vector)
+    uint32_t first;          // see above
+};
 template <int DT, int KIND>
-__device__ __forceinline__ u32x4 load_slot(const unsigned char *base, uint32_t slot, uint32_t n, const ItemShape &sh, uint32_t &first)
+__device__ __forceinline__ SlotPlace slot_place(uint32_t slot, uint32_t n, const ItemShape &sh)
 {
     constexpr uint32_t E = Traits<DT>::E;
     if constexpr (KIND == kTailRows) {
         const uint32_t row = (slot * sh.inv) >> 16, vec = slot - row * sh.vpr, col = vec * E;
-        first = row * sh.row_elems + col;
-        const uint32_t valid = row < sh.rows ? sh.row_elems - col : 0u;    // col < row_elems by construction of vpr
-        return load_partial<DT>((global_vec_ptr)(base + (u64)row * sh.pitch) + vec, valid);
+        return SlotPlace{row, vec, 0u, row < sh.rows ? sh.row_elems - col : 0u, row * sh.row_elems + col};   // col < row_elems by construction of vpr
     } else if constexpr (KIND == kTailShifted) {
-        first = slot * E - sh.skip;
         const uint32_t end = sh.skip + n;                                  // in slot positions
-        return load_partial_from<DT>((global_vec_ptr)base + slot, slot == 0 ? sh.skip : 0u, slot * E < end ? end - slot * E : 0u);
+        return SlotPlace{0u, slot, slot == 0 ? sh.skip : 0u, slot * E < end ? end - slot * E : 0u, slot * E - sh.skip};
     } else {
-        first = slot * E;
-        return load_partial<DT>((global_vec_ptr)base + slot, first < n ? n - first : 0u);
+        return SlotPlace{0u, slot, 0u, slot * E < n ? n - slot * E : 0u, slot * E};
     }
+}
+template <int DT, int KIND>
+__device__ __forceinline__ u32x4 load_slot(const unsigned char *base, uint32_t slot, uint32_t n, const ItemShape &sh, uint32_t &first)
+{
+    const SlotPlace sp = slot_place<DT, KIND>(slot, n, sh);
+    first = sp.first;
+    if constexpr (KIND == kTailRows) return load_partial_from<DT>((global_vec_ptr)(base + (u64)sp.row * sh.pitch) + sp.vec, sp.lo, sp.valid);
+    else return load_partial_from<DT>((global_vec_ptr)base + sp.vec, sp.lo, sp.valid);
+}
+
+// Where the reference's elements of an item lie when the segment's reference has a layout of its own
+// (GEAK_ITEM_REFMAP): the candidates' slots keep their shape, the reference's rows have their own pitch
+// -- possibly 0: one row for all -- and either lie as the candidates' rows do or hold one element that
+// every element of the row is compared with.  All fields wave-uniform.
+struct RefPlace {
+    u64 offset;              // byte offset in the reference buffer of what the item's first element is compared with
+    u64 pitch;               // bytes between the reference's rows
+    bool splat;              // one reference element per row
+};
+template <int DT>
+__device__ __forceinline__ RefPlace ref_place(const geak_item &it, uint32_t item_index, const SegDesc *segments, const uint64_t *ref_item_offset)
+{
+    const GEAK_AS_CONSTANT unsigned long long *g = (const GEAK_AS_CONSTANT unsigned long long *)(segments + it.segment);
+    const GEAK_AS_CONSTANT unsigned long long *t = (const GEAK_AS_CONSTANT unsigned long long *)ref_item_offset;
+    // SegDesc: byte_offset, numel, row_elems, pitch_bytes, {dtype, layout}, ref_byte_offset, ref_pitch_bytes
+    return RefPlace{t[item_index], g[6], ((uint32_t)(g[4] >> 32) & (uint32_t)kRefSplat) != 0};
+}
+// Vector slot `slot` of the reference side of such an item: the elements that the same slot of a
+// candidate is compared with, zero where the candidate's slot reads as zero.
+template <int DT, int KIND>
+__device__ __forceinline__ u32x4 load_ref_slot(const unsigned char *ref_base, const RefPlace &rp, uint32_t slot, uint32_t n, const ItemShape &sh,
+                                               uint32_t &first)
+{
+    constexpr uint32_t E = Traits<DT>::E, W = Traits<DT>::W;
+    const SlotPlace sp = slot_place<DT, KIND>(slot, n, sh);
+    first = sp.first;
+    const unsigned char *row = ref_base + rp.offset + (u64)sp.row * rp.pitch;
+    if (!rp.splat) {
+        // a shifted item's slot 0 starts `skip` elements before the item: so does the reference's (those are not read
+        // unless they share an aligned 16-byte granule with the item's own)
+        if constexpr (KIND == kTailShifted) row -= (u64)sh.skip * W;
+        return load_partial_from<DT>((global_vec_ptr)row + sp.vec, sp.lo, sp.valid);
+    }
+    u32x4 q = {0u, 0u, 0u, 0u};
+    if (sp.valid > sp.lo) {
+        uint32_t w0, w1 = 0u;
+        if constexpr (W == 1) { w0 = *row; w0 |= w0 << 8; w0 |= w0 << 16; w1 = w0; }
+        else if constexpr (W == 2) { w0 = *reinterpret_cast<const uint16_t *>(row); w0 |= w0 << 16; w1 = w0; }
+        else if constexpr (W == 4) { w0 = *reinterpret_cast<const uint32_t *>(row); w1 = w0; }
+        else { w0 = reinterpret_cast<const uint32_t *>(row)[0]; w1 = reinterpret_cast<const uint32_t *>(row)[1]; }
+        q[0] = w0; q[1] = w1; q[2] = w0; q[3] = w1;
+        if (sp.lo != 0 || sp.valid < E) q = cut_vector_call(q, (int)(sp.lo * W), (int)((sp.valid < E ? sp.valid : E) * W));
+    }
+    return q;
 }
 // Vector v of this lane.
 template <int DT, int KIND>

@@ -53,27 +53,43 @@ struct SegTol {
 };
 static_assert(sizeof(SegTol) == 24, "SegTol is read as three 64-bit words");
 
-// A segment as the planner and the report kernel see it: `numel` elements in rows of `row_elems`, row r starting
-// pitch_bytes * r behind byte_offset.  A contiguous segment is one row.
+// A segment as the planner and the kernels see it: `numel` elements in rows of `row_elems`, row r starting
+// pitch_bytes * r behind byte_offset.  A contiguous segment is one row.  `layout` says where the reference's
+// elements lie: 0 at the candidates' own offsets; kRefMapped: element (r, c) at ref_byte_offset + r * ref_pitch_bytes
+// + c * element size; kRefMapped | kRefSplat: one element per row, at ref_byte_offset + r * ref_pitch_bytes.
+// Seven 64-bit words: device code reads the record word by word.
+constexpr int32_t kRefMapped = 1, kRefSplat = 2;
 struct SegDesc {
     uint64_t byte_offset;
     uint64_t numel;
     uint64_t row_elems;                  // >= 1
     uint64_t pitch_bytes;
     int32_t dtype;
-    int32_t reserved;
+    int32_t layout;
+    uint64_t ref_byte_offset;
+    uint64_t ref_pitch_bytes;
 };
+static_assert(sizeof(SegDesc) == 56, "SegDesc is read as seven 64-bit words");
 inline uint64_t seg_rows(const SegDesc &g) { return g.numel / g.row_elems; }
 // bytes from the segment's first to behind its last element
 inline uint64_t seg_span(const SegDesc &g)
 {
     return g.numel ? (seg_rows(g) - 1) * g.pitch_bytes + g.row_elems * (uint64_t)elem_size(g.dtype) : 0;
 }
+// the same for the reference's elements of a mapped segment
+inline uint64_t seg_ref_span(const SegDesc &g)
+{
+    if (!g.numel) return 0;
+    const uint64_t row = ((g.layout & kRefSplat) ? 1 : g.row_elems) * (uint64_t)elem_size(g.dtype);
+    return (seg_rows(g) - 1) * g.ref_pitch_bytes + row;
+}
 
 // Host side of a plan: everything that can be decided without a device.
 struct HostPlan {
     std::vector<SegDesc> segments;
     std::vector<geak_item> items;
+    std::vector<uint64_t> ref_item_offset; // per item, only when a segment is mapped: byte offset of the reference element
+                                           // that the item's first element is compared with
     std::vector<uint32_t> slot_begin;      // per segment, size nsegs + 1; slots of a segment are contiguous
     uint64_t algorithmic_bytes = 0;
     int num_candidates = 0;
@@ -131,7 +147,8 @@ struct CompareArgs {
     int equal_nan;
     int reserved;
     const uint32_t *wave_first;          // grid_blocks * kWavesPerBlock entries
-    const SegDesc *segments;             // device table: the row geometry of row-group items
+    const SegDesc *segments;             // device table: the row geometry of row-group items, the reference's layout
+    const uint64_t *ref_item_offset;     // device table, per item; null when no segment's reference is mapped
 };
 
 struct ReduceArgs {
@@ -147,7 +164,8 @@ struct ReduceArgs {
     const SegTol *seg_tol;               // device table, one entry per segment
     int equal_nan;
     uint32_t replicas;
-    const SegDesc *segments;             // device table: the row geometry of row-group items
+    const SegDesc *segments;             // device table: the row geometry of row-group items, the reference's layout
+    const uint64_t *ref_item_offset;     // device table, per item; null when no segment's reference is mapped
 };
 
 // Read probe: num_buffers device buffers (pointer table in the workspace), bytes_each bytes of each.
@@ -200,7 +218,8 @@ struct UlpArgs {
     uint32_t k_count;
     uint32_t nslots;
     uint32_t reserved;
-    const SegDesc *segments;             // device table: the row geometry of row-group items
+    const SegDesc *segments;             // device table: the row geometry of row-group items, the reference's layout
+    const uint64_t *ref_item_offset;     // device table, per item; null when no segment's reference is mapped
 };
 
 struct UlpReduceArgs {

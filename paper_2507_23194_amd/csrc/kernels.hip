@@ -1230,7 +1230,8 @@ struct RunArgs {
     uint32_t k0;
     uint32_t priority_phase;             // dispatch round of the block: (block * 4) / grid
     const SegTol *seg_tol;               // per-segment tolerances
-    const SegDesc *segments;             // row geometry of row-group items
+    const SegDesc *segments;             // row geometry of row-group items, layout of mapped references
+    const uint64_t *ref_item_offset;     // per item, for mapped references (null when the plan has none)
     int equal_nan;
 };
 
@@ -1357,7 +1358,9 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
 // group (short rows of a pitched segment, a pitch apart) goes the same way: only the address and the
 // number of valid elements of a lane's vector differ.  So does an item that starts off the 16-byte
 // grid (a segment's or a row's first item): it is read from the boundary before it.
-template <int DT, int KIND>
+// MAPPED: the segment's reference has a layout of its own; only where the reference's vectors are loaded
+// from differs.
+template <int DT, int KIND, bool MAPPED>
 __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_in)
 {
     typedef typename ItemOf<DT>::type Item;
@@ -1407,8 +1410,16 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     ref.attach_lds(st.tol_off, lane);
     {
         u32x4 r[kVecPerLane];
+        if constexpr (MAPPED) {
+            const RefPlace place = ref_place<DT>(it, j, uniform_ptr(in.segments), uniform_ptr(in.ref_item_offset));
+            uint32_t first;
 #pragma unroll
-        for (int v = 0; v < kVecPerLane; ++v) r[v] = load_shaped<DT, KIND>(ref_base + offset, lane, v, n, shape);
+            for (int v = 0; v < kVecPerLane; ++v)
+                r[v] = load_ref_slot<DT, KIND>(ref_base, place, (uint32_t)(v * kWaveSize + lane), n, shape, first);
+        } else {
+#pragma unroll
+            for (int v = 0; v < kVecPerLane; ++v) r[v] = load_shaped<DT, KIND>(ref_base + offset, lane, v, n, shape);
+        }
         load_batch(0);                                     // in flight together with the reference
         ref.template stage_vec<0>(r[0], tolerance);
         ref.template stage_vec<1>(r[1], tolerance);
@@ -1490,6 +1501,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.priority_phase = (blockIdx.x * 4u) / gridDim.x;
     r.seg_tol = p.seg_tol;
     r.segments = p.segments;
+    r.ref_item_offset = p.ref_item_offset;
     r.equal_nan = p.equal_nan;
 
     // the wave's list of items: its first one from the wave table, then along the next links
@@ -1502,12 +1514,16 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
         uint32_t next_j = it.next;
         if (it.flags & GEAK_ITEM_FULL) {
             for_dtype(it.dtype, [&](auto dt) { next_j = process_run<decltype(dt)::value>(r, st); });
+        } else if (it.flags & GEAK_ITEM_REFMAP) {
+            if (it.flags & GEAK_ITEM_ROWS) for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailRows, true>(r, st); });
+            else if (it.flags & GEAK_ITEM_ALIGNED) for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailPlain, true>(r, st); });
+            else for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailShifted, true>(r, st); });
         } else if (it.flags & GEAK_ITEM_ROWS) {
-            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailRows>(r, st); });
+            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailRows, false>(r, st); });
         } else if (it.flags & GEAK_ITEM_ALIGNED) {
-            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailPlain>(r, st); });
+            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailPlain, false>(r, st); });
         } else {
-            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailShifted>(r, st); });
+            for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailShifted, false>(r, st); });
         }
         j = __builtin_amdgcn_readfirstlane(next_j);
     }
@@ -1561,29 +1577,33 @@ __device__ __forceinline__ uint32_t first_bad_in_vector(const u32x4 &qa, const u
     });
     return best;
 }
-template <int DT>
-__device__ __forceinline__ uint32_t first_bad_of_thread(const unsigned char *ref, const unsigned char *cand, int tid, const geak_item &it,
-                                                        const SegDesc *segments, const SegTol &tolerance, int equal_nan)
+template <int DT, int KIND>
+__device__ __forceinline__ uint32_t first_bad_of_slot(const unsigned char *ref, const unsigned char *cand, uint32_t slot, const geak_item &it,
+                                                      uint32_t item_index, const SegDesc *segments, const uint64_t *ref_item_offset,
+                                                      const SegTol &tolerance, int equal_nan)
 {
-    u32x4 qa, qb;
+    const ItemShape shape = item_shape<DT, KIND>(it, segments);
+    const u64 offset = it.byte_offset - (u64)shape.skip * Traits<DT>::W;         // of vector slot 0
     uint32_t first;
-    if (it.flags & GEAK_ITEM_ROWS) {                       // the three branches are uniform
-        const ItemShape shape = item_shape<DT, kTailRows>(it, segments);
-        qb = load_slot<DT, kTailRows>(ref + it.byte_offset, (uint32_t)tid, it.numel, shape, first);
-        qa = load_slot<DT, kTailRows>(cand + it.byte_offset, (uint32_t)tid, it.numel, shape, first);
-    } else if (it.flags & GEAK_ITEM_ALIGNED) {
-        const ItemShape shape = item_shape<DT, kTailPlain>(it, segments);
-        qb = load_slot<DT, kTailPlain>(ref + it.byte_offset, (uint32_t)tid, it.numel, shape, first);
-        qa = load_slot<DT, kTailPlain>(cand + it.byte_offset, (uint32_t)tid, it.numel, shape, first);
-    } else {
-        const ItemShape shape = item_shape<DT, kTailShifted>(it, segments);
-        const u64 offset = it.byte_offset - (u64)shape.skip * Traits<DT>::W;
-        qb = load_slot<DT, kTailShifted>(ref + offset, (uint32_t)tid, it.numel, shape, first);
-        qa = load_slot<DT, kTailShifted>(cand + offset, (uint32_t)tid, it.numel, shape, first);
-    }
+    u32x4 qb;
+    if (it.flags & GEAK_ITEM_REFMAP) qb = load_ref_slot<DT, KIND>(ref, ref_place<DT>(it, item_index, segments, ref_item_offset), slot, it.numel, shape, first);
+    else qb = load_slot<DT, KIND>(ref + offset, slot, it.numel, shape, first);
+    const u32x4 qa = load_slot<DT, KIND>(cand + offset, slot, it.numel, shape, first);
     // positions outside the item read as 0 on both sides and are close under every rule
     const uint32_t e = first_bad_in_vector<DT>(qa, qb, (uint32_t)Traits<DT>::E, tolerance, equal_nan);
     return e == kNoItem ? kNoItem : first + e;
+}
+template <int DT>
+__device__ __forceinline__ uint32_t first_bad_of_thread(const unsigned char *ref, const unsigned char *cand, int tid, const geak_item &it,
+                                                        uint32_t item_index, const SegDesc *segments, const uint64_t *ref_item_offset,
+                                                        const SegTol &tolerance, int equal_nan)
+{
+    // the three branches are uniform
+    if (it.flags & GEAK_ITEM_ROWS)
+        return first_bad_of_slot<DT, kTailRows>(ref, cand, (uint32_t)tid, it, item_index, segments, ref_item_offset, tolerance, equal_nan);
+    if (it.flags & GEAK_ITEM_ALIGNED)
+        return first_bad_of_slot<DT, kTailPlain>(ref, cand, (uint32_t)tid, it, item_index, segments, ref_item_offset, tolerance, equal_nan);
+    return first_bad_of_slot<DT, kTailShifted>(ref, cand, (uint32_t)tid, it, item_index, segments, ref_item_offset, tolerance, equal_nan);
 }
 
 __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs p)
@@ -1638,7 +1658,7 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
         const SegTol tolerance = p.seg_tol[seg];
         uint32_t best = kNoItem;
         for_dtype(it.dtype, [&](auto dt) {
-            best = first_bad_of_thread<decltype(dt)::value>(p.ref, p.cand_table[k], tid, it, p.segments, tolerance, p.equal_nan);
+            best = first_bad_of_thread<decltype(dt)::value>(p.ref, p.cand_table[k], tid, it, first_item, p.segments, p.ref_item_offset, tolerance, p.equal_nan);
         });
         best = wave_min_u(best);
         if (lane == 0) s_best[wave] = best;
@@ -1680,12 +1700,13 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
 // item that is scanned again.
 template <int DT>
 __device__ __forceinline__ uint32_t first_bad_of_lane(const unsigned char *ref, const unsigned char *cand, int lane, const geak_item &it,
-                                                      const SegDesc *segments, const SegTol &tolerance, int equal_nan)
+                                                      uint32_t item_index, const SegDesc *segments, const uint64_t *ref_item_offset,
+                                                      const SegTol &tolerance, int equal_nan)
 {
     uint32_t best = kNoItem;
 #pragma unroll
     for (int v = kVecPerLane - 1; v >= 0; --v) {            // downwards, so that the least index is kept
-        const uint32_t b = first_bad_of_thread<DT>(ref, cand, v * kWaveSize + lane, it, segments, tolerance, equal_nan);
+        const uint32_t b = first_bad_of_thread<DT>(ref, cand, v * kWaveSize + lane, it, item_index, segments, ref_item_offset, tolerance, equal_nan);
         best = b < best ? b : best;
     }
     return best;
@@ -1738,7 +1759,7 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_wave_kernel(const Reduc
         const SegTol tolerance = p.seg_tol[seg];
         uint32_t best = kNoItem;
         for_dtype(it.dtype, [&](auto dt) {
-            best = first_bad_of_lane<decltype(dt)::value>(p.ref, p.cand_table[k], lane, it, p.segments, tolerance, p.equal_nan);
+            best = first_bad_of_lane<decltype(dt)::value>(p.ref, p.cand_table[k], lane, it, first_item, p.segments, p.ref_item_offset, tolerance, p.equal_nan);
         });
         best = wave_min_u(best);
         first = (long long)it.elem_start + (long long)best;
@@ -1789,6 +1810,9 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
     // a pitched segment: flat index i sits in row i / row_elems; in units of elements the rows are pitch_elems apart
     const bool pitched = sg.row_elems != sg.numel;
     const u64 pitch_elems = sg.pitch_bytes / (u64)Traits<DT>::W;
+    // a reference with a layout of its own: its rows are ref_pitch_elems apart and hold the row's elements or one for all
+    const bool mapped = (sg.layout & kRefMapped) != 0, splat = (sg.layout & kRefSplat) != 0;
+    const u64 ref_pitch_elems = sg.ref_pitch_bytes / (u64)Traits<DT>::W;
     u64 found = 0;
     for (u64 base = (u64)rec.first_mismatch; base < sg.numel && found < want; base += kReportThreads * kReportPerThread) {
         // all loads of the tile first, then the rule
@@ -1799,18 +1823,19 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
             const u64 i = base + (u64)u * kReportThreads + tid;
             const bool in = i < sg.numel;
             const u64 j = (pitched && in) ? (i / sg.row_elems) * pitch_elems + i % sg.row_elems : i;     // where element i is stored
+            const u64 jr = (mapped && in) ? (i / sg.row_elems) * ref_pitch_elems + (splat ? 0 : i % sg.row_elems) : j;   // and what it is compared with
             if constexpr (DT == GEAK_I32) {
                 ai[u] = in ? reinterpret_cast<const int *>(cb)[j] : 0;
-                bi[u] = in ? reinterpret_cast<const int *>(rb)[j] : 0;
+                bi[u] = in ? reinterpret_cast<const int *>(rb)[jr] : 0;
             } else if constexpr (DT == GEAK_I64 || DT == GEAK_F64) {     // binary64 travels as its bit pattern
                 ai[u] = in ? reinterpret_cast<const long long *>(cb)[j] : 0;
-                bi[u] = in ? reinterpret_cast<const long long *>(rb)[j] : 0;
+                bi[u] = in ? reinterpret_cast<const long long *>(rb)[jr] : 0;
             } else if constexpr (DT == GEAK_U8 || DT == GEAK_I8) {
                 ai[u] = in ? load_elem_int(cb, j, DT) : 0;
-                bi[u] = in ? load_elem_int(rb, j, DT) : 0;
+                bi[u] = in ? load_elem_int(rb, jr, DT) : 0;
             } else {
                 av[u] = in ? elem_f<DT>(cb, j) : 0.0f;
-                bv[u] = in ? elem_f<DT>(rb, j) : 0.0f;
+                bv[u] = in ? elem_f<DT>(rb, jr) : 0.0f;
             }
         }
         bool bad[kReportPerThread];
@@ -1885,7 +1910,7 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     if (want == 0) return;                                   // uniform
     const SegDesc sg = p.segments[seg];
     const SegTol tolerance = p.seg_tol[seg];
-    const unsigned char *rb = p.ref + sg.byte_offset, *cb = p.cand_table[k] + sg.byte_offset;
+    const unsigned char *rb = p.ref + ((sg.layout & kRefMapped) ? sg.ref_byte_offset : sg.byte_offset), *cb = p.cand_table[k] + sg.byte_offset;
     geak_mismatch *out = p.records + (u64)blockIdx.x * p.max_records;
     for_dtype(sg.dtype, [&](auto dt) {                     // uniform
         report_pair<decltype(dt)::value>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt);

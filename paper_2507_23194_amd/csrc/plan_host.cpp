@@ -27,11 +27,13 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
     }
 
     // per-segment checks
-    uint64_t total_bytes = 0;
+    uint64_t total_bytes = 0, total_ref_bytes = 0;       // the candidates' elements; the reference's distinct elements
+    bool any_mapped = false;
     for (uint64_t s = 0; s < nsegs; ++s) {
         const SegDesc &g = segs[s];
         if (g.dtype < GEAK_F32 || g.dtype > GEAK_F8E5M2) return GEAK_EDTYPE;
-        if (g.reserved != 0) return GEAK_EINVAL;
+        if ((g.layout & ~(kRefMapped | kRefSplat)) != 0 || g.layout == kRefSplat) return GEAK_EINVAL;
+        any_mapped |= g.layout != 0;
         if (g.row_elems == 0 || g.numel % g.row_elems != 0) return GEAK_EINVAL;
         // the rule of every dtype but binary64 runs in binary32: its tolerances must be finite there too
         if (g.dtype != GEAK_F64 && (std::isinf((float)tols[s].atol) || std::isinf((float)tols[s].rtol))) return GEAK_EINVAL;
@@ -50,6 +52,21 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         }
         if (total_bytes > UINT64_MAX - bytes) return GEAK_EBOUNDS;
         total_bytes += bytes;
+        // the reference's side of a mapped segment: element-aligned, inside the address space; its rows may
+        // overlap or coincide, so its distinct bytes are at most its span
+        uint64_t ref_bytes = bytes;
+        if (g.layout & kRefMapped) {
+            if (g.ref_byte_offset % w != 0 || g.ref_pitch_bytes % w != 0) return GEAK_EALIGN;
+            if (g.numel) {
+                if (mul_overflows(seg_rows(g) - 1, g.ref_pitch_bytes)) return GEAK_EBOUNDS;
+                const uint64_t ref_row_bytes = ((g.layout & kRefSplat) ? 1 : g.row_elems) * w;
+                if ((seg_rows(g) - 1) * g.ref_pitch_bytes > UINT64_MAX - ref_row_bytes) return GEAK_EBOUNDS;
+                if (g.ref_byte_offset > UINT64_MAX - seg_ref_span(g)) return GEAK_EBOUNDS;
+                const uint64_t ref_rows = g.ref_pitch_bytes ? seg_rows(g) : 1;
+                ref_bytes = std::min(seg_ref_span(g), mul_overflows(ref_rows, ref_row_bytes) ? UINT64_MAX : ref_rows * ref_row_bytes);
+            }
+        }
+        total_ref_bytes += ref_bytes;                        // <= total_bytes: no overflow
     }
     if (mul_overflows(total_bytes, (uint64_t)num_candidates + 1)) return GEAK_EBOUNDS;
 
@@ -95,12 +112,14 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         hp.segments.assign(segs, segs + nsegs);
         hp.items.clear();
         hp.items.reserve(n_items);
+        hp.ref_item_offset.clear();
+        if (any_mapped) hp.ref_item_offset.reserve(n_items);
         hp.slot_begin.assign(nsegs + 1, 0);
         hp.num_candidates = num_candidates;
         hp.seg_tol.resize(nsegs);
         for (uint64_t s = 0; s < nsegs; ++s) hp.seg_tol[s] = SegTol{(float)tols[s].atol, (float)tols[s].rtol, tols[s].atol, tols[s].rtol};
         hp.equal_nan = equal_nan;
-        hp.algorithmic_bytes = total_bytes * ((uint64_t)num_candidates + 1);
+        hp.algorithmic_bytes = total_bytes * (uint64_t)num_candidates + total_ref_bytes;
         hp.max_blocks = max_blocks;
         // Replicas of the running maxima.  Many waves raising one address serialise, so few
         // candidates (few addresses per segment) want many replicas; but every replica has to learn
@@ -131,8 +150,9 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     it.numel = (uint16_t)(rows_here * g.row_elems);                 // at most 4096 / w elements
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
-                    it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS);
+                    it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS | (g.layout ? GEAK_ITEM_REFMAP : 0));
                     hp.items.push_back(it);
+                    if (any_mapped) hp.ref_item_offset.push_back(g.layout ? g.ref_byte_offset + r * g.ref_pitch_bytes : it.byte_offset);
                 }
                 continue;
             }
@@ -151,8 +171,13 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     it.numel = (uint16_t)n;
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
-                    it.flags = (uint8_t)((full ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0));
+                    // an item whose reference lies elsewhere is never a full one: it takes the guarded path
+                    it.flags = (uint8_t)((full && !g.layout ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0) |
+                                         (g.layout ? GEAK_ITEM_REFMAP : 0));
                     hp.items.push_back(it);
+                    if (any_mapped)
+                        hp.ref_item_offset.push_back(!g.layout ? it.byte_offset
+                                                     : g.ref_byte_offset + r * g.ref_pitch_bytes + ((g.layout & kRefSplat) ? 0 : done * w));
                     done += n;
                 };
                 const uint64_t skip = (row_start % 16) / w;

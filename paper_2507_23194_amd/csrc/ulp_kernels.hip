@@ -189,6 +189,7 @@ struct UlpRunArgs {
     uint32_t num_items;
     uint32_t K, k_begin, k_count;
     const SegDesc *segments;
+    const uint64_t *ref_item_offset;     // per item, for references with a layout of their own (null when the plan has none)
 };
 
 __device__ __forceinline__ uint32_t uniform32(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -504,8 +505,18 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
         else return load_vec<DT>(base, lane, v, n, full);
     };
     u32x4 cur[kVecPerLane];
+    bool mapped = false;
+    if constexpr (TAIL) mapped = (it.flags & GEAK_ITEM_REFMAP) != 0;          // uniform; such items are never full ones
+    if (mapped) {
+        const RefPlace place = ref_place<DT>(it, j, uniform_ptr(in.segments), uniform_ptr(in.ref_item_offset));
+        uint32_t first;
 #pragma unroll
-    for (int v = 0; v < kVecPerLane; ++v) cur[v] = fetch(ref_base + it.byte_offset, v, it.numel);
+        for (int v = 0; v < kVecPerLane; ++v)
+            cur[v] = load_ref_slot<DT, KIND>(ref_base, place, (uint32_t)(v * kWaveSize + lane), it.numel, shape, first);
+    } else {
+#pragma unroll
+        for (int v = 0; v < kVecPerLane; ++v) cur[v] = fetch(ref_base + it.byte_offset, v, it.numel);
+    }
     typedef typename UlpRefOf<DT>::type Ref;
     Ref ref;
     for (;;) {
@@ -569,6 +580,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
     r.k_begin = p.k_begin;
     r.k_count = p.k_count;
     r.segments = p.segments;
+    r.ref_item_offset = p.ref_item_offset;
 
     const GEAK_AS_CONSTANT uint32_t *wave_first = (const GEAK_AS_CONSTANT uint32_t *)p.wave_first;
     uint32_t j = wave_first[blockIdx.x * kWavesPerBlock + wave];

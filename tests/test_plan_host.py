@@ -422,3 +422,72 @@ def test_item_count_in_closed_form(lib):
     assert st == B.GEAK_OK
     assert B.geak_check_plan_info(plan).num_items == (1 << 31) // 256
     B.geak_check_destroy(plan)
+
+
+def test_mapped_reference_table(lib):
+    """Segments whose reference has a layout of its own: the candidates' side is cut like a pitched segment
+    (rows never collapse, no item is a full one), every item carries the mapped flag, and the table of reference
+    offsets says for each item where the element lies that its first element is compared with."""
+    esize = {"f32": 4, "f16": 2, "u8": 1, "f64": 8}
+    #        cand off, rows, cols, pitch, ref off, ref pitch, stride
+    segs = [(0, 3, 5000, 5000 * 2 + 32, 6, 0, 1, "f16"),               # one reference row for all rows; long rows
+            (40000, 7, 100, 416, 100, 400, 1, "f32"),                  # own pitch; short rows on the grid: grouped
+            (50003, 4, 1000, 1003, 77, 3, 0, "u8"),                    # one element per row, 3 bytes apart; rows off the grid
+            (60000, 5, 9, 80, 4096, 0, 0, "f64"),                      # one element for all
+            (70000, 0, 9, 72, 0, 0, 1, "f64"),                         # empty
+            (80000, 2, 2048, 2048 * 4, 0, 2048 * 4, 1, "f32")]         # rows back to back, each two full-length items
+    st, plan = B.geak_check_plan_mapped(segs, None, 3, 1e-3, 1e-3, 0, -1)
+    assert st == B.GEAK_OK
+    items = B.geak_check_plan_items(plan)
+    ref_off = B.geak_check_plan_ref_offsets(plan)
+    info = B.geak_check_plan_info(plan)
+    assert len(ref_off) == len(items) == info.num_items
+    # candidates' elements K times, the reference's distinct elements once
+    cand_bytes = 3 * 5000 * 2 + 7 * 100 * 4 + 4 * 1000 + 5 * 9 * 8 + 2 * 2048 * 4
+    ref_bytes = 5000 * 2 + 7 * 100 * 4 + 4 * 1 + 8 + 2 * 2048 * 4
+    assert info.algorithmic_bytes == 3 * cand_bytes + ref_bytes
+    covered = {}
+    for it, ro in zip(items, ref_off):
+        s = int(it["segment"])
+        off, rows, cols, pitch, roff, rpitch, stride, dt = segs[s]
+        w = esize[dt]
+        e0, n = int(it["elem_start"]), int(it["numel"])
+        r, c = divmod(e0, cols)
+        assert it["flags"] & B.GEAK_ITEM_REFMAP and not it["flags"] & B.GEAK_ITEM_FULL
+        assert int(it["byte_offset"]) == off + r * pitch + c * w
+        assert int(ro) == roff + r * rpitch + c * w * stride
+        if it["flags"] & B.GEAK_ITEM_ROWS:
+            assert c == 0 and n % cols == 0
+        else:
+            assert c + n <= cols
+        assert e0 == covered.get(s, 0)
+        covered[s] = e0 + n
+    assert covered == {0: 15000, 1: 700, 2: 4000, 3: 45, 5: 4096}
+    assert all(i["flags"] & B.GEAK_ITEM_ROWS for i in items if i["segment"] in (1, 3))
+    assert [int(i["numel"]) for i in items if i["segment"] == 5] == [1024, 1024, 1024, 1024]    # as long as full items
+    B.geak_check_destroy(plan)
+    # plans without such a segment have no table, and no item of theirs carries the flag
+    st, plan = B.geak_check_plan_pitched([(0, 3, 5000, 5000 * 2 + 32, "f16")], None, 2, 0, 0, 0, -1)
+    assert len(B.geak_check_plan_ref_offsets(plan)) == 0
+    assert not any(i["flags"] & B.GEAK_ITEM_REFMAP for i in B.geak_check_plan_items(plan))
+    B.geak_check_destroy(plan)
+
+
+@pytest.mark.parametrize("seg,status", [
+    ((0, 4, 8, 32, 0, 0, 2, "f32"), B.GEAK_EINVAL),               # stride other than 0 / 1
+    ((0, 4, 8, 32, 0, 0, -1, "f32"), B.GEAK_EINVAL),
+    ((0, 4, 8, 32, 2, 0, 1, "f32"), B.GEAK_EALIGN),               # reference offset off the element grid
+    ((0, 4, 8, 32, 0, 6, 1, "f32"), B.GEAK_EALIGN),               # reference pitch off the element grid
+    ((0, 4, 8, 30, 0, 0, 1, "f32"), B.GEAK_EALIGN),               # the candidates' pitch
+    ((0, 4, 8, 16, 0, 0, 1, "f32"), B.GEAK_EBOUNDS),              # the candidates' rows run into each other
+    ((0, 4, 8, 32, 2 ** 64 - 8, 4, 1, "f32"), B.GEAK_EBOUNDS),    # the reference leaves the address space
+    ((0, 4, 8, 32, 0, 2 ** 63, 1, "f32"), B.GEAK_EBOUNDS),
+    ((0, 4, 8, 32, 0, 0, 1, 77), B.GEAK_EDTYPE),
+])
+def test_mapped_plan_rejects(lib, seg, status):
+    st, plan = B.geak_check_plan_mapped([seg], None, 2, 0.0, 0.0, False, -1)
+    assert st == status and plan is None
+    # overlapping reference rows and a reference region shared by two segments are fine
+    st, plan = B.geak_check_plan_mapped([(0, 4, 8, 32, 0, 4, 1, "f32"), (128, 4, 8, 32, 0, 4, 1, "f32")], None, 2, 0.0, 0.0, False, -1)
+    assert st == B.GEAK_OK
+    B.geak_check_destroy(plan)
