@@ -59,7 +59,9 @@ typedef enum {
 
 typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64 = 4,
                GEAK_U8 = 5 /* also boolean masks stored as bytes */, GEAK_I8 = 6, GEAK_F64 = 7,
-               GEAK_F8E4M3 = 8, GEAK_F8E5M2 = 9 /* the 8-bit formats of the OCP 8-bit floating point specification */ } geak_dtype;
+               GEAK_F8E4M3 = 8, GEAK_F8E5M2 = 9, /* the 8-bit formats of the OCP 8-bit floating point specification */
+               /* element formats of block-scaled segments (geak_segment_mx only) */
+               GEAK_MXFP8_E4M3 = 10, GEAK_MXFP8_E5M2 = 11, GEAK_MXINT8 = 12 } geak_dtype;
 
 #define GEAK_MAX_CANDIDATES 256
 #define GEAK_MAX_SEGMENT_NUMEL (1ull << 40)
@@ -159,8 +161,9 @@ geak_status geak_check_plan_pitched(geak_plan **out, const geak_segment2d *segs,
  * Reference regions of different segments may overlap each other; the candidates' spans may not, as for every
  * other plan.  Indices in the results are flat over the candidates' rows * row_elems elements.  A reference element
  * that several candidate elements share is read once per work item that needs it: the algorithmic bytes of such a
- * plan count the candidates' elements K times and the reference's distinct elements once.  Every work item of
- * such a segment takes the guarded path of a segment's tail (about half the rate of contiguous segments). */
+ * plan count the candidates' elements K times and the reference's distinct elements once.  With a contiguous
+ * reference row (stride 1), rows that start 16-byte aligned and are at least 4 KiB long run as full work items;
+ * with one element per row (stride 0) every item takes the guarded path of a segment's tail. */
 typedef struct {
     uint64_t byte_offset;
     uint64_t rows;
@@ -179,6 +182,37 @@ typedef struct {
 geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *segs, const geak_tolerance *tols,
                                    uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
                                    int32_t equal_nan, int32_t device);
+
+/* A block-scaled segment (OCP Microscaling Formats (MX) specification v1.0): a payload of numel one-byte
+ * elements and one shared scale byte (E8M0: 2^(X - 127), X = 0xFF is NaN) per block of 32 consecutive elements.
+ * Quantising kernels -- the benchmark kernels of section 4.1, Table 1 include an MXFP matmul and fp8 kernels --
+ * write such outputs; a candidate may choose other scales than the reference and still encode the same numbers,
+ * so the rule of section 3.1 is applied to the VALUES: element i stands for scale(block of i) * value(payload
+ * code), formed in binary32 -- exact, except that a product beyond binary32's range becomes an infinity of its
+ * sign (the specification leaves that case open) -- and the binary32 rule of the other narrow floating dtypes
+ * judges them.  A NaN scale makes its 32 elements NaN; the payload's own NaN and infinity codes stay what they
+ * are under any scale.
+ *   dtype               GEAK_MXFP8_E4M3, GEAK_MXFP8_E5M2 (payload codes as GEAK_F8E4M3 / GEAK_F8E5M2) or GEAK_MXINT8
+ *                       (two's complement, value code / 64)
+ *   byte_offset         of the payload within every packed buffer; a multiple of 16
+ *   numel               a multiple of 32 (whole blocks)
+ *   scale_byte_offset   of the numel / 32 scale bytes within the same buffer
+ * Payloads and scale regions of a plan may not overlap each other.  The algorithmic bytes count payload and
+ * scales of every tensor once.  The ulp histogram is not defined for such plans (GEAK_EDTYPE). */
+typedef struct {
+    uint64_t byte_offset;
+    uint64_t numel;
+    uint64_t scale_byte_offset;
+    int32_t  dtype;
+    int32_t  reserved;   /* must be 0 */
+} geak_segment_mx;
+
+/* Like geak_check_plan_tolerances for block-scaled segments; `tols` may be null, then atol / rtol apply to all.
+ * GEAK_EDTYPE for another dtype, GEAK_EALIGN for a payload off the 16-byte grid, GEAK_EINVAL for a ragged last
+ * block, GEAK_EBOUNDS for overlapping regions. */
+geak_status geak_check_plan_mx(geak_plan **out, const geak_segment_mx *segs, const geak_tolerance *tols,
+                               uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
+                               int32_t equal_nan, int32_t device);
 
 /* Dense convenience (section 3.1: one output tensor against its reference): a single segment at
  * offset 0 with prod(shape) elements; shape is a host array of ndim >= 0 non-negative extents
@@ -276,8 +310,7 @@ typedef struct {
                               boundaries: numel / row_elems rows, pitch_bytes apart, the first at byte_offset;
                               elem_start is the flat index of the first row's first element (ALIGNED is set) */
 #define GEAK_ITEM_REFMAP 32u /* the segment's reference has a layout of its own (geak_segment_mapped): the item's
-                                reference elements are found through the segment's mapping, not at byte_offset;
-                                never set together with FULL */
+                                reference elements are found through the segment's mapping, not at byte_offset */
 
 geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
 

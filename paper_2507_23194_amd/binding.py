@@ -22,6 +22,7 @@ GEAK_OK = 0
 GEAK_EINVAL, GEAK_EDTYPE, GEAK_EALIGN, GEAK_EBOUNDS, GEAK_ENOMEM, GEAK_EWORKSPACE, GEAK_EHIP = 1, 2, 3, 4, 5, 6, 7
 GEAK_F32, GEAK_F16, GEAK_BF16, GEAK_I32, GEAK_I64, GEAK_U8, GEAK_I8, GEAK_F64 = 0, 1, 2, 3, 4, 5, 6, 7
 GEAK_F8E4M3, GEAK_F8E5M2 = 8, 9
+GEAK_MXFP8_E4M3, GEAK_MXFP8_E5M2, GEAK_MXINT8 = 10, 11, 12        # element formats of block-scaled segments
 GEAK_MAX_CANDIDATES = 256
 GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED, GEAK_ITEM_ROWS, GEAK_ITEM_REFMAP = 1, 2, 4, 8, 16, 32
 GEAK_ULP_BINS = 66
@@ -36,6 +37,8 @@ SEGMENT2D_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_elems
                             ("dtype", "<i4"), ("reserved", "<i4")])
 SEGMENT_MAPPED_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_elems", "<u8"), ("pitch_bytes", "<u8"),
                                  ("ref_byte_offset", "<u8"), ("ref_pitch_bytes", "<u8"), ("ref_elem_stride", "<i4"), ("dtype", "<i4")])
+SEGMENT_MX_DTYPE = np.dtype([("byte_offset", "<u8"), ("numel", "<u8"), ("scale_byte_offset", "<u8"), ("dtype", "<i4"), ("reserved", "<i4")])
+MX_DTYPE_CODE = {"mxfp8e4m3": GEAK_MXFP8_E4M3, "mxfp8e5m2": GEAK_MXFP8_E5M2, "mxint8": GEAK_MXINT8}
 RESULT_DTYPE = np.dtype([("pass", "<i4"), ("reserved", "<i4"), ("mismatch_count", "<u8"),
                          ("first_mismatch", "<i8"), ("max_abs_err", "<f8"), ("max_rel_err", "<f8")])
 MISMATCH_DTYPE = np.dtype([("index", "<i8"), ("a", "<f8"), ("b", "<f8"), ("d", "<f8"), ("tol", "<f8")])
@@ -130,6 +133,9 @@ def library() -> ctypes.CDLL:
         lib.geak_check_plan_mapped.restype = ctypes.c_int
         lib.geak_check_plan_mapped.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
                                                ctypes.c_int32, ctypes.c_int32]
+        lib.geak_check_plan_mx.restype = ctypes.c_int
+        lib.geak_check_plan_mx.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                                           ctypes.c_int32, ctypes.c_int32]
         lib.geak_check_plan_dense.restype = ctypes.c_int
         lib.geak_check_plan_dense.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(ctypes.c_int64), i32, i32, dbl, dbl, i32, i32]
         lib.geak_check_workspace_bytes.restype = u64
@@ -185,7 +191,7 @@ def library() -> ctypes.CDLL:
     return _lib
 
 
-EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_mapped", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
+EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_mapped", "geak_check_plan_mx", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_run_static", "geak_check_destroy", "geak_status_string", "geak_check_build_id", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_ref_offsets", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
             "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram", "geak_check_verdicts",
@@ -247,6 +253,21 @@ def geak_check_plan_mapped(segments, tolerances, num_candidates: int, atol: floa
     st = library().geak_check_plan_mapped(ctypes.byref(out), arr.ctypes.data if len(segs) else None,
                                           None if tol is None else tol.ctypes.data,
                                           len(segs), num_candidates, float(atol), float(rtol), int(equal_nan), int(device))
+    return st, (out.value if st == GEAK_OK else None)
+
+
+def geak_check_plan_mx(segments, tolerances, num_candidates: int, atol: float, rtol: float, equal_nan, device: int):
+    """segments: iterable of (payload byte_offset, numel, scale_byte_offset, element format name or code); tolerances:
+    one (atol, rtol) pair per segment or None, then atol / rtol apply to all.  Returns (status, plan handle or None)."""
+    segs = list(segments)
+    arr = np.zeros(len(segs), dtype=SEGMENT_MX_DTYPE)
+    for i, (off, n, scale_off, dt) in enumerate(segs):
+        arr[i] = (off, n, scale_off, MX_DTYPE_CODE.get(dt, DTYPE_CODE.get(dt, dt)), 0)
+    tol = None if tolerances is None else np.ascontiguousarray(np.asarray(list(tolerances), dtype=np.float64).reshape(-1, 2))
+    out = ctypes.c_void_p(None)
+    st = library().geak_check_plan_mx(ctypes.byref(out), arr.ctypes.data if len(segs) else None,
+                                      None if tol is None else tol.ctypes.data,
+                                      len(segs), num_candidates, float(atol), float(rtol), int(equal_nan), int(device))
     return st, (out.value if st == GEAK_OK else None)
 
 
@@ -424,10 +445,12 @@ def geak_check_profile_read(plan, capacity: int) -> np.ndarray:
 class Checker:
     """A plan plus its workspace and results buffers (torch tensors on the plan's device)."""
 
-    def __init__(self, segments=None, *, dense=None, pitched=None, mapped=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
+    def __init__(self, segments=None, *, dense=None, pitched=None, mapped=None, mx=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
                  equal_nan: bool, device: int = 0, tolerances=None):
         import torch
-        if mapped is not None:
+        if mx is not None:
+            st, plan = geak_check_plan_mx(mx, tolerances, num_candidates, atol, rtol, equal_nan, device)
+        elif mapped is not None:
             st, plan = geak_check_plan_mapped(mapped, tolerances, num_candidates, atol, rtol, equal_nan, device)
         elif pitched is not None:
             st, plan = geak_check_plan_pitched(pitched, tolerances, num_candidates, atol, rtol, equal_nan, device)

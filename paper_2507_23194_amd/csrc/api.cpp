@@ -128,6 +128,28 @@ geak_status geak_check_plan_pitched(geak_plan **out, const geak_segment2d *segs,
     return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
 }
 
+geak_status geak_check_plan_mx(geak_plan **out, const geak_segment_mx *segs, const geak_tolerance *tols, uint64_t nsegs,
+                               int32_t num_candidates, double atol, double rtol, int32_t equal_nan, int32_t device)
+{
+    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    std::vector<SegDesc> descs;
+    std::vector<geak_tolerance> same;
+    try {
+        descs.resize(nsegs);
+        if (!tols) same.assign(nsegs, geak_tolerance{atol, rtol});
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    for (uint64_t s = 0; s < nsegs; ++s) {
+        const geak_segment_mx &g = segs[s];
+        if (g.reserved != 0) return GEAK_EINVAL;
+        if (!is_mx_dtype(g.dtype)) return GEAK_EDTYPE;
+        // one contiguous row of one-byte elements; the scales' offset travels in the record's reference field
+        descs[s] = SegDesc{g.byte_offset, g.numel, g.numel ? g.numel : 1, g.numel, g.dtype, kMxScaled, g.scale_byte_offset, 0};
+    }
+    return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
+}
+
 geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *segs, const geak_tolerance *tols, uint64_t nsegs,
                                    int32_t num_candidates, double atol, double rtol, int32_t equal_nan, int32_t device)
 {
@@ -507,6 +529,8 @@ geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev,
     if (!plan || !cand_dev || !hist_dev || !ulp_workspace_dev) return GEAK_EINVAL;
     if (plan->device < 0) return GEAK_EINVAL;
     const HostPlan &hp = plan->host;
+    for (const SegDesc &sg : hp.segments)
+        if (sg.layout == kMxScaled) return GEAK_EDTYPE;          // a distance in code steps says nothing across different scales
     const int K = hp.num_candidates;
     const bool reads_data = !hp.items.empty();
     if (const geak_status st = check_tensor_pointers(hp, ref_dev, cand_dev)) return st;

@@ -70,6 +70,12 @@ template <> struct Traits<GEAK_I8>   { static constexpr int E = 16, W = 1; };
 template <> struct Traits<GEAK_F64>  { static constexpr int E = 2, W = 8; };
 template <> struct Traits<GEAK_F8E4M3> { static constexpr int E = 16, W = 1; };
 template <> struct Traits<GEAK_F8E5M2> { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_MXFP8_E4M3> { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_MXFP8_E5M2> { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_MXINT8>     { static constexpr int E = 16, W = 1; };
+// Block-scaled element formats: a 16-byte vector holds half a block of 32 elements, so one scale byte
+// belongs to every vector.
+template <int DT> constexpr bool kScaled = (DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP8_E5M2 || DT == GEAK_MXINT8);
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ double bits_d(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(double, (u64)lo | ((u64)hi << 32)); }
@@ -309,7 +315,8 @@ __device__ __forceinline__ u32x4 load_shaped(const unsigned char *base, int lane
 template <int DT, int BYTE>
 __device__ __forceinline__ float f8_to_f32(uint32_t word)
 {
-    if constexpr (DT == GEAK_F8E4M3) return __builtin_amdgcn_cvt_f32_fp8((int)word, BYTE);
+    if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3) return __builtin_amdgcn_cvt_f32_fp8((int)word, BYTE);
+    else if constexpr (DT == GEAK_MXINT8) return (float)((int)(word << (24 - 8 * BYTE)) >> 24);     // the code as an integer; the scale carries the 1/64
     else return __builtin_amdgcn_cvt_f32_bf8((int)word, BYTE);
 }
 
@@ -319,10 +326,40 @@ template <int DT, bool HI>
 __device__ __forceinline__ F32Pair f8_pair_to_f32(uint32_t word)
 {
     typedef float f32x2 __attribute__((ext_vector_type(2)));
-    f32x2 v;
-    if constexpr (DT == GEAK_F8E4M3) v = __builtin_amdgcn_cvt_pk_f32_fp8((int)word, HI);
-    else v = __builtin_amdgcn_cvt_pk_f32_bf8((int)word, HI);
-    return F32Pair{v[0], v[1]};
+    if constexpr (DT == GEAK_MXINT8) {
+        return F32Pair{f8_to_f32<DT, HI ? 2 : 0>(word), f8_to_f32<DT, HI ? 3 : 1>(word)};
+    } else {
+        f32x2 v;
+        if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3) v = __builtin_amdgcn_cvt_pk_f32_fp8((int)word, HI);
+        else v = __builtin_amdgcn_cvt_pk_f32_bf8((int)word, HI);
+        return F32Pair{v[0], v[1]};
+    }
+}
+
+// The factor a scale byte X stands for, as binary32: 2^(X - 127), NaN for X = 0xFF.  2^-127 is a binary32
+// subnormal.  For the integer element format the element's own 2^-6 is folded in (2^(X - 133), subnormal for
+// X <= 6); multiplying the code's integer value by it is exact.
+template <int DT>
+__device__ __forceinline__ float scale_of_byte(uint32_t x)
+{
+    constexpr int kFold = DT == GEAK_MXINT8 ? 6 : 0;
+    const int e = (int)x - 127 - kFold;                                       // -133 .. 127
+    const uint32_t bits = e >= -126 ? (uint32_t)(e + 127) << 23 : 1u << (e + 149);
+    return bits_f(x == 0xFFu ? 0x7FC00000u : bits);
+}
+// The scale byte of vector slot `slot` (= v * 64 + lane) of an item of n elements whose first block's scale
+// lies at `scales`: sixteen elements per vector, two vectors per block.  A slot behind the item's end has no
+// elements (they read as 0 in every tensor) and gets the byte of 2^0.
+__device__ __forceinline__ uint32_t load_scale_byte(const unsigned char *scales, uint32_t slot, uint32_t n)
+{
+    return slot * 16u < n ? (uint32_t)((const GEAK_AS_GLOBAL unsigned char *)scales)[slot >> 1] : 127u;
+}
+// Byte offset in every packed buffer of the scale of an item's first block: the segment's scales begin at the
+// record's sixth word, one byte per block of 32 elements (items of such segments start on block boundaries).
+__device__ __forceinline__ u64 item_scale_offset(const geak_item &it, const SegDesc *segments)
+{
+    const GEAK_AS_CONSTANT unsigned long long *g = (const GEAK_AS_CONSTANT unsigned long long *)(segments + it.segment);
+    return g[5] + (it.elem_start >> 5);
 }
 
 // One integer element straight from memory, widened exactly to 64 bits.
@@ -362,6 +399,17 @@ __device__ __forceinline__ void for_dtype(int dtype, F &&f)
     case GEAK_F64:    f(Index<GEAK_F64>{}); break;
     case GEAK_F8E4M3: f(Index<GEAK_F8E4M3>{}); break;
     default:          f(Index<GEAK_F8E5M2>{}); break;
+    }
+}
+
+// The same for the element formats of block-scaled segments.
+template <typename F>
+__device__ __forceinline__ void for_scaled_dtype(int dtype, F &&f)
+{
+    switch (dtype) {
+    case GEAK_MXFP8_E4M3: f(Index<GEAK_MXFP8_E4M3>{}); break;
+    case GEAK_MXFP8_E5M2: f(Index<GEAK_MXFP8_E5M2>{}); break;
+    default:              f(Index<GEAK_MXINT8>{}); break;
     }
 }
 

@@ -21,6 +21,7 @@ inline int elem_size(int dtype)
     case GEAK_F16: case GEAK_BF16: return 2;
     case GEAK_I64: case GEAK_F64: return 8;
     case GEAK_U8: case GEAK_I8: case GEAK_F8E4M3: case GEAK_F8E5M2: return 1;
+    case GEAK_MXFP8_E4M3: case GEAK_MXFP8_E5M2: case GEAK_MXINT8: return 1;       // the payload's elements
     default: return 4;
     }
 }
@@ -57,8 +58,12 @@ static_assert(sizeof(SegTol) == 24, "SegTol is read as three 64-bit words");
 // pitch_bytes * r behind byte_offset.  A contiguous segment is one row.  `layout` says where the reference's
 // elements lie: 0 at the candidates' own offsets; kRefMapped: element (r, c) at ref_byte_offset + r * ref_pitch_bytes
 // + c * element size; kRefMapped | kRefSplat: one element per row, at ref_byte_offset + r * ref_pitch_bytes.
+// kMxScaled: a block-scaled segment (dtype one of the GEAK_MX* codes, contiguous, whole blocks of kMxBlock
+// elements); ref_byte_offset then holds the offset of its scale bytes, one per block, in every packed buffer.
 // Seven 64-bit words: device code reads the record word by word.
-constexpr int32_t kRefMapped = 1, kRefSplat = 2;
+constexpr int32_t kRefMapped = 1, kRefSplat = 2, kMxScaled = 4;
+constexpr uint64_t kMxBlock = 32;
+inline bool is_mx_dtype(int dtype) { return dtype >= GEAK_MXFP8_E4M3 && dtype <= GEAK_MXINT8; }
 struct SegDesc {
     uint64_t byte_offset;
     uint64_t numel;

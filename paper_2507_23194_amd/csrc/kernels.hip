@@ -906,11 +906,21 @@ struct DoubleItem {
 // path is bound by arithmetic.  Elements the bare inequality cannot judge (b NaN, b +-Inf, tolerance
 // overflowed) are only marked when the slice is staged; vectors that hold one are counted again
 // with the full rule.
+// The block-scaled element formats (payload byte plus the scale of the vector's block) take the same path:
+// wherever an element is widened it is multiplied by its vector's scale, `sa` for the candidate's and `sb` for
+// the reference's vector (both 1 and not applied for the plain 8-bit formats).
 template <int DT>
-__device__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel, MaxPair *rec_in);
+__device__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel, MaxPair *rec_in,
+                                     const float sa, const float sb);
 template <int DT>
 __device__ int recount_vector_f8(const u32x4 q, const u32x4 b, const uint32_t marked_in, const float atol_in, const float rtol_in,
-                                 const int equal_nan_in);
+                                 const int equal_nan_in, const float sa, const float sb);
+template <int DT, int BYTE>
+__device__ __forceinline__ float f8_value(uint32_t word, [[maybe_unused]] float scale)
+{
+    if constexpr (kScaled<DT>) return f8_to_f32<DT, BYTE>(word) * scale;
+    else return f8_to_f32<DT, BYTE>(word);
+}
 
 template <int DT>
 struct Fp8Item {
@@ -921,6 +931,22 @@ struct Fp8Item {
     uint32_t bref[kVecPerLane * 4];
     float atol_f, rtol_f;           // wave-uniform
     u64 poisoned_slots;             // wave-uniform: bit i set if any lane's element i is poisoned
+    // block-scaled formats only: the scales of the reference's four vectors, and of the candidate's vector that is
+    // compared next (set by the caller before each vector)
+    float sb[kVecPerLane];
+    float sa;
+    template <int V> __device__ __forceinline__ void stage_scale(uint32_t byte) { sb[V] = scale_of_byte<DT>(byte); }
+    __device__ __forceinline__ void candidate_scale(uint32_t byte) { sa = scale_of_byte<DT>(byte); }
+    template <int V> __device__ __forceinline__ float ref_scale() const
+    {
+        if constexpr (kScaled<DT>) return sb[V];
+        else return 1.0f;
+    }
+    __device__ __forceinline__ float cand_scale() const
+    {
+        if constexpr (kScaled<DT>) return sa;
+        else return 1.0f;
+    }
     // The wave's LDS region holds the tolerances of half the slice (vectors 0 and 1: 32 per lane);
     // those of the other half are computed again for every candidate.
     static constexpr int kStoredVectors = 2;
@@ -939,7 +965,7 @@ struct Fp8Item {
         float tv[E];
         static_for<E>([&](auto idx) {
             constexpr int e = decltype(idx)::value;
-            const float x = value<e>(q);
+            const float x = f8_value<DT, e & 3>(q[e >> 2], ref_scale<V>());
             const float prod = rtol_f * __builtin_fabsf(x);
             const float t = atol_f + prod;
             tv[e] = t;
@@ -968,8 +994,12 @@ struct Fp8Item {
         if constexpr (V < kStoredVectors) tol.template get<V>(tv);
         static_for<E / 2>([&](auto idx) {
             constexpr int p = decltype(idx)::value;
-            const F32Pair x = f8_pair_to_f32<DT, (p & 1) != 0>(words[p >> 1]);
-            const F32Pair a = f8_pair_to_f32<DT, (p & 1) != 0>(q[p >> 1]);
+            F32Pair x = f8_pair_to_f32<DT, (p & 1) != 0>(words[p >> 1]);
+            F32Pair a = f8_pair_to_f32<DT, (p & 1) != 0>(q[p >> 1]);
+            if constexpr (kScaled<DT>) {
+                x.lo *= sb[V]; x.hi *= sb[V];
+                a.lo *= sa; a.hi *= sa;
+            }
             const float d0 = a.lo - x.lo, d1 = a.hi - x.hi;
             float t0, t1;
             if constexpr (V < kStoredVectors) {
@@ -1003,7 +1033,7 @@ struct Fp8Item {
         u32x4 b;
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
-        return recount_vector_f8<DT>(q, b, (uint32_t)(poisoned_slots >> (V * E)) & 0xFFFFu, atol_f, rtol_f, equal_nan);
+        return recount_vector_f8<DT>(q, b, (uint32_t)(poisoned_slots >> (V * E)) & 0xFFFFu, atol_f, rtol_f, equal_nan, cand_scale(), ref_scale<V>());
     }
     template <int V>
     __device__ __forceinline__ uint32_t false_suspects_call(const u32x4 &q, int equal_nan) const
@@ -1017,7 +1047,7 @@ struct Fp8Item {
         u32x4 b;
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
-        const FloatPair out = raise_vector_f8<DT>(q, b, max_abs, max_rel, rec);
+        const FloatPair out = raise_vector_f8<DT>(q, b, max_abs, max_rel, rec, cand_scale(), ref_scale<V>());
         max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
         max_rel = uniform_of(out.rel);
     }
@@ -1030,7 +1060,7 @@ struct Fp8Item {
 
 template <int DT>
 __device__ __noinline__ int recount_vector_f8(const u32x4 q, const u32x4 b, const uint32_t marked_in, const float atol_in,
-                                              const float rtol_in, const int equal_nan_in)
+                                              const float rtol_in, const int equal_nan_in, const float sa, const float sb)
 {
     const uint32_t marked = uniform32(marked_in);
     const float atol_f = bits_f(uniform32(f_bits(atol_in))), rtol_f = bits_f(uniform32(f_bits(rtol_in)));
@@ -1039,7 +1069,7 @@ __device__ __noinline__ int recount_vector_f8(const u32x4 q, const u32x4 b, cons
     static_for<16>([&](auto idx) {
         constexpr int e = decltype(idx)::value;
         if (marked & (1u << e)) {
-            const float x = f8_to_f32<DT, e & 3>(b[e >> 2]), a = f8_to_f32<DT, e & 3>(q[e >> 2]);
+            const float x = f8_value<DT, e & 3>(b[e >> 2], sb), a = f8_value<DT, e & 3>(q[e >> 2], sa);
             const float prod = rtol_f * __builtin_fabsf(x);
             const float t = atol_f + prod;
             const float d = __builtin_fabsf(a - x);
@@ -1052,14 +1082,14 @@ __device__ __noinline__ int recount_vector_f8(const u32x4 q, const u32x4 b, cons
 
 template <int DT>
 __device__ __noinline__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, const float max_abs, const float max_rel,
-                                                  MaxPair *rec_in)
+                                                  MaxPair *rec_in, const float sa, const float sb)
 {
     MaxPair *rec = uniform_ptr(rec_in);
     float dm = max_abs, rm = max_rel;
     static_for<16>([&](auto idx) {
         constexpr int e = decltype(idx)::value;
-        const float x = f8_to_f32<DT, e & 3>(b[e >> 2]);
-        const float d = __builtin_fabsf(f8_to_f32<DT, e & 3>(q[e >> 2]) - x);
+        const float x = f8_value<DT, e & 3>(b[e >> 2], sb);
+        const float d = __builtin_fabsf(f8_value<DT, e & 3>(q[e >> 2], sa) - x);
         const float babs = __builtin_fabsf(x);
         dm = (d > dm) ? d : dm;                                          // false for NaN: skipped
         const bool hit = (rm < kInfF) && may_raise_rel(rm, babs, d);     // implies d > 0
@@ -1189,6 +1219,9 @@ template <> struct ItemOf<GEAK_I64> { typedef Int64Item type; };
 template <> struct ItemOf<GEAK_F64> { typedef DoubleItem type; };
 template <> struct ItemOf<GEAK_F8E4M3> { typedef Fp8Item<GEAK_F8E4M3> type; };
 template <> struct ItemOf<GEAK_F8E5M2> { typedef Fp8Item<GEAK_F8E5M2> type; };
+template <> struct ItemOf<GEAK_MXFP8_E4M3> { typedef Fp8Item<GEAK_MXFP8_E4M3> type; };
+template <> struct ItemOf<GEAK_MXFP8_E5M2> { typedef Fp8Item<GEAK_MXFP8_E5M2> type; };
+template <> struct ItemOf<GEAK_MXINT8> { typedef Fp8Item<GEAK_MXINT8> type; };
 
 __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 {
@@ -1243,12 +1276,15 @@ template <int DT, int V, bool OUTLINE = false, typename Item>
 __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsigned char *next, bool has_next,
                                             uint32_t next_n, const bool next_full, typename Item::Hint &max_abs,
                                             typename Item::Hint &max_rel, int equal_nan, MaxPair *rec, int lane,
-                                            uint32_t &bad)
+                                            uint32_t &bad, [[maybe_unused]] uint32_t *scale_byte = nullptr,
+                                            [[maybe_unused]] const unsigned char *next_scales = nullptr)
 {
     u64 trip_abs = 0, trip_rel = 0;
+    // block-scaled formats: the vector's scale byte travels beside it and is refilled with it
+    if constexpr (kScaled<DT>) ref.candidate_scale(*scale_byte);
     ref.template compare_vec<V, !OUTLINE>(slot, max_abs, max_rel, bad, trip_abs, trip_rel, equal_nan);
     if constexpr (OUTLINE && (DT == GEAK_F32 || DT == GEAK_F16 || DT == GEAK_BF16 || DT == GEAK_F64 || DT == GEAK_F8E4M3 ||
-                              DT == GEAK_F8E5M2)) {      // only floating items poison slots
+                              DT == GEAK_F8E5M2 || kScaled<DT>)) {      // only floating items poison slots
         constexpr u64 kVecMask = ((Traits<DT>::E == 16) ? 0xFFFFull : ((1ull << Traits<DT>::E) - 1ull)) << (V * Traits<DT>::E);
         if (ref.poisoned_slots & kVecMask) bad -= ref.template false_suspects_call<V>(slot, equal_nan);
     }
@@ -1257,7 +1293,10 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
         if constexpr (OUTLINE || Item::kRaiseOutOfLine) ref.template raise_call<V>(slot, max_abs, max_rel, rec);
         else ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
     }
-    if (has_next) slot = load_vec<DT>(next, lane, V, next_n, next_full);
+    if (has_next) {
+        slot = load_vec<DT>(next, lane, V, next_n, next_full);
+        if constexpr (kScaled<DT>) *scale_byte = load_scale_byte(next_scales, (uint32_t)(V * kWaveSize + lane), next_n);
+    }
 }
 
 // Each dtype's routine is a real function, so that its register allocation stands alone instead of
@@ -1290,9 +1329,24 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     ref.attach_lds(st.tol_off, lane);
     u32x4 cur[kVecPerLane];
     constexpr bool full = true;
+    // Where an item's reference slice lies: at the item's own offset, or -- a segment whose reference has a layout
+    // of its own, contiguous along the row -- at the offset the plan's table gives (any alignment: whole vectors).
+    const GEAK_AS_CONSTANT unsigned long long *ref_table = (const GEAK_AS_CONSTANT unsigned long long *)uniform_ptr(in.ref_item_offset);
+    const auto ref_offset_of = [&](const geak_item &item, uint32_t index) -> u64 {
+        return (item.flags & GEAK_ITEM_REFMAP) ? ref_table[index] : item.byte_offset;
+    };
+    u64 next_ref_off = 0;
 #pragma unroll
     for (int v = 0; v < kVecPerLane; ++v)                  // the only loads of the run that nothing hides
-        cur[v] = load_vec<DT>(ref_base + it.byte_offset, lane, v, it.numel, full);
+        cur[v] = load_vec<DT>(ref_base + ref_offset_of(it, j), lane, v, it.numel, full);
+    // block-scaled formats: the scale byte of each vector's block, loaded and refilled beside the vector
+    [[maybe_unused]] uint32_t sc[kVecPerLane] = {0u, 0u, 0u, 0u};
+    [[maybe_unused]] u64 scale_off = 0, next_scale_off = 0;
+    if constexpr (kScaled<DT>) {
+        scale_off = item_scale_offset(it, uniform_ptr(in.segments));
+#pragma unroll
+        for (int v = 0; v < kVecPerLane; ++v) sc[v] = load_scale_byte(ref_base + scale_off, (uint32_t)(v * kWaveSize + lane), it.numel);
+    }
 
     for (;;) {
         // look ahead: does the wave's next item continue the run?
@@ -1303,8 +1357,12 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
             nx = load_work_item(items, jn);
             more = (nx.flags & GEAK_ITEM_FULL) && nx.dtype == DT;
         }
+        if (more) next_ref_off = ref_offset_of(nx, jn);
         const SegTol cur_tol = tolerance;
         if (more) tolerance = load_tol(seg_tol, nx.segment);          // the next item's, a whole item ahead of its use
+        if constexpr (kScaled<DT>) {
+            if (more) next_scale_off = item_scale_offset(nx, uniform_ptr(in.segments));
+        }
         if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
         MaxPair *recs = board + (u64)it.segment * K * replicas + replica;     // candidate k: recs[k * replicas]
 
@@ -1312,6 +1370,14 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
         uint32_t k = k0;
         {
             const unsigned char *first = table_entry(cand, k) + it.byte_offset;
+            if constexpr (kScaled<DT>) {
+                const unsigned char *first_scales = table_entry(cand, k) + scale_off;
+                static_for<kVecPerLane>([&](auto idx) {
+                    constexpr int v = decltype(idx)::value;
+                    ref.template stage_scale<v>(sc[v]);
+                    sc[v] = load_scale_byte(first_scales, (uint32_t)(v * kWaveSize + lane), it.numel);
+                });
+            }
             ref.template stage_vec<0>(cur[0], cur_tol); cur[0] = load_vec<DT>(first, lane, 0, it.numel, full);
             ref.template stage_vec<1>(cur[1], cur_tol); cur[1] = load_vec<DT>(first, lane, 1, it.numel, full);
             ref.template stage_vec<2>(cur[2], cur_tol); cur[2] = load_vec<DT>(first, lane, 2, it.numel, full);
@@ -1324,8 +1390,10 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
             const uint32_t kn = (k + 1 == K) ? 0 : k + 1;
             const bool last = step + 1 == K;
             const bool has_next = !last || more;
-            const unsigned char *next = last ? ref_base + nx.byte_offset : table_entry(cand, kn) + it.byte_offset;
+            const unsigned char *next = last ? ref_base + next_ref_off : table_entry(cand, kn) + it.byte_offset;
             const uint32_t next_n = last ? nx.numel : it.numel;
+            [[maybe_unused]] const unsigned char *next_scales = nullptr;
+            if constexpr (kScaled<DT>) next_scales = last ? ref_base + next_scale_off : table_entry(cand, kn) + scale_off;
 
             Hint max_abs = Item::hint_from_bits(abs_bits);      // exact: floating maxima are published from binary32
             Hint max_rel = Item::hint_from_bits(rel_bits);
@@ -1334,10 +1402,10 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
                 rel_bits = load_bits(&recs[kn * replicas].rel);
             }
             uint32_t bad = 0;
-            stream_step<DT, 0>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
-            stream_step<DT, 1>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
-            stream_step<DT, 2>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
-            stream_step<DT, 3>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
+            stream_step<DT, 0>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[0], next_scales);
+            stream_step<DT, 1>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[1], next_scales);
+            stream_step<DT, 2>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[2], next_scales);
+            stream_step<DT, 3>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[3], next_scales);
             note_mismatches(st, k, bad, j, lane);
             k = kn;
         }
@@ -1345,6 +1413,7 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
         if (!more) break;
         it = nx;
         j = jn;
+        scale_off = next_scale_off;
     }
     return it.next;
 }
@@ -1386,23 +1455,31 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     const uint32_t per_batch = vectors == 1 ? 4 : (vectors == 2 ? 2 : 1);                       // candidates per batch
     MaxPair *recs = board + (u64)it.segment * K * replicas + replica;         // candidate k: recs[k * replicas]
 
-    // loads of one batch: candidate kb + c occupies registers [c * (4 / per_batch), ...)
+    // loads of one batch: candidate kb + c occupies registers [c * (4 / per_batch), ...); for the block-scaled
+    // formats the scale byte of each register's vector is loaded beside it (such items are plain tails)
     u32x4 cur[kVecPerLane];
+    [[maybe_unused]] uint32_t cs[kVecPerLane] = {127u, 127u, 127u, 127u};
+    [[maybe_unused]] u64 scale_off = 0;
+    if constexpr (kScaled<DT>) scale_off = item_scale_offset(it, uniform_ptr(in.segments));
+    const auto load_register = [&](int reg, uint32_t k, int v) {
+        cur[reg] = load_shaped<DT, KIND>(table_entry(cand, k) + offset, lane, v, n, shape);
+        if constexpr (kScaled<DT>) cs[reg] = load_scale_byte(table_entry(cand, k) + scale_off, (uint32_t)(v * kWaveSize + lane), n);
+    };
     const auto load_batch = [&](uint32_t kb) {
         if (per_batch == 4) {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (kb + c < K) cur[c] = load_shaped<DT, KIND>(table_entry(cand, kb + c) + offset, lane, 0, n, shape);
+                if (kb + c < K) load_register(c, kb + c, 0);
         } else if (per_batch == 2) {
 #pragma unroll
             for (int c = 0; c < 2; ++c)
                 if (kb + c < K) {
-                    cur[2 * c + 0] = load_shaped<DT, KIND>(table_entry(cand, kb + c) + offset, lane, 0, n, shape);
-                    cur[2 * c + 1] = load_shaped<DT, KIND>(table_entry(cand, kb + c) + offset, lane, 1, n, shape);
+                    load_register(2 * c + 0, kb + c, 0);
+                    load_register(2 * c + 1, kb + c, 1);
                 }
         } else {
 #pragma unroll
-            for (int v = 0; v < kVecPerLane; ++v) cur[v] = load_shaped<DT, KIND>(table_entry(cand, kb) + offset, lane, v, n, shape);
+            for (int v = 0; v < kVecPerLane; ++v) load_register(v, kb, v);
         }
     };
 
@@ -1420,7 +1497,15 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
 #pragma unroll
             for (int v = 0; v < kVecPerLane; ++v) r[v] = load_shaped<DT, KIND>(ref_base + offset, lane, v, n, shape);
         }
+        [[maybe_unused]] uint32_t rs[kVecPerLane];
+        if constexpr (kScaled<DT>) {
+#pragma unroll
+            for (int v = 0; v < kVecPerLane; ++v) rs[v] = load_scale_byte(ref_base + scale_off, (uint32_t)(v * kWaveSize + lane), n);
+        }
         load_batch(0);                                     // in flight together with the reference
+        if constexpr (kScaled<DT>) {
+            static_for<kVecPerLane>([&](auto idx) { ref.template stage_scale<decltype(idx)::value>(rs[decltype(idx)::value]); });
+        }
         ref.template stage_vec<0>(r[0], tolerance);
         ref.template stage_vec<1>(r[1], tolerance);
         ref.template stage_vec<2>(r[2], tolerance);
@@ -1429,10 +1514,10 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
     if (it.flags & GEAK_ITEM_FIRST) begin_run(st, K, lane);
 
     // compare register vector `q` as vector V of candidate k, accumulating into bad
-    const auto one = [&](auto vtag, const u32x4 &q, uint32_t k, Hint &max_abs, Hint &max_rel, uint32_t &bad) {
+    const auto one = [&](auto vtag, int reg, uint32_t k, Hint &max_abs, Hint &max_rel, uint32_t &bad) {
         constexpr int V = decltype(vtag)::value;
-        u32x4 slot = q;
-        stream_step<DT, V, true>(ref, slot, nullptr, false, 0, false, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad);
+        u32x4 slot = cur[reg];
+        stream_step<DT, V, true>(ref, slot, nullptr, false, 0, false, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &cs[reg]);
     };
     const auto hints = [&](uint32_t k, Hint &max_abs, Hint &max_rel) {
         max_abs = Item::hint_from_bits(load_bits(&recs[k * replicas].abs));
@@ -1448,7 +1533,7 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
                     Hint ma, mr;
                     hints(kb + c, ma, mr);
                     uint32_t bad = 0;
-                    one(Index<0>{}, cur[c], kb + c, ma, mr, bad);
+                    one(Index<0>{}, c, kb + c, ma, mr, bad);
                     note_mismatches(st, kb + c, bad, j, lane);
                 }
         } else if (per_batch == 2) {
@@ -1458,18 +1543,18 @@ __device__ __noinline__ void process_tail(const RunArgs in, const WaveState st_i
                     Hint ma, mr;
                     hints(kb + c, ma, mr);
                     uint32_t bad = 0;
-                    one(Index<0>{}, cur[2 * c + 0], kb + c, ma, mr, bad);
-                    one(Index<1>{}, cur[2 * c + 1], kb + c, ma, mr, bad);
+                    one(Index<0>{}, 2 * c + 0, kb + c, ma, mr, bad);
+                    one(Index<1>{}, 2 * c + 1, kb + c, ma, mr, bad);
                     note_mismatches(st, kb + c, bad, j, lane);
                 }
         } else {
             Hint ma, mr;
             hints(kb, ma, mr);
             uint32_t bad = 0;
-            one(Index<0>{}, cur[0], kb, ma, mr, bad);
-            one(Index<1>{}, cur[1], kb, ma, mr, bad);
-            one(Index<2>{}, cur[2], kb, ma, mr, bad);
-            one(Index<3>{}, cur[3], kb, ma, mr, bad);
+            one(Index<0>{}, 0, kb, ma, mr, bad);
+            one(Index<1>{}, 1, kb, ma, mr, bad);
+            one(Index<2>{}, 2, kb, ma, mr, bad);
+            one(Index<3>{}, 3, kb, ma, mr, bad);
             note_mismatches(st, kb, bad, j, lane);
         }
     }
@@ -1512,7 +1597,10 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
         // a run of full items, or one item of another shape: handled, state bookkeeping included, by the dtype's routine
         r.first_item = j;
         uint32_t next_j = it.next;
-        if (it.flags & GEAK_ITEM_FULL) {
+        if (it.dtype >= GEAK_MXFP8_E4M3) {                  // block-scaled: contiguous, on the grid, so full items and plain tails only
+            if (it.flags & GEAK_ITEM_FULL) for_scaled_dtype(it.dtype, [&](auto dt) { next_j = process_run<decltype(dt)::value>(r, st); });
+            else for_scaled_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailPlain, false>(r, st); });
+        } else if (it.flags & GEAK_ITEM_FULL) {
             for_dtype(it.dtype, [&](auto dt) { next_j = process_run<decltype(dt)::value>(r, st); });
         } else if (it.flags & GEAK_ITEM_REFMAP) {
             if (it.flags & GEAK_ITEM_ROWS) for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailRows, true>(r, st); });
@@ -1558,7 +1646,7 @@ constexpr uint64_t kReduceWavePairs = 1024;        // from this many (segment, c
 // first mismatch, one vector per thread.  `valid` elements of the vector lie inside the item.
 template <int DT>
 __device__ __forceinline__ uint32_t first_bad_in_vector(const u32x4 &qa, const u32x4 &qb, uint32_t valid, const SegTol &tolerance,
-                                                        int equal_nan)
+                                                        int equal_nan, [[maybe_unused]] float sa = 1.0f, [[maybe_unused]] float sb = 1.0f)
 {
     constexpr int E = Traits<DT>::E;
     uint32_t best = kNoItem;
@@ -1570,8 +1658,8 @@ __device__ __forceinline__ uint32_t first_bad_in_vector(const u32x4 &qa, const u
         else if constexpr (DT == GEAK_U8 || DT == GEAK_I8) close = ((qa[e >> 2] ^ qb[e >> 2]) >> (8 * (e & 3)) & 0xFFu) == 0;
         else if constexpr (DT == GEAK_F64)
             close = close_exact_d(bits_d(qa[2 * e], qa[2 * e + 1]), bits_d(qb[2 * e], qb[2 * e + 1]), tolerance.atol, tolerance.rtol, equal_nan);
-        else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2)
-            close = close_exact(f8_to_f32<DT, e & 3>(qa[e >> 2]), f8_to_f32<DT, e & 3>(qb[e >> 2]), tolerance.atol_f, tolerance.rtol_f, equal_nan);
+        else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2 || kScaled<DT>)
+            close = close_exact(f8_value<DT, e & 3>(qa[e >> 2], sa), f8_value<DT, e & 3>(qb[e >> 2], sb), tolerance.atol_f, tolerance.rtol_f, equal_nan);
         else close = close_exact(decode<DT>(qa, e), decode<DT>(qb, e), tolerance.atol_f, tolerance.rtol_f, equal_nan);
         if ((uint32_t)e < valid && !close) best = (uint32_t)e;
     });
@@ -1590,7 +1678,15 @@ __device__ __forceinline__ uint32_t first_bad_of_slot(const unsigned char *ref, 
     else qb = load_slot<DT, KIND>(ref + offset, slot, it.numel, shape, first);
     const u32x4 qa = load_slot<DT, KIND>(cand + offset, slot, it.numel, shape, first);
     // positions outside the item read as 0 on both sides and are close under every rule
-    const uint32_t e = first_bad_in_vector<DT>(qa, qb, (uint32_t)Traits<DT>::E, tolerance, equal_nan);
+    uint32_t e;
+    if constexpr (kScaled<DT>) {
+        const u64 scale_off = item_scale_offset(it, segments);
+        e = first_bad_in_vector<DT>(qa, qb, (uint32_t)Traits<DT>::E, tolerance, equal_nan,
+                                    scale_of_byte<DT>(load_scale_byte(cand + scale_off, slot, it.numel)),
+                                    scale_of_byte<DT>(load_scale_byte(ref + scale_off, slot, it.numel)));
+    } else {
+        e = first_bad_in_vector<DT>(qa, qb, (uint32_t)Traits<DT>::E, tolerance, equal_nan);
+    }
     return e == kNoItem ? kNoItem : first + e;
 }
 template <int DT>
@@ -1657,9 +1753,11 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(const ReduceArgs
         const geak_item it = p.items[first_item];
         const SegTol tolerance = p.seg_tol[seg];
         uint32_t best = kNoItem;
-        for_dtype(it.dtype, [&](auto dt) {
+        const auto rescan = [&](auto dt) {
             best = first_bad_of_thread<decltype(dt)::value>(p.ref, p.cand_table[k], tid, it, first_item, p.segments, p.ref_item_offset, tolerance, p.equal_nan);
-        });
+        };
+        if (it.dtype >= GEAK_MXFP8_E4M3) for_scaled_dtype(it.dtype, rescan);
+        else for_dtype(it.dtype, rescan);
         best = wave_min_u(best);
         if (lane == 0) s_best[wave] = best;
         __syncthreads();
@@ -1758,9 +1856,11 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_wave_kernel(const Reduc
         const geak_item it = p.items[first_item];
         const SegTol tolerance = p.seg_tol[seg];
         uint32_t best = kNoItem;
-        for_dtype(it.dtype, [&](auto dt) {
+        const auto rescan = [&](auto dt) {
             best = first_bad_of_lane<decltype(dt)::value>(p.ref, p.cand_table[k], lane, it, first_item, p.segments, p.ref_item_offset, tolerance, p.equal_nan);
-        });
+        };
+        if (it.dtype >= GEAK_MXFP8_E4M3) for_scaled_dtype(it.dtype, rescan);
+        else for_dtype(it.dtype, rescan);
         best = wave_min_u(best);
         first = (long long)it.elem_start + (long long)best;
     }
@@ -1794,7 +1894,7 @@ template <int DT>
 __device__ __forceinline__ float elem_f(const unsigned char *base, u64 idx)
 {
     if constexpr (DT == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
-    else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2) return f8_to_f32<DT, 0>(base[idx]);
+    else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2 || kScaled<DT>) return f8_to_f32<DT, 0>(base[idx]);     // block-scaled: the bare code's value
     else if constexpr (DT == GEAK_F16) return (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t *>(base)[idx]);
     else return bits_f((uint32_t)reinterpret_cast<const uint16_t *>(base)[idx] << 16);
 }
@@ -1813,6 +1913,8 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
     // a reference with a layout of its own: its rows are ref_pitch_elems apart and hold the row's elements or one for all
     const bool mapped = (sg.layout & kRefMapped) != 0, splat = (sg.layout & kRefSplat) != 0;
     const u64 ref_pitch_elems = sg.ref_pitch_bytes / (u64)Traits<DT>::W;
+    // a block-scaled segment: its scale bytes, one per 32 elements, in the same buffers
+    [[maybe_unused]] const unsigned char *rscales = p.ref + sg.ref_byte_offset, *cscales = p.cand_table[blockIdx.x % p.num_candidates] + sg.ref_byte_offset;
     u64 found = 0;
     for (u64 base = (u64)rec.first_mismatch; base < sg.numel && found < want; base += kReportThreads * kReportPerThread) {
         // all loads of the tile first, then the rule
@@ -1833,6 +1935,9 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
             } else if constexpr (DT == GEAK_U8 || DT == GEAK_I8) {
                 ai[u] = in ? load_elem_int(cb, j, DT) : 0;
                 bi[u] = in ? load_elem_int(rb, jr, DT) : 0;
+            } else if constexpr (kScaled<DT>) {             // the value: the code's times the scale of its block
+                av[u] = in ? elem_f<DT>(cb, j) * scale_of_byte<DT>(cscales[j >> 5]) : 0.0f;
+                bv[u] = in ? elem_f<DT>(rb, j) * scale_of_byte<DT>(rscales[j >> 5]) : 0.0f;
             } else {
                 av[u] = in ? elem_f<DT>(cb, j) : 0.0f;
                 bv[u] = in ? elem_f<DT>(rb, jr) : 0.0f;
@@ -1912,9 +2017,9 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     const SegTol tolerance = p.seg_tol[seg];
     const unsigned char *rb = p.ref + ((sg.layout & kRefMapped) ? sg.ref_byte_offset : sg.byte_offset), *cb = p.cand_table[k] + sg.byte_offset;
     geak_mismatch *out = p.records + (u64)blockIdx.x * p.max_records;
-    for_dtype(sg.dtype, [&](auto dt) {                     // uniform
-        report_pair<decltype(dt)::value>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt);
-    });
+    const auto report = [&](auto dt) { report_pair<decltype(dt)::value>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); };
+    if (sg.dtype >= GEAK_MXFP8_E4M3) for_scaled_dtype(sg.dtype, report);          // uniform
+    else for_dtype(sg.dtype, report);
 }
 
 // ---- read probe: what a kernel that only reads the same bytes achieves ---------------------------

@@ -31,9 +31,16 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
     bool any_mapped = false;
     for (uint64_t s = 0; s < nsegs; ++s) {
         const SegDesc &g = segs[s];
-        if (g.dtype < GEAK_F32 || g.dtype > GEAK_F8E5M2) return GEAK_EDTYPE;
-        if ((g.layout & ~(kRefMapped | kRefSplat)) != 0 || g.layout == kRefSplat) return GEAK_EINVAL;
-        any_mapped |= g.layout != 0;
+        if (g.dtype < GEAK_F32 || g.dtype > GEAK_MXINT8) return GEAK_EDTYPE;
+        if (is_mx_dtype(g.dtype) != (g.layout == kMxScaled)) return GEAK_EDTYPE;     // block-scaled element formats belong to block-scaled segments only
+        if (g.layout != kMxScaled && ((g.layout & ~(kRefMapped | kRefSplat)) != 0 || g.layout == kRefSplat)) return GEAK_EINVAL;
+        any_mapped |= (g.layout & kRefMapped) != 0;
+        if (g.layout == kMxScaled) {
+            // payload on the 16-byte grid (a vector then lies inside one block), whole blocks, one contiguous row
+            if (g.byte_offset % 16 != 0) return GEAK_EALIGN;
+            if (g.numel % kMxBlock != 0 || (g.numel && g.row_elems != g.numel)) return GEAK_EINVAL;
+            if (g.ref_byte_offset > UINT64_MAX - g.numel / kMxBlock) return GEAK_EBOUNDS;
+        }
         if (g.row_elems == 0 || g.numel % g.row_elems != 0) return GEAK_EINVAL;
         // the rule of every dtype but binary64 runs in binary32: its tolerances must be finite there too
         if (g.dtype != GEAK_F64 && (std::isinf((float)tols[s].atol) || std::isinf((float)tols[s].rtol))) return GEAK_EINVAL;
@@ -50,11 +57,13 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
             if ((seg_rows(g) - 1) * g.pitch_bytes > UINT64_MAX - row_bytes) return GEAK_EBOUNDS;
             if (g.byte_offset > UINT64_MAX - seg_span(g)) return GEAK_EBOUNDS;
         }
-        if (total_bytes > UINT64_MAX - bytes) return GEAK_EBOUNDS;
-        total_bytes += bytes;
+        // what one tensor holds of the segment: its elements, and for a block-scaled one its scale bytes (numel <= 2^40)
+        const uint64_t tensor_bytes = bytes + (g.layout == kMxScaled ? g.numel / kMxBlock : 0);
+        if (total_bytes > UINT64_MAX - tensor_bytes) return GEAK_EBOUNDS;
+        total_bytes += tensor_bytes;
         // the reference's side of a mapped segment: element-aligned, inside the address space; its rows may
         // overlap or coincide, so its distinct bytes are at most its span
-        uint64_t ref_bytes = bytes;
+        uint64_t ref_bytes = tensor_bytes;
         if (g.layout & kRefMapped) {
             if (g.ref_byte_offset % w != 0 || g.ref_pitch_bytes % w != 0) return GEAK_EALIGN;
             if (g.numel) {
@@ -75,8 +84,11 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         std::vector<std::pair<uint64_t, uint64_t>> spans;
         spans.reserve(nsegs);
         for (uint64_t s = 0; s < nsegs; ++s)
-            if (segs[s].numel)
+            if (segs[s].numel) {
                 spans.emplace_back(segs[s].byte_offset, segs[s].byte_offset + seg_span(segs[s]));   // pitched segments: first to last byte
+                if (segs[s].layout == kMxScaled)                                                     // and a block-scaled segment's scales
+                    spans.emplace_back(segs[s].ref_byte_offset, segs[s].ref_byte_offset + segs[s].numel / kMxBlock);
+            }
         std::sort(spans.begin(), spans.end());
         for (size_t i = 1; i < spans.size(); ++i)
             if (spans[i].first < spans[i - 1].second) return GEAK_EBOUNDS;
@@ -134,6 +146,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         for (uint64_t s = 0; s < nsegs; ++s) {
             const SegDesc &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
+            const bool mapped = (g.layout & kRefMapped) != 0;
             if (!g.numel) continue;
             // Short rows of a pitched segment that all start on 16-byte boundaries: whole rows are
             // grouped into one item, as many as its 256 vector slots hold (a row takes
@@ -150,9 +163,9 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     it.numel = (uint16_t)(rows_here * g.row_elems);                 // at most 4096 / w elements
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
-                    it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS | (g.layout ? GEAK_ITEM_REFMAP : 0));
+                    it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS | (mapped ? GEAK_ITEM_REFMAP : 0));
                     hp.items.push_back(it);
-                    if (any_mapped) hp.ref_item_offset.push_back(g.layout ? g.ref_byte_offset + r * g.ref_pitch_bytes : it.byte_offset);
+                    if (any_mapped) hp.ref_item_offset.push_back(mapped ? g.ref_byte_offset + r * g.ref_pitch_bytes : it.byte_offset);
                 }
                 continue;
             }
@@ -171,12 +184,12 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     it.numel = (uint16_t)n;
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
-                    // an item whose reference lies elsewhere is never a full one: it takes the guarded path
-                    it.flags = (uint8_t)((full && !g.layout ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0) |
-                                         (g.layout ? GEAK_ITEM_REFMAP : 0));
+                    // an item whose reference is one element for the whole row is never a full one: it takes the guarded path
+                    it.flags = (uint8_t)((full && !(g.layout & kRefSplat) ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0) |
+                                         (mapped ? GEAK_ITEM_REFMAP : 0));
                     hp.items.push_back(it);
                     if (any_mapped)
-                        hp.ref_item_offset.push_back(!g.layout ? it.byte_offset
+                        hp.ref_item_offset.push_back(!mapped ? it.byte_offset
                                                      : g.ref_byte_offset + r * g.ref_pitch_bytes + ((g.layout & kRefSplat) ? 0 : done * w));
                     done += n;
                 };
@@ -205,7 +218,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
         const uint64_t slices = (uint64_t)num_candidates + 1;
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
-            const uint64_t per_slice = (it.dtype == GEAK_F8E4M3 || it.dtype == GEAK_F8E5M2) ? 40 : (it.dtype == GEAK_F32 || it.dtype == GEAK_F64) ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
+            const uint64_t per_slice = is_mx_dtype(it.dtype) ? 48 : (it.dtype == GEAK_F8E4M3 || it.dtype == GEAK_F8E5M2) ? 40 : (it.dtype == GEAK_F32 || it.dtype == GEAK_F64) ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
             if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 140;       // tails, row groups, starts off the grid
             return per_slice * slices + (starts_run ? 100 : 0);
         };

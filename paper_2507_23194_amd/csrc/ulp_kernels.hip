@@ -505,8 +505,14 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
         else return load_vec<DT>(base, lane, v, n, full);
     };
     u32x4 cur[kVecPerLane];
+    // a reference with a layout of its own: a full item's slice lies at the offset the plan's table gives (whole
+    // vectors at any alignment); the other shapes go through the guarded loads of the mapped reference
+    const GEAK_AS_CONSTANT unsigned long long *ref_table = (const GEAK_AS_CONSTANT unsigned long long *)uniform_ptr(in.ref_item_offset);
+    const auto ref_offset_of = [&](const geak_item &item, uint32_t index) -> u64 {
+        return (item.flags & GEAK_ITEM_REFMAP) ? ref_table[index] : item.byte_offset;
+    };
     bool mapped = false;
-    if constexpr (TAIL) mapped = (it.flags & GEAK_ITEM_REFMAP) != 0;          // uniform; such items are never full ones
+    if constexpr (TAIL) mapped = (it.flags & GEAK_ITEM_REFMAP) != 0;          // uniform
     if (mapped) {
         const RefPlace place = ref_place<DT>(it, j, uniform_ptr(in.segments), uniform_ptr(in.ref_item_offset));
         uint32_t first;
@@ -515,7 +521,7 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
             cur[v] = load_ref_slot<DT, KIND>(ref_base, place, (uint32_t)(v * kWaveSize + lane), it.numel, shape, first);
     } else {
 #pragma unroll
-        for (int v = 0; v < kVecPerLane; ++v) cur[v] = fetch(ref_base + it.byte_offset, v, it.numel);
+        for (int v = 0; v < kVecPerLane; ++v) cur[v] = fetch(ref_base + ref_offset_of(it, j), v, it.numel);
     }
     typedef typename UlpRefOf<DT>::type Ref;
     Ref ref;
@@ -540,7 +546,7 @@ __device__ __noinline__ uint32_t ulp_run(const UlpRunArgs in, const UlpState st_
             // Every step refills its registers, so that the number of loads in flight is known at each wait:
             // behind the run's very last slice the same slice is simply read again (from the cache).
             const unsigned char *next = !last ? table_entry(cand, k_begin + kk + 1) + it.byte_offset
-                                      : more ? ref_base + nx.byte_offset
+                                      : more ? ref_base + ref_offset_of(nx, jn)
                                              : table_entry(cand, k_begin + kk) + it.byte_offset;
             GEAK_AS_LDS uint32_t *row = ulp_row(st, kk);
             typename Ref::Counts c = Ref::zero();

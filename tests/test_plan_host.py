@@ -426,8 +426,8 @@ def test_item_count_in_closed_form(lib):
 
 def test_mapped_reference_table(lib):
     """Segments whose reference has a layout of its own: the candidates' side is cut like a pitched segment
-    (rows never collapse, no item is a full one), every item carries the mapped flag, and the table of reference
-    offsets says for each item where the element lies that its first element is compared with."""
+    (rows never collapse), every item carries the mapped flag, and the table of reference offsets says for each
+    item where the element lies that its first element is compared with."""
     esize = {"f32": 4, "f16": 2, "u8": 1, "f64": 8}
     #        cand off, rows, cols, pitch, ref off, ref pitch, stride
     segs = [(0, 3, 5000, 5000 * 2 + 32, 6, 0, 1, "f16"),               # one reference row for all rows; long rows
@@ -453,7 +453,9 @@ def test_mapped_reference_table(lib):
         w = esize[dt]
         e0, n = int(it["elem_start"]), int(it["numel"])
         r, c = divmod(e0, cols)
-        assert it["flags"] & B.GEAK_ITEM_REFMAP and not it["flags"] & B.GEAK_ITEM_FULL
+        assert it["flags"] & B.GEAK_ITEM_REFMAP
+        # full items where the candidates' side allows it and the reference is contiguous along the row
+        assert bool(it["flags"] & B.GEAK_ITEM_FULL) == (n * w == 4096 and int(it["byte_offset"]) % 16 == 0 and stride == 1)
         assert int(it["byte_offset"]) == off + r * pitch + c * w
         assert int(ro) == roff + r * rpitch + c * w * stride
         if it["flags"] & B.GEAK_ITEM_ROWS:
@@ -464,7 +466,7 @@ def test_mapped_reference_table(lib):
         covered[s] = e0 + n
     assert covered == {0: 15000, 1: 700, 2: 4000, 3: 45, 5: 4096}
     assert all(i["flags"] & B.GEAK_ITEM_ROWS for i in items if i["segment"] in (1, 3))
-    assert [int(i["numel"]) for i in items if i["segment"] == 5] == [1024, 1024, 1024, 1024]    # as long as full items
+    assert [int(i["numel"]) for i in items if i["segment"] == 5] == [1024, 1024, 1024, 1024]
     B.geak_check_destroy(plan)
     # plans without such a segment have no table, and no item of theirs carries the flag
     st, plan = B.geak_check_plan_pitched([(0, 3, 5000, 5000 * 2 + 32, "f16")], None, 2, 0, 0, 0, -1)
@@ -491,3 +493,40 @@ def test_mapped_plan_rejects(lib, seg, status):
     st, plan = B.geak_check_plan_mapped([(0, 4, 8, 32, 0, 4, 1, "f32"), (128, 4, 8, 32, 0, 4, 1, "f32")], None, 2, 0.0, 0.0, False, -1)
     assert st == B.GEAK_OK
     B.geak_check_destroy(plan)
+
+
+def test_block_scaled_plan_table(lib):
+    """Block-scaled segments: contiguous one-byte payloads on the 16-byte grid, cut into full items and plain
+    tails on block boundaries; payload and scale bytes of every tensor count once."""
+    segs = [(0, 4096 * 3 + 64, 20000, "mxfp8e4m3"), (32768, 32, 40000, "mxint8"), (40960, 0, 50000, "mxfp8e5m2")]
+    st, plan = B.geak_check_plan_mx(segs, None, 3, 1e-3, 1e-3, 0, -1)
+    assert st == B.GEAK_OK
+    items = B.geak_check_plan_items(plan)
+    info = B.geak_check_plan_info(plan)
+    assert info.algorithmic_bytes == 4 * ((4096 * 3 + 64) * 33 // 32 + 33)
+    assert [(int(i["byte_offset"]), int(i["elem_start"]), int(i["numel"]), int(i["dtype"])) for i in items] == \
+        [(0, 0, 4096, 10), (4096, 4096, 4096, 10), (8192, 8192, 4096, 10), (12288, 12288, 64, 10), (32768, 0, 32, 12)]
+    assert [bool(i["flags"] & B.GEAK_ITEM_FULL) for i in items] == [True, True, True, False, False]
+    assert all(i["flags"] & B.GEAK_ITEM_ALIGNED and not i["flags"] & (B.GEAK_ITEM_REFMAP | B.GEAK_ITEM_ROWS) for i in items)
+    assert all(int(i["elem_start"]) % 32 == 0 for i in items)           # an item starts with a block
+    assert len(B.geak_check_plan_ref_offsets(plan)) == 0
+    B.geak_check_destroy(plan)
+
+
+@pytest.mark.parametrize("seg,status", [
+    ((8, 64, 100, "mxfp8e4m3"), B.GEAK_EALIGN),                # payload off the 16-byte grid
+    ((0, 40, 100, "mxfp8e4m3"), B.GEAK_EINVAL),                # ragged last block
+    ((0, 64, 63, "mxfp8e4m3"), B.GEAK_EBOUNDS),                # scales inside the payload
+    ((0, 64, 100, "f8e4m3"), B.GEAK_EDTYPE),                   # not a block-scaled element format
+    ((0, 64, 100, 13), B.GEAK_EDTYPE),
+    ((0, 64, 2 ** 64 - 1, "mxint8"), B.GEAK_EBOUNDS),
+])
+def test_block_scaled_plan_rejects(lib, seg, status):
+    st, plan = B.geak_check_plan_mx([seg], None, 2, 0.0, 0.0, False, -1)
+    assert st == status and plan is None
+    for code in (B.GEAK_MXFP8_E4M3, B.GEAK_MXFP8_E5M2, B.GEAK_MXINT8):    # these codes are not for the other plan calls
+        assert B.geak_check_plan([(0, 64, code)], 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
+        assert B.geak_check_plan_pitched([(0, 2, 32, 32, code)], None, 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
+        assert B.geak_check_plan_mapped([(0, 2, 32, 32, 0, 0, 1, code)], None, 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
+    st, plan = B.geak_check_plan_mx([(0, 64, 1000, "mxint8"), (64, 64, 1001, "mxint8")], None, 1, 0.0, 0.0, False, -1)
+    assert st == B.GEAK_EBOUNDS                                            # scale regions collide
