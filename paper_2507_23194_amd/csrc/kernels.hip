@@ -279,7 +279,10 @@ __device__ uint32_t false_suspects_vector(const u32x4 q, const RefVec<DT> ref, c
                                           const int equal_nan_in);
 template <int DT>
 __device__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> ref, const float max_abs, const float max_rel, MaxPair *rec_in);
-__device__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel, MaxPair *rec_in);
+template <int DT>
+__device__ __noinline__ DoublePair raise_vector_integer(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel, MaxPair *rec_in);
+template <typename T, typename Pair>
+__device__ __forceinline__ Pair close_raise(T dm, T rm, const T max_abs, const T max_rel, MaxPair *rec);
 
 // Tolerances of the staged reference slice, one per element the lane holds.  The 32-bit dtypes
 // keep them in registers.  The 16-bit dtypes hold twice the elements per slice; their 32
@@ -572,16 +575,7 @@ __device__ __noinline__ FloatPair raise_vector(const u32x4 q, const RefVec<DT> r
             rm = (hit && r > rm) ? r : rm;
         }
     }
-    dm = wave_max_f(dm);
-    rm = wave_max_f(rm);
-    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
-        if (dm > max_abs) publish_max(&rec->abs, (double)dm);
-        if (rm > max_rel) publish_max(&rec->rel, (double)rm);
-    }
-    FloatPair out;
-    out.abs = dm;
-    out.rel = rm;
-    return out;
+    return close_raise<float, FloatPair>(dm, rm, max_abs, max_rel, rec);
 }
 
 // ---- int32: same interface, exact equality ---------------------------------------------------------
@@ -621,7 +615,7 @@ struct IntItem {
         u32x4 b;
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
-        const DoublePair out = raise_vector_int(q, b, max_abs, max_rel, rec);
+        const DoublePair out = raise_vector_integer<GEAK_I32>(q, b, max_abs, max_rel, rec);
         max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
         max_rel = uniform_of(out.rel);
     }
@@ -654,66 +648,67 @@ struct IntItem {
     }
 };
 
-__device__ __noinline__ DoublePair raise_vector_int(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
-                                                    MaxPair *rec_in)
+// Element e of a 16-byte vector of an integer dtype, widened exactly.
+template <int DT>
+__device__ __forceinline__ long long integer_element(const u32x4 &v, int e)
 {
-    MaxPair *rec = uniform_ptr(rec_in);
-    double dm = max_abs, rm = max_rel;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const long long a = (int)q[e], x = (int)b[e];
-        const long long diff = a - x;
-        const double d = (double)(diff < 0 ? -diff : diff);          // exact
-        const double babs = (double)(x < 0 ? -x : x);
-        dm = (d > dm) ? d : dm;
-        if (d > 0.0 && (rm < (double)kInfF) && d > rm * (1.0 - 0x1p-30) * babs) {
-            const double r = d / babs;                               // binary64, correctly rounded; d/0 = +Inf
-            rm = (r > rm) ? r : rm;
-        }
+    if constexpr (DT == GEAK_I32) return (int)v[e];
+    else if constexpr (DT == GEAK_I64) return (long long)((u64)v[2 * e] | ((u64)v[2 * e + 1] << 32));
+    else {
+        const uint32_t byte = (v[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+        return DT == GEAK_I8 ? (long long)(signed char)byte : (long long)byte;
     }
-    dm = wave_max_d(dm);
-    rm = wave_max_d(rm);
+}
+// What closes every raise routine: the wave's maxima, published by one lane where they grew, returned in every lane.
+template <typename T, typename Pair>
+__device__ __forceinline__ Pair close_raise(T dm, T rm, const T max_abs, const T max_rel, MaxPair *rec)
+{
+    if constexpr (sizeof(T) == 8) { dm = wave_max_d(dm); rm = wave_max_d(rm); }
+    else { dm = wave_max_f(dm); rm = wave_max_f(rm); }
     if ((threadIdx.x & (kWaveSize - 1)) == 0) {
-        if (dm > max_abs) publish_max(&rec->abs, dm);
-        if (rm > max_rel) publish_max(&rec->rel, rm);
+        if (dm > max_abs) publish_max(&rec->abs, (double)dm);
+        if (rm > max_rel) publish_max(&rec->rel, (double)rm);
     }
-    DoublePair out;
+    Pair out;
     out.abs = dm;
     out.rel = rm;
     return out;
 }
-
-// ---- int64: two elements per 16-byte vector, exact equality ------------------------------------------
-__device__ __noinline__ DoublePair raise_vector_int64(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
-                                                      MaxPair *rec_in)
+// The rare path of the integer dtypes (int32, int64, uint8, int8), one routine: the exact |a - b| and
+// |a - b| / |b| of a vector in which some lane saw a difference, folded into the running maxima.
+template <int DT>
+__device__ __noinline__ DoublePair raise_vector_integer(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
+                                                        MaxPair *rec_in)
 {
     MaxPair *rec = uniform_ptr(rec_in);
     double dm = max_abs, rm = max_rel;
+    constexpr int E = Traits<DT>::E, kPerWord = E / 4 > 0 ? E / 4 : 1;
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const long long a = (long long)((u64)q[2 * e] | ((u64)q[2 * e + 1] << 32));
-        const long long x = (long long)((u64)b[2 * e] | ((u64)b[2 * e + 1] << 32));
-        const double d = i64_abs_diff(a, x);
-        const double babs = i64_abs(x);
+    for (int e = 0; e < E; ++e) {
+        if constexpr (kPerWord > 1) {
+            if (q[e / kPerWord] == b[e / kPerWord]) continue;            // bytes: most words of a tripping lane are equal
+        }
+        const long long a = integer_element<DT>(q, e), x = integer_element<DT>(b, e);
+        double d, babs;
+        if constexpr (DT == GEAK_I64) {
+            d = i64_abs_diff(a, x);                                      // the difference may leave 64 bits: one rounding
+            babs = i64_abs(x);
+        } else {
+            const long long diff = a - x;                                // narrower elements: exact in 64 bits
+            d = (double)(diff < 0 ? -diff : diff);
+            babs = (double)(x < 0 ? -x : x);
+        }
         dm = (d > dm) ? d : dm;
         // d/|b| > rm implies d > rm*|b|*(1 - 2^-30); the margin covers the product's rounding
         if (d > 0.0 && (rm < (double)kInfF) && d > rm * (1.0 - 0x1p-30) * babs) {
-            const double r = d / babs;                               // binary64, correctly rounded; d/0 = +Inf
+            const double r = d / babs;                                   // binary64, correctly rounded; d/0 = +Inf
             rm = (r > rm) ? r : rm;
         }
     }
-    dm = wave_max_d(dm);
-    rm = wave_max_d(rm);
-    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
-        if (dm > max_abs) publish_max(&rec->abs, dm);
-        if (rm > max_rel) publish_max(&rec->rel, rm);
-    }
-    DoublePair out;
-    out.abs = dm;
-    out.rel = rm;
-    return out;
+    return close_raise<double, DoublePair>(dm, rm, max_abs, max_rel, rec);
 }
 
+// ---- int64: two elements per 16-byte vector, exact equality ------------------------------------------
 struct Int64Item {
     typedef double Hint;
     static __device__ __forceinline__ double hint_from_bits(u64 bits) { return __builtin_bit_cast(double, uniform64(bits)); }
@@ -749,7 +744,7 @@ struct Int64Item {
         u32x4 b;
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
-        const DoublePair out = raise_vector_int64(q, b, max_abs, max_rel, rec);
+        const DoublePair out = raise_vector_integer<GEAK_I64>(q, b, max_abs, max_rel, rec);
         max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
         max_rel = uniform_of(out.rel);
     }
@@ -786,16 +781,7 @@ __device__ __noinline__ DoublePair raise_vector_f64(const u32x4 q, const u32x4 b
             rm = (hit && r > rm) ? r : rm;
         }
     }
-    dm = wave_max_d(dm);
-    rm = wave_max_d(rm);
-    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
-        if (dm > max_abs) publish_max(&rec->abs, dm);
-        if (rm > max_rel) publish_max(&rec->rel, rm);
-    }
-    DoublePair out;
-    out.abs = dm;
-    out.rel = rm;
-    return out;
+    return close_raise<double, DoublePair>(dm, rm, max_abs, max_rel, rec);
 }
 
 struct DoubleItem {
@@ -1098,16 +1084,7 @@ __device__ __noinline__ FloatPair raise_vector_f8(const u32x4 q, const u32x4 b, 
             rm = (hit && r > rm) ? r : rm;
         }
     });
-    dm = wave_max_f(dm);
-    rm = wave_max_f(rm);
-    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
-        if (dm > max_abs) publish_max(&rec->abs, (double)dm);
-        if (rm > max_rel) publish_max(&rec->rel, (double)rm);
-    }
-    FloatPair out;
-    out.abs = dm;
-    out.rel = rm;
-    return out;
+    return close_raise<float, FloatPair>(dm, rm, max_abs, max_rel, rec);
 }
 
 // ---- uint8 / int8: sixteen elements per 16-byte vector, exact equality ---------------------------
@@ -1123,46 +1100,6 @@ __device__ __forceinline__ uint32_t nonzero_bytes(uint32_t x)
     const uint32_t t = (((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u;
     return (uint32_t)__builtin_popcount(t);
 }
-template <bool SIGNED>
-__device__ __forceinline__ long long byte_value(uint32_t word, int byte)
-{
-    const uint32_t v = (word >> (8 * byte)) & 0xFFu;
-    return SIGNED ? (long long)(signed char)v : (long long)v;
-}
-
-template <bool SIGNED>
-__device__ __noinline__ DoublePair raise_vector_bytes(const u32x4 q, const u32x4 b, const double max_abs, const double max_rel,
-                                                      MaxPair *rec_in)
-{
-    MaxPair *rec = uniform_ptr(rec_in);
-    double dm = max_abs, rm = max_rel;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        if (q[w] == b[w]) continue;                                      // most words of a tripping lane are equal
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const long long a = byte_value<SIGNED>(q[w], e), x = byte_value<SIGNED>(b[w], e);
-            const double d = i64_abs_diff(a, x);                         // exact
-            const double babs = i64_abs(x);
-            dm = (d > dm) ? d : dm;
-            if (d > 0.0 && (rm < (double)kInfF) && d > rm * (1.0 - 0x1p-30) * babs) {
-                const double r = d / babs;                               // binary64, correctly rounded; d/0 = +Inf
-                rm = (r > rm) ? r : rm;
-            }
-        }
-    }
-    dm = wave_max_d(dm);
-    rm = wave_max_d(rm);
-    if ((threadIdx.x & (kWaveSize - 1)) == 0) {
-        if (dm > max_abs) publish_max(&rec->abs, dm);
-        if (rm > max_rel) publish_max(&rec->rel, rm);
-    }
-    DoublePair out;
-    out.abs = dm;
-    out.rel = rm;
-    return out;
-}
-
 template <bool SIGNED>
 struct ByteItem {
     typedef double Hint;
@@ -1200,7 +1137,7 @@ struct ByteItem {
         u32x4 b;
 #pragma unroll
         for (int w = 0; w < 4; ++w) b[w] = bref[V * 4 + w];
-        const DoublePair out = raise_vector_bytes<SIGNED>(q, b, max_abs, max_rel, rec);
+        const DoublePair out = raise_vector_integer<SIGNED ? GEAK_I8 : GEAK_U8>(q, b, max_abs, max_rel, rec);
         max_abs = uniform_of(out.abs);      // the callee returns the wave's maxima in every lane
         max_rel = uniform_of(out.rel);
     }

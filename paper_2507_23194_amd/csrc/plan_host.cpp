@@ -213,7 +213,13 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         // long as a binary32 one.  Every fresh start of the stream (a new segment, a tail) is priced at
         // about six slice times whatever K is -- nothing hides its first loads, and waves with many
         // starts were the last to finish until they were priced this high -- and a tail at a full
-        // item on top of that, whatever its length.  Units: sixteenths of a binary32 slice.
+        // item on top of that, whatever its length.  Units: sixteenths of a binary32 slice.  A regression of
+        // per-wave durations on what each wave's list holds, over four seeds of the ragged batch at K = 4 and
+        // batches at K = 8 and K = 16, gives 16 / 20 / 19 / 13 per binary32 / binary16 / bfloat16 / int32 slice,
+        // about 50 for a start and 1.3 slices' worth plus 80 for a tail; planning with those instead moves the
+        // kernel's duration by -1.8 % to +2.4 % depending on the seed, inside the run-to-run spread, so the
+        // constants below stand.  What the model cannot see -- which compute unit a block lands on, how many of
+        // a segment's elements trip the maxima filters -- leaves blocks of equal estimated cost 5 % apart.
         const uint64_t blocks_wanted = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
         const uint64_t target_blocks = std::max<uint64_t>(1, std::min<uint64_t>(max_blocks, blocks_wanted));
         const uint64_t slices = (uint64_t)num_candidates + 1;
