@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # They were taken in profiling runs of their own, not in the run that prints them, and describe the
 # library whose build id is recorded with them: for any other build roofline.traffic is null.
 MEASURED_TRAFFIC = {
-    "build_id": "",
-    "bytes": {},
+    "build_id": "548828f7e34cb03b",
+    "bytes": {2: 8.7935e9, 3: 9.1949e9, 4: 1.2294e9, 5: 141.8644e9},
     "source": "profiles/compare_kernel_config*.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, not this run)",
 }
 
@@ -88,7 +88,12 @@ def run_config(cid: int, args, build_id: str):
     from paper_2507_23194_amd import binding as B
     from paper_2507_23194_amd import synth
 
-    w = synth.CONFIGS[cid](device="cuda:0")
+    if cid == 0:                        # --dense: a profiling aid for other dtypes, never part of the default line
+        dt, lg, kk = args.dense.split(":")
+        w = synth.dense_noise(dt, int(lg), int(kk), device="cuda:0")
+        WORKLOADS[0] = f"dense {dt} 2^{lg} elements, K={kk}, normal data with 2 % relative noise, atol=1e-2, rtol=0.1"
+    else:
+        w = synth.CONFIGS[cid](device="cuda:0")
     torch.cuda.synchronize()
 
     t_plan = time.perf_counter()
@@ -240,6 +245,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=None, choices=sorted(WORKLOADS),
                     help="run this workload alone (default: all five, headline on config 5)")
+    ap.add_argument("--dense", default=None, metavar="DTYPE:LOG2N:K",
+                    help="instead of a configuration: one dense tensor of a floating dtype (f8e4m3:26:16, say) with "
+                         "normal data, for profiles of dtypes the five configurations do not use; implies --no-cpu-baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per compare launch from rocprofv3 counters, overriding the recorded figure "
@@ -281,6 +289,8 @@ def main():
         sys.exit("bench.py: --traffic-bytes describes one workload; give --config with it")
 
     configs = [args.config] if args.config is not None else [1, 2, 3, 4, 5]
+    if args.dense is not None:
+        configs, args.no_cpu_baseline, args.config = [0], True, 0
     per_config = []
     for cid in configs:
         t0 = time.perf_counter()

@@ -313,6 +313,21 @@ def config5(log2_n: int = 30, num_candidates: int = 32, device="cpu",
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 
+def dense_noise(dtype: str, log2_n: int, num_candidates: int, device="cpu") -> Workload:
+    """A plain dense workload of any floating dtype, for measuring the dtypes the five configurations do not
+    use (the 8-bit formats above all): standard normal reference, candidates = reference * (1 + 2 % noise),
+    rounded to the dtype; finite values only."""
+    n = 1 << log2_n
+    g = _gen(77, device)
+    ref32 = torch.randn(n, generator=g, device=device)
+    ref = ref32.to(TORCH_DTYPE[dtype])
+    cands = []
+    for k in range(num_candidates):
+        gk = _gen(7700 + k, device)
+        cands.append((ref32 * (1.0 + 0.02 * torch.randn(n, generator=gk, device=device))).to(TORCH_DTYPE[dtype]))
+    return Workload(f"dense_noise_{dtype}", 1e-2, 0.1, False, ref, cands, dtype, (n,), None, {})
+
+
 def small(config_id: int, device="cpu") -> Workload:
     """Reduced-size version of a config with the same recipe, sized so the CPU oracle
     finishes in a second or so while the GPU path still sees several tiles and a ragged tail."""
