@@ -469,7 +469,8 @@ geak_status geak_metrics_pass_at_k(uint64_t n, uint64_t c, uint64_t k, double *o
  * nothing from them: the rate it reaches is what this machine's memory system delivers to any
  * kernel with this traffic, the yardstick beside the nominal HBM peak.  Arguments as for
  * geak_check_run (at most GEAK_MAX_CANDIDATES - 1 candidates); the workspace is used as scratch and
- * no results are produced.  The caller times it on its stream. */
+ * no results are produced.  The caller times it on its stream.  GEAK_EINVAL for a plan built by
+ * geak_check_plan_mapped: its reference need not be as long as the candidates. */
 geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, const void *const *cand_dev,
                                   void *workspace_dev, void *hip_stream);
 

@@ -614,6 +614,9 @@ geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, co
     if (!workspace_dev) return GEAK_EINVAL;
     if (const geak_status st = check_tensor_pointers(hp, ref_dev, cand_dev)) return st;
     if ((uintptr_t)workspace_dev & 15u) return GEAK_EALIGN;
+    // the probe reads the same span of every buffer: a reference with a layout of its own may be far shorter
+    for (const SegDesc &sg : hp.segments)
+        if (sg.layout & kRefMapped) return GEAK_EINVAL;
     const int K = hp.num_candidates;
     // the span of the packed buffers that the plan's segments cover
     uint64_t end = 0;

@@ -78,11 +78,11 @@ def _build(rng, specs, K):
     return np.concatenate(ref_parts), [np.concatenate(p) for p in cand_parts], table
 
 
-def _run_and_compare(oracle_mod, ref_np, cand_nps, table, atol, rtol, equal_nan, what, with_report=True):
+def _run_and_compare(oracle_mod, ref_np, cand_nps, table, atol, rtol, equal_nan, what, with_report=True, tolerances=None):
     ref = torch.from_numpy(ref_np.copy()).cuda()
     cands = [torch.from_numpy(c.copy()).cuda() for c in cand_nps]
     K = len(cands)
-    ck = B.Checker(mapped=table, num_candidates=K, atol=atol, rtol=rtol, equal_nan=equal_nan, device=0)
+    ck = B.Checker(mapped=table, num_candidates=K, atol=atol, rtol=rtol, equal_nan=equal_nan, device=0, tolerances=tolerances)
     try:
         ck.run(ref, cands)
         gpu = ck.read().copy()
@@ -92,6 +92,8 @@ def _run_and_compare(oracle_mod, ref_np, cand_nps, table, atol, rtol, equal_nan,
         ck.close()
     cpu = np.zeros((len(table), K), dtype=gpu.dtype)
     for s, (coff, rows, cols, cpitch, roff, rpitch, stride, dtype) in enumerate(table):
+        if tolerances is not None:
+            atol, rtol = tolerances[s]
         for k in range(K):
             r = oracle_mod.check_segment_mapped(ref_np, cand_nps[k], rows, cols, dtype, atol, rtol, equal_nan,
                                                 coff, cpitch, roff, rpitch, stride)
@@ -101,6 +103,8 @@ def _run_and_compare(oracle_mod, ref_np, cand_nps, table, atol, rtol, equal_nan,
     if not with_report:
         return gpu
     for s, (coff, rows, cols, cpitch, roff, rpitch, stride, dtype) in enumerate(table):
+        if tolerances is not None:
+            atol, rtol = tolerances[s]
         b = oracle_mod.gather_rows(ref_np, rows, cols, dtype, roff, rpitch, stride)
         for k in range(K):
             a = oracle_mod.gather_rows(cand_nps[k], rows, cols, dtype, coff, cpitch, 1)
@@ -150,6 +154,32 @@ def test_rows_longer_than_work_items(oracle_mod, dtype, kind):
     _run_and_compare(oracle_mod, ref_np, cand_nps, table, 1e-3, 1e-3, False, f"{dtype} {kind} long rows")
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_mapped_plan(oracle_mod, seed):
+    """Seeded random plans: a few segments of random dtype, geometry (rows from one element to several work items,
+    pitches tight, padded to the grid or odd, starts on or off the grid), reference layout and tolerances."""
+    rng = np.random.default_rng(9400 + seed)
+    nsegs, K = int(rng.integers(1, 9)), int(rng.integers(1, 6))
+    specs, tols = [], []
+    for _ in range(nsegs):
+        dtype = DTYPES[int(rng.integers(0, len(DTYPES)))]
+        w = synth.ELEM_SIZE[dtype]
+        grid = 16 // w
+        rows = int(rng.choice([0, 1, 2, int(rng.integers(3, 40)), int(rng.integers(40, 300))]))
+        cols = int(rng.choice([1, int(rng.integers(2, 40)), int(rng.integers(40, 2048 // w + 1)), int(rng.integers(2048 // w, 3 * 4096 // w))]))
+        if rows * cols > 30000:
+            rows = max(1, 30000 // cols)
+        on_grid = bool(rng.integers(0, 2))
+        cand_pad = int((-cols) % grid + grid * rng.integers(0, 3)) if on_grid else int(rng.integers(0, 9))
+        specs.append(dict(dtype=dtype, rows=rows, cols=cols, kind=str(rng.choice(["row", "col", "scalar", "pitch"])),
+                          cand_pad=cand_pad, cand_shift=0 if on_grid else int(rng.integers(0, 2 * grid)),
+                          ref_pad=int(rng.integers(0, 5)), ref_shift=int(rng.integers(0, 7))))
+        tols.append((float(rng.choice([0.0, 1e-3, 0.25])), float(rng.choice([0.0, 1e-2, 0.125]))))
+    print("random mapped plan", seed, [(sp["dtype"], sp["rows"], sp["cols"], sp["kind"]) for sp in specs], "K", K, flush=True)
+    ref_np, cand_nps, table = _build(rng, specs, K=K)
+    _run_and_compare(oracle_mod, ref_np, cand_nps, table, 0.0, 0.0, bool(rng.integers(0, 2)), f"random mapped plan {seed}", tolerances=tols)
+
+
 def test_mapped_reference_equals_plain_check_of_the_expanded_reference(oracle_mod):
     """The same candidates checked twice on the GPU: against a reference row through the mapped plan, and
     against that row written out for every row through the plain pitched plan.  Every record agrees."""
@@ -172,6 +202,14 @@ def test_mapped_reference_equals_plain_check_of_the_expanded_reference(oracle_mo
         finally:
             ck.close()
     _assert_same(recs[0], recs[1], "row reference against its expansion")
+    # the read-only probe walks the same span of every buffer: refused where the reference is shorter
+    ck = B.Checker(mapped=[(0, rows, cols, cols * 4, 0, 0, 1, "f32")], num_candidates=K, atol=1e-3, rtol=1e-3, equal_nan=False, device=0)
+    try:
+        with pytest.raises(B.GeakError) as err:
+            ck.read_probe(ref_row, dc)
+        assert err.value.status == B.GEAK_EINVAL
+    finally:
+        ck.close()
     assert recs[0][0, 2]["pass"] == 1 and recs[0][0, 0]["first_mismatch"] <= 77 * cols + 5
     cpu = oracle_mod.check_segment_mapped(b_row.view(np.uint8), cands[0].view(np.uint8).reshape(-1), rows, cols, "f32", 1e-3, 1e-3, False,
                                           0, cols * 4, 0, 0, 1)

@@ -145,6 +145,43 @@ def test_several_segments_of_all_formats(oracle_mod):
     _assert_same(rec, cpu, "mixed formats")
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_block_scaled_plan(oracle_mod, seed):
+    """Seeded random plans: a few segments of random format and length (whole blocks, from one block to several
+    work items), random candidate count and per-segment tolerances; records and reports against the oracle."""
+    rng = np.random.default_rng(9500 + seed)
+    nsegs, K = int(rng.integers(1, 7)), int(rng.integers(1, 10))
+    fmts = [FORMATS[int(rng.integers(0, 3))] for _ in range(nsegs)]
+    sizes = [32 * int(rng.choice([1, int(rng.integers(2, 33)), int(rng.integers(33, 129)), int(rng.integers(129, 400))])) for _ in range(nsegs)]
+    print("random block-scaled plan", seed, list(zip(fmts, sizes)), "K", K, flush=True)
+    segs = [_tensors(rng, f, n, K) for f, n in zip(fmts, sizes)]
+    tols = [(float(rng.choice([0.0, 1e-3, 0.25, 1e30])), float(rng.choice([0.0, 1e-2, 0.125, 3.0]))) for _ in range(nsegs)]
+    equal_nan = bool(rng.integers(0, 2))
+    bufs, table = _pack(segs)
+    dev = [torch.from_numpy(b.copy()).cuda() for b in bufs]
+    ck = B.Checker(mx=[(o, n, so, f) for (o, n, so), f in zip(table, fmts)], num_candidates=K, equal_nan=equal_nan, device=0, tolerances=tols)
+    try:
+        ck.run(dev[0], dev[1:])
+        rec = ck.read().copy()
+        rep, cnt = ck.report(dev[0], dev[1:], 4)
+    finally:
+        ck.close()
+    cpu = np.zeros((nsegs, K), dtype=rec.dtype)
+    for s, seg in enumerate(segs):
+        b = mx.dequantize(seg[0][0], seg[0][1], sizes[s], fmts[s])
+        for k in range(K):
+            a = mx.dequantize(seg[k + 1][0], seg[k + 1][1], sizes[s], fmts[s])
+            r = oracle_mod.check_segment(b, a, sizes[s], "f32", tols[s][0], tols[s][1], equal_nan)
+            for f in cpu.dtype.names:
+                cpu[s, k][f] = r[f]
+            want = oracle_mod.report_segment(b, a, sizes[s], "f32", tols[s][0], tols[s][1], equal_nan, 4)
+            assert int(cnt[s, k]) == len(want), (seed, s, k)
+            got = rep[s, k][:len(want)]
+            assert (got["index"] == want["index"]).all(), (seed, s, k)
+            assert all(np.array_equal(got[f], want[f], equal_nan=True) for f in ("a", "b", "d", "tol")), (seed, s, k)
+    _assert_same(rec, cpu, f"random block-scaled plan {seed}")
+
+
 @pytest.mark.parametrize("fmt", ["mxfp8e4m3", "mxfp8e5m2"])
 def test_the_same_numbers_under_other_scales_pass(oracle_mod, fmt):
     """A candidate that stores every block one binade lower in the payload and one higher in the scale encodes
