@@ -156,14 +156,17 @@ geak_status geak_check_plan_pitched(geak_plan **out, const geak_segment2d *segs,
  * is unchanged, only where b is read differs.
  *   ref_pitch_bytes   bytes between the reference's rows; any multiple of the element size, also one below a row's
  *                     length (overlapping rows) and 0: one reference row for all rows
- *   ref_elem_stride   1: the reference's row is contiguous; 0: one reference element for the whole row
- *                     (with ref_pitch_bytes == 0: one element for the whole segment)
+ *   ref_elem_stride   elements between neighbours of a reference row.  1: the row is contiguous; 0: one reference
+ *                     element for the whole row (with ref_pitch_bytes == 0: one element for the whole segment);
+ *                     more (below 2^22): a strided row -- a reference stored transposed is ref_pitch_bytes = element
+ *                     size, ref_elem_stride = rows of the reference's own storage
  * Reference regions of different segments may overlap each other; the candidates' spans may not, as for every
  * other plan.  Indices in the results are flat over the candidates' rows * row_elems elements.  A reference element
  * that several candidate elements share is read once per work item that needs it: the algorithmic bytes of such a
  * plan count the candidates' elements K times and the reference's distinct elements once.  With a contiguous
  * reference row (stride 1), rows that start 16-byte aligned and are at least 4 KiB long run as full work items;
- * with one element per row (stride 0) every item takes the guarded path of a segment's tail. */
+ * with one element per row every item takes the guarded path of a segment's tail, and a strided row is gathered
+ * element by element (correct, far from the memory's rate). */
 typedef struct {
     uint64_t byte_offset;
     uint64_t rows;
@@ -171,14 +174,14 @@ typedef struct {
     uint64_t pitch_bytes;
     uint64_t ref_byte_offset;
     uint64_t ref_pitch_bytes;
-    int32_t  ref_elem_stride;    /* 0 or 1 */
+    int32_t  ref_elem_stride;    /* >= 0 */
     int32_t  dtype;
 } geak_segment_mapped;
 
 /* Like geak_check_plan_pitched for segments whose reference has its own layout; `tols` may be null, then
- * atol / rtol apply to all.  GEAK_EINVAL for a stride other than 0 or 1, GEAK_EALIGN for reference offsets or
- * pitches that are no multiple of the element size, GEAK_EBOUNDS when the reference region leaves the address
- * space. */
+ * atol / rtol apply to all.  GEAK_EINVAL for a negative stride, GEAK_EALIGN for reference offsets or pitches that
+ * are no multiple of the element size, GEAK_EBOUNDS for a stride of 2^22 or more or when the reference region
+ * leaves the address space. */
 geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *segs, const geak_tolerance *tols,
                                    uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
                                    int32_t equal_nan, int32_t device);

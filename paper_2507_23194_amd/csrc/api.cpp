@@ -164,12 +164,13 @@ geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *s
     }
     for (uint64_t s = 0; s < nsegs; ++s) {
         const geak_segment_mapped &g = segs[s];
-        if (g.ref_elem_stride != 0 && g.ref_elem_stride != 1) return GEAK_EINVAL;
+        if (g.ref_elem_stride < 0) return GEAK_EINVAL;
+        if ((uint64_t)g.ref_elem_stride > kMaxRefStride) return GEAK_EBOUNDS;
         if (g.rows && g.row_elems > GEAK_MAX_SEGMENT_NUMEL / g.rows) return GEAK_EBOUNDS;
         const uint64_t numel = g.rows * g.row_elems;
         // the rows stay rows, also when the candidates store them back to back: the reference's row differs
         SegDesc d{g.byte_offset, numel, numel ? g.row_elems : 1, numel ? g.pitch_bytes : 0, g.dtype,
-                  kRefMapped | (g.ref_elem_stride == 0 ? kRefSplat : 0), g.ref_byte_offset, numel ? g.ref_pitch_bytes : 0};
+                  kRefMapped | (int32_t)((uint32_t)g.ref_elem_stride << kRefStrideShift), g.ref_byte_offset, numel ? g.ref_pitch_bytes : 0};
         descs[s] = d;
     }
     return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
@@ -616,7 +617,7 @@ geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, co
     if ((uintptr_t)workspace_dev & 15u) return GEAK_EALIGN;
     // the probe reads the same span of every buffer: a reference with a layout of its own may be far shorter
     for (const SegDesc &sg : hp.segments)
-        if (sg.layout & kRefMapped) return GEAK_EINVAL;
+        if (seg_ref_mapped(sg)) return GEAK_EINVAL;
     const int K = hp.num_candidates;
     // the span of the packed buffers that the plan's segments cover
     uint64_t end = 0;

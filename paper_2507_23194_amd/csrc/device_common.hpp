@@ -263,7 +263,7 @@ __device__ __forceinline__ u32x4 load_slot(const unsigned char *base, uint32_t s
 struct RefPlace {
     u64 offset;              // byte offset in the reference buffer of what the item's first element is compared with
     u64 pitch;               // bytes between the reference's rows
-    bool splat;              // one reference element per row
+    uint32_t stride;         // elements between neighbours of a reference row: 1 contiguous, 0 one element per row
 };
 template <int DT>
 __device__ __forceinline__ RefPlace ref_place(const geak_item &it, uint32_t item_index, const SegDesc *segments, const uint64_t *ref_item_offset)
@@ -271,7 +271,26 @@ __device__ __forceinline__ RefPlace ref_place(const geak_item &it, uint32_t item
     const GEAK_AS_CONSTANT unsigned long long *g = (const GEAK_AS_CONSTANT unsigned long long *)(segments + it.segment);
     const GEAK_AS_CONSTANT unsigned long long *t = (const GEAK_AS_CONSTANT unsigned long long *)ref_item_offset;
     // SegDesc: byte_offset, numel, row_elems, pitch_bytes, {dtype, layout}, ref_byte_offset, ref_pitch_bytes
-    return RefPlace{t[item_index], g[6], ((uint32_t)(g[4] >> 32) & (uint32_t)kRefSplat) != 0};
+    return RefPlace{t[item_index], g[6], (uint32_t)(g[4] >> 32) >> kRefStrideShift};
+}
+// Elements [lo, hi) of a 16-byte vector gathered one by one: element e from `first` + e * stride_bytes, the others 0.
+// The reference of a segment whose reference row is strided (a transposed reference, a column of a wider
+// matrix); rare and slow by nature: a real function.
+template <int DT>
+__device__ __noinline__ u32x4 gather_elements_call(const unsigned char *first, const u64 stride_bytes, const uint32_t lo, const uint32_t hi)
+{
+    constexpr int E = Traits<DT>::E, W = Traits<DT>::W;
+    u32x4 q = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        if ((uint32_t)e < lo || (uint32_t)e >= hi) continue;
+        const GEAK_AS_GLOBAL unsigned char *p = (const GEAK_AS_GLOBAL unsigned char *)(first + (u64)e * stride_bytes);
+        if constexpr (W == 1) q[e >> 2] |= (uint32_t)p[0] << (8 * (e & 3));
+        else if constexpr (W == 2) q[e >> 1] |= (uint32_t)*(const GEAK_AS_GLOBAL uint16_t *)p << (16 * (e & 1));
+        else if constexpr (W == 4) q[e] = *(const GEAK_AS_GLOBAL uint32_t *)p;
+        else { q[2 * e] = ((const GEAK_AS_GLOBAL uint32_t *)p)[0]; q[2 * e + 1] = ((const GEAK_AS_GLOBAL uint32_t *)p)[1]; }
+    }
+    return q;
 }
 // Vector slot `slot` of the reference side of such an item: the elements that the same slot of a
 // candidate is compared with, zero where the candidate's slot reads as zero.
@@ -283,13 +302,24 @@ __device__ __forceinline__ u32x4 load_ref_slot(const unsigned char *ref_base, co
     const SlotPlace sp = slot_place<DT, KIND>(slot, n, sh);
     first = sp.first;
     const unsigned char *row = ref_base + rp.offset + (u64)sp.row * rp.pitch;
-    if (!rp.splat) {
+    if (rp.stride == 1) {
         // a shifted item's slot 0 starts `skip` elements before the item: so does the reference's (those are not read
         // unless they share an aligned 16-byte granule with the item's own)
         if constexpr (KIND == kTailShifted) row -= (u64)sh.skip * W;
         return load_partial_from<DT>((global_vec_ptr)row + sp.vec, sp.lo, sp.valid);
     }
     u32x4 q = {0u, 0u, 0u, 0u};
+    if (rp.stride != 0) {
+        // column of the slot's element 0 within its row (for slot 0 of a shifted item it lies before the item's first
+        // element: only elements from `lo` on are touched)
+        long long col = (long long)sp.vec * E;
+        if constexpr (KIND == kTailShifted) col -= sh.skip;
+        if (__builtin_amdgcn_ballot_w64(sp.valid > sp.lo)) {
+            if (sp.valid > sp.lo)
+                q = gather_elements_call<DT>(row + col * (long long)((u64)rp.stride * W), (u64)rp.stride * W, sp.lo, sp.valid < E ? sp.valid : E);
+        }
+        return q;
+    }
     if (sp.valid > sp.lo) {
         uint32_t w0, w1 = 0u;
         if constexpr (W == 1) { w0 = *row; w0 |= w0 << 8; w0 |= w0 << 16; w1 = w0; }

@@ -56,12 +56,15 @@ static_assert(sizeof(SegTol) == 24, "SegTol is read as three 64-bit words");
 
 // A segment as the planner and the kernels see it: `numel` elements in rows of `row_elems`, row r starting
 // pitch_bytes * r behind byte_offset.  A contiguous segment is one row.  `layout` says where the reference's
-// elements lie: 0 at the candidates' own offsets; kRefMapped: element (r, c) at ref_byte_offset + r * ref_pitch_bytes
-// + c * element size; kRefMapped | kRefSplat: one element per row, at ref_byte_offset + r * ref_pitch_bytes.
+// elements lie: 0 at the candidates' own offsets; kRefMapped (bit 0) with the reference's element stride in the
+// bits from kRefStrideShift up: element (r, c) at ref_byte_offset + r * ref_pitch_bytes + c * stride * element size
+// (stride 0: one element per row; stride 1: the row is contiguous; more: its elements are gathered one by one).
 // kMxScaled: a block-scaled segment (dtype one of the GEAK_MX* codes, contiguous, whole blocks of kMxBlock
 // elements); ref_byte_offset then holds the offset of its scale bytes, one per block, in every packed buffer.
 // Seven 64-bit words: device code reads the record word by word.
-constexpr int32_t kRefMapped = 1, kRefSplat = 2, kMxScaled = 4;
+constexpr int32_t kRefMapped = 1, kMxScaled = 4;
+constexpr int kRefStrideShift = 8;
+constexpr uint64_t kMaxRefStride = (1ull << 22) - 1;
 constexpr uint64_t kMxBlock = 32;
 inline bool is_mx_dtype(int dtype) { return dtype >= GEAK_MXFP8_E4M3 && dtype <= GEAK_MXINT8; }
 struct SegDesc {
@@ -76,17 +79,22 @@ struct SegDesc {
 };
 static_assert(sizeof(SegDesc) == 56, "SegDesc is read as seven 64-bit words");
 inline uint64_t seg_rows(const SegDesc &g) { return g.numel / g.row_elems; }
+constexpr bool seg_ref_mapped(const SegDesc &g) { return g.layout != kMxScaled && (g.layout & kRefMapped) != 0; }
+constexpr uint64_t seg_ref_stride(const SegDesc &g) { return (uint32_t)g.layout >> kRefStrideShift; }       // of a mapped segment
 // bytes from the segment's first to behind its last element
 inline uint64_t seg_span(const SegDesc &g)
 {
     return g.numel ? (seg_rows(g) - 1) * g.pitch_bytes + g.row_elems * (uint64_t)elem_size(g.dtype) : 0;
 }
-// the same for the reference's elements of a mapped segment
+// bytes of one row of a mapped segment's reference, first to behind last element (the planner refuses what would overflow)
+inline uint64_t seg_ref_row_span(const SegDesc &g)
+{
+    return ((g.row_elems - 1) * seg_ref_stride(g) + 1) * (uint64_t)elem_size(g.dtype);
+}
+// the same for all rows
 inline uint64_t seg_ref_span(const SegDesc &g)
 {
-    if (!g.numel) return 0;
-    const uint64_t row = ((g.layout & kRefSplat) ? 1 : g.row_elems) * (uint64_t)elem_size(g.dtype);
-    return (seg_rows(g) - 1) * g.ref_pitch_bytes + row;
+    return g.numel ? (seg_rows(g) - 1) * g.ref_pitch_bytes + seg_ref_row_span(g) : 0;
 }
 
 // Host side of a plan: everything that can be decided without a device.

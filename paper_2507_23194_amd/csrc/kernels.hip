@@ -1848,7 +1848,8 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
     const bool pitched = sg.row_elems != sg.numel;
     const u64 pitch_elems = sg.pitch_bytes / (u64)Traits<DT>::W;
     // a reference with a layout of its own: its rows are ref_pitch_elems apart and hold the row's elements or one for all
-    const bool mapped = (sg.layout & kRefMapped) != 0, splat = (sg.layout & kRefSplat) != 0;
+    const bool mapped = seg_ref_mapped(sg);
+    const u64 ref_stride = seg_ref_stride(sg);          // elements between neighbours of a reference row
     const u64 ref_pitch_elems = sg.ref_pitch_bytes / (u64)Traits<DT>::W;
     // a block-scaled segment: its scale bytes, one per 32 elements, in the same buffers
     [[maybe_unused]] const unsigned char *rscales = p.ref + sg.ref_byte_offset, *cscales = p.cand_table[blockIdx.x % p.num_candidates] + sg.ref_byte_offset;
@@ -1862,7 +1863,7 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
             const u64 i = base + (u64)u * kReportThreads + tid;
             const bool in = i < sg.numel;
             const u64 j = (pitched && in) ? (i / sg.row_elems) * pitch_elems + i % sg.row_elems : i;     // where element i is stored
-            const u64 jr = (mapped && in) ? (i / sg.row_elems) * ref_pitch_elems + (splat ? 0 : i % sg.row_elems) : j;   // and what it is compared with
+            const u64 jr = (mapped && in) ? (i / sg.row_elems) * ref_pitch_elems + (i % sg.row_elems) * ref_stride : j;   // and what it is compared with
             if constexpr (DT == GEAK_I32) {
                 ai[u] = in ? reinterpret_cast<const int *>(cb)[j] : 0;
                 bi[u] = in ? reinterpret_cast<const int *>(rb)[jr] : 0;
@@ -1952,7 +1953,7 @@ __global__ __launch_bounds__(kReportThreads) void report_kernel(const ReportArgs
     if (want == 0) return;                                   // uniform
     const SegDesc sg = p.segments[seg];
     const SegTol tolerance = p.seg_tol[seg];
-    const unsigned char *rb = p.ref + ((sg.layout & kRefMapped) ? sg.ref_byte_offset : sg.byte_offset), *cb = p.cand_table[k] + sg.byte_offset;
+    const unsigned char *rb = p.ref + (seg_ref_mapped(sg) ? sg.ref_byte_offset : sg.byte_offset), *cb = p.cand_table[k] + sg.byte_offset;
     geak_mismatch *out = p.records + (u64)blockIdx.x * p.max_records;
     const auto report = [&](auto dt) { report_pair<decltype(dt)::value>(p, tolerance, sg, rec, want, rb, cb, out, s_cnt); };
     if (sg.dtype >= GEAK_MXFP8_E4M3) for_scaled_dtype(sg.dtype, report);          // uniform

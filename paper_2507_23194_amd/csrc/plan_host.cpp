@@ -33,8 +33,9 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         const SegDesc &g = segs[s];
         if (g.dtype < GEAK_F32 || g.dtype > GEAK_MXINT8) return GEAK_EDTYPE;
         if (is_mx_dtype(g.dtype) != (g.layout == kMxScaled)) return GEAK_EDTYPE;     // block-scaled element formats belong to block-scaled segments only
-        if (g.layout != kMxScaled && ((g.layout & ~(kRefMapped | kRefSplat)) != 0 || g.layout == kRefSplat)) return GEAK_EINVAL;
-        any_mapped |= (g.layout & kRefMapped) != 0;
+        if (g.layout != kMxScaled && g.layout != 0 && (!(g.layout & kRefMapped) || (g.layout & 0xFE) != 0 || g.layout < 0 ||
+                                                       seg_ref_stride(g) > kMaxRefStride)) return GEAK_EINVAL;
+        any_mapped |= seg_ref_mapped(g);
         if (g.layout == kMxScaled) {
             // payload on the 16-byte grid (a vector then lies inside one block), whole blocks, one contiguous row
             if (g.byte_offset % 16 != 0) return GEAK_EALIGN;
@@ -64,14 +65,16 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         // the reference's side of a mapped segment: element-aligned, inside the address space; its rows may
         // overlap or coincide, so its distinct bytes are at most its span
         uint64_t ref_bytes = tensor_bytes;
-        if (g.layout & kRefMapped) {
+        if (seg_ref_mapped(g)) {
             if (g.ref_byte_offset % w != 0 || g.ref_pitch_bytes % w != 0) return GEAK_EALIGN;
             if (g.numel) {
                 if (mul_overflows(seg_rows(g) - 1, g.ref_pitch_bytes)) return GEAK_EBOUNDS;
-                const uint64_t ref_row_bytes = ((g.layout & kRefSplat) ? 1 : g.row_elems) * w;
-                if ((seg_rows(g) - 1) * g.ref_pitch_bytes > UINT64_MAX - ref_row_bytes) return GEAK_EBOUNDS;
+                if (seg_ref_stride(g) && g.row_elems - 1 > (UINT64_MAX / 16) / seg_ref_stride(g)) return GEAK_EBOUNDS;
+                const uint64_t ref_row_span = seg_ref_row_span(g);                       // fits: checked in the line above
+                if ((seg_rows(g) - 1) * g.ref_pitch_bytes > UINT64_MAX - ref_row_span) return GEAK_EBOUNDS;
                 if (g.ref_byte_offset > UINT64_MAX - seg_ref_span(g)) return GEAK_EBOUNDS;
                 const uint64_t ref_rows = g.ref_pitch_bytes ? seg_rows(g) : 1;
+                const uint64_t ref_row_bytes = (seg_ref_stride(g) ? g.row_elems : 1) * w;    // distinct elements of a row
                 ref_bytes = std::min(seg_ref_span(g), mul_overflows(ref_rows, ref_row_bytes) ? UINT64_MAX : ref_rows * ref_row_bytes);
             }
         }
@@ -146,7 +149,8 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         for (uint64_t s = 0; s < nsegs; ++s) {
             const SegDesc &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
-            const bool mapped = (g.layout & kRefMapped) != 0;
+            const bool mapped = seg_ref_mapped(g);
+            const uint64_t ref_stride = mapped ? seg_ref_stride(g) : 1;
             if (!g.numel) continue;
             // Short rows of a pitched segment that all start on 16-byte boundaries: whole rows are
             // grouped into one item, as many as its 256 vector slots hold (a row takes
@@ -184,13 +188,14 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     it.numel = (uint16_t)n;
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
-                    // an item whose reference is one element for the whole row is never a full one: it takes the guarded path
-                    it.flags = (uint8_t)((full && !(g.layout & kRefSplat) ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0) |
+                    // a full item needs a contiguous reference slice: with one reference element per row, or a strided
+                    // reference row, the item takes the guarded path
+                    it.flags = (uint8_t)((full && ref_stride == 1 ? GEAK_ITEM_FULL : 0) | (it.byte_offset % 16 == 0 ? GEAK_ITEM_ALIGNED : 0) |
                                          (mapped ? GEAK_ITEM_REFMAP : 0));
                     hp.items.push_back(it);
                     if (any_mapped)
                         hp.ref_item_offset.push_back(!mapped ? it.byte_offset
-                                                     : g.ref_byte_offset + r * g.ref_pitch_bytes + ((g.layout & kRefSplat) ? 0 : done * w));
+                                                     : g.ref_byte_offset + r * g.ref_pitch_bytes + done * ref_stride * w);
                     done += n;
                 };
                 const uint64_t skip = (row_start % 16) / w;

@@ -1,5 +1,6 @@
 """References with a layout of their own (geak_check_plan_mapped): one reference row for all rows, one
-reference element per row, one element for the whole output, a reference with its own pitch and start.
+reference element per row, one element for the whole output, a reference with its own pitch and start, strided
+reference rows and a reference stored transposed.
 Records, mismatch report and ulp histogram equal what the oracle finds when it gathers the reference by plain
 index arithmetic (oracle.gather_rows) and applies the unchanged rule -- every dtype, rows that are grouped,
 rows that start off the 16-byte grid, rows longer than several work items, several such segments in one plan."""
@@ -23,6 +24,8 @@ def _segment(rng, dtype, rows, cols, kind, cand_pad, cand_shift, ref_pad, ref_sh
     "pitch" a full reference with its own pitch.  Pads and shifts in elements."""
     w = synth.ELEM_SIZE[dtype]
     store = STORE[w]
+    if kind in ("strided", "transposed"):
+        return _segment_strided(rng, dtype, rows, cols, kind, cand_pad, cand_shift, ref_pad, ref_shift, cand_base, ref_base, K)
     ref_rows, ref_cols = {"row": (1, cols), "col": (rows, 1), "scalar": (1, 1), "pitch": (rows, cols)}[kind]
     n_store = ref_rows * ref_cols
     b_store, a_store = _special_case(rng, dtype, max(1, n_store))
@@ -59,6 +62,46 @@ def _segment(rng, dtype, rows, cols, kind, cand_pad, cand_shift, ref_pad, ref_sh
         cands.append(cb)
     entry = (cand_base + cand_shift * w, rows, cols, cand_pitch_elems * w, ref_base + ref_shift * w, ref_pitch_elems * w,
              0 if kind in ("col", "scalar") else 1, dtype)
+    return ref_bytes, cands, entry
+
+
+def _segment_strided(rng, dtype, rows, cols, kind, cand_pad, cand_shift, ref_pad, ref_shift, cand_base, ref_base, K):
+    """The reference's rows are strided: "transposed" stores element (r, c) at c * rows + r (rows one element apart,
+    neighbours of a row `rows` apart), "strided" keeps every (2 + ref_pad)-th element of rows that lie a full strided
+    row apart."""
+    w = synth.ELEM_SIZE[dtype]
+    store = STORE[w]
+    n = rows * cols
+    b_full, a_full = _special_case(rng, dtype, max(1, n))
+    b_full, a_full = b_full.view(store)[:n], a_full.view(store)[:n]
+    _, other = _special_case(rng, dtype, max(1, n))
+    other = other.view(store)[:n]
+    if kind == "transposed":
+        stride, ref_pitch_elems = max(rows, 1), 1
+    else:
+        stride = 2 + ref_pad
+        ref_pitch_elems = (cols - 1) * stride + 1 + ref_pad if cols else 0
+    r_idx, c_idx = np.divmod(np.arange(n), max(cols, 1))
+    where = ref_shift + r_idx * ref_pitch_elems + c_idx * stride
+    ref_len = int(where.max()) + 1 if n else ref_shift
+    ref_bytes = rng.integers(0, 256, ref_len * w + 16, dtype=np.uint8)
+    ref_bytes[: ref_len * w].view(store)[where] = b_full
+    cand_pitch_elems = cols + cand_pad
+    cand_len = cand_shift + (rows - 1) * cand_pitch_elems + cols if n else cand_shift
+    cands = []
+    for k in range(K):
+        full = (b_full if k == 1 else a_full).copy()
+        if k != 1 and n:
+            same = rng.random(n) < 0.3
+            full[same] = b_full[same]
+            repl = rng.random(n) < 0.01
+            full[repl] = other[repl]
+        cb = rng.integers(0, 256, cand_len * w + 16, dtype=np.uint8)
+        ce = cb[: cand_len * w].view(store)
+        for r in range(rows if cols else 0):
+            ce[cand_shift + r * cand_pitch_elems: cand_shift + r * cand_pitch_elems + cols] = full[r * cols:(r + 1) * cols]
+        cands.append(cb)
+    entry = (cand_base + cand_shift * w, rows, cols, cand_pitch_elems * w, ref_base + ref_shift * w, ref_pitch_elems * w, stride, dtype)
     return ref_bytes, cands, entry
 
 
@@ -118,15 +161,16 @@ def _run_and_compare(oracle_mod, ref_np, cand_nps, table, atol, rtol, equal_nan,
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-def test_four_layouts_every_dtype(oracle_mod, dtype):
-    """Short rows (grouped when the candidates' rows start on the grid, one by one when they do not), all four
-    reference layouts, reference and candidates at their own odd element offsets."""
+def test_all_layouts_every_dtype(oracle_mod, dtype):
+    """Short rows (grouped when the candidates' rows start on the grid, one by one when they do not), all
+    reference layouts (one row, one element per row, one element, own pitch, strided rows, stored transposed),
+    reference and candidates at their own odd element offsets."""
     print("mapped layouts", dtype, flush=True)
     w = synth.ELEM_SIZE[dtype]
     rng = np.random.default_rng(9100 + DTYPES.index(dtype))
     grid = 16 // w                                   # elements per 16 bytes
     specs = []
-    for kind in ("row", "col", "scalar", "pitch"):
+    for kind in ("row", "col", "scalar", "pitch", "strided", "transposed"):
         # rows on the grid (pitch a multiple of 16 bytes, no shift): row groups
         specs.append(dict(dtype=dtype, rows=37, cols=3 * grid + 1, kind=kind, cand_pad=grid - 1, cand_shift=0, ref_pad=2, ref_shift=1))
         # rows off the grid: shifted first items and plain tails, row by row
@@ -140,7 +184,7 @@ def test_four_layouts_every_dtype(oracle_mod, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-@pytest.mark.parametrize("kind", ["row", "col", "pitch"])
+@pytest.mark.parametrize("kind", ["row", "col", "pitch", "transposed"])
 def test_rows_longer_than_work_items(oracle_mod, dtype, kind):
     """Rows of more than two full work items plus a tail: the items inside a row are as long as full ones but
     take the guarded path, since their reference lies elsewhere; rows start on and off the grid."""
@@ -171,7 +215,7 @@ def test_random_mapped_plan(oracle_mod, seed):
             rows = max(1, 30000 // cols)
         on_grid = bool(rng.integers(0, 2))
         cand_pad = int((-cols) % grid + grid * rng.integers(0, 3)) if on_grid else int(rng.integers(0, 9))
-        specs.append(dict(dtype=dtype, rows=rows, cols=cols, kind=str(rng.choice(["row", "col", "scalar", "pitch"])),
+        specs.append(dict(dtype=dtype, rows=rows, cols=cols, kind=str(rng.choice(["row", "col", "scalar", "pitch", "strided", "transposed"])),
                           cand_pad=cand_pad, cand_shift=0 if on_grid else int(rng.integers(0, 2 * grid)),
                           ref_pad=int(rng.integers(0, 5)), ref_shift=int(rng.integers(0, 7))))
         tols.append((float(rng.choice([0.0, 1e-3, 0.25])), float(rng.choice([0.0, 1e-2, 0.125]))))
@@ -221,8 +265,8 @@ def test_mapped_plan_argument_errors():
     st, plan = B.geak_check_plan_mapped([ok], None, 2, 0.0, 0.0, False, 0)
     assert st == B.GEAK_OK
     B.geak_check_destroy(plan)
-    for bad, code in (((0, 4, 8, 32, 0, 0, 2, "f32"), B.GEAK_EINVAL),          # stride other than 0 / 1
-                      ((0, 4, 8, 32, 0, 0, -1, "f32"), B.GEAK_EINVAL),
+    for bad, code in (((0, 4, 8, 32, 0, 0, -1, "f32"), B.GEAK_EINVAL),         # negative stride
+                      ((0, 4, 8, 32, 0, 0, 1 << 22, "f32"), B.GEAK_EBOUNDS),   # stride too long
                       ((0, 4, 8, 32, 2, 0, 1, "f32"), B.GEAK_EALIGN),          # reference offset off the element grid
                       ((0, 4, 8, 32, 0, 6, 1, "f32"), B.GEAK_EALIGN),          # reference pitch off the element grid
                       ((0, 4, 8, 30, 0, 0, 1, "f32"), B.GEAK_EALIGN),          # candidates' pitch

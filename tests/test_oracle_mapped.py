@@ -59,3 +59,23 @@ def test_same_layout_on_both_sides_is_the_plain_check(oracle_mod, dtype):
     plain = oracle_mod.check_segment(b, a, rows * row_elems, dtype, 1e-3, 1e-3, True)
     mapped = oracle_mod.check_segment_mapped(raw_ref, raw_cand, rows, row_elems, dtype, 1e-3, 1e-3, True, 16, pitch, 16, pitch)
     assert record_tuple(plain) == record_tuple(mapped)
+
+
+def test_transposed_reference_equals_plain_check_of_its_transpose(oracle_mod):
+    """A reference stored transposed (element (r, c) at c * rows + r: rows one element apart, neighbours of a row
+    `rows` apart) judged through the index map gives the record of the plain check against its transpose written
+    out by the library's transpose."""
+    rng = np.random.default_rng(41)
+    rows, cols = 13, 29
+    b = rng.normal(size=(rows, cols)).astype(np.float32)
+    a = (b * (1 + 2e-3 * rng.normal(size=b.shape))).astype(np.float32)
+    stored = np.ascontiguousarray(b.T)                              # cols x rows
+    got = oracle_mod.check_segment_mapped(stored.view(np.uint8).reshape(-1), a.view(np.uint8).reshape(-1), rows, cols, "f32",
+                                          1e-3, 1e-3, False, 0, cols * 4, 0, 4, rows)
+    want = oracle_mod.check_segment(b.reshape(-1), a.reshape(-1), rows * cols, "f32", 1e-3, 1e-3, False)
+    assert all(got[f] == want[f] for f in got.dtype.names) and int(got["mismatch_count"]) > 0
+    # every third element of a longer row
+    wide = rng.integers(0, 100, size=(rows, 3 * cols + 5)).astype(np.int32)
+    picked = np.ascontiguousarray(wide[:, 2::3][:, :cols])
+    g = oracle_mod.gather_rows(wide.view(np.uint8).reshape(-1), rows, cols, "i32", 8, (3 * cols + 5) * 4, 3)
+    assert (g.view(np.int32) == picked.reshape(-1)).all()

@@ -435,7 +435,8 @@ def test_mapped_reference_table(lib):
             (50003, 4, 1000, 1003, 77, 3, 0, "u8"),                    # one element per row, 3 bytes apart; rows off the grid
             (60000, 5, 9, 80, 4096, 0, 0, "f64"),                      # one element for all
             (70000, 0, 9, 72, 0, 0, 1, "f64"),                         # empty
-            (80000, 2, 2048, 2048 * 4, 0, 2048 * 4, 1, "f32")]         # rows back to back, each two full-length items
+            (80000, 2, 2048, 2048 * 4, 0, 2048 * 4, 1, "f32"),         # rows back to back, each two full-length items
+            (100000, 3, 1500, 6000, 8, 4, 3, "f32")]                   # stored transposed: rows 4 bytes apart, elements 3 apart
     st, plan = B.geak_check_plan_mapped(segs, None, 3, 1e-3, 1e-3, 0, -1)
     assert st == B.GEAK_OK
     items = B.geak_check_plan_items(plan)
@@ -443,8 +444,8 @@ def test_mapped_reference_table(lib):
     info = B.geak_check_plan_info(plan)
     assert len(ref_off) == len(items) == info.num_items
     # candidates' elements K times, the reference's distinct elements once
-    cand_bytes = 3 * 5000 * 2 + 7 * 100 * 4 + 4 * 1000 + 5 * 9 * 8 + 2 * 2048 * 4
-    ref_bytes = 5000 * 2 + 7 * 100 * 4 + 4 * 1 + 8 + 2 * 2048 * 4
+    cand_bytes = 3 * 5000 * 2 + 7 * 100 * 4 + 4 * 1000 + 5 * 9 * 8 + 2 * 2048 * 4 + 3 * 1500 * 4
+    ref_bytes = 5000 * 2 + 7 * 100 * 4 + 4 * 1 + 8 + 2 * 2048 * 4 + 3 * 1500 * 4
     assert info.algorithmic_bytes == 3 * cand_bytes + ref_bytes
     covered = {}
     for it, ro in zip(items, ref_off):
@@ -464,7 +465,7 @@ def test_mapped_reference_table(lib):
             assert c + n <= cols
         assert e0 == covered.get(s, 0)
         covered[s] = e0 + n
-    assert covered == {0: 15000, 1: 700, 2: 4000, 3: 45, 5: 4096}
+    assert covered == {0: 15000, 1: 700, 2: 4000, 3: 45, 5: 4096, 6: 4500}
     assert all(i["flags"] & B.GEAK_ITEM_ROWS for i in items if i["segment"] in (1, 3))
     assert [int(i["numel"]) for i in items if i["segment"] == 5] == [1024, 1024, 1024, 1024]
     B.geak_check_destroy(plan)
@@ -476,8 +477,9 @@ def test_mapped_reference_table(lib):
 
 
 @pytest.mark.parametrize("seg,status", [
-    ((0, 4, 8, 32, 0, 0, 2, "f32"), B.GEAK_EINVAL),               # stride other than 0 / 1
-    ((0, 4, 8, 32, 0, 0, -1, "f32"), B.GEAK_EINVAL),
+    ((0, 4, 8, 32, 0, 0, -1, "f32"), B.GEAK_EINVAL),              # negative stride
+    ((0, 4, 8, 32, 0, 0, 1 << 22, "f32"), B.GEAK_EBOUNDS),        # stride too long
+    ((0, 4, 2 ** 39, 2 ** 41, 0, 0, (1 << 22) - 1, "f32"), B.GEAK_EBOUNDS),   # the strided row leaves the address space
     ((0, 4, 8, 32, 2, 0, 1, "f32"), B.GEAK_EALIGN),               # reference offset off the element grid
     ((0, 4, 8, 32, 0, 6, 1, "f32"), B.GEAK_EALIGN),               # reference pitch off the element grid
     ((0, 4, 8, 30, 0, 0, 1, "f32"), B.GEAK_EALIGN),               # the candidates' pitch
