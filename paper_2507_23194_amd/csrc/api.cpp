@@ -145,7 +145,7 @@ geak_status geak_check_plan_mx(geak_plan **out, const geak_segment_mx *segs, con
         if (g.reserved != 0) return GEAK_EINVAL;
         if (!is_mx_dtype(g.dtype)) return GEAK_EDTYPE;
         // one contiguous row of one-byte elements; the scales' offset travels in the record's reference field
-        descs[s] = SegDesc{g.byte_offset, g.numel, g.numel ? g.numel : 1, g.numel, g.dtype, kMxScaled, g.scale_byte_offset, 0};
+        descs[s] = SegDesc{g.byte_offset, g.numel, g.numel ? g.numel : 1, payload_bytes(g.dtype, g.numel), g.dtype, kMxScaled, g.scale_byte_offset, 0};
     }
     return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
 }

@@ -73,9 +73,12 @@ template <> struct Traits<GEAK_F8E5M2> { static constexpr int E = 16, W = 1; };
 template <> struct Traits<GEAK_MXFP8_E4M3> { static constexpr int E = 16, W = 1; };
 template <> struct Traits<GEAK_MXFP8_E5M2> { static constexpr int E = 16, W = 1; };
 template <> struct Traits<GEAK_MXINT8>     { static constexpr int E = 16, W = 1; };
+// The four-bit format never reaches the arithmetic as such: the loads rewrite sixteen E2M1 codes (8 bytes) as the
+// sixteen E4M3 byte codes of the same values, so a lane's "vector" is sixteen elements here too.
+template <> struct Traits<GEAK_MXFP4_E2M1> { static constexpr int E = 16, W = 1; };
 // Block-scaled element formats: a 16-byte vector holds half a block of 32 elements, so one scale byte
 // belongs to every vector.
-template <int DT> constexpr bool kScaled = (DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP8_E5M2 || DT == GEAK_MXINT8);
+template <int DT> constexpr bool kScaled = (DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP8_E5M2 || DT == GEAK_MXINT8 || DT == GEAK_MXFP4_E2M1);
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ double bits_d(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(double, (u64)lo | ((u64)hi << 32)); }
@@ -170,10 +173,41 @@ __device__ __forceinline__ u32x4 load_partial(global_vec_ptr p, uint32_t valid)
 // straddles the end is loaded and cut, vectors past the end are not loaded, and everything past the
 // end reads as 0 -- in the reference and in every candidate alike, so that those positions compare
 // as close and add nothing to either maximum.
+// Sixteen E2M1 codes -- two per byte, the even element in the low nibble: the 64 bits {lo, hi} -- rewritten as
+// the sixteen E4M3 byte codes of the same values (0, 0.5, 1, 1.5, 2, 3, 4, 6 are 0x00, 0x30, 0x38, 0x3C, 0x40, 0x44,
+// 0x48, 0x4C; bit 3 of a nibble is the sign): the nibbles of 16 bits are spread into four bytes, and one byte permute
+// looks all four magnitudes up.
+__device__ __forceinline__ uint32_t e2m1_four(uint32_t h16)
+{
+    const uint32_t t = (h16 | (h16 << 8)) & 0x00FF00FFu;
+    const uint32_t u = (t | (t << 4)) & 0x0F0F0F0Fu;
+    const uint32_t code = __builtin_amdgcn_perm(0x4C484440u, 0x3C383000u, u & 0x07070707u);     // selector i: byte i of the table
+    return code | ((u & 0x08080808u) << 4);
+}
+__device__ __forceinline__ u32x4 expand_e2m1(uint32_t lo, uint32_t hi)
+{
+    u32x4 q;
+    q[0] = e2m1_four(lo & 0xFFFFu); q[1] = e2m1_four(lo >> 16);
+    q[2] = e2m1_four(hi & 0xFFFFu); q[3] = e2m1_four(hi >> 16);
+    return q;
+}
+// Slot `slot` of an item of the four-bit format: 8 bytes of payload, as sixteen byte codes.
+__device__ __forceinline__ u32x4 load_e2m1_slot(const unsigned char *base, uint32_t slot)
+{
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 w = __builtin_nontemporal_load((const GEAK_AS_GLOBAL u32x2 *)base + slot);
+    return expand_e2m1(w[0], w[1]);
+}
+
 template <int DT>
 __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, int v, uint32_t n, bool full)
 {
     constexpr uint32_t E = Traits<DT>::E;
+    if constexpr (DT == GEAK_MXFP4_E2M1) {              // whole blocks only: a slot is inside the item or behind it
+        const uint32_t slot = (uint32_t)(v * kWaveSize + lane);
+        if (full || slot * E < n) return load_e2m1_slot(base, slot);
+        return u32x4{0u, 0u, 0u, 0u};
+    }
     global_vec_ptr p = (global_vec_ptr)base + (v * kWaveSize + lane);
     if (full) return __builtin_nontemporal_load(p);
     const uint32_t first = (uint32_t)(v * kWaveSize + lane) * E;
@@ -252,6 +286,10 @@ __device__ __forceinline__ u32x4 load_slot(const unsigned char *base, uint32_t s
 {
     const SlotPlace sp = slot_place<DT, KIND>(slot, n, sh);
     first = sp.first;
+    if constexpr (DT == GEAK_MXFP4_E2M1) {              // plain tails of whole blocks only
+        if (sp.valid > 0) return load_e2m1_slot(base, sp.vec);
+        return u32x4{0u, 0u, 0u, 0u};
+    }
     if constexpr (KIND == kTailRows) return load_partial_from<DT>((global_vec_ptr)(base + (u64)sp.row * sh.pitch) + sp.vec, sp.lo, sp.valid);
     else return load_partial_from<DT>((global_vec_ptr)base + sp.vec, sp.lo, sp.valid);
 }
@@ -345,7 +383,7 @@ __device__ __forceinline__ u32x4 load_shaped(const unsigned char *base, int lane
 template <int DT, int BYTE>
 __device__ __forceinline__ float f8_to_f32(uint32_t word)
 {
-    if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3) return __builtin_amdgcn_cvt_f32_fp8((int)word, BYTE);
+    if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP4_E2M1) return __builtin_amdgcn_cvt_f32_fp8((int)word, BYTE);
     else if constexpr (DT == GEAK_MXINT8) return (float)((int)(word << (24 - 8 * BYTE)) >> 24);     // the code as an integer; the scale carries the 1/64
     else return __builtin_amdgcn_cvt_f32_bf8((int)word, BYTE);
 }
@@ -360,7 +398,7 @@ __device__ __forceinline__ F32Pair f8_pair_to_f32(uint32_t word)
         return F32Pair{f8_to_f32<DT, HI ? 2 : 0>(word), f8_to_f32<DT, HI ? 3 : 1>(word)};
     } else {
         f32x2 v;
-        if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3) v = __builtin_amdgcn_cvt_pk_f32_fp8((int)word, HI);
+        if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP4_E2M1) v = __builtin_amdgcn_cvt_pk_f32_fp8((int)word, HI);
         else v = __builtin_amdgcn_cvt_pk_f32_bf8((int)word, HI);
         return F32Pair{v[0], v[1]};
     }
@@ -439,6 +477,7 @@ __device__ __forceinline__ void for_scaled_dtype(int dtype, F &&f)
     switch (dtype) {
     case GEAK_MXFP8_E4M3: f(Index<GEAK_MXFP8_E4M3>{}); break;
     case GEAK_MXFP8_E5M2: f(Index<GEAK_MXFP8_E5M2>{}); break;
+    case GEAK_MXFP4_E2M1: f(Index<GEAK_MXFP4_E2M1>{}); break;
     default:              f(Index<GEAK_MXINT8>{}); break;
     }
 }

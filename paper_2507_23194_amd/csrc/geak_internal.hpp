@@ -22,8 +22,17 @@ inline int elem_size(int dtype)
     case GEAK_I64: case GEAK_F64: return 8;
     case GEAK_U8: case GEAK_I8: case GEAK_F8E4M3: case GEAK_F8E5M2: return 1;
     case GEAK_MXFP8_E4M3: case GEAK_MXFP8_E5M2: case GEAK_MXINT8: return 1;       // the payload's elements
+    case GEAK_MXFP4_E2M1: return 1;                                               // nominal: a byte holds two (payload_bytes)
     default: return 4;
     }
+}
+
+// Bytes that n elements of a dtype occupy (n even for the four-bit format), and elements of one full work item.
+inline uint64_t payload_bytes(int dtype, uint64_t n) { return dtype == GEAK_MXFP4_E2M1 ? n / 2 : n * (uint64_t)elem_size(dtype); }
+inline uint64_t elems_per_item(int dtype)
+{
+    // the four-bit codes are rewritten as byte codes when they are loaded: an item is 4096 of them, 2 KiB of payload
+    return dtype == GEAK_MXFP4_E2M1 ? (uint64_t)kItemBytes : (uint64_t)kItemBytes / (uint64_t)elem_size(dtype);
 }
 
 // Partial result of one (worker, segment) run for one candidate; 16 bytes.
@@ -66,7 +75,7 @@ constexpr int32_t kRefMapped = 1, kMxScaled = 4;
 constexpr int kRefStrideShift = 8;
 constexpr uint64_t kMaxRefStride = (1ull << 22) - 1;
 constexpr uint64_t kMxBlock = 32;
-inline bool is_mx_dtype(int dtype) { return dtype >= GEAK_MXFP8_E4M3 && dtype <= GEAK_MXINT8; }
+inline bool is_mx_dtype(int dtype) { return dtype >= GEAK_MXFP8_E4M3 && dtype <= GEAK_MXFP4_E2M1; }
 struct SegDesc {
     uint64_t byte_offset;
     uint64_t numel;
@@ -84,7 +93,7 @@ constexpr uint64_t seg_ref_stride(const SegDesc &g) { return (uint32_t)g.layout 
 // bytes from the segment's first to behind its last element
 inline uint64_t seg_span(const SegDesc &g)
 {
-    return g.numel ? (seg_rows(g) - 1) * g.pitch_bytes + g.row_elems * (uint64_t)elem_size(g.dtype) : 0;
+    return g.numel ? (seg_rows(g) - 1) * g.pitch_bytes + payload_bytes(g.dtype, g.row_elems) : 0;
 }
 // bytes of one row of a mapped segment's reference, first to behind last element (the planner refuses what would overflow)
 inline uint64_t seg_ref_row_span(const SegDesc &g)

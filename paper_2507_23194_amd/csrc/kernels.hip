@@ -1159,6 +1159,7 @@ template <> struct ItemOf<GEAK_F8E5M2> { typedef Fp8Item<GEAK_F8E5M2> type; };
 template <> struct ItemOf<GEAK_MXFP8_E4M3> { typedef Fp8Item<GEAK_MXFP8_E4M3> type; };
 template <> struct ItemOf<GEAK_MXFP8_E5M2> { typedef Fp8Item<GEAK_MXFP8_E5M2> type; };
 template <> struct ItemOf<GEAK_MXINT8> { typedef Fp8Item<GEAK_MXINT8> type; };
+template <> struct ItemOf<GEAK_MXFP4_E2M1> { typedef Fp8Item<GEAK_MXFP4_E2M1> type; };
 
 __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 {
@@ -1831,6 +1832,11 @@ template <int DT>
 __device__ __forceinline__ float elem_f(const unsigned char *base, u64 idx)
 {
     if constexpr (DT == GEAK_F32) return reinterpret_cast<const float *>(base)[idx];
+    else if constexpr (DT == GEAK_MXFP4_E2M1) {             // element idx is a nibble of byte idx / 2; its E4M3 code from the same table as the loads'
+        const uint32_t nib = ((uint32_t)base[idx >> 1] >> (4 * (uint32_t)(idx & 1))) & 0xFu;
+        const uint32_t code = (uint32_t)((0x4C4844403C383000ull >> (8 * (nib & 7u))) & 0xFFu) | ((nib & 8u) << 4);
+        return f8_to_f32<DT, 0>(code);
+    }
     else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2 || kScaled<DT>) return f8_to_f32<DT, 0>(base[idx]);     // block-scaled: the bare code's value
     else if constexpr (DT == GEAK_F16) return (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t *>(base)[idx]);
     else return bits_f((uint32_t)reinterpret_cast<const uint16_t *>(base)[idx] << 16);

@@ -31,7 +31,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
     bool any_mapped = false;
     for (uint64_t s = 0; s < nsegs; ++s) {
         const SegDesc &g = segs[s];
-        if (g.dtype < GEAK_F32 || g.dtype > GEAK_MXINT8) return GEAK_EDTYPE;
+        if (g.dtype < GEAK_F32 || g.dtype > GEAK_MXFP4_E2M1) return GEAK_EDTYPE;
         if (is_mx_dtype(g.dtype) != (g.layout == kMxScaled)) return GEAK_EDTYPE;     // block-scaled element formats belong to block-scaled segments only
         if (g.layout != kMxScaled && g.layout != 0 && (!(g.layout & kRefMapped) || (g.layout & 0xFE) != 0 || g.layout < 0 ||
                                                        seg_ref_stride(g) > kMaxRefStride)) return GEAK_EINVAL;
@@ -49,10 +49,10 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         if (g.byte_offset % w != 0 || g.pitch_bytes % w != 0) return GEAK_EALIGN;
         if (g.numel > GEAK_MAX_SEGMENT_NUMEL) return GEAK_EBOUNDS;
         if (mul_overflows(g.numel, w)) return GEAK_EBOUNDS;
-        const uint64_t bytes = g.numel * w;
+        const uint64_t bytes = payload_bytes(g.dtype, g.numel);
         // rows must not run into each other, and the last one must end inside the address space
         if (g.numel) {
-            const uint64_t row_bytes = g.row_elems * w;             // <= bytes: no overflow
+            const uint64_t row_bytes = payload_bytes(g.dtype, g.row_elems);     // <= bytes: no overflow
             if (g.pitch_bytes < row_bytes) return GEAK_EBOUNDS;
             if (mul_overflows(seg_rows(g) - 1, g.pitch_bytes)) return GEAK_EBOUNDS;
             if ((seg_rows(g) - 1) * g.pitch_bytes > UINT64_MAX - row_bytes) return GEAK_EBOUNDS;
@@ -102,7 +102,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         uint64_t n_items = 0;
         for (uint64_t s = 0; s < nsegs; ++s) {
             const SegDesc &g = segs[s];
-            const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
+            const uint64_t w = elem_size(g.dtype), per = elems_per_item(g.dtype);
             if (!g.numel) continue;
             const uint64_t rows = seg_rows(g);
             const uint64_t row_vectors = (g.row_elems * w + 15) / 16;
@@ -148,7 +148,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
 
         for (uint64_t s = 0; s < nsegs; ++s) {
             const SegDesc &g = segs[s];
-            const uint64_t w = elem_size(g.dtype), per = kItemBytes / w;
+            const uint64_t w = elem_size(g.dtype), per = elems_per_item(g.dtype);
             const bool mapped = seg_ref_mapped(g);
             const uint64_t ref_stride = mapped ? seg_ref_stride(g) : 1;
             if (!g.numel) continue;
@@ -182,7 +182,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                 uint64_t done = 0;
                 auto push = [&](uint64_t n, bool full) {
                     geak_item it{};
-                    it.byte_offset = row_start + done * w;
+                    it.byte_offset = row_start + payload_bytes(g.dtype, done);     // done is even for the four-bit format
                     it.elem_start = r * g.row_elems + done;
                     it.segment = (uint32_t)s;
                     it.numel = (uint16_t)n;

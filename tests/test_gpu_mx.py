@@ -1,6 +1,6 @@
 """Block-scaled (MX) segments on the GPU against the oracle's front end (oracle/mx.py: every element written
 out as the binary32 value it encodes, then the unchanged rule): records and mismatch reports for the three
-one-byte element formats, all payload codes and scale bytes (2^-127, 2^127, NaN among them), candidates whose
+one-byte element formats and the four-bit one, all payload codes and scale bytes (2^-127, 2^127, NaN among them), candidates whose
 payload, scales or both differ, sizes from one block to several work items with every tail shape."""
 import numpy as np
 import pytest
@@ -12,12 +12,14 @@ from test_gpu_parity import _assert_same
 
 pytestmark = pytest.mark.gpu
 
-FORMATS = ["mxfp8e4m3", "mxfp8e5m2", "mxint8"]
+FORMATS = ["mxfp8e4m3", "mxfp8e5m2", "mxint8", "mxfp4e2m1"]
 
 
 def _tensors(rng, fmt, n, K):
-    """(payload, scales) of the reference and of K candidates."""
+    """(payload, scales) of the reference and of K candidates; n elements (the four-bit format: n / 2 payload bytes,
+    every byte two codes, so what follows perturbs codes of either half)."""
     nb = n // 32
+    n = n * mx.MX_BITS[fmt] // 8                          # payload bytes from here on
     payload = rng.integers(0, 256, n).astype(np.uint8)
     scales = rng.integers(110, 140, nb).astype(np.uint8)
     pick = rng.random(nb)
@@ -48,7 +50,7 @@ def _tensors(rng, fmt, n, K):
             blk = rng.random(nb) < 0.1
             s[blk] = rng.integers(0, 256, int(blk.sum())).astype(np.uint8)
         else:                                              # one element, the last
-            p[n - 1] ^= 0x11
+            p[n - 1] ^= 0x10                               # (the high nibble: the four-bit format's last element too)
         out.append((p, s))
     return out
 
@@ -60,9 +62,9 @@ def _pack(tensors_per_segment):
     parts = [[] for _ in range(ntens)]
     table, off = [], 0
     for seg in tensors_per_segment:
-        n, nb = seg[0][0].size, seg[0][1].size
+        n, nb = seg[0][0].size, seg[0][1].size            # payload bytes, blocks
         pad = (-(n + nb + 3)) % 16
-        table.append((off, n, off + n + 3))
+        table.append((off, nb * 32, off + n + 3))
         for t, (p, s) in enumerate(seg):
             parts[t].append(np.concatenate([p, np.full(3, 0xEE, np.uint8), s, np.full(pad, 0xDD, np.uint8)]))
         off += n + 3 + nb + pad
@@ -87,7 +89,7 @@ def _compare(oracle_mod, segs, fmts, K, atol, rtol, equal_nan, what):
     rec, rep, cnt = _gpu(bufs, table, fmts, K, atol, rtol, equal_nan)
     cpu = np.zeros((len(segs), K), dtype=rec.dtype)
     for s, seg in enumerate(segs):
-        n = seg[0][0].size
+        n = seg[0][1].size * 32
         b = mx.dequantize(seg[0][0], seg[0][1], n, fmts[s])
         for k in range(K):
             a = mx.dequantize(seg[k + 1][0], seg[k + 1][1], n, fmts[s])
@@ -104,7 +106,7 @@ def _compare(oracle_mod, segs, fmts, K, atol, rtol, equal_nan, what):
 
 
 @pytest.mark.parametrize("fmt", FORMATS)
-@pytest.mark.parametrize("n", [32, 5 * 32, 1024 + 32, 4096 + 64, 3 * 4096 + 31 * 32, 6 * 4096])
+@pytest.mark.parametrize("n", [32, 5 * 32, 1024 + 32, 4096 + 64, 3 * 4096 + 31 * 32, 6 * 4096, 2 * 8192 + 96])
 def test_one_segment(oracle_mod, fmt, n):
     print("mx", fmt, n, flush=True)
     rng = np.random.default_rng(8800 + n + FORMATS.index(fmt))
@@ -122,7 +124,7 @@ def test_several_segments_of_all_formats(oracle_mod):
     rng = np.random.default_rng(8900)
     K = 7
     sizes = [64, 2048, 4096 * 2 + 512, 32, 4096, 1024 + 64, 4096 * 3]
-    fmts = [FORMATS[i % 3] for i in range(len(sizes))]
+    fmts = [FORMATS[i % 4] for i in range(len(sizes))]
     segs = [_tensors(rng, f, n, K) for f, n in zip(fmts, sizes)]
     bufs, table = _pack(segs)
     tols = [(10.0 ** -(i % 3), 0.05 * (i % 4)) for i in range(len(sizes))]
@@ -151,7 +153,7 @@ def test_random_block_scaled_plan(oracle_mod, seed):
     work items), random candidate count and per-segment tolerances; records and reports against the oracle."""
     rng = np.random.default_rng(9500 + seed)
     nsegs, K = int(rng.integers(1, 7)), int(rng.integers(1, 10))
-    fmts = [FORMATS[int(rng.integers(0, 3))] for _ in range(nsegs)]
+    fmts = [FORMATS[int(rng.integers(0, 4))] for _ in range(nsegs)]
     sizes = [32 * int(rng.choice([1, int(rng.integers(2, 33)), int(rng.integers(33, 129)), int(rng.integers(129, 400))])) for _ in range(nsegs)]
     print("random block-scaled plan", seed, list(zip(fmts, sizes)), "K", K, flush=True)
     segs = [_tensors(rng, f, n, K) for f, n in zip(fmts, sizes)]
@@ -207,9 +209,10 @@ def test_extreme_products(oracle_mod):
     print("mx extremes", flush=True)
     n = 64
     for fmt in FORMATS:
-        codes = np.tile(np.array([0x01, 0x7E, 0xFE, 0x00, 0x80, 0x7B, 0x81, 0x08], np.uint8), n // 8)
+        nbytes = n * mx.MX_BITS[fmt] // 8
+        codes = np.tile(np.array([0x01, 0x7E, 0xFE, 0x00, 0x80, 0x7B, 0x81, 0x08], np.uint8), nbytes // 8)
         cand = codes.copy()
-        cand[[1, 9, 33]] = [0x7D, 0x02, 0x7D]
+        cand[[1, 9, nbytes - 7]] = [0x7D, 0x02, 0x7D]
         for lo, hi in ((0, 254), (1, 253)):
             s = np.array([lo, hi], np.uint8)
             segs = [[(codes, s), (cand, s), (codes, s[::-1].copy())]]

@@ -513,6 +513,17 @@ def test_block_scaled_plan_table(lib):
     assert all(int(i["elem_start"]) % 32 == 0 for i in items)           # an item starts with a block
     assert len(B.geak_check_plan_ref_offsets(plan)) == 0
     B.geak_check_destroy(plan)
+    # the four-bit format: two elements per byte, a full item is 4096 elements = 2 KiB of payload
+    st, plan = B.geak_check_plan_mx([(64, 4096 * 2 + 96, 9000, "mxfp4e2m1")], None, 2, 0, 0, 0, -1)
+    assert st == B.GEAK_OK
+    items = B.geak_check_plan_items(plan)
+    assert [(int(i["byte_offset"]), int(i["elem_start"]), int(i["numel"]), bool(i["flags"] & B.GEAK_ITEM_FULL)) for i in items] == \
+        [(64, 0, 4096, True), (64 + 2048, 4096, 4096, True), (64 + 4096, 8192, 96, False)]
+    assert B.geak_check_plan_info(plan).algorithmic_bytes == 3 * ((8192 + 96) // 2 + (8192 + 96) // 32)
+    B.geak_check_destroy(plan)
+    # its payload is half as long: scales may sit where a one-byte format's payload would still run
+    assert B.geak_check_plan_mx([(0, 64, 32, "mxfp4e2m1")], None, 1, 0, 0, 0, -1)[0] == B.GEAK_OK
+    assert B.geak_check_plan_mx([(0, 64, 31, "mxfp4e2m1")], None, 1, 0, 0, 0, -1)[0] == B.GEAK_EBOUNDS
 
 
 @pytest.mark.parametrize("seg,status", [
@@ -520,13 +531,13 @@ def test_block_scaled_plan_table(lib):
     ((0, 40, 100, "mxfp8e4m3"), B.GEAK_EINVAL),                # ragged last block
     ((0, 64, 63, "mxfp8e4m3"), B.GEAK_EBOUNDS),                # scales inside the payload
     ((0, 64, 100, "f8e4m3"), B.GEAK_EDTYPE),                   # not a block-scaled element format
-    ((0, 64, 100, 13), B.GEAK_EDTYPE),
+    ((0, 64, 100, 14), B.GEAK_EDTYPE),
     ((0, 64, 2 ** 64 - 1, "mxint8"), B.GEAK_EBOUNDS),
 ])
 def test_block_scaled_plan_rejects(lib, seg, status):
     st, plan = B.geak_check_plan_mx([seg], None, 2, 0.0, 0.0, False, -1)
     assert st == status and plan is None
-    for code in (B.GEAK_MXFP8_E4M3, B.GEAK_MXFP8_E5M2, B.GEAK_MXINT8):    # these codes are not for the other plan calls
+    for code in (B.GEAK_MXFP8_E4M3, B.GEAK_MXFP8_E5M2, B.GEAK_MXINT8, B.GEAK_MXFP4_E2M1):    # these codes are not for the other plan calls
         assert B.geak_check_plan([(0, 64, code)], 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
         assert B.geak_check_plan_pitched([(0, 2, 32, 32, code)], None, 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
         assert B.geak_check_plan_mapped([(0, 2, 32, 32, 0, 0, 1, code)], None, 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
