@@ -360,10 +360,11 @@ __device__ __forceinline__ u32x4 load_ref_slot(const unsigned char *ref_base, co
     }
     if (sp.valid > sp.lo) {
         uint32_t w0, w1 = 0u;
-        if constexpr (W == 1) { w0 = *row; w0 |= w0 << 8; w0 |= w0 << 16; w1 = w0; }
-        else if constexpr (W == 2) { w0 = *reinterpret_cast<const uint16_t *>(row); w0 |= w0 << 16; w1 = w0; }
-        else if constexpr (W == 4) { w0 = *reinterpret_cast<const uint32_t *>(row); w1 = w0; }
-        else { w0 = reinterpret_cast<const uint32_t *>(row)[0]; w1 = reinterpret_cast<const uint32_t *>(row)[1]; }
+        const GEAK_AS_GLOBAL unsigned char *one = (const GEAK_AS_GLOBAL unsigned char *)row;        // the row's one element
+        if constexpr (W == 1) { w0 = *one; w0 |= w0 << 8; w0 |= w0 << 16; w1 = w0; }
+        else if constexpr (W == 2) { w0 = *(const GEAK_AS_GLOBAL uint16_t *)one; w0 |= w0 << 16; w1 = w0; }
+        else if constexpr (W == 4) { w0 = *(const GEAK_AS_GLOBAL uint32_t *)one; w1 = w0; }
+        else { w0 = ((const GEAK_AS_GLOBAL uint32_t *)one)[0]; w1 = ((const GEAK_AS_GLOBAL uint32_t *)one)[1]; }
         q[0] = w0; q[1] = w1; q[2] = w0; q[3] = w1;
         if (sp.lo != 0 || sp.valid < E) q = cut_vector_call(q, (int)(sp.lo * W), (int)((sp.valid < E ? sp.valid : E) * W));
     }

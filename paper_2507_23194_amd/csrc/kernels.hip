@@ -939,8 +939,6 @@ struct Fp8Item {
     TolStore<E, true> tol;
     __device__ __forceinline__ void attach_lds(uint32_t region, int lane) { tol.attach(region, lane); }
 
-    template <int e> static __device__ __forceinline__ float value(const uint32_t *words) { return f8_to_f32<DT, e & 3>(words[e >> 2]); }
-    template <int e> static __device__ __forceinline__ float value(const u32x4 &q) { return f8_to_f32<DT, e & 3>(q[e >> 2]); }
 
     template <int V>
     __device__ __forceinline__ void stage_vec(const u32x4 &q, const SegTol &tolerance)
