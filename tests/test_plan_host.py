@@ -543,3 +543,114 @@ def test_block_scaled_plan_rejects(lib, seg, status):
         assert B.geak_check_plan_mapped([(0, 2, 32, 32, 0, 0, 1, code)], None, 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
     st, plan = B.geak_check_plan_mx([(0, 64, 1000, "mxint8"), (64, 64, 1001, "mxint8")], None, 1, 0.0, 0.0, False, -1)
     assert st == B.GEAK_EBOUNDS                                            # scale regions collide
+
+
+def _check_lists_and_runs(plan):
+    """The part of a plan that does not depend on how its segments are laid out: the block ranges partition the table, the
+    waves' lists hold every item exactly once and ascend, FIRST / LAST bracket the (wave, segment) runs, slots are unique to
+    their run and contiguous per segment."""
+    info = B.geak_check_plan_info(plan)
+    items = B.geak_check_plan_items(plan)
+    waves = info.block_threads // 64
+    blocks = B.geak_check_plan_blocks(plan).astype(np.int64)
+    assert len(blocks) == info.grid_blocks + 1 and blocks[0] == 0 and blocks[-1] == len(items)
+    assert (np.diff(blocks) > 0).all() or len(items) == 0
+    assert (np.diff(items["segment"].astype(np.int64)) >= 0).all()
+    first = B.geak_check_plan_waves(plan).astype(np.int64)
+    nxt = items["next"].astype(np.int64)
+    owner = np.full(len(items), -1, dtype=np.int64)
+    seen_slots = {}
+    for wv, j in enumerate(first):
+        b, last_j, open_slot = wv // waves, -1, None
+        while j != B.GEAK_NO_ITEM:
+            assert blocks[b] <= j < blocks[b + 1] and owner[j] == -1 and j > last_j
+            owner[j], last_j = wv, j
+            it = items[j]
+            if it["flags"] & B.GEAK_ITEM_FIRST:
+                assert open_slot is None and int(it["slot"]) not in seen_slots
+                open_slot = int(it["slot"])
+                seen_slots[open_slot] = int(it["segment"])
+            assert open_slot == int(it["slot"]) and seen_slots[open_slot] == int(it["segment"])
+            if it["flags"] & B.GEAK_ITEM_LAST:
+                open_slot = None
+            j = nxt[j]
+        assert open_slot is None
+    assert (owner >= 0).all() and sorted(seen_slots) == list(range(info.num_slots))
+    by_seg = {}
+    for slot, sg in seen_slots.items():
+        by_seg.setdefault(sg, []).append(slot)
+    assert all(max(sl) - min(sl) + 1 == len(sl) for sl in by_seg.values())
+    return info, items
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_mapped_and_block_scaled_tables(lib, seed):
+    """Seeded random plans of the two newer kinds: every element covered exactly once and in order, candidate and
+    reference offsets as the layout says, flags as documented, and the same list / run structure as every plan."""
+    rng = np.random.default_rng(700 + seed)
+    esize = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "i8": 1, "f64": 8, "f8e4m3": 1, "f8e5m2": 1}
+    K = int(rng.integers(1, 9))
+    # --- mapped references
+    segs, off = [], 0
+    for _ in range(int(rng.integers(1, 30))):
+        dt = list(esize)[int(rng.integers(0, len(esize)))]
+        w = esize[dt]
+        rows = int(rng.choice([0, 1, 2, int(rng.integers(3, 50)), int(rng.integers(50, 3000))]))
+        cols = int(rng.choice([1, int(rng.integers(2, 40)), int(rng.integers(40, 2048 // w + 1)), int(rng.integers(2048 // w, 5 * 4096 // w))]))
+        tight = cols * w
+        pitch = int(rng.choice([tight, (tight + 15) // 16 * 16, tight + w * int(rng.integers(1, 9))]))
+        off = (off + 15) // 16 * 16 if rng.random() < 0.5 else (off + w - 1) // w * w + w * int(rng.integers(0, 5))
+        stride = int(rng.choice([0, 1, 1, 1, 2, 7, max(rows, 1)]))
+        rpitch = w * int(rng.choice([0, 1, cols, cols + 3, (cols - 1) * max(stride, 1) + 1]))
+        segs.append((off, rows, cols, pitch, w * int(rng.integers(0, 100)), rpitch, stride, dt))
+        off += (rows - 1) * pitch + tight if rows else 0
+    st, plan = B.geak_check_plan_mapped(segs, None, K, 1e-3, 1e-3, 0, -1)
+    assert st == B.GEAK_OK, st
+    info, items = _check_lists_and_runs(plan)
+    ref_off = B.geak_check_plan_ref_offsets(plan)
+    assert len(ref_off) == len(items)
+    cursor = {}
+    for it, ro in zip(items, ref_off):
+        sg = int(it["segment"])
+        coff, rows, cols, pitch, roff, rpitch, stride, dt = segs[sg]
+        w = esize[dt]
+        e0, n = int(it["elem_start"]), int(it["numel"])
+        r, c = divmod(e0, cols)
+        assert e0 == cursor.get(sg, 0) and it["flags"] & B.GEAK_ITEM_REFMAP
+        assert int(it["byte_offset"]) == coff + r * pitch + c * w and int(ro) == roff + r * rpitch + c * w * stride
+        assert bool(it["flags"] & B.GEAK_ITEM_ALIGNED) == (int(it["byte_offset"]) % 16 == 0)
+        if it["flags"] & B.GEAK_ITEM_ROWS:
+            assert c == 0 and n % cols == 0 and coff % 16 == 0 and pitch % 16 == 0 and cols * w <= 2048 and rows > 1
+            assert not it["flags"] & B.GEAK_ITEM_FULL
+        else:
+            assert c + n <= cols
+            assert bool(it["flags"] & B.GEAK_ITEM_FULL) == (n * w == 4096 and int(it["byte_offset"]) % 16 == 0 and stride == 1)
+        cursor[sg] = e0 + n
+    assert all(cursor.get(sg, 0) == segs[sg][1] * segs[sg][2] for sg in range(len(segs)))
+    B.geak_check_destroy(plan)
+    # --- block-scaled segments
+    bits = {"mxfp8e4m3": 8, "mxfp8e5m2": 8, "mxint8": 8, "mxfp4e2m1": 4}
+    segs, off = [], 0
+    for _ in range(int(rng.integers(1, 30))):
+        fmt = list(bits)[int(rng.integers(0, 4))]
+        n = 32 * int(rng.choice([0, 1, int(rng.integers(2, 200)), int(rng.integers(200, 3000))]))
+        off = (off + 15) // 16 * 16
+        pb = n * bits[fmt] // 8
+        segs.append((off, n, off + pb + int(rng.integers(0, 7)), fmt))
+        off = segs[-1][2] + n // 32
+    st, plan = B.geak_check_plan_mx(segs, None, K, 1e-3, 1e-3, 0, -1)
+    assert st == B.GEAK_OK, st
+    info, items = _check_lists_and_runs(plan)
+    cursor = {}
+    for it in items:
+        sg = int(it["segment"])
+        poff, n_seg, soff, fmt = segs[sg]
+        e0, n = int(it["elem_start"]), int(it["numel"])
+        assert e0 == cursor.get(sg, 0) and e0 % 32 == 0 and n % 32 == 0 and 0 < n <= 4096
+        assert int(it["byte_offset"]) == poff + e0 * bits[fmt] // 8 and int(it["byte_offset"]) % 16 == 0
+        assert bool(it["flags"] & B.GEAK_ITEM_FULL) == (n == 4096)
+        assert it["flags"] & B.GEAK_ITEM_ALIGNED and not it["flags"] & (B.GEAK_ITEM_ROWS | B.GEAK_ITEM_REFMAP)
+        cursor[sg] = e0 + n
+    assert all(cursor.get(sg, 0) == segs[sg][1] for sg in range(len(segs)))
+    assert info.algorithmic_bytes == (K + 1) * sum(n * bits[f] // 8 + n // 32 for _, n, _, f in segs)
+    B.geak_check_destroy(plan)
