@@ -220,6 +220,37 @@ geak_status geak_check_plan_mx(geak_plan **out, const geak_segment_mx *segs, con
                                uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
                                int32_t equal_nan, int32_t device);
 
+/* One table for a batch whose unit-test outputs are of different kinds (section 3.3: a kernel is checked on all of
+ * its unit tests, and those need not produce the same kind of output): every entry is a plain or padded segment, a
+ * segment whose reference has a layout of its own, or a block-scaled segment, with the fields of geak_segment2d,
+ * geak_segment_mapped or geak_segment_mx and the same rules.
+ *   kind GEAK_KIND_PITCHED   byte_offset, rows, row_elems, pitch_bytes, dtype (a contiguous segment: rows = 1 and
+ *                            pitch_bytes = its length in bytes); the other fields 0
+ *   kind GEAK_KIND_MAPPED    all fields, as in geak_segment_mapped
+ *   kind GEAK_KIND_MX        byte_offset, rows = 1, row_elems = the element count, aux_byte_offset = the scales' offset,
+ *                            dtype one of the GEAK_MX* formats; pitch_bytes, aux_pitch_bytes and ref_elem_stride 0
+ * One plan, one launch, one result table in the entries' order; the ulp histogram is refused when any entry is
+ * block-scaled, the read probe when any entry's reference has its own layout. */
+enum { GEAK_KIND_PITCHED = 0, GEAK_KIND_MAPPED = 1, GEAK_KIND_MX = 2 };
+typedef struct {
+    uint64_t byte_offset;
+    uint64_t rows;
+    uint64_t row_elems;
+    uint64_t pitch_bytes;
+    uint64_t aux_byte_offset;    /* MAPPED: the reference's byte offset; MX: the scales' */
+    uint64_t aux_pitch_bytes;    /* MAPPED: bytes between the reference's rows */
+    int32_t  ref_elem_stride;    /* MAPPED */
+    int32_t  dtype;
+    int32_t  kind;               /* GEAK_KIND_* */
+    int32_t  reserved;           /* must be 0 */
+} geak_segment_any;
+
+/* `tols` may be null, then atol / rtol apply to all.  Errors as for the entry point of each kind; GEAK_EINVAL for an
+ * unknown kind or a field that the kind asks to be 0 and is not. */
+geak_status geak_check_plan_table(geak_plan **out, const geak_segment_any *segs, const geak_tolerance *tols,
+                                  uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
+                                  int32_t equal_nan, int32_t device);
+
 /* Dense convenience (section 3.1: one output tensor against its reference): a single segment at
  * offset 0 with prod(shape) elements; shape is a host array of ndim >= 0 non-negative extents
  * (ndim == 0 is a scalar).  Only the element count matters: indices are flat, row-major. */

@@ -39,6 +39,10 @@ SEGMENT_MAPPED_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_
                                  ("ref_byte_offset", "<u8"), ("ref_pitch_bytes", "<u8"), ("ref_elem_stride", "<i4"), ("dtype", "<i4")])
 SEGMENT_MX_DTYPE = np.dtype([("byte_offset", "<u8"), ("numel", "<u8"), ("scale_byte_offset", "<u8"), ("dtype", "<i4"), ("reserved", "<i4")])
 MX_DTYPE_CODE = {"mxfp8e4m3": GEAK_MXFP8_E4M3, "mxfp8e5m2": GEAK_MXFP8_E5M2, "mxint8": GEAK_MXINT8, "mxfp4e2m1": GEAK_MXFP4_E2M1}
+SEGMENT_ANY_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_elems", "<u8"), ("pitch_bytes", "<u8"),
+                              ("aux_byte_offset", "<u8"), ("aux_pitch_bytes", "<u8"), ("ref_elem_stride", "<i4"), ("dtype", "<i4"),
+                              ("kind", "<i4"), ("reserved", "<i4")])
+GEAK_KIND_PITCHED, GEAK_KIND_MAPPED, GEAK_KIND_MX = 0, 1, 2
 RESULT_DTYPE = np.dtype([("pass", "<i4"), ("reserved", "<i4"), ("mismatch_count", "<u8"),
                          ("first_mismatch", "<i8"), ("max_abs_err", "<f8"), ("max_rel_err", "<f8")])
 MISMATCH_DTYPE = np.dtype([("index", "<i8"), ("a", "<f8"), ("b", "<f8"), ("d", "<f8"), ("tol", "<f8")])
@@ -136,6 +140,9 @@ def library() -> ctypes.CDLL:
         lib.geak_check_plan_mx.restype = ctypes.c_int
         lib.geak_check_plan_mx.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
                                            ctypes.c_int32, ctypes.c_int32]
+        lib.geak_check_plan_table.restype = ctypes.c_int
+        lib.geak_check_plan_table.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                                              ctypes.c_int32, ctypes.c_int32]
         lib.geak_check_plan_dense.restype = ctypes.c_int
         lib.geak_check_plan_dense.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(ctypes.c_int64), i32, i32, dbl, dbl, i32, i32]
         lib.geak_check_workspace_bytes.restype = u64
@@ -191,7 +198,7 @@ def library() -> ctypes.CDLL:
     return _lib
 
 
-EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_mapped", "geak_check_plan_mx", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
+EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_mapped", "geak_check_plan_mx", "geak_check_plan_table", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_run_static", "geak_check_destroy", "geak_status_string", "geak_check_build_id", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_ref_offsets", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
             "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram", "geak_check_verdicts",
@@ -268,6 +275,31 @@ def geak_check_plan_mx(segments, tolerances, num_candidates: int, atol: float, r
     st = library().geak_check_plan_mx(ctypes.byref(out), arr.ctypes.data if len(segs) else None,
                                       None if tol is None else tol.ctypes.data,
                                       len(segs), num_candidates, float(atol), float(rtol), int(equal_nan), int(device))
+    return st, (out.value if st == GEAK_OK else None)
+
+
+def geak_check_plan_table(segments, tolerances, num_candidates: int, atol: float, rtol: float, equal_nan, device: int):
+    """segments: iterable of ("pitched", byte_offset, rows, row_elems, pitch_bytes, dtype),
+    ("mapped", byte_offset, rows, row_elems, pitch_bytes, ref_byte_offset, ref_pitch_bytes, ref_elem_stride, dtype) or
+    ("mx", byte_offset, numel, scale_byte_offset, format); tolerances: one (atol, rtol) pair per segment or None.
+    Returns (status, plan handle or None)."""
+    segs = list(segments)
+    arr = np.zeros(len(segs), dtype=SEGMENT_ANY_DTYPE)
+    for i, sg in enumerate(segs):
+        if sg[0] == "pitched":
+            _, off, rows, row_elems, pitch, dt = sg
+            arr[i] = (off, rows, row_elems, pitch, 0, 0, 0, DTYPE_CODE.get(dt, dt), GEAK_KIND_PITCHED, 0)
+        elif sg[0] == "mapped":
+            _, off, rows, row_elems, pitch, ref_off, ref_pitch, ref_stride, dt = sg
+            arr[i] = (off, rows, row_elems, pitch, ref_off, ref_pitch, ref_stride, DTYPE_CODE.get(dt, dt), GEAK_KIND_MAPPED, 0)
+        else:
+            _, off, n, scale_off, dt = sg
+            arr[i] = (off, 1, n, 0, scale_off, 0, 0, MX_DTYPE_CODE.get(dt, DTYPE_CODE.get(dt, dt)), GEAK_KIND_MX, 0)
+    tol = None if tolerances is None else np.ascontiguousarray(np.asarray(list(tolerances), dtype=np.float64).reshape(-1, 2))
+    out = ctypes.c_void_p(None)
+    st = library().geak_check_plan_table(ctypes.byref(out), arr.ctypes.data if len(segs) else None,
+                                         None if tol is None else tol.ctypes.data,
+                                         len(segs), num_candidates, float(atol), float(rtol), int(equal_nan), int(device))
     return st, (out.value if st == GEAK_OK else None)
 
 
@@ -445,10 +477,12 @@ def geak_check_profile_read(plan, capacity: int) -> np.ndarray:
 class Checker:
     """A plan plus its workspace and results buffers (torch tensors on the plan's device)."""
 
-    def __init__(self, segments=None, *, dense=None, pitched=None, mapped=None, mx=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
+    def __init__(self, segments=None, *, dense=None, pitched=None, mapped=None, mx=None, table=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
                  equal_nan: bool, device: int = 0, tolerances=None):
         import torch
-        if mx is not None:
+        if table is not None:
+            st, plan = geak_check_plan_table(table, tolerances, num_candidates, atol, rtol, equal_nan, device)
+        elif mx is not None:
             st, plan = geak_check_plan_mx(mx, tolerances, num_candidates, atol, rtol, equal_nan, device)
         elif mapped is not None:
             st, plan = geak_check_plan_mapped(mapped, tolerances, num_candidates, atol, rtol, equal_nan, device)

@@ -150,6 +150,52 @@ geak_status geak_check_plan_mx(geak_plan **out, const geak_segment_mx *segs, con
     return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
 }
 
+geak_status geak_check_plan_table(geak_plan **out, const geak_segment_any *segs, const geak_tolerance *tols, uint64_t nsegs,
+                                  int32_t num_candidates, double atol, double rtol, int32_t equal_nan, int32_t device)
+{
+    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    std::vector<SegDesc> descs;
+    std::vector<geak_tolerance> same;
+    try {
+        descs.resize(nsegs);
+        if (!tols) same.assign(nsegs, geak_tolerance{atol, rtol});
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    for (uint64_t s = 0; s < nsegs; ++s) {                 // each kind exactly as its own entry point builds it
+        const geak_segment_any &g = segs[s];
+        if (g.reserved != 0) return GEAK_EINVAL;
+        if (g.rows && g.row_elems > GEAK_MAX_SEGMENT_NUMEL / g.rows) return GEAK_EBOUNDS;
+        const uint64_t numel = g.rows * g.row_elems;
+        if (g.kind == GEAK_KIND_PITCHED) {
+            if (g.aux_byte_offset || g.aux_pitch_bytes || g.ref_elem_stride) return GEAK_EINVAL;
+            if (is_mx_dtype(g.dtype)) return GEAK_EDTYPE;
+            const uint64_t w = (g.dtype >= GEAK_F32 && g.dtype <= GEAK_F8E5M2) ? (uint64_t)elem_size(g.dtype) : 1;
+            SegDesc d{g.byte_offset, numel, numel ? g.row_elems : 1, g.pitch_bytes, g.dtype, 0, 0, 0};
+            if (numel && g.row_elems <= UINT64_MAX / w && g.pitch_bytes == g.row_elems * w) {    // rows back to back: one row
+                d.row_elems = numel;
+                d.pitch_bytes = numel * w;
+            }
+            if (!numel) d.pitch_bytes = 0;
+            descs[s] = d;
+        } else if (g.kind == GEAK_KIND_MAPPED) {
+            if (g.ref_elem_stride < 0) return GEAK_EINVAL;
+            if ((uint64_t)g.ref_elem_stride > kMaxRefStride) return GEAK_EBOUNDS;
+            if (is_mx_dtype(g.dtype)) return GEAK_EDTYPE;
+            descs[s] = SegDesc{g.byte_offset, numel, numel ? g.row_elems : 1, numel ? g.pitch_bytes : 0, g.dtype,
+                               kRefMapped | (int32_t)((uint32_t)g.ref_elem_stride << kRefStrideShift), g.aux_byte_offset,
+                               numel ? g.aux_pitch_bytes : 0};
+        } else if (g.kind == GEAK_KIND_MX) {
+            if (g.rows > 1 || g.pitch_bytes || g.aux_pitch_bytes || g.ref_elem_stride) return GEAK_EINVAL;
+            if (!is_mx_dtype(g.dtype)) return GEAK_EDTYPE;
+            descs[s] = SegDesc{g.byte_offset, numel, numel ? numel : 1, payload_bytes(g.dtype, numel), g.dtype, kMxScaled, g.aux_byte_offset, 0};
+        } else {
+            return GEAK_EINVAL;
+        }
+    }
+    return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
+}
+
 geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *segs, const geak_tolerance *tols, uint64_t nsegs,
                                    int32_t num_candidates, double atol, double rtol, int32_t equal_nan, int32_t device)
 {

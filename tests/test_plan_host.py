@@ -33,6 +33,8 @@ def test_struct_sizes_match_header():
     assert B.ITEM_DTYPE.itemsize == 32
     assert B.MISMATCH_DTYPE.itemsize == 40
     assert ctypes.sizeof(B.PlanInfo) == 64
+    assert B.SEGMENT2D_DTYPE.itemsize == 40 and B.SEGMENT_MAPPED_DTYPE.itemsize == 56
+    assert B.SEGMENT_MX_DTYPE.itemsize == 32 and B.SEGMENT_ANY_DTYPE.itemsize == 64
 
 
 def _plan(segs, K=2, atol=1e-3, rtol=1e-3, eq=0, device=-1):
@@ -654,3 +656,38 @@ def test_random_mapped_and_block_scaled_tables(lib, seed):
     assert all(cursor.get(sg, 0) == segs[sg][1] for sg in range(len(segs)))
     assert info.algorithmic_bytes == (K + 1) * sum(n * bits[f] // 8 + n // 32 for _, n, _, f in segs)
     B.geak_check_destroy(plan)
+
+
+def test_table_of_mixed_kinds_builds_what_each_entry_point_builds(lib):
+    """geak_check_plan_table with one kind of entry gives the items of that kind's own entry point; a mixed table
+    gives the concatenation, with the table of reference offsets covering every item."""
+    pitched = [(0, 3, 5000, 5000 * 2 + 32, "f16"), (40000, 7, 100, 416, "f32"), (50003, 4, 1000, 1003, "u8"), (60000, 1, 700, 2800, "f32")]
+    mapped = [(0, 37, 301, 304 * 4, 8, 0, 1, "f32"), (80000, 5, 9, 80, 4096, 8, 5, "f64")]
+    mxs = [(0, 4096 * 2 + 64, 20000, "mxfp8e4m3"), (32768, 8192 + 96, 40000, "mxfp4e2m1")]
+    def items_of(st_plan):
+        st, plan = st_plan
+        assert st == B.GEAK_OK
+        out = B.geak_check_plan_items(plan), B.geak_check_plan_ref_offsets(plan), B.geak_check_plan_info(plan).algorithmic_bytes
+        B.geak_check_destroy(plan)
+        return out
+    for own, table in ((B.geak_check_plan_pitched(pitched, None, 2, 0, 0, 0, -1), [("pitched",) + p for p in pitched]),
+                       (B.geak_check_plan_mapped(mapped, None, 2, 0, 0, 0, -1), [("mapped",) + m for m in mapped]),
+                       (B.geak_check_plan_mx(mxs, None, 2, 0, 0, 0, -1), [("mx",) + m for m in mxs])):
+        a, b = items_of(own), items_of(B.geak_check_plan_table(table, None, 2, 0, 0, 0, -1))
+        assert (a[0] == b[0]).all() and (a[1] == b[1]).all() and a[2] == b[2]
+    # mixed: the kinds one behind the other in one buffer layout
+    shift = 200000
+    table = [("pitched",) + pitched[1], ("mapped", shift) + mapped[0][1:], ("mx", 2 * shift, mxs[1][1], 2 * shift + 50000, mxs[1][3]),
+             ("pitched", 3 * shift, 0, 7, 28, "i32"), ("mapped", 3 * shift + 64) + mapped[1][1:]]
+    items, ref_off, alg = items_of(B.geak_check_plan_table(table, None, 3, 0, 0, 0, -1))
+    assert sorted(set(int(i["segment"]) for i in items)) == [0, 1, 2, 4] and len(ref_off) == len(items)
+    for it, ro in zip(items, ref_off):
+        if it["flags"] & B.GEAK_ITEM_REFMAP:
+            assert int(it["segment"]) in (1, 4)
+        else:
+            assert int(ro) == int(it["byte_offset"])
+    assert alg == 4 * 7 * 100 * 4 + (3 * 37 * 301 * 4 + 301 * 4) + 4 * ((8192 + 96) // 2 + (8192 + 96) // 32) + (3 * 45 * 8 + 45 * 8)
+    # a kind's unused fields must be 0, the kind known
+    arr_bad = [("mx", 0, 64, 100, "f32")]
+    assert B.geak_check_plan_table(arr_bad, None, 1, 0, 0, 0, -1)[0] == B.GEAK_EDTYPE
+    assert B.geak_check_plan_table([("pitched", 0, 1, 64, 64, B.GEAK_MXINT8)], None, 1, 0, 0, 0, -1)[0] == B.GEAK_EDTYPE
