@@ -668,7 +668,10 @@ geak_status geak_check_read_probe(const geak_plan *plan, const void *ref_dev, co
     // the span of the packed buffers that the plan's segments cover
     uint64_t end = 0;
     for (const SegDesc &g : hp.segments)
-        if (g.numel) end = std::max<uint64_t>(end, g.byte_offset + seg_span(g));
+        if (g.numel) {
+            end = std::max<uint64_t>(end, g.byte_offset + seg_span(g));
+            if (g.layout == kMxScaled) end = std::max<uint64_t>(end, g.ref_byte_offset + g.numel / kMxBlock);     // its scale bytes
+        }
     DeviceGuard g(plan->device);
     if (!g.ok) return GEAK_EHIP;
     // the candidate pointer table of a run is reused; the reference pointer goes behind it
@@ -705,6 +708,8 @@ geak_status geak_check_profile_enable(geak_plan *plan, uint32_t num_pairs)
     plan->ev_stop.clear();
     plan->ev_next = plan->ev_used = 0;
     try {
+        plan->ev_start.reserve(num_pairs);                  // so that the two rings cannot end up of different lengths
+        plan->ev_stop.reserve(num_pairs);
         for (uint32_t i = 0; i < num_pairs; ++i) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess) return GEAK_EHIP;

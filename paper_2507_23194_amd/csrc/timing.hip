@@ -5,6 +5,7 @@
 // last-level cache is overwritten on the same stream first -- and is bracketed by two events on that
 // stream.  The latencies go to geak_metrics_speedup.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include "geak_internal.hpp"
 
 namespace geak {
@@ -30,9 +31,9 @@ geak_status geak_timing_flush(void *scratch_dev, uint64_t scratch_bytes, void *h
 {
     if (!scratch_dev || scratch_bytes < 16) return GEAK_EINVAL;
     if ((uintptr_t)scratch_dev & 15u) return GEAK_EALIGN;
-    static uint32_t round = 0;                               // a different value every time: the stores cannot be elided as silent
+    static std::atomic<uint32_t> round{0};                   // a different value every time: the stores cannot be elided as silent
     hipLaunchKernelGGL(geak::flush_kernel, dim3(2048), dim3(256), 0, (hipStream_t)hip_stream, (geak::u32x4 *)scratch_dev,
-                       (unsigned long long)(scratch_bytes / 16), ++round);
+                       (unsigned long long)(scratch_bytes / 16), round.fetch_add(1u) + 1u);
     return hipGetLastError() == hipSuccess ? GEAK_OK : GEAK_EHIP;
 }
 
@@ -46,7 +47,7 @@ geak_status geak_timing_measure(geak_launch_fn launch, void *user, uint32_t warm
     if (hipEventCreate(&start) != hipSuccess) return GEAK_EHIP;
     if (hipEventCreate(&stop) != hipSuccess) { (void)hipEventDestroy(start); return GEAK_EHIP; }
     geak_status st = GEAK_OK;
-    for (uint32_t r = 0; r < warmup + repetitions && st == GEAK_OK; ++r) {
+    for (uint64_t r = 0; r < (uint64_t)warmup + repetitions && st == GEAK_OK; ++r) {
         if (flush_scratch_dev) st = geak_timing_flush(flush_scratch_dev, flush_bytes, hip_stream);
         if (st != GEAK_OK) break;
         if (hipEventRecord(start, stream) != hipSuccess) { st = GEAK_EHIP; break; }

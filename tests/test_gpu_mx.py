@@ -236,3 +236,25 @@ def test_mx_plan_argument_errors():
     # two segments whose scale regions collide
     st, plan = B.geak_check_plan_mx([(0, 64, 1000, "mxint8"), (64, 64, 1001, "mxint8")], None, 1, 0.0, 0.0, False, 0)
     assert st == B.GEAK_EBOUNDS
+
+
+def test_read_probe_over_a_block_scaled_plan(oracle_mod):
+    """The read-only probe reads what a run reads, the scale bytes behind the last payload included, and leaves the
+    plan's next run alone."""
+    print("mx probe", flush=True)
+    rng = np.random.default_rng(8899)
+    K = 3
+    segs = [_tensors(rng, f, n, K) for f, n in (("mxfp8e4m3", 4096 + 64), ("mxfp4e2m1", 8192))]
+    bufs, table = _pack(segs)
+    fmts = ["mxfp8e4m3", "mxfp4e2m1"]
+    dev = [torch.from_numpy(b.copy()).cuda() for b in bufs]
+    ck = B.Checker(mx=[(o, n, so, f) for (o, n, so), f in zip(table, fmts)], num_candidates=K, atol=1e-2, rtol=0.05, equal_nan=False, device=0)
+    try:
+        ck.run(dev[0], dev[1:])
+        first = ck.read().copy()
+        ck.read_probe(dev[0], dev[1:])
+        torch.cuda.synchronize()
+        ck.run(dev[0], dev[1:])
+        _assert_same(ck.read().copy(), first, "run after a probe")
+    finally:
+        ck.close()
