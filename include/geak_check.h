@@ -321,7 +321,9 @@ typedef struct {
     uint32_t lds_bytes;          /* dynamic LDS per block */
     uint32_t item_bytes;         /* bytes of one full work item per tensor */
     int32_t  device;
-    uint32_t reserved[2];
+    uint32_t unit_groups;        /* 1, or the number of compute units when the block table is laid out by compute unit
+                                    (geak_check_plan_blocks) */
+    uint32_t reserved;
 } geak_plan_info;
 
 /* One work item, as the compare kernel sees it.  32 bytes. */
@@ -352,13 +354,20 @@ typedef struct {
 geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
 
 /* Copies up to `capacity` entries of the block table into `out` (host); returns its length,
- * grid_blocks + 1.  Block b of the compare kernel owns items [table[b], table[b + 1]). */
+ * grid_blocks + 1.  Range r of the table is the items [table[r], table[r + 1]); the ranges partition
+ * the item table in order and none is empty.  With unit_groups == 1 block r of the compare kernel
+ * runs range r.  A grid that fills the chip is dispatched round by round, block b to compute unit
+ * b mod unit_groups, and the waves of a compute unit finish together; for a batch whose ranges would
+ * load the units unequally the table is cut so that every unit streams the same number of bytes,
+ * with the ranges of the blocks that share a unit side by side: with per_unit = grid_blocks /
+ * unit_groups, ranges g * per_unit .. g * per_unit + per_unit - 1 are run by the blocks of unit
+ * u = g ^ ((g >> 3) & 7), block u + q * unit_groups running range g * per_unit + q. */
 uint64_t geak_check_plan_blocks(const geak_plan *plan, uint32_t *out, uint64_t capacity);
 
 /* Copies up to `capacity` entries of the wavefront table into `out` (host); returns its length,
- * grid_blocks * (block_threads / 64).  Entry b * (block_threads / 64) + w is the first item of
- * wavefront w of block b (GEAK_NO_ITEM if it has none); the wavefront then follows the items'
- * `next` links, which stay inside the block's range and ascend. */
+ * grid_blocks * (block_threads / 64).  Entry r * (block_threads / 64) + w is the first item of
+ * wavefront w of the block that runs range r (GEAK_NO_ITEM if it has none); the wavefront then
+ * follows the items' `next` links, which stay inside the range and ascend. */
 uint64_t geak_check_plan_waves(const geak_plan *plan, uint32_t *out, uint64_t capacity);
 
 /* Copies up to `capacity` items into `out` (host); returns the total number of items. */

@@ -56,7 +56,7 @@ class PlanInfo(ctypes.Structure):
                 ("algorithmic_bytes", ctypes.c_uint64), ("num_candidates", ctypes.c_uint32),
                 ("grid_blocks", ctypes.c_uint32), ("block_threads", ctypes.c_uint32), ("lds_bytes", ctypes.c_uint32),
                 ("item_bytes", ctypes.c_uint32), ("device", ctypes.c_int32),
-                ("reserved", ctypes.c_uint32 * 2)]
+                ("unit_groups", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 LAUNCH_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p)     # geak_launch_fn(user, hip_stream)

@@ -235,7 +235,7 @@ static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const g
     p->device = device;
     p->lds_bytes = lds_bytes_for(num_candidates);
 
-    uint32_t max_blocks = (uint32_t)(kDefaultComputeUnits * kDefaultBlocksPerCU);
+    uint32_t max_blocks = (uint32_t)(kDefaultComputeUnits * kDefaultBlocksPerCU), compute_units = (uint32_t)kDefaultComputeUnits;
     if (device >= 0) {
         int n_dev = 0;
         if (hipGetDeviceCount(&n_dev) != hipSuccess || device >= n_dev) { delete p; return GEAK_EHIP; }
@@ -245,9 +245,10 @@ static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const g
         const int per_cu = compare_blocks_per_cu(p->lds_bytes);
         if (per_cu <= 0 || prop.multiProcessorCount <= 0) { delete p; return GEAK_EHIP; }
         max_blocks = (uint32_t)prop.multiProcessorCount * (uint32_t)per_cu;
+        compute_units = (uint32_t)prop.multiProcessorCount;
     }
 
-    geak_status st = build_host_plan(p->host, segs, tols, nsegs, num_candidates, equal_nan, max_blocks);
+    geak_status st = build_host_plan(p->host, segs, tols, nsegs, num_candidates, equal_nan, max_blocks, compute_units);
     if (st != GEAK_OK) { delete p; return st; }
 
     if (device >= 0) {
@@ -381,7 +382,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.partials = partials;
         ca.board = board;
         ca.replicas = hp.replicas;
-        ca.reserved0 = 0;
+        ca.unit_groups = hp.unit_groups;
         ca.num_items = (uint32_t)hp.items.size();
         ca.num_candidates = (uint32_t)K;
         ca.seg_tol = plan->seg_tol_dev;
@@ -463,6 +464,8 @@ geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out)
     out->lds_bytes = plan->lds_bytes;
     out->item_bytes = kItemBytes;
     out->device = plan->device;
+    out->unit_groups = hp.unit_groups;
+    out->reserved = 0;
     return GEAK_OK;
 }
 
@@ -614,7 +617,7 @@ geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev,
             ua.k_begin = k0;
             ua.k_count = std::min<uint32_t>(per_pass, (uint32_t)K - k0);
             ua.nslots = nslots;
-            ua.reserved = 0;
+            ua.unit_groups = hp.unit_groups;
             ua.segments = plan->segments_dev;
             ua.ref_item_offset = plan->ref_item_offset_dev;
             const uint32_t lds = kWavesPerBlock * ua.k_count * nslots * 4u;

@@ -46,6 +46,21 @@ __device__ __forceinline__ const unsigned char *table_entry(const unsigned char 
     return reinterpret_cast<const unsigned char *>(t[k]);
 }
 
+// The range of the plan's block table that block `block` of a grid of `grid` blocks runs: range `block`, unless
+// the planner laid the table out by compute unit (unit_groups = their number, a multiple of 8).  A grid that fills
+// the chip is dispatched round by round, block b to XCD b mod 8 and there to compute unit b mod units, and the
+// ranges of the blocks that share a unit lie side by side in the table: group g of grid / units ranges belongs
+// to one unit.  Which unit: not g itself -- every eighth group would go to the same XCD, and in a table of
+// regular segments an XCD's addresses then differ from the other XCDs' in a few fixed bits (measured: dense
+// tensors 5 - 15 % slower) -- but g with its three low bits rotated by the three bits above them.
+__device__ __forceinline__ uint32_t table_range_of_block(uint32_t block, uint32_t grid, uint32_t unit_groups)
+{
+    if (unit_groups <= 1) return block;
+    const uint32_t unit = block % unit_groups, round = block / unit_groups;
+    const uint32_t group = unit ^ ((unit >> 3) & 7u);
+    return group * (grid / unit_groups) + round;
+}
+
 // A segment's tolerances, read with scalar loads when the segment index is wave-uniform.
 __device__ __forceinline__ SegTol load_tol(const SegTol *table, uint32_t segment)
 {

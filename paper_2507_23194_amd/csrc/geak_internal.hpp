@@ -122,11 +122,12 @@ struct HostPlan {
     std::vector<uint32_t> block_first;     // size grid_blocks + 1: block b owns items [block_first[b], block_first[b + 1])
     std::vector<uint32_t> wave_first;      // size grid_blocks * kWavesPerBlock: first item of each wave's list (kNoItem: none)
     uint32_t max_blocks = 1;               // compute units x resident blocks per unit
+    uint32_t unit_groups = 1;              // > 1: the block table is laid out by compute unit; which block runs which range: table_range_of_block()
 };
 
 // Validates and builds the work table for a persistent grid of at most `max_blocks` blocks.
 geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
-                            int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks);
+                            int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks, uint32_t compute_units);
 
 // Running maxima of one (segment, candidate, replica): non-negative doubles, raised by atomic max on
 // their bit patterns.
@@ -162,7 +163,7 @@ struct CompareArgs {
     Partial *partials;
     MaxPair *board;
     uint32_t replicas;                   // power of two
-    uint32_t reserved0;
+    uint32_t unit_groups;                // HostPlan::unit_groups: which range of the wave table a block runs (1: range b)
     uint32_t num_items;
     uint32_t num_candidates;
     const SegTol *seg_tol;               // device table, one entry per segment
@@ -239,7 +240,7 @@ struct UlpArgs {
     uint32_t k_begin;                    // candidates [k_begin, k_begin + k_count) are counted by this pass
     uint32_t k_count;
     uint32_t nslots;
-    uint32_t reserved;
+    uint32_t unit_groups;                // as in CompareArgs
     const SegDesc *segments;             // device table: the row geometry of row-group items, the reference's layout
     const uint64_t *ref_item_offset;     // device table, per item; null when no segment's reference is mapped
 };

@@ -1502,6 +1502,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t K = p.num_candidates;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t range = table_range_of_block(blockIdx.x, gridDim.x, p.unit_groups);
     WaveState st;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(GEAK_AS_LDS unsigned char *)lds;
     st.count_off = lds_base + (uint32_t)sizeof(u64) * wave * K;
@@ -1514,11 +1515,11 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     r.cand = p.cand_table;
     r.board = p.board;
     r.replicas = p.replicas;
-    r.replica = blockIdx.x & (p.replicas - 1);
+    r.replica = range & (p.replicas - 1);
     r.partials = p.partials;
     r.num_items = p.num_items;
     r.K = K;
-    r.k0 = (blockIdx.x / p.replicas) % K;
+    r.k0 = (range / p.replicas) % K;
     r.priority_phase = (blockIdx.x * 4u) / gridDim.x;
     r.seg_tol = p.seg_tol;
     r.segments = p.segments;
@@ -1527,7 +1528,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
 
     // the wave's list of items: its first one from the wave table, then along the next links
     const GEAK_AS_CONSTANT uint32_t *wave_first = (const GEAK_AS_CONSTANT uint32_t *)p.wave_first;
-    uint32_t j = wave_first[blockIdx.x * kWavesPerBlock + wave];
+    uint32_t j = wave_first[range * kWavesPerBlock + wave];
     while (j < p.num_items) {                                   // kNoItem ends the list; nothing past the table is read
         const geak_item it = load_work_item(p.items, j);
         // a run of full items, or one item of another shape: handled, state bookkeeping included, by the dtype's routine

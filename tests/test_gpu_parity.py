@@ -524,6 +524,24 @@ def test_full_config4(oracle_mod):
     _full(oracle_mod, 4)
 
 
+def test_full_config4_runs_the_layout_by_compute_unit():
+    """The ragged workload is the one whose block table is cut by compute unit (test_full_config4 and the full-size
+    histogram test then prove that layout against the oracle); the dense ones keep the plain table."""
+    w = synth.CONFIGS[4](device="cuda")
+    ck = B.Checker(w.segments, num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol, equal_nan=w.equal_nan, device=0)
+    try:
+        info = ck.info()
+        assert info.unit_groups == torch.cuda.get_device_properties(0).multi_processor_count
+        assert info.grid_blocks % info.unit_groups == 0 and info.grid_blocks // info.unit_groups >= 2
+    finally:
+        ck.close()
+    ck = B.Checker(dense=("f16", (1 << 24,)), num_candidates=4, atol=0.0, rtol=0.0, equal_nan=False, device=0)
+    try:
+        assert ck.info().unit_groups == 1
+    finally:
+        ck.close()
+
+
 def test_full_config5(oracle_mod):
     # every third candidate element by element through the oracle (11 x 2^30 elements: what the time limit
     # allows), all 32 by the planted counts and first indices

@@ -258,8 +258,59 @@ def test_work_table_many_segments_uneven_blocks(lib):
             j = int(items["next"][j])
     per_block = counts.reshape(info.grid_blocks, 4)
     assert counts.sum() == info.num_items
-    assert (per_block.max(axis=1) - per_block.min(axis=1) <= 4).all()
+    assert (per_block.max(axis=1) - per_block.min(axis=1) <= 6).all()         # a block of bfloat16 items, tails and int32 items
     assert (per_block.max(axis=1) - per_block.min(axis=1)).mean() < 1.5
+    B.geak_check_destroy(plan)
+
+
+def _range_of_block(b, grid, units):
+    """Which range of the block table block b runs (the rule in the header's comment on geak_check_plan_blocks)."""
+    if units <= 1:
+        return b
+    u, q = b % units, b // units
+    return (u ^ ((u >> 3) & 7)) * (grid // units) + q
+
+
+def test_ragged_batch_is_cut_by_compute_unit(lib):
+    """A batch of mixed dtypes and sizes that fills the grid: the table is laid out by compute unit, every unit
+    streams nearly the same number of slices, and the blocks' ranges of a unit are equal in what they cost a wave;
+    a dense tensor keeps the plain layout."""
+    rng = np.random.default_rng(3)
+    segs, off = [], 0
+    for s in range(1024):
+        dt = ["f32", "f16", "bf16", "i32"][rng.integers(0, 4)]
+        w = 2 if dt in ("f16", "bf16") else 4
+        n = max(1, int(2 ** (20 * rng.random())))
+        off = (off + 15) // 16 * 16
+        segs.append((off, n, dt))
+        off += n * w
+    st, plan = _plan(segs, K=4)
+    assert st == B.GEAK_OK
+    info = B.geak_check_plan_info(plan)
+    units, grid = int(info.unit_groups), int(info.grid_blocks)
+    assert units == 256 and grid == 1024                      # host-only plans assume 256 compute units, four blocks each
+    _check_lists_and_runs(plan)
+    items = B.geak_check_plan_items(plan)
+    blocks = B.geak_check_plan_blocks(plan).astype(np.int64)
+    per = grid // units
+    full = (items["flags"] & B.GEAK_ITEM_FULL) != 0
+    cum_full = np.concatenate([[0], np.cumsum(full)])
+    unit_full = np.array([cum_full[blocks[(g + 1) * per]] - cum_full[blocks[g * per]] for g in range(units)])
+    assert unit_full.min() >= 0.75 * unit_full.max()                          # units of many small segments hold fewer full items
+    big = unit_full >= np.median(unit_full)
+    assert unit_full[big].max() - unit_full[big].min() <= 0.05 * unit_full.mean()
+    # the map from blocks to ranges is one to one, and a unit's blocks run one group of ranges
+    ranges = np.array([_range_of_block(b, grid, units) for b in range(grid)])
+    assert sorted(ranges) == list(range(grid))
+    for u in (0, 1, 9, 77, 255):
+        assert sorted(ranges[u::units] // per) == [ranges[u] // per] * per
+    B.geak_check_destroy(plan)
+    # the same segments, all binary32 and of one size: the one-step ranges already load the units evenly
+    st, plan = _plan([(i * (1 << 22), 1 << 20, "f32") for i in range(64)], K=4)
+    assert B.geak_check_plan_info(plan).unit_groups == 1
+    B.geak_check_destroy(plan)
+    st, plan = B.geak_check_plan_dense("bf16", [1 << 27], 8, 0, 0, 0, -1)
+    assert B.geak_check_plan_info(plan).unit_groups == 1
     B.geak_check_destroy(plan)
 
 
