@@ -321,9 +321,9 @@ typedef struct {
     uint32_t lds_bytes;          /* dynamic LDS per block */
     uint32_t item_bytes;         /* bytes of one full work item per tensor */
     int32_t  device;
-    uint32_t unit_groups;        /* 1, or the number of compute units when the block table is laid out by compute unit
-                                    (geak_check_plan_blocks) */
-    uint32_t reserved;
+    uint32_t unit_groups;        /* compute units of the device, when block_map is not GEAK_MAP_PLAIN; else 1 */
+    uint32_t block_map;          /* GEAK_MAP_*: which block of the compare kernel runs which range of the block
+                                    table (geak_check_plan_blocks) */
 } geak_plan_info;
 
 /* One work item, as the compare kernel sees it.  32 bytes. */
@@ -353,15 +353,23 @@ typedef struct {
 
 geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out);
 
+/* values of geak_plan_info.block_map */
+#define GEAK_MAP_PLAIN 0u
+#define GEAK_MAP_ROTATED 1u
+#define GEAK_MAP_BY_UNIT 2u
+
 /* Copies up to `capacity` entries of the block table into `out` (host); returns its length,
  * grid_blocks + 1.  Range r of the table is the items [table[r], table[r + 1]); the ranges partition
- * the item table in order and none is empty.  With unit_groups == 1 block r of the compare kernel
- * runs range r.  A grid that fills the chip is dispatched round by round, block b to compute unit
- * b mod unit_groups, and the waves of a compute unit finish together; for a batch whose ranges would
- * load the units unequally the table is cut so that every unit streams the same number of bytes,
- * with the ranges of the blocks that share a unit side by side: with per_unit = grid_blocks /
- * unit_groups, ranges g * per_unit .. g * per_unit + per_unit - 1 are run by the blocks of unit
- * u = g ^ ((g >> 3) & 7), block u + q * unit_groups running range g * per_unit + q. */
+ * the item table in order and none is empty.  Which block runs range r depends on block_map; a grid
+ * that fills the chip is dispatched round by round, block b to XCD b mod 8 and to compute unit
+ * u = b mod unit_groups in round q = b / unit_groups, and with g = u ^ ((u >> 3) & 7):
+ *   GEAK_MAP_PLAIN    block b runs range b (grids that do not fill the chip).
+ *   GEAK_MAP_ROTATED  block b runs range q * unit_groups + g: the same table, the XCDs taking turns
+ *                     within every eight ranges instead of each keeping every eighth one.
+ *   GEAK_MAP_BY_UNIT  block b runs range g * per_unit + q, per_unit = grid_blocks / unit_groups.  The
+ *                     waves of a compute unit finish together; for a batch whose plain ranges would
+ *                     load the units unequally the table is cut so that every unit streams the same
+ *                     number of bytes, the ranges of the blocks that share a unit side by side. */
 uint64_t geak_check_plan_blocks(const geak_plan *plan, uint32_t *out, uint64_t capacity);
 
 /* Copies up to `capacity` entries of the wavefront table into `out` (host); returns its length,

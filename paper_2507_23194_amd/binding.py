@@ -49,6 +49,7 @@ MISMATCH_DTYPE = np.dtype([("index", "<i8"), ("a", "<f8"), ("b", "<f8"), ("d", "
 ITEM_DTYPE = np.dtype([("byte_offset", "<u8"), ("elem_start", "<u8"), ("segment", "<u4"), ("slot", "<u4"),
                        ("numel", "<u2"), ("dtype", "u1"), ("flags", "u1"), ("next", "<u4")])
 GEAK_NO_ITEM = 0xFFFFFFFF
+GEAK_MAP_PLAIN, GEAK_MAP_ROTATED, GEAK_MAP_BY_UNIT = 0, 1, 2
 
 
 class PlanInfo(ctypes.Structure):
@@ -56,7 +57,7 @@ class PlanInfo(ctypes.Structure):
                 ("algorithmic_bytes", ctypes.c_uint64), ("num_candidates", ctypes.c_uint32),
                 ("grid_blocks", ctypes.c_uint32), ("block_threads", ctypes.c_uint32), ("lds_bytes", ctypes.c_uint32),
                 ("item_bytes", ctypes.c_uint32), ("device", ctypes.c_int32),
-                ("unit_groups", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("unit_groups", ctypes.c_uint32), ("block_map", ctypes.c_uint32)]
 
 
 LAUNCH_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p)     # geak_launch_fn(user, hip_stream)

@@ -387,7 +387,7 @@ geak_status geak_check_run(const geak_plan *plan, const void *ref_dev, const voi
         ca.num_candidates = (uint32_t)K;
         ca.seg_tol = plan->seg_tol_dev;
         ca.equal_nan = hp.equal_nan;
-        ca.reserved = 0;
+        ca.block_map = hp.block_map;
         ca.wave_first = plan->wave_first_dev;
         ca.segments = plan->segments_dev;
         ca.ref_item_offset = plan->ref_item_offset_dev;
@@ -465,7 +465,7 @@ geak_status geak_check_plan_info(const geak_plan *plan, geak_plan_info *out)
     out->item_bytes = kItemBytes;
     out->device = plan->device;
     out->unit_groups = hp.unit_groups;
-    out->reserved = 0;
+    out->block_map = hp.block_map;
     return GEAK_OK;
 }
 
@@ -618,6 +618,8 @@ geak_status geak_check_ulp_histogram(const geak_plan *plan, const void *ref_dev,
             ua.k_count = std::min<uint32_t>(per_pass, (uint32_t)K - k0);
             ua.nslots = nslots;
             ua.unit_groups = hp.unit_groups;
+            ua.block_map = hp.block_map;
+            ua.reserved = 0;
             ua.segments = plan->segments_dev;
             ua.ref_item_offset = plan->ref_item_offset_dev;
             const uint32_t lds = kWavesPerBlock * ua.k_count * nslots * 4u;

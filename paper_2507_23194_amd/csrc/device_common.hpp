@@ -46,19 +46,23 @@ __device__ __forceinline__ const unsigned char *table_entry(const unsigned char 
     return reinterpret_cast<const unsigned char *>(t[k]);
 }
 
-// The range of the plan's block table that block `block` of a grid of `grid` blocks runs: range `block`, unless
-// the planner laid the table out by compute unit (unit_groups = their number, a multiple of 8).  A grid that fills
-// the chip is dispatched round by round, block b to XCD b mod 8 and there to compute unit b mod units, and the
-// ranges of the blocks that share a unit lie side by side in the table: group g of grid / units ranges belongs
-// to one unit.  Which unit: not g itself -- every eighth group would go to the same XCD, and in a table of
-// regular segments an XCD's addresses then differ from the other XCDs' in a few fixed bits (measured: dense
-// tensors 5 - 15 % slower) -- but g with its three low bits rotated by the three bits above them.
-__device__ __forceinline__ uint32_t table_range_of_block(uint32_t block, uint32_t grid, uint32_t unit_groups)
+// The range of the plan's block table that block `block` of a grid of `grid` blocks runs.  A grid that fills the
+// chip is dispatched round by round: block b goes to XCD b mod 8 and there to compute unit u = b mod units, in
+// round q = b / units (measured; the same in every run).
+//   GEAK_MAP_PLAIN    range b.
+//   GEAK_MAP_ROTATED  range q * units + g: the plain table, but within every stripe of eight ranges the XCDs take
+//                     turns (g = u with its three low bits rotated by the three bits above them).  With range b
+//                     every eighth range goes to the same XCD, whose addresses then differ from the other XCDs' in a
+//                     few fixed bits; a bfloat16 tensor of 2^28 elements ran 2.5 % slower that way.
+//   GEAK_MAP_BY_UNIT  range g * (grid / units) + q: the planner laid the ranges of the blocks that share a compute
+//                     unit side by side (group g of the table belongs to one unit), the XCDs rotated as above --
+//                     unrotated, dense tensors ran 5 - 15 % slower in this layout.
+__device__ __forceinline__ uint32_t table_range_of_block(uint32_t block, uint32_t grid, uint32_t units, uint32_t block_map)
 {
-    if (unit_groups <= 1) return block;
-    const uint32_t unit = block % unit_groups, round = block / unit_groups;
+    if (block_map == GEAK_MAP_PLAIN || units <= 1) return block;
+    const uint32_t unit = block % units, round = block / units;
     const uint32_t group = unit ^ ((unit >> 3) & 7u);
-    return group * (grid / unit_groups) + round;
+    return block_map == GEAK_MAP_BY_UNIT ? group * (grid / units) + round : round * units + group;
 }
 
 // A segment's tolerances, read with scalar loads when the segment index is wave-uniform.

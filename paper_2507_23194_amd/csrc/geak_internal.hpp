@@ -122,7 +122,8 @@ struct HostPlan {
     std::vector<uint32_t> block_first;     // size grid_blocks + 1: block b owns items [block_first[b], block_first[b + 1])
     std::vector<uint32_t> wave_first;      // size grid_blocks * kWavesPerBlock: first item of each wave's list (kNoItem: none)
     uint32_t max_blocks = 1;               // compute units x resident blocks per unit
-    uint32_t unit_groups = 1;              // > 1: the block table is laid out by compute unit; which block runs which range: table_range_of_block()
+    uint32_t unit_groups = 1;              // compute units, when a full grid's blocks take the table's ranges by GEAK_MAP_ROTATED or _BY_UNIT
+    uint32_t block_map = GEAK_MAP_PLAIN;   // which block runs which range: table_range_of_block() in device_common.hpp
 };
 
 // Validates and builds the work table for a persistent grid of at most `max_blocks` blocks.
@@ -163,12 +164,12 @@ struct CompareArgs {
     Partial *partials;
     MaxPair *board;
     uint32_t replicas;                   // power of two
-    uint32_t unit_groups;                // HostPlan::unit_groups: which range of the wave table a block runs (1: range b)
+    uint32_t unit_groups;                // HostPlan::unit_groups and, below, block_map: which range of the wave table a block runs
     uint32_t num_items;
     uint32_t num_candidates;
     const SegTol *seg_tol;               // device table, one entry per segment
     int equal_nan;
-    int reserved;
+    uint32_t block_map;
     const uint32_t *wave_first;          // grid_blocks * kWavesPerBlock entries
     const SegDesc *segments;             // device table: the row geometry of row-group items, the reference's layout
     const uint64_t *ref_item_offset;     // device table, per item; null when no segment's reference is mapped
@@ -241,6 +242,8 @@ struct UlpArgs {
     uint32_t k_count;
     uint32_t nslots;
     uint32_t unit_groups;                // as in CompareArgs
+    uint32_t block_map;
+    uint32_t reserved;
     const SegDesc *segments;             // device table: the row geometry of row-group items, the reference's layout
     const uint64_t *ref_item_offset;     // device table, per item; null when no segment's reference is mapped
 };

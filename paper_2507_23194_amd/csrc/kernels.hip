@@ -1502,7 +1502,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t K = p.num_candidates;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t range = table_range_of_block(blockIdx.x, gridDim.x, p.unit_groups);
+    const uint32_t range = table_range_of_block(blockIdx.x, gridDim.x, p.unit_groups, p.block_map);
     WaveState st;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(GEAK_AS_LDS unsigned char *)lds;
     st.count_off = lds_base + (uint32_t)sizeof(u64) * wave * K;

@@ -269,20 +269,23 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                 acc += cost(hp.items[j], starts(j));
             }
         };
-        // One step: ranges of equal cost to a wave, block b runs range b.
+        // One step: ranges of equal cost to a wave.
         hp.block_first.clear();
         hp.block_first.push_back(0);
         cut(0, hp.items.size(), target_blocks, 1, item_cost, hp.block_first);
         hp.unit_groups = 1;
+        hp.block_map = GEAK_MAP_PLAIN;
         // A grid that fills the chip is dispatched round by round: block b lands on compute unit b mod (number of
         // units), so blocks b, b + units, b + 2 units, ... share one.  Where the one-step ranges would leave the units
         // with unequal loads (a batch of mixed dtypes and sizes; never a dense tensor), the table is cut in two steps
         // instead: into as many ranges as there are units, equal in what they cost a unit, and each of those into the
-        // ranges of the unit's blocks, equal in what they cost a wave.  The kernels then run range r of the table on
-        // the block that hp.unit_groups and table_range_of_block() give (device_common.hpp).
+        // ranges of the unit's blocks, equal in what they cost a wave.  Which block runs which range of the table:
+        // hp.block_map and table_range_of_block() (device_common.hpp).
         const uint64_t per_unit = target_blocks / compute_units;
         if (target_blocks == max_blocks && per_unit >= 2 && per_unit * compute_units == target_blocks && compute_units % 8 == 0 &&
             hp.items.size() >= target_blocks) {
+            hp.unit_groups = compute_units;
+            hp.block_map = GEAK_MAP_ROTATED;               // the plain table; only the XCDs take turns (device_common.hpp)
             std::vector<uint64_t> load(compute_units, 0);
             for (uint64_t r = 0; r < target_blocks; ++r) {
                 const uint64_t end = r + 1 < target_blocks ? hp.block_first[r + 1] : hp.items.size();
@@ -301,7 +304,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                 }
                 if (ranges.size() == target_blocks) {       // always: every unit's range holds at least per_unit items
                     hp.block_first.swap(ranges);
-                    hp.unit_groups = compute_units;
+                    hp.block_map = GEAK_MAP_BY_UNIT;
                 }
             }
         }

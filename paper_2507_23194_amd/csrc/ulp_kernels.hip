@@ -589,7 +589,7 @@ __global__ __launch_bounds__(kBlockThreads, 4) void ulp_histogram_kernel(const U
     r.ref_item_offset = p.ref_item_offset;
 
     const GEAK_AS_CONSTANT uint32_t *wave_first = (const GEAK_AS_CONSTANT uint32_t *)p.wave_first;
-    uint32_t j = wave_first[table_range_of_block(blockIdx.x, gridDim.x, p.unit_groups) * kWavesPerBlock + wave];
+    uint32_t j = wave_first[table_range_of_block(blockIdx.x, gridDim.x, p.unit_groups, p.block_map) * kWavesPerBlock + wave];
     while (j < p.num_items) {                                   // kNoItem ends the list
         const geak_item it = load_work_item(p.items, j);
         r.first_item = j;

@@ -531,13 +531,13 @@ def test_full_config4_runs_the_layout_by_compute_unit():
     ck = B.Checker(w.segments, num_candidates=len(w.cands), atol=w.atol, rtol=w.rtol, equal_nan=w.equal_nan, device=0)
     try:
         info = ck.info()
-        assert info.unit_groups == torch.cuda.get_device_properties(0).multi_processor_count
+        assert info.block_map == B.GEAK_MAP_BY_UNIT and info.unit_groups == torch.cuda.get_device_properties(0).multi_processor_count
         assert info.grid_blocks % info.unit_groups == 0 and info.grid_blocks // info.unit_groups >= 2
     finally:
         ck.close()
     ck = B.Checker(dense=("f16", (1 << 24,)), num_candidates=4, atol=0.0, rtol=0.0, equal_nan=False, device=0)
     try:
-        assert ck.info().unit_groups == 1
+        assert ck.info().block_map == B.GEAK_MAP_ROTATED          # 8192 items fill the grid: plain table, XCDs taking turns
     finally:
         ck.close()
 

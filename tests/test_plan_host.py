@@ -263,12 +263,13 @@ def test_work_table_many_segments_uneven_blocks(lib):
     B.geak_check_destroy(plan)
 
 
-def _range_of_block(b, grid, units):
+def _range_of_block(b, grid, units, block_map):
     """Which range of the block table block b runs (the rule in the header's comment on geak_check_plan_blocks)."""
-    if units <= 1:
+    if block_map == B.GEAK_MAP_PLAIN:
         return b
     u, q = b % units, b // units
-    return (u ^ ((u >> 3) & 7)) * (grid // units) + q
+    g = u ^ ((u >> 3) & 7)
+    return g * (grid // units) + q if block_map == B.GEAK_MAP_BY_UNIT else q * units + g
 
 
 def test_ragged_batch_is_cut_by_compute_unit(lib):
@@ -288,7 +289,7 @@ def test_ragged_batch_is_cut_by_compute_unit(lib):
     assert st == B.GEAK_OK
     info = B.geak_check_plan_info(plan)
     units, grid = int(info.unit_groups), int(info.grid_blocks)
-    assert units == 256 and grid == 1024                      # host-only plans assume 256 compute units, four blocks each
+    assert units == 256 and grid == 1024 and info.block_map == B.GEAK_MAP_BY_UNIT       # host-only plans assume 256 compute units, four blocks each
     _check_lists_and_runs(plan)
     items = B.geak_check_plan_items(plan)
     blocks = B.geak_check_plan_blocks(plan).astype(np.int64)
@@ -300,17 +301,23 @@ def test_ragged_batch_is_cut_by_compute_unit(lib):
     big = unit_full >= np.median(unit_full)
     assert unit_full[big].max() - unit_full[big].min() <= 0.05 * unit_full.mean()
     # the map from blocks to ranges is one to one, and a unit's blocks run one group of ranges
-    ranges = np.array([_range_of_block(b, grid, units) for b in range(grid)])
+    ranges = np.array([_range_of_block(b, grid, units, B.GEAK_MAP_BY_UNIT) for b in range(grid)])
     assert sorted(ranges) == list(range(grid))
     for u in (0, 1, 9, 77, 255):
         assert sorted(ranges[u::units] // per) == [ranges[u] // per] * per
     B.geak_check_destroy(plan)
-    # the same segments, all binary32 and of one size: the one-step ranges already load the units evenly
-    st, plan = _plan([(i * (1 << 22), 1 << 20, "f32") for i in range(64)], K=4)
-    assert B.geak_check_plan_info(plan).unit_groups == 1
-    B.geak_check_destroy(plan)
-    st, plan = B.geak_check_plan_dense("bf16", [1 << 27], 8, 0, 0, 0, -1)
-    assert B.geak_check_plan_info(plan).unit_groups == 1
+    # segments all binary32 and of one size, a dense tensor: the plain ranges already load the units evenly; a grid
+    # that fills the chip still rotates the XCDs, a smaller one does not
+    for st_plan in (_plan([(i * (1 << 22), 1 << 20, "f32") for i in range(64)], K=4), B.geak_check_plan_dense("bf16", [1 << 27], 8, 0, 0, 0, -1)):
+        info = B.geak_check_plan_info(st_plan[1])
+        assert info.block_map == B.GEAK_MAP_ROTATED and info.unit_groups == 256
+        ranges = np.array([_range_of_block(b, 1024, 256, B.GEAK_MAP_ROTATED) for b in range(1024)])
+        assert sorted(ranges) == list(range(1024)) and (ranges // 8 == np.arange(1024) // 8).all()       # within its stripe of eight
+        assert len({int(r) % 8 for r in ranges[0::8]}) == 8                                                # XCD 0 takes every position of a stripe in turn
+        B.geak_check_destroy(st_plan[1])
+    st, plan = B.geak_check_plan_dense("f32", [1 << 20], 2, 0, 0, 0, -1)
+    info = B.geak_check_plan_info(plan)
+    assert info.block_map == B.GEAK_MAP_PLAIN and info.unit_groups == 1 and info.grid_blocks < 1024
     B.geak_check_destroy(plan)
 
 
