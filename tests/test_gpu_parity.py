@@ -542,6 +542,25 @@ def test_full_config4_runs_the_layout_by_compute_unit():
         ck.close()
 
 
+def test_layout_by_compute_unit_with_three_blocks_per_unit(oracle_mod):
+    """180 candidates: the blocks' LDS leaves room for three per compute unit, so a unit's group of ranges has three."""
+    print("by unit, three per unit", flush=True)
+    K = 180
+    w = synth.config4(device="cuda", seed=41, num_candidates=K, log2_max=16.5, dtypes=("f32", "f16", "bf16", "i32", "u8"))
+    ck = B.Checker(w.segments, num_candidates=K, atol=w.atol, rtol=w.rtol, equal_nan=w.equal_nan, device=0)
+    try:
+        info = ck.info()
+        assert info.block_map == B.GEAK_MAP_BY_UNIT and info.grid_blocks == 3 * info.unit_groups
+        ck.run(w.ref, w.cands)
+        gpu = ck.read().copy()
+    finally:
+        ck.close()
+    ks = [0, 1, 59, 90, 178, 179]
+    _assert_same(gpu[:, ks], workload_oracle(oracle_mod, w, cand_subset=ks), "three blocks per unit")
+    for (s, k), e in w.expect.items():
+        assert int(gpu[s, k]["mismatch_count"]) == e["count"] and int(gpu[s, k]["first_mismatch"]) == e["first"], (s, k)
+
+
 def test_full_config5(oracle_mod):
     # every third candidate element by element through the oracle (11 x 2^30 elements: what the time limit
     # allows), all 32 by the planted counts and first indices
