@@ -17,8 +17,10 @@ it becomes +-Inf (E4M3's 448 * 2^127, say) -- the specification leaves that case
 the reading used here and by the kernels.
 
 Formats: "mxfp8e4m3", "mxfp8e5m2" (one byte per element), "mxfp4e2m1" (two elements per byte, element 2j in the
-low nibble of byte j), "mxint8" (two's complement, value P / 64).  Plain Python loops and numpy; nothing here is
-shared with the HIP path.
+low nibble of byte j), "mxfp6e2m3", "mxfp6e3m2" (six bits per element, no infinities and no NaN; the specification
+does not fix how they lie in memory: here the codes are packed without gaps, element i in bits 6 i .. 6 i + 5 of the
+payload read as one little-endian number, so a block of 32 elements is 24 bytes), "mxint8" (two's complement,
+value P / 64).  Plain Python loops and numpy; nothing here is shared with the HIP path.
 """
 from __future__ import annotations
 
@@ -29,8 +31,8 @@ import numpy as np
 from .oracle import check_segment, report_segment
 
 MX_BLOCK = 32
-MX_FORMATS = ("mxfp8e4m3", "mxfp8e5m2", "mxfp4e2m1", "mxint8")
-MX_BITS = {"mxfp8e4m3": 8, "mxfp8e5m2": 8, "mxfp4e2m1": 4, "mxint8": 8}
+MX_FORMATS = ("mxfp8e4m3", "mxfp8e5m2", "mxfp4e2m1", "mxint8", "mxfp6e2m3", "mxfp6e3m2")
+MX_BITS = {"mxfp8e4m3": 8, "mxfp8e5m2": 8, "mxfp4e2m1": 4, "mxint8": 8, "mxfp6e2m3": 6, "mxfp6e3m2": 6}
 
 
 def minifloat_value(code: int, ebits: int, mbits: int, bias: int, ieee_specials: bool, nan_is_all_ones: bool) -> float:
@@ -57,6 +59,10 @@ def element_table(fmt: str) -> np.ndarray:
         return np.array([minifloat_value(c, 5, 2, 15, True, False) for c in range(256)])
     if fmt == "mxfp4e2m1":
         return np.array([minifloat_value(c, 2, 1, 1, False, False) for c in range(16)])
+    if fmt == "mxfp6e2m3":
+        return np.array([minifloat_value(c, 2, 3, 1, False, False) for c in range(64)])
+    if fmt == "mxfp6e3m2":
+        return np.array([minifloat_value(c, 3, 2, 3, False, False) for c in range(64)])
     if fmt == "mxint8":
         return np.array([(c - 256 if c >= 128 else c) / 64.0 for c in range(256)])
     raise ValueError(fmt)
@@ -73,6 +79,12 @@ def payload_codes(payload, numel: int, fmt: str) -> np.ndarray:
     if MX_BITS[fmt] == 8:
         return raw[:numel].astype(np.int64)
     codes = np.zeros(numel, dtype=np.int64)
+    if MX_BITS[fmt] == 6:
+        for i in range(numel):
+            bit = 6 * i                                                  # the code may straddle two bytes
+            pair = int(raw[bit // 8]) | (int(raw[bit // 8 + 1]) << 8 if bit % 8 > 2 else 0)
+            codes[i] = (pair >> (bit % 8)) & 0x3F
+        return codes
     for i in range(numel):
         byte = int(raw[i // 2])
         codes[i] = (byte >> 4) & 0xF if i % 2 else byte & 0xF

@@ -112,6 +112,8 @@ def test_dequantize_equals_ldexp_in_binary32(fmt):
         n = ncodes
         if mx.MX_BITS[fmt] == 8:
             payload = np.arange(256, dtype=np.uint8)
+        elif mx.MX_BITS[fmt] == 6:                                   # codes 0 .. 63 in element order, 48 bytes
+            payload = np.frombuffer(sum(c << (6 * c) for c in range(64)).to_bytes(48, "little"), np.uint8)
         else:
             payload = np.array([(2 * j) | ((2 * j + 1) << 4) for j in range(8)], np.uint8)
         scales = np.full((n + 31) // 32, s, np.uint8)
@@ -197,3 +199,62 @@ def test_a_common_power_of_two_scales_the_absolute_error_only():
     assert int(r0["mismatch_count"]) == int(r1["mismatch_count"]) > 0 and int(r0["first_mismatch"]) == int(r1["first_mismatch"])
     assert float(r1["max_abs_err"]) == float(r0["max_abs_err"]) * 2.0 ** 20
     assert float(r1["max_rel_err"]) == float(r0["max_rel_err"])
+
+
+def test_fp6_tables_have_the_stated_extremes():
+    # the specification's table of FP6 encodings.  E2M3: bias 1, largest normal 7.5, least normal 1, largest subnormal
+    # 0.875, least subnormal 0.125.  E3M2: bias 3, largest normal 28, least normal 0.25, largest subnormal 0.1875, least
+    # subnormal 0.0625.  Neither has infinities or NaN; bit 5 is the sign.
+    a, b = mx.element_table("mxfp6e2m3"), mx.element_table("mxfp6e3m2")
+    assert len(a) == 64 and len(b) == 64 and np.isfinite(a).all() and np.isfinite(b).all()
+    assert a[0x1F] == 7.5 and a[0x08] == 1.0 and a[0x07] == 0.875 and a[0x01] == 0.125 and a[0x00] == 0.0
+    assert b[0x1F] == 28.0 and b[0x04] == 0.25 and b[0x03] == 0.1875 and b[0x01] == 0.0625 and b[0x00] == 0.0
+    for t in (a, b):
+        assert all(t[c] < t[c + 1] for c in range(31))                       # positive codes ascend with the code
+        assert all(t[c + 32] == -t[c] for c in range(32)) and math.copysign(1.0, t[32]) == -1.0
+    # every FP6 value is an E4M3 value too (three mantissa bits at most, exponents inside E4M3's range)
+    e4 = set(mx.element_table("mxfp8e4m3")[:0x7F].tolist())
+    assert set(a[:32].tolist()) <= e4 and set(b[:32].tolist()) <= e4
+
+
+def test_fp6_codes_are_packed_without_gaps():
+    # four codes in three bytes: 0x01, 0x02, 0x03, 0x3F -> bits 000001 | 000010 | 000011 | 111111 from the low end:
+    # byte 0 = 01 + low two bits of 0x02 (10) on top = 0x81, byte 1 = high four bits of 0x02 (0000) + low four of 0x03
+    # (0011) on top = 0x30, byte 2 = high two bits of 0x03 (00) + 0x3F on top = 0xFC
+    payload = np.array([0x81, 0x30, 0xFC], np.uint8)
+    assert list(mx.payload_codes(payload, 4, "mxfp6e2m3")) == [0x01, 0x02, 0x03, 0x3F]
+    v = mx.dequantize(payload, np.array([128], np.uint8), 4, "mxfp6e2m3")           # scale 2
+    assert list(v) == [0.25, 0.5, 0.75, -15.0]
+    v = mx.dequantize(payload, np.array([126], np.uint8), 4, "mxfp6e3m2")           # scale 1/2
+    assert list(v) == [0.03125, 0.0625, 0.09375, -14.0]
+    # a whole block: code i in element i, read back in order
+    codes = np.arange(32, dtype=np.int64) * 2 + 1                                   # 1, 3, ..., 63
+    number = sum(int(c) << (6 * i) for i, c in enumerate(codes))
+    block = np.frombuffer(number.to_bytes(24, "little"), np.uint8)
+    assert list(mx.payload_codes(block, 32, "mxfp6e3m2")) == list(codes)
+
+
+def test_fp6_records_equal_those_of_the_same_numbers_in_e4m3():
+    """The same numbers written as FP6 codes and as E4M3 codes must give the same records: the FP6 path against the
+    8-bit one, whose decoder is pinned on its own."""
+    rng = np.random.default_rng(77)
+    for fmt in ("mxfp6e2m3", "mxfp6e3m2"):
+        t6, t8 = mx.element_table(fmt), mx.element_table("mxfp8e4m3")
+        to8 = {}
+        for c8 in range(256):
+            if not math.isnan(t8[c8]):
+                to8[(float(t8[c8]), math.copysign(1.0, t8[c8]))] = c8
+        n = 96
+        def pack(codes):
+            number = sum(int(c) << (6 * i) for i, c in enumerate(codes))
+            return np.frombuffer(number.to_bytes(n * 6 // 8, "little"), np.uint8).copy()
+        ref6 = rng.integers(0, 64, n); cand6 = ref6.copy()
+        step = rng.random(n) < 0.4
+        cand6[step] = (cand6[step] + rng.integers(-2, 3, int(step.sum()))) % 64
+        scales_b = rng.integers(120, 135, n // 32).astype(np.uint8); scales_a = scales_b.copy(); scales_a[1] += 1
+        ref8 = np.array([to8[(float(t6[c]), math.copysign(1.0, t6[c]))] for c in ref6], np.uint8)
+        cand8 = np.array([to8[(float(t6[c]), math.copysign(1.0, t6[c]))] for c in cand6], np.uint8)
+        for atol, rtol in ((0.0, 0.0), (0.05, 0.1)):
+            r6 = mx.check_segment_mx(pack(ref6), scales_b, pack(cand6), scales_a, n, fmt, atol, rtol, False)
+            r8 = mx.check_segment_mx(ref8, scales_b, cand8, scales_a, n, "mxfp8e4m3", atol, rtol, False)
+            assert r6 == r8 and r6["mismatch_count"] > 0
