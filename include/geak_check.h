@@ -61,7 +61,8 @@ typedef enum { GEAK_F32 = 0, GEAK_F16 = 1, GEAK_BF16 = 2, GEAK_I32 = 3, GEAK_I64
                GEAK_U8 = 5 /* also boolean masks stored as bytes */, GEAK_I8 = 6, GEAK_F64 = 7,
                GEAK_F8E4M3 = 8, GEAK_F8E5M2 = 9, /* the 8-bit formats of the OCP 8-bit floating point specification */
                /* element formats of block-scaled segments (geak_segment_mx only) */
-               GEAK_MXFP8_E4M3 = 10, GEAK_MXFP8_E5M2 = 11, GEAK_MXINT8 = 12, GEAK_MXFP4_E2M1 = 13 } geak_dtype;
+               GEAK_MXFP8_E4M3 = 10, GEAK_MXFP8_E5M2 = 11, GEAK_MXINT8 = 12, GEAK_MXFP4_E2M1 = 13,
+               GEAK_MXFP6_E2M3 = 14, GEAK_MXFP6_E3M2 = 15 } geak_dtype;
 
 #define GEAK_MAX_CANDIDATES 256
 #define GEAK_MAX_SEGMENT_NUMEL (1ull << 40)
@@ -196,15 +197,20 @@ geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *s
  * judges them.  A NaN scale makes its 32 elements NaN; the payload's own NaN and infinity codes stay what they
  * are under any scale.
  *   dtype               GEAK_MXFP8_E4M3, GEAK_MXFP8_E5M2 (payload codes as GEAK_F8E4M3 / GEAK_F8E5M2), GEAK_MXINT8
- *                       (two's complement, value code / 64) or GEAK_MXFP4_E2M1 (two four-bit codes per byte, element
+ *                       (two's complement, value code / 64), GEAK_MXFP4_E2M1 (two four-bit codes per byte, element
  *                       2j in the low nibble of byte j: sign, two exponent bits, one mantissa bit; magnitudes 0, 0.5,
- *                       1, 1.5, 2, 3, 4, 6)
+ *                       1, 1.5, 2, 3, 4, 6), GEAK_MXFP6_E2M3 or GEAK_MXFP6_E3M2 (six-bit codes: sign, exponent,
+ *                       mantissa, bias 1 and 3, no infinities and no NaN, largest values 7.5 and 28; the
+ *                       specification leaves their place in memory open: here they are packed without gaps, element
+ *                       i in bits 6 i .. 6 i + 5 of the payload read as one little-endian number, a block of 32
+ *                       elements in 24 bytes)
  *   byte_offset         of the payload within every packed buffer; a multiple of 16
- *   numel               a multiple of 32 (whole blocks); the payload is numel bytes, numel / 2 for the four-bit format
+ *   numel               a multiple of 32 (whole blocks); the payload is numel bytes, numel / 2 for the four-bit
+ *                       format, numel * 3 / 4 for the six-bit ones
  *   scale_byte_offset   of the numel / 32 scale bytes within the same buffer
  * Payloads and scale regions of a plan may not overlap each other.  The algorithmic bytes count payload and
- * scales of every tensor once.  A full work item of the four-bit format is 4096 elements, 2 KiB of payload.  The
- * ulp histogram is not defined for such plans (GEAK_EDTYPE). */
+ * scales of every tensor once.  A full work item of the four- and six-bit formats is 4096 elements, 2 KiB and
+ * 3 KiB of payload.  The ulp histogram is not defined for such plans (GEAK_EDTYPE). */
 typedef struct {
     uint64_t byte_offset;
     uint64_t numel;

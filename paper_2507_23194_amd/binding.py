@@ -22,7 +22,7 @@ GEAK_OK = 0
 GEAK_EINVAL, GEAK_EDTYPE, GEAK_EALIGN, GEAK_EBOUNDS, GEAK_ENOMEM, GEAK_EWORKSPACE, GEAK_EHIP = 1, 2, 3, 4, 5, 6, 7
 GEAK_F32, GEAK_F16, GEAK_BF16, GEAK_I32, GEAK_I64, GEAK_U8, GEAK_I8, GEAK_F64 = 0, 1, 2, 3, 4, 5, 6, 7
 GEAK_F8E4M3, GEAK_F8E5M2 = 8, 9
-GEAK_MXFP8_E4M3, GEAK_MXFP8_E5M2, GEAK_MXINT8, GEAK_MXFP4_E2M1 = 10, 11, 12, 13        # element formats of block-scaled segments
+GEAK_MXFP8_E4M3, GEAK_MXFP8_E5M2, GEAK_MXINT8, GEAK_MXFP4_E2M1, GEAK_MXFP6_E2M3, GEAK_MXFP6_E3M2 = 10, 11, 12, 13, 14, 15        # element formats of block-scaled segments
 GEAK_MAX_CANDIDATES = 256
 GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED, GEAK_ITEM_ROWS, GEAK_ITEM_REFMAP = 1, 2, 4, 8, 16, 32
 GEAK_ULP_BINS = 66
@@ -38,7 +38,8 @@ SEGMENT2D_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_elems
 SEGMENT_MAPPED_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_elems", "<u8"), ("pitch_bytes", "<u8"),
                                  ("ref_byte_offset", "<u8"), ("ref_pitch_bytes", "<u8"), ("ref_elem_stride", "<i4"), ("dtype", "<i4")])
 SEGMENT_MX_DTYPE = np.dtype([("byte_offset", "<u8"), ("numel", "<u8"), ("scale_byte_offset", "<u8"), ("dtype", "<i4"), ("reserved", "<i4")])
-MX_DTYPE_CODE = {"mxfp8e4m3": GEAK_MXFP8_E4M3, "mxfp8e5m2": GEAK_MXFP8_E5M2, "mxint8": GEAK_MXINT8, "mxfp4e2m1": GEAK_MXFP4_E2M1}
+MX_DTYPE_CODE = {"mxfp8e4m3": GEAK_MXFP8_E4M3, "mxfp8e5m2": GEAK_MXFP8_E5M2, "mxint8": GEAK_MXINT8, "mxfp4e2m1": GEAK_MXFP4_E2M1,
+                 "mxfp6e2m3": GEAK_MXFP6_E2M3, "mxfp6e3m2": GEAK_MXFP6_E3M2}
 SEGMENT_ANY_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_elems", "<u8"), ("pitch_bytes", "<u8"),
                               ("aux_byte_offset", "<u8"), ("aux_pitch_bytes", "<u8"), ("ref_elem_stride", "<i4"), ("dtype", "<i4"),
                               ("kind", "<i4"), ("reserved", "<i4")])

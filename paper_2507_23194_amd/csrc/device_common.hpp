@@ -95,9 +95,17 @@ template <> struct Traits<GEAK_MXINT8>     { static constexpr int E = 16, W = 1;
 // The four-bit format never reaches the arithmetic as such: the loads rewrite sixteen E2M1 codes (8 bytes) as the
 // sixteen E4M3 byte codes of the same values, so a lane's "vector" is sixteen elements here too.
 template <> struct Traits<GEAK_MXFP4_E2M1> { static constexpr int E = 16, W = 1; };
+// The same for the six-bit formats: sixteen codes (12 bytes) become sixteen E4M3 byte codes (every E2M3 and E3M2
+// value is an E4M3 value).
+template <> struct Traits<GEAK_MXFP6_E2M3> { static constexpr int E = 16, W = 1; };
+template <> struct Traits<GEAK_MXFP6_E3M2> { static constexpr int E = 16, W = 1; };
 // Block-scaled element formats: a 16-byte vector holds half a block of 32 elements, so one scale byte
 // belongs to every vector.
-template <int DT> constexpr bool kScaled = (DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP8_E5M2 || DT == GEAK_MXINT8 || DT == GEAK_MXFP4_E2M1);
+template <int DT> constexpr bool kScaled = (DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP8_E5M2 || DT == GEAK_MXINT8 || DT == GEAK_MXFP4_E2M1 ||
+                                           DT == GEAK_MXFP6_E2M3 || DT == GEAK_MXFP6_E3M2);
+// formats whose loads rewrite sub-byte codes as E4M3 byte codes
+template <int DT> constexpr bool kFp6 = (DT == GEAK_MXFP6_E2M3 || DT == GEAK_MXFP6_E3M2);
+template <int DT> constexpr bool kSubByte = (DT == GEAK_MXFP4_E2M1 || kFp6<DT>);
 
 __device__ __forceinline__ float bits_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ double bits_d(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(double, (u64)lo | ((u64)hi << 32)); }
@@ -218,13 +226,67 @@ __device__ __forceinline__ u32x4 load_e2m1_slot(const unsigned char *base, uint3
     return expand_e2m1(w[0], w[1]);
 }
 
+// Four six-bit codes, one in the low bits of each byte of u (bit 5 the sign), as the E4M3 byte codes of the same values.
+//   E2M3 (bias 1): magnitude code c = e e m m m.  c >= 8: 2^(e-1) * (1 + m/8), E4M3 exponent field e + 6, the same
+//                  mantissa: code c + 0x30.  c < 8: the subnormal c / 8 = 0, 2^-3, 2^-2, 1.5 * 2^-2, 2^-1, 1.25 * 2^-1,
+//                  1.5 * 2^-1, 1.75 * 2^-1: codes 0x00, 0x20, 0x28, 0x2C, 0x30, 0x32, 0x34, 0x36 (a byte-permute table).
+//   E3M2 (bias 3): c = e e e m m.  c >= 4: 2^(e-3) * (1 + m/4), exponent field e + 4, mantissa m0: code 2 c + 0x20.
+//                  c < 4: c / 16 = 0, 2^-4, 2^-3, 1.5 * 2^-3: codes 0x00, 0x18, 0x20, 0x24.
+template <int DT>
+__device__ __forceinline__ uint32_t fp6_four(uint32_t u)
+{
+    constexpr uint32_t kLeastNormal = DT == GEAK_MXFP6_E2M3 ? 8u : 4u;
+    const uint32_t mag = u & 0x1F1F1F1Fu;
+    const uint32_t top = (mag + (0x80u - kLeastNormal) * 0x01010101u) & 0x80808080u;      // bit 7 of a byte: its code is a normal number's
+    const uint32_t normal_bytes = (top - (top >> 7)) | top;                              // 0xFF in those bytes
+    uint32_t normal, subnormal;
+    if constexpr (DT == GEAK_MXFP6_E2M3) {
+        normal = mag + 0x30303030u;
+        subnormal = __builtin_amdgcn_perm(0x36343230u, 0x2C282000u, mag & 0x07070707u);     // selector i: byte i of the table
+    } else {
+        normal = (mag << 1) + 0x20202020u;                                                  // mag <= 31: no bit leaves its byte
+        subnormal = __builtin_amdgcn_perm(0u, 0x24201800u, mag & 0x03030303u);
+    }
+    const uint32_t code = (normal & normal_bytes) | (subnormal & ~normal_bytes);
+    return code | ((u & 0x20202020u) << 2);
+}
+// Sixteen six-bit codes -- element i in bits 6 i .. 6 i + 5 of the 96 bits {w0, w1, w2} -- as sixteen E4M3 byte codes.
+template <int DT>
+__device__ __forceinline__ u32x4 expand_fp6(uint32_t w0, uint32_t w1, uint32_t w2)
+{
+    // elements 4 j .. 4 j + 3 are the 24 bits from bit 24 j on
+    const uint32_t x[4] = {w0, __builtin_amdgcn_alignbit(w1, w0, 24), __builtin_amdgcn_alignbit(w2, w1, 16), w2 >> 8};
+    u32x4 q;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t spread = (x[j] & 0x3Fu) | ((x[j] << 2) & 0x3F00u) | ((x[j] << 4) & 0x3F0000u) | ((x[j] << 6) & 0x3F000000u);
+        q[j] = fp6_four<DT>(spread);
+    }
+    return q;
+}
+// Slot `slot` of an item of a six-bit format: 12 bytes of payload (on a 4-byte boundary), as sixteen byte codes.
+template <int DT>
+__device__ __forceinline__ u32x4 load_fp6_slot(const unsigned char *base, uint32_t slot)
+{
+    const GEAK_AS_GLOBAL uint32_t *w = (const GEAK_AS_GLOBAL uint32_t *)(base + (u64)slot * 12u);
+    const uint32_t w0 = __builtin_nontemporal_load(w), w1 = __builtin_nontemporal_load(w + 1), w2 = __builtin_nontemporal_load(w + 2);
+    return expand_fp6<DT>(w0, w1, w2);
+}
+// A slot of a format narrower than a byte.
+template <int DT>
+__device__ __forceinline__ u32x4 load_sub_byte_slot(const unsigned char *base, uint32_t slot)
+{
+    if constexpr (kFp6<DT>) return load_fp6_slot<DT>(base, slot);
+    else return load_e2m1_slot(base, slot);
+}
+
 template <int DT>
 __device__ __forceinline__ u32x4 load_vec(const unsigned char *base, int lane, int v, uint32_t n, bool full)
 {
     constexpr uint32_t E = Traits<DT>::E;
-    if constexpr (DT == GEAK_MXFP4_E2M1) {              // whole blocks only: a slot is inside the item or behind it
+    if constexpr (kSubByte<DT>) {                       // whole blocks only: a slot is inside the item or behind it
         const uint32_t slot = (uint32_t)(v * kWaveSize + lane);
-        if (full || slot * E < n) return load_e2m1_slot(base, slot);
+        if (full || slot * E < n) return load_sub_byte_slot<DT>(base, slot);
         return u32x4{0u, 0u, 0u, 0u};
     }
     global_vec_ptr p = (global_vec_ptr)base + (v * kWaveSize + lane);
@@ -305,8 +367,8 @@ __device__ __forceinline__ u32x4 load_slot(const unsigned char *base, uint32_t s
 {
     const SlotPlace sp = slot_place<DT, KIND>(slot, n, sh);
     first = sp.first;
-    if constexpr (DT == GEAK_MXFP4_E2M1) {              // plain tails of whole blocks only
-        if (sp.valid > 0) return load_e2m1_slot(base, sp.vec);
+    if constexpr (kSubByte<DT>) {                       // plain tails of whole blocks only
+        if (sp.valid > 0) return load_sub_byte_slot<DT>(base, sp.vec);
         return u32x4{0u, 0u, 0u, 0u};
     }
     if constexpr (KIND == kTailRows) return load_partial_from<DT>((global_vec_ptr)(base + (u64)sp.row * sh.pitch) + sp.vec, sp.lo, sp.valid);
@@ -403,7 +465,7 @@ __device__ __forceinline__ u32x4 load_shaped(const unsigned char *base, int lane
 template <int DT, int BYTE>
 __device__ __forceinline__ float f8_to_f32(uint32_t word)
 {
-    if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP4_E2M1) return __builtin_amdgcn_cvt_f32_fp8((int)word, BYTE);
+    if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3 || kSubByte<DT>) return __builtin_amdgcn_cvt_f32_fp8((int)word, BYTE);
     else if constexpr (DT == GEAK_MXINT8) return (float)((int)(word << (24 - 8 * BYTE)) >> 24);     // the code as an integer; the scale carries the 1/64
     else return __builtin_amdgcn_cvt_f32_bf8((int)word, BYTE);
 }
@@ -418,7 +480,7 @@ __device__ __forceinline__ F32Pair f8_pair_to_f32(uint32_t word)
         return F32Pair{f8_to_f32<DT, HI ? 2 : 0>(word), f8_to_f32<DT, HI ? 3 : 1>(word)};
     } else {
         f32x2 v;
-        if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3 || DT == GEAK_MXFP4_E2M1) v = __builtin_amdgcn_cvt_pk_f32_fp8((int)word, HI);
+        if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_MXFP8_E4M3 || kSubByte<DT>) v = __builtin_amdgcn_cvt_pk_f32_fp8((int)word, HI);
         else v = __builtin_amdgcn_cvt_pk_f32_bf8((int)word, HI);
         return F32Pair{v[0], v[1]};
     }
@@ -498,6 +560,8 @@ __device__ __forceinline__ void for_scaled_dtype(int dtype, F &&f)
     case GEAK_MXFP8_E4M3: f(Index<GEAK_MXFP8_E4M3>{}); break;
     case GEAK_MXFP8_E5M2: f(Index<GEAK_MXFP8_E5M2>{}); break;
     case GEAK_MXFP4_E2M1: f(Index<GEAK_MXFP4_E2M1>{}); break;
+    case GEAK_MXFP6_E2M3: f(Index<GEAK_MXFP6_E2M3>{}); break;
+    case GEAK_MXFP6_E3M2: f(Index<GEAK_MXFP6_E3M2>{}); break;
     default:              f(Index<GEAK_MXINT8>{}); break;
     }
 }

@@ -22,17 +22,23 @@ inline int elem_size(int dtype)
     case GEAK_I64: case GEAK_F64: return 8;
     case GEAK_U8: case GEAK_I8: case GEAK_F8E4M3: case GEAK_F8E5M2: return 1;
     case GEAK_MXFP8_E4M3: case GEAK_MXFP8_E5M2: case GEAK_MXINT8: return 1;       // the payload's elements
-    case GEAK_MXFP4_E2M1: return 1;                                               // nominal: a byte holds two (payload_bytes)
+    case GEAK_MXFP4_E2M1: case GEAK_MXFP6_E2M3: case GEAK_MXFP6_E3M2: return 1;   // nominal: narrower than a byte (payload_bytes)
     default: return 4;
     }
 }
 
-// Bytes that n elements of a dtype occupy (n even for the four-bit format), and elements of one full work item.
-inline uint64_t payload_bytes(int dtype, uint64_t n) { return dtype == GEAK_MXFP4_E2M1 ? n / 2 : n * (uint64_t)elem_size(dtype); }
+// Bytes that n elements of a dtype occupy (n a multiple of 2 for the four-bit format, of 4 for the six-bit ones),
+// and elements of one full work item.
+inline bool is_fp6_dtype(int dtype) { return dtype == GEAK_MXFP6_E2M3 || dtype == GEAK_MXFP6_E3M2; }
+inline uint64_t payload_bytes(int dtype, uint64_t n)
+{
+    return dtype == GEAK_MXFP4_E2M1 ? n / 2 : is_fp6_dtype(dtype) ? n / 4 * 3 : n * (uint64_t)elem_size(dtype);
+}
 inline uint64_t elems_per_item(int dtype)
 {
-    // the four-bit codes are rewritten as byte codes when they are loaded: an item is 4096 of them, 2 KiB of payload
-    return dtype == GEAK_MXFP4_E2M1 ? (uint64_t)kItemBytes : (uint64_t)kItemBytes / (uint64_t)elem_size(dtype);
+    // the four- and six-bit codes are rewritten as byte codes when they are loaded: an item is 4096 of them, 2 KiB
+    // and 3 KiB of payload
+    return (dtype == GEAK_MXFP4_E2M1 || is_fp6_dtype(dtype)) ? (uint64_t)kItemBytes : (uint64_t)kItemBytes / (uint64_t)elem_size(dtype);
 }
 
 // Partial result of one (worker, segment) run for one candidate; 16 bytes.
@@ -75,7 +81,7 @@ constexpr int32_t kRefMapped = 1, kMxScaled = 4;
 constexpr int kRefStrideShift = 8;
 constexpr uint64_t kMaxRefStride = (1ull << 22) - 1;
 constexpr uint64_t kMxBlock = 32;
-inline bool is_mx_dtype(int dtype) { return dtype >= GEAK_MXFP8_E4M3 && dtype <= GEAK_MXFP4_E2M1; }
+inline bool is_mx_dtype(int dtype) { return dtype >= GEAK_MXFP8_E4M3 && dtype <= GEAK_MXFP6_E3M2; }
 struct SegDesc {
     uint64_t byte_offset;
     uint64_t numel;

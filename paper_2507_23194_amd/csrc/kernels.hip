@@ -1158,6 +1158,8 @@ template <> struct ItemOf<GEAK_MXFP8_E4M3> { typedef Fp8Item<GEAK_MXFP8_E4M3> ty
 template <> struct ItemOf<GEAK_MXFP8_E5M2> { typedef Fp8Item<GEAK_MXFP8_E5M2> type; };
 template <> struct ItemOf<GEAK_MXINT8> { typedef Fp8Item<GEAK_MXINT8> type; };
 template <> struct ItemOf<GEAK_MXFP4_E2M1> { typedef Fp8Item<GEAK_MXFP4_E2M1> type; };
+template <> struct ItemOf<GEAK_MXFP6_E2M3> { typedef Fp8Item<GEAK_MXFP6_E2M3> type; };
+template <> struct ItemOf<GEAK_MXFP6_E3M2> { typedef Fp8Item<GEAK_MXFP6_E3M2> type; };
 
 __device__ __forceinline__ WaveState uniform_state(const WaveState &in)
 {
@@ -1835,6 +1837,11 @@ __device__ __forceinline__ float elem_f(const unsigned char *base, u64 idx)
         const uint32_t nib = ((uint32_t)base[idx >> 1] >> (4 * (uint32_t)(idx & 1))) & 0xFu;
         const uint32_t code = (uint32_t)((0x4C4844403C383000ull >> (8 * (nib & 7u))) & 0xFFu) | ((nib & 8u) << 4);
         return f8_to_f32<DT, 0>(code);
+    }
+    else if constexpr (kFp6<DT>) {                           // element idx is the six bits from bit 6 idx on; its E4M3 code as the loads form it
+        const u64 bit = 6 * idx;
+        const uint32_t lo = base[bit >> 3], hi = (bit & 7) > 2 ? (uint32_t)base[(bit >> 3) + 1] : 0u;       // the code may straddle two bytes
+        return f8_to_f32<DT, 0>(fp6_four<DT>(((lo | (hi << 8)) >> (bit & 7)) & 0x3Fu));
     }
     else if constexpr (DT == GEAK_F8E4M3 || DT == GEAK_F8E5M2 || kScaled<DT>) return f8_to_f32<DT, 0>(base[idx]);     // block-scaled: the bare code's value
     else if constexpr (DT == GEAK_F16) return (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t *>(base)[idx]);

@@ -36,7 +36,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
     bool any_mapped = false;
     for (uint64_t s = 0; s < nsegs; ++s) {
         const SegDesc &g = segs[s];
-        if (g.dtype < GEAK_F32 || g.dtype > GEAK_MXFP4_E2M1) return GEAK_EDTYPE;
+        if (g.dtype < GEAK_F32 || g.dtype > GEAK_MXFP6_E3M2) return GEAK_EDTYPE;
         if (is_mx_dtype(g.dtype) != (g.layout == kMxScaled)) return GEAK_EDTYPE;     // block-scaled element formats belong to block-scaled segments only
         if (g.layout != kMxScaled && g.layout != 0 && (!(g.layout & kRefMapped) || (g.layout & 0xFE) != 0 || g.layout < 0 ||
                                                        seg_ref_stride(g) > kMaxRefStride)) return GEAK_EINVAL;
@@ -187,7 +187,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                 uint64_t done = 0;
                 auto push = [&](uint64_t n, bool full) {
                     geak_item it{};
-                    it.byte_offset = row_start + payload_bytes(g.dtype, done);     // done is even for the four-bit format
+                    it.byte_offset = row_start + payload_bytes(g.dtype, done);     // done is a multiple of 4096 for the sub-byte formats
                     it.elem_start = r * g.row_elems + done;
                     it.segment = (uint32_t)s;
                     it.numel = (uint16_t)n;

@@ -1,6 +1,6 @@
 """Block-scaled (MX) segments on the GPU against the oracle's front end (oracle/mx.py: every element written
 out as the binary32 value it encodes, then the unchanged rule): records and mismatch reports for the three
-one-byte element formats and the four-bit one, all payload codes and scale bytes (2^-127, 2^127, NaN among them), candidates whose
+one-byte element formats, the four-bit one and the two six-bit ones, all payload codes and scale bytes (2^-127, 2^127, NaN among them), candidates whose
 payload, scales or both differ, sizes from one block to several work items with every tail shape."""
 import numpy as np
 import pytest
@@ -12,7 +12,7 @@ from test_gpu_parity import _assert_same
 
 pytestmark = pytest.mark.gpu
 
-FORMATS = ["mxfp8e4m3", "mxfp8e5m2", "mxint8", "mxfp4e2m1"]
+FORMATS = ["mxfp8e4m3", "mxfp8e5m2", "mxint8", "mxfp4e2m1", "mxfp6e2m3", "mxfp6e3m2"]
 
 
 def _tensors(rng, fmt, n, K):
@@ -124,7 +124,7 @@ def test_several_segments_of_all_formats(oracle_mod):
     rng = np.random.default_rng(8900)
     K = 7
     sizes = [64, 2048, 4096 * 2 + 512, 32, 4096, 1024 + 64, 4096 * 3]
-    fmts = [FORMATS[i % 4] for i in range(len(sizes))]
+    fmts = [FORMATS[i % len(FORMATS)] for i in range(len(sizes))]
     segs = [_tensors(rng, f, n, K) for f, n in zip(fmts, sizes)]
     bufs, table = _pack(segs)
     tols = [(10.0 ** -(i % 3), 0.05 * (i % 4)) for i in range(len(sizes))]
@@ -153,7 +153,7 @@ def test_random_block_scaled_plan(oracle_mod, seed):
     work items), random candidate count and per-segment tolerances; records and reports against the oracle."""
     rng = np.random.default_rng(9500 + seed)
     nsegs, K = int(rng.integers(1, 7)), int(rng.integers(1, 10))
-    fmts = [FORMATS[int(rng.integers(0, 4))] for _ in range(nsegs)]
+    fmts = [FORMATS[int(rng.integers(0, len(FORMATS)))] for _ in range(nsegs)]
     sizes = [32 * int(rng.choice([1, int(rng.integers(2, 33)), int(rng.integers(33, 129)), int(rng.integers(129, 400))])) for _ in range(nsegs)]
     print("random block-scaled plan", seed, list(zip(fmts, sizes)), "K", K, flush=True)
     segs = [_tensors(rng, f, n, K) for f, n in zip(fmts, sizes)]
@@ -258,3 +258,28 @@ def test_read_probe_over_a_block_scaled_plan(oracle_mod):
         _assert_same(ck.read().copy(), first, "run after a probe")
     finally:
         ck.close()
+
+
+@pytest.mark.parametrize("fmt", ["mxfp6e2m3", "mxfp6e3m2"])
+def test_every_six_bit_code_at_every_position(oracle_mod, fmt):
+    """Each of the 64 codes in each of a lane's sixteen positions (the codes straddle bytes and words differently at
+    each), against candidates holding the next code, the negated one and the same one under another scale."""
+    print("mx six-bit codes", fmt, flush=True)
+    n = 4096 + 1024                                           # a full item and a tail
+    i = np.arange(n)
+    codes = (i // 16 + i % 16 * 5) % 64                        # position p of slot s holds code (s + 5 p) mod 64: every pair occurs
+
+    def pack(c):
+        out = np.zeros(n * 3 // 4, np.uint8)
+        for j in range(0, n, 4):                               # four codes in three bytes
+            v = int(c[j]) | int(c[j + 1]) << 6 | int(c[j + 2]) << 12 | int(c[j + 3]) << 18
+            out[j * 3 // 4: j * 3 // 4 + 3] = [v & 0xFF, (v >> 8) & 0xFF, v >> 16]
+        return out
+    assert {(int(c), int(p)) for c, p in zip(codes, i % 16)} == {(c, p) for c in range(64) for p in range(16)}
+    scales = np.full(n // 32, 127, np.uint8)
+    other = scales.copy(); other[::3] = 129
+    segs = [[(pack(codes), scales), (pack((codes + 1) % 64), scales), (pack(codes ^ 0x20), scales), (pack(codes), other)]]
+    _compare(oracle_mod, segs, [fmt], 3, 0.01, 0.1, False, f"{fmt} all codes")
+    rec = _compare(oracle_mod, [[(pack(codes), scales), (pack(codes), scales), (pack(codes ^ 0x20), scales)]], [fmt], 2, 0.0, 0.0, False,
+                   f"{fmt} all codes, zero tolerance")
+    assert rec[0, 0]["pass"] == 1 and rec[0, 1]["mismatch_count"] == n - (codes % 32 == 0).sum()      # only +0 against -0 passes

@@ -72,7 +72,7 @@ def test_mixed_table(oracle_mod, seed):
             table.append(["mapped", start + entry[0], rows, cols, entry[3], entry[4], entry[5], entry[6], dt])      # reference offset patched below
             checks.append(("mapped", len(table) - 1))
         elif kind in ("mx8", "mx4"):
-            fmt = str(rng.choice(["mxfp8e4m3", "mxfp8e5m2", "mxint8"])) if kind == "mx8" else "mxfp4e2m1"
+            fmt = str(rng.choice(["mxfp8e4m3", "mxfp8e5m2", "mxint8"])) if kind == "mx8" else str(rng.choice(["mxfp4e2m1", "mxfp6e2m3", "mxfp6e3m2"]))
             n = 32 * int(rng.integers(1, 400))
             tensors = _tensors(rng, fmt, n, K)
             blob = lambda t: np.concatenate([t[0], np.full(5, 0xEE, np.uint8), t[1]])

@@ -581,6 +581,18 @@ def test_block_scaled_plan_table(lib):
         [(64, 0, 4096, True), (64 + 2048, 4096, 4096, True), (64 + 4096, 8192, 96, False)]
     assert B.geak_check_plan_info(plan).algorithmic_bytes == 3 * ((8192 + 96) // 2 + (8192 + 96) // 32)
     B.geak_check_destroy(plan)
+    # the six-bit formats: four elements in three bytes, a full item is 4096 elements = 3 KiB of payload
+    for fmt in ("mxfp6e2m3", "mxfp6e3m2"):
+        st, plan = B.geak_check_plan_mx([(64, 4096 * 2 + 96, 9000, fmt)], None, 2, 0, 0, 0, -1)
+        assert st == B.GEAK_OK
+        items = B.geak_check_plan_items(plan)
+        assert [(int(i["byte_offset"]), int(i["elem_start"]), int(i["numel"]), bool(i["flags"] & B.GEAK_ITEM_FULL)) for i in items] == \
+            [(64, 0, 4096, True), (64 + 3072, 4096, 4096, True), (64 + 6144, 8192, 96, False)]
+        assert all(int(i["dtype"]) == B.MX_DTYPE_CODE[fmt] for i in items)
+        assert B.geak_check_plan_info(plan).algorithmic_bytes == 3 * ((8192 + 96) * 3 // 4 + (8192 + 96) // 32)
+        B.geak_check_destroy(plan)
+    assert B.geak_check_plan_mx([(0, 64, 48, "mxfp6e2m3")], None, 1, 0, 0, 0, -1)[0] == B.GEAK_OK         # 64 elements: 48 bytes
+    assert B.geak_check_plan_mx([(0, 64, 47, "mxfp6e2m3")], None, 1, 0, 0, 0, -1)[0] == B.GEAK_EBOUNDS
     # its payload is half as long: scales may sit where a one-byte format's payload would still run
     assert B.geak_check_plan_mx([(0, 64, 32, "mxfp4e2m1")], None, 1, 0, 0, 0, -1)[0] == B.GEAK_OK
     assert B.geak_check_plan_mx([(0, 64, 31, "mxfp4e2m1")], None, 1, 0, 0, 0, -1)[0] == B.GEAK_EBOUNDS
@@ -591,13 +603,13 @@ def test_block_scaled_plan_table(lib):
     ((0, 40, 100, "mxfp8e4m3"), B.GEAK_EINVAL),                # ragged last block
     ((0, 64, 63, "mxfp8e4m3"), B.GEAK_EBOUNDS),                # scales inside the payload
     ((0, 64, 100, "f8e4m3"), B.GEAK_EDTYPE),                   # not a block-scaled element format
-    ((0, 64, 100, 14), B.GEAK_EDTYPE),
+    ((0, 64, 100, 16), B.GEAK_EDTYPE),
     ((0, 64, 2 ** 64 - 1, "mxint8"), B.GEAK_EBOUNDS),
 ])
 def test_block_scaled_plan_rejects(lib, seg, status):
     st, plan = B.geak_check_plan_mx([seg], None, 2, 0.0, 0.0, False, -1)
     assert st == status and plan is None
-    for code in (B.GEAK_MXFP8_E4M3, B.GEAK_MXFP8_E5M2, B.GEAK_MXINT8, B.GEAK_MXFP4_E2M1):    # these codes are not for the other plan calls
+    for code in (B.GEAK_MXFP8_E4M3, B.GEAK_MXFP8_E5M2, B.GEAK_MXINT8, B.GEAK_MXFP4_E2M1, B.GEAK_MXFP6_E2M3, B.GEAK_MXFP6_E3M2):    # these codes are not for the other plan calls
         assert B.geak_check_plan([(0, 64, code)], 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
         assert B.geak_check_plan_pitched([(0, 2, 32, 32, code)], None, 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
         assert B.geak_check_plan_mapped([(0, 2, 32, 32, 0, 0, 1, code)], None, 2, 0.0, 0.0, False, -1)[0] == B.GEAK_EDTYPE
@@ -689,10 +701,10 @@ def test_random_mapped_and_block_scaled_tables(lib, seed):
     assert all(cursor.get(sg, 0) == segs[sg][1] * segs[sg][2] for sg in range(len(segs)))
     B.geak_check_destroy(plan)
     # --- block-scaled segments
-    bits = {"mxfp8e4m3": 8, "mxfp8e5m2": 8, "mxint8": 8, "mxfp4e2m1": 4}
+    bits = {"mxfp8e4m3": 8, "mxfp8e5m2": 8, "mxint8": 8, "mxfp4e2m1": 4, "mxfp6e2m3": 6, "mxfp6e3m2": 6}
     segs, off = [], 0
     for _ in range(int(rng.integers(1, 30))):
-        fmt = list(bits)[int(rng.integers(0, 4))]
+        fmt = list(bits)[int(rng.integers(0, len(bits)))]
         n = 32 * int(rng.choice([0, 1, int(rng.integers(2, 200)), int(rng.integers(200, 3000))]))
         off = (off + 15) // 16 * 16
         pb = n * bits[fmt] // 8
