@@ -17,6 +17,8 @@ from .oracle import (  # noqa: F401
     check_ragged,
     check_dense_chunked,
     check_segment_mapped,
+    check_segment_nd,
+    gather_nd,
     gather_rows,
     combine_records,
     host_cores,

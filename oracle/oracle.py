@@ -218,6 +218,43 @@ def check_segment_mapped(ref, cand, rows: int, row_elems: int, dtype: str, atol:
     return check_segment(b, a, rows * row_elems, dtype, atol, rtol, equal_nan)
 
 
+def gather_nd(buf, shape, stride_bytes, dtype: str, byte_offset: int) -> np.ndarray:
+    """The elements of an N-d layout gathered into one contiguous array of raw storage, row-major over `shape`:
+    element (i0, i1, ...) is read at byte_offset + i0 * stride_bytes[0] + i1 * stride_bytes[1] + ...  A stride of 0
+    repeats the dimension (a broadcast operand).  Plain index arithmetic, nothing else."""
+    w = ELEM_SIZE[dtype]
+    raw = _as_bytes(buf)
+    if byte_offset % w or any(int(t) % w for t in stride_bytes) or len(shape) != len(stride_bytes):
+        raise ValueError("offsets and strides must be multiples of the element size, one stride per dimension")
+    store = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[w]
+    elems = raw[: raw.size // w * w].view(store)
+    total = 1
+    for e in shape:
+        total *= int(e)
+    out = np.zeros(total, dtype=store)
+    index = [0] * len(shape)
+    for flat in range(total):
+        at = byte_offset
+        for d in range(len(shape)):
+            at += index[d] * int(stride_bytes[d])
+        out[flat] = elems[at // w]
+        for d in range(len(shape) - 1, -1, -1):              # the next index in row-major order
+            index[d] += 1
+            if index[d] < int(shape[d]):
+                break
+            index[d] = 0
+    return out
+
+
+def check_segment_nd(ref, cand, shape, dtype: str, atol: float, rtol: float, equal_nan: bool, cand_byte_offset: int,
+                     cand_stride_bytes, ref_byte_offset: int, ref_stride_bytes):
+    """One (segment, candidate) pair of N-d tensors, each with its own strides (the reference's may be 0 where it is
+    broadcast): element by element in row-major order of `shape`, the rule itself check_segment's, unchanged."""
+    b = gather_nd(ref, shape, ref_stride_bytes, dtype, ref_byte_offset)
+    a = gather_nd(cand, shape, cand_stride_bytes, dtype, cand_byte_offset)
+    return check_segment(b, a, b.size, dtype, atol, rtol, equal_nan)
+
+
 def combine_records(parts, offsets):
     """Fold the records of consecutive chunks of one tensor (chunk i starts at flat index offsets[i]) into the
     record of the whole tensor.  Every field of the record is a sum, a least index or a maximum over the

@@ -79,3 +79,41 @@ def test_transposed_reference_equals_plain_check_of_its_transpose(oracle_mod):
     picked = np.ascontiguousarray(wide[:, 2::3][:, :cols])
     g = oracle_mod.gather_rows(wide.view(np.uint8).reshape(-1), rows, cols, "i32", 8, (3 * cols + 5) * 4, 3)
     assert (g.view(np.int32) == picked.reshape(-1)).all()
+
+
+def test_gather_nd_equals_numpys_own_strided_views(oracle_mod):
+    """The N-d index map against the library's: broadcasting, transposes and slices of a numpy array are strided
+    views whose strides numpy computes itself; gathering by those strides must give the view's elements in order."""
+    rng = np.random.default_rng(5)
+    for dt, np_t in (("f32", np.float32), ("bf16", np.uint16), ("i64", np.int64), ("u8", np.uint8)):
+        base = rng.integers(0, 200, (3, 4, 5, 6)).astype(np_t)
+        views = [base, base.transpose(2, 0, 3, 1), base[:, 1:3, ::2, 1:], base.transpose(3, 2, 1, 0)[::2],
+                 np.broadcast_to(base[:, :1, :, :1], (3, 7, 5, 2)), np.broadcast_to(base[1, 2, 3, 4:5].reshape(()), (2, 3, 4)),
+                 np.broadcast_to(base[None, 0, :, 0, :], (4, 4, 6))]
+        for v in views:
+            off = v.__array_interface__["data"][0] - base.__array_interface__["data"][0]
+            got = oracle_mod.gather_nd(base, v.shape, v.strides, dt, off)
+            assert np.array_equal(got, np.ascontiguousarray(v).reshape(-1).view(got.dtype)), (dt, v.shape, v.strides)
+    # two dimensions: the 2-D map is the special case
+    buf = rng.integers(0, 255, 4000).astype(np.uint8)
+    assert np.array_equal(oracle_mod.gather_nd(buf, (7, 9), (80, 8), "f32", 12), oracle_mod.gather_rows(buf, 7, 9, "f32", 12, 80, 2))
+    with pytest.raises(ValueError):
+        oracle_mod.gather_nd(buf, (2, 2), (6, 4), "f32", 0)
+
+
+def test_nd_records_by_hand_and_against_the_plain_check(oracle_mod):
+    # candidate [2, 2, 3] contiguous; reference [2, 1, 3] broadcast over the middle dimension
+    ref = np.array([1, 2, 3, 10, 20, 30], np.float32)
+    cand = np.array([1, 2, 3, 1, 2, 4, 10, 20, 30, 11, 20, 30], np.float32)        # elements (0,1,2) and (1,1,0) differ by 1
+    r = oracle_mod.check_segment_nd(ref, cand, (2, 2, 3), "f32", 0.5, 0.0, False, 0, (24, 12, 4), 0, (12, 0, 4))
+    assert (int(r["pass"]), int(r["mismatch_count"]), int(r["first_mismatch"])) == (0, 2, 5)
+    assert float(r["max_abs_err"]) == 1.0 and float(r["max_rel_err"]) == float(np.float32(1.0) / np.float32(3.0))
+    r = oracle_mod.check_segment_nd(ref, cand, (2, 2, 3), "f32", 1.0, 0.0, False, 0, (24, 12, 4), 0, (12, 0, 4))
+    assert int(r["pass"]) == 1 and int(r["first_mismatch"]) == -1                  # inclusive: 1 <= 1
+    # the same through numpy's broadcasting and the plain check
+    rng = np.random.default_rng(6)
+    b = rng.standard_normal((3, 1, 4, 1)).astype(np.float32)
+    a = (np.broadcast_to(b, (3, 5, 4, 6)) + (rng.random((3, 5, 4, 6)) < 0.1) * 0.25).astype(np.float32)
+    want = oracle_mod.check_segment(np.ascontiguousarray(np.broadcast_to(b, a.shape)), a, a.size, "f32", 1e-3, 1e-3, False)
+    got = oracle_mod.check_segment_nd(b, a, a.shape, "f32", 1e-3, 1e-3, False, 0, a.strides, 0, (16, 0, 4, 0))
+    assert got == want and got["mismatch_count"] > 0
