@@ -226,6 +226,43 @@ geak_status geak_check_plan_mx(geak_plan **out, const geak_segment_mx *segs, con
                                uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
                                int32_t equal_nan, int32_t device);
 
+/* N-d segments (section 3.1: the outputs that are compared are tensors, and what a reference implementation returns
+ * need not be laid out like what a generated kernel writes): every tensor of the unit test is an N-d array of up
+ * to GEAK_MAX_DIMS dimensions and the reference has strides of its own -- 0 along a dimension where it is broadcast
+ * against the candidates, a permutation of the candidates' where it is a transposed view, anything else that
+ * numpy-style strides express.  The rule is applied to element (i0, i1, ...) of the candidate against element
+ * (i0, i1, ...) of the reference; flat indices (first_mismatch, the mismatch report) are row-major over `shape`.
+ *   byte_offset        of the candidates' element (0, ..., 0) within every candidate buffer
+ *   ref_byte_offset    of the reference's element (0, ..., 0) within the reference buffer
+ *   shape              extents, outermost first; the first ndim entries are used (ndim 0: one element)
+ *   stride_bytes       candidates: bytes from one index of a dimension to the next; multiples of the element size;
+ *                      the innermost is the element size, and every other one at least the bytes that the dimensions
+ *                      inside it span (no two elements share a byte: a slice of a larger array, a padded layout)
+ *   ref_stride_bytes   reference: multiples of the element size, 0 where broadcast; the innermost at most
+ *                      (2^22 - 1) elements; the reference's elements may overlap and coincide freely
+ *   dtype              any but the block-scaled element formats
+ * Neighbouring dimensions that both tensors step through in one stride are merged and extents of 1 dropped; what
+ * is left as one or two dimensions is exactly a geak_segment_mapped, three or four are cut into 2-D blocks, one per
+ * index of the outer dimensions.  GEAK_EINVAL: ndim outside 0 .. GEAK_MAX_DIMS, the candidates' innermost stride not
+ * the element size; GEAK_EALIGN: a stride or offset off the element grid; GEAK_EBOUNDS: candidates' dimensions that
+ * run into each other, more than GEAK_MAX_SEGMENT_NUMEL elements, offsets beyond the address space, a reference
+ * stride too large.  The read probe is not defined for such plans (GEAK_EINVAL), as for geak_check_plan_mapped. */
+#define GEAK_MAX_DIMS 4
+typedef struct {
+    uint64_t byte_offset;
+    uint64_t ref_byte_offset;
+    uint64_t shape[GEAK_MAX_DIMS];
+    uint64_t stride_bytes[GEAK_MAX_DIMS];
+    uint64_t ref_stride_bytes[GEAK_MAX_DIMS];
+    int32_t  ndim;
+    int32_t  dtype;
+} geak_segment_nd;
+
+/* `tols` may be null, then atol / rtol apply to all. */
+geak_status geak_check_plan_nd(geak_plan **out, const geak_segment_nd *segs, const geak_tolerance *tols,
+                               uint64_t nsegs, int32_t num_candidates, double atol, double rtol,
+                               int32_t equal_nan, int32_t device);
+
 /* One table for a batch whose unit-test outputs are of different kinds (section 3.3: a kernel is checked on all of
  * its unit tests, and those need not produce the same kind of output): every entry is a plain or padded segment, a
  * segment whose reference has a layout of its own, or a block-scaled segment, with the fields of geak_segment2d,

@@ -44,6 +44,9 @@ SEGMENT_ANY_DTYPE = np.dtype([("byte_offset", "<u8"), ("rows", "<u8"), ("row_ele
                               ("aux_byte_offset", "<u8"), ("aux_pitch_bytes", "<u8"), ("ref_elem_stride", "<i4"), ("dtype", "<i4"),
                               ("kind", "<i4"), ("reserved", "<i4")])
 GEAK_KIND_PITCHED, GEAK_KIND_MAPPED, GEAK_KIND_MX = 0, 1, 2
+GEAK_MAX_DIMS = 4
+SEGMENT_ND_DTYPE = np.dtype([("byte_offset", "<u8"), ("ref_byte_offset", "<u8"), ("shape", "<u8", (GEAK_MAX_DIMS,)),
+                             ("stride_bytes", "<u8", (GEAK_MAX_DIMS,)), ("ref_stride_bytes", "<u8", (GEAK_MAX_DIMS,)), ("ndim", "<i4"), ("dtype", "<i4")])
 RESULT_DTYPE = np.dtype([("pass", "<i4"), ("reserved", "<i4"), ("mismatch_count", "<u8"),
                          ("first_mismatch", "<i8"), ("max_abs_err", "<f8"), ("max_rel_err", "<f8")])
 MISMATCH_DTYPE = np.dtype([("index", "<i8"), ("a", "<f8"), ("b", "<f8"), ("d", "<f8"), ("tol", "<f8")])
@@ -142,6 +145,9 @@ def library() -> ctypes.CDLL:
         lib.geak_check_plan_mx.restype = ctypes.c_int
         lib.geak_check_plan_mx.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
                                            ctypes.c_int32, ctypes.c_int32]
+        lib.geak_check_plan_nd.restype = ctypes.c_int
+        lib.geak_check_plan_nd.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                                           ctypes.c_int32, ctypes.c_int32]
         lib.geak_check_plan_table.restype = ctypes.c_int
         lib.geak_check_plan_table.argtypes = [ctypes.POINTER(vp), vp, vp, u64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
                                               ctypes.c_int32, ctypes.c_int32]
@@ -200,7 +206,7 @@ def library() -> ctypes.CDLL:
     return _lib
 
 
-EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_mapped", "geak_check_plan_mx", "geak_check_plan_table", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
+EXPORTED = ["geak_check_plan", "geak_check_plan_tolerances", "geak_check_plan_pitched", "geak_check_plan_mapped", "geak_check_plan_mx", "geak_check_plan_nd", "geak_check_plan_table", "geak_check_plan_dense", "geak_check_workspace_bytes", "geak_check_result_count",
             "geak_check_run", "geak_check_run_static", "geak_check_destroy", "geak_status_string", "geak_check_build_id", "geak_check_plan_info",
             "geak_check_plan_items", "geak_check_plan_ref_offsets", "geak_check_plan_blocks", "geak_check_plan_waves", "geak_check_profile_enable", "geak_check_profile_read", "geak_check_read_probe", "geak_check_report",
             "geak_check_ulp_workspace_bytes", "geak_check_ulp_histogram", "geak_check_verdicts",
@@ -276,6 +282,24 @@ def geak_check_plan_mx(segments, tolerances, num_candidates: int, atol: float, r
     out = ctypes.c_void_p(None)
     st = library().geak_check_plan_mx(ctypes.byref(out), arr.ctypes.data if len(segs) else None,
                                       None if tol is None else tol.ctypes.data,
+                                      len(segs), num_candidates, float(atol), float(rtol), int(equal_nan), int(device))
+    return st, (out.value if st == GEAK_OK else None)
+
+
+def geak_check_plan_nd(segments, tolerances, num_candidates: int, atol: float, rtol: float, equal_nan, device: int):
+    """segments: iterable of (byte_offset, ref_byte_offset, shape, stride_bytes, ref_stride_bytes, dtype code or name), the
+    three sequences of equal length <= GEAK_MAX_DIMS; tolerances: one (atol, rtol) pair per segment or None.
+    Returns (status, plan handle or None)."""
+    segs = list(segments)
+    arr = np.zeros(len(segs), dtype=SEGMENT_ND_DTYPE)
+    for i, (off, ref_off, shape, strides, ref_strides, dt) in enumerate(segs):
+        nd = len(shape)
+        arr[i]["byte_offset"], arr[i]["ref_byte_offset"], arr[i]["ndim"], arr[i]["dtype"] = off, ref_off, nd, DTYPE_CODE.get(dt, dt)
+        if nd <= GEAK_MAX_DIMS:                                  # more dimensions than the record holds: the library refuses ndim
+            arr[i]["shape"][:nd], arr[i]["stride_bytes"][:nd], arr[i]["ref_stride_bytes"][:nd] = shape, strides, ref_strides
+    tol = None if tolerances is None else np.ascontiguousarray(np.asarray(list(tolerances), dtype=np.float64).reshape(-1, 2))
+    out = ctypes.c_void_p(None)
+    st = library().geak_check_plan_nd(ctypes.byref(out), arr.ctypes.data if len(segs) else None, None if tol is None else tol.ctypes.data,
                                       len(segs), num_candidates, float(atol), float(rtol), int(equal_nan), int(device))
     return st, (out.value if st == GEAK_OK else None)
 
@@ -479,11 +503,13 @@ def geak_check_profile_read(plan, capacity: int) -> np.ndarray:
 class Checker:
     """A plan plus its workspace and results buffers (torch tensors on the plan's device)."""
 
-    def __init__(self, segments=None, *, dense=None, pitched=None, mapped=None, mx=None, table=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
+    def __init__(self, segments=None, *, dense=None, pitched=None, mapped=None, mx=None, table=None, nd=None, num_candidates: int, atol: float = 0.0, rtol: float = 0.0,
                  equal_nan: bool, device: int = 0, tolerances=None):
         import torch
         if table is not None:
             st, plan = geak_check_plan_table(table, tolerances, num_candidates, atol, rtol, equal_nan, device)
+        elif nd is not None:
+            st, plan = geak_check_plan_nd(nd, tolerances, num_candidates, atol, rtol, equal_nan, device)
         elif mx is not None:
             st, plan = geak_check_plan_mx(mx, tolerances, num_candidates, atol, rtol, equal_nan, device)
         elif mapped is not None:

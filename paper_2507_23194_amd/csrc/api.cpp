@@ -18,6 +18,7 @@ struct geak_plan {
     SegDesc *segments_dev = nullptr;
     SegTol *seg_tol_dev = nullptr;
     uint64_t *ref_item_offset_dev = nullptr;     // only when a segment's reference has a layout of its own
+    SegNd *nd_dev = nullptr;                     // only when a segment is N-d
     // optional timing ring
     std::vector<hipEvent_t> ev_start, ev_stop;
     uint32_t ev_next = 0, ev_used = 0;
@@ -48,6 +49,7 @@ void free_device_side(geak_plan *p)
     if (p->segments_dev) (void)hipFree(p->segments_dev);
     if (p->seg_tol_dev) (void)hipFree(p->seg_tol_dev);
     if (p->ref_item_offset_dev) (void)hipFree(p->ref_item_offset_dev);
+    if (p->nd_dev) (void)hipFree(p->nd_dev);
     for (auto e : p->ev_start) (void)hipEventDestroy(e);
     for (auto e : p->ev_stop) (void)hipEventDestroy(e);
     p->items_dev = nullptr;
@@ -56,6 +58,7 @@ void free_device_side(geak_plan *p)
     p->segments_dev = nullptr;
     p->seg_tol_dev = nullptr;
     p->ref_item_offset_dev = nullptr;
+    p->nd_dev = nullptr;
     p->ev_start.clear();
     p->ev_stop.clear();
 }
@@ -78,7 +81,7 @@ geak_status geak_check_plan(geak_plan **out, const geak_segment *segs, uint64_t 
 }
 
 static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
-                                   int32_t num_candidates, int32_t equal_nan, int32_t device);
+                                   int32_t num_candidates, int32_t equal_nan, int32_t device, const SegNd *nd = nullptr);
 
 geak_status geak_check_plan_tolerances(geak_plan **out, const geak_segment *segs, const geak_tolerance *tols,
                                        uint64_t nsegs, int32_t num_candidates, int32_t equal_nan, int32_t device)
@@ -222,8 +225,92 @@ geak_status geak_check_plan_mapped(geak_plan **out, const geak_segment_mapped *s
     return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device);
 }
 
+geak_status geak_check_plan_nd(geak_plan **out, const geak_segment_nd *segs, const geak_tolerance *tols, uint64_t nsegs,
+                               int32_t num_candidates, double atol, double rtol, int32_t equal_nan, int32_t device)
+{
+    if (!segs || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
+    std::vector<SegDesc> descs;
+    std::vector<SegNd> nds;
+    std::vector<geak_tolerance> same;
+    try {
+        descs.resize(nsegs);
+        nds.assign(nsegs, SegNd{1, {1, 1}, {0, 0}, {0, 0}});
+        if (!tols) same.assign(nsegs, geak_tolerance{atol, rtol});
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    bool any_nd = false;
+    for (uint64_t s = 0; s < nsegs; ++s) {
+        const geak_segment_nd &g = segs[s];
+        if (g.ndim < 0 || g.ndim > GEAK_MAX_DIMS) return GEAK_EINVAL;
+        if (g.dtype < GEAK_F32 || g.dtype > GEAK_F8E5M2) return GEAK_EDTYPE;
+        const uint64_t w = (uint64_t)elem_size(g.dtype);
+        // the dimensions that matter, outermost first: extents of 1 dropped, neighbours that both tensors step through
+        // in one stride merged (an empty tensor has no dimensions to look at)
+        uint64_t shape[GEAK_MAX_DIMS], stride[GEAK_MAX_DIMS], ref_stride[GEAK_MAX_DIMS], numel = 1;
+        int n = 0;
+        bool empty = false;
+        for (int d = 0; d < g.ndim; ++d) empty |= g.shape[d] == 0;
+        for (int d = 0; d < g.ndim && !empty; ++d) {
+            if (g.shape[d] > GEAK_MAX_SEGMENT_NUMEL || numel > GEAK_MAX_SEGMENT_NUMEL / g.shape[d]) return GEAK_EBOUNDS;
+            numel *= g.shape[d];
+            if (g.shape[d] == 1) continue;                      // its strides are never stepped
+            if (g.stride_bytes[d] % w || g.ref_stride_bytes[d] % w) return GEAK_EALIGN;
+            // dimension n - 1 steps over all of dimension d in both tensors: one dimension (products below 2^40 * 2^64 are
+            // compared by division)
+            if (n && g.stride_bytes[d] && stride[n - 1] / g.shape[d] == g.stride_bytes[d] && stride[n - 1] % g.shape[d] == 0 &&
+                ((ref_stride[n - 1] == 0 && g.ref_stride_bytes[d] == 0) ||
+                 (g.ref_stride_bytes[d] && ref_stride[n - 1] / g.shape[d] == g.ref_stride_bytes[d] && ref_stride[n - 1] % g.shape[d] == 0))) {
+                shape[n - 1] *= g.shape[d];
+                stride[n - 1] = g.stride_bytes[d];
+                ref_stride[n - 1] = g.ref_stride_bytes[d];
+            } else {
+                shape[n] = g.shape[d];
+                stride[n] = g.stride_bytes[d];
+                ref_stride[n] = g.ref_stride_bytes[d];
+                ++n;
+            }
+        }
+        if (empty) numel = 0;
+        if (numel == 0) {
+            descs[s] = SegDesc{g.byte_offset, 0, 1, 0, g.dtype, kRefMapped | (1 << kRefStrideShift), g.ref_byte_offset, 0};
+            continue;
+        }
+        if (n == 0) { shape[0] = 1; stride[0] = w; ref_stride[0] = w; n = 1; }          // one element
+        if (stride[n - 1] != w) {
+            // the candidates' innermost dimension must be contiguous -- unless its extent is 1 (a column of a wider array:
+            // dropped above), then the rows are one element long
+            if (g.shape[g.ndim - 1] != 1) return GEAK_EINVAL;
+            shape[n] = 1; stride[n] = w; ref_stride[n] = w;    // n <= GEAK_MAX_DIMS - 1: the innermost dimension was dropped
+            ++n;
+        }
+        if (ref_stride[n - 1] / w > kMaxRefStride) return GEAK_EBOUNDS;
+        const uint64_t row_elems = shape[n - 1];
+        const uint64_t rows = n >= 2 ? shape[n - 2] : 1;
+        int32_t layout = kRefMapped | (int32_t)((uint32_t)(ref_stride[n - 1] / w) << kRefStrideShift);
+        if (n > 2) {
+            layout |= kSegNd;
+            any_nd = true;
+            SegNd &o = nds[s];
+            o.inner_rows = rows;
+            // dimensions n - 3 and, if there is one, n - 4: the inner of the two in slot 1
+            o.outer_shape[1] = shape[n - 3];
+            o.outer_stride[1] = stride[n - 3];
+            o.outer_ref_stride[1] = ref_stride[n - 3];
+            if (n == 4) {
+                o.outer_shape[0] = shape[0];
+                o.outer_stride[0] = stride[0];
+                o.outer_ref_stride[0] = ref_stride[0];
+            }
+        }
+        descs[s] = SegDesc{g.byte_offset, numel, row_elems, n >= 2 ? stride[n - 2] : row_elems * w, g.dtype, layout, g.ref_byte_offset,
+                           n >= 2 ? ref_stride[n - 2] : 0};
+    }
+    return plan_from_descs(out, descs.data(), tols ? tols : same.data(), nsegs, num_candidates, equal_nan, device, any_nd ? nds.data() : nullptr);
+}
+
 static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
-                                   int32_t num_candidates, int32_t equal_nan, int32_t device)
+                                   int32_t num_candidates, int32_t equal_nan, int32_t device, const SegNd *nd)
 {
     if (!out) return GEAK_EINVAL;
     if (device < -1) return GEAK_EINVAL;
@@ -248,7 +335,7 @@ static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const g
         compute_units = (uint32_t)prop.multiProcessorCount;
     }
 
-    geak_status st = build_host_plan(p->host, segs, tols, nsegs, num_candidates, equal_nan, max_blocks, compute_units);
+    geak_status st = build_host_plan(p->host, segs, tols, nsegs, num_candidates, equal_nan, max_blocks, compute_units, nd);
     if (st != GEAK_OK) { delete p; return st; }
 
     if (device >= 0) {
@@ -266,6 +353,8 @@ static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const g
         if (ok) ok = hipMalloc((void **)&p->seg_tol_dev, tol_bytes) == hipSuccess;
         const size_t ref_off_bytes = p->host.ref_item_offset.size() * sizeof(uint64_t);
         if (ok && ref_off_bytes) ok = hipMalloc((void **)&p->ref_item_offset_dev, ref_off_bytes) == hipSuccess;
+        const size_t nd_bytes = p->host.nd.size() * sizeof(SegNd);
+        if (ok && nd_bytes) ok = hipMalloc((void **)&p->nd_dev, nd_bytes) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_ENOMEM; }
         if (item_bytes) ok = hipMemcpy(p->items_dev, p->host.items.data(), item_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok) ok = hipMemcpy(p->slot_begin_dev, p->host.slot_begin.data(), slot_bytes, hipMemcpyHostToDevice) == hipSuccess;
@@ -274,6 +363,7 @@ static geak_status plan_from_descs(geak_plan **out, const SegDesc *segs, const g
         if (ok) ok = hipMemcpy(p->seg_tol_dev, p->host.seg_tol.data(), tol_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (ok && ref_off_bytes)
             ok = hipMemcpy(p->ref_item_offset_dev, p->host.ref_item_offset.data(), ref_off_bytes, hipMemcpyHostToDevice) == hipSuccess;
+        if (ok && nd_bytes) ok = hipMemcpy(p->nd_dev, p->host.nd.data(), nd_bytes, hipMemcpyHostToDevice) == hipSuccess;
         if (!ok) { free_device_side(p); delete p; return GEAK_EHIP; }
         // set-up is the place to look up the device's copy of the static scratch array: geak_check_run_static
         // then finds the address there (a failure here only surfaces if that entry point is used)
@@ -555,6 +645,8 @@ geak_status geak_check_report(const geak_plan *plan, const void *ref_dev, const 
     ra.max_records = max_records;
     ra.seg_tol = plan->seg_tol_dev;
     ra.equal_nan = hp.equal_nan;
+    ra.reserved = 0;
+    ra.nd = plan->nd_dev;
     if (launch_report(ra, hip_stream) != (int)hipSuccess) return GEAK_EHIP;
     return GEAK_OK;
 }

@@ -76,8 +76,10 @@ static_assert(sizeof(SegTol) == 24, "SegTol is read as three 64-bit words");
 // (stride 0: one element per row; stride 1: the row is contiguous; more: its elements are gathered one by one).
 // kMxScaled: a block-scaled segment (dtype one of the GEAK_MX* codes, contiguous, whole blocks of kMxBlock
 // elements); ref_byte_offset then holds the offset of its scale bytes, one per block, in every packed buffer.
+// kSegNd (bit 1, with kRefMapped): the rows x row_elems of the record are one 2-D block of an N-d segment; the
+// segment's SegNd entry says how many rows a block has and where the blocks lie.
 // Seven 64-bit words: device code reads the record word by word.
-constexpr int32_t kRefMapped = 1, kMxScaled = 4;
+constexpr int32_t kRefMapped = 1, kSegNd = 2, kMxScaled = 4;
 constexpr int kRefStrideShift = 8;
 constexpr uint64_t kMaxRefStride = (1ull << 22) - 1;
 constexpr uint64_t kMxBlock = 32;
@@ -93,6 +95,18 @@ struct SegDesc {
     uint64_t ref_pitch_bytes;
 };
 static_assert(sizeof(SegDesc) == 56, "SegDesc is read as seven 64-bit words");
+// The dimensions of an N-d segment above its 2-D blocks (up to two; extent 1 and stride 0 where unused): block
+// (o0, o1) starts outer_stride[0] * o0 + outer_stride[1] * o1 bytes behind the segment's byte_offset in the
+// candidates, and outer_ref_stride likewise behind ref_byte_offset in the reference (0: broadcast); element
+// indices are row-major over (outer_shape[0], outer_shape[1], inner_rows, row_elems).  Seven 64-bit words.
+struct SegNd {
+    uint64_t inner_rows;
+    uint64_t outer_shape[2];
+    uint64_t outer_stride[2];
+    uint64_t outer_ref_stride[2];
+};
+static_assert(sizeof(SegNd) == 56, "SegNd is seven 64-bit words");
+constexpr bool seg_is_nd(const SegDesc &g) { return g.layout != kMxScaled && (g.layout & kSegNd) != 0; }
 inline uint64_t seg_rows(const SegDesc &g) { return g.numel / g.row_elems; }
 constexpr bool seg_ref_mapped(const SegDesc &g) { return g.layout != kMxScaled && (g.layout & kRefMapped) != 0; }
 constexpr uint64_t seg_ref_stride(const SegDesc &g) { return (uint32_t)g.layout >> kRefStrideShift; }       // of a mapped segment
@@ -115,6 +129,7 @@ inline uint64_t seg_ref_span(const SegDesc &g)
 // Host side of a plan: everything that can be decided without a device.
 struct HostPlan {
     std::vector<SegDesc> segments;
+    std::vector<SegNd> nd;                 // per segment, only when a segment is N-d (else empty)
     std::vector<geak_item> items;
     std::vector<uint64_t> ref_item_offset; // per item, only when a segment is mapped: byte offset of the reference element
                                            // that the item's first element is compared with
@@ -133,8 +148,10 @@ struct HostPlan {
 };
 
 // Validates and builds the work table for a persistent grid of at most `max_blocks` blocks.
+// `nd`: one entry per segment when any segment carries kSegNd (entries of the other segments are ignored), else null.
 geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
-                            int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks, uint32_t compute_units);
+                            int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks, uint32_t compute_units,
+                            const SegNd *nd = nullptr);
 
 // Running maxima of one (segment, candidate, replica): non-negative doubles, raised by atomic max on
 // their bit patterns.
@@ -219,6 +236,8 @@ struct ReportArgs {
     uint32_t max_records;
     const SegTol *seg_tol;               // device table, one entry per segment
     int equal_nan;
+    int reserved;
+    const SegNd *nd;                     // device table, per segment; null when no segment is N-d
 };
 
 // ---- ulp-distance histogram ------------------------------------------------------------------------

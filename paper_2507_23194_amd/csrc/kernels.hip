@@ -1865,6 +1865,13 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
     const u64 ref_pitch_elems = sg.ref_pitch_bytes / (u64)Traits<DT>::W;
     // a block-scaled segment: its scale bytes, one per 32 elements, in the same buffers
     [[maybe_unused]] const unsigned char *rscales = p.ref + sg.ref_byte_offset, *cscales = p.cand_table[blockIdx.x % p.num_candidates] + sg.ref_byte_offset;
+    // an N-d segment: the rows above are those of one 2-D block; block (o0, o1) lies at its own offsets in both tensors
+    const bool is_nd = seg_is_nd(sg) && p.nd != nullptr;
+    SegNd outer{1, {1, 1}, {0, 0}, {0, 0}};
+    if (is_nd) outer = p.nd[blockIdx.x / p.num_candidates];
+    const u64 block_elems = outer.inner_rows * sg.row_elems;
+    const u64 outer_elems[2] = {outer.outer_stride[0] / (u64)Traits<DT>::W, outer.outer_stride[1] / (u64)Traits<DT>::W};
+    const u64 outer_ref_elems[2] = {outer.outer_ref_stride[0] / (u64)Traits<DT>::W, outer.outer_ref_stride[1] / (u64)Traits<DT>::W};
     u64 found = 0;
     for (u64 base = (u64)rec.first_mismatch; base < sg.numel && found < want; base += kReportThreads * kReportPerThread) {
         // all loads of the tile first, then the rule
@@ -1874,8 +1881,15 @@ __device__ __forceinline__ void report_pair(const ReportArgs &p, const SegTol to
         for (int u = 0; u < kReportPerThread; ++u) {
             const u64 i = base + (u64)u * kReportThreads + tid;
             const bool in = i < sg.numel;
-            const u64 j = (pitched && in) ? (i / sg.row_elems) * pitch_elems + i % sg.row_elems : i;     // where element i is stored
-            const u64 jr = (mapped && in) ? (i / sg.row_elems) * ref_pitch_elems + (i % sg.row_elems) * ref_stride : j;   // and what it is compared with
+            u64 j = (pitched && in) ? (i / sg.row_elems) * pitch_elems + i % sg.row_elems : i;     // where element i is stored
+            u64 jr = (mapped && in) ? (i / sg.row_elems) * ref_pitch_elems + (i % sg.row_elems) * ref_stride : j;   // and what it is compared with
+            if (is_nd && in) {
+                const u64 block = i / block_elems, within = i % block_elems;             // row-major over (o0, o1, row, column)
+                const u64 o0 = block / outer.outer_shape[1], o1 = block % outer.outer_shape[1];
+                const u64 row = within / sg.row_elems, col = within % sg.row_elems;
+                j = o0 * outer_elems[0] + o1 * outer_elems[1] + row * pitch_elems + col;
+                jr = o0 * outer_ref_elems[0] + o1 * outer_ref_elems[1] + row * ref_pitch_elems + col * ref_stride;
+            }
             if constexpr (DT == GEAK_I32) {
                 ai[u] = in ? reinterpret_cast<const int *>(cb)[j] : 0;
                 bi[u] = in ? reinterpret_cast<const int *>(rb)[jr] : 0;

@@ -20,7 +20,7 @@ constexpr uint64_t kUnitStart = 110, kUnitTailMul16 = 10, kUnitTailFix = 8;
 constexpr uint64_t kUnitSpreadNum = 8, kUnitSpreadDen = 100;
 
 geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolerance *tols, uint64_t nsegs,
-                            int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks, uint32_t compute_units)
+                            int32_t num_candidates, int32_t equal_nan, uint32_t max_blocks, uint32_t compute_units, const SegNd *nd)
 {
     if (!segs || !tols || nsegs == 0 || nsegs > 0x7FFFFFFFull) return GEAK_EINVAL;
     if (num_candidates < 1 || num_candidates > GEAK_MAX_CANDIDATES) return GEAK_EINVAL;
@@ -33,14 +33,26 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
 
     // per-segment checks
     uint64_t total_bytes = 0, total_ref_bytes = 0;       // the candidates' elements; the reference's distinct elements
-    bool any_mapped = false;
+    bool any_mapped = false, any_nd = false;
+    std::vector<uint64_t> span_of;                        // bytes from a segment's first to behind its last element, candidates' side
+    try {
+        span_of.assign(nsegs, 0);
+    } catch (const std::bad_alloc &) {
+        return GEAK_ENOMEM;
+    }
+    // rows of one 2-D block of a segment: all its rows, unless it is N-d
+    const auto block_rows = [&](uint64_t s) { return seg_is_nd(segs[s]) ? nd[s].inner_rows : seg_rows(segs[s]); };
     for (uint64_t s = 0; s < nsegs; ++s) {
         const SegDesc &g = segs[s];
         if (g.dtype < GEAK_F32 || g.dtype > GEAK_MXFP6_E3M2) return GEAK_EDTYPE;
         if (is_mx_dtype(g.dtype) != (g.layout == kMxScaled)) return GEAK_EDTYPE;     // block-scaled element formats belong to block-scaled segments only
-        if (g.layout != kMxScaled && g.layout != 0 && (!(g.layout & kRefMapped) || (g.layout & 0xFE) != 0 || g.layout < 0 ||
+        if (g.layout != kMxScaled && g.layout != 0 && (!(g.layout & kRefMapped) || (g.layout & 0xFC) != 0 || g.layout < 0 ||
                                                        seg_ref_stride(g) > kMaxRefStride)) return GEAK_EINVAL;
         any_mapped |= seg_ref_mapped(g);
+        if (seg_is_nd(g)) {
+            if (!nd) return GEAK_EINVAL;
+            any_nd = true;
+        }
         if (g.layout == kMxScaled) {
             // payload on the 16-byte grid (a vector then lies inside one block), whole blocks, one contiguous row
             if (g.byte_offset % 16 != 0) return GEAK_EALIGN;
@@ -48,6 +60,16 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
             if (g.ref_byte_offset > UINT64_MAX - g.numel / kMxBlock) return GEAK_EBOUNDS;
         }
         if (g.row_elems == 0 || g.numel % g.row_elems != 0) return GEAK_EINVAL;
+        if (seg_is_nd(g)) {                                  // numel = outer extents x rows of a block x row_elems (all <= 2^40: no overflow)
+            const SegNd &o = nd[s];
+            if (!o.inner_rows || !o.outer_shape[0] || !o.outer_shape[1]) return GEAK_EINVAL;
+            if (o.inner_rows > GEAK_MAX_SEGMENT_NUMEL || o.outer_shape[0] > GEAK_MAX_SEGMENT_NUMEL || o.outer_shape[1] > GEAK_MAX_SEGMENT_NUMEL) return GEAK_EBOUNDS;
+            if (g.numel) {
+                const uint64_t rows = seg_rows(g);
+                if (rows % o.inner_rows || (rows / o.inner_rows) % o.outer_shape[1] || rows / o.inner_rows / o.outer_shape[1] != o.outer_shape[0])
+                    return GEAK_EINVAL;
+            }
+        }
         // the rule of every dtype but binary64 runs in binary32: its tolerances must be finite there too
         if (g.dtype != GEAK_F64 && (std::isinf((float)tols[s].atol) || std::isinf((float)tols[s].rtol))) return GEAK_EINVAL;
         const uint64_t w = (uint64_t)elem_size(g.dtype);
@@ -58,10 +80,24 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         // rows must not run into each other, and the last one must end inside the address space
         if (g.numel) {
             const uint64_t row_bytes = payload_bytes(g.dtype, g.row_elems);     // <= bytes: no overflow
+            const uint64_t rows = block_rows(s);
             if (g.pitch_bytes < row_bytes) return GEAK_EBOUNDS;
-            if (mul_overflows(seg_rows(g) - 1, g.pitch_bytes)) return GEAK_EBOUNDS;
-            if ((seg_rows(g) - 1) * g.pitch_bytes > UINT64_MAX - row_bytes) return GEAK_EBOUNDS;
-            if (g.byte_offset > UINT64_MAX - seg_span(g)) return GEAK_EBOUNDS;
+            if (mul_overflows(rows - 1, g.pitch_bytes)) return GEAK_EBOUNDS;
+            if ((rows - 1) * g.pitch_bytes > UINT64_MAX - row_bytes) return GEAK_EBOUNDS;
+            uint64_t span = (rows - 1) * g.pitch_bytes + row_bytes;
+            if (seg_is_nd(g)) {
+                // the blocks: element-aligned, nested from the inside out (a block ends before the next one begins)
+                for (int d = 1; d >= 0; --d) {
+                    const uint64_t extent = nd[s].outer_shape[d], stride = nd[s].outer_stride[d];
+                    if (extent == 1) continue;
+                    if (stride % w != 0) return GEAK_EALIGN;
+                    if (stride < span) return GEAK_EBOUNDS;
+                    if (mul_overflows(extent - 1, stride) || (extent - 1) * stride > UINT64_MAX - span) return GEAK_EBOUNDS;
+                    span += (extent - 1) * stride;
+                }
+            }
+            if (g.byte_offset > UINT64_MAX - span) return GEAK_EBOUNDS;
+            span_of[s] = span;
         }
         // what one tensor holds of the segment: its elements, and for a block-scaled one its scale bytes (numel <= 2^40)
         const uint64_t tensor_bytes = bytes + (g.layout == kMxScaled ? g.numel / kMxBlock : 0);
@@ -73,14 +109,27 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         if (seg_ref_mapped(g)) {
             if (g.ref_byte_offset % w != 0 || g.ref_pitch_bytes % w != 0) return GEAK_EALIGN;
             if (g.numel) {
-                if (mul_overflows(seg_rows(g) - 1, g.ref_pitch_bytes)) return GEAK_EBOUNDS;
+                const uint64_t rows = block_rows(s);
+                if (mul_overflows(rows - 1, g.ref_pitch_bytes)) return GEAK_EBOUNDS;
                 if (seg_ref_stride(g) && g.row_elems - 1 > (UINT64_MAX / 16) / seg_ref_stride(g)) return GEAK_EBOUNDS;
                 const uint64_t ref_row_span = seg_ref_row_span(g);                       // fits: checked in the line above
-                if ((seg_rows(g) - 1) * g.ref_pitch_bytes > UINT64_MAX - ref_row_span) return GEAK_EBOUNDS;
-                if (g.ref_byte_offset > UINT64_MAX - seg_ref_span(g)) return GEAK_EBOUNDS;
-                const uint64_t ref_rows = g.ref_pitch_bytes ? seg_rows(g) : 1;
+                if ((rows - 1) * g.ref_pitch_bytes > UINT64_MAX - ref_row_span) return GEAK_EBOUNDS;
+                uint64_t ref_span = (rows - 1) * g.ref_pitch_bytes + ref_row_span;
+                const uint64_t ref_rows = g.ref_pitch_bytes ? rows : 1;
                 const uint64_t ref_row_bytes = (seg_ref_stride(g) ? g.row_elems : 1) * w;    // distinct elements of a row
-                ref_bytes = std::min(seg_ref_span(g), mul_overflows(ref_rows, ref_row_bytes) ? UINT64_MAX : ref_rows * ref_row_bytes);
+                uint64_t distinct = mul_overflows(ref_rows, ref_row_bytes) ? UINT64_MAX : ref_rows * ref_row_bytes;
+                if (seg_is_nd(g)) {
+                    for (int d = 1; d >= 0; --d) {
+                        const uint64_t extent = nd[s].outer_shape[d], stride = nd[s].outer_ref_stride[d];
+                        if (extent == 1) continue;
+                        if (stride % w != 0) return GEAK_EALIGN;
+                        if (mul_overflows(extent - 1, stride) || (extent - 1) * stride > UINT64_MAX - ref_span) return GEAK_EBOUNDS;
+                        ref_span += (extent - 1) * stride;
+                        if (stride) distinct = mul_overflows(distinct, extent) ? UINT64_MAX : distinct * extent;
+                    }
+                }
+                if (g.ref_byte_offset > UINT64_MAX - ref_span) return GEAK_EBOUNDS;
+                ref_bytes = std::min(std::min(ref_span, distinct), tensor_bytes);           // overlapping reference blocks: never more than the candidates' bytes
             }
         }
         total_ref_bytes += ref_bytes;                        // <= total_bytes: no overflow
@@ -93,7 +142,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         spans.reserve(nsegs);
         for (uint64_t s = 0; s < nsegs; ++s)
             if (segs[s].numel) {
-                spans.emplace_back(segs[s].byte_offset, segs[s].byte_offset + seg_span(segs[s]));   // pitched segments: first to last byte
+                spans.emplace_back(segs[s].byte_offset, segs[s].byte_offset + span_of[s]);   // pitched and N-d segments: first to last byte
                 if (segs[s].layout == kMxScaled)                                                     // and a block-scaled segment's scales
                     spans.emplace_back(segs[s].ref_byte_offset, segs[s].ref_byte_offset + segs[s].numel / kMxBlock);
             }
@@ -104,32 +153,46 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         // Count items first, in closed form (a segment may have 2^40 one-element rows): a group of short rows
         // is one item; otherwise a row gives a shorter first item where it starts off the 16-byte grid, full
         // items and a tail, and the rows' starts repeat modulo 16 with a period of at most 16 rows.
+        // items of one 2-D block of segment s whose first row starts at byte `base`
+        const auto count_block = [&](uint64_t s, uint64_t base) -> uint64_t {
+            const SegDesc &g = segs[s];
+            const uint64_t w = elem_size(g.dtype), per = elems_per_item(g.dtype);
+            const uint64_t rows = block_rows(s);
+            const uint64_t row_vectors = (g.row_elems * w + 15) / 16;
+            if (rows > 1 && base % 16 == 0 && g.pitch_bytes % 16 == 0 && row_vectors <= kItemBytes / 32) {
+                const uint64_t group = (kItemBytes / 16) / row_vectors;
+                return (rows + group - 1) / group;
+            }
+            uint64_t period = 1, total = 0;
+            while ((g.pitch_bytes * period) % 16 != 0) period *= 2;        // 1, 2, 4, 8 or 16
+            for (uint64_t r = 0; r < period && r < rows; ++r) {
+                uint64_t n = g.row_elems, count = 0;
+                const uint64_t skip = ((base + r * g.pitch_bytes) % 16) / w;
+                if (skip) { ++count; n -= std::min<uint64_t>(n, per - skip); }
+                count += n / per + (n % per ? 1 : 0);
+                total += count * ((rows - r + period - 1) / period);     // rows r, r + period, r + 2 period, ...
+            }
+            return total;
+        };
         uint64_t n_items = 0;
         for (uint64_t s = 0; s < nsegs; ++s) {
             const SegDesc &g = segs[s];
-            const uint64_t w = elem_size(g.dtype), per = elems_per_item(g.dtype);
             if (!g.numel) continue;
-            const uint64_t rows = seg_rows(g);
-            const uint64_t row_vectors = (g.row_elems * w + 15) / 16;
-            if (rows > 1 && g.byte_offset % 16 == 0 && g.pitch_bytes % 16 == 0 && row_vectors <= kItemBytes / 32) {
-                const uint64_t group = (kItemBytes / 16) / row_vectors;
-                n_items += (rows + group - 1) / group;
+            if (!seg_is_nd(g)) {
+                n_items += count_block(s, g.byte_offset);
             } else {
-                uint64_t period = 1;
-                while ((g.pitch_bytes * period) % 16 != 0) period *= 2;        // 1, 2, 4, 8 or 16
-                for (uint64_t r = 0; r < period && r < rows; ++r) {
-                    uint64_t n = g.row_elems, count = 0;
-                    const uint64_t skip = ((g.byte_offset + r * g.pitch_bytes) % 16) / w;
-                    if (skip) { ++count; n -= std::min<uint64_t>(n, per - skip); }
-                    count += n / per + (n % per ? 1 : 0);
-                    n_items += count * ((rows - r + period - 1) / period);     // rows r, r + period, r + 2 period, ...
-                }
+                // block by block: every block holds at least one item, so the loop ends with the item limit
+                for (uint64_t o0 = 0; o0 < nd[s].outer_shape[0] && n_items < 0x7FFFFFFFull; ++o0)
+                    for (uint64_t o1 = 0; o1 < nd[s].outer_shape[1] && n_items < 0x7FFFFFFFull; ++o1)
+                        n_items += count_block(s, g.byte_offset + o0 * nd[s].outer_stride[0] + o1 * nd[s].outer_stride[1]);
             }
             if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
         }
         if (n_items >= 0x7FFFFFFFull) return GEAK_EBOUNDS;
 
         hp.segments.assign(segs, segs + nsegs);
+        hp.nd.clear();
+        if (any_nd) hp.nd.assign(nd, nd + nsegs);
         hp.items.clear();
         hp.items.reserve(n_items);
         hp.ref_item_offset.clear();
@@ -151,44 +214,45 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         while (hp.replicas > 1 && (uint64_t)nsegs * (uint64_t)num_candidates * hp.replicas * sizeof(MaxPair) > kBoardBudgetBytes)
             hp.replicas /= 2;
 
-        for (uint64_t s = 0; s < nsegs; ++s) {
+        // The items of one 2-D block of segment s: `rows` rows whose first starts at byte cand_base in the candidates and
+        // is compared with what lies at ref_base in the reference; the block's first element has flat index elem_base.
+        const auto emit_block = [&](uint64_t s, uint64_t cand_base, uint64_t ref_base, uint64_t elem_base, uint64_t rows) {
             const SegDesc &g = segs[s];
             const uint64_t w = elem_size(g.dtype), per = elems_per_item(g.dtype);
             const bool mapped = seg_ref_mapped(g);
             const uint64_t ref_stride = mapped ? seg_ref_stride(g) : 1;
-            if (!g.numel) continue;
             // Short rows of a pitched segment that all start on 16-byte boundaries: whole rows are
             // grouped into one item, as many as its 256 vector slots hold (a row takes
             // ceil(row bytes / 16) of them), instead of one mostly idle item per row.
             const uint64_t row_vectors = (g.row_elems * w + 15) / 16;
-            if (seg_rows(g) > 1 && g.byte_offset % 16 == 0 && g.pitch_bytes % 16 == 0 && row_vectors <= kItemBytes / 32) {
+            if (rows > 1 && cand_base % 16 == 0 && g.pitch_bytes % 16 == 0 && row_vectors <= kItemBytes / 32) {
                 const uint64_t group = (kItemBytes / 16) / row_vectors;             // >= 2 rows per item
-                for (uint64_t r = 0; r < seg_rows(g); r += group) {
-                    const uint64_t rows_here = std::min<uint64_t>(group, seg_rows(g) - r);
+                for (uint64_t r = 0; r < rows; r += group) {
+                    const uint64_t rows_here = std::min<uint64_t>(group, rows - r);
                     geak_item it{};
-                    it.byte_offset = g.byte_offset + r * g.pitch_bytes;
-                    it.elem_start = r * g.row_elems;
+                    it.byte_offset = cand_base + r * g.pitch_bytes;
+                    it.elem_start = elem_base + r * g.row_elems;
                     it.segment = (uint32_t)s;
                     it.numel = (uint16_t)(rows_here * g.row_elems);                 // at most 4096 / w elements
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
                     it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS | (mapped ? GEAK_ITEM_REFMAP : 0));
                     hp.items.push_back(it);
-                    if (any_mapped) hp.ref_item_offset.push_back(mapped ? g.ref_byte_offset + r * g.ref_pitch_bytes : it.byte_offset);
+                    if (any_mapped) hp.ref_item_offset.push_back(mapped ? ref_base + r * g.ref_pitch_bytes : it.byte_offset);
                 }
-                continue;
+                return;
             }
             // Row by row (a contiguous segment is one row): full items and a tail.  A row that starts off the
             // 16-byte grid begins with one item that ends where a full item read from the boundary before
             // it would end (the kernels read it from that boundary and ignore the foreign elements in
             // front), so that everything behind it is aligned again.
-            for (uint64_t r = 0; r < seg_rows(g); ++r) {
-                const uint64_t row_start = g.byte_offset + r * g.pitch_bytes;
+            for (uint64_t r = 0; r < rows; ++r) {
+                const uint64_t row_start = cand_base + r * g.pitch_bytes;
                 uint64_t done = 0;
                 auto push = [&](uint64_t n, bool full) {
                     geak_item it{};
                     it.byte_offset = row_start + payload_bytes(g.dtype, done);     // done is a multiple of 4096 for the sub-byte formats
-                    it.elem_start = r * g.row_elems + done;
+                    it.elem_start = elem_base + r * g.row_elems + done;
                     it.segment = (uint32_t)s;
                     it.numel = (uint16_t)n;
                     it.next = kNoItem;
@@ -200,7 +264,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     hp.items.push_back(it);
                     if (any_mapped)
                         hp.ref_item_offset.push_back(!mapped ? it.byte_offset
-                                                     : g.ref_byte_offset + r * g.ref_pitch_bytes + done * ref_stride * w);
+                                                     : ref_base + r * g.ref_pitch_bytes + done * ref_stride * w);
                     done += n;
                 };
                 const uint64_t skip = (row_start % 16) / w;
@@ -208,6 +272,21 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                 while (g.row_elems - done >= per) push(per, true);
                 if (g.row_elems - done) push(g.row_elems - done, false);
             }
+        };
+        for (uint64_t s = 0; s < nsegs; ++s) {
+            const SegDesc &g = segs[s];
+            if (!g.numel) continue;
+            if (!seg_is_nd(g)) {
+                emit_block(s, g.byte_offset, g.ref_byte_offset, 0, seg_rows(g));
+                continue;
+            }
+            const SegNd &o = nd[s];                           // blocks in row-major order of the outer dimensions
+            const uint64_t block_elems = o.inner_rows * g.row_elems;
+            for (uint64_t o0 = 0; o0 < o.outer_shape[0]; ++o0)
+                for (uint64_t o1 = 0; o1 < o.outer_shape[1]; ++o1)
+                    emit_block(s, g.byte_offset + o0 * o.outer_stride[0] + o1 * o.outer_stride[1],
+                               g.ref_byte_offset + o0 * o.outer_ref_stride[0] + o1 * o.outer_ref_stride[1],
+                               (o0 * o.outer_shape[1] + o1) * block_elems, o.inner_rows);
         }
 
         if (hp.items.size() != n_items) return GEAK_EINVAL;     // the closed-form count and the table must agree

@@ -761,3 +761,122 @@ def test_table_of_mixed_kinds_builds_what_each_entry_point_builds(lib):
     arr_bad = [("mx", 0, 64, 100, "f32")]
     assert B.geak_check_plan_table(arr_bad, None, 1, 0, 0, 0, -1)[0] == B.GEAK_EDTYPE
     assert B.geak_check_plan_table([("pitched", 0, 1, 64, 64, B.GEAK_MXINT8)], None, 1, 0, 0, 0, -1)[0] == B.GEAK_EDTYPE
+
+
+def _nd_offsets(off, shape, strides):
+    """Byte offset of every element of an N-d layout, row-major over shape (numpy's own index arithmetic)."""
+    out = np.full(tuple(shape), off, dtype=np.int64)
+    for d, (n, t) in enumerate(zip(shape, strides)):
+        idx = np.arange(n, dtype=np.int64) * int(t)
+        out = out + idx.reshape([-1 if e == d else 1 for e in range(len(shape))])
+    return out.reshape(-1)
+
+
+def _check_nd_plan(segs, K=2):
+    """Every element of every N-d segment is covered exactly once, at the candidates' and the reference's right bytes."""
+    st, plan = B.geak_check_plan_nd(segs, None, K, 1e-3, 1e-3, False, -1)
+    assert st == B.GEAK_OK, st
+    try:
+        _check_lists_and_runs(plan)
+        items = B.geak_check_plan_items(plan)
+        ref_off = B.geak_check_plan_ref_offsets(plan).astype(np.int64)
+        assert len(ref_off) == len(items)
+        for sg, (off, roff, shape, strides, rstrides, dt) in enumerate(segs):
+            w = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4, "i64": 8, "u8": 1, "f64": 8, "i8": 1}[dt]
+            want_c, want_r = _nd_offsets(off, shape, strides), _nd_offsets(roff, shape, rstrides)
+            got_c, got_r = np.full(want_c.size, -1, np.int64), np.full(want_c.size, -1, np.int64)
+            mine = [j for j in range(len(items)) if int(items[j]["segment"]) == sg]
+            # the 2-D geometry of the segment as the plan holds it: from two neighbouring elements / rows of the items
+            for j in mine:
+                it = items[j]
+                e0, n, base = int(it["elem_start"]), int(it["numel"]), int(it["byte_offset"])
+                assert (got_c[e0:e0 + n] == -1).all()
+                if it["flags"] & B.GEAK_ITEM_ROWS:
+                    cols = shape[-1]
+                    rows_here = n // cols
+                    # rows of one 2-D block: pitch = the second-to-last stride on both sides
+                    for r in range(rows_here):
+                        got_c[e0 + r * cols: e0 + (r + 1) * cols] = base + r * strides[-2] + np.arange(cols) * w
+                        got_r[e0 + r * cols: e0 + (r + 1) * cols] = ref_off[j] + r * rstrides[-2] + np.arange(cols) * rstrides[-1]
+                else:
+                    got_c[e0:e0 + n] = base + np.arange(n) * w
+                    got_r[e0:e0 + n] = ref_off[j] + np.arange(n) * rstrides_inner(shape, strides, rstrides)
+                    assert bool(it["flags"] & B.GEAK_ITEM_FULL) <= (rstrides_inner(shape, strides, rstrides) == w)
+            assert np.array_equal(got_c, want_c), sg
+            assert np.array_equal(got_r, want_r), sg
+    finally:
+        B.geak_check_destroy(plan)
+
+
+def rstrides_inner(shape, strides, rstrides):
+    """The reference's byte stride along what the planner treats as a row: the innermost dimension with extent > 1 (the
+    dimensions merged into it share that stride by construction); the element size's worth for a single element."""
+    for d in range(len(shape) - 1, -1, -1):
+        if shape[d] > 1:
+            return int(rstrides[d])
+    return 0
+
+
+def test_nd_segments_cover_every_element_at_the_right_bytes(lib):
+    segs = [
+        # [B, H, S, D] contiguous against a reference [1, H, 1, D] (broadcast over batch and sequence)
+        (0, 0, (2, 3, 5, 8), (480, 160, 32, 4), (0, 32, 0, 4), "f32"),
+        # a slice of a larger bf16 array (padded rows and planes) against a transposed view of a compact one
+        (4096, 512, (3, 4, 6), (400, 80, 2), (2, 6, 24), "bf16"),
+        # four dimensions that do not merge: every stride padded; reference permuted and strided
+        (8192, 2048, (2, 3, 4, 5), (2000, 600, 120, 8), (8, 16, 1920, 48), "i64"),
+        # long rows: full items inside N-d blocks; reference row contiguous, planes broadcast
+        (65536, 16384, (2, 2, 3, 3000), (80000, 38000, 12032, 4), (0, 36000, 12000, 4), "i32"),
+        # one element, and an empty tensor
+        (400000, 0, (1, 1), (4, 4), (0, 0), "f32"),
+        (400016, 0, (3, 0, 2), (0, 8, 4), (0, 0, 4), "f32"),
+        # a column of a wider array: the innermost extent is 1 and the rows are a padded stride apart
+        (500000, 200, (5, 6, 1), (96, 16, 4), (24, 4, 4), "f32"),
+        (501000, 300, (7, 1), (12, 4), (4, 4), "f32"),
+        # bytes, short rows on the 16-byte grid (row groups inside the blocks), reference one element per row
+        (400064, 100, (3, 5, 7, 16), (2048, 256, 32, 1), (35, 7, 1, 0), "u8"),
+    ]
+    _check_nd_plan(segs)
+
+
+def test_nd_segments_that_fold_give_the_two_dimensional_plan(lib):
+    """Dimensions that both tensors step through in one stride are merged, extents of 1 dropped: a contiguous [2, 3, 4, 8]
+    tensor against a [1, 1, 1, 8] reference is 24 rows of 8 with one reference row; against a reference of the same
+    layout it is one row."""
+    pairs = [
+        ((0, 64, (2, 3, 4, 8), (384, 128, 32, 4), (0, 0, 0, 4), "f32"), (0, 24, 8, 32, 64, 0, 1, "f32")),
+        ((0, 64, (2, 3, 4, 8), (384, 128, 32, 4), (384, 128, 32, 4), "f32"), (0, 1, 192, 768, 64, 0, 1, "f32")),
+        ((16, 0, (5, 1, 7), (56, 999, 8), (0, 0, 16), "i64"), (16, 5, 7, 56, 0, 0, 2, "i64")),
+        ((0, 0, (6, 10), (64, 4), (4, 24), "f32"), (0, 6, 10, 64, 0, 4, 6, "f32")),                      # transposed: stays two-dimensional
+        ((0, 32, (4, 2, 16), (128, 64, 2), (0, 0, 0), "f16"), (0, 4 * 2, 16, 64, 32, 0, 0, "f16")),       # splat over everything
+    ]
+    for nd, mapped in pairs:
+        st, a = B.geak_check_plan_nd([nd], None, 3, 0.0, 0.0, False, -1)
+        st2, b = B.geak_check_plan_mapped([mapped], None, 3, 0.0, 0.0, False, -1)
+        assert st == B.GEAK_OK and st2 == B.GEAK_OK, (nd, st, st2)
+        ia, ib = B.geak_check_plan_items(a), B.geak_check_plan_items(b)
+        assert ia.tobytes() == ib.tobytes(), nd
+        assert np.array_equal(B.geak_check_plan_ref_offsets(a), B.geak_check_plan_ref_offsets(b))
+        assert B.geak_check_plan_info(a).algorithmic_bytes == B.geak_check_plan_info(b).algorithmic_bytes
+        B.geak_check_destroy(a); B.geak_check_destroy(b)
+
+
+@pytest.mark.parametrize("seg,status", [
+    ((0, 0, (2, 3, 4, 5, 6), (1, 1, 1, 1, 1), (1, 1, 1, 1, 1), "u8"), B.GEAK_EINVAL),                 # five dimensions
+    ((0, 0, (4, 8), (64, 8), (32, 4), "f32"), B.GEAK_EINVAL),                                        # candidates' innermost not contiguous
+    ((0, 0, (4, 8), (30, 4), (32, 4), "f32"), B.GEAK_EALIGN),                                        # stride off the element grid
+    ((0, 0, (4, 8), (32, 4), (34, 4), "f32"), B.GEAK_EALIGN),
+    ((2, 0, (4, 8), (32, 4), (32, 4), "f32"), B.GEAK_EALIGN),                                        # offset off the element grid
+    ((0, 0, (4, 8), (16, 4), (32, 4), "f32"), B.GEAK_EBOUNDS),                                       # rows run into each other
+    ((0, 0, (3, 4, 8), (100, 32, 4), (0, 0, 4), "f32"), B.GEAK_EBOUNDS),                             # planes run into each other
+    ((0, 0, (2, 3, 4, 8), (300, 128, 32, 4), (0, 0, 0, 4), "f32"), B.GEAK_EBOUNDS),
+    ((0, 0, (1 << 21, 1 << 21), (1 << 23, 4), (0, 4), "f32"), B.GEAK_EBOUNDS),                       # more than 2^40 elements
+    ((0, 0, (4, 8), (32, 4), (0, 4 << 22), "f32"), B.GEAK_EBOUNDS),                                  # reference stride too large
+    ((0, 0, (4, 8), (32, 4), (0, 4), "mxint8"), B.GEAK_EDTYPE),
+    ((2 ** 64 - 64, 0, (4, 8), (32, 4), (0, 4), "f32"), B.GEAK_EBOUNDS),                             # beyond the address space
+])
+def test_nd_plan_rejects(lib, seg, status):
+    dt = seg[5]
+    seg = seg[:5] + (B.MX_DTYPE_CODE.get(dt, dt),)
+    st, plan = B.geak_check_plan_nd([seg], None, 2, 0.0, 0.0, False, -1)
+    assert st == status and plan is None, (seg, st)
