@@ -181,7 +181,9 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
             if (!seg_is_nd(g)) {
                 n_items += count_block(s, g.byte_offset);
             } else {
-                // block by block: every block holds at least one item, so the loop ends with the item limit
+                // block by block: every block holds at least one item, so more blocks than the table can hold items are
+                // refused before they are walked, and the loop ends with the item limit
+                if (nd[s].outer_shape[0] >= 0x7FFFFFFFull / nd[s].outer_shape[1]) return GEAK_EBOUNDS;
                 for (uint64_t o0 = 0; o0 < nd[s].outer_shape[0] && n_items < 0x7FFFFFFFull; ++o0)
                     for (uint64_t o1 = 0; o1 < nd[s].outer_shape[1] && n_items < 0x7FFFFFFFull; ++o1)
                         n_items += count_block(s, g.byte_offset + o0 * nd[s].outer_stride[0] + o1 * nd[s].outer_stride[1]);

@@ -872,6 +872,7 @@ def test_nd_segments_that_fold_give_the_two_dimensional_plan(lib):
     ((0, 0, (2, 3, 4, 8), (300, 128, 32, 4), (0, 0, 0, 4), "f32"), B.GEAK_EBOUNDS),
     ((0, 0, (1 << 21, 1 << 21), (1 << 23, 4), (0, 4), "f32"), B.GEAK_EBOUNDS),                       # more than 2^40 elements
     ((0, 0, (4, 8), (32, 4), (0, 4 << 22), "f32"), B.GEAK_EBOUNDS),                                  # reference stride too large
+    ((0, 0, (1 << 17, 1 << 16, 2, 2), (1 << 23, 64, 16, 4), (0, 0, 0, 4), "f32"), B.GEAK_EBOUNDS),     # more 2-D blocks than the item table holds
     ((0, 0, (4, 8), (32, 4), (0, 4), "mxint8"), B.GEAK_EDTYPE),
     ((2 ** 64 - 64, 0, (4, 8), (32, 4), (0, 4), "f32"), B.GEAK_EBOUNDS),                             # beyond the address space
 ])
