@@ -24,7 +24,7 @@ GEAK_F32, GEAK_F16, GEAK_BF16, GEAK_I32, GEAK_I64, GEAK_U8, GEAK_I8, GEAK_F64 = 
 GEAK_F8E4M3, GEAK_F8E5M2 = 8, 9
 GEAK_MXFP8_E4M3, GEAK_MXFP8_E5M2, GEAK_MXINT8, GEAK_MXFP4_E2M1, GEAK_MXFP6_E2M3, GEAK_MXFP6_E3M2 = 10, 11, 12, 13, 14, 15        # element formats of block-scaled segments
 GEAK_MAX_CANDIDATES = 256
-GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED, GEAK_ITEM_ROWS, GEAK_ITEM_REFMAP = 1, 2, 4, 8, 16, 32
+GEAK_ITEM_FULL, GEAK_ITEM_FIRST, GEAK_ITEM_LAST, GEAK_ITEM_ALIGNED, GEAK_ITEM_ROWS, GEAK_ITEM_REFMAP, GEAK_ITEM_STREAM = 1, 2, 4, 8, 16, 32, 64
 GEAK_ULP_BINS = 66
 GEAK_STATIC_SCRATCH_BYTES = 8 << 20
 

@@ -1210,12 +1210,13 @@ struct RunArgs {
 // registers for the same vector of the next element of the wave's stream (the next candidate, or
 // the reference slice of the wave's next item).  Four loads per lane stay in flight and each has a
 // whole element's worth of compute to land.
-template <int DT, int V, bool OUTLINE = false, typename Item>
+template <int DT, int V, bool OUTLINE = false, bool ROWS = false, typename Item>
 __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsigned char *next, bool has_next,
                                             uint32_t next_n, const bool next_full, typename Item::Hint &max_abs,
                                             typename Item::Hint &max_rel, int equal_nan, MaxPair *rec, int lane,
                                             uint32_t &bad, [[maybe_unused]] uint32_t *scale_byte = nullptr,
-                                            [[maybe_unused]] const unsigned char *next_scales = nullptr)
+                                            [[maybe_unused]] const unsigned char *next_scales = nullptr,
+                                            [[maybe_unused]] uint32_t next_off = 0)
 {
     u64 trip_abs = 0, trip_rel = 0;
     // block-scaled formats: the vector's scale byte travels beside it and is refilled with it
@@ -1232,7 +1233,8 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
         else ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
     }
     if (has_next) {
-        slot = load_vec<DT>(next, lane, V, next_n, next_full);
+        if constexpr (ROWS) slot = __builtin_nontemporal_load((global_vec_ptr)(next + next_off));      // a whole row group: this lane's vector of its row
+        else slot = load_vec<DT>(next, lane, V, next_n, next_full);
         if constexpr (kScaled<DT>) *scale_byte = load_scale_byte(next_scales, (uint32_t)(V * kWaveSize + lane), next_n);
     }
 }
@@ -1242,7 +1244,10 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
 // FULL items of the dtype: the wave's loads form one stream -- reference slice, K candidate slices,
 // next reference slice, ... -- that never drains at an item boundary, and every load is an
 // unguarded 16-byte vector load.  Returns the index of the wave's first item it did not process.
-template <int DT>
+// ROWS: the same stream for whole row groups of one pitched segment (GEAK_ITEM_STREAM: rows of whole vectors that fill
+// all of the item's vector slots): a lane's vector v is vector `vec` of row `row` of the group, `row * pitch + 16 vec`
+// bytes behind the item's start -- in the reference, when it has a layout of its own, with its own pitch.
+template <int DT, bool ROWS = false>
 __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState st_in)
 {
     typedef typename ItemOf<DT>::type Item;
@@ -1274,9 +1279,23 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
         return (item.flags & GEAK_ITEM_REFMAP) ? ref_table[index] : item.byte_offset;
     };
     u64 next_ref_off = 0;
+    [[maybe_unused]] uint32_t cand_off[kVecPerLane] = {0u, 0u, 0u, 0u}, ref_off[kVecPerLane] = {0u, 0u, 0u, 0u};
+    if constexpr (ROWS) {
+        const ItemShape sh = item_shape<DT, kTailRows>(it, uniform_ptr(in.segments));
+        const GEAK_AS_CONSTANT unsigned long long *g = (const GEAK_AS_CONSTANT unsigned long long *)(uniform_ptr(in.segments) + it.segment);
+        const uint32_t pitch = (uint32_t)sh.pitch, ref_pitch = (it.flags & GEAK_ITEM_REFMAP) ? (uint32_t)g[6] : pitch;     // the planner admits pitches whose group fits 32 bits
 #pragma unroll
-    for (int v = 0; v < kVecPerLane; ++v)                  // the only loads of the run that nothing hides
-        cur[v] = load_vec<DT>(ref_base + ref_offset_of(it, j), lane, v, it.numel, full);
+        for (int v = 0; v < kVecPerLane; ++v) {
+            const uint32_t slot = (uint32_t)(v * kWaveSize + lane), row = (slot * sh.inv) >> 16, vec = slot - row * sh.vpr;
+            cand_off[v] = row * pitch + vec * 16u;
+            ref_off[v] = row * ref_pitch + vec * 16u;
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < kVecPerLane; ++v) {                // the only loads of the run that nothing hides
+        if constexpr (ROWS) cur[v] = __builtin_nontemporal_load((global_vec_ptr)(ref_base + ref_offset_of(it, j) + ref_off[v]));
+        else cur[v] = load_vec<DT>(ref_base + ref_offset_of(it, j), lane, v, it.numel, full);
+    }
     // block-scaled formats: the scale byte of each vector's block, loaded and refilled beside the vector
     [[maybe_unused]] uint32_t sc[kVecPerLane] = {0u, 0u, 0u, 0u};
     [[maybe_unused]] u64 scale_off = 0, next_scale_off = 0;
@@ -1293,7 +1312,8 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
         geak_item nx = it;
         if (more) {
             nx = load_work_item(items, jn);
-            more = (nx.flags & GEAK_ITEM_FULL) && nx.dtype == DT;
+            if constexpr (ROWS) more = (nx.flags & GEAK_ITEM_STREAM) && nx.dtype == DT && nx.segment == it.segment;     // the same rows: the same offsets
+            else more = (nx.flags & GEAK_ITEM_FULL) && nx.dtype == DT;
         }
         if (more) next_ref_off = ref_offset_of(nx, jn);
         const SegTol cur_tol = tolerance;
@@ -1316,10 +1336,15 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
                     sc[v] = load_scale_byte(first_scales, (uint32_t)(v * kWaveSize + lane), it.numel);
                 });
             }
-            ref.template stage_vec<0>(cur[0], cur_tol); cur[0] = load_vec<DT>(first, lane, 0, it.numel, full);
-            ref.template stage_vec<1>(cur[1], cur_tol); cur[1] = load_vec<DT>(first, lane, 1, it.numel, full);
-            ref.template stage_vec<2>(cur[2], cur_tol); cur[2] = load_vec<DT>(first, lane, 2, it.numel, full);
-            ref.template stage_vec<3>(cur[3], cur_tol); cur[3] = load_vec<DT>(first, lane, 3, it.numel, full);
+            const auto first_vec = [&](auto idx) -> u32x4 {
+                constexpr int v = decltype(idx)::value;
+                if constexpr (ROWS) return __builtin_nontemporal_load((global_vec_ptr)(first + cand_off[v]));
+                else return load_vec<DT>(first, lane, v, it.numel, full);
+            };
+            ref.template stage_vec<0>(cur[0], cur_tol); cur[0] = first_vec(Index<0>{});
+            ref.template stage_vec<1>(cur[1], cur_tol); cur[1] = first_vec(Index<1>{});
+            ref.template stage_vec<2>(cur[2], cur_tol); cur[2] = first_vec(Index<2>{});
+            ref.template stage_vec<3>(cur[3], cur_tol); cur[3] = first_vec(Index<3>{});
         }
         u64 abs_bits = load_bits(&recs[k * replicas].abs), rel_bits = load_bits(&recs[k * replicas].rel);
 
@@ -1340,10 +1365,10 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
                 rel_bits = load_bits(&recs[kn * replicas].rel);
             }
             uint32_t bad = 0;
-            stream_step<DT, 0>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[0], next_scales);
-            stream_step<DT, 1>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[1], next_scales);
-            stream_step<DT, 2>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[2], next_scales);
-            stream_step<DT, 3>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[3], next_scales);
+            stream_step<DT, 0, false, ROWS>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[0], next_scales, last ? ref_off[0] : cand_off[0]);
+            stream_step<DT, 1, false, ROWS>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[1], next_scales, last ? ref_off[1] : cand_off[1]);
+            stream_step<DT, 2, false, ROWS>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[2], next_scales, last ? ref_off[2] : cand_off[2]);
+            stream_step<DT, 3, false, ROWS>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[3], next_scales, last ? ref_off[3] : cand_off[3]);
             note_mismatches(st, k, bad, j, lane);
             k = kn;
         }
@@ -1541,6 +1566,8 @@ __global__ __launch_bounds__(kBlockThreads, 4) void compare_kernel(const Compare
             else for_scaled_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailPlain, false>(r, st); });
         } else if (it.flags & GEAK_ITEM_FULL) {
             for_dtype(it.dtype, [&](auto dt) { next_j = process_run<decltype(dt)::value>(r, st); });
+        } else if (it.flags & GEAK_ITEM_STREAM) {            // whole row groups: streamed like full items
+            for_dtype(it.dtype, [&](auto dt) { next_j = process_run<decltype(dt)::value, true>(r, st); });
         } else if (it.flags & GEAK_ITEM_REFMAP) {
             if (it.flags & GEAK_ITEM_ROWS) for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailRows, true>(r, st); });
             else if (it.flags & GEAK_ITEM_ALIGNED) for_dtype(it.dtype, [&](auto dt) { process_tail<decltype(dt)::value, kTailPlain, true>(r, st); });

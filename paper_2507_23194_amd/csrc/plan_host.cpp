@@ -238,7 +238,12 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     it.numel = (uint16_t)(rows_here * g.row_elems);                 // at most 4096 / w elements
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
-                    it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS | (mapped ? GEAK_ITEM_REFMAP : 0));
+                    // rows of whole vectors that fill the item's 256 slots, a group's offsets within 32 bits, the reference's
+                    // rows (if they are its own) contiguous: streamed like a full item
+                    const bool stream = rows_here == group && group * row_vectors == kItemBytes / 16 && (g.row_elems * w) % 16 == 0 &&
+                                        (group - 1) * g.pitch_bytes < (1ull << 32) &&
+                                        (!mapped || (ref_stride == 1 && (group - 1) * g.ref_pitch_bytes < (1ull << 32)));
+                    it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS | (mapped ? GEAK_ITEM_REFMAP : 0) | (stream ? GEAK_ITEM_STREAM : 0));
                     hp.items.push_back(it);
                     if (any_mapped) hp.ref_item_offset.push_back(mapped ? ref_base + r * g.ref_pitch_bytes : it.byte_offset);
                 }
@@ -316,7 +321,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         const uint64_t slices = (uint64_t)num_candidates + 1;
         auto item_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
             const uint64_t per_slice = is_mx_dtype(it.dtype) ? 48 : (it.dtype == GEAK_F8E4M3 || it.dtype == GEAK_F8E5M2) ? 40 : (it.dtype == GEAK_F32 || it.dtype == GEAK_F64) ? 16 : it.dtype == GEAK_BF16 ? 19 : it.dtype == GEAK_F16 ? 21 : 13;   // integers: 13
-            if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices + 140;       // tails, row groups, starts off the grid
+            if (!(it.flags & (GEAK_ITEM_FULL | GEAK_ITEM_STREAM))) return per_slice * slices + 140;       // tails, ragged row groups, starts off the grid
             return per_slice * slices + (starts_run ? 100 : 0);
         };
         // What the blocks that share a compute unit cost it together.  The waves of a compute unit slow each other
@@ -330,7 +335,7 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
         // what is left does not follow anything the planner can count.
         auto unit_cost = [&](const geak_item &it, bool starts_run) -> uint64_t {
             const uint64_t per_slice = is_mx_dtype(it.dtype) ? 48 : (it.dtype == GEAK_F8E4M3 || it.dtype == GEAK_F8E5M2) ? 40 : 16;
-            if (!(it.flags & GEAK_ITEM_FULL)) return per_slice * slices * kUnitTailMul16 / 16 + kUnitTailFix;
+            if (!(it.flags & (GEAK_ITEM_FULL | GEAK_ITEM_STREAM))) return per_slice * slices * kUnitTailMul16 / 16 + kUnitTailFix;
             return per_slice * slices + (starts_run ? kUnitStart : 0);
         };
         const auto starts = [&](uint64_t j) { return j > 0 && hp.items[j - 1].segment != hp.items[j].segment; };
