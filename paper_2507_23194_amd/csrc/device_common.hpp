@@ -411,6 +411,19 @@ __device__ __noinline__ u32x4 gather_elements_call(const unsigned char *first, c
     }
     return q;
 }
+// A 16-byte vector filled with the one element at `at`.
+template <int DT>
+__device__ __forceinline__ u32x4 splat_element(const unsigned char *at)
+{
+    constexpr uint32_t W = Traits<DT>::W;
+    const GEAK_AS_GLOBAL unsigned char *one = (const GEAK_AS_GLOBAL unsigned char *)at;
+    uint32_t w0, w1 = 0u;
+    if constexpr (W == 1) { w0 = *one; w0 |= w0 << 8; w0 |= w0 << 16; w1 = w0; }
+    else if constexpr (W == 2) { w0 = *(const GEAK_AS_GLOBAL uint16_t *)one; w0 |= w0 << 16; w1 = w0; }
+    else if constexpr (W == 4) { w0 = *(const GEAK_AS_GLOBAL uint32_t *)one; w1 = w0; }
+    else { w0 = ((const GEAK_AS_GLOBAL uint32_t *)one)[0]; w1 = ((const GEAK_AS_GLOBAL uint32_t *)one)[1]; }
+    return u32x4{w0, w1, w0, w1};
+}
 // Vector slot `slot` of the reference side of such an item: the elements that the same slot of a
 // candidate is compared with, zero where the candidate's slot reads as zero.
 template <int DT, int KIND>
@@ -440,13 +453,7 @@ __device__ __forceinline__ u32x4 load_ref_slot(const unsigned char *ref_base, co
         return q;
     }
     if (sp.valid > sp.lo) {
-        uint32_t w0, w1 = 0u;
-        const GEAK_AS_GLOBAL unsigned char *one = (const GEAK_AS_GLOBAL unsigned char *)row;        // the row's one element
-        if constexpr (W == 1) { w0 = *one; w0 |= w0 << 8; w0 |= w0 << 16; w1 = w0; }
-        else if constexpr (W == 2) { w0 = *(const GEAK_AS_GLOBAL uint16_t *)one; w0 |= w0 << 16; w1 = w0; }
-        else if constexpr (W == 4) { w0 = *(const GEAK_AS_GLOBAL uint32_t *)one; w1 = w0; }
-        else { w0 = ((const GEAK_AS_GLOBAL uint32_t *)one)[0]; w1 = ((const GEAK_AS_GLOBAL uint32_t *)one)[1]; }
-        q[0] = w0; q[1] = w1; q[2] = w0; q[3] = w1;
+        q = splat_element<DT>(row);                                                                 // the row's one element
         if (sp.lo != 0 || sp.valid < E) q = cut_vector_call(q, (int)(sp.lo * W), (int)((sp.valid < E ? sp.valid : E) * W));
     }
     return q;

@@ -1216,7 +1216,7 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
                                             typename Item::Hint &max_rel, int equal_nan, MaxPair *rec, int lane,
                                             uint32_t &bad, [[maybe_unused]] uint32_t *scale_byte = nullptr,
                                             [[maybe_unused]] const unsigned char *next_scales = nullptr,
-                                            [[maybe_unused]] uint32_t next_off = 0)
+                                            [[maybe_unused]] uint32_t next_off = 0, [[maybe_unused]] bool next_splat = false)
 {
     u64 trip_abs = 0, trip_rel = 0;
     // block-scaled formats: the vector's scale byte travels beside it and is refilled with it
@@ -1233,7 +1233,10 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
         else ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
     }
     if (has_next) {
-        if constexpr (ROWS) slot = __builtin_nontemporal_load((global_vec_ptr)(next + next_off));      // a whole row group: this lane's vector of its row
+        if constexpr (ROWS) {                              // a whole row group: this lane's vector of its row, or its row's one reference element
+            if (next_splat) slot = splat_element<DT>(next + next_off);
+            else slot = __builtin_nontemporal_load((global_vec_ptr)(next + next_off));
+        }
         else slot = load_vec<DT>(next, lane, V, next_n, next_full);
         if constexpr (kScaled<DT>) *scale_byte = load_scale_byte(next_scales, (uint32_t)(V * kWaveSize + lane), next_n);
     }
@@ -1280,21 +1283,28 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
     };
     u64 next_ref_off = 0;
     [[maybe_unused]] uint32_t cand_off[kVecPerLane] = {0u, 0u, 0u, 0u}, ref_off[kVecPerLane] = {0u, 0u, 0u, 0u};
+    [[maybe_unused]] bool ref_splat = false;
     if constexpr (ROWS) {
         const ItemShape sh = item_shape<DT, kTailRows>(it, uniform_ptr(in.segments));
         const GEAK_AS_CONSTANT unsigned long long *g = (const GEAK_AS_CONSTANT unsigned long long *)(uniform_ptr(in.segments) + it.segment);
         const uint32_t pitch = (uint32_t)sh.pitch, ref_pitch = (it.flags & GEAK_ITEM_REFMAP) ? (uint32_t)g[6] : pitch;     // the planner admits pitches whose group fits 32 bits
+        ref_splat = (it.flags & GEAK_ITEM_REFMAP) && ((uint32_t)(g[4] >> 32) >> kRefStrideShift) == 0;                     // one reference element per row
 #pragma unroll
         for (int v = 0; v < kVecPerLane; ++v) {
             const uint32_t slot = (uint32_t)(v * kWaveSize + lane), row = (slot * sh.inv) >> 16, vec = slot - row * sh.vpr;
             cand_off[v] = row * pitch + vec * 16u;
-            ref_off[v] = row * ref_pitch + vec * 16u;
+            ref_off[v] = row * ref_pitch + (ref_splat ? 0u : vec * 16u);
         }
     }
 #pragma unroll
     for (int v = 0; v < kVecPerLane; ++v) {                // the only loads of the run that nothing hides
-        if constexpr (ROWS) cur[v] = __builtin_nontemporal_load((global_vec_ptr)(ref_base + ref_offset_of(it, j) + ref_off[v]));
-        else cur[v] = load_vec<DT>(ref_base + ref_offset_of(it, j), lane, v, it.numel, full);
+        if constexpr (ROWS) {
+            const unsigned char *at = ref_base + ref_offset_of(it, j) + ref_off[v];
+            if (ref_splat) cur[v] = splat_element<DT>(at);
+            else cur[v] = __builtin_nontemporal_load((global_vec_ptr)at);
+        } else {
+            cur[v] = load_vec<DT>(ref_base + ref_offset_of(it, j), lane, v, it.numel, full);
+        }
     }
     // block-scaled formats: the scale byte of each vector's block, loaded and refilled beside the vector
     [[maybe_unused]] uint32_t sc[kVecPerLane] = {0u, 0u, 0u, 0u};
@@ -1365,10 +1375,10 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
                 rel_bits = load_bits(&recs[kn * replicas].rel);
             }
             uint32_t bad = 0;
-            stream_step<DT, 0, false, ROWS>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[0], next_scales, last ? ref_off[0] : cand_off[0]);
-            stream_step<DT, 1, false, ROWS>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[1], next_scales, last ? ref_off[1] : cand_off[1]);
-            stream_step<DT, 2, false, ROWS>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[2], next_scales, last ? ref_off[2] : cand_off[2]);
-            stream_step<DT, 3, false, ROWS>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[3], next_scales, last ? ref_off[3] : cand_off[3]);
+            stream_step<DT, 0, false, ROWS>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[0], next_scales, last ? ref_off[0] : cand_off[0], last && ref_splat);
+            stream_step<DT, 1, false, ROWS>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[1], next_scales, last ? ref_off[1] : cand_off[1], last && ref_splat);
+            stream_step<DT, 2, false, ROWS>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[2], next_scales, last ? ref_off[2] : cand_off[2], last && ref_splat);
+            stream_step<DT, 3, false, ROWS>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[3], next_scales, last ? ref_off[3] : cand_off[3], last && ref_splat);
             note_mismatches(st, k, bad, j, lane);
             k = kn;
         }

@@ -239,10 +239,10 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
                     // rows of whole vectors that fill the item's 256 slots, a group's offsets within 32 bits, the reference's
-                    // rows (if they are its own) contiguous: streamed like a full item
+                    // rows (if they are its own) contiguous or one element each: streamed like a full item
                     const bool stream = rows_here == group && group * row_vectors == kItemBytes / 16 && (g.row_elems * w) % 16 == 0 &&
                                         (group - 1) * g.pitch_bytes < (1ull << 32) &&
-                                        (!mapped || (ref_stride == 1 && (group - 1) * g.ref_pitch_bytes < (1ull << 32)));
+                                        (!mapped || (ref_stride <= 1 && (group - 1) * g.ref_pitch_bytes < (1ull << 32)));
                     it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS | (mapped ? GEAK_ITEM_REFMAP : 0) | (stream ? GEAK_ITEM_STREAM : 0));
                     hp.items.push_back(it);
                     if (any_mapped) hp.ref_item_offset.push_back(mapped ? ref_base + r * g.ref_pitch_bytes : it.byte_offset);

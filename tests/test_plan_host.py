@@ -886,7 +886,7 @@ def test_nd_plan_rejects(lib, seg, status):
 def test_whole_row_groups_are_marked_for_streaming(lib):
     """Row groups whose rows are whole 16-byte vectors and fill the item's 256 vector slots carry GEAK_ITEM_STREAM (the
     compare kernel streams them like full items); a ragged last group, rows of a length that leaves slots idle or a
-    partial vector, a reference with one element per row and pitches whose group does not fit 32 bits do not."""
+    partial vector, a reference with strided rows and pitches whose group does not fit 32 bits do not."""
     def flags_of(st_plan):
         st, plan = st_plan
         assert st == B.GEAK_OK
@@ -900,10 +900,10 @@ def test_whole_row_groups_are_marked_for_streaming(lib):
     # rows of 48 binary32 (12 vectors: 21 rows leave 4 slots idle) and of 62 (the last vector partial)
     assert not any(x & S for x in flags_of(B.geak_check_plan_pitched([(0, 64, 48, 256, "f32")], None, 2, 0, 0, 0, -1)))
     assert not any(x & S for x in flags_of(B.geak_check_plan_pitched([(0, 64, 62, 256, "f32")], None, 2, 0, 0, 0, -1)))
-    # a reference of its own: contiguous rows (any pitch, also one row for all) stream, one element per row does not
+    # a reference of its own: contiguous rows (any pitch, also one row for all) and one element per row stream, strided rows do not
     f = flags_of(B.geak_check_plan_mapped([(0, 32, 128, 512, 0, 0, 1, "bf16")], None, 2, 0, 0, 0, -1))
     assert all(x & S and x & B.GEAK_ITEM_REFMAP for x in f) and len(f) == 2
-    assert not any(x & S for x in flags_of(B.geak_check_plan_mapped([(0, 32, 128, 512, 0, 2, 0, "bf16")], None, 2, 0, 0, 0, -1)))
+    assert all(x & S for x in flags_of(B.geak_check_plan_mapped([(0, 32, 128, 512, 0, 2, 0, "bf16")], None, 2, 0, 0, 0, -1)))
     assert not any(x & S for x in flags_of(B.geak_check_plan_mapped([(0, 32, 128, 512, 0, 512, 2, "bf16")], None, 2, 0, 0, 0, -1)))
     # a pitch of 2^29 bytes: fifteen of them do not fit 32 bits
     f = flags_of(B.geak_check_plan_pitched([(0, 32, 64, 1 << 29, "f32")], None, 2, 0, 0, 0, -1))
