@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 # They were taken in profiling runs of their own, not in the run that prints them, and describe the
 # library whose build id is recorded with them: for any other build roofline.traffic is null.
 MEASURED_TRAFFIC = {
-    "build_id": "8ec5c6035a11f434",
-    "bytes": {2: 8.7964e9, 3: 9.1980e9, 4: 1.2292e9, 5: 141.8672e9},
+    "build_id": "51dda1bf0b5a52f2",
+    "bytes": {2: 8.7964e9, 3: 9.1980e9, 4: 1.2294e9, 5: 141.8672e9},
     "source": "profiles/compare_kernel_config*.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, not this run)",
 }
 

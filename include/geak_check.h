@@ -391,9 +391,8 @@ typedef struct {
 #define GEAK_ITEM_ROWS 16u /* several whole rows of a pitched segment whose rows are short and start on 16-byte
                               boundaries: numel / row_elems rows, pitch_bytes apart, the first at byte_offset;
                               elem_start is the flat index of the first row's first element (ALIGNED is set) */
-#define GEAK_ITEM_STREAM 64u /* with ROWS: the rows are whole 16-byte vectors and fill all 256 vector slots of the item (and
-                                the reference's rows, if it has a layout of its own, are contiguous or one element each): the compare kernel streams
-                                such groups like full items */
+#define GEAK_ITEM_STREAM 64u /* with ROWS: the rows are whole 16-byte vectors (and the reference's rows, if it has a layout of
+                                its own, are contiguous or one element each): the compare kernel streams such groups like full items */
 #define GEAK_ITEM_REFMAP 32u /* the segment's reference has a layout of its own (geak_segment_mapped): the item's
                                 reference elements are found through the segment's mapping, not at byte_offset */
 

@@ -1216,7 +1216,8 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
                                             typename Item::Hint &max_rel, int equal_nan, MaxPair *rec, int lane,
                                             uint32_t &bad, [[maybe_unused]] uint32_t *scale_byte = nullptr,
                                             [[maybe_unused]] const unsigned char *next_scales = nullptr,
-                                            [[maybe_unused]] uint32_t next_off = 0, [[maybe_unused]] bool next_splat = false)
+                                            [[maybe_unused]] uint32_t next_off = 0, [[maybe_unused]] bool next_splat = false,
+                                            [[maybe_unused]] bool next_active = true)
 {
     u64 trip_abs = 0, trip_rel = 0;
     // block-scaled formats: the vector's scale byte travels beside it and is refilled with it
@@ -1233,9 +1234,12 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
         else ref.template raise_vec<V>(slot, max_abs, max_rel, rec, lane);
     }
     if (has_next) {
-        if constexpr (ROWS) {                              // a whole row group: this lane's vector of its row, or its row's one reference element
-            if (next_splat) slot = splat_element<DT>(next + next_off);
-            else slot = __builtin_nontemporal_load((global_vec_ptr)(next + next_off));
+        if constexpr (ROWS) {                              // a row group: this lane's vector of its row, or its row's one reference element;
+            slot = u32x4{0u, 0u, 0u, 0u};                  // a slot behind the group's last row is not loaded and reads as 0 in every tensor
+            if (next_active) {
+                if (next_splat) slot = splat_element<DT>(next + next_off);
+                else slot = __builtin_nontemporal_load((global_vec_ptr)(next + next_off));
+            }
         }
         else slot = load_vec<DT>(next, lane, V, next_n, next_full);
         if constexpr (kScaled<DT>) *scale_byte = load_scale_byte(next_scales, (uint32_t)(V * kWaveSize + lane), next_n);
@@ -1247,8 +1251,8 @@ __device__ __forceinline__ void stream_step(Item &ref, u32x4 &slot, const unsign
 // FULL items of the dtype: the wave's loads form one stream -- reference slice, K candidate slices,
 // next reference slice, ... -- that never drains at an item boundary, and every load is an
 // unguarded 16-byte vector load.  Returns the index of the wave's first item it did not process.
-// ROWS: the same stream for whole row groups of one pitched segment (GEAK_ITEM_STREAM: rows of whole vectors that fill
-// all of the item's vector slots): a lane's vector v is vector `vec` of row `row` of the group, `row * pitch + 16 vec`
+// ROWS: the same stream for row groups of one pitched segment whose rows are whole vectors (GEAK_ITEM_STREAM; slots
+// behind the group's last row are not loaded and read as 0 on every side): a lane's vector v is vector `vec` of row `row` of the group, `row * pitch + 16 vec`
 // bytes behind the item's start -- in the reference, when it has a layout of its own, with its own pitch.
 template <int DT, bool ROWS = false>
 __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState st_in)
@@ -1299,9 +1303,13 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
 #pragma unroll
     for (int v = 0; v < kVecPerLane; ++v) {                // the only loads of the run that nothing hides
         if constexpr (ROWS) {
+            // the group's rows are whole vectors: numel / E of the item's 256 slots hold them, the others read as 0
             const unsigned char *at = ref_base + ref_offset_of(it, j) + ref_off[v];
-            if (ref_splat) cur[v] = splat_element<DT>(at);
-            else cur[v] = __builtin_nontemporal_load((global_vec_ptr)at);
+            cur[v] = u32x4{0u, 0u, 0u, 0u};
+            if ((uint32_t)(v * kWaveSize + lane) < (uint32_t)it.numel / (uint32_t)Traits<DT>::E) {
+                if (ref_splat) cur[v] = splat_element<DT>(at);
+                else cur[v] = __builtin_nontemporal_load((global_vec_ptr)at);
+            }
         } else {
             cur[v] = load_vec<DT>(ref_base + ref_offset_of(it, j), lane, v, it.numel, full);
         }
@@ -1348,8 +1356,13 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
             }
             const auto first_vec = [&](auto idx) -> u32x4 {
                 constexpr int v = decltype(idx)::value;
-                if constexpr (ROWS) return __builtin_nontemporal_load((global_vec_ptr)(first + cand_off[v]));
-                else return load_vec<DT>(first, lane, v, it.numel, full);
+                if constexpr (ROWS) {
+                    u32x4 q = {0u, 0u, 0u, 0u};
+                    if ((uint32_t)(v * kWaveSize + lane) < (uint32_t)it.numel / (uint32_t)Traits<DT>::E) q = __builtin_nontemporal_load((global_vec_ptr)(first + cand_off[v]));
+                    return q;
+                } else {
+                    return load_vec<DT>(first, lane, v, it.numel, full);
+                }
             };
             ref.template stage_vec<0>(cur[0], cur_tol); cur[0] = first_vec(Index<0>{});
             ref.template stage_vec<1>(cur[1], cur_tol); cur[1] = first_vec(Index<1>{});
@@ -1375,10 +1388,14 @@ __device__ __noinline__ uint32_t process_run(const RunArgs in, const WaveState s
                 rel_bits = load_bits(&recs[kn * replicas].rel);
             }
             uint32_t bad = 0;
-            stream_step<DT, 0, false, ROWS>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[0], next_scales, last ? ref_off[0] : cand_off[0], last && ref_splat);
-            stream_step<DT, 1, false, ROWS>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[1], next_scales, last ? ref_off[1] : cand_off[1], last && ref_splat);
-            stream_step<DT, 2, false, ROWS>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[2], next_scales, last ? ref_off[2] : cand_off[2], last && ref_splat);
-            stream_step<DT, 3, false, ROWS>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[3], next_scales, last ? ref_off[3] : cand_off[3], last && ref_splat);
+            stream_step<DT, 0, false, ROWS>(ref, cur[0], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[0], next_scales, last ? ref_off[0] : cand_off[0], last && ref_splat,
+                                            (uint32_t)(0 * kWaveSize + lane) < (uint32_t)(last ? nx.numel : it.numel) / (uint32_t)Traits<DT>::E);
+            stream_step<DT, 1, false, ROWS>(ref, cur[1], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[1], next_scales, last ? ref_off[1] : cand_off[1], last && ref_splat,
+                                            (uint32_t)(1 * kWaveSize + lane) < (uint32_t)(last ? nx.numel : it.numel) / (uint32_t)Traits<DT>::E);
+            stream_step<DT, 2, false, ROWS>(ref, cur[2], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[2], next_scales, last ? ref_off[2] : cand_off[2], last && ref_splat,
+                                            (uint32_t)(2 * kWaveSize + lane) < (uint32_t)(last ? nx.numel : it.numel) / (uint32_t)Traits<DT>::E);
+            stream_step<DT, 3, false, ROWS>(ref, cur[3], next, has_next, next_n, full, max_abs, max_rel, equal_nan, &recs[k * replicas], lane, bad, &sc[3], next_scales, last ? ref_off[3] : cand_off[3], last && ref_splat,
+                                            (uint32_t)(3 * kWaveSize + lane) < (uint32_t)(last ? nx.numel : it.numel) / (uint32_t)Traits<DT>::E);
             note_mismatches(st, k, bad, j, lane);
             k = kn;
         }

@@ -238,11 +238,11 @@ geak_status build_host_plan(HostPlan &hp, const SegDesc *segs, const geak_tolera
                     it.numel = (uint16_t)(rows_here * g.row_elems);                 // at most 4096 / w elements
                     it.next = kNoItem;
                     it.dtype = (uint8_t)g.dtype;
-                    // rows of whole vectors that fill the item's 256 slots, a group's offsets within 32 bits, the reference's
-                    // rows (if they are its own) contiguous or one element each: streamed like a full item
-                    const bool stream = rows_here == group && group * row_vectors == kItemBytes / 16 && (g.row_elems * w) % 16 == 0 &&
-                                        (group - 1) * g.pitch_bytes < (1ull << 32) &&
-                                        (!mapped || (ref_stride <= 1 && (group - 1) * g.ref_pitch_bytes < (1ull << 32)));
+                    // rows of whole vectors, a group's offsets within 32 bits, the reference's rows (if they are its own)
+                    // contiguous or one element each: streamed like a full item (slots that the group leaves idle read as 0)
+                    constexpr uint64_t kOffsetLimit = (1ull << 32) - kItemBytes;      // a row's offset plus a vector's within the row: 32 bits
+                    const bool stream = (g.row_elems * w) % 16 == 0 && (group - 1) * g.pitch_bytes < kOffsetLimit &&
+                                        (!mapped || (ref_stride <= 1 && (group - 1) * g.ref_pitch_bytes < kOffsetLimit));
                     it.flags = (uint8_t)(GEAK_ITEM_ALIGNED | GEAK_ITEM_ROWS | (mapped ? GEAK_ITEM_REFMAP : 0) | (stream ? GEAK_ITEM_STREAM : 0));
                     hp.items.push_back(it);
                     if (any_mapped) hp.ref_item_offset.push_back(mapped ? ref_base + r * g.ref_pitch_bytes : it.byte_offset);

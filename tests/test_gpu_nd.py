@@ -173,3 +173,17 @@ def test_nd_plan_refuses_the_read_probe():
             ck.read_probe(x, [x])
     finally:
         ck.close()
+
+
+def test_row_groups_that_leave_slots_idle(oracle_mod):
+    """Rows of whole vectors whose groups do not fill an item's 256 vector slots (12 or 3 vectors per row), and ragged last
+    groups: the compare kernel streams them with the idle slots reading as 0; against a reference that is one row for
+    all, one element per row, or compact rows of its own pitch."""
+    print("nd idle slots", flush=True)
+    cases = [
+        ("f32", (45, 48), "bcast:10", (0, 4)), ("f32", (45, 48), "bcast:01", (0, 4)), ("f32", (21 * 3 + 5, 48), "same", (0, 4)),
+        ("bf16", (100, 24), "bcast:10", (0, 8)), ("bf16", (3, 37, 24), "bcast:010", (0, 0, 8)), ("bf16", (3, 37, 24), "bcast:101", (0, 1, 8)),
+        ("u8", (300, 48), "bcast:01", (0, 16)), ("i64", (50, 6), "same", (0, 2)), ("f16", (2, 2, 90, 40), "bcast:1100", (0, 0, 0, 8)),
+    ]
+    _run(oracle_mod, cases, 3, 1e-2, 1e-2, False, "nd idle slots")
+    _run(oracle_mod, cases, 5, 0.0, 0.0, True, "nd idle slots exact")

@@ -883,10 +883,10 @@ def test_nd_plan_rejects(lib, seg, status):
     assert st == status and plan is None, (seg, st)
 
 
-def test_whole_row_groups_are_marked_for_streaming(lib):
-    """Row groups whose rows are whole 16-byte vectors and fill the item's 256 vector slots carry GEAK_ITEM_STREAM (the
-    compare kernel streams them like full items); a ragged last group, rows of a length that leaves slots idle or a
-    partial vector, a reference with strided rows and pitches whose group does not fit 32 bits do not."""
+def test_row_groups_of_whole_vectors_are_marked_for_streaming(lib):
+    """Row groups whose rows are whole 16-byte vectors carry GEAK_ITEM_STREAM (the compare kernel streams them like full
+    items, slots that a group leaves idle reading as 0); rows that end in a partial vector, a reference with strided
+    rows and pitches whose group does not fit 32 bits do not."""
     def flags_of(st_plan):
         st, plan = st_plan
         assert st == B.GEAK_OK
@@ -894,11 +894,11 @@ def test_whole_row_groups_are_marked_for_streaming(lib):
         B.geak_check_destroy(plan)
         return [int(f) for f in items["flags"]]
     S, R = B.GEAK_ITEM_STREAM, B.GEAK_ITEM_ROWS
-    # 40 rows of 64 binary32 (16 vectors each): groups of 16 rows: two whole groups and one of 8 rows
+    # 40 rows of 64 binary32 (16 vectors each): groups of 16 rows, the last one of 8 rows
     f = flags_of(B.geak_check_plan_pitched([(0, 40, 64, 320, "f32")], None, 2, 0, 0, 0, -1))
-    assert [bool(x & S) for x in f] == [True, True, False] and all(x & R for x in f)
-    # rows of 48 binary32 (12 vectors: 21 rows leave 4 slots idle) and of 62 (the last vector partial)
-    assert not any(x & S for x in flags_of(B.geak_check_plan_pitched([(0, 64, 48, 256, "f32")], None, 2, 0, 0, 0, -1)))
+    assert len(f) == 3 and all(x & S and x & R for x in f)
+    # rows of 48 binary32 (12 vectors: 21 rows leave 4 slots idle) stream, rows of 62 (the last vector partial) do not
+    assert all(x & S for x in flags_of(B.geak_check_plan_pitched([(0, 64, 48, 256, "f32")], None, 2, 0, 0, 0, -1)))
     assert not any(x & S for x in flags_of(B.geak_check_plan_pitched([(0, 64, 62, 256, "f32")], None, 2, 0, 0, 0, -1)))
     # a reference of its own: contiguous rows (any pitch, also one row for all) and one element per row stream, strided rows do not
     f = flags_of(B.geak_check_plan_mapped([(0, 32, 128, 512, 0, 0, 1, "bf16")], None, 2, 0, 0, 0, -1))
@@ -910,3 +910,6 @@ def test_whole_row_groups_are_marked_for_streaming(lib):
     assert all(x & R for x in f) and not any(x & S for x in f)
     f = flags_of(B.geak_check_plan_pitched([(0, 32, 64, 1 << 28, "f32")], None, 2, 0, 0, 0, -1))
     assert all(x & S for x in f)
+    # fifteen pitches plus a vector's offset in the row must fit as well
+    f = flags_of(B.geak_check_plan_pitched([(0, 32, 64, ((1 << 32) - 256) // 15 // 16 * 16, "f32")], None, 2, 0, 0, 0, -1))
+    assert not any(x & S for x in f)
